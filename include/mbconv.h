@@ -1,0 +1,158 @@
+/*
+ * mbconv.h - C ABI of libmbconv: one training step (forward and backward) of an
+ * EfficientNet MBConv block on one AMD MI355X (gfx950).
+ *
+ * The block is the one the paper optimises by hand in its EfficientNet case study
+ * (section "Guided Optimization Case Study: EfficientNet"): 1x1 expansion conv ->
+ * BN -> Swish -> kxk depthwise conv -> BN -> Swish -> squeeze-and-excitation ->
+ * 1x1 projection conv -> BN -> optional residual.  Batch normalisation is the
+ * formula of section "Statistical Normalization" taken over (N,H,W) per channel
+ * with batch statistics, and it updates running mean/variance as that section
+ * says training-mode BN does.  What backward needs is either recomputed from the
+ * pre-normalisation tensors or stored, the choice the paper describes in section
+ * "Backpropagation and Data Movement".
+ *
+ * Conventions
+ *   - Every tensor is NCHW, contiguous, W fastest.  Ho = (H+2*pad-k)/stride+1.
+ *   - "dtype" is the storage type of activation-sized tensors and of the three
+ *     convolution weights (fp32, or bf16 with round-to-nearest-even).  BN
+ *     parameters and state, SE parameters and every parameter gradient are fp32.
+ *     All accumulation is fp32 or wider.
+ *   - Every pointer below is a DEVICE pointer unless stated otherwise, owned by the
+ *     caller, and must be 16-byte aligned.  The library allocates nothing, keeps no
+ *     state between calls and never synchronises: all work is enqueued on the
+ *     hipStream_t passed as `hip_stream` (NULL = the default stream).
+ *   - Descriptors and the pointer structs themselves live in HOST memory and are
+ *     read during the call only.
+ *   - Errors: every argument check happens on the host before the first launch and
+ *     returns a negative status without touching device memory.  A failed launch
+ *     returns MBCONV_EHIP.  Nothing throws, nothing aborts.
+ */
+#ifndef MBCONV_H
+#define MBCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MBCONV_OK = 0,
+    MBCONV_EINVAL = -1,       /* null pointer or inconsistent descriptor */
+    MBCONV_EUNSUPPORTED = -2, /* shape outside what the kernels cover */
+    MBCONV_EWORKSPACE = -3,   /* reserved */
+    MBCONV_EALIGN = -4,       /* a pointer is not 16-byte aligned */
+    MBCONV_EHIP = -5          /* a HIP launch failed */
+} mbconv_status;
+
+typedef enum { MBCONV_F32 = 0, MBCONV_BF16 = 1 } mbconv_dtype;
+
+/* What forward keeps for backward (section "Backpropagation and Data Movement").
+ * RECOMPUTE keeps only the three pre-normalisation tensors e, d, p and O(N*C)
+ * statistics; backward rebuilds Swish(BN(.)) from them.  STORE additionally keeps the
+ * depthwise input a1 = Swish(BN1(e)) and the projection input sc = Swish(BN2(d))*g, and
+ * backward reads those instead of rebuilding them. */
+typedef enum { MBCONV_RECOMPUTE = 0, MBCONV_STORE = 1 } mbconv_policy;
+
+typedef struct {
+    int32_t N, Cin, H, W; /* input x is [N,Cin,H,W] */
+    int32_t Cexp;         /* expanded channels; must equal Cin when has_expand == 0 */
+    int32_t Cse, Cout;    /* SE bottleneck width, output channels */
+    int32_t k, stride, pad; /* depthwise: k in {3,5}, stride in {1,2}, pad == (k-1)/2 */
+    int32_t has_expand;   /* 0: no expansion conv, no BN1, no first Swish (expand ratio 1) */
+    int32_t residual;     /* 1: out += x; requires stride == 1 and Cin == Cout */
+    int32_t dtype;        /* mbconv_dtype */
+    int32_t policy;       /* mbconv_policy */
+    float bn_eps;         /* added to the biased batch variance */
+    float bn_momentum;    /* running <- (1-momentum)*running + momentum*batch */
+} mbconv_desc;
+
+/* Parameters, read-only in both calls. */
+typedef struct {
+    const void *w_expand;               /* [Cexp,Cin]   dtype; NULL iff !has_expand */
+    const float *bn1_gamma, *bn1_beta;  /* [Cexp]; NULL iff !has_expand */
+    const void *w_dw;                   /* [Cexp,k,k]   dtype */
+    const float *bn2_gamma, *bn2_beta;  /* [Cexp] */
+    const float *se_w1, *se_b1;         /* [Cse,Cexp], [Cse] */
+    const float *se_w2, *se_b2;         /* [Cexp,Cse], [Cexp] */
+    const void *w_proj;                 /* [Cout,Cexp]  dtype */
+    const float *bn3_gamma, *bn3_beta;  /* [Cout] */
+} mbconv_params;
+
+/* Running statistics, updated in place by mbconv_forward.  The variance entering the
+ * update is the unbiased batch estimate.  bn1_* may be NULL iff !has_expand. */
+typedef struct {
+    float *bn1_mean, *bn1_var; /* [Cexp] */
+    float *bn2_mean, *bn2_var; /* [Cexp] */
+    float *bn3_mean, *bn3_var; /* [Cout] */
+} mbconv_bn_state;
+
+/* Parameter gradients, all fp32, same shapes as mbconv_params; OVERWRITTEN, never
+ * accumulated.  w_expand, bn1_gamma, bn1_beta may be NULL iff !has_expand. */
+typedef struct {
+    float *w_expand;
+    float *bn1_gamma, *bn1_beta;
+    float *w_dw;
+    float *bn2_gamma, *bn2_beta;
+    float *se_w1, *se_b1;
+    float *se_w2, *se_b2;
+    float *w_proj;
+    float *bn3_gamma, *bn3_beta;
+} mbconv_grads;
+
+/* Byte offsets of the named tensors inside the saved workspace, for inspection by
+ * tests and tools (SIZE_MAX where a tensor is absent for this descriptor).
+ * e, d, p, a1, sc are stored in `dtype`; the rest are fp32.
+ * bnX holds four consecutive [C] arrays: scale = gamma*rstd, shift = beta-mean*scale,
+ * mean, rstd. */
+typedef struct {
+    size_t e;   /* [N,Cexp,H,W]   expansion conv output, before BN1 */
+    size_t d;   /* [N,Cexp,Ho,Wo] depthwise conv output, before BN2 */
+    size_t p;   /* [N,Cout,Ho,Wo] projection conv output, before BN3 */
+    size_t bn1, bn2, bn3;
+    size_t z;   /* [N,Cexp] SE squeeze (plane means of Swish(BN2(d))) */
+    size_t g;   /* [N,Cexp] SE gate */
+    size_t q;   /* [N,Cse]  SE hidden pre-activation */
+    size_t a1;  /* [N,Cexp,H,W]   STORE policy only */
+    size_t sc;  /* [N,Cexp,Ho,Wo] STORE policy only */
+} mbconv_saved_layout;
+
+/* Host-only queries.  Both validate the descriptor (MBCONV_EINVAL / MBCONV_EUNSUPPORTED).
+ * saved_bytes: what forward writes and the matching backward reads.
+ * scratch_bytes: temporary storage either call may overwrite; it can be shared by every
+ * block of a network provided it is as large as the largest request. */
+mbconv_status mbconv_workspace_size(const mbconv_desc *desc, size_t *saved_bytes,
+                                    size_t *scratch_bytes);
+mbconv_status mbconv_saved_offsets(const mbconv_desc *desc, mbconv_saved_layout *layout);
+
+/* Forward, training mode.
+ *   x   [N,Cin,H,W] dtype, read-only.      out [N,Cout,Ho,Wo] dtype, written.
+ *   running: updated in place (may be NULL as a whole to skip the running update).
+ *   saved_ws: at least saved_bytes, written; must reach the matching backward unmodified.
+ *   scratch_ws: at least scratch_bytes, overwritten. */
+mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *params,
+                             mbconv_bn_state *running, const void *x, void *out, void *saved_ws,
+                             void *scratch_ws, void *hip_stream);
+
+/* Backward of the forward call that wrote saved_ws (same desc, params and x).
+ *   dout [N,Cout,Ho,Wo] dtype, read-only.   dx [N,Cin,H,W] dtype, written.
+ *   grads: every non-NULL member is overwritten with the gradient of sum(out*dout).
+ * Every reduction runs in a fixed order without floating-point atomics, so results are
+ * bitwise repeatable (the paper removes backward atomics by map fission, section
+ * "Guided Optimization Case Study: EfficientNet"). */
+mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *params, const void *x,
+                              const void *dout, const void *saved_ws, void *scratch_ws, void *dx,
+                              mbconv_grads *grads, void *hip_stream);
+
+/* Static string for a status code. */
+const char *mbconv_status_string(mbconv_status status);
+
+/* Library version, for the binding's sanity check. */
+int32_t mbconv_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MBCONV_H */

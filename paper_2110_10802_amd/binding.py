@@ -1,0 +1,151 @@
+"""ctypes binding of libmbconv (argument marshalling only).
+
+The functions mirror include/mbconv.h one to one.  Tensors are anything with a
+``data_ptr()`` method (PyTorch-ROCm tensors are used for device memory and the
+stream; nothing is computed in Python).  There is no fallback: if the HIP
+library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Any, Dict, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmbconv.so")
+
+MBCONV_F32, MBCONV_BF16 = 0, 1
+MBCONV_RECOMPUTE, MBCONV_STORE = 0, 1
+ABI_VERSION = 1
+ABSENT = C.c_size_t(-1).value
+
+PARAM_NAMES = ["w_expand", "bn1_gamma", "bn1_beta", "w_dw", "bn2_gamma", "bn2_beta", "se_w1",
+               "se_b1", "se_w2", "se_b2", "w_proj", "bn3_gamma", "bn3_beta"]
+RUNNING_NAMES = ["bn1_mean", "bn1_var", "bn2_mean", "bn2_var", "bn3_mean", "bn3_var"]
+SAVED_NAMES = ["e", "d", "p", "bn1", "bn2", "bn3", "z", "g", "q", "a1", "sc"]
+EXPORTS = ["mbconv_workspace_size", "mbconv_saved_offsets", "mbconv_forward", "mbconv_backward",
+           "mbconv_status_string", "mbconv_abi_version"]
+
+
+class MBConvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class Desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("N", "Cin", "H", "W", "Cexp", "Cse", "Cout", "k", "stride",
+                                          "pad", "has_expand", "residual", "dtype", "policy")] + \
+               [("bn_eps", C.c_float), ("bn_momentum", C.c_float)]
+
+
+class Params(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES]
+
+
+class Grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES]
+
+
+class BNState(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in RUNNING_NAMES]
+
+
+class SavedLayout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in SAVED_NAMES]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libmbconv.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2110_10802_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        lib = C.CDLL(LIB_PATH)
+        vp = C.c_void_p
+        lib.mbconv_abi_version.restype = C.c_int32
+        lib.mbconv_status_string.restype = C.c_char_p
+        lib.mbconv_status_string.argtypes = [C.c_int]
+        lib.mbconv_workspace_size.restype = C.c_int
+        lib.mbconv_workspace_size.argtypes = [C.POINTER(Desc), C.POINTER(C.c_size_t),
+                                              C.POINTER(C.c_size_t)]
+        lib.mbconv_saved_offsets.restype = C.c_int
+        lib.mbconv_saved_offsets.argtypes = [C.POINTER(Desc), C.POINTER(SavedLayout)]
+        lib.mbconv_forward.restype = C.c_int
+        lib.mbconv_forward.argtypes = [C.POINTER(Desc), C.POINTER(Params), C.POINTER(BNState), vp,
+                                       vp, vp, vp, vp]
+        lib.mbconv_backward.restype = C.c_int
+        lib.mbconv_backward.argtypes = [C.POINTER(Desc), C.POINTER(Params), vp, vp, vp, vp, vp,
+                                        C.POINTER(Grads), vp]
+        if lib.mbconv_abi_version() != ABI_VERSION:
+            raise RuntimeError("libmbconv.so ABI version mismatch; rebuild")
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().mbconv_status_string(int(status)).decode()
+
+
+def _ptr(t: Any) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def make_desc(shape: Any, policy: int = MBCONV_RECOMPUTE) -> Desc:
+    """Descriptor from any object with the BlockShape attributes."""
+    return Desc(shape.N, shape.Cin, shape.H, shape.W, shape.Cexp, shape.Cse, shape.Cout, shape.k,
+                shape.stride, shape.pad, int(shape.has_expand), int(shape.residual),
+                MBCONV_BF16 if shape.dtype == "bf16" else MBCONV_F32, int(policy),
+                float(shape.eps), float(shape.momentum))
+
+
+def _fill(struct, tensors: Optional[Dict[str, Any]]):
+    if tensors is not None:
+        for name, _ in struct._fields_:
+            setattr(struct, name, _ptr(tensors.get(name)))
+    return struct
+
+
+def mbconv_workspace_size(desc: Desc) -> Tuple[int, int]:
+    saved, scratch = C.c_size_t(0), C.c_size_t(0)
+    rc = load().mbconv_workspace_size(C.byref(desc), C.byref(saved), C.byref(scratch))
+    if rc != 0:
+        raise MBConvError(rc, "mbconv_workspace_size")
+    return saved.value, scratch.value
+
+
+def mbconv_saved_offsets(desc: Desc) -> Dict[str, Optional[int]]:
+    lay = SavedLayout()
+    rc = load().mbconv_saved_offsets(C.byref(desc), C.byref(lay))
+    if rc != 0:
+        raise MBConvError(rc, "mbconv_saved_offsets")
+    return {n: (None if getattr(lay, n) == ABSENT else getattr(lay, n)) for n in SAVED_NAMES}
+
+
+def mbconv_forward(desc: Desc, params: Dict[str, Any], running: Optional[Dict[str, Any]], x: Any,
+                   out: Any, saved_ws: Any, scratch_ws: Any, stream: int = 0) -> None:
+    ps = _fill(Params(), params)
+    rs = _fill(BNState(), running) if running is not None else None
+    rc = load().mbconv_forward(C.byref(desc), C.byref(ps), C.byref(rs) if rs is not None else None,
+                               _ptr(x), _ptr(out), _ptr(saved_ws), _ptr(scratch_ws), stream or None)
+    if rc != 0:
+        raise MBConvError(rc, "mbconv_forward")
+
+
+def mbconv_backward(desc: Desc, params: Dict[str, Any], x: Any, dout: Any, saved_ws: Any,
+                    scratch_ws: Any, dx: Any, grads: Dict[str, Any], stream: int = 0) -> None:
+    ps = _fill(Params(), params)
+    gs = _fill(Grads(), grads)
+    rc = load().mbconv_backward(C.byref(desc), C.byref(ps), _ptr(x), _ptr(dout), _ptr(saved_ws),
+                                _ptr(scratch_ws), _ptr(dx), C.byref(gs), stream or None)
+    if rc != 0:
+        raise MBConvError(rc, "mbconv_backward")

@@ -1,0 +1,364 @@
+// 1x1 convolutions as N-batched GEMMs on the gfx950 matrix cores.
+//
+// A 1x1 convolution in NCHW is out_n[M x HW] = A[M x K] * B_n[K x HW] with no im2col
+// copy (the paper lowers convolutions to matrix products, section "ONNX on SDFG").  The
+// pixel axis is the contiguous one, so it is put on the MFMA column axis: every
+// accumulator register then holds 32 consecutive pixels of one output channel across
+// lanes 0..31 and stores are 128-byte runs.
+//
+// The B operand is produced by an elementwise prologue while it is staged into LDS
+// (Swish(BN(.))*gate for the projection conv, the BN-backward expression for the two
+// data-gradient convs), so those intermediates never exist in HBM (the paper's
+// SubgraphFusion / TaskletFusion recompute knob, sections "Local Data Movement
+// Reduction" and "Backpropagation and Data Movement").
+#include "mbconv_dev.h"
+#include "mbconv_launch.h"
+
+namespace mbk {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+struct DevOperand {
+    const void *p0, *p1;
+    const float *c0, *c1, *c2, *gate;
+};
+
+template <typename T, int PRO>
+__device__ __forceinline__ float load_operand(const DevOperand &o, int n, int c, int C, int HW,
+                                              int pix)
+{
+    const size_t idx = ((size_t)n * C + c) * HW + pix;
+    const float v = ld<T>((const T *)o.p0, idx);
+    if (PRO == PRO_NONE) {
+        return v;
+    } else if (PRO == PRO_BNSWISH_GATE) {
+        const float y = fmaf(v, o.c0[c], o.c1[c]);
+        return swishf(y) * o.gate[(size_t)n * C + c];
+    } else {
+        const float raw = ld<T>((const T *)o.p1, idx);
+        return fmaf(o.c0[c], v, fmaf(o.c1[c], raw, o.c2[c]));
+    }
+}
+
+struct Conv1x1Args {
+    int N, M, K, HW;
+    long long Q; // N*HW
+    FastDiv divHW;
+    const void *w;
+    int sAm, sAk;
+    DevOperand B;
+    void *out;
+    const void *res;
+    float *psum, *psq;
+    int NT;
+    void *sc_store; // optional: receives the staged B operand (STORE policy), same layout as B
+};
+
+// Workgroup tile: 64 output channels x 128 pixels, K consumed 16 at a time.
+// 4 waves as 2 (channels) x 2 (pixels); each wave owns a 32 x 64 block = two
+// v_mfma_f32_32x32x2_f32 accumulators.
+template <typename T, int PRO, int EPI>
+__global__ __launch_bounds__(256) void conv1x1_kernel(Conv1x1Args a)
+{
+    constexpr int BM = 64, BQ = kConvBQ, BK = 16;
+    __shared__ float As[BK][BM];
+    __shared__ float Bs[BK][BQ];
+    __shared__ float red[2][BM][2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wq = wave & 1;
+    const int m0 = blockIdx.y * BM;
+    const long long q0 = (long long)blockIdx.x * BQ;
+
+    // B staging: this thread always stages pixel column bq, rows bk0, bk0+2, ...
+    const int bq = tid & (BQ - 1), bk0 = tid >> 7;
+    const long long qb = q0 + bq;
+    const bool bvalid = qb < a.Q;
+    int bn = 0, bpix = 0;
+    if (bvalid) {
+        bn = (int)fdiv((uint32_t)qb, a.divHW);
+        bpix = (int)(qb - (long long)bn * a.HW);
+    }
+
+    float16v acc0 = {0}, acc1 = {0};
+    for (int k0 = 0; k0 < a.K; k0 += BK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = tid + 256 * i;
+            const int m = id & (BM - 1), kk = id >> 6;
+            const int gm = m0 + m, gk = k0 + kk;
+            float v = 0.f;
+            if (gm < a.M && gk < a.K)
+                v = ld<T>((const T *)a.w, (size_t)gm * a.sAm + (size_t)gk * a.sAk);
+            As[kk][m] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int kk = bk0 + 2 * i, gk = k0 + kk;
+            float v = 0.f;
+            if (bvalid && gk < a.K) {
+                v = load_operand<T, PRO>(a.B, bn, gk, a.K, a.HW, bpix);
+                if (PRO == PRO_BNSWISH_GATE && a.sc_store && blockIdx.y == 0)
+                    st<T>((T *)a.sc_store, ((size_t)bn * a.K + gk) * a.HW + bpix, v);
+            }
+            Bs[kk][bq] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            const float av = As[kk + (lane >> 5)][wm * 32 + (lane & 31)];
+            const float b0 = Bs[kk + (lane >> 5)][wq * 64 + (lane & 31)];
+            const float b1 = Bs[kk + (lane >> 5)][wq * 64 + 32 + (lane & 31)];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b1, acc1, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // Accumulator register r of lane l is out[row 8*(r/4)+4*(l/32)+r%4][col l%32].
+    float rs[16], rq[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        rs[r] = rq[r] = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const long long q = q0 + wq * 64 + t * 32 + (lane & 31);
+        const bool valid = q < a.Q;
+        int n = 0, pix = 0;
+        if (valid) {
+            n = (int)fdiv((uint32_t)q, a.divHW);
+            pix = (int)(q - (long long)n * a.HW);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            float v = t == 0 ? acc0[r] : acc1[r];
+            if (valid && m < a.M) {
+                const size_t idx = ((size_t)n * a.M + m) * a.HW + pix;
+                if (EPI == EPI_RES)
+                    v += ld<T>((const T *)a.res, idx);
+                st<T>((T *)a.out, idx, v);
+                if (EPI == EPI_STATS) {
+                    const float sv = as_stored<T>(v);
+                    rs[r] += sv;
+                    rq[r] += sv * sv;
+                }
+            }
+        }
+    }
+    if (EPI == EPI_STATS) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float s = half_wave_sum(rs[r]);
+            const float s2 = half_wave_sum(rq[r]);
+            if ((lane & 31) == 0) {
+                const int row = wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                red[0][row][wq] = s;
+                red[1][row][wq] = s2;
+            }
+        }
+        __syncthreads();
+        if (tid < BM && m0 + tid < a.M) {
+            a.psum[(size_t)(m0 + tid) * a.NT + blockIdx.x] = red[0][tid][0] + red[0][tid][1];
+            a.psq[(size_t)(m0 + tid) * a.NT + blockIdx.x] = red[1][tid][0] + red[1][tid][1];
+        }
+    }
+}
+
+static DevOperand to_dev(const Operand &o)
+{
+    DevOperand d;
+    d.p0 = o.p0;
+    d.p1 = o.p1;
+    d.c0 = o.c0;
+    d.c1 = o.c1;
+    d.c2 = o.c2;
+    d.gate = o.gate;
+    return d;
+}
+
+template <typename T>
+static hipError_t conv1x1_dispatch(const Conv1x1Args &a, int pro, int epi, dim3 grid, hipStream_t st)
+{
+#define MBK_CASE(P, E)                                                                            \
+    if (pro == P && epi == E) {                                                                   \
+        hipLaunchKernelGGL((conv1x1_kernel<T, P, E>), grid, dim3(256), 0, st, a);                 \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(PRO_NONE, EPI_STATS)
+    MBK_CASE(PRO_BNSWISH_GATE, EPI_STATS)
+    MBK_CASE(PRO_BNBWD, EPI_NONE)
+    MBK_CASE(PRO_BNBWD, EPI_RES)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
+                          const Operand &B, void *out, int epi, const void *res, float *psum,
+                          float *psq, void *sc_store, hipStream_t st)
+{
+    Conv1x1Args a;
+    a.N = N;
+    a.M = M;
+    a.K = K;
+    a.HW = HW;
+    a.Q = (long long)N * HW;
+    a.divHW = make_div((uint32_t)HW);
+    a.w = w;
+    a.sAm = sAm;
+    a.sAk = sAk;
+    a.B = to_dev(B);
+    a.out = out;
+    a.res = res;
+    a.psum = psum;
+    a.psq = psq;
+    a.NT = conv1x1_num_qtiles(N, HW);
+    a.sc_store = sc_store;
+    dim3 grid((unsigned)a.NT, (unsigned)((M + 63) / 64));
+    return bf16 ? conv1x1_dispatch<bf16_t>(a, B.pro, epi, grid, st)
+                : conv1x1_dispatch<float>(a, B.pro, epi, grid, st);
+}
+
+// ---- weight gradient ------------------------------------------------------------------------
+// dW[a,b] = sum_q U[a,q]*V[b,q]: the contraction runs over all N*HW pixels, so it is
+// split across workgroups; every workgroup writes its own partial tile and a second
+// kernel adds the partials in a fixed order (no atomics: the paper's map-fission step,
+// section "Guided Optimization Case Study: EfficientNet").
+
+struct WgradArgs {
+    int N, Ma, Mb, HW;
+    long long Q, chunk;
+    FastDiv divHW;
+    DevOperand U, V;
+    float *partial;
+};
+
+template <typename T, int PROU, int PROV>
+__global__ __launch_bounds__(256) void wgrad1x1_kernel(WgradArgs a)
+{
+    constexpr int BA = 64, BB = 64, BQ = 32;
+    __shared__ float Us[BQ][BA + 1];
+    __shared__ float Vs[BQ][BB + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wa = wave >> 1, wb = wave & 1;
+    const int a0 = blockIdx.x * BA, b0 = blockIdx.y * BB;
+    const long long qbeg = (long long)blockIdx.z * a.chunk;
+    const long long qend = (qbeg + a.chunk < a.Q) ? qbeg + a.chunk : a.Q;
+    const int sq = tid & 31, r0 = tid >> 5;
+
+    float16v acc = {0};
+    for (long long qb = qbeg; qb < qend; qb += BQ) {
+        const long long q = qb + sq;
+        const bool valid = q < qend;
+        int n = 0, pix = 0;
+        if (valid) {
+            n = (int)fdiv((uint32_t)q, a.divHW);
+            pix = (int)(q - (long long)n * a.HW);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = r0 + 8 * i;
+            float u = 0.f, v = 0.f;
+            if (valid && a0 + r < a.Ma)
+                u = load_operand<T, PROU>(a.U, n, a0 + r, a.Ma, a.HW, pix);
+            if (valid && b0 + r < a.Mb)
+                v = load_operand<T, PROV>(a.V, n, b0 + r, a.Mb, a.HW, pix);
+            Us[sq][r] = u;
+            Vs[sq][r] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int qq = 0; qq < BQ; qq += 2) {
+            const float u = Us[qq + (lane >> 5)][wa * 32 + (lane & 31)];
+            const float v = Vs[qq + (lane >> 5)][wb * 32 + (lane & 31)];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(u, v, acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    float *dst = a.partial + (size_t)blockIdx.z * a.Ma * a.Mb;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int ai = a0 + wa * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int bi = b0 + wb * 32 + (lane & 31);
+        if (ai < a.Ma && bi < a.Mb)
+            dst[(size_t)ai * a.Mb + bi] = acc[r];
+    }
+}
+
+static long long wgrad_chunk(int Ma, int Mb, long long Q)
+{
+    const long long tiles = (long long)((Ma + 63) / 64) * ((Mb + 63) / 64);
+    long long want = 1024 / tiles; // workgroups along the contraction
+    if (want < 1)
+        want = 1;
+    long long chunk = (Q + want - 1) / want;
+    chunk = ((chunk + 31) / 32) * 32;
+    if (chunk < 128)
+        chunk = 128;
+    return chunk;
+}
+
+int wgrad_splits(int Ma, int Mb, int N, int HW)
+{
+    const long long Q = (long long)N * HW;
+    const long long chunk = wgrad_chunk(Ma, Mb, Q);
+    return (int)((Q + chunk - 1) / chunk);
+}
+
+__global__ void reduce_splits_kernel(const float *__restrict__ in, int S, size_t count,
+                                     float *__restrict__ out)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count)
+        return;
+    float s = 0.f;
+    for (int k = 0; k < S; ++k)
+        s += in[(size_t)k * count + i];
+    out[i] = s;
+}
+
+hipError_t launch_reduce_splits(const float *in, int S, size_t count, float *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0,
+                       st, in, S, count, out);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t wgrad_dispatch(const WgradArgs &a, int pu, int pv, dim3 grid, hipStream_t st)
+{
+#define MBK_CASE(PU, PV)                                                                          \
+    if (pu == PU && pv == PV) {                                                                   \
+        hipLaunchKernelGGL((wgrad1x1_kernel<T, PU, PV>), grid, dim3(256), 0, st, a);              \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(PRO_BNBWD, PRO_NONE)
+    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
+                           const Operand &V, float *partial, float *dW, hipStream_t st)
+{
+    WgradArgs a;
+    a.N = N;
+    a.Ma = Ma;
+    a.Mb = Mb;
+    a.HW = HW;
+    a.Q = (long long)N * HW;
+    a.chunk = wgrad_chunk(Ma, Mb, a.Q);
+    a.divHW = make_div((uint32_t)HW);
+    a.U = to_dev(U);
+    a.V = to_dev(V);
+    a.partial = partial;
+    const int S = (int)((a.Q + a.chunk - 1) / a.chunk);
+    dim3 grid((unsigned)((Ma + 63) / 64), (unsigned)((Mb + 63) / 64), (unsigned)S);
+    hipError_t err = bf16 ? wgrad_dispatch<bf16_t>(a, U.pro, V.pro, grid, st)
+                          : wgrad_dispatch<float>(a, U.pro, V.pro, grid, st);
+    if (err != hipSuccess)
+        return err;
+    return launch_reduce_splits(partial, S, (size_t)Ma * Mb, dW, st);
+}
+
+} // namespace mbk

@@ -1,0 +1,469 @@
+// C ABI of libmbconv: argument validation, workspace layout and the launch sequence of
+// one MBConv training step.  See include/mbconv.h for the contract.
+#include "../../include/mbconv.h"
+#include "mbconv_launch.h"
+
+#include <algorithm>
+#include <cstdint>
+
+using namespace mbk;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr size_t kAbsent = SIZE_MAX;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+    int N, Cin, H, W, Cexp, Cse, Cout, k, s, p, Ho, Wo;
+    bool expand, res, bf16, store;
+    size_t esz;
+    size_t nX, nE, nD, nP;
+    int HW, HWo;
+    // saved workspace (byte offsets)
+    size_t o_e, o_d, o_p, o_bn1, o_bn2, o_bn3, o_z, o_g, o_q, o_s3, o_s4, o_a1, o_sc, saved_bytes;
+    // scratch workspace (byte offsets)
+    size_t o_part;  // partial sums: 2 arrays of part_floats
+    size_t part_floats;
+    size_t o_G, o_dy1, o_coef3, o_coef2, o_coef1, o_dg, o_A1, o_A2, o_dt, o_dq, o_dzs, o_pdw, o_wg;
+    size_t scratch_bytes;
+    int NT1, NT5; // q-tiles of the expansion / projection conv
+};
+
+mbconv_status check_desc(const mbconv_desc *d)
+{
+    if (!d)
+        return MBCONV_EINVAL;
+    if (d->N < 1 || d->Cin < 1 || d->H < 1 || d->W < 1 || d->Cexp < 1 || d->Cse < 1 || d->Cout < 1)
+        return MBCONV_EINVAL;
+    if (d->dtype != MBCONV_F32 && d->dtype != MBCONV_BF16)
+        return MBCONV_EINVAL;
+    if (d->policy != MBCONV_RECOMPUTE && d->policy != MBCONV_STORE)
+        return MBCONV_EINVAL;
+    if (!d->has_expand && d->Cexp != d->Cin)
+        return MBCONV_EINVAL;
+    if (d->residual && (d->stride != 1 || d->Cin != d->Cout))
+        return MBCONV_EINVAL;
+    if (!(d->bn_eps >= 0.f) || !(d->bn_momentum >= 0.f && d->bn_momentum <= 1.f))
+        return MBCONV_EINVAL;
+    if (d->k != 3 && d->k != 5)
+        return MBCONV_EUNSUPPORTED;
+    if (d->stride != 1 && d->stride != 2)
+        return MBCONV_EUNSUPPORTED;
+    if (d->pad != (d->k - 1) / 2)
+        return MBCONV_EUNSUPPORTED;
+    if (d->H > 128 || d->W > 128) // a whole plane (with border) must fit in LDS
+        return MBCONV_EUNSUPPORTED;
+    if ((long long)d->N * d->H * d->W >= (1ll << 31) ||
+        (long long)d->N * std::max(d->Cexp, std::max(d->Cin, d->Cout)) >= (1ll << 31))
+        return MBCONV_EUNSUPPORTED;
+    return MBCONV_OK;
+}
+
+Plan make_plan(const mbconv_desc *d)
+{
+    Plan P = {};
+    P.N = d->N;
+    P.Cin = d->Cin;
+    P.H = d->H;
+    P.W = d->W;
+    P.Cexp = d->Cexp;
+    P.Cse = d->Cse;
+    P.Cout = d->Cout;
+    P.k = d->k;
+    P.s = d->stride;
+    P.p = d->pad;
+    P.Ho = (d->H + 2 * d->pad - d->k) / d->stride + 1;
+    P.Wo = (d->W + 2 * d->pad - d->k) / d->stride + 1;
+    P.expand = d->has_expand != 0;
+    P.res = d->residual != 0;
+    P.bf16 = d->dtype == MBCONV_BF16;
+    P.store = d->policy == MBCONV_STORE;
+    P.esz = P.bf16 ? 2 : 4;
+    P.HW = P.H * P.W;
+    P.HWo = P.Ho * P.Wo;
+    P.nX = (size_t)P.N * P.Cin * P.HW;
+    P.nE = (size_t)P.N * P.Cexp * P.HW;
+    P.nD = (size_t)P.N * P.Cexp * P.HWo;
+    P.nP = (size_t)P.N * P.Cout * P.HWo;
+    P.NT1 = conv1x1_num_qtiles(P.N, P.HW);
+    P.NT5 = conv1x1_num_qtiles(P.N, P.HWo);
+
+    size_t o = 0;
+    auto take = [&o](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes);
+        return at;
+    };
+    const size_t f = sizeof(float);
+    P.o_e = P.expand ? take(P.nE * P.esz) : kAbsent;
+    P.o_d = take(P.nD * P.esz);
+    P.o_p = take(P.nP * P.esz);
+    P.o_bn1 = P.expand ? take(4 * P.Cexp * f) : kAbsent;
+    P.o_bn2 = take(4 * P.Cexp * f);
+    P.o_bn3 = take(4 * P.Cout * f);
+    P.o_z = take((size_t)P.N * P.Cexp * f);
+    P.o_g = take((size_t)P.N * P.Cexp * f);
+    P.o_q = take((size_t)P.N * P.Cse * f);
+    P.o_s3 = take((size_t)P.N * P.Cexp * f);
+    P.o_s4 = take((size_t)P.N * P.Cexp * f);
+    P.o_a1 = (P.store && P.expand) ? take(P.nE * P.esz) : kAbsent;
+    P.o_sc = P.store ? take(P.nD * P.esz) : kAbsent;
+    P.saved_bytes = o;
+
+    o = 0;
+    size_t part = (size_t)P.Cexp * P.N;                       // depthwise planes
+    part = std::max(part, (size_t)P.Cout * P.N);              // BN3 backward planes
+    part = std::max(part, (size_t)P.Cout * P.NT5);            // projection conv tiles
+    if (P.expand)
+        part = std::max(part, (size_t)P.Cexp * P.NT1);        // expansion conv tiles
+    P.part_floats = part;
+    P.o_part = take(2 * part * f);
+    P.o_G = take(P.nD * P.esz);
+    P.o_dy1 = P.expand ? take(P.nE * P.esz) : kAbsent;
+    P.o_coef3 = take(3 * P.Cout * f);
+    P.o_coef2 = take(3 * P.Cexp * f);
+    P.o_coef1 = P.expand ? take(3 * P.Cexp * f) : kAbsent;
+    P.o_dg = take((size_t)P.N * P.Cexp * f);
+    P.o_A1 = take((size_t)P.N * P.Cexp * f);
+    P.o_A2 = take((size_t)P.N * P.Cexp * f);
+    P.o_dt = take((size_t)P.N * P.Cexp * f);
+    P.o_dq = take((size_t)P.N * P.Cse * f);
+    P.o_dzs = take((size_t)P.N * P.Cexp * f);
+    P.o_pdw = take((size_t)P.N * P.Cexp * P.k * P.k * f);
+    size_t wg = (size_t)wgrad_splits(P.Cout, P.Cexp, P.N, P.HWo) * P.Cout * P.Cexp;
+    if (P.expand)
+        wg = std::max(wg, (size_t)wgrad_splits(P.Cexp, P.Cin, P.N, P.HW) * P.Cexp * P.Cin);
+    P.o_wg = take(wg * f);
+    P.scratch_bytes = o;
+    return P;
+}
+
+bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+template <typename T>
+T *at(void *base, size_t off)
+{
+    return reinterpret_cast<T *>(static_cast<char *>(base) + off);
+}
+template <typename T>
+const T *at(const void *base, size_t off)
+{
+    return reinterpret_cast<const T *>(static_cast<const char *>(base) + off);
+}
+
+#define MBK_TRY(expr)                                                                             \
+    do {                                                                                          \
+        if ((expr) != hipSuccess)                                                                 \
+            return MBCONV_EHIP;                                                                   \
+    } while (0)
+
+mbconv_status check_params(const mbconv_desc *d, const mbconv_params *p)
+{
+    if (!p)
+        return MBCONV_EINVAL;
+    const void *req[] = {p->w_dw,  p->bn2_gamma, p->bn2_beta, p->se_w1,     p->se_b1,   p->se_w2,
+                         p->se_b2, p->w_proj,    p->bn3_gamma, p->bn3_beta};
+    for (const void *q : req)
+        if (!q)
+            return MBCONV_EINVAL;
+    if (d->has_expand && (!p->w_expand || !p->bn1_gamma || !p->bn1_beta))
+        return MBCONV_EINVAL;
+    const void *all[] = {p->w_expand, p->bn1_gamma, p->bn1_beta, p->w_dw,  p->bn2_gamma,
+                         p->bn2_beta, p->se_w1,     p->se_b1,    p->se_w2, p->se_b2,
+                         p->w_proj,   p->bn3_gamma, p->bn3_beta};
+    for (const void *q : all)
+        if (q && misaligned(q))
+            return MBCONV_EALIGN;
+    return MBCONV_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int32_t mbconv_abi_version(void) { return 1; }
+
+const char *mbconv_status_string(mbconv_status s)
+{
+    switch (s) {
+    case MBCONV_OK:
+        return "ok";
+    case MBCONV_EINVAL:
+        return "invalid argument";
+    case MBCONV_EUNSUPPORTED:
+        return "unsupported shape";
+    case MBCONV_EWORKSPACE:
+        return "workspace too small";
+    case MBCONV_EALIGN:
+        return "pointer not 16-byte aligned";
+    case MBCONV_EHIP:
+        return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+mbconv_status mbconv_workspace_size(const mbconv_desc *desc, size_t *saved_bytes,
+                                    size_t *scratch_bytes)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!saved_bytes || !scratch_bytes)
+        return MBCONV_EINVAL;
+    const Plan P = make_plan(desc);
+    *saved_bytes = P.saved_bytes;
+    *scratch_bytes = P.scratch_bytes;
+    return MBCONV_OK;
+}
+
+mbconv_status mbconv_saved_offsets(const mbconv_desc *desc, mbconv_saved_layout *L)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!L)
+        return MBCONV_EINVAL;
+    const Plan P = make_plan(desc);
+    L->e = P.o_e;
+    L->d = P.o_d;
+    L->p = P.o_p;
+    L->bn1 = P.o_bn1;
+    L->bn2 = P.o_bn2;
+    L->bn3 = P.o_bn3;
+    L->z = P.o_z;
+    L->g = P.o_g;
+    L->q = P.o_q;
+    L->a1 = P.o_a1;
+    L->sc = P.o_sc;
+    return MBCONV_OK;
+}
+
+mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *prm,
+                             mbconv_bn_state *run, const void *x, void *out, void *saved,
+                             void *scratch, void *hip_stream)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    s = check_params(desc, prm);
+    if (s != MBCONV_OK)
+        return s;
+    if (!x || !out || !saved || !scratch)
+        return MBCONV_EINVAL;
+    if (misaligned(x) || misaligned(out) || misaligned(saved) || misaligned(scratch))
+        return MBCONV_EALIGN;
+    if (run) {
+        if (!run->bn2_mean || !run->bn2_var || !run->bn3_mean || !run->bn3_var)
+            return MBCONV_EINVAL;
+        if (desc->has_expand && (!run->bn1_mean || !run->bn1_var))
+            return MBCONV_EINVAL;
+    }
+    const Plan P = make_plan(desc);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool bf = P.bf16;
+    float *psum = at<float>(scratch, P.o_part);
+    float *psq = psum + P.part_floats;
+    float *bn2 = at<float>(saved, P.o_bn2), *bn3 = at<float>(saved, P.o_bn3);
+    float *bn1 = P.expand ? at<float>(saved, P.o_bn1) : nullptr;
+    void *d = at<char>(saved, P.o_d), *p = at<char>(saved, P.o_p);
+    const float eps = desc->bn_eps, mom = desc->bn_momentum;
+
+    // expansion conv + BN1 statistics
+    const void *dw_in = x;
+    if (P.expand) {
+        void *e = at<char>(saved, P.o_e);
+        Operand B;
+        B.p0 = x;
+        B.pro = PRO_NONE;
+        MBK_TRY(launch_conv1x1(bf, P.N, P.Cexp, P.Cin, P.HW, prm->w_expand, P.Cin, 1, B, e,
+                               EPI_STATS, nullptr, psum, psq, nullptr, st));
+        MBK_TRY(launch_bn_finalize(P.Cexp, P.NT1, (double)P.N * P.HW, psum, psq, prm->bn1_gamma,
+                                   prm->bn1_beta, eps, mom, run ? run->bn1_mean : nullptr,
+                                   run ? run->bn1_var : nullptr, bn1, st));
+        dw_in = e;
+    }
+    // BN1 + Swish + depthwise + BN2 statistics
+    const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
+    void *a1_store = (P.store && P.expand) ? at<char>(saved, P.o_a1) : nullptr;
+    MBK_TRY(launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum, psq, a1_store, st));
+    MBK_TRY(launch_bn_finalize(P.Cexp, P.N, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
+                               prm->bn2_beta, eps, mom, run ? run->bn2_mean : nullptr,
+                               run ? run->bn2_var : nullptr, bn2, st));
+    // BN2 + Swish + SE squeeze, SE excite
+    float *z = at<float>(saved, P.o_z), *g = at<float>(saved, P.o_g), *q = at<float>(saved, P.o_q);
+    MBK_TRY(launch_pool(bf, P.N, P.Cexp, P.HWo, d, bn2, z, at<float>(saved, P.o_s3),
+                        at<float>(saved, P.o_s4), st));
+    MBK_TRY(launch_se_fwd(P.N, P.Cexp, P.Cse, z, prm->se_w1, prm->se_b1, prm->se_w2, prm->se_b2, q,
+                          g, st));
+    // projection conv on Swish(BN2(d))*g + BN3 statistics
+    {
+        Operand B;
+        B.p0 = d;
+        B.c0 = bn2;
+        B.c1 = bn2 + P.Cexp;
+        B.gate = g;
+        B.pro = PRO_BNSWISH_GATE;
+        void *sc_store = P.store ? at<char>(saved, P.o_sc) : nullptr;
+        MBK_TRY(launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p,
+                               EPI_STATS, nullptr, psum, psq, sc_store, st));
+        MBK_TRY(launch_bn_finalize(P.Cout, P.NT5, (double)P.N * P.HWo, psum, psq, prm->bn3_gamma,
+                                   prm->bn3_beta, eps, mom, run ? run->bn3_mean : nullptr,
+                                   run ? run->bn3_var : nullptr, bn3, st));
+    }
+    // BN3 (+ residual)
+    MBK_TRY(launch_bn_apply(bf, P.N, P.Cout, P.HWo, p, bn3, P.res ? x : nullptr, out, st));
+    return MBCONV_OK;
+}
+
+mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm, const void *x,
+                              const void *dout, const void *saved, void *scratch, void *dx,
+                              mbconv_grads *gr, void *hip_stream)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    s = check_params(desc, prm);
+    if (s != MBCONV_OK)
+        return s;
+    if (!x || !dout || !saved || !scratch || !dx || !gr)
+        return MBCONV_EINVAL;
+    if (misaligned(x) || misaligned(dout) || misaligned(saved) || misaligned(scratch) ||
+        misaligned(dx))
+        return MBCONV_EALIGN;
+    {
+        const void *req[] = {gr->w_dw,  gr->bn2_gamma, gr->bn2_beta,  gr->se_w1,   gr->se_b1,
+                             gr->se_w2, gr->se_b2,     gr->w_proj,    gr->bn3_gamma, gr->bn3_beta};
+        for (const void *q : req)
+            if (!q)
+                return MBCONV_EINVAL;
+        if (desc->has_expand && (!gr->w_expand || !gr->bn1_gamma || !gr->bn1_beta))
+            return MBCONV_EINVAL;
+    }
+    const Plan P = make_plan(desc);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool bf = P.bf16;
+    float *pa = at<float>(scratch, P.o_part);
+    float *pb = pa + P.part_floats;
+    const float *bn2 = at<float>(saved, P.o_bn2), *bn3 = at<float>(saved, P.o_bn3);
+    const float *bn1 = P.expand ? at<float>(saved, P.o_bn1) : nullptr;
+    const void *d = at<char>(saved, P.o_d), *p = at<char>(saved, P.o_p);
+    const float *z = at<float>(saved, P.o_z), *g = at<float>(saved, P.o_g);
+    const float *q = at<float>(saved, P.o_q);
+    float *coef3 = at<float>(scratch, P.o_coef3), *coef2 = at<float>(scratch, P.o_coef2);
+    void *G = at<char>(scratch, P.o_G);
+    float *wg = at<float>(scratch, P.o_wg);
+    const double m2 = (double)P.N * P.HWo;
+
+    // BN3 backward reductions
+    MBK_TRY(launch_plane_dot(bf, P.N, P.Cout, P.HWo, dout, p, bn3, pa, pb, st));
+    MBK_TRY(launch_bn_bwd_finalize(P.Cout, P.N, m2, pa, pb, prm->bn3_gamma, bn3, gr->bn3_gamma,
+                                   gr->bn3_beta, coef3, st));
+    // projection conv: data gradient G = W_p^T dp and weight gradient dW_p = dp * sc^T,
+    // dp rebuilt in the prologue from dout and p
+    Operand dp;
+    dp.p0 = dout;
+    dp.p1 = p;
+    dp.c0 = coef3;
+    dp.c1 = coef3 + P.Cout;
+    dp.c2 = coef3 + 2 * P.Cout;
+    dp.pro = PRO_BNBWD;
+    MBK_TRY(launch_conv1x1(bf, P.N, P.Cexp, P.Cout, P.HWo, prm->w_proj, 1, P.Cexp, dp, G, EPI_NONE,
+                           nullptr, nullptr, nullptr, nullptr, st));
+    {
+        Operand sc;
+        if (P.store) {
+            sc.p0 = at<char>(saved, P.o_sc);
+            sc.pro = PRO_NONE;
+        } else {
+            sc.p0 = d;
+            sc.c0 = bn2;
+            sc.c1 = bn2 + P.Cexp;
+            sc.gate = g;
+            sc.pro = PRO_BNSWISH_GATE;
+        }
+        MBK_TRY(launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, wg, gr->w_proj, st));
+    }
+    // SE backward and BN2 backward reductions
+    float *dg = at<float>(scratch, P.o_dg), *A1 = at<float>(scratch, P.o_A1);
+    float *A2 = at<float>(scratch, P.o_A2), *dzs = at<float>(scratch, P.o_dzs);
+    MBK_TRY(launch_gate_sums(bf, P.N, P.Cexp, P.HWo, G, d, bn2, dg, A1, A2, st));
+    {
+        SeBwdArgs a;
+        a.N = P.N;
+        a.C = P.Cexp;
+        a.Cse = P.Cse;
+        a.HW = P.HWo;
+        a.z = z;
+        a.g = g;
+        a.q = q;
+        a.w1 = prm->se_w1;
+        a.w2 = prm->se_w2;
+        a.dg = dg;
+        a.A1 = A1;
+        a.A2 = A2;
+        a.s3 = at<float>(saved, P.o_s3);
+        a.s4 = at<float>(saved, P.o_s4);
+        a.gamma2 = prm->bn2_gamma;
+        a.bn2 = bn2;
+        a.dt = at<float>(scratch, P.o_dt);
+        a.dq = at<float>(scratch, P.o_dq);
+        a.dzs = dzs;
+        a.dw1 = gr->se_w1;
+        a.db1 = gr->se_b1;
+        a.dw2 = gr->se_w2;
+        a.db2 = gr->se_b2;
+        a.dgamma2 = gr->bn2_gamma;
+        a.dbeta2 = gr->bn2_beta;
+        a.coef2 = coef2;
+        MBK_TRY(launch_se_bwd(a, st));
+    }
+    // fused depthwise backward
+    {
+        DwBwdArgs a;
+        a.s = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
+        a.G = G;
+        a.d = d;
+        a.e = P.expand ? at<char>(saved, P.o_e) : x;
+        a.g = g;
+        a.dzs = dzs;
+        a.bn2 = bn2;
+        a.coef2 = coef2;
+        a.bn1 = bn1;
+        a.w_dw = prm->w_dw;
+        a.a1_saved = (P.store && P.expand) ? at<char>(saved, P.o_a1) : nullptr;
+        a.dy1_out = P.expand ? at<char>(scratch, P.o_dy1) : dx;
+        a.res = (!P.expand && P.res) ? dout : nullptr;
+        a.pdw = at<float>(scratch, P.o_pdw);
+        a.psb = pa;
+        a.psr = pb;
+        MBK_TRY(launch_dw_bwd(bf, a, st));
+        MBK_TRY(launch_reduce_planes(a.pdw, P.Cexp, P.N, P.k * P.k, gr->w_dw, st));
+    }
+    if (P.expand) {
+        float *coef1 = at<float>(scratch, P.o_coef1);
+        const void *e = at<char>(saved, P.o_e);
+        const void *dy1 = at<char>(scratch, P.o_dy1);
+        MBK_TRY(launch_bn_bwd_finalize(P.Cexp, P.N, (double)P.N * P.HW, pa, pb, prm->bn1_gamma, bn1,
+                                       gr->bn1_gamma, gr->bn1_beta, coef1, st));
+        Operand de;
+        de.p0 = dy1;
+        de.p1 = e;
+        de.c0 = coef1;
+        de.c1 = coef1 + P.Cexp;
+        de.c2 = coef1 + 2 * P.Cexp;
+        de.pro = PRO_BNBWD;
+        // dx = W_e^T de (+ dout), dW_e = de * x^T
+        MBK_TRY(launch_conv1x1(bf, P.N, P.Cin, P.Cexp, P.HW, prm->w_expand, 1, P.Cin, de, dx,
+                               P.res ? EPI_RES : EPI_NONE, P.res ? dout : nullptr, nullptr, nullptr,
+                               nullptr, st));
+        Operand xo;
+        xo.p0 = x;
+        xo.pro = PRO_NONE;
+        MBK_TRY(launch_wgrad1x1(bf, P.N, P.Cexp, P.Cin, P.HW, de, xo, wg, gr->w_expand, st));
+    }
+    return MBCONV_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,162 @@
+// Device-side helpers shared by the gfx950 kernels of libmbconv.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mbk {
+
+constexpr int kWave = 64;
+
+struct bf16_t {
+    uint16_t bits;
+};
+
+// ---- storage <-> fp32 --------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ float ld(const T *p, size_t i);
+template <>
+__device__ __forceinline__ float ld<float>(const float *p, size_t i)
+{
+    return p[i];
+}
+template <>
+__device__ __forceinline__ float ld<bf16_t>(const bf16_t *p, size_t i)
+{
+    return bf16_bits_to_float(p[i].bits);
+}
+
+template <typename T>
+__device__ __forceinline__ void st(T *p, size_t i, float v);
+template <>
+__device__ __forceinline__ void st<float>(float *p, size_t i, float v)
+{
+    p[i] = v;
+}
+template <>
+__device__ __forceinline__ void st<bf16_t>(bf16_t *p, size_t i, float v)
+{
+    p[i].bits = float_to_bf16_bits(v);
+}
+
+// The value a tensor of type T holds after storing v.
+template <typename T>
+__device__ __forceinline__ float as_stored(float v);
+template <>
+__device__ __forceinline__ float as_stored<float>(float v)
+{
+    return v;
+}
+template <>
+__device__ __forceinline__ float as_stored<bf16_t>(float v)
+{
+    return bf16_bits_to_float(float_to_bf16_bits(v));
+}
+
+// ---- activation ----------------------------------------------------------------------
+
+__device__ __forceinline__ float sigmoidf_fast(float t)
+{
+    // 1/(1+2^(-t*log2 e)); v_exp_f32 and v_rcp_f32 are accurate to about 1 ulp
+    return __frcp_rn(1.0f + __expf(-t));
+}
+
+__device__ __forceinline__ float swishf(float t) { return t * sigmoidf_fast(t); }
+
+// Swish(t) and its derivative sigma*(1+t*(1-sigma)) from one sigmoid evaluation.
+__device__ __forceinline__ void swish_both(float t, float &val, float &grad)
+{
+    float s = sigmoidf_fast(t);
+    val = t * s;
+    grad = s * (1.0f + t * (1.0f - s));
+}
+
+// ---- integer division by a per-launch constant ------------------------------------------
+// Exact for every 32-bit numerator (the round-up multiply-shift scheme of Granlund and
+// Montgomery): with l = ceil(log2 d) and m = floor(2^32*(2^l-d)/d)+1,
+//   t = mulhi(m, n);  n/d = (t + ((n-t) >> min(l,1))) >> max(l-1,0).
+struct FastDiv {
+    uint32_t d, m, sh1, sh2;
+};
+inline FastDiv make_div(uint32_t d)
+{
+    FastDiv f;
+    uint32_t l = 0;
+    while ((1ull << l) < d)
+        ++l;
+    f.d = d;
+    f.m = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1ull);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l > 1 ? l - 1 : 0;
+    return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
+{
+    const uint32_t t = __umulhi(f.m, n);
+    return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
+// ---- reductions ------------------------------------------------------------------------
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// sum over the 32 lanes that share lane/32
+__device__ __forceinline__ float half_wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1)
+        v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// Sum of NV per-thread values over a group of TPP consecutive threads of the block
+// (TPP a multiple of 64, groups aligned).  `red` is LDS scratch of at least
+// (blockDim/64)*NV floats.  The result is valid in every thread of the group whose
+// lane index within the group is < NV... for simplicity it is returned in all threads.
+// All threads of the block must call it (it synchronises the block).
+template <int NV, int TPP>
+__device__ __forceinline__ void group_sum(float (&v)[NV], float *red)
+{
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+        v[i] = wave_sum(v[i]);
+    if (TPP > kWave) {
+        const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+        constexpr int WPG = TPP / kWave;
+        __syncthreads();
+        if (lane == 0) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+                red[wave * NV + i] = v[i];
+        }
+        __syncthreads();
+        const int g0 = (wave / WPG) * WPG;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            float s = 0.f;
+            for (int w = 0; w < WPG; ++w)
+                s += red[(g0 + w) * NV + i];
+            v[i] = s;
+        }
+    }
+}
+
+} // namespace mbk

@@ -1,0 +1,123 @@
+// Host-side launchers of the gfx950 kernels (internal to libmbconv).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mbk {
+
+// ---- operand of a 1x1 convolution with an elementwise prologue ------------------------
+// The tensor is [N,C,HW] in the activation dtype.  What the GEMM consumes is
+//   PRO_NONE         p0
+//   PRO_BNSWISH_GATE swish(p0*c0[c]+c1[c]) * gate[n,c]       (Swish(BN(.)) times the SE gate)
+//   PRO_BNBWD        c0[c]*p0 + c1[c]*p1 + c2[c]             (BN backward: p0 = dy, p1 = raw input)
+enum { PRO_NONE = 0, PRO_BNSWISH_GATE = 1, PRO_BNBWD = 2 };
+enum { EPI_NONE = 0, EPI_STATS = 1, EPI_RES = 2 };
+
+struct Operand {
+    const void *p0 = nullptr;
+    const void *p1 = nullptr;
+    const float *c0 = nullptr, *c1 = nullptr, *c2 = nullptr;
+    const float *gate = nullptr;
+    int pro = PRO_NONE;
+};
+
+constexpr int kConvBQ = 128; // pixel columns per workgroup of the 1x1 conv kernel
+
+inline int conv1x1_num_qtiles(int N, int HW) { return (int)(((long long)N * HW + kConvBQ - 1) / kConvBQ); }
+
+// out[n,m,q] = sum_k A(m,k) * op(B)[n,k,q], A(m,k) = w[m*sAm + k*sAk] (dtype).
+// epi: EPI_STATS writes per-(channel,q-tile) partial sums of out and out^2 to
+// psum/psq laid out [M][num_qtiles]; EPI_RES adds res[n,m,q] before the store.
+hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
+                          const Operand &B, void *out, int epi, const void *res, float *psum,
+                          float *psq, void *sc_store, hipStream_t st);
+
+// Weight gradient of a 1x1 conv: dW[a,b] = sum_{n,q} op(U)[n,a,q] * op(V)[n,b,q].
+// `partial` needs wgrad_splits(...)*Ma*Mb floats.
+int wgrad_splits(int Ma, int Mb, int N, int HW);
+hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
+                           const Operand &V, float *partial, float *dW, hipStream_t st);
+
+// ---- batch-norm statistics ---------------------------------------------------------------
+// psum/psq: [C][NP] partial sums.  Writes bn = {scale[C], shift[C], mean[C], rstd[C]} and
+// updates running statistics (if non-null) with momentum.
+hipError_t launch_bn_finalize(int C, int NP, double m, const float *psum, const float *psq,
+                              const float *gamma, const float *beta, float eps, float momentum,
+                              float *run_mean, float *run_var, float *bn, hipStream_t st);
+
+// BN backward finalise from partial sums [C][NP] of dy (psb) and dy*xhat (psr):
+//   dbeta = sum psb, dgamma = sum psr, and coef = {c0,c1,c2}[C] such that
+//   dx = c0*dy + c1*raw + c2  equals  gamma*rstd*(dy - dbeta/m - xhat*dgamma/m).
+hipError_t launch_bn_bwd_finalize(int C, int NP, double m, const float *psb, const float *psr,
+                                  const float *gamma, const float *bn, float *dgamma,
+                                  float *dbeta, float *coef, hipStream_t st);
+
+// ---- depthwise chain ---------------------------------------------------------------------
+struct DwShape {
+    int N, C, H, W, Ho, Wo, k, s, p;
+};
+size_t dw_fwd_lds_bytes(const DwShape &s);
+size_t dw_bwd_lds_bytes(const DwShape &s);
+
+// d = depthwise(swish(e*scale1+shift1)) (or depthwise(e) when bn1 == nullptr), plus per-plane
+// partial sums of d and d^2 laid out [C][N].  a1_store (optional) receives swish(bn1(e)).
+hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
+                         const void *w_dw, void *d, float *psum, float *psq, void *a1_store,
+                         hipStream_t st);
+
+// Per plane of d: z = mean swish(y2), s3 = sum swish'(y2), s4 = sum swish'(y2)*dhat.
+hipError_t launch_pool(bool bf16, int N, int C, int HW, const void *d, const float *bn2, float *z,
+                       float *s3, float *s4, hipStream_t st);
+
+// SE excite: q = W1 z + b1, g = sigmoid(W2 swish(q) + b2).
+hipError_t launch_se_fwd(int N, int C, int Cse, const float *z, const float *w1, const float *b1,
+                         const float *w2, const float *b2, float *q, float *g, hipStream_t st);
+
+// out = p*scale3+shift3 (+ x).
+hipError_t launch_bn_apply(bool bf16, int N, int C, int HW, const void *p, const float *bn3,
+                           const void *res, void *out, hipStream_t st);
+
+// Per plane: sums of dy and dy*xhat with xhat = (raw-mean)*rstd, laid out [C][N].
+hipError_t launch_plane_dot(bool bf16, int N, int C, int HW, const void *dy, const void *raw,
+                            const float *bn, float *psb, float *psr, hipStream_t st);
+
+// Per plane of (G, d): dg = sum G*a2, A1 = sum G*swish'(y2), A2 = sum G*swish'(y2)*dhat.
+hipError_t launch_gate_sums(bool bf16, int N, int C, int HW, const void *G, const void *d,
+                            const float *bn2, float *dg, float *A1, float *A2, hipStream_t st);
+
+// SE backward.  Step 1 (one workgroup per image): dt, dq, dzs = dz/HW.
+// Step 2: the four FC gradients, and BN2's dgamma/dbeta/coef from the plane sums.
+struct SeBwdArgs {
+    int N, C, Cse, HW;
+    const float *z, *g, *q, *w1, *w2;
+    const float *dg, *A1, *A2, *s3, *s4;
+    const float *gamma2, *bn2;
+    float *dt, *dq, *dzs;
+    float *dw1, *db1, *dw2, *db2, *dgamma2, *dbeta2, *coef2;
+};
+hipError_t launch_se_bwd(const SeBwdArgs &a, hipStream_t st);
+
+// The fused depthwise backward (per plane):
+//   dy2 = (G*g + dzs)*swish'(y2);  dd = c0*dy2 + c1*d + c2  (BN2 backward)
+//   dw partial[c][n][k*k] = sum dd * a1(shifted);  da1 = depthwise-transpose(dd)
+//   with expansion: dy1 = da1*swish'(y1) -> dy1_out, partial sums of dy1 and dy1*e -> [C][N]
+//   without:        dx = da1 (+ dout)            -> dx_out
+struct DwBwdArgs {
+    DwShape s;
+    const void *G, *d, *e; // e is x when there is no expansion
+    const float *g, *dzs, *bn2, *coef2, *bn1; // bn1 == nullptr: no expansion
+    const void *w_dw;
+    const void *a1_saved; // optional (STORE policy): swish(bn1(e)) saved by forward
+    void *dy1_out;        // or dx when there is no expansion
+    const void *res;      // residual dout (no-expansion case only)
+    float *pdw, *psb, *psr;
+};
+hipError_t launch_dw_bwd(bool bf16, const DwBwdArgs &a, hipStream_t st);
+
+// out[i] = sum_{s<S} in[s*count+i]  /  out[c*inner+i] = sum_{n<N} in[(c*N+n)*inner+i]
+hipError_t launch_reduce_splits(const float *in, int S, size_t count, float *out, hipStream_t st);
+hipError_t launch_reduce_planes(const float *in, int C, int N, int inner, float *out,
+                                hipStream_t st);
+
+} // namespace mbk

@@ -1,0 +1,104 @@
+"""Helpers shared by the GPU parity tests: run one block through the HIP path and the
+oracle on the same seeded inputs and compare tensor by tensor."""
+from __future__ import annotations
+
+import numpy as np
+
+# Tolerances (max relative error per tensor):
+#   fp32: 1e-4 forward, 1e-3 gradients, element by element relative to max(|ref_i|, rms(ref)).
+#   bf16 storage: 2e-2, relative to the tensor's largest magnitude (max|err| / max|ref|).
+#     An fp64 model that does nothing but round e, d, p, G, dy1 to bf16 already deviates
+#     from the unrounded oracle by 2-5e-2 under the element-wise metric (BN1's gamma gradient
+#     is a heavily cancelling sum), so that metric cannot be met by any bf16-storage
+#     implementation; the element-wise metric is applied instead against the oracle steps
+#     with the same storage rounding inserted (see test_bf16_matches_rounding_model).
+TOL = {"f32": {"fwd": 1e-4, "grad": 1e-3}, "bf16": {"fwd": 2e-2, "grad": 2e-2}}
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref)).
+
+    Element-wise relative error with the tensor's own RMS as floor: BN backward and the
+    residual sum cross zero, where a plain element-wise ratio is meaningless."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    assert np.all(np.isfinite(got)), "non-finite value from the HIP path"
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    floor = max(rms, 1e-30)
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), floor)))
+
+
+def linf_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max_i |got_i - ref_i| / max_i |ref_i|."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    assert np.all(np.isfinite(got)), "non-finite value from the HIP path"
+    return float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+
+
+def metric_for(shape):
+    return linf_err if shape.dtype == "bf16" else rel_err
+
+
+def run_gpu_block(shape, t, policy=0, device="cuda:0"):
+    """Forward + backward on the GPU; returns dict of numpy results and the DeviceBlock."""
+    import torch
+    from paper_2110_10802_amd.harness import DeviceBlock, to_numpy
+
+    blk = DeviceBlock(shape, t, policy=policy, device=device)
+    x = blk.to_device(t["x"])
+    dout = blk.to_device(t["dout"])
+    blk.forward(x)
+    blk.backward(x, dout)
+    torch.cuda.synchronize()
+    res = {"out": to_numpy(blk.out), "dx": to_numpy(blk.dx)}
+    res["grads"] = {n: to_numpy(g) for n, g in blk.grads.items()}
+    res["running"] = {n: to_numpy(r) for n, r in blk.running.items()}
+    return res, blk
+
+
+def _dump_report(shape, errs):
+    """Leave the error table where a GPU run's caller can read it (best effort)."""
+    import json
+    import os
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        name = (f"parity_N{shape.N}_{shape.Cin}-{shape.Cexp}-{shape.Cout}_{shape.H}x{shape.W}_"
+                f"k{shape.k}s{shape.stride}_{shape.dtype}.json")
+        try:
+            with open(os.path.join(d, name), "w") as fh:
+                json.dump({k: {"err": v[0], "tol": v[1]} for k, v in errs.items()}, fh, indent=1)
+        except OSError:
+            pass
+
+
+def compare_block(shape, t, res, f, b, blk=None, report=None):
+    """Assert the HIP results match the oracle's (f, b) within TOL; returns the error table."""
+    tol = TOL[shape.dtype]
+    err = metric_for(shape)
+    errs = {}
+    if blk is not None:
+        # intermediates, for localising a failure (same forward tolerance)
+        for name, ref in (("e", f.tape["e"]), ("d", f.tape["d"]), ("p", f.tape["p"]),
+                          ("z", f.tape["z"]), ("g", f.tape["g"]), ("q", f.tape["q"])):
+            got = blk.saved_tensor(name)
+            if got is not None and (name != "e" or shape.has_expand):
+                errs["saved." + name] = (err(got, ref), tol["fwd"])
+    errs["out"] = (err(res["out"], f.out), tol["fwd"])
+    for n, r in res["running"].items():
+        errs["running." + n] = (err(r, f.running[n]), tol["fwd"])
+    errs["dx"] = (err(res["dx"], b.dx), tol["grad"])
+    for n, g in res["grads"].items():
+        errs["grad." + n] = (err(g, b.grads[n]), tol["grad"])
+    if report is not None:
+        report.update({k: v[0] for k, v in errs.items()})
+    _dump_report(shape, errs)
+    bad = {k: v for k, v in errs.items() if not (v[0] <= v[1])}
+    assert not bad, f"HIP path differs from the oracle beyond tolerance: {bad}\nall: {errs}"
+    return errs

@@ -1,0 +1,142 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 CPU oracle."""
+import numpy as np
+import pytest
+
+from mbconv_inputs import BlockShape, CONFIG0, CONFIG1, CONFIG2, CONFIG3, b0_chain, make_block_inputs
+from oracle import oracle as orc
+from parity_util import compare_block, rel_err, run_gpu_block, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _shape(**kw):
+    base = dict(N=2, Cin=8, H=9, W=11, Cexp=24, Cse=2, Cout=8, k=3, stride=1, residual=True)
+    base.update(kw)
+    return BlockShape(**base)
+
+
+# small blocks: ragged planes, channel counts that are not multiples of the GEMM tiles,
+# every (k, stride), with and without expansion / residual, planes of each thread-group size
+SMALL = {
+    "k3s1_ragged": _shape(),
+    "k5s1": _shape(k=5, H=14, W=14, Cin=16, Cexp=40, Cout=16),
+    "k3s2": _shape(stride=2, residual=False, Cout=12, H=16, W=16),
+    "k5s2_odd": _shape(k=5, stride=2, residual=False, Cout=20, H=15, W=13),
+    "noexpand": _shape(Cin=24, Cexp=24, Cout=16, has_expand=False, residual=False, H=20, W=20),
+    "noexpand_res": _shape(Cin=16, Cexp=16, Cout=16, has_expand=False, residual=True, k=5),
+    "wide": _shape(N=3, Cin=72, Cexp=200, Cse=18, Cout=72, H=7, W=7, k=5),
+    "plane_1024_threads": _shape(N=1, Cin=8, Cexp=16, Cout=8, H=70, W=66),
+    "plane_256_threads": _shape(N=2, Cin=8, Cexp=16, Cout=8, H=28, W=28, k=5),
+    "n1_tiny": _shape(N=1, Cin=1, Cexp=1, Cse=1, Cout=1, H=3, W=3, has_expand=False),
+    "bf16_small": _shape(dtype="bf16", H=14, W=14, k=5, Cin=16, Cexp=64, Cout=16, N=4),
+    "bf16_s2": _shape(dtype="bf16", H=16, W=16, k=3, stride=2, Cin=16, Cexp=32, Cout=24, N=4,
+                      residual=False),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_small_block_matches_oracle(name):
+    s = SMALL[name]
+    t = make_block_inputs(s, seed=7)
+    print(f"[parity] {name} {s}", flush=True)
+    res, blk = run_gpu_block(s, t)
+    f, b = orc.mbconv_step(s, t)
+    compare_block(s, t, res, f, b, blk)
+
+
+@pytest.mark.parametrize("name", ["k3s1_ragged", "k5s2_odd", "bf16_small"])
+def test_store_policy_matches_oracle(name):
+    s = SMALL[name]
+    t = make_block_inputs(s, seed=11)
+    print(f"[parity/store] {name}", flush=True)
+    res, blk = run_gpu_block(s, t, policy=1)
+    f, b = orc.mbconv_step(s, t)
+    compare_block(s, t, res, f, b, blk)
+    tol = TOL[s.dtype]["fwd"]
+    assert rel_err(blk.saved_tensor("a1"), f.tape["a1"]) <= tol
+    assert rel_err(blk.saved_tensor("sc"), f.tape["sc"]) <= tol
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_benchmark_config_matches_oracle(cfg):
+    s = [CONFIG0, CONFIG1, CONFIG2, CONFIG3][cfg]
+    t = make_block_inputs(s, seed=0)
+    print(f"[parity] config {cfg} {s}", flush=True)
+    res, blk = run_gpu_block(s, t)
+    print("[parity] gpu done, running oracle", flush=True)
+    f, b = orc.mbconv_step(s, t)
+    errs = compare_block(s, t, res, f, b, blk)
+    print({k: f"{v[0]:.2e}" for k, v in errs.items()}, flush=True)
+
+
+def test_backward_is_bitwise_repeatable():
+    s = SMALL["k5s1"]
+    t = make_block_inputs(s, seed=3)
+    r1, _ = run_gpu_block(s, t)
+    r2, _ = run_gpu_block(s, t)
+    assert np.array_equal(r1["out"], r2["out"]) and np.array_equal(r1["dx"], r2["dx"])
+    for n in r1["grads"]:
+        assert np.array_equal(r1["grads"][n], r2["grads"][n]), n
+
+
+def _rounding_model(s, t):
+    """The oracle's steps with bf16 rounding inserted at exactly the places where the HIP
+    path stores an activation-sized tensor (e, d, p, out, G, dy1, dx); everything else fp64."""
+    from mbconv_inputs import round_to_bf16
+
+    def rb(a):
+        return round_to_bf16(a.astype(np.float32)).astype(np.float64)
+
+    def swish(v):
+        return v / (1.0 + np.exp(-v))
+
+    def swish_grad(v):
+        sg = 1.0 / (1.0 + np.exp(-v))
+        return sg * (1.0 + v * (1.0 - sg))
+
+    x, dout = t["x"].astype(np.float64), t["dout"].astype(np.float64)
+    e = rb(orc.conv1x1(t["w_expand"], x))
+    y1, xh1, _, v1, _, _ = orc.bn_fwd(e, t["bn1_gamma"], t["bn1_beta"], s.eps, s.momentum)
+    a1 = swish(y1)
+    d = rb(orc.depthwise_fwd(t["w_dw"], a1, s.stride, s.pad))
+    y2, xh2, _, v2, _, _ = orc.bn_fwd(d, t["bn2_gamma"], t["bn2_beta"], s.eps, s.momentum)
+    a2 = swish(y2)
+    se = orc.se_fwd(a2, t["se_w1"], t["se_b1"], t["se_w2"], t["se_b2"])
+    p = rb(orc.conv1x1(t["w_proj"], se.sc))
+    y3, xh3, _, v3, _, _ = orc.bn_fwd(p, t["bn3_gamma"], t["bn3_beta"], s.eps, s.momentum)
+    out = rb(y3 + (x if s.residual else 0.0))
+    dp, dg3, db3 = orc.bn_bwd(dout, xh3, t["bn3_gamma"], v3, s.eps)
+    G = rb(orc.conv1x1_bwd_input(t["w_proj"], dp))
+    g = {"w_proj": orc.conv1x1_bwd_weight(se.sc, dp), "bn3_gamma": dg3, "bn3_beta": db3}
+    sb = orc.se_bwd(a2, t["se_w1"], t["se_w2"], se, G)
+    g.update(se_w1=sb.dw1, se_b1=sb.db1, se_w2=sb.dw2, se_b2=sb.db2)
+    dd, g["bn2_gamma"], g["bn2_beta"] = orc.bn_bwd(sb.da2 * swish_grad(y2), xh2, t["bn2_gamma"], v2,
+                                                   s.eps)
+    g["w_dw"] = orc.depthwise_bwd_weight(a1, dd, s.k, s.stride, s.pad)
+    da1 = orc.depthwise_bwd_input(t["w_dw"], dd, s.H, s.W, s.stride, s.pad)
+    dy1 = rb(da1 * swish_grad(y1))
+    de, g["bn1_gamma"], g["bn1_beta"] = orc.bn_bwd(dy1, xh1, t["bn1_gamma"], v1, s.eps)
+    g["w_expand"] = orc.conv1x1_bwd_weight(x, de)
+    dx = rb(orc.conv1x1_bwd_input(t["w_expand"], de) + (dout if s.residual else 0.0))
+    return {"out": out, "e": e, "d": d, "p": p, "dx": dx, "grads": g}
+
+
+@pytest.mark.parametrize("name", ["bf16_small", "config3_n16"])
+def test_bf16_matches_rounding_model(name):
+    """bf16 storage: element-wise agreement with the oracle steps once the same storage
+    rounding is applied.  A value within fp32 noise of a bf16 rounding boundary may round the
+    other way (one bf16 ulp = 2^-7 of the value) and a flipped input can flip the tensor stored
+    after it, so the bound is two bf16 ulps, 2^-6, under the element-wise metric that the
+    unrounded oracle cannot be held to."""
+    s = SMALL["bf16_small"] if name == "bf16_small" else CONFIG3.with_batch(16)
+    t = make_block_inputs(s, seed=5)
+    print(f"[parity/bf16-model] {name}", flush=True)
+    res, blk = run_gpu_block(s, t)
+    m = _rounding_model(s, t)
+    errs = {"out": rel_err(res["out"], m["out"]), "dx": rel_err(res["dx"], m["dx"])}
+    for n in ("e", "d", "p"):
+        errs[n] = rel_err(blk.saved_tensor(n), m[n])
+    gerrs = {n: rel_err(res["grads"][n], m["grads"][n]) for n in res["grads"]}
+    print(errs, gerrs, flush=True)
+    assert max(errs.values()) <= 2.0 ** -6, errs
+    assert max(gerrs.values()) <= 2.0 ** -6, gerrs
