@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the MBConv training step (forward + backward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--policy recompute|store]
+
+A step is one forward plus one backward of the block through the C ABI, on seeded synthetic
+inputs that are already resident in HBM.  The default workload is benchmark config 1
+(EfficientNet-B0 stage-2 repeat block, fp32, batch 32).  Prints ONE JSON line:
+  value      images/s over the whole job
+  roofline   the slowest kernel of the step, timed live with HIP events recorded on the launch
+             stream inside the timed region, against the HBM roofline (algorithmic bytes)
+  cpu_baseline  the fp64 CPU oracle timed on this host (a reported baseline, not a target)
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+# HBM bytes measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
+# counters' reading on a plain copy kernel of known size; per launch, keyed by
+# (workload, step).  Filled from the summaries under profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(s, step: str):
+    """Bytes the step must move by the fusion plan (each tensor it consumes or produces
+    crosses HBM once); None for the O(N*C) steps."""
+    b = 2 if s.dtype == "bf16" else 4
+    X = s.N * s.Cin * s.H * s.W
+    E = s.N * s.Cexp * s.H * s.W
+    D = s.N * s.Cexp * s.Ho * s.Wo
+    P = s.N * s.Cout * s.Ho * s.Wo
+    res = P if s.residual else 0
+    table = {
+        "expand_conv": X + E, "dw_fwd": E + D, "se_pool": D, "proj_conv": D + P,
+        "bn3_apply": 2 * P + res, "bn3_bwd_reduce": 2 * P, "proj_dgrad": 2 * P + D,
+        "proj_wgrad": 2 * P + D, "gate_sums": 2 * D,
+        "dw_bwd": (2 * D + 2 * E) if s.has_expand else (2 * D + 2 * X + res),
+        "expand_dgrad": 2 * E + X + res, "expand_wgrad": 2 * E + X,
+    }
+    return table[step] * b if step in table else None
+
+
+class HipEvents:
+    """HIP events through the runtime's C API (torch.cuda.Event only sees torch's stream)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self) -> C.c_void_p:
+        ev = C.c_void_p()
+        rc = self.hip.hipEventCreate(C.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed ({rc})")
+        return ev
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
+def cpu_baseline(shape, tensors):
+    """The oracle, as it stands, on this host: one forward+backward of the same workload."""
+    from oracle import oracle as orc
+    t0 = time.perf_counter()
+    orc.mbconv_step(shape, tensors)
+    dt = time.perf_counter() - t0
+    return {"value": shape.N / dt, "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"one fp64 forward+backward of the full workload batch ({shape.N} images), "
+                      f"{dt:.1f} s wall"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3])
+    ap.add_argument("--policy", default="recompute", choices=["recompute", "store"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe-step", default=None,
+                    help="time this step for the roofline instead of the slowest one")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (for scaling rocprofv3 "
+                         "FETCH_SIZE/WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from mbconv_inputs import CONFIGS, make_block_inputs
+    from paper_2110_10802_amd import binding as B
+    from paper_2110_10802_amd.harness import DeviceBlock
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    B.load()  # fails loudly if the HIP library has not been built
+    shape = CONFIGS[args.config]
+    tensors = make_block_inputs(shape, seed=0)
+    policy = B.MBCONV_STORE if args.policy == "store" else B.MBCONV_RECOMPUTE
+    blk = DeviceBlock(shape, tensors, policy=policy)
+    x = blk.to_device(tensors["x"])
+    dout = blk.to_device(tensors["dout"])
+    stream = torch.cuda.current_stream().cuda_stream
+    params = B._fill(B.Params(), blk.params)
+    running = B._fill(B.BNState(), blk.running)
+    grads = B._fill(B.Grads(), blk.grads)
+    desc = blk.desc
+
+    def step(probe=None):
+        fprobe = probe if probe is not None and probe.step <= 9 else None
+        bprobe = probe if probe is not None and probe.step > 9 else None
+        B.mbconv_forward_probed(desc, params, running, x, blk.out, blk.saved, blk.scratch, stream,
+                                fprobe)
+        B.mbconv_backward_probed(desc, params, x, dout, blk.saved, blk.scratch, blk.dx, grads,
+                                 stream, bprobe)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+
+    ev = HipEvents()
+    # untimed survey: duration of every step, to find the slowest kernel
+    survey = {}
+    e0, e1 = ev.create(), ev.create()
+    for name, sid in B.STEPS.items():
+        if not shape.has_expand and name in ("expand_conv", "bn1_finalize", "bn1_bwd_finalize",
+                                             "expand_dgrad", "expand_wgrad"):
+            continue
+        reps = []
+        for _ in range(3):
+            step(B.Probe(sid, e0, e1))
+            torch.cuda.synchronize()
+            reps.append(ev.elapsed_ms(e0, e1))
+        survey[name] = sorted(reps)[1]
+    ev.destroy(e0)
+    ev.destroy(e1)
+    dominant = args.probe_step or max(
+        (n for n in survey if algorithmic_bytes(shape, n) is not None), key=lambda n: survey[n])
+    print("per-step ms (untimed survey): " +
+          ", ".join(f"{n}={v * 1e3:.1f}us" for n, v in survey.items()), file=sys.stderr)
+
+    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    sid = B.STEPS[dominant]
+    probes = [B.Probe(sid, a, b) for a, b in pairs]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(probes[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = sum(ev.elapsed_ms(a, b) for a, b in pairs) / args.steps
+    for a, b in pairs:
+        ev.destroy(a)
+        ev.destroy(b)
+
+    if args.pmc_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    nbytes = algorithmic_bytes(shape, dominant)
+    achieved = nbytes / (kern_ms * 1e-3) / 1e9
+    workload = f"config{args.config}"
+    result = {
+        "metric": "mbconv_fwd_bwd_images_per_sec",
+        "value": shape.N / (ms_per_step * 1e-3),
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": workload, "block": f"N{shape.N} {shape.Cin}->{shape.Cexp}->{shape.Cout} "
+                   f"{shape.H}x{shape.W} k{shape.k}s{shape.stride} se{shape.Cse} "
+                   f"res{int(shape.residual)}", "policy": args.policy},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((workload, dominant)),
+                     "kernel_ms": kern_ms, "algorithmic_bytes": nbytes},
+        "step_ms_survey": {n: round(v, 5) for n, v in survey.items()},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(shape, tensors)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -146,6 +146,55 @@ mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *para
                               const void *dout, const void *saved_ws, void *scratch_ws, void *dx,
                               mbconv_grads *grads, void *hip_stream);
 
+/* Optional timing probe.  The steps of the two calls, in launch order; a probe brackets
+ * exactly one of them with two caller-created HIP events recorded on the call's stream
+ * (hipEventRecord(start) before the step's first launch, hipEventRecord(stop) after its last),
+ * so a caller can time one kernel inside the timed region without synchronising.
+ * The library neither creates, waits on nor destroys the events. */
+typedef enum {
+    MBCONV_STEP_NONE = 0,
+    /* forward */
+    MBCONV_STEP_EXPAND_CONV = 1,   /* 1x1 expansion conv + BN1 partial statistics */
+    MBCONV_STEP_BN1_FINALIZE = 2,
+    MBCONV_STEP_DW_FWD = 3,        /* BN1 + Swish + depthwise conv + BN2 partial statistics */
+    MBCONV_STEP_BN2_FINALIZE = 4,
+    MBCONV_STEP_SE_POOL = 5,       /* BN2 + Swish + plane means */
+    MBCONV_STEP_SE_FC = 6,
+    MBCONV_STEP_PROJ_CONV = 7,     /* (BN2 + Swish)*gate + 1x1 projection conv + BN3 partials */
+    MBCONV_STEP_BN3_FINALIZE = 8,
+    MBCONV_STEP_BN3_APPLY = 9,     /* BN3 (+ residual) */
+    /* backward */
+    MBCONV_STEP_BN3_BWD_REDUCE = 10,
+    MBCONV_STEP_BN3_BWD_FINALIZE = 11,
+    MBCONV_STEP_PROJ_DGRAD = 12,
+    MBCONV_STEP_PROJ_WGRAD = 13,
+    MBCONV_STEP_GATE_SUMS = 14,
+    MBCONV_STEP_SE_BWD = 15,
+    MBCONV_STEP_DW_BWD = 16,       /* BN2 backward + depthwise dgrad/wgrad + Swish' + BN1 partials */
+    MBCONV_STEP_DW_WGRAD_REDUCE = 17,
+    MBCONV_STEP_BN1_BWD_FINALIZE = 18,
+    MBCONV_STEP_EXPAND_DGRAD = 19,
+    MBCONV_STEP_EXPAND_WGRAD = 20,
+    MBCONV_STEP_COUNT = 21
+} mbconv_step;
+
+typedef struct {
+    int32_t step;      /* mbconv_step to bracket */
+    void *start_event; /* hipEvent_t */
+    void *stop_event;  /* hipEvent_t */
+} mbconv_probe;
+
+/* Same as mbconv_forward / mbconv_backward, plus the probe (NULL = none).  A probe whose step
+ * does not occur in the call (e.g. an expansion step when has_expand == 0) records nothing. */
+mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params *params,
+                                    mbconv_bn_state *running, const void *x, void *out,
+                                    void *saved_ws, void *scratch_ws, void *hip_stream,
+                                    const mbconv_probe *probe);
+mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_params *params,
+                                     const void *x, const void *dout, const void *saved_ws,
+                                     void *scratch_ws, void *dx, mbconv_grads *grads,
+                                     void *hip_stream, const mbconv_probe *probe);
+
 /* Static string for a status code. */
 const char *mbconv_status_string(mbconv_status status);
 

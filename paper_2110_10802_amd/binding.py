@@ -24,7 +24,15 @@ PARAM_NAMES = ["w_expand", "bn1_gamma", "bn1_beta", "w_dw", "bn2_gamma", "bn2_be
 RUNNING_NAMES = ["bn1_mean", "bn1_var", "bn2_mean", "bn2_var", "bn3_mean", "bn3_var"]
 SAVED_NAMES = ["e", "d", "p", "bn1", "bn2", "bn3", "z", "g", "q", "a1", "sc"]
 EXPORTS = ["mbconv_workspace_size", "mbconv_saved_offsets", "mbconv_forward", "mbconv_backward",
-           "mbconv_status_string", "mbconv_abi_version"]
+           "mbconv_forward_probed", "mbconv_backward_probed", "mbconv_status_string",
+           "mbconv_abi_version"]
+# mbconv_step values (launch order of the two calls)
+STEPS = {"expand_conv": 1, "bn1_finalize": 2, "dw_fwd": 3, "bn2_finalize": 4, "se_pool": 5,
+         "se_fc": 6, "proj_conv": 7, "bn3_finalize": 8, "bn3_apply": 9, "bn3_bwd_reduce": 10,
+         "bn3_bwd_finalize": 11, "proj_dgrad": 12, "proj_wgrad": 13, "gate_sums": 14, "se_bwd": 15,
+         "dw_bwd": 16, "dw_wgrad_reduce": 17, "bn1_bwd_finalize": 18, "expand_dgrad": 19,
+         "expand_wgrad": 20}
+FORWARD_STEPS = [n for n, v in STEPS.items() if v <= 9]
 
 
 class MBConvError(RuntimeError):
@@ -49,6 +57,10 @@ class Grads(C.Structure):
 
 class BNState(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in RUNNING_NAMES]
+
+
+class Probe(C.Structure):
+    _fields_ = [("step", C.c_int32), ("start_event", C.c_void_p), ("stop_event", C.c_void_p)]
 
 
 class SavedLayout(C.Structure):
@@ -82,6 +94,10 @@ def load() -> C.CDLL:
         lib.mbconv_backward.restype = C.c_int
         lib.mbconv_backward.argtypes = [C.POINTER(Desc), C.POINTER(Params), vp, vp, vp, vp, vp,
                                         C.POINTER(Grads), vp]
+        lib.mbconv_forward_probed.restype = C.c_int
+        lib.mbconv_forward_probed.argtypes = lib.mbconv_forward.argtypes + [C.POINTER(Probe)]
+        lib.mbconv_backward_probed.restype = C.c_int
+        lib.mbconv_backward_probed.argtypes = lib.mbconv_backward.argtypes + [C.POINTER(Probe)]
         if lib.mbconv_abi_version() != ABI_VERSION:
             raise RuntimeError("libmbconv.so ABI version mismatch; rebuild")
         _lib = lib
@@ -133,19 +149,44 @@ def mbconv_saved_offsets(desc: Desc) -> Dict[str, Optional[int]]:
 
 def mbconv_forward(desc: Desc, params: Dict[str, Any], running: Optional[Dict[str, Any]], x: Any,
                    out: Any, saved_ws: Any, scratch_ws: Any, stream: int = 0) -> None:
-    ps = _fill(Params(), params)
-    rs = _fill(BNState(), running) if running is not None else None
-    rc = load().mbconv_forward(C.byref(desc), C.byref(ps), C.byref(rs) if rs is not None else None,
-                               _ptr(x), _ptr(out), _ptr(saved_ws), _ptr(scratch_ws), stream or None)
-    if rc != 0:
-        raise MBConvError(rc, "mbconv_forward")
+    mbconv_forward_probed(desc, params, running, x, out, saved_ws, scratch_ws, stream, None)
 
 
 def mbconv_backward(desc: Desc, params: Dict[str, Any], x: Any, dout: Any, saved_ws: Any,
                     scratch_ws: Any, dx: Any, grads: Dict[str, Any], stream: int = 0) -> None:
-    ps = _fill(Params(), params)
-    gs = _fill(Grads(), grads)
-    rc = load().mbconv_backward(C.byref(desc), C.byref(ps), _ptr(x), _ptr(dout), _ptr(saved_ws),
-                                _ptr(scratch_ws), _ptr(dx), C.byref(gs), stream or None)
+    mbconv_backward_probed(desc, params, x, dout, saved_ws, scratch_ws, dx, grads, stream, None)
+
+
+def mbconv_forward_probed(desc: Desc, params: Any, running: Any, x: Any, out: Any, saved_ws: Any,
+                          scratch_ws: Any, stream: int = 0, probe: Optional[Probe] = None) -> None:
+    """``params`` / ``running`` may be dicts of tensors or already filled structs."""
+    ps = params if isinstance(params, Params) else _fill(Params(), params)
+    rs = running if isinstance(running, BNState) or running is None else _fill(BNState(), running)
+    lib = load()
+    if probe is None:
+        rc = lib.mbconv_forward(C.byref(desc), C.byref(ps), C.byref(rs) if rs is not None else None,
+                                _ptr(x), _ptr(out), _ptr(saved_ws), _ptr(scratch_ws), stream or None)
+    else:
+        rc = lib.mbconv_forward_probed(C.byref(desc), C.byref(ps),
+                                       C.byref(rs) if rs is not None else None, _ptr(x), _ptr(out),
+                                       _ptr(saved_ws), _ptr(scratch_ws), stream or None,
+                                       C.byref(probe))
+    if rc != 0:
+        raise MBConvError(rc, "mbconv_forward")
+
+
+def mbconv_backward_probed(desc: Desc, params: Any, x: Any, dout: Any, saved_ws: Any,
+                           scratch_ws: Any, dx: Any, grads: Any, stream: int = 0,
+                           probe: Optional[Probe] = None) -> None:
+    ps = params if isinstance(params, Params) else _fill(Params(), params)
+    gs = grads if isinstance(grads, Grads) else _fill(Grads(), grads)
+    lib = load()
+    if probe is None:
+        rc = lib.mbconv_backward(C.byref(desc), C.byref(ps), _ptr(x), _ptr(dout), _ptr(saved_ws),
+                                 _ptr(scratch_ws), _ptr(dx), C.byref(gs), stream or None)
+    else:
+        rc = lib.mbconv_backward_probed(C.byref(desc), C.byref(ps), _ptr(x), _ptr(dout),
+                                        _ptr(saved_ws), _ptr(scratch_ws), _ptr(dx), C.byref(gs),
+                                        stream or None, C.byref(probe))
     if rc != 0:
         raise MBConvError(rc, "mbconv_backward")

@@ -159,6 +159,18 @@ const T *at(const void *base, size_t off)
             return MBCONV_EHIP;                                                                   \
     } while (0)
 
+// Runs one step of the launch sequence, bracketed by the probe's events when it names it.
+#define MBK_STEP(id, expr)                                                                        \
+    do {                                                                                          \
+        const bool probed_ = probe && probe->step == (id) && probe->start_event &&                \
+                             probe->stop_event;                                                   \
+        if (probed_)                                                                              \
+            MBK_TRY(hipEventRecord((hipEvent_t)probe->start_event, st));                          \
+        MBK_TRY(expr);                                                                            \
+        if (probed_)                                                                              \
+            MBK_TRY(hipEventRecord((hipEvent_t)probe->stop_event, st));                           \
+    } while (0)
+
 mbconv_status check_params(const mbconv_desc *d, const mbconv_params *p)
 {
     if (!p)
@@ -244,6 +256,13 @@ mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *prm,
                              mbconv_bn_state *run, const void *x, void *out, void *saved,
                              void *scratch, void *hip_stream)
 {
+    return mbconv_forward_probed(desc, prm, run, x, out, saved, scratch, hip_stream, nullptr);
+}
+
+mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params *prm,
+                                    mbconv_bn_state *run, const void *x, void *out, void *saved,
+                                    void *scratch, void *hip_stream, const mbconv_probe *probe)
+{
     mbconv_status s = check_desc(desc);
     if (s != MBCONV_OK)
         return s;
@@ -277,9 +296,9 @@ mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *prm,
         Operand B;
         B.p0 = x;
         B.pro = PRO_NONE;
-        MBK_TRY(launch_conv1x1(bf, P.N, P.Cexp, P.Cin, P.HW, prm->w_expand, P.Cin, 1, B, e,
+        MBK_STEP(MBCONV_STEP_EXPAND_CONV, launch_conv1x1(bf, P.N, P.Cexp, P.Cin, P.HW, prm->w_expand, P.Cin, 1, B, e,
                                EPI_STATS, nullptr, psum, psq, nullptr, st));
-        MBK_TRY(launch_bn_finalize(P.Cexp, P.NT1, (double)P.N * P.HW, psum, psq, prm->bn1_gamma,
+        MBK_STEP(MBCONV_STEP_BN1_FINALIZE, launch_bn_finalize(P.Cexp, P.NT1, (double)P.N * P.HW, psum, psq, prm->bn1_gamma,
                                    prm->bn1_beta, eps, mom, run ? run->bn1_mean : nullptr,
                                    run ? run->bn1_var : nullptr, bn1, st));
         dw_in = e;
@@ -287,15 +306,15 @@ mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *prm,
     // BN1 + Swish + depthwise + BN2 statistics
     const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
     void *a1_store = (P.store && P.expand) ? at<char>(saved, P.o_a1) : nullptr;
-    MBK_TRY(launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum, psq, a1_store, st));
-    MBK_TRY(launch_bn_finalize(P.Cexp, P.N, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
+    MBK_STEP(MBCONV_STEP_DW_FWD, launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum, psq, a1_store, st));
+    MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.N, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
                                prm->bn2_beta, eps, mom, run ? run->bn2_mean : nullptr,
                                run ? run->bn2_var : nullptr, bn2, st));
     // BN2 + Swish + SE squeeze, SE excite
     float *z = at<float>(saved, P.o_z), *g = at<float>(saved, P.o_g), *q = at<float>(saved, P.o_q);
-    MBK_TRY(launch_pool(bf, P.N, P.Cexp, P.HWo, d, bn2, z, at<float>(saved, P.o_s3),
+    MBK_STEP(MBCONV_STEP_SE_POOL, launch_pool(bf, P.N, P.Cexp, P.HWo, d, bn2, z, at<float>(saved, P.o_s3),
                         at<float>(saved, P.o_s4), st));
-    MBK_TRY(launch_se_fwd(P.N, P.Cexp, P.Cse, z, prm->se_w1, prm->se_b1, prm->se_w2, prm->se_b2, q,
+    MBK_STEP(MBCONV_STEP_SE_FC, launch_se_fwd(P.N, P.Cexp, P.Cse, z, prm->se_w1, prm->se_b1, prm->se_w2, prm->se_b2, q,
                           g, st));
     // projection conv on Swish(BN2(d))*g + BN3 statistics
     {
@@ -306,20 +325,28 @@ mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *prm,
         B.gate = g;
         B.pro = PRO_BNSWISH_GATE;
         void *sc_store = P.store ? at<char>(saved, P.o_sc) : nullptr;
-        MBK_TRY(launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p,
+        MBK_STEP(MBCONV_STEP_PROJ_CONV, launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p,
                                EPI_STATS, nullptr, psum, psq, sc_store, st));
-        MBK_TRY(launch_bn_finalize(P.Cout, P.NT5, (double)P.N * P.HWo, psum, psq, prm->bn3_gamma,
+        MBK_STEP(MBCONV_STEP_BN3_FINALIZE, launch_bn_finalize(P.Cout, P.NT5, (double)P.N * P.HWo, psum, psq, prm->bn3_gamma,
                                    prm->bn3_beta, eps, mom, run ? run->bn3_mean : nullptr,
                                    run ? run->bn3_var : nullptr, bn3, st));
     }
     // BN3 (+ residual)
-    MBK_TRY(launch_bn_apply(bf, P.N, P.Cout, P.HWo, p, bn3, P.res ? x : nullptr, out, st));
+    MBK_STEP(MBCONV_STEP_BN3_APPLY, launch_bn_apply(bf, P.N, P.Cout, P.HWo, p, bn3, P.res ? x : nullptr, out, st));
     return MBCONV_OK;
 }
 
 mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm, const void *x,
                               const void *dout, const void *saved, void *scratch, void *dx,
                               mbconv_grads *gr, void *hip_stream)
+{
+    return mbconv_backward_probed(desc, prm, x, dout, saved, scratch, dx, gr, hip_stream, nullptr);
+}
+
+mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_params *prm,
+                                     const void *x, const void *dout, const void *saved,
+                                     void *scratch, void *dx, mbconv_grads *gr, void *hip_stream,
+                                     const mbconv_probe *probe)
 {
     mbconv_status s = check_desc(desc);
     if (s != MBCONV_OK)
@@ -357,8 +384,8 @@ mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm,
     const double m2 = (double)P.N * P.HWo;
 
     // BN3 backward reductions
-    MBK_TRY(launch_plane_dot(bf, P.N, P.Cout, P.HWo, dout, p, bn3, pa, pb, st));
-    MBK_TRY(launch_bn_bwd_finalize(P.Cout, P.N, m2, pa, pb, prm->bn3_gamma, bn3, gr->bn3_gamma,
+    MBK_STEP(MBCONV_STEP_BN3_BWD_REDUCE, launch_plane_dot(bf, P.N, P.Cout, P.HWo, dout, p, bn3, pa, pb, st));
+    MBK_STEP(MBCONV_STEP_BN3_BWD_FINALIZE, launch_bn_bwd_finalize(P.Cout, P.N, m2, pa, pb, prm->bn3_gamma, bn3, gr->bn3_gamma,
                                    gr->bn3_beta, coef3, st));
     // projection conv: data gradient G = W_p^T dp and weight gradient dW_p = dp * sc^T,
     // dp rebuilt in the prologue from dout and p
@@ -369,7 +396,7 @@ mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm,
     dp.c1 = coef3 + P.Cout;
     dp.c2 = coef3 + 2 * P.Cout;
     dp.pro = PRO_BNBWD;
-    MBK_TRY(launch_conv1x1(bf, P.N, P.Cexp, P.Cout, P.HWo, prm->w_proj, 1, P.Cexp, dp, G, EPI_NONE,
+    MBK_STEP(MBCONV_STEP_PROJ_DGRAD, launch_conv1x1(bf, P.N, P.Cexp, P.Cout, P.HWo, prm->w_proj, 1, P.Cexp, dp, G, EPI_NONE,
                            nullptr, nullptr, nullptr, nullptr, st));
     {
         Operand sc;
@@ -383,12 +410,12 @@ mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm,
             sc.gate = g;
             sc.pro = PRO_BNSWISH_GATE;
         }
-        MBK_TRY(launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, wg, gr->w_proj, st));
+        MBK_STEP(MBCONV_STEP_PROJ_WGRAD, launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, wg, gr->w_proj, st));
     }
     // SE backward and BN2 backward reductions
     float *dg = at<float>(scratch, P.o_dg), *A1 = at<float>(scratch, P.o_A1);
     float *A2 = at<float>(scratch, P.o_A2), *dzs = at<float>(scratch, P.o_dzs);
-    MBK_TRY(launch_gate_sums(bf, P.N, P.Cexp, P.HWo, G, d, bn2, dg, A1, A2, st));
+    MBK_STEP(MBCONV_STEP_GATE_SUMS, launch_gate_sums(bf, P.N, P.Cexp, P.HWo, G, d, bn2, dg, A1, A2, st));
     {
         SeBwdArgs a;
         a.N = P.N;
@@ -417,7 +444,7 @@ mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm,
         a.dgamma2 = gr->bn2_gamma;
         a.dbeta2 = gr->bn2_beta;
         a.coef2 = coef2;
-        MBK_TRY(launch_se_bwd(a, st));
+        MBK_STEP(MBCONV_STEP_SE_BWD, launch_se_bwd(a, st));
     }
     // fused depthwise backward
     {
@@ -438,14 +465,14 @@ mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm,
         a.pdw = at<float>(scratch, P.o_pdw);
         a.psb = pa;
         a.psr = pb;
-        MBK_TRY(launch_dw_bwd(bf, a, st));
-        MBK_TRY(launch_reduce_planes(a.pdw, P.Cexp, P.N, P.k * P.k, gr->w_dw, st));
+        MBK_STEP(MBCONV_STEP_DW_BWD, launch_dw_bwd(bf, a, st));
+        MBK_STEP(MBCONV_STEP_DW_WGRAD_REDUCE, launch_reduce_planes(a.pdw, P.Cexp, P.N, P.k * P.k, gr->w_dw, st));
     }
     if (P.expand) {
         float *coef1 = at<float>(scratch, P.o_coef1);
         const void *e = at<char>(saved, P.o_e);
         const void *dy1 = at<char>(scratch, P.o_dy1);
-        MBK_TRY(launch_bn_bwd_finalize(P.Cexp, P.N, (double)P.N * P.HW, pa, pb, prm->bn1_gamma, bn1,
+        MBK_STEP(MBCONV_STEP_BN1_BWD_FINALIZE, launch_bn_bwd_finalize(P.Cexp, P.N, (double)P.N * P.HW, pa, pb, prm->bn1_gamma, bn1,
                                        gr->bn1_gamma, gr->bn1_beta, coef1, st));
         Operand de;
         de.p0 = dy1;
@@ -455,13 +482,13 @@ mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm,
         de.c2 = coef1 + 2 * P.Cexp;
         de.pro = PRO_BNBWD;
         // dx = W_e^T de (+ dout), dW_e = de * x^T
-        MBK_TRY(launch_conv1x1(bf, P.N, P.Cin, P.Cexp, P.HW, prm->w_expand, 1, P.Cin, de, dx,
+        MBK_STEP(MBCONV_STEP_EXPAND_DGRAD, launch_conv1x1(bf, P.N, P.Cin, P.Cexp, P.HW, prm->w_expand, 1, P.Cin, de, dx,
                                P.res ? EPI_RES : EPI_NONE, P.res ? dout : nullptr, nullptr, nullptr,
                                nullptr, st));
         Operand xo;
         xo.p0 = x;
         xo.pro = PRO_NONE;
-        MBK_TRY(launch_wgrad1x1(bf, P.N, P.Cexp, P.Cin, P.HW, de, xo, wg, gr->w_expand, st));
+        MBK_STEP(MBCONV_STEP_EXPAND_WGRAD, launch_wgrad1x1(bf, P.N, P.Cexp, P.Cin, P.HW, de, xo, wg, gr->w_expand, st));
     }
     return MBCONV_OK;
 }
