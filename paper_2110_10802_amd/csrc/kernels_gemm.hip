@@ -193,10 +193,32 @@ static hipError_t conv1x1_dispatch(const Conv1x1Args &a, int pro, int epi, dim3 
     return hipErrorInvalidValue;
 }
 
+// kernels_wave.hip
+int wave_conv_kind(int M, int K, int HW);
+int wave_conv_num_partials(int kind, int N, int HW);
+hipError_t launch_wave_conv1x1(bool bf16, int kind, int N, int M, int K, int HW, const void *w,
+                               int sAm, int sAk, const Operand &B, void *out, int epi,
+                               const void *res, float *psum, float *psq, hipStream_t st);
+bool wgrad_cl_plan(int Ma, int Mb, int N, int HW, bool *swap, int *splits);
+hipError_t launch_wgrad_cl(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
+                           const Operand &V, float *partial, int *splits_out, hipStream_t st);
+
+int conv1x1_num_partials(int N, int M, int K, int HW, bool stores_operand)
+{
+    const int kind = stores_operand ? 0 : wave_conv_kind(M, K, HW);
+    if (kind)
+        return wave_conv_num_partials(kind, N, HW);
+    return conv1x1_num_qtiles(N, HW);
+}
+
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
                           float *psq, void *sc_store, hipStream_t st)
 {
+    const int kind = sc_store ? 0 : wave_conv_kind(M, K, HW);
+    if (kind)
+        return launch_wave_conv1x1(bf16, kind, N, M, K, HW, w, sAm, sAk, B, out, epi, res, psum,
+                                   psq, st);
     Conv1x1Args a;
     a.N = N;
     a.M = M;
@@ -288,7 +310,7 @@ __global__ __launch_bounds__(256) void wgrad1x1_kernel(WgradArgs a)
 static long long wgrad_chunk(int Ma, int Mb, long long Q)
 {
     const long long tiles = (long long)((Ma + 63) / 64) * ((Mb + 63) / 64);
-    long long want = 1024 / tiles; // workgroups along the contraction
+    long long want = 512 / tiles; // workgroups along the contraction
     if (want < 1)
         want = 1;
     long long chunk = (Q + want - 1) / want;
@@ -300,27 +322,52 @@ static long long wgrad_chunk(int Ma, int Mb, long long Q)
 
 int wgrad_splits(int Ma, int Mb, int N, int HW)
 {
+    bool swap;
+    int splits;
+    if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits))
+        return splits;
     const long long Q = (long long)N * HW;
     const long long chunk = wgrad_chunk(Ma, Mb, Q);
     return (int)((Q + chunk - 1) / chunk);
 }
 
-__global__ void reduce_splits_kernel(const float *__restrict__ in, int S, size_t count,
-                                     float *__restrict__ out)
+// Second stage of a split reduction: out[i] = sum_k in[k*count+i].  A workgroup owns 32
+// outputs; its 32 thread groups each add every 32nd partial in ascending order (four
+// independent running sums per thread to keep loads in flight), then the groups are combined
+// by a fixed-shape tree in LDS.  No atomics, bitwise repeatable.
+__global__ __launch_bounds__(1024) void reduce_splits_kernel(const float *__restrict__ in, int S,
+                                                             size_t count, float *__restrict__ out)
 {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count)
-        return;
-    float s = 0.f;
-    for (int k = 0; k < S; ++k)
-        s += in[(size_t)k * count + i];
-    out[i] = s;
+    __shared__ float part[32][33];
+    const int e = threadIdx.x & 31, grp = threadIdx.x >> 5;
+    const size_t i = (size_t)blockIdx.x * 32 + e;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (i < count) {
+        int k = grp;
+        for (; k + 96 < S; k += 128) {
+            s0 += in[(size_t)k * count + i];
+            s1 += in[(size_t)(k + 32) * count + i];
+            s2 += in[(size_t)(k + 64) * count + i];
+            s3 += in[(size_t)(k + 96) * count + i];
+        }
+        for (; k < S; k += 32)
+            s0 += in[(size_t)k * count + i];
+    }
+    part[grp][e] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    for (int half = 16; half > 0; half >>= 1) {
+        if (grp < half)
+            part[grp][e] += part[grp + half][e];
+        __syncthreads();
+    }
+    if (grp == 0 && i < count)
+        out[i] = part[0][e];
 }
 
 hipError_t launch_reduce_splits(const float *in, int S, size_t count, float *out, hipStream_t st)
 {
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0,
-                       st, in, S, count, out);
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((count + 31) / 32)), dim3(1024), 0, st,
+                       in, S, count, out);
     return hipGetLastError();
 }
 
@@ -341,6 +388,16 @@ static hipError_t wgrad_dispatch(const WgradArgs &a, int pu, int pv, dim3 grid, 
 hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
                            const Operand &V, float *partial, float *dW, hipStream_t st)
 {
+    {
+        bool swap;
+        int splits;
+        if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits)) {
+            hipError_t e = launch_wgrad_cl(bf16, N, Ma, Mb, HW, U, V, partial, &splits, st);
+            if (e != hipSuccess)
+                return e;
+            return launch_reduce_splits(partial, splits, (size_t)Ma * Mb, dW, st);
+        }
+    }
     WgradArgs a;
     a.N = N;
     a.Ma = Ma;

@@ -196,31 +196,46 @@ __global__ __launch_bounds__(256) void se_bwd_image_kernel(SeBwdArgs a)
     }
 }
 
-// Sums over the batch, one thread per output element, images added in index order:
+// Sums over the batch.  Each output element is owned by 32 consecutive lanes: lane l adds
+// the images l, l+32, ... and the 32 partial sums are combined by a fixed butterfly, so the
+// result does not depend on scheduling.  Output elements in order:
 //   [0, C*Cse)            dW2[c,j] = sum_n dt[n,c]*swish(q[n,j])
 //   [C*Cse, 2*C*Cse)      dW1[j,c] = sum_n dq[n,j]*z[n,c]
 //   next C                db2[c], and BN2's dbeta/dgamma/coef from the plane sums:
 //                         dbeta2 = sum_n g*A1 + dzs*s3,  dgamma2 = sum_n g*A2 + dzs*s4
 //   next Cse              db1[j]
+__device__ __forceinline__ double half_wave_sum_d(double v)
+{
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1)
+        v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
 __global__ __launch_bounds__(256) void se_bwd_batch_kernel(SeBwdArgs a)
 {
     const int C = a.C, Cse = a.Cse, N = a.N;
-    int i = blockIdx.x * 256 + threadIdx.x;
+    const int ln = threadIdx.x & 31;
+    int i = blockIdx.x * 8 + (threadIdx.x >> 5);
     if (i < C * Cse) {
         const int c = i / Cse, j = i - c * Cse;
         float acc = 0.f;
-        for (int n = 0; n < N; ++n)
+        for (int n = ln; n < N; n += 32)
             acc = fmaf(a.dt[(size_t)n * C + c], swishf(a.q[(size_t)n * Cse + j]), acc);
-        a.dw2[i] = acc;
+        acc = half_wave_sum(acc);
+        if (ln == 0)
+            a.dw2[i] = acc;
         return;
     }
     i -= C * Cse;
     if (i < C * Cse) {
         const int j = i / C, c = i - j * C;
         float acc = 0.f;
-        for (int n = 0; n < N; ++n)
+        for (int n = ln; n < N; n += 32)
             acc = fmaf(a.dq[(size_t)n * Cse + j], a.z[(size_t)n * C + c], acc);
-        a.dw1[i] = acc;
+        acc = half_wave_sum(acc);
+        if (ln == 0)
+            a.dw1[i] = acc;
         return;
     }
     i -= C * Cse;
@@ -228,24 +243,31 @@ __global__ __launch_bounds__(256) void se_bwd_batch_kernel(SeBwdArgs a)
         const int c = i;
         float sb = 0.f;
         double dbeta = 0.0, dgamma = 0.0;
-        for (int n = 0; n < N; ++n) {
+        for (int n = ln; n < N; n += 32) {
             const size_t o = (size_t)n * C + c;
             sb += a.dt[o];
             dbeta += (double)a.g[o] * a.A1[o] + (double)a.dzs[o] * a.s3[o];
             dgamma += (double)a.g[o] * a.A2[o] + (double)a.dzs[o] * a.s4[o];
         }
-        a.db2[c] = sb;
-        a.dbeta2[c] = (float)dbeta;
-        a.dgamma2[c] = (float)dgamma;
-        bn_bwd_coef(C, c, (double)N * a.HW, dgamma, dbeta, a.gamma2[c], a.bn2, a.coef2);
+        sb = half_wave_sum(sb);
+        dbeta = half_wave_sum_d(dbeta);
+        dgamma = half_wave_sum_d(dgamma);
+        if (ln == 0) {
+            a.db2[c] = sb;
+            a.dbeta2[c] = (float)dbeta;
+            a.dgamma2[c] = (float)dgamma;
+            bn_bwd_coef(C, c, (double)N * a.HW, dgamma, dbeta, a.gamma2[c], a.bn2, a.coef2);
+        }
         return;
     }
     i -= C;
     if (i < Cse) {
         float sb = 0.f;
-        for (int n = 0; n < N; ++n)
+        for (int n = ln; n < N; n += 32)
             sb += a.dq[(size_t)n * Cse + i];
-        a.db1[i] = sb;
+        sb = half_wave_sum(sb);
+        if (ln == 0)
+            a.db1[i] = sb;
     }
 }
 
@@ -257,7 +279,7 @@ hipError_t launch_se_bwd(const SeBwdArgs &a, hipStream_t st)
     if (e != hipSuccess)
         return e;
     const int total = 2 * a.C * a.Cse + a.C + a.Cse;
-    hipLaunchKernelGGL(se_bwd_batch_kernel, dim3((total + 255) / 256), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(se_bwd_batch_kernel, dim3((total + 7) / 8), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

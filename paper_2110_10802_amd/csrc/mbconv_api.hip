@@ -87,8 +87,8 @@ Plan make_plan(const mbconv_desc *d)
     P.nE = (size_t)P.N * P.Cexp * P.HW;
     P.nD = (size_t)P.N * P.Cexp * P.HWo;
     P.nP = (size_t)P.N * P.Cout * P.HWo;
-    P.NT1 = conv1x1_num_qtiles(P.N, P.HW);
-    P.NT5 = conv1x1_num_qtiles(P.N, P.HWo);
+    P.NT1 = conv1x1_num_partials(P.N, P.Cexp, P.Cin, P.HW, false);
+    P.NT5 = conv1x1_num_partials(P.N, P.Cout, P.Cexp, P.HWo, d->policy == MBCONV_STORE);
 
     size_t o = 0;
     auto take = [&o](size_t bytes) {

@@ -27,8 +27,10 @@ constexpr int kConvBQ = 128; // pixel columns per workgroup of the 1x1 conv kern
 inline int conv1x1_num_qtiles(int N, int HW) { return (int)(((long long)N * HW + kConvBQ - 1) / kConvBQ); }
 
 // out[n,m,q] = sum_k A(m,k) * op(B)[n,k,q], A(m,k) = w[m*sAm + k*sAk] (dtype).
-// epi: EPI_STATS writes per-(channel,q-tile) partial sums of out and out^2 to
-// psum/psq laid out [M][num_qtiles]; EPI_RES adds res[n,m,q] before the store.
+// epi: EPI_STATS writes partial sums of out and out^2 to psum/psq laid out
+// [M][conv1x1_num_partials(...)]; EPI_RES adds res[n,m,q] before the store.
+// sc_store (optional) receives the operand after its prologue (STORE policy).
+int conv1x1_num_partials(int N, int M, int K, int HW, bool stores_operand);
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
                           float *psq, void *sc_store, hipStream_t st);
