@@ -18,6 +18,12 @@
 
 namespace mbk {
 
+// kernels_dw4.hip: vectorised variants for stride 1 and W % 4 == 0
+bool dw4_supported(const DwShape &s);
+hipError_t launch_dw4_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
+                          const void *w_dw, void *d, float *psum, float *psq, hipStream_t st);
+hipError_t launch_dw4_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st);
+
 // Threads per plane: a wavefront for planes up to 16x16, a 256-thread workgroup up to
 // 64x64, 1024 threads above.
 static int pick_tpp(int plane_elems) { return plane_elems <= 256 ? 64 : plane_elems <= 4096 ? 256 : 1024; }
@@ -178,6 +184,8 @@ hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float
                          const void *w_dw, void *d, float *psum, float *psq, void *a1_store,
                          hipStream_t st)
 {
+    if (!a1_store && dw4_supported(s))
+        return launch_dw4_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
     DwFwdDev a;
     a.s = s;
     a.divC = make_div((uint32_t)s.C);
@@ -400,6 +408,8 @@ static hipError_t dw_bwd_ks(const DwBwdDev &a, hipStream_t st)
 
 hipError_t launch_dw_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st)
 {
+    if (!h.a1_saved && dw4_supported(h.s))
+        return launch_dw4_bwd(bf16, h, st);
     DwBwdDev a;
     a.s = h.s;
     const int p = h.s.p;

@@ -1,0 +1,526 @@
+// Vectorised depthwise chain for stride 1 and plane width a multiple of 4 (the 112, 56, 28
+// and 14 wide EfficientNet stages).
+//
+// Same plan as kernels_dw.hip (whole plane in LDS with a zero border, BN + Swish evaluated
+// once per input element while staging, no atomics), restructured so that every global and
+// LDS access is 16 bytes per lane and every thread keeps the element positions it staged:
+//   - a thread owns up to NG runs of four consecutive pixels; it loads them as float4,
+//     applies BN + Swish and writes the run to LDS with one ds_write_b128 (the interior of a
+//     tile row starts at column 4, so runs are 16-byte aligned);
+//   - the k x k stencil of a run reads, per filter row, one ds_read_b128 plus the (k-1)
+//     neighbours, i.e. about one LDS instruction per output instead of k*k;
+//   - backward keeps y1 and sigmoid(y1) of its own runs in registers between staging and the
+//     Swish' multiplication, so the expansion output e is read once (recompute without a second
+//     load; section "Backpropagation and Data Movement" of the paper).
+#include "mbconv_dev.h"
+#include "mbconv_launch.h"
+
+namespace mbk {
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+template <typename T>
+__device__ __forceinline__ void gload4(const T *p, size_t i, float (&v)[4]);
+template <>
+__device__ __forceinline__ void gload4<float>(const float *p, size_t i, float (&v)[4])
+{
+    const float4v t = *reinterpret_cast<const float4v *>(p + i);
+    v[0] = t.x;
+    v[1] = t.y;
+    v[2] = t.z;
+    v[3] = t.w;
+}
+template <>
+__device__ __forceinline__ void gload4<bf16_t>(const bf16_t *p, size_t i, float (&v)[4])
+{
+    const uint2 t = *reinterpret_cast<const uint2 *>(&p[i]);
+    v[0] = bf16_bits_to_float(t.x & 0xffffu);
+    v[1] = bf16_bits_to_float(t.x >> 16);
+    v[2] = bf16_bits_to_float(t.y & 0xffffu);
+    v[3] = bf16_bits_to_float(t.y >> 16);
+}
+template <typename T>
+__device__ __forceinline__ void gstore4(T *p, size_t i, const float (&v)[4]);
+template <>
+__device__ __forceinline__ void gstore4<float>(float *p, size_t i, const float (&v)[4])
+{
+    float4v t = {v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<float4v *>(p + i) = t;
+}
+template <>
+__device__ __forceinline__ void gstore4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
+{
+    uint2 t;
+    t.x = (uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16);
+    t.y = (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16);
+    *reinterpret_cast<uint2 *>(&p[i]) = t;
+}
+
+struct Dw4Args {
+    int N, C, H, W;
+    int WP;      // tile pitch = W + 8
+    int groups;  // H*W/4
+    FastDiv divC, divW4; // W/4
+    // forward
+    const void *e;
+    const float *bn1;
+    const void *w;
+    void *d;
+    float *psum, *psq;
+    // backward
+    const void *G;
+    const float *g, *dzs, *bn2, *coef2;
+    void *dy1_out;
+    const void *res;
+    float *pdw, *psb, *psr;
+};
+
+template <int TPP>
+__device__ __forceinline__ bool plane_of(const Dw4Args &a, size_t &plane, int &n, int &c)
+{
+    constexpr int BLOCK = TPP > 256 ? TPP : 256;
+    constexpr int PPB = BLOCK / TPP;
+    const size_t pl = (size_t)blockIdx.x * PPB + threadIdx.x / TPP;
+    const bool active = pl < (size_t)a.N * a.C;
+    plane = active ? pl : 0;
+    n = (int)fdiv((uint32_t)plane, a.divC);
+    c = (int)(plane - (size_t)n * a.C);
+    return active;
+}
+
+// Zero the border of a tile: the two 4-column pads of every row, and the P top/bottom rows.
+template <int P, int TPP>
+__device__ __forceinline__ void zero_border(float *tile, int H, int W, int WP, int lt)
+{
+    const float4v z = {0.f, 0.f, 0.f, 0.f};
+    const int rows = H + 2 * P;
+    for (int r = lt; r < rows; r += TPP) {
+        *reinterpret_cast<float4v *>(tile + r * WP) = z;
+        *reinterpret_cast<float4v *>(tile + r * WP + 4 + W) = z;
+    }
+    const int w4 = W >> 2;
+    for (int i = lt; i < 2 * P * w4; i += TPP) {
+        const int rr = i / w4, cc = i - rr * w4;
+        const int r = rr < P ? rr : H + rr; // rows 0..P-1 and H+P..H+2P-1
+        *reinterpret_cast<float4v *>(tile + r * WP + 4 + 4 * cc) = z;
+    }
+}
+
+// One row of a (K+3)-wide window starting at column (4 + w - P) of tile row `row`.
+template <int K>
+__device__ __forceinline__ void read_window_row(const float *tile, int row, int WP, int w,
+                                                float (&o)[K + 3])
+{
+    constexpr int P = (K - 1) / 2;
+    const float *p = tile + row * WP + 4 + w;
+    const float4v m = *reinterpret_cast<const float4v *>(p);
+    if (P == 1) {
+        o[0] = p[-1];
+        o[5] = p[4];
+    } else {
+        const float2 l = *reinterpret_cast<const float2 *>(p - 2);
+        const float2 r = *reinterpret_cast<const float2 *>(p + 4);
+        o[0] = l.x;
+        o[1] = l.y;
+        o[K + 1] = r.x;
+        o[K + 2] = r.y;
+    }
+    o[P] = m.x;
+    o[P + 1] = m.y;
+    o[P + 2] = m.z;
+    o[P + 3] = m.w;
+}
+
+// ---- forward ---------------------------------------------------------------------------------
+
+template <typename T, int K, int TPP, int NG, bool EXPAND>
+__global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_fwd_kernel(Dw4Args a)
+{
+    constexpr int P = (K - 1) / 2;
+    constexpr int BLOCK = TPP > 256 ? TPP : 256;
+    constexpr int PPB = BLOCK / TPP;
+    extern __shared__ float lds[];
+    const int H = a.H, W = a.W, WP = a.WP;
+    const int tileElems = (H + 2 * P) * WP;
+    const int lt = threadIdx.x % TPP;
+    float *tile = lds + (threadIdx.x / TPP) * tileElems;
+    float *red = lds + PPB * tileElems;
+    size_t plane;
+    int n, c;
+    const bool active = plane_of<TPP>(a, plane, n, c);
+
+    float wt[K * K];
+    if (active) {
+        float scale = 1.f, shift = 0.f;
+        if (EXPAND) {
+            scale = a.bn1[c];
+            shift = a.bn1[a.C + c];
+        }
+#pragma unroll
+        for (int t = 0; t < K * K; ++t)
+            wt[t] = ld<T>((const T *)a.w, (size_t)c * K * K + t);
+        zero_border<P, TPP>(tile, H, W, WP, lt);
+        const size_t base = plane * (size_t)H * W;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            if (gidx < a.groups) {
+                const int h = (int)fdiv((uint32_t)gidx, a.divW4);
+                const int w = 4 * (gidx - h * (W >> 2));
+                float v[4];
+                gload4<T>((const T *)a.e, base + 4 * (size_t)gidx, v);
+                if (EXPAND) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        v[r] = swishf(fmaf(v[r], scale, shift));
+                }
+                float4v t4 = {v[0], v[1], v[2], v[3]};
+                *reinterpret_cast<float4v *>(tile + (h + P) * WP + 4 + w) = t4;
+            }
+        }
+    }
+    __syncthreads();
+    float acc2[2] = {0.f, 0.f};
+    if (active) {
+        const size_t base = plane * (size_t)H * W;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            if (gidx < a.groups) {
+                const int h = (int)fdiv((uint32_t)gidx, a.divW4);
+                const int w = 4 * (gidx - h * (W >> 2));
+                float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u < K; ++u) {
+                    float row[K + 3];
+                    read_window_row<K>(tile, h + u, WP, w, row);
+#pragma unroll
+                    for (int v = 0; v < K; ++v)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            o[r] = fmaf(wt[u * K + v], row[r + v], o[r]);
+                }
+                gstore4<T>((T *)a.d, base + 4 * (size_t)gidx, o);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float sv = as_stored<T>(o[r]);
+                    acc2[0] += sv;
+                    acc2[1] = fmaf(sv, sv, acc2[1]);
+                }
+            }
+        }
+    }
+    group_sum<2, TPP>(acc2, red);
+    if (active && lt == 0) {
+        a.psum[(size_t)c * a.N + n] = acc2[0];
+        a.psq[(size_t)c * a.N + n] = acc2[1];
+    }
+}
+
+// ---- backward ----------------------------------------------------------------------------------
+
+template <typename T, int K, int TPP, int NG, bool EXPAND>
+__global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_bwd_kernel(Dw4Args a)
+{
+    constexpr int P = (K - 1) / 2;
+    constexpr int BLOCK = TPP > 256 ? TPP : 256;
+    constexpr int PPB = BLOCK / TPP;
+    constexpr int NV = K * K + 2;
+    extern __shared__ float lds[];
+    const int H = a.H, W = a.W, WP = a.WP, C = a.C;
+    const int tileElems = (H + 2 * P) * WP;
+    const int lt = threadIdx.x % TPP;
+    float *a1t = lds + (threadIdx.x / TPP) * (2 * tileElems);
+    float *ddt = a1t + tileElems;
+    float *red = lds + PPB * 2 * tileElems;
+    size_t plane;
+    int n, c;
+    const bool active = plane_of<TPP>(a, plane, n, c);
+
+    float wt[K * K];
+    float rawk[NG][4], sgk[NG][4]; // e and sigmoid(y1) of the runs this thread staged
+    float mean1 = 0.f, rstd1 = 0.f, scale1 = 1.f, shift1 = 0.f;
+    if (active) {
+#pragma unroll
+        for (int t = 0; t < K * K; ++t)
+            wt[t] = ld<T>((const T *)a.w, (size_t)c * K * K + t);
+        if (EXPAND) {
+            scale1 = a.bn1[c];
+            shift1 = a.bn1[C + c];
+            mean1 = a.bn1[2 * C + c];
+            rstd1 = a.bn1[3 * C + c];
+        }
+        const float scale2 = a.bn2[c], shift2 = a.bn2[C + c];
+        const float c0 = a.coef2[c], c1 = a.coef2[C + c], c2 = a.coef2[2 * C + c];
+        const float gate = a.g[plane], dzs = a.dzs[plane];
+        zero_border<P, TPP>(a1t, H, W, WP, lt);
+        zero_border<P, TPP>(ddt, H, W, WP, lt);
+        const size_t base = plane * (size_t)H * W;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            if (gidx < a.groups) {
+                const int h = (int)fdiv((uint32_t)gidx, a.divW4);
+                const int w = 4 * (gidx - h * (W >> 2));
+                float ev[4], Gv[4], dv[4], av[4], ddv[4];
+                gload4<T>((const T *)a.e, base + 4 * (size_t)gidx, ev);
+                gload4<T>((const T *)a.G, base + 4 * (size_t)gidx, Gv);
+                gload4<T>((const T *)a.d, base + 4 * (size_t)gidx, dv);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (EXPAND) {
+                        const float y = fmaf(ev[r], scale1, shift1);
+                        const float sg = sigmoidf_fast(y);
+                        rawk[i][r] = ev[r];
+                        sgk[i][r] = sg;
+                        av[r] = y * sg;
+                    } else {
+                        av[r] = ev[r];
+                    }
+                    const float y2 = fmaf(dv[r], scale2, shift2);
+                    const float s2 = sigmoidf_fast(y2);
+                    const float grad2 = s2 * (1.f + y2 * (1.f - s2));
+                    const float dy2 = fmaf(Gv[r], gate, dzs) * grad2;
+                    ddv[r] = fmaf(c0, dy2, fmaf(c1, dv[r], c2));
+                }
+                float4v t4 = {av[0], av[1], av[2], av[3]};
+                *reinterpret_cast<float4v *>(a1t + (h + P) * WP + 4 + w) = t4;
+                float4v u4 = {ddv[0], ddv[1], ddv[2], ddv[3]};
+                *reinterpret_cast<float4v *>(ddt + (h + P) * WP + 4 + w) = u4;
+            }
+        }
+    }
+    __syncthreads();
+
+    float acc[NV];
+#pragma unroll
+    for (int t = 0; t < NV; ++t)
+        acc[t] = 0.f;
+    if (active) {
+        const size_t base = plane * (size_t)H * W;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            if (gidx < a.groups) {
+                const int h = (int)fdiv((uint32_t)gidx, a.divW4);
+                const int w = 4 * (gidx - h * (W >> 2));
+                float da[4] = {0.f, 0.f, 0.f, 0.f};
+                float ddc[4];
+                // input gradient: da[r] = sum_{u,v} wt[u][v] * ddwin[K-1-u][r+K-1-v]
+#pragma unroll
+                for (int rr = 0; rr < K; ++rr) {
+                    float row[K + 3];
+                    read_window_row<K>(ddt, h + rr, WP, w, row);
+                    if (rr == P) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            ddc[r] = row[P + r];
+                    }
+                    const int u = K - 1 - rr;
+#pragma unroll
+                    for (int v = 0; v < K; ++v)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            da[r] = fmaf(wt[u * K + v], row[r + K - 1 - v], da[r]);
+                }
+                // filter gradient: acc[u][v] += sum_r dd[h][w+r] * a1win[u][r+v]
+#pragma unroll
+                for (int u = 0; u < K; ++u) {
+                    float row[K + 3];
+                    read_window_row<K>(a1t, h + u, WP, w, row);
+#pragma unroll
+                    for (int v = 0; v < K; ++v)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            acc[u * K + v] = fmaf(ddc[r], row[r + v], acc[u * K + v]);
+                }
+                float o[4];
+                if (EXPAND) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float raw = rawk[i][r], sg = sgk[i][r];
+                        const float y = fmaf(raw, scale1, shift1);
+                        o[r] = da[r] * (sg * (1.f + y * (1.f - sg)));
+                        const float sv = as_stored<T>(o[r]);
+                        acc[K * K] += sv;
+                        acc[K * K + 1] = fmaf(sv, (raw - mean1) * rstd1, acc[K * K + 1]);
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        o[r] = da[r];
+                    if (a.res) {
+                        float rv[4];
+                        gload4<T>((const T *)a.res, base + 4 * (size_t)gidx, rv);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            o[r] += rv[r];
+                    }
+                }
+                gstore4<T>((T *)a.dy1_out, base + 4 * (size_t)gidx, o);
+            }
+        }
+    }
+    group_sum<NV, TPP>(acc, red);
+    if (active && lt == 0) {
+        float *dst = a.pdw + ((size_t)c * a.N + n) * (K * K);
+#pragma unroll
+        for (int t = 0; t < K * K; ++t)
+            dst[t] = acc[t];
+        if (EXPAND) {
+            a.psb[(size_t)c * a.N + n] = acc[K * K];
+            a.psr[(size_t)c * a.N + n] = acc[K * K + 1];
+        }
+    }
+}
+
+// ---- dispatch ---------------------------------------------------------------------------------
+
+// Thread-group shape for a plane of `groups` float4 runs: (threads per plane, runs per thread).
+static bool dw4_shape(int groups, int *tpp, int *ng)
+{
+    if (groups <= 64) {
+        *tpp = 64;
+        *ng = 1;
+    } else if (groups <= 256) {
+        *tpp = 64;
+        *ng = 4;
+    } else if (groups <= 1024) {
+        *tpp = 256;
+        *ng = 4;
+    } else if (groups <= 4096) {
+        *tpp = 1024;
+        *ng = 4;
+    } else {
+        return false;
+    }
+    return true;
+}
+
+bool dw4_supported(const DwShape &s)
+{
+    int tpp, ng;
+    return s.s == 1 && (s.W % 4) == 0 && (s.k == 3 || s.k == 5) && s.Ho == s.H && s.Wo == s.W &&
+           dw4_shape(s.H * s.W / 4, &tpp, &ng);
+}
+
+static size_t dw4_lds(const DwShape &s, int tiles, int nv)
+{
+    int tpp, ng;
+    dw4_shape(s.H * s.W / 4, &tpp, &ng);
+    const int block = tpp > 256 ? tpp : 256;
+    const int ppb = block / tpp;
+    const int p = (s.k - 1) / 2;
+    return sizeof(float) * ((size_t)ppb * tiles * (s.H + 2 * p) * (s.W + 8) + (size_t)(block / 64) * nv);
+}
+
+static Dw4Args dw4_args(const DwShape &s)
+{
+    Dw4Args a = {};
+    a.N = s.N;
+    a.C = s.C;
+    a.H = s.H;
+    a.W = s.W;
+    a.WP = s.W + 8;
+    a.groups = s.H * s.W / 4;
+    a.divC = make_div((uint32_t)s.C);
+    a.divW4 = make_div((uint32_t)(s.W / 4));
+    return a;
+}
+
+template <typename KERN>
+static hipError_t dw4_launch(KERN kern, const Dw4Args &a, int block, int ppb, size_t lds,
+                             hipStream_t st)
+{
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess)
+        return e;
+    const size_t planes = (size_t)a.N * a.C;
+    const unsigned grid = (unsigned)((planes + ppb - 1) / ppb);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(block), lds, st, a);
+    return hipGetLastError();
+}
+
+#define MBK_DW4_SHAPES(KERNEL, T, K, EXP)                                                         \
+    if (tpp == 64 && ng == 1)                                                                     \
+        return dw4_launch(KERNEL<T, K, 64, 1, EXP>, a, 256, 4, lds, st);                          \
+    if (tpp == 64 && ng == 4)                                                                     \
+        return dw4_launch(KERNEL<T, K, 64, 4, EXP>, a, 256, 4, lds, st);                          \
+    if (tpp == 256)                                                                               \
+        return dw4_launch(KERNEL<T, K, 256, 4, EXP>, a, 256, 1, lds, st);                         \
+    return dw4_launch(KERNEL<T, K, 1024, 4, EXP>, a, 1024, 1, lds, st);
+
+template <typename T, int K, bool EXP>
+static hipError_t dw4_fwd_go(const Dw4Args &a, int tpp, int ng, size_t lds, hipStream_t st)
+{
+    MBK_DW4_SHAPES(dw4_fwd_kernel, T, K, EXP)
+}
+template <typename T, int K, bool EXP>
+static hipError_t dw4_bwd_go(const Dw4Args &a, int tpp, int ng, size_t lds, hipStream_t st)
+{
+    MBK_DW4_SHAPES(dw4_bwd_kernel, T, K, EXP)
+}
+
+hipError_t launch_dw4_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
+                          const void *w_dw, void *d, float *psum, float *psq, hipStream_t st)
+{
+    Dw4Args a = dw4_args(s);
+    a.e = e;
+    a.bn1 = bn1;
+    a.w = w_dw;
+    a.d = d;
+    a.psum = psum;
+    a.psq = psq;
+    int tpp, ng;
+    dw4_shape(a.groups, &tpp, &ng);
+    const size_t lds = dw4_lds(s, 1, 2);
+    const bool ex = bn1 != nullptr;
+#define MBK_GO(T, K)                                                                              \
+    return ex ? dw4_fwd_go<T, K, true>(a, tpp, ng, lds, st) : dw4_fwd_go<T, K, false>(a, tpp, ng, lds, st);
+    if (bf16) {
+        if (s.k == 3)
+            MBK_GO(bf16_t, 3)
+        MBK_GO(bf16_t, 5)
+    }
+    if (s.k == 3)
+        MBK_GO(float, 3)
+    MBK_GO(float, 5)
+#undef MBK_GO
+}
+
+hipError_t launch_dw4_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st)
+{
+    Dw4Args a = dw4_args(h.s);
+    a.e = h.e;
+    a.bn1 = h.bn1;
+    a.w = h.w_dw;
+    a.d = const_cast<void *>(h.d); // read-only in backward
+    a.G = h.G;
+    a.g = h.g;
+    a.dzs = h.dzs;
+    a.bn2 = h.bn2;
+    a.coef2 = h.coef2;
+    a.dy1_out = h.dy1_out;
+    a.res = h.res;
+    a.pdw = h.pdw;
+    a.psb = h.psb;
+    a.psr = h.psr;
+    int tpp, ng;
+    dw4_shape(a.groups, &tpp, &ng);
+    const size_t lds = dw4_lds(h.s, 2, h.s.k * h.s.k + 2);
+    const bool ex = h.bn1 != nullptr;
+#define MBK_GO(T, K)                                                                              \
+    return ex ? dw4_bwd_go<T, K, true>(a, tpp, ng, lds, st) : dw4_bwd_go<T, K, false>(a, tpp, ng, lds, st);
+    if (bf16) {
+        if (h.s.k == 3)
+            MBK_GO(bf16_t, 3)
+        MBK_GO(bf16_t, 5)
+    }
+    if (h.s.k == 3)
+        MBK_GO(float, 3)
+    MBK_GO(float, 5)
+#undef MBK_GO
+}
+
+} // namespace mbk
