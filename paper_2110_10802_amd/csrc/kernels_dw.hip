@@ -450,14 +450,50 @@ struct PlaneArgs {
     const void *res;
 };
 
+// Four consecutive elements at once (16 bytes per lane for fp32, 8 for bf16).
+template <typename T>
+__device__ __forceinline__ void ldvec4(const T *p, size_t i, float (&v)[4]);
+template <>
+__device__ __forceinline__ void ldvec4<float>(const float *p, size_t i, float (&v)[4])
+{
+    const float4 t = *reinterpret_cast<const float4 *>(p + i);
+    v[0] = t.x;
+    v[1] = t.y;
+    v[2] = t.z;
+    v[3] = t.w;
+}
+template <>
+__device__ __forceinline__ void ldvec4<bf16_t>(const bf16_t *p, size_t i, float (&v)[4])
+{
+    const uint2 t = *reinterpret_cast<const uint2 *>(&p[i]);
+    v[0] = bf16_bits_to_float(t.x & 0xffffu);
+    v[1] = bf16_bits_to_float(t.x >> 16);
+    v[2] = bf16_bits_to_float(t.y & 0xffffu);
+    v[3] = bf16_bits_to_float(t.y >> 16);
+}
+template <typename T>
+__device__ __forceinline__ void stvec4(T *p, size_t i, const float (&v)[4]);
+template <>
+__device__ __forceinline__ void stvec4<float>(float *p, size_t i, const float (&v)[4])
+{
+    *reinterpret_cast<float4 *>(p + i) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <>
+__device__ __forceinline__ void stvec4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
+{
+    uint2 t;
+    t.x = (uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16);
+    t.y = (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16);
+    *reinterpret_cast<uint2 *>(&p[i]) = t;
+}
+
 // z = mean swish(y), s3 = sum swish'(y), s4 = sum swish'(y)*xhat, y = BN(t0)
 struct OpPool {
     static constexpr int NV = 3;
-    template <typename T>
-    static __device__ __forceinline__ void eval(const PlaneArgs &a, size_t i, float sc, float sh,
-                                                float mu, float rs, float (&acc)[NV])
+    static constexpr bool kTwo = false;
+    static __device__ __forceinline__ void eval(float v, float, float sc, float sh, float mu,
+                                                float rs, float (&acc)[NV])
     {
-        const float v = ld<T>((const T *)a.t0, i);
         float val, grad;
         swish_both(fmaf(v, sc, sh), val, grad);
         acc[0] += val;
@@ -468,12 +504,10 @@ struct OpPool {
 // sums of dy (t0) and dy*xhat(t1)
 struct OpDot {
     static constexpr int NV = 2;
-    template <typename T>
-    static __device__ __forceinline__ void eval(const PlaneArgs &a, size_t i, float, float, float mu,
+    static constexpr bool kTwo = true;
+    static __device__ __forceinline__ void eval(float dy, float raw, float, float, float mu,
                                                 float rs, float (&acc)[NV])
     {
-        const float dy = ld<T>((const T *)a.t0, i);
-        const float raw = ld<T>((const T *)a.t1, i);
         acc[0] += dy;
         acc[1] = fmaf(dy, (raw - mu) * rs, acc[1]);
     }
@@ -481,12 +515,10 @@ struct OpDot {
 // G (t0) against a2, swish'(y2), swish'(y2)*dhat rebuilt from d (t1)
 struct OpGate {
     static constexpr int NV = 3;
-    template <typename T>
-    static __device__ __forceinline__ void eval(const PlaneArgs &a, size_t i, float sc, float sh,
-                                                float mu, float rs, float (&acc)[NV])
+    static constexpr bool kTwo = true;
+    static __device__ __forceinline__ void eval(float Gv, float v, float sc, float sh, float mu,
+                                                float rs, float (&acc)[NV])
     {
-        const float Gv = ld<T>((const T *)a.t0, i);
-        const float v = ld<T>((const T *)a.t1, i);
         float val, grad;
         swish_both(fmaf(v, sc, sh), val, grad);
         acc[0] = fmaf(Gv, val, acc[0]);
@@ -510,8 +542,23 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void plane_reduce_kernel(Pla
         const float sc = a.bn[pl.c], sh = a.bn[a.C + pl.c];
         const float mu = a.bn[2 * a.C + pl.c], rs = a.bn[3 * a.C + pl.c];
         const size_t base = pl.plane * (size_t)a.HW;
-        for (int idx = lt; idx < a.HW; idx += TPP)
-            OP::template eval<T>(a, base + idx, sc, sh, mu, rs, acc);
+        if ((a.HW & 3) == 0) {
+            for (int idx = 4 * lt; idx < a.HW; idx += 4 * TPP) {
+                float v0[4], v1[4] = {0.f, 0.f, 0.f, 0.f};
+                ldvec4<T>((const T *)a.t0, base + idx, v0);
+                if (OP::kTwo)
+                    ldvec4<T>((const T *)a.t1, base + idx, v1);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    OP::eval(v0[r], v1[r], sc, sh, mu, rs, acc);
+            }
+        } else {
+            for (int idx = lt; idx < a.HW; idx += TPP) {
+                const float v0 = ld<T>((const T *)a.t0, base + idx);
+                const float v1 = OP::kTwo ? ld<T>((const T *)a.t1, base + idx) : 0.f;
+                OP::eval(v0, v1, sc, sh, mu, rs, acc);
+            }
+        }
     }
     group_sum<OP::NV, TPP>(acc, red);
     if (pl.active && lt == 0) {
@@ -532,11 +579,29 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void bn_apply_kernel(PlaneAr
         return;
     const float sc = a.bn[pl.c], sh = a.bn[a.C + pl.c];
     const size_t base = pl.plane * (size_t)a.HW;
-    for (int idx = lt; idx < a.HW; idx += TPP) {
-        float v = fmaf(ld<T>((const T *)a.t0, base + idx), sc, sh);
-        if (a.res)
-            v += ld<T>((const T *)a.res, base + idx);
-        st<T>((T *)a.out, base + idx, v);
+    if ((a.HW & 3) == 0) {
+        for (int idx = 4 * lt; idx < a.HW; idx += 4 * TPP) {
+            float v[4];
+            ldvec4<T>((const T *)a.t0, base + idx, v);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                v[r] = fmaf(v[r], sc, sh);
+            if (a.res) {
+                float rr[4];
+                ldvec4<T>((const T *)a.res, base + idx, rr);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    v[r] += rr[r];
+            }
+            stvec4<T>((T *)a.out, base + idx, v);
+        }
+    } else {
+        for (int idx = lt; idx < a.HW; idx += TPP) {
+            float v = fmaf(ld<T>((const T *)a.t0, base + idx), sc, sh);
+            if (a.res)
+                v += ld<T>((const T *)a.res, base + idx);
+            st<T>((T *)a.out, base + idx, v);
+        }
     }
 }
 

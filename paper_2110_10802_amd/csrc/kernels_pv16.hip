@@ -1,0 +1,519 @@
+// Register-direct 1x1 convolutions for the HBM-bound ("skinny") shapes, built on
+// v_mfma_f32_16x16x4_f32 with four-pixel vectors.
+//
+// What decides the speed of a 24 <-> 144 channel 1x1 convolution on this chip is not flops but
+// (a) 16-byte-per-lane global accesses (a dword-per-lane stream reaches under half the
+// bandwidth) and (b) enough independent wavefronts: a batch-32 56x56 layer has only 100 k
+// pixels, so tiles must be small.  Hence:
+//
+//   out[ch][pix] = sum_k W[ch][k] * act[k][pix],   C[i][j] += sum_k A[i][k] * B[k][j] with
+//   A = weights     lane l holds A[i = l%16][k = l/16]          (i = output channel)
+//   B = activations lane l holds B[k = l/16][j = l%16]          (j = group of 4 pixels)
+//   C               lane l, register v holds C[i = 4*(l/16)+v][j = l%16]
+//
+// A lane loads FOUR consecutive pixels of one input channel (float4; one load instruction
+// covers 4 input channels x 64 pixels, 256 contiguous bytes per channel) and feeds element r of
+// the vector to MFMA number r, so accumulator C_r holds pixels 4j+r.  Register v of C_0..C_3
+// is then four consecutive pixels of one output channel: stores are float4 too.  A tile is 64
+// pixels; activations never pass through LDS; there is no barrier in a main loop.
+//
+//   conv_pe ("expand-like", few input channels, K <= 40): the activation tile (K/4 float4 per
+//     lane) stays in registers; each wavefront of the workgroup produces 48 output channels.
+//   conv_pr ("reduce-like", at most 32 output channels): the input channels are split over the
+//     four wavefronts (each matrix core gets a quarter of the MFMAs); each wavefront then
+//     finishes a quarter of the output channels after one exchange of partial tiles via LDS.
+//
+// The elementwise prologues (Swish(BN(.))*gate, BN backward) run on the activation registers
+// between load and MFMA, so those tensors never exist in memory (recomputation instead of
+// load/store: section "Backpropagation and Data Movement" of the paper).  Per-channel BN
+// partial sums are reduced over the 16 lanes of a row with DPP row rotations (the paper's
+// warp-collective reductions, section "Hardware Specialization").
+#include "mbconv_dev.h"
+#include "mbconv_launch.h"
+
+namespace mbk {
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+struct PvArgs {
+    int N, M, K, HW;
+    uint32_t Q; // N*HW, a multiple of 4
+    int numTiles; // 64-pixel tiles
+    FastDiv divHW;
+    const void *w;
+    int sAm, sAk;
+    const void *p0, *p1;
+    const float *c0, *c1, *c2, *gate;
+    void *out;
+    const void *res;
+    float *psum, *psq;
+    int NP; // partial-sum slots per channel (= gridDim.x)
+};
+
+template <typename T>
+__device__ __forceinline__ void pv_load4(const T *p, size_t i, float (&v)[4]);
+template <>
+__device__ __forceinline__ void pv_load4<float>(const float *p, size_t i, float (&v)[4])
+{
+    const float4v t = *reinterpret_cast<const float4v *>(p + i);
+    v[0] = t.x;
+    v[1] = t.y;
+    v[2] = t.z;
+    v[3] = t.w;
+}
+template <>
+__device__ __forceinline__ void pv_load4<bf16_t>(const bf16_t *p, size_t i, float (&v)[4])
+{
+    const uint2 t = *reinterpret_cast<const uint2 *>(&p[i]);
+    v[0] = bf16_bits_to_float(t.x & 0xffffu);
+    v[1] = bf16_bits_to_float(t.x >> 16);
+    v[2] = bf16_bits_to_float(t.y & 0xffffu);
+    v[3] = bf16_bits_to_float(t.y >> 16);
+}
+template <typename T>
+__device__ __forceinline__ void pv_store4(T *p, size_t i, const float (&v)[4]);
+template <>
+__device__ __forceinline__ void pv_store4<float>(float *p, size_t i, const float (&v)[4])
+{
+    float4v t = {v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<float4v *>(p + i) = t;
+}
+template <>
+__device__ __forceinline__ void pv_store4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
+{
+    uint2 t;
+    t.x = (uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16);
+    t.y = (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16);
+    *reinterpret_cast<uint2 *>(&p[i]) = t;
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, false)); // row_ror:8
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xf, 0xf, false)); // row_ror:4
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x122, 0xf, 0xf, false)); // row_ror:2
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x121, 0xf, 0xf, false)); // row_ror:1
+    return v;
+}
+
+// One float4 of activations of input channel k, image n, with its prologue (PRO_* in the header).
+template <typename T, int PRO>
+__device__ __forceinline__ void pv_load_act(const PvArgs &a, size_t idx, uint32_t n, int k,
+                                            const float *coef, int cstride, float (&v)[4])
+{
+    pv_load4<T>((const T *)a.p0, idx, v);
+    if (PRO == PRO_BNBWD) {
+        float raw[4];
+        pv_load4<T>((const T *)a.p1, idx, raw);
+        const float c0 = coef[k], c1 = coef[cstride + k], c2 = coef[2 * cstride + k];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            v[r] = fmaf(c0, v[r], fmaf(c1, raw[r], c2));
+    } else if (PRO == PRO_BNSWISH_GATE) {
+        const float sc = coef[k], sh = coef[cstride + k];
+        const float g = a.gate[(size_t)n * a.K + k];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            v[r] = swishf(fmaf(v[r], sc, sh)) * g;
+    }
+}
+
+template <int PRO>
+__device__ __forceinline__ void pv_stage_coef(const PvArgs &a, float *coef, int cstride)
+{
+    if (PRO == PRO_NONE)
+        return;
+    for (int idx = threadIdx.x; idx < cstride; idx += blockDim.x) {
+        const bool ok = idx < a.K;
+        coef[idx] = ok ? a.c0[idx] : 0.f;
+        coef[cstride + idx] = ok ? a.c1[idx] : 0.f;
+        if (PRO == PRO_BNBWD)
+            coef[2 * cstride + idx] = ok ? a.c2[idx] : 0.f;
+    }
+    __syncthreads();
+}
+
+// ---- conv_pe: few input channels --------------------------------------------------------------
+constexpr int kPeTT = 3;      // 16-channel tiles per wavefront (48 output channels)
+constexpr int kPeMaxWaves = 8; // M <= 384
+
+template <typename T, int KS4, int PRO, int EPI>
+__global__ __launch_bounds__(64 * kPeMaxWaves) void conv_pe_kernel(PvArgs a)
+{
+    __shared__ float coef[3 * 4 * KS4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int kk = lane >> 4, j = lane & 15;
+    pv_stage_coef<PRO>(a, coef, 4 * KS4);
+
+    // this wavefront's weights in A-operand order: wreg[t][s] = W(ch = 16*(wv*TT+t) + l%16, k = 4s + l/16)
+    float wreg[kPeTT][KS4];
+#pragma unroll
+    for (int t = 0; t < kPeTT; ++t)
+#pragma unroll
+        for (int s = 0; s < KS4; ++s) {
+            const int m = 16 * (wv * kPeTT + t) + j, k = 4 * s + kk;
+            wreg[t][s] = (m < a.M && k < a.K)
+                             ? ld<T>((const T *)a.w, (size_t)m * a.sAm + (size_t)k * a.sAk)
+                             : 0.f;
+        }
+
+    float ssum[kPeTT][4], ssq[kPeTT][4];
+#pragma unroll
+    for (int t = 0; t < kPeTT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            ssum[t][v] = ssq[t][v] = 0.f;
+
+    for (int tile = blockIdx.x; tile < a.numTiles; tile += gridDim.x) {
+        const uint32_t qv = (uint32_t)tile * 64u + 4u * j;
+        const bool valid = qv < a.Q;
+        const uint32_t n = valid ? fdiv(qv, a.divHW) : 0;
+        const uint32_t pix = valid ? qv - n * (uint32_t)a.HW : 0;
+        float bv[KS4][4];
+#pragma unroll
+        for (int s = 0; s < KS4; ++s) {
+            const int k = 4 * s + kk;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                bv[s][r] = 0.f;
+            if (valid && k < a.K)
+                pv_load_act<T, PRO>(a, ((size_t)n * a.K + k) * a.HW + pix, n, k, coef, 4 * KS4, bv[s]);
+        }
+#pragma unroll
+        for (int t = 0; t < kPeTT; ++t) {
+            float4v acc[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[r] = (float4v){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS4; ++s)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wreg[t][s], bv[s][r], acc[r], 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = 16 * (wv * kPeTT + t) + 4 * kk + v;
+                if (valid && m < a.M) {
+                    const size_t idx = ((size_t)n * a.M + m) * a.HW + pix;
+                    float o[4] = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+                    if (EPI == EPI_RES) {
+                        float rr[4];
+                        pv_load4<T>((const T *)a.res, idx, rr);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            o[r] += rr[r];
+                    }
+                    pv_store4<T>((T *)a.out, idx, o);
+                    if (EPI == EPI_STATS) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float sv = as_stored<T>(o[r]);
+                            ssum[t][v] += sv;
+                            ssq[t][v] = fmaf(sv, sv, ssq[t][v]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (EPI == EPI_STATS) {
+#pragma unroll
+        for (int t = 0; t < kPeTT; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float s = row16_sum(ssum[t][v]);
+                const float s2 = row16_sum(ssq[t][v]);
+                const int m = 16 * (wv * kPeTT + t) + 4 * kk + v;
+                if (j == 0 && m < a.M) {
+                    a.psum[(size_t)m * a.NP + blockIdx.x] = s;
+                    a.psq[(size_t)m * a.NP + blockIdx.x] = s2;
+                }
+            }
+    }
+}
+
+// ---- conv_pr: at most 32 output channels --------------------------------------------------------
+// Wavefront w contracts the input-channel quads [w*KSW, (w+1)*KSW) of the tile into two
+// 16-channel accumulator tiles; then output-channel registers (t, v) with 2*t + v/2 == g go to
+// wavefront g, which adds the four partials in wavefront order and stores channels
+// 16*(g/2) + 4*(l/16) + 2*(g%2) + {0,1}.
+constexpr int kPrU = 9; // input-channel quads loaded per batch
+
+template <typename T, int PRO, int EPI>
+__global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a)
+{
+    extern __shared__ float lds[];
+    const int KS4 = (a.K + 3) >> 2;
+    const int KSW = (KS4 + 3) >> 2;
+    float *coef = lds;                 // [3][4*KS4]
+    float *xch = lds + 12 * KS4;       // [4 src][3 other dst][8 values][64 lanes]
+    float *wl = xch + 12 * 8 * 64;     // [KS4][2][64]: weights in A-operand order
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int kk = lane >> 4, j = lane & 15;
+    // wl[(s*2+t)*64 + l] = W(ch = 16t + l%16, k = 4s + l/16)
+    for (int idx = threadIdx.x; idx < KS4 * 2 * 64; idx += 256) {
+        const int ln = idx & 63, st_ = idx >> 6;
+        const int m = 16 * (st_ & 1) + (ln & 15), k = 4 * (st_ >> 1) + (ln >> 4);
+        wl[idx] = (m < a.M && k < a.K)
+                      ? ld<T>((const T *)a.w, (size_t)m * a.sAm + (size_t)k * a.sAk)
+                      : 0.f;
+    }
+    if (PRO == PRO_NONE)
+        __syncthreads();
+    pv_stage_coef<PRO>(a, coef, 4 * KS4); // ends with a barrier when there is a prologue
+
+    float ssum[2] = {0.f, 0.f}, ssq[2] = {0.f, 0.f};
+    const int sBeg = w * KSW, sEnd = (sBeg + KSW < KS4) ? sBeg + KSW : KS4;
+    const int tOwn = w >> 1, vOwn = 2 * (w & 1);
+
+    for (int tile = blockIdx.x; tile < a.numTiles; tile += gridDim.x) {
+        const uint32_t qv = (uint32_t)tile * 64u + 4u * j;
+        const bool valid = qv < a.Q;
+        const uint32_t n = valid ? fdiv(qv, a.divHW) : 0;
+        const uint32_t pix = valid ? qv - n * (uint32_t)a.HW : 0;
+        const size_t base = (size_t)n * a.K * a.HW + pix;
+        float4v acc[2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[t][r] = (float4v){0.f, 0.f, 0.f, 0.f};
+
+        for (int s0 = sBeg; s0 < sEnd; s0 += kPrU) {
+            float bv[kPrU][4];
+#pragma unroll
+            for (int u = 0; u < kPrU; ++u) {
+                const int s = s0 + u, k = 4 * s + kk;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    bv[u][r] = 0.f;
+                if (valid && s < sEnd && k < a.K)
+                    pv_load_act<T, PRO>(a, base + (size_t)k * a.HW, n, k, coef, 4 * KS4, bv[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < kPrU; ++u) {
+                const int s = s0 + u;
+                if (s < sEnd) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const float wv = wl[(s * 2 + t) * 64 + lane];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            acc[t][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv, bv[u][r], acc[t][r],
+                                                                             0, 0, 0);
+                    }
+                }
+            }
+        }
+        // exchange partial tiles
+        float own[2][4]; // [v - vOwn][r]
+        __syncthreads(); // the previous tile's buffer has been consumed
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int tg = g >> 1, vg = 2 * (g & 1);
+            if (g == w) {
+#pragma unroll
+                for (int dv = 0; dv < 2; ++dv)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        own[dv][r] = acc[tg][r][vg + dv];
+            } else {
+                const int slot = w * 3 + (g < w ? g : g - 1);
+#pragma unroll
+                for (int dv = 0; dv < 2; ++dv)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        xch[(slot * 8 + dv * 4 + r) * 64 + lane] = acc[tg][r][vg + dv];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int dv = 0; dv < 2; ++dv) {
+            float o[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float sacc = 0.f;
+#pragma unroll
+                for (int src = 0; src < 4; ++src) {
+                    if (src == w) {
+                        sacc += own[dv][r];
+                    } else {
+                        const int slot = src * 3 + (w < src ? w : w - 1);
+                        sacc += xch[(slot * 8 + dv * 4 + r) * 64 + lane];
+                    }
+                }
+                o[r] = sacc;
+            }
+            const int m = 16 * tOwn + 4 * kk + vOwn + dv;
+            if (valid && m < a.M) {
+                const size_t idx = ((size_t)n * a.M + m) * a.HW + pix;
+                if (EPI == EPI_RES) {
+                    float rr[4];
+                    pv_load4<T>((const T *)a.res, idx, rr);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        o[r] += rr[r];
+                }
+                pv_store4<T>((T *)a.out, idx, o);
+                if (EPI == EPI_STATS) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float sv = as_stored<T>(o[r]);
+                        ssum[dv] += sv;
+                        ssq[dv] = fmaf(sv, sv, ssq[dv]);
+                    }
+                }
+            }
+        }
+    }
+    if (EPI == EPI_STATS) {
+#pragma unroll
+        for (int dv = 0; dv < 2; ++dv) {
+            const float s = row16_sum(ssum[dv]);
+            const float s2 = row16_sum(ssq[dv]);
+            const int m = 16 * tOwn + 4 * kk + vOwn + dv;
+            if (j == 0 && m < a.M) {
+                a.psum[(size_t)m * a.NP + blockIdx.x] = s;
+                a.psq[(size_t)m * a.NP + blockIdx.x] = s2;
+            }
+        }
+        // slots of workgroups that were not launched contribute nothing
+        if (blockIdx.x == 0) {
+            const int extra = a.NP - (int)gridDim.x;
+            for (int idx = threadIdx.x; idx < a.M * extra; idx += 256) {
+                const int m = idx / extra, slot = (int)gridDim.x + (idx - m * extra);
+                a.psum[(size_t)m * a.NP + slot] = 0.f;
+                a.psq[(size_t)m * a.NP + slot] = 0.f;
+            }
+        }
+    }
+}
+
+// ---- dispatch ---------------------------------------------------------------------------------
+
+// At most 1024 workgroups, each taking the same number of tiles (up to rounding).
+static int pv_grid(int numTiles)
+{
+    if (numTiles <= 1024)
+        return numTiles < 1 ? 1 : numTiles;
+    const int per = (numTiles + 1023) / 1024;
+    return (numTiles + per - 1) / per;
+}
+
+static size_t conv_pr_lds(int K)
+{
+    const int ks4 = (K + 3) / 4;
+    return sizeof(float) * ((size_t)12 * ks4 + 12 * 8 * 64 + (size_t)ks4 * 2 * 64);
+}
+
+// Which register-direct kernel covers (M, K, HW), if any: 1 = conv_pe, 2 = conv_pr, 0 = none.
+int wave_conv_kind(int M, int K, int HW)
+{
+    if (HW % 4 != 0)
+        return 0;
+    if (K <= 40 && M <= 16 * kPeTT * kPeMaxWaves)
+        return 1;
+    if (M <= 32 && conv_pr_lds(K) <= 60 * 1024)
+        return 2;
+    return 0;
+}
+
+int wave_conv_num_partials(int kind, int N, int HW)
+{
+    (void)kind;
+    return pv_grid((int)(((long long)N * HW + 63) / 64));
+}
+
+template <typename T, int PRO, int EPI>
+static hipError_t launch_pe(const PvArgs &a, int grid, hipStream_t st)
+{
+    const int ks4 = (a.K + 3) / 4;
+    const int waves = ((a.M + 15) / 16 + kPeTT - 1) / kPeTT;
+#define MBK_E(KS4)                                                                                \
+    if (ks4 <= KS4) {                                                                             \
+        hipLaunchKernelGGL((conv_pe_kernel<T, KS4, PRO, EPI>), dim3(grid), dim3(64 * waves), 0, st, \
+                           a);                                                                    \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_E(4)
+    MBK_E(6)
+    MBK_E(8)
+    MBK_E(10)
+#undef MBK_E
+    return hipErrorInvalidValue;
+}
+
+// conv_pr workgroups are long (two barriers per tile), so a second wave of workgroups that
+// starts when the first finishes would double the kernel's duration: launch no more than
+// can be resident at once and let them stride over the tiles.  Partial-sum slots beyond the
+// launched grid are zeroed by workgroup 0.
+static int device_cu_count()
+{
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess)
+        (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    return cus > 0 ? cus : 256;
+}
+
+template <typename T, int PRO, int EPI>
+static hipError_t launch_pr(PvArgs a, int grid, hipStream_t st)
+{
+    auto kern = conv_pr_kernel<T, PRO, EPI>;
+    const size_t lds = conv_pr_lds(a.K);
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds) != hipSuccess || per_cu < 1)
+        per_cu = 1;
+    const int resident = per_cu * device_cu_count();
+    if (grid > resident)
+        grid = resident;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t pv_dispatch(const PvArgs &a, int kind, int pro, int epi, int grid, hipStream_t st)
+{
+#define MBK_CASE(P, E)                                                                            \
+    if (pro == P && epi == E)                                                                     \
+        return kind == 1 ? launch_pe<T, P, E>(a, grid, st) : launch_pr<T, P, E>(a, grid, st);
+    MBK_CASE(PRO_NONE, EPI_STATS)
+    MBK_CASE(PRO_BNSWISH_GATE, EPI_STATS)
+    MBK_CASE(PRO_BNBWD, EPI_NONE)
+    MBK_CASE(PRO_BNBWD, EPI_RES)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_wave_conv1x1(bool bf16, int kind, int N, int M, int K, int HW, const void *w,
+                               int sAm, int sAk, const Operand &B, void *out, int epi,
+                               const void *res, float *psum, float *psq, hipStream_t st)
+{
+    PvArgs a;
+    a.N = N;
+    a.M = M;
+    a.K = K;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    a.numTiles = (int)((a.Q + 63u) / 64u);
+    a.divHW = make_div((uint32_t)HW);
+    a.w = w;
+    a.sAm = sAm;
+    a.sAk = sAk;
+    a.p0 = B.p0;
+    a.p1 = B.p1;
+    a.c0 = B.c0;
+    a.c1 = B.c1;
+    a.c2 = B.c2;
+    a.gate = B.gate;
+    a.out = out;
+    a.res = res;
+    a.psum = psum;
+    a.psq = psq;
+    const int grid = pv_grid(a.numTiles);
+    a.NP = grid;
+    return bf16 ? pv_dispatch<bf16_t>(a, kind, B.pro, epi, grid, st)
+                : pv_dispatch<float>(a, kind, B.pro, epi, grid, st);
+}
+
+} // namespace mbk
