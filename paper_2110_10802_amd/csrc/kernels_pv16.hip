@@ -142,7 +142,8 @@ template <typename T, int KS4, int PRO, int EPI>
 __global__ __launch_bounds__(64 * kPeMaxWaves) void conv_pe_kernel(PvArgs a)
 {
     __shared__ float coef[3 * 4 * KS4];
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform
     const int kk = lane >> 4, j = lane & 15;
     pv_stage_coef<PRO>(a, coef, 4 * KS4);
 
@@ -238,21 +239,22 @@ __global__ __launch_bounds__(64 * kPeMaxWaves) void conv_pe_kernel(PvArgs a)
 // 16-channel accumulator tiles; then output-channel registers (t, v) with 2*t + v/2 == g go to
 // wavefront g, which adds the four partials in wavefront order and stores channels
 // 16*(g/2) + 4*(l/16) + 2*(g%2) + {0,1}.
-constexpr int kPrU = 9; // input-channel quads loaded per batch
-
-template <typename T, int PRO, int EPI>
-__global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a)
+// The share of every wavefront is padded to KSWp quads (a multiple of the batch size U); padded
+// quads have zero weights in LDS and read a clamped, valid address, so the load / MFMA loops
+// carry no bounds checks.
+template <typename T, int PRO, int EPI, int U>
+__global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
 {
     extern __shared__ float lds[];
-    const int KS4 = (a.K + 3) >> 2;
-    const int KSW = (KS4 + 3) >> 2;
-    float *coef = lds;                 // [3][4*KS4]
-    float *xch = lds + 12 * KS4;       // [4 src][3 other dst][8 values][64 lanes]
-    float *wl = xch + 12 * 8 * 64;     // [KS4][2][64]: weights in A-operand order
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int KS4p = 4 * KSWp;
+    float *coef = lds;                 // [3][4*KS4p]
+    float *xch = lds + 12 * KS4p;      // [4 src][4 dst][8 values][64 lanes]
+    float *wl = xch + 16 * 8 * 64;     // [KS4p][2][64]: weights in A-operand order
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, keep it scalar
     const int kk = lane >> 4, j = lane & 15;
-    // wl[(s*2+t)*64 + l] = W(ch = 16t + l%16, k = 4s + l/16)
-    for (int idx = threadIdx.x; idx < KS4 * 2 * 64; idx += 256) {
+    // wl[(s*2+t)*64 + l] = W(ch = 16t + l%16, k = 4s + l/16), zero outside M x K
+    for (int idx = threadIdx.x; idx < KS4p * 2 * 64; idx += 256) {
         const int ln = idx & 63, st_ = idx >> 6;
         const int m = 16 * (st_ & 1) + (ln & 15), k = 4 * (st_ >> 1) + (ln >> 4);
         wl[idx] = (m < a.M && k < a.K)
@@ -261,17 +263,19 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a)
     }
     if (PRO == PRO_NONE)
         __syncthreads();
-    pv_stage_coef<PRO>(a, coef, 4 * KS4); // ends with a barrier when there is a prologue
+    pv_stage_coef<PRO>(a, coef, 4 * KS4p); // ends with a barrier when there is a prologue
 
     float ssum[2] = {0.f, 0.f}, ssq[2] = {0.f, 0.f};
-    const int sBeg = w * KSW, sEnd = (sBeg + KSW < KS4) ? sBeg + KSW : KS4;
+    const int sBeg = w * KSWp;
     const int tOwn = w >> 1, vOwn = 2 * (w & 1);
+    const int kLast = a.K - 1;
 
     for (int tile = blockIdx.x; tile < a.numTiles; tile += gridDim.x) {
         const uint32_t qv = (uint32_t)tile * 64u + 4u * j;
         const bool valid = qv < a.Q;
-        const uint32_t n = valid ? fdiv(qv, a.divHW) : 0;
-        const uint32_t pix = valid ? qv - n * (uint32_t)a.HW : 0;
+        const uint32_t qs = valid ? qv : 0u; // lanes past the end read pixel 0 and store nothing
+        const uint32_t n = fdiv(qs, a.divHW);
+        const uint32_t pix = qs - n * (uint32_t)a.HW;
         const size_t base = (size_t)n * a.K * a.HW + pix;
         float4v acc[2][4];
 #pragma unroll
@@ -280,53 +284,37 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a)
             for (int r = 0; r < 4; ++r)
                 acc[t][r] = (float4v){0.f, 0.f, 0.f, 0.f};
 
-        for (int s0 = sBeg; s0 < sEnd; s0 += kPrU) {
-            float bv[kPrU][4];
+        for (int u0 = 0; u0 < KSWp; u0 += U) {
+            float bv[U][4];
 #pragma unroll
-            for (int u = 0; u < kPrU; ++u) {
-                const int s = s0 + u, k = 4 * s + kk;
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    bv[u][r] = 0.f;
-                if (valid && s < sEnd && k < a.K)
-                    pv_load_act<T, PRO>(a, base + (size_t)k * a.HW, n, k, coef, 4 * KS4, bv[u]);
+            for (int u = 0; u < U; ++u) {
+                int k = 4 * (sBeg + u0 + u) + kk;
+                k = k < kLast ? k : kLast;
+                pv_load_act<T, PRO>(a, base + (size_t)k * a.HW, n, k, coef, 4 * KS4p, bv[u]);
             }
 #pragma unroll
-            for (int u = 0; u < kPrU; ++u) {
-                const int s = s0 + u;
-                if (s < sEnd) {
+            for (int u = 0; u < U; ++u) {
+                const int s = sBeg + u0 + u;
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const float wv = wl[(s * 2 + t) * 64 + lane];
+                for (int t = 0; t < 2; ++t) {
+                    const float wv = wl[(s * 2 + t) * 64 + lane];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            acc[t][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv, bv[u][r], acc[t][r],
-                                                                             0, 0, 0);
-                    }
+                    for (int r = 0; r < 4; ++r)
+                        acc[t][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv, bv[u][r], acc[t][r], 0,
+                                                                         0, 0);
                 }
             }
         }
-        // exchange partial tiles
-        float own[2][4]; // [v - vOwn][r]
+        // exchange partial tiles: every wavefront publishes, per destination g, the two
+        // accumulator registers that g finishes (tile g/2, registers 2*(g%2) + {0,1})
         __syncthreads(); // the previous tile's buffer has been consumed
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int tg = g >> 1, vg = 2 * (g & 1);
-            if (g == w) {
+        for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int dv = 0; dv < 2; ++dv)
+            for (int dv = 0; dv < 2; ++dv)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        own[dv][r] = acc[tg][r][vg + dv];
-            } else {
-                const int slot = w * 3 + (g < w ? g : g - 1);
-#pragma unroll
-                for (int dv = 0; dv < 2; ++dv)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        xch[(slot * 8 + dv * 4 + r) * 64 + lane] = acc[tg][r][vg + dv];
-            }
-        }
+                for (int r = 0; r < 4; ++r)
+                    xch[(((w * 4 + g) * 8) + dv * 4 + r) * 64 + lane] = acc[g >> 1][r][2 * (g & 1) + dv];
         __syncthreads();
 #pragma unroll
         for (int dv = 0; dv < 2; ++dv) {
@@ -335,14 +323,8 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a)
             for (int r = 0; r < 4; ++r) {
                 float sacc = 0.f;
 #pragma unroll
-                for (int src = 0; src < 4; ++src) {
-                    if (src == w) {
-                        sacc += own[dv][r];
-                    } else {
-                        const int slot = src * 3 + (w < src ? w : w - 1);
-                        sacc += xch[(slot * 8 + dv * 4 + r) * 64 + lane];
-                    }
-                }
+                for (int src = 0; src < 4; ++src)
+                    sacc += xch[(((src * 4 + w) * 8) + dv * 4 + r) * 64 + lane];
                 o[r] = sacc;
             }
             const int m = 16 * tOwn + 4 * kk + vOwn + dv;
@@ -401,10 +383,21 @@ static int pv_grid(int numTiles)
     return (numTiles + per - 1) / per;
 }
 
+// Batch size and padded per-wavefront share (in input-channel quads) of conv_pr.
+static void conv_pr_shape(int K, int *U, int *KSWp)
+{
+    const int ks4 = (K + 3) / 4, ksw = (ks4 + 3) / 4;
+    const int p3 = (ksw + 2) / 3 * 3;
+    *KSWp = p3;
+    *U = (p3 % 9 == 0) ? 9 : (p3 % 6 == 0) ? 6 : 3;
+}
+
 static size_t conv_pr_lds(int K)
 {
-    const int ks4 = (K + 3) / 4;
-    return sizeof(float) * ((size_t)12 * ks4 + 12 * 8 * 64 + (size_t)ks4 * 2 * 64);
+    int U, kswp;
+    conv_pr_shape(K, &U, &kswp);
+    const int ks4p = 4 * kswp;
+    return sizeof(float) * ((size_t)12 * ks4p + 16 * 8 * 64 + (size_t)ks4p * 2 * 64);
 }
 
 // Which register-direct kernel covers (M, K, HW), if any: 1 = conv_pe, 2 = conv_pr, 0 = none.
@@ -459,16 +452,27 @@ static int device_cu_count()
 template <typename T, int PRO, int EPI>
 static hipError_t launch_pr(PvArgs a, int grid, hipStream_t st)
 {
-    auto kern = conv_pr_kernel<T, PRO, EPI>;
+    int U, kswp;
+    conv_pr_shape(a.K, &U, &kswp);
     const size_t lds = conv_pr_lds(a.K);
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds) != hipSuccess || per_cu < 1)
-        per_cu = 1;
-    const int resident = per_cu * device_cu_count();
-    if (grid > resident)
-        grid = resident;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
-    return hipGetLastError();
+#define MBK_PR(UU)                                                                                \
+    if (U == UU) {                                                                                \
+        auto kern = conv_pr_kernel<T, PRO, EPI, UU>;                                              \
+        int per_cu = 0;                                                                           \
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds) != hipSuccess || \
+            per_cu < 1)                                                                           \
+            per_cu = 1;                                                                           \
+        const int resident = per_cu * device_cu_count();                                          \
+        if (grid > resident)                                                                      \
+            grid = resident;                                                                      \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a, kswp);                        \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_PR(9)
+    MBK_PR(6)
+    MBK_PR(3)
+#undef MBK_PR
+    return hipErrorInvalidValue;
 }
 
 template <typename T>
