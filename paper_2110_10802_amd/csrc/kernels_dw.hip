@@ -16,6 +16,8 @@
 #include "mbconv_dev.h"
 #include "mbconv_launch.h"
 
+#include <algorithm>
+
 namespace mbk {
 
 // kernels_dw4.hip: vectorised variants for stride 1 and W % 4 == 0
@@ -206,6 +208,7 @@ hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float
 struct DwBwdDev {
     DwShape s;
     FastDiv divC, divWp, divWq, divWo, divW;
+    FastDiv divWc0, divWc1; // stride 2: columns per parity class starting at column 0 / 1
     const void *G, *d, *e;
     const float *g, *dzs, *bn2, *coef2, *bn1;
     const void *w;
@@ -307,24 +310,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw_bwd_kernel(DwBwdDev 
         // for which both quotients are exact; in border coordinates the row is
         // (h+P-u+S*P)/S, always non-negative.
         const size_t ebase = pl.plane * (size_t)H * W;
-        for (int idx = lt; idx < H * W; idx += TPP) {
-            const int h = (int)fdiv((uint32_t)idx, a.divW);
-            const int x = idx - h * W;
-            float da = 0.f;
-#pragma unroll
-            for (int u = 0; u < K; ++u) {
-                const int nh = h + P - u + S * P;
-                if (S > 1 && (nh % S) != 0)
-                    continue;
-                const int ip = nh / S;
-#pragma unroll
-                for (int v = 0; v < K; ++v) {
-                    const int nx = x + P - v + S * P;
-                    if (S > 1 && (nx % S) != 0)
-                        continue;
-                    da = fmaf(w[u * K + v], ddt[ip * Wq + nx / S], da);
-                }
-            }
+        auto finish = [&](int idx, float da) { // Swish', store, BN1 partial sums
             if (bn) {
                 const float raw = ld<T>((const T *)a.e, ebase + idx);
                 float val, grad;
@@ -339,6 +325,44 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw_bwd_kernel(DwBwdDev 
                     da += ld<T>((const T *)a.res, ebase + idx);
                 st<T>((T *)a.dy1_out, ebase + idx, da);
             }
+        };
+        if (S == 1) {
+            for (int idx = lt; idx < H * W; idx += TPP) {
+                const int h = (int)fdiv((uint32_t)idx, a.divW);
+                const int x = idx - h * W;
+                float da = 0.f;
+#pragma unroll
+                for (int u = 0; u < K; ++u)
+#pragma unroll
+                    for (int v = 0; v < K; ++v)
+                        da = fmaf(w[u * K + v], ddt[(h + 2 * P - u) * Wq + x + 2 * P - v], da);
+                finish(idx, da);
+            }
+        } else {
+            // stride 2: an input pixel only meets the taps u = ph (mod 2), v = pw (mod 2) with
+            // ph = (h+P)&1, pw = (x+P)&1.  The four parity classes are walked one after the
+            // other so that the tap set, and hence the weight registers, are compile-time.
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph)
+#pragma unroll
+                for (int pw = 0; pw < 2; ++pw) {
+                    const int hs = ph ^ (P & 1), xs = pw ^ (P & 1); // first row / column of the class
+                    const int Hc = (H - hs + 1) >> 1, Wc = (W - xs + 1) >> 1;
+                    const FastDiv dv = xs ? a.divWc1 : a.divWc0;
+                    for (int idx = lt; idx < Hc * Wc; idx += TPP) {
+                        const int hh = (int)fdiv((uint32_t)idx, dv);
+                        const int h = hs + 2 * hh, x = xs + 2 * (idx - hh * Wc);
+                        const int r0 = ((h + P - ph) >> 1) + P, c0 = ((x + P - pw) >> 1) + P;
+                        float da = 0.f;
+#pragma unroll
+                        for (int ua = 0; ph + 2 * ua < K; ++ua)
+#pragma unroll
+                            for (int vb = 0; pw + 2 * vb < K; ++vb)
+                                da = fmaf(w[(ph + 2 * ua) * K + pw + 2 * vb],
+                                          ddt[(r0 - ua) * Wq + c0 - vb], da);
+                        finish(h * W + x, da);
+                    }
+                }
         }
     }
     group_sum<NV, TPP>(acc, red);
@@ -418,6 +442,8 @@ hipError_t launch_dw_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st)
     a.divWq = make_div((uint32_t)(h.s.Wo + 2 * p));
     a.divWo = make_div((uint32_t)h.s.Wo);
     a.divW = make_div((uint32_t)h.s.W);
+    a.divWc0 = make_div((uint32_t)std::max(1, (h.s.W + 1) / 2));
+    a.divWc1 = make_div((uint32_t)std::max(1, h.s.W / 2));
     a.G = h.G;
     a.d = h.d;
     a.e = h.e;

@@ -140,3 +140,81 @@ def test_bf16_matches_rounding_model(name):
     print(errs, gerrs, flush=True)
     assert max(errs.values()) <= 2.0 ** -6, errs
     assert max(gerrs.values()) <= 2.0 ** -6, gerrs
+
+
+def _oracle_chain(blocks, seed0=100):
+    """Oracle forward through the whole chain, then backward; returns per-block inputs/results."""
+    recs = []
+    x = None
+    for i, s in enumerate(blocks):
+        t = make_block_inputs(s, seed=seed0 + i, with_x=(i == 0), with_dout=(i == len(blocks) - 1))
+        if i > 0:
+            t["x"] = x
+        f = orc.mbconv_forward(s, t)
+        recs.append({"shape": s, "t": t, "f": f})
+        x = f.out
+    dout = recs[-1]["t"]["dout"].astype(np.float64)
+    for r in reversed(recs):
+        r["dout"] = dout
+        r["b"] = orc.mbconv_backward(r["shape"], r["t"], r["f"].tape, dout)
+        dout = r["b"].dx
+    return recs
+
+
+def test_b0_chain_matches_oracle():
+    """The 16 MBConv blocks of EfficientNet-B0 (benchmark config 4) at batch 4: every block is
+    run on the GPU from the oracle's input and upstream gradient (isolated, standard tolerances),
+    and the chain is also run end to end on the GPU (block i fed by GPU block i-1)."""
+    import torch
+    from paper_2110_10802_amd.harness import DeviceBlock, to_numpy
+
+    blocks = b0_chain(N=4)
+    recs = _oracle_chain(blocks)
+    # isolated
+    for i, r in enumerate(recs):
+        s = r["shape"]
+        t = dict(r["t"])
+        t["x"] = np.asarray(t["x"], dtype=np.float32)
+        t["dout"] = np.asarray(r["dout"], dtype=np.float32)
+        print(f"[parity/chain] block {i + 1} {s.Cin}->{s.Cexp}->{s.Cout} {s.H}x{s.W} k{s.k}s{s.stride}",
+              flush=True)
+        res, blk = run_gpu_block(s, t)
+        # the oracle saw float64 x/dout; the GPU their float32 roundings (1e-7, far below tolerance)
+        compare_block(s, t, res, r["f"], r["b"], blk)
+        del blk
+    # end to end
+    dev = []
+    x = None
+    for i, r in enumerate(recs):
+        blk = DeviceBlock(r["shape"], r["t"])
+        xin = blk.to_device(r["t"]["x"]) if i == 0 else x
+        blk.forward(xin)
+        dev.append((blk, xin))
+        x = blk.out
+    torch.cuda.synchronize()
+    assert rel_err(to_numpy(dev[-1][0].out), recs[-1]["f"].out) <= 1e-3
+    dout = dev[-1][0].to_device(recs[-1]["t"]["dout"])
+    for blk, xin in reversed(dev):
+        blk.backward(xin, dout)
+        dout = blk.dx
+    torch.cuda.synchronize()
+    assert rel_err(to_numpy(dev[0][0].dx), recs[0]["b"].dx) <= 1e-2
+    for (blk, _), r in zip(dev, recs):
+        # d(beta3) of an inner block is zero by invariance (see compare_block): absolute floor
+        d = np.asarray(r["dout"], dtype=np.float64)
+        beta_floor = float(np.sqrt(np.mean(d * d)) * np.sqrt(d.size / d.shape[1]))
+        for n, g in blk.grads.items():
+            floor = beta_floor if n == "bn3_beta" else 0.0
+            assert rel_err(to_numpy(g), r["b"].grads[n], floor) <= 1e-2, (r["shape"], n)
+
+
+@pytest.mark.parametrize("index", [0, 1])
+def test_b0_chain_first_blocks_full_batch(index):
+    """Blocks 1 and 2 of config 4 (112x112 planes, the largest thread-group shape, no expansion
+    / stride 2) at the full batch of 64."""
+    s = b0_chain(N=64)[index]
+    t = make_block_inputs(s, seed=0)
+    print(f"[parity/chain-full] block {index + 1} {s}", flush=True)
+    res, blk = run_gpu_block(s, t)
+    f, b = orc.mbconv_step(s, t)
+    compare_block(s, t, res, f, b, blk)
