@@ -88,12 +88,118 @@ def cpu_baseline(shape, tensors):
                       f"{dt:.1f} s wall"}
 
 
+NO_EXPAND_STEPS = ("expand_conv", "bn1_finalize", "bn1_bwd_finalize", "expand_dgrad", "expand_wgrad")
+
+
+def run_chain(args) -> int:
+    """Benchmark config 4: the 16 MBConv blocks of EfficientNet-B0 chained (block i's output is
+    block i+1's input; backward in reverse order), one scratch workspace shared by all blocks."""
+    import torch
+    from mbconv_inputs import b0_chain, make_block_inputs
+    from paper_2110_10802_amd import binding as B
+    from paper_2110_10802_amd.harness import DeviceBlock
+
+    B.load()
+    shapes = b0_chain()
+    policy = B.MBCONV_STORE if args.policy == "store" else B.MBCONV_RECOMPUTE
+    scratch_bytes = max(B.mbconv_workspace_size(B.make_desc(s, policy))[1] for s in shapes)
+    scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device="cuda")
+    blocks, ctx = [], []
+    for i, s in enumerate(shapes):
+        t = make_block_inputs(s, seed=i, with_x=(i == 0), with_dout=(i == len(shapes) - 1))
+        blk = DeviceBlock(s, t, policy=policy, scratch=scratch)
+        if i == 0:
+            x0 = blk.to_device(t["x"])
+        if i == len(shapes) - 1:
+            dlast = blk.to_device(t["dout"])
+        blocks.append(blk)
+    stream = torch.cuda.current_stream().cuda_stream
+    for i, blk in enumerate(blocks):
+        ctx.append({
+            "blk": blk, "desc": blk.desc, "params": B._fill(B.Params(), blk.params),
+            "running": B._fill(B.BNState(), blk.running) if blk.running else None,
+            "grads": B._fill(B.Grads(), blk.grads),
+            "x": x0 if i == 0 else blocks[i - 1].out,
+            "dout": dlast if i == len(blocks) - 1 else blocks[i + 1].dx,
+        })
+
+    def step(probe=None, probe_block=-1):
+        for i, c in enumerate(ctx):
+            pr = probe if (i == probe_block and probe.step <= 9) else None
+            B.mbconv_forward_probed(c["desc"], c["params"], c["running"], c["x"], c["blk"].out,
+                                    c["blk"].saved, scratch, stream, pr)
+        for i in range(len(ctx) - 1, -1, -1):
+            c = ctx[i]
+            pr = probe if (i == probe_block and probe.step > 9) else None
+            B.mbconv_backward_probed(c["desc"], c["params"], c["x"], c["dout"], c["blk"].saved,
+                                     scratch, c["blk"].dx, c["grads"], stream, pr)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    survey = []
+    for i, c in enumerate(ctx):
+        row = {}
+        for name, sid in B.STEPS.items():
+            if not shapes[i].has_expand and name in NO_EXPAND_STEPS:
+                continue
+            reps = []
+            for _ in range(3):
+                step(B.Probe(sid, e0, e1), i)
+                torch.cuda.synchronize()
+                reps.append(ev.elapsed_ms(e0, e1))
+            row[name] = sorted(reps)[1]
+        survey.append(row)
+        s = shapes[i]
+        print(f"block {i + 1:2d} {s.Cin}->{s.Cexp}->{s.Cout} {s.H}x{s.W} k{s.k}s{s.stride}: "
+              f"{sum(row.values()) * 1e3:7.1f}us  " +
+              " ".join(f"{n}={v * 1e3:.0f}" for n, v in row.items()), file=sys.stderr)
+    ev.destroy(e0)
+    ev.destroy(e1)
+    cand = [(i, n) for i, row in enumerate(survey) for n in row
+            if algorithmic_bytes(shapes[i], n) is not None]
+    if args.probe_step:
+        bi, dominant = args.probe_step.split(":")
+        bi = int(bi) - 1
+    else:
+        bi, dominant = max(cand, key=lambda c: survey[c[0]][c[1]])
+    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    probes = [B.Probe(B.STEPS[dominant], a, b) for a, b in pairs]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(probes[i], bi)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = sum(ev.elapsed_ms(a, b) for a, b in pairs) / args.steps
+    nbytes = algorithmic_bytes(shapes[bi], dominant)
+    achieved = nbytes / (kern_ms * 1e-3) / 1e9
+    N = shapes[0].N
+    result = {
+        "metric": "mbconv_fwd_bwd_images_per_sec", "value": N / (ms_per_step * 1e-3),
+        "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config4", "block": f"N{N} EfficientNet-B0 chain of 16 MBConv blocks, "
+                   "32ch 112x112 in", "policy": args.policy},
+        "roofline": {"bound": "hbm", "kernel": f"block{bi + 1}:{dominant}", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "kernel_ms": kern_ms, "algorithmic_bytes": nbytes},
+        "block_ms_survey": [round(sum(r.values()), 5) for r in survey],
+    }
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3])
+    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--policy", default="recompute", choices=["recompute", "store"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe-step", default=None,
@@ -115,6 +221,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.config == 4:
+        return run_chain(args)
     B.load()  # fails loudly if the HIP library has not been built
     shape = CONFIGS[args.config]
     tensors = make_block_inputs(shape, seed=0)
@@ -145,8 +253,7 @@ def main() -> int:
     survey = {}
     e0, e1 = ev.create(), ev.create()
     for name, sid in B.STEPS.items():
-        if not shape.has_expand and name in ("expand_conv", "bn1_finalize", "bn1_bwd_finalize",
-                                             "expand_dgrad", "expand_wgrad"):
+        if not shape.has_expand and name in NO_EXPAND_STEPS:
             continue
         reps = []
         for _ in range(3):

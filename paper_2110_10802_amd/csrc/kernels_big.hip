@@ -1,0 +1,631 @@
+// 1x1 convolutions and their weight gradients for the wide blocks (tens to a thousand
+// channels on both sides), where the contraction is long enough to be bound by the matrix
+// cores rather than by HBM.
+//
+// The batch is flattened: the GEMM column index is q = n*HW + pixel over all images, so small
+// planes (14x14, 7x7) fill whole tiles.  A workgroup of four waves owns a (64*WT) x (64*WT) output
+// tile, every wave a (32*WT) x (32*WT) block of v_mfma_f32_32x32x2_f32 accumulators; the
+// contraction is consumed 16 (convolution) or 32 (weight gradient) at a time through two LDS
+// buffers: the global loads of chunk i+1 are issued before the MFMAs of chunk i and land in LDS
+// after them, so one barrier per chunk suffices.  The activation operand goes through its
+// elementwise prologue on the way into LDS (Swish(BN(.))*gate, or the BN-backward expression),
+// so these intermediates never exist in HBM (sections "Local Data Movement Reduction" and
+// "Backpropagation and Data Movement").  Workgroups that share an activation tile are placed on
+// the same XCD (blockIdx % 8) so the second read hits that XCD's L2.
+#include "mbconv_dev.h"
+#include "mbconv_launch.h"
+
+namespace mbk {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+struct BigOperand {
+    const void *p0, *p1;
+    const float *c0, *c1, *c2, *gate;
+};
+
+// VEC consecutive elements of a tensor stored as T, widened to fp32
+template <typename T, int VEC>
+__device__ __forceinline__ void big_ld(const T *p, size_t i, float (&v)[VEC]);
+template <>
+__device__ __forceinline__ void big_ld<float, 4>(const float *p, size_t i, float (&v)[4])
+{
+    const float4 t = *reinterpret_cast<const float4 *>(p + i);
+    v[0] = t.x;
+    v[1] = t.y;
+    v[2] = t.z;
+    v[3] = t.w;
+}
+template <>
+__device__ __forceinline__ void big_ld<float, 1>(const float *p, size_t i, float (&v)[1])
+{
+    v[0] = p[i];
+}
+template <>
+__device__ __forceinline__ void big_ld<bf16_t, 4>(const bf16_t *p, size_t i, float (&v)[4])
+{
+    const uint2 t = *reinterpret_cast<const uint2 *>(&p[i]);
+    v[0] = bf16_bits_to_float(t.x & 0xffffu);
+    v[1] = bf16_bits_to_float(t.x >> 16);
+    v[2] = bf16_bits_to_float(t.y & 0xffffu);
+    v[3] = bf16_bits_to_float(t.y >> 16);
+}
+template <>
+__device__ __forceinline__ void big_ld<bf16_t, 1>(const bf16_t *p, size_t i, float (&v)[1])
+{
+    v[0] = bf16_bits_to_float(p[i].bits);
+}
+
+// Raw registers of one staged run of VEC elements of an operand row, with the row's
+// prologue coefficients.  zero() makes apply() return 0 for every element.
+template <int PRO, int VEC>
+struct Staged {
+    float v0[VEC];
+    float v1[PRO == PRO_BNBWD ? VEC : 1];
+    float k0, k1, k2; // BNBWD: c0,c1,c2; BNSWISH_GATE: scale, shift, gate
+
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j)
+            v0[j] = 0.f;
+        if (PRO == PRO_BNBWD) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j)
+                v1[j] = 0.f;
+        }
+        k0 = k1 = k2 = 0.f;
+    }
+    template <typename T>
+    __device__ __forceinline__ void load(const BigOperand &o, size_t idx)
+    {
+        big_ld<T, VEC>((const T *)o.p0, idx, v0);
+        if constexpr (PRO == PRO_BNBWD)
+            big_ld<T, VEC>((const T *)o.p1, idx, v1);
+    }
+    __device__ __forceinline__ float apply(int j) const
+    {
+        if (PRO == PRO_NONE)
+            return v0[j];
+        if (PRO == PRO_BNSWISH_GATE)
+            return swishf(fmaf(v0[j], k0, k1)) * k2;
+        return fmaf(k0, v0[j], fmaf(k1, v1[PRO == PRO_BNBWD ? j : 0], k2));
+    }
+};
+
+struct BigConvArgs {
+    int M, K, HW;
+    uint32_t Q; // N*HW
+    FastDiv divHW;
+    const void *w;
+    int sAm, sAk;
+    BigOperand B;
+    void *out;
+    const void *res;
+    float *psum, *psq;
+    int QT, MT; // tiles along q and m
+};
+
+// out[n,m,pix] = sum_k A(m,k) * op(B)[n,k,pix].  Requirements (checked by the host):
+// K % 4 == 0, M % 4 == 0, HW % VEC == 0, one of sAm/sAk equal to 1.
+template <typename T, int PRO, int EPI, int WM, int WP, int VEC>
+__global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
+{
+    constexpr int BM = 64 * WM, BP = 64 * WP, BK = 16;
+    constexpr int PA = BM + 4; // pitch = 4 mod 8: the transposing stores of A are 2-way at worst
+    constexpr int NB = VEC == 4 ? WP : 4 * WP; // staged runs of B per thread
+    constexpr int BCOLS = BP / VEC;            // runs per row of the B tile
+    constexpr int BROWS = 256 / BCOLS;         // rows staged per pass
+    __shared__ __attribute__((aligned(16))) float As[2][BK][PA];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BP];
+    __shared__ float red[2][BM][2];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wp = wave & 1;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int qt = (slot / a.MT) * 8 + xcd, mt = slot % a.MT;
+    if (qt >= a.QT)
+        return;
+    const int m0 = mt * BM;
+    const uint32_t q0 = (uint32_t)qt * BP;
+    const bool kcontig = a.sAk == 1;
+
+    // ---- A staging ----
+    float4 ra[WM];
+    auto load_a = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (kcontig) {
+                const int m = m0 + (tid >> 2) + 64 * i, k = k0 + 4 * (tid & 3);
+                if (m < a.M && k < a.K)
+                    big_ld<T, 4>((const T *)a.w, (size_t)m * a.sAm + k, v);
+            } else {
+                const int m = m0 + 4 * (tid % (BM / 4)), k = k0 + tid / (BM / 4) + (1024 / BM) * i;
+                if (m < a.M && k < a.K)
+                    big_ld<T, 4>((const T *)a.w, (size_t)k * a.sAk + m, v);
+            }
+            ra[i] = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    };
+    auto store_a = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            if (kcontig) {
+                const int m = (tid >> 2) + 64 * i, kk = 4 * (tid & 3);
+                As[buf][kk + 0][m] = ra[i].x;
+                As[buf][kk + 1][m] = ra[i].y;
+                As[buf][kk + 2][m] = ra[i].z;
+                As[buf][kk + 3][m] = ra[i].w;
+            } else {
+                const int m = 4 * (tid % (BM / 4)), kk = tid / (BM / 4) + (1024 / BM) * i;
+                *reinterpret_cast<float4 *>(&As[buf][kk][m]) = ra[i];
+            }
+        }
+    };
+
+    // ---- B staging: this thread's pixel run is the same for every chunk ----
+    const int bcol = tid % BCOLS, brow = tid / BCOLS;
+    const uint32_t qb = q0 + (uint32_t)bcol * VEC;
+    const bool bvalid = qb < a.Q;
+    uint32_t bn = 0;
+    size_t bbase = 0;
+    if (bvalid) {
+        bn = fdiv(qb, a.divHW);
+        bbase = (size_t)bn * a.K * a.HW + (qb - bn * (uint32_t)a.HW);
+    }
+    Staged<PRO, VEC> rb[NB];
+    auto load_b = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int k = k0 + brow + BROWS * i;
+            if (bvalid && k < a.K) {
+                rb[i].template load<T>(a.B, bbase + (size_t)k * a.HW);
+                if (PRO == PRO_BNSWISH_GATE) {
+                    rb[i].k0 = a.B.c0[k];
+                    rb[i].k1 = a.B.c1[k];
+                    rb[i].k2 = a.B.gate[(size_t)bn * a.K + k];
+                } else if (PRO == PRO_BNBWD) {
+                    rb[i].k0 = a.B.c0[k];
+                    rb[i].k1 = a.B.c1[k];
+                    rb[i].k2 = a.B.c2[k];
+                }
+            } else {
+                rb[i].zero();
+            }
+        }
+    };
+    auto store_b = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int kk = brow + BROWS * i;
+            if (VEC == 4) {
+                *reinterpret_cast<float4 *>(&Bs[buf][kk][4 * bcol]) =
+                    make_float4(rb[i].apply(0), rb[i].apply(VEC == 4 ? 1 : 0),
+                                rb[i].apply(VEC == 4 ? 2 : 0), rb[i].apply(VEC == 4 ? 3 : 0));
+            } else {
+                Bs[buf][kk][bcol] = rb[i].apply(0);
+            }
+        }
+    };
+
+    float16v acc[WM][WP];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WP; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0.f;
+
+    const int nchunks = (a.K + BK - 1) / BK;
+    load_a(0);
+    load_b(0);
+    store_a(0);
+    store_b(0);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        const bool more = c + 1 < nchunks;
+        if (more) {
+            load_a((c + 1) * BK);
+            load_b((c + 1) * BK);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float av[WM], bv[WP];
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+                av[i] = As[buf][kk + (lane >> 5)][wm * 32 * WM + 32 * i + (lane & 31)];
+#pragma unroll
+            for (int j = 0; j < WP; ++j)
+                bv[j] = Bs[buf][kk + (lane >> 5)][wp * 32 * WP + 32 * j + (lane & 31)];
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WP; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            store_a(buf ^ 1);
+            store_b(buf ^ 1);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: register r of lane l is row 8*(r/4)+4*(l/32)+r%4, column l%32 ----
+    float rs[WM][16], rq[WM][16];
+    if (EPI == EPI_STATS) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                rs[i][r] = rq[i][r] = 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < WP; ++j) {
+        const uint32_t q = q0 + wp * 32 * WP + 32 * j + (lane & 31);
+        const bool valid = q < a.Q;
+        uint32_t n = 0, pix = 0;
+        if (valid) {
+            n = fdiv(q, a.divHW);
+            pix = q - n * (uint32_t)a.HW;
+        }
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 32 * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (valid && m < a.M) {
+                    float v = acc[i][j][r];
+                    const size_t idx = ((size_t)n * a.M + m) * a.HW + pix;
+                    if (EPI == EPI_RES)
+                        v += ld<T>((const T *)a.res, idx);
+                    st<T>((T *)a.out, idx, v);
+                    if (EPI == EPI_STATS) {
+                        const float sv = as_stored<T>(v);
+                        rs[i][r] += sv;
+                        rq[i][r] = fmaf(sv, sv, rq[i][r]);
+                    }
+                }
+            }
+        }
+    }
+    if (EPI == EPI_STATS) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float s = half_wave_sum(rs[i][r]);
+                const float s2 = half_wave_sum(rq[i][r]);
+                if ((lane & 31) == 0) {
+                    const int row = wm * 32 * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    red[0][row][wp] = s;
+                    red[1][row][wp] = s2;
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < BM && m0 + tid < a.M) {
+            a.psum[(size_t)(m0 + tid) * a.QT + qt] = red[0][tid][0] + red[0][tid][1];
+            a.psq[(size_t)(m0 + tid) * a.QT + qt] = red[1][tid][0] + red[1][tid][1];
+        }
+    }
+}
+
+static BigOperand to_big(const Operand &o)
+{
+    BigOperand d;
+    d.p0 = o.p0;
+    d.p1 = o.p1;
+    d.c0 = o.c0;
+    d.c1 = o.c1;
+    d.c2 = o.c2;
+    d.gate = o.gate;
+    return d;
+}
+
+// 128 rows per tile when that pads the channel count no further than 64 would
+static int big_rows(int M) { return ((M + 127) / 128) * 128 == ((M + 63) / 64) * 64 ? 2 : 1; }
+
+// Tile choice: 128 pixel columns when that still gives every CU work, else 64.  `wt` packs
+// the row and column factors as 4*WM + WP.
+bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles)
+{
+    const long long Q = (long long)N * HW;
+    if (K % 4 != 0 || M % 4 != 0 || Q >= (1ll << 31) || K < 16)
+        return false;
+    const int wm = big_rows(M);
+    const long long t128 = ((Q + 127) / 128) * ((M + 64 * wm - 1) / (64 * wm));
+    const int wp = (t128 >= 384 && HW % 4 == 0) ? 2 : 1;
+    *wt = 4 * wm + wp;
+    *qtiles = (int)((Q + 64 * wp - 1) / (64 * wp));
+    return true;
+}
+
+template <typename T, int WM, int WP, int VEC>
+static hipError_t big_conv_dispatch(const BigConvArgs &a, int pro, int epi, dim3 grid, hipStream_t st)
+{
+#define MBK_CASE(P, E)                                                                            \
+    if (pro == P && epi == E) {                                                                   \
+        hipLaunchKernelGGL((conv_big_kernel<T, P, E, WM, WP, VEC>), grid, dim3(256), 0, st, a);   \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(PRO_NONE, EPI_STATS)
+    MBK_CASE(PRO_BNSWISH_GATE, EPI_STATS)
+    MBK_CASE(PRO_BNBWD, EPI_NONE)
+    MBK_CASE(PRO_BNBWD, EPI_RES)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_big_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm,
+                              int sAk, const Operand &B, void *out, int epi, const void *res,
+                              float *psum, float *psq, hipStream_t st)
+{
+    int wt, qtiles;
+    if (!big_conv_plan(N, M, K, HW, &wt, &qtiles) || (sAm != 1 && sAk != 1))
+        return hipErrorInvalidValue;
+    BigConvArgs a;
+    a.M = M;
+    a.K = K;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    a.divHW = make_div((uint32_t)HW);
+    a.w = w;
+    a.sAm = sAm;
+    a.sAk = sAk;
+    a.B = to_big(B);
+    a.out = out;
+    a.res = res;
+    a.psum = psum;
+    a.psq = psq;
+    const int wm = wt >> 2, wp = wt & 3;
+    a.QT = qtiles;
+    a.MT = (M + 64 * wm - 1) / (64 * wm);
+    dim3 grid((unsigned)(((qtiles + 7) / 8) * 8 * a.MT));
+    const bool v4 = HW % 4 == 0;
+    if (!v4 && wp != 1)
+        return hipErrorInvalidValue;
+#define MBK_GO(TT)                                                                                \
+    (!v4 ? (wm == 2 ? big_conv_dispatch<TT, 2, 1, 1>(a, B.pro, epi, grid, st)                     \
+                    : big_conv_dispatch<TT, 1, 1, 1>(a, B.pro, epi, grid, st))                    \
+         : wm == 2 ? (wp == 2 ? big_conv_dispatch<TT, 2, 2, 4>(a, B.pro, epi, grid, st)           \
+                              : big_conv_dispatch<TT, 2, 1, 4>(a, B.pro, epi, grid, st))          \
+                   : (wp == 2 ? big_conv_dispatch<TT, 1, 2, 4>(a, B.pro, epi, grid, st)           \
+                              : big_conv_dispatch<TT, 1, 1, 4>(a, B.pro, epi, grid, st)))
+    return bf16 ? MBK_GO(bf16_t) : MBK_GO(float);
+#undef MBK_GO
+}
+
+// ---- weight gradient -------------------------------------------------------------------
+// dW[a,b] = sum_q op(U)[a,q] * op(V)[b,q]: both operands are pixel-contiguous in memory and
+// the matrix cores want the channel index across lanes, so both tiles are transposed on their
+// way into LDS ([q][channel], pitch = 2 mod 8 keeps the scalar stores 2-way at worst).  The
+// contraction is split over blockIdx.z; each split writes its own partial tile and a
+// fixed-order second stage adds them (no atomics: the map-fission step of section "Guided
+// Optimization Case Study: EfficientNet").
+
+struct BigWgradArgs {
+    int Ma, Mb, HW;
+    uint32_t Q;
+    int chunksPerSplit; // chunks of 32 pixels
+    FastDiv divHW;
+    BigOperand U, V;
+    float *partial;
+};
+
+template <typename T, int PROU, int PROV, int WA, int WB, int VEC>
+__global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
+{
+    constexpr int BA = 64 * WA, BB = 64 * WB, BQ = 32;
+    constexpr int PU = BA + 2, PV = BB + 2;
+    constexpr int QCOLS = BQ / VEC;     // runs per operand row
+    constexpr int RROWS = 256 / QCOLS;  // rows staged per pass
+    constexpr int NRU = BA / RROWS, NRV = BB / RROWS; // runs per thread of U and of V
+    // two LDS buffers, except for the 128x128 tile, where two would exceed 64 KiB
+    constexpr int NBUF = (WA == 2 && WB == 2) ? 1 : 2;
+    __shared__ __attribute__((aligned(16))) float Us[NBUF][BQ][PU];
+    __shared__ __attribute__((aligned(16))) float Vs[NBUF][BQ][PV];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wa = wave >> 1, wb = wave & 1;
+    const int a0 = blockIdx.x * BA, b0 = blockIdx.y * BB;
+    const int numChunks = (int)((a.Q + BQ - 1) / BQ);
+    const int cbeg = blockIdx.z * a.chunksPerSplit;
+    const int cend = min(cbeg + a.chunksPerSplit, numChunks);
+
+    const int qcol = tid % QCOLS, rrow = tid / QCOLS;
+    Staged<PROU, VEC> ru[NRU];
+    Staged<PROV, VEC> rv[NRV];
+    // per-row coefficients do not depend on the chunk (rows past the end keep zeros, which
+    // make apply() return 0 for zero data)
+#pragma unroll
+    for (int i = 0; i < NRU; ++i) {
+        const int ra = a0 + rrow + RROWS * i;
+        ru[i].zero();
+        if (PROU != PRO_NONE && ra < a.Ma) {
+            ru[i].k0 = a.U.c0[ra];
+            ru[i].k1 = a.U.c1[ra];
+            if (PROU == PRO_BNBWD)
+                ru[i].k2 = a.U.c2[ra];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NRV; ++i) {
+        const int rb = b0 + rrow + RROWS * i;
+        rv[i].zero();
+        if (PROV != PRO_NONE && rb < a.Mb) {
+            rv[i].k0 = a.V.c0[rb];
+            rv[i].k1 = a.V.c1[rb];
+            if (PROV == PRO_BNBWD)
+                rv[i].k2 = a.V.c2[rb];
+        }
+    }
+    bool staged_valid = false; // the staged pixel run lies inside the tensor
+    auto load = [&](int chunk) {
+        const uint32_t q = (uint32_t)chunk * BQ + (uint32_t)qcol * VEC;
+        staged_valid = q < a.Q;
+        if (!staged_valid)
+            return;
+        const uint32_t n = fdiv(q, a.divHW);
+        const uint32_t pix = q - n * (uint32_t)a.HW;
+#pragma unroll
+        for (int i = 0; i < NRU; ++i) {
+            const int ra = a0 + rrow + RROWS * i;
+            if (ra < a.Ma) {
+                ru[i].template load<T>(a.U, ((size_t)n * a.Ma + ra) * a.HW + pix);
+                if (PROU == PRO_BNSWISH_GATE)
+                    ru[i].k2 = a.U.gate[(size_t)n * a.Ma + ra];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NRV; ++i) {
+            const int rb = b0 + rrow + RROWS * i;
+            if (rb < a.Mb) {
+                rv[i].template load<T>(a.V, ((size_t)n * a.Mb + rb) * a.HW + pix);
+                if (PROV == PRO_BNSWISH_GATE)
+                    rv[i].k2 = a.V.gate[(size_t)n * a.Mb + rb];
+            }
+        }
+    };
+    auto store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NRU; ++i) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j)
+                Us[buf][qcol * VEC + j][rrow + RROWS * i] = staged_valid ? ru[i].apply(j) : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < NRV; ++i) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j)
+                Vs[buf][qcol * VEC + j][rrow + RROWS * i] = staged_valid ? rv[i].apply(j) : 0.f;
+        }
+    };
+
+    float16v acc[WA][WB];
+#pragma unroll
+    for (int i = 0; i < WA; ++i)
+#pragma unroll
+        for (int j = 0; j < WB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0.f;
+
+    if (cbeg < cend) {
+        load(cbeg);
+        store(0);
+    }
+    __syncthreads();
+    for (int c = cbeg; c < cend; ++c) {
+        const int buf = NBUF == 2 ? (c - cbeg) & 1 : 0;
+        const bool more = c + 1 < cend;
+        if (more)
+            load(c + 1);
+#pragma unroll
+        for (int kk = 0; kk < BQ; kk += 2) {
+            float av[WA], bv[WB];
+#pragma unroll
+            for (int i = 0; i < WA; ++i)
+                av[i] = Us[buf][kk + (lane >> 5)][wa * 32 * WA + 32 * i + (lane & 31)];
+#pragma unroll
+            for (int j = 0; j < WB; ++j)
+                bv[j] = Vs[buf][kk + (lane >> 5)][wb * 32 * WB + 32 * j + (lane & 31)];
+#pragma unroll
+            for (int i = 0; i < WA; ++i)
+#pragma unroll
+                for (int j = 0; j < WB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        if (NBUF == 1)
+            __syncthreads();
+        if (more)
+            store(NBUF == 2 ? buf ^ 1 : 0);
+        __syncthreads();
+    }
+    float *dst = a.partial + (size_t)blockIdx.z * a.Ma * a.Mb;
+#pragma unroll
+    for (int i = 0; i < WA; ++i)
+#pragma unroll
+        for (int j = 0; j < WB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ai = a0 + wa * 32 * WA + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int bi = b0 + wb * 32 * WB + 32 * j + (lane & 31);
+                if (ai < a.Ma && bi < a.Mb)
+                    dst[(size_t)ai * a.Mb + bi] = acc[i][j][r];
+            }
+}
+
+// `wt` packs the tile factors as 4*WA + WB.
+bool big_wgrad_plan(int Ma, int Mb, int N, int HW, int *wt, int *splits)
+{
+    const long long Q = (long long)N * HW;
+    if (Q >= (1ll << 31))
+        return false;
+    // the scalar-load variant (HW not a multiple of 4) is built for 64x64 tiles only
+    const int wa = HW % 4 == 0 ? big_rows(Ma) : 1, wb = HW % 4 == 0 ? big_rows(Mb) : 1;
+    *wt = 4 * wa + wb;
+    const long long tiles = (long long)((Ma + 64 * wa - 1) / (64 * wa)) * ((Mb + 64 * wb - 1) / (64 * wb));
+    const long long chunks = (Q + 31) / 32;
+    long long s = (512 + tiles - 1) / tiles;
+    const long long smax = (chunks + 3) / 4; // at least four chunks per split
+    if (s > smax)
+        s = smax;
+    if (s < 1)
+        s = 1;
+    const long long per = (chunks + s - 1) / s;
+    *splits = (int)((chunks + per - 1) / per);
+    return true;
+}
+
+template <typename T, int WA, int WB, int VEC>
+static hipError_t big_wgrad_dispatch(const BigWgradArgs &a, int pu, int pv, dim3 grid, hipStream_t st)
+{
+#define MBK_CASE(PU, PV)                                                                          \
+    if (pu == PU && pv == PV) {                                                                   \
+        hipLaunchKernelGGL((wgrad_big_kernel<T, PU, PV, WA, WB, VEC>), grid, dim3(256), 0, st, a); \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(PRO_BNBWD, PRO_NONE)
+    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_big_wgrad(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
+                            const Operand &V, float *partial, int *splits_out, hipStream_t st)
+{
+    int wt, splits;
+    if (!big_wgrad_plan(Ma, Mb, N, HW, &wt, &splits))
+        return hipErrorInvalidValue;
+    const int wa = wt >> 2, wb = wt & 3;
+    BigWgradArgs a;
+    a.Ma = Ma;
+    a.Mb = Mb;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    const int chunks = (int)((a.Q + 31u) / 32u);
+    a.chunksPerSplit = (chunks + splits - 1) / splits;
+    a.divHW = make_div((uint32_t)HW);
+    a.U = to_big(U);
+    a.V = to_big(V);
+    a.partial = partial;
+    *splits_out = splits;
+    dim3 grid((unsigned)((Ma + 64 * wa - 1) / (64 * wa)), (unsigned)((Mb + 64 * wb - 1) / (64 * wb)),
+              (unsigned)splits);
+    const bool v4 = HW % 4 == 0;
+#define MBK_GO(TT)                                                                                \
+    (!v4 ? big_wgrad_dispatch<TT, 1, 1, 1>(a, U.pro, V.pro, grid, st)                             \
+         : wa == 2 ? (wb == 2 ? big_wgrad_dispatch<TT, 2, 2, 4>(a, U.pro, V.pro, grid, st)        \
+                              : big_wgrad_dispatch<TT, 2, 1, 4>(a, U.pro, V.pro, grid, st))       \
+                   : (wb == 2 ? big_wgrad_dispatch<TT, 1, 2, 4>(a, U.pro, V.pro, grid, st)        \
+                              : big_wgrad_dispatch<TT, 1, 1, 4>(a, U.pro, V.pro, grid, st)))
+    return bf16 ? MBK_GO(bf16_t) : MBK_GO(float);
+#undef MBK_GO
+}
+
+} // namespace mbk

@@ -203,11 +203,23 @@ bool wgrad_cl_plan(int Ma, int Mb, int N, int HW, bool *swap, int *splits);
 hipError_t launch_wgrad_cl(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
                            const Operand &V, float *partial, int *splits_out, hipStream_t st);
 
+// kernels_big.hip
+bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles);
+hipError_t launch_big_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm,
+                              int sAk, const Operand &B, void *out, int epi, const void *res,
+                              float *psum, float *psq, hipStream_t st);
+bool big_wgrad_plan(int Ma, int Mb, int N, int HW, int *wt, int *splits);
+hipError_t launch_big_wgrad(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
+                            const Operand &V, float *partial, int *splits_out, hipStream_t st);
+
 int conv1x1_num_partials(int N, int M, int K, int HW, bool stores_operand)
 {
     const int kind = stores_operand ? 0 : wave_conv_kind(M, K, HW);
     if (kind)
         return wave_conv_num_partials(kind, N, HW);
+    int wt, qtiles;
+    if (!stores_operand && big_conv_plan(N, M, K, HW, &wt, &qtiles))
+        return qtiles;
     return conv1x1_num_qtiles(N, HW);
 }
 
@@ -219,6 +231,12 @@ hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w,
     if (kind)
         return launch_wave_conv1x1(bf16, kind, N, M, K, HW, w, sAm, sAk, B, out, epi, res, psum,
                                    psq, st);
+    {
+        int wt, qtiles;
+        if (!sc_store && (sAm == 1 || sAk == 1) && big_conv_plan(N, M, K, HW, &wt, &qtiles))
+            return launch_big_conv1x1(bf16, N, M, K, HW, w, sAm, sAk, B, out, epi, res, psum, psq,
+                                      st);
+    }
     Conv1x1Args a;
     a.N = N;
     a.M = M;
@@ -326,6 +344,9 @@ int wgrad_splits(int Ma, int Mb, int N, int HW)
     int splits;
     if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits))
         return splits;
+    int wt;
+    if (big_wgrad_plan(Ma, Mb, N, HW, &wt, &splits))
+        return splits;
     const long long Q = (long long)N * HW;
     const long long chunk = wgrad_chunk(Ma, Mb, Q);
     return (int)((Q + chunk - 1) / chunk);
@@ -393,6 +414,13 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
         int splits;
         if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits)) {
             hipError_t e = launch_wgrad_cl(bf16, N, Ma, Mb, HW, U, V, partial, &splits, st);
+            if (e != hipSuccess)
+                return e;
+            return launch_reduce_splits(partial, splits, (size_t)Ma * Mb, dW, st);
+        }
+        int wt;
+        if (big_wgrad_plan(Ma, Mb, N, HW, &wt, &splits)) {
+            hipError_t e = launch_big_wgrad(bf16, N, Ma, Mb, HW, U, V, partial, &splits, st);
             if (e != hipSuccess)
                 return e;
             return launch_reduce_splits(partial, splits, (size_t)Ma * Mb, dW, st);
