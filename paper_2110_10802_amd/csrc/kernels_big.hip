@@ -104,6 +104,8 @@ struct BigConvArgs {
     const void *res;
     float *psum, *psq;
     int QT, MT; // tiles along q and m
+    float *partial;     // EPI_PARTIAL: [splits][M][Q]
+    int chunksPerSplit; // EPI_PARTIAL: chunks of 16 of the contraction per blockIdx.y
 };
 
 // out[n,m,pix] = sum_k A(m,k) * op(B)[n,k,pix].  Requirements (checked by the host):
@@ -219,15 +221,19 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
             for (int r = 0; r < 16; ++r)
                 acc[i][j][r] = 0.f;
 
-    const int nchunks = (a.K + BK - 1) / BK;
-    load_a(0);
-    load_b(0);
+    int cbeg = 0, cend = (a.K + BK - 1) / BK;
+    if (EPI == EPI_PARTIAL) {
+        cbeg = blockIdx.y * a.chunksPerSplit;
+        cend = min(cbeg + a.chunksPerSplit, cend);
+    }
+    load_a(cbeg * BK);
+    load_b(cbeg * BK);
     store_a(0);
     store_b(0);
     __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        const bool more = c + 1 < nchunks;
+    for (int c = cbeg; c < cend; ++c) {
+        const int buf = (c - cbeg) & 1;
+        const bool more = c + 1 < cend;
         if (more) {
             load_a((c + 1) * BK);
             load_b((c + 1) * BK);
@@ -277,7 +283,10 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int m = m0 + wm * 32 * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (valid && m < a.M) {
+                if (EPI == EPI_PARTIAL) {
+                    if (valid && m < a.M)
+                        a.partial[((size_t)blockIdx.y * a.M + m) * a.Q + q] = acc[i][j][r];
+                } else if (valid && m < a.M) {
                     float v = acc[i][j][r];
                     const size_t idx = ((size_t)n * a.M + m) * a.HW + pix;
                     if (EPI == EPI_RES)
@@ -314,6 +323,51 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
     }
 }
 
+// Second stage of a split convolution: adds the partial tiles in a fixed order and applies the
+// epilogue.  A workgroup owns 1024 consecutive q of one output channel.
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restrict__ partial, int S,
+                                                            int M, uint32_t Q, FastDiv divHW, int HW,
+                                                            T *out, const T *res, float *psum,
+                                                            float *psq, int NT)
+{
+    __shared__ float red[2][4];
+    const int m = blockIdx.y, tid = threadIdx.x;
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t q = blockIdx.x * 1024u + 256u * i + tid;
+        if (q < Q) {
+            float v = 0.f;
+            for (int s = 0; s < S; ++s)
+                v += partial[((size_t)s * M + m) * Q + q];
+            const uint32_t n = fdiv(q, divHW), pix = q - n * (uint32_t)HW;
+            const size_t idx = ((size_t)n * M + m) * HW + pix;
+            if (EPI == EPI_RES)
+                v += ld<T>(res, idx);
+            st<T>(out, idx, v);
+            if (EPI == EPI_STATS) {
+                const float sv = as_stored<T>(v);
+                s1 += sv;
+                s2 = fmaf(sv, sv, s2);
+            }
+        }
+    }
+    if (EPI == EPI_STATS) {
+        s1 = wave_sum(s1);
+        s2 = wave_sum(s2);
+        if ((tid & 63) == 0) {
+            red[0][tid >> 6] = s1;
+            red[1][tid >> 6] = s2;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            psum[(size_t)m * NT + blockIdx.x] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+            psq[(size_t)m * NT + blockIdx.x] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+        }
+    }
+}
+
 static BigOperand to_big(const Operand &o)
 {
     BigOperand d;
@@ -330,8 +384,11 @@ static BigOperand to_big(const Operand &o)
 static int big_rows(int M) { return ((M + 127) / 128) * 128 == ((M + 63) / 64) * 64 ? 2 : 1; }
 
 // Tile choice: 128 pixel columns when that still gives every CU work, else 64.  `wt` packs
-// the row and column factors as 4*WM + WP.
-bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles)
+// the row and column factors as 4*WM + WP.  When even the 64-column tiles are too few to fill
+// the chip and the contraction is long, it is split `splits` ways (each at least four chunks of
+// 16) and a second kernel adds the partial tiles; `qtiles` is then that kernel's count of
+// 1024-pixel groups.
+bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles, int *splits)
 {
     const long long Q = (long long)N * HW;
     if (K % 4 != 0 || M % 4 != 0 || Q >= (1ll << 31) || K < 16)
@@ -341,6 +398,20 @@ bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles)
     const int wp = (t128 >= 384 && HW % 4 == 0) ? 2 : 1;
     *wt = 4 * wm + wp;
     *qtiles = (int)((Q + 64 * wp - 1) / (64 * wp));
+    *splits = 1;
+    const long long tiles = (long long)*qtiles * ((M + 64 * wm - 1) / (64 * wm));
+    const int chunks = (K + 15) / 16;
+    if (wp == 1 && tiles < 384 && chunks >= 16) {
+        long long s = (768 + tiles - 1) / tiles;
+        if (s > chunks / 4)
+            s = chunks / 4;
+        if (s > 16)
+            s = 16;
+        const int per = (int)((chunks + s - 1) / s);
+        *splits = (chunks + per - 1) / per;
+        if (*splits > 1)
+            *qtiles = (int)((Q + 1023) / 1024);
+    }
     return true;
 }
 
@@ -356,16 +427,51 @@ static hipError_t big_conv_dispatch(const BigConvArgs &a, int pro, int epi, dim3
     MBK_CASE(PRO_BNSWISH_GATE, EPI_STATS)
     MBK_CASE(PRO_BNBWD, EPI_NONE)
     MBK_CASE(PRO_BNBWD, EPI_RES)
+    if constexpr (WP == 1) {
+        MBK_CASE(PRO_NONE, EPI_PARTIAL)
+        MBK_CASE(PRO_BNSWISH_GATE, EPI_PARTIAL)
+        MBK_CASE(PRO_BNBWD, EPI_PARTIAL)
+    }
 #undef MBK_CASE
     return hipErrorInvalidValue;
 }
 
+template <typename T>
+static hipError_t splitk_finish(const float *partial, int S, int M, uint32_t Q, int HW, void *out,
+                                const void *res, int epi, float *psum, float *psq, int NT,
+                                hipStream_t st)
+{
+    dim3 grid((unsigned)NT, (unsigned)M);
+    const FastDiv dv = make_div((uint32_t)HW);
+#define MBK_CASE(E)                                                                               \
+    if (epi == E) {                                                                               \
+        hipLaunchKernelGGL((splitk_finish_kernel<T, E>), grid, dim3(256), 0, st, partial, S, M, Q, \
+                           dv, HW, (T *)out, (const T *)res, psum, psq, NT);                      \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(EPI_NONE)
+    MBK_CASE(EPI_STATS)
+    MBK_CASE(EPI_RES)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+size_t big_conv_splitk_floats(int N, int M, int K, int HW)
+{
+    int wt, qtiles, splits;
+    if (!big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits) || splits == 1)
+        return 0;
+    return (size_t)splits * M * N * HW;
+}
+
 hipError_t launch_big_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm,
                               int sAk, const Operand &B, void *out, int epi, const void *res,
-                              float *psum, float *psq, hipStream_t st)
+                              float *psum, float *psq, float *splitk_ws, hipStream_t st)
 {
-    int wt, qtiles;
-    if (!big_conv_plan(N, M, K, HW, &wt, &qtiles) || (sAm != 1 && sAk != 1))
+    int wt, qtiles, splits;
+    if (!big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits) || (sAm != 1 && sAk != 1))
+        return hipErrorInvalidValue;
+    if (splits > 1 && !splitk_ws)
         return hipErrorInvalidValue;
     BigConvArgs a;
     a.M = M;
@@ -382,12 +488,18 @@ hipError_t launch_big_conv1x1(bool bf16, int N, int M, int K, int HW, const void
     a.psum = psum;
     a.psq = psq;
     const int wm = wt >> 2, wp = wt & 3;
-    a.QT = qtiles;
+    a.QT = (int)((a.Q + 64u * wp - 1) / (64u * wp));
     a.MT = (M + 64 * wm - 1) / (64 * wm);
-    dim3 grid((unsigned)(((qtiles + 7) / 8) * 8 * a.MT));
+    a.partial = splitk_ws;
+    const int chunks = (K + 15) / 16;
+    a.chunksPerSplit = (chunks + splits - 1) / splits;
+    dim3 grid((unsigned)(((a.QT + 7) / 8) * 8 * a.MT), (unsigned)splits);
     const bool v4 = HW % 4 == 0;
     if (!v4 && wp != 1)
         return hipErrorInvalidValue;
+    const int user_epi = epi;
+    if (splits > 1)
+        epi = EPI_PARTIAL;
 #define MBK_GO(TT)                                                                                \
     (!v4 ? (wm == 2 ? big_conv_dispatch<TT, 2, 1, 1>(a, B.pro, epi, grid, st)                     \
                     : big_conv_dispatch<TT, 1, 1, 1>(a, B.pro, epi, grid, st))                    \
@@ -395,8 +507,14 @@ hipError_t launch_big_conv1x1(bool bf16, int N, int M, int K, int HW, const void
                               : big_conv_dispatch<TT, 2, 1, 4>(a, B.pro, epi, grid, st))          \
                    : (wp == 2 ? big_conv_dispatch<TT, 1, 2, 4>(a, B.pro, epi, grid, st)           \
                               : big_conv_dispatch<TT, 1, 1, 4>(a, B.pro, epi, grid, st)))
-    return bf16 ? MBK_GO(bf16_t) : MBK_GO(float);
+    const hipError_t e = bf16 ? MBK_GO(bf16_t) : MBK_GO(float);
 #undef MBK_GO
+    if (e != hipSuccess || splits == 1)
+        return e;
+    return bf16 ? splitk_finish<bf16_t>(splitk_ws, splits, M, a.Q, HW, out, res, user_epi, psum,
+                                        psq, qtiles, st)
+                : splitk_finish<float>(splitk_ws, splits, M, a.Q, HW, out, res, user_epi, psum, psq,
+                                       qtiles, st);
 }
 
 // ---- weight gradient -------------------------------------------------------------------

@@ -204,10 +204,11 @@ hipError_t launch_wgrad_cl(bool bf16, int N, int Ma, int Mb, int HW, const Opera
                            const Operand &V, float *partial, int *splits_out, hipStream_t st);
 
 // kernels_big.hip
-bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles);
+bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles, int *splits);
+size_t big_conv_splitk_floats(int N, int M, int K, int HW);
 hipError_t launch_big_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm,
                               int sAk, const Operand &B, void *out, int epi, const void *res,
-                              float *psum, float *psq, hipStream_t st);
+                              float *psum, float *psq, float *splitk_ws, hipStream_t st);
 bool big_wgrad_plan(int Ma, int Mb, int N, int HW, int *wt, int *splits);
 hipError_t launch_big_wgrad(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
                             const Operand &V, float *partial, int *splits_out, hipStream_t st);
@@ -217,25 +218,33 @@ int conv1x1_num_partials(int N, int M, int K, int HW, bool stores_operand)
     const int kind = stores_operand ? 0 : wave_conv_kind(M, K, HW);
     if (kind)
         return wave_conv_num_partials(kind, N, HW);
-    int wt, qtiles;
-    if (!stores_operand && big_conv_plan(N, M, K, HW, &wt, &qtiles))
+    int wt, qtiles, splits;
+    if (!stores_operand && big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits))
         return qtiles;
     return conv1x1_num_qtiles(N, HW);
 }
 
+size_t conv1x1_splitk_floats(int N, int M, int K, int HW, bool stores_operand)
+{
+    if (stores_operand || wave_conv_kind(M, K, HW))
+        return 0;
+    return big_conv_splitk_floats(N, M, K, HW);
+}
+
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
-                          float *psq, void *sc_store, hipStream_t st)
+                          float *psq, void *sc_store, float *splitk_ws, hipStream_t st)
 {
     const int kind = sc_store ? 0 : wave_conv_kind(M, K, HW);
     if (kind)
         return launch_wave_conv1x1(bf16, kind, N, M, K, HW, w, sAm, sAk, B, out, epi, res, psum,
                                    psq, st);
     {
-        int wt, qtiles;
-        if (!sc_store && (sAm == 1 || sAk == 1) && big_conv_plan(N, M, K, HW, &wt, &qtiles))
+        int wt, qtiles, splits;
+        if (!sc_store && (sAm == 1 || sAk == 1) &&
+            big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits))
             return launch_big_conv1x1(bf16, N, M, K, HW, w, sAm, sAk, B, out, epi, res, psum, psq,
-                                      st);
+                                      splitk_ws, st);
     }
     Conv1x1Args a;
     a.N = N;

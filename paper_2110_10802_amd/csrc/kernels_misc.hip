@@ -151,9 +151,112 @@ __global__ __launch_bounds__(256) void se_fwd_kernel(int C, int Cse, const float
     }
 }
 
+// The same for wide blocks (hundreds of channels): a workgroup per (image, channel slice).
+// Every workgroup of an image recomputes the whole of q (Cse dot products of length C: cheap,
+// and it keeps the kernel free of a grid-wide dependency), then produces g for its slice.
+// A dependent global load costs about a microsecond here, so every phase issues all of its
+// loads before it consumes any: loops are unrolled over compile-time bounds (CI*256 >= C,
+// Cse <= 64) with guards.  Requires Cse % 4 == 0.
+template <int CI>
+__global__ __launch_bounds__(256) void se_fwd_wide_kernel(int C, int Cse, int slice,
+                                                          const float *__restrict__ z,
+                                                          const float *__restrict__ w1,
+                                                          const float *__restrict__ b1,
+                                                          const float *__restrict__ w2,
+                                                          const float *__restrict__ b2, float *q,
+                                                          float *g)
+{
+    __shared__ float part[4][64];
+    __shared__ float rs[64];
+    const int n = blockIdx.x, sl = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float zv[CI];
+#pragma unroll
+    for (int i = 0; i < CI; ++i) {
+        const int c = tid + 256 * i;
+        zv[i] = c < C ? z[(size_t)n * C + c] : 0.f;
+    }
+    for (int jb = 0; jb < Cse; jb += 16) {
+        float wv[16][CI];
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+#pragma unroll
+            for (int i = 0; i < CI; ++i) {
+                const int c = tid + 256 * i;
+                wv[u][i] = (jb + u < Cse && c < C) ? w1[(size_t)(jb + u) * C + c] : 0.f;
+            }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            float acc = 0.f;
+#pragma unroll
+            for (int i = 0; i < CI; ++i)
+                acc = fmaf(wv[u][i], zv[i], acc);
+            acc = wave_sum(acc);
+            if (lane == 0)
+                part[wave][jb + u] = acc;
+        }
+    }
+    __syncthreads();
+    if (tid < Cse) {
+        const float qv = (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]) + b1[tid];
+        if (sl == 0)
+            q[(size_t)n * Cse + tid] = qv;
+        rs[tid] = swishf(qv);
+    }
+    __syncthreads();
+    const int cend = min(C, (sl + 1) * slice);
+    for (int c = sl * slice + tid; c < cend; c += 256) {
+        const float4 *row = reinterpret_cast<const float4 *>(w2 + (size_t)c * Cse);
+        float4 w[16];
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj)
+            w[jj] = 4 * jj < Cse ? row[jj] : make_float4(0.f, 0.f, 0.f, 0.f);
+        float acc = b2[c];
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            if (4 * jj < Cse) {
+                acc = fmaf(w[jj].x, rs[4 * jj], acc);
+                acc = fmaf(w[jj].y, rs[4 * jj + 1], acc);
+                acc = fmaf(w[jj].z, rs[4 * jj + 2], acc);
+                acc = fmaf(w[jj].w, rs[4 * jj + 3], acc);
+            }
+        }
+        g[(size_t)n * C + c] = sigmoidf_fast(acc);
+    }
+}
+
+// channel slices per image so that a wide block launches a few hundred workgroups
+static int se_slices(int N, int C)
+{
+    int G = (512 + N - 1) / N;
+    const int maxG = (C + 63) / 64;
+    if (G > maxG)
+        G = maxG;
+    if (G > 8)
+        G = 8;
+    return G < 1 ? 1 : G;
+}
+static bool se_wide(int C, int Cse)
+{
+    return C >= 256 && C <= 2048 && C % 4 == 0 && Cse % 4 == 0 && Cse <= 64;
+}
+
 hipError_t launch_se_fwd(int N, int C, int Cse, const float *z, const float *w1, const float *b1,
                          const float *w2, const float *b2, float *q, float *g, hipStream_t st)
 {
+    if (se_wide(C, Cse)) {
+        const int G = se_slices(N, C), slice = (C + G - 1) / G;
+        if (C <= 768)
+            hipLaunchKernelGGL(se_fwd_wide_kernel<3>, dim3(N, G), dim3(256), 0, st, C, Cse, slice, z,
+                               w1, b1, w2, b2, q, g);
+        else if (C <= 1280)
+            hipLaunchKernelGGL(se_fwd_wide_kernel<5>, dim3(N, G), dim3(256), 0, st, C, Cse, slice, z,
+                               w1, b1, w2, b2, q, g);
+        else
+            hipLaunchKernelGGL(se_fwd_wide_kernel<8>, dim3(N, G), dim3(256), 0, st, C, Cse, slice, z,
+                               w1, b1, w2, b2, q, g);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(se_fwd_kernel, dim3(N), dim3(256), sizeof(float) * (C + Cse), st, C, Cse, z,
                        w1, b1, w2, b2, q, g);
     return hipGetLastError();
@@ -271,8 +374,202 @@ __global__ __launch_bounds__(256) void se_bwd_batch_kernel(SeBwdArgs a)
     }
 }
 
+// Wide-block variants of the two SE backward kernels (Cse % 4 == 0, Cse <= 64).
+// Per (image, channel slice): dt for every channel, dq by a [C x Cse] sweep of W2 with float4
+// loads (a thread owns four consecutive j of every RP-th row; row groups are combined in LDS in
+// a fixed order), then dzs for the slice.
+__global__ __launch_bounds__(256) void se_bwd_image_wide_kernel(SeBwdArgs a, int slice)
+{
+    extern __shared__ float lds[];
+    const int C = a.C, Cse = a.Cse;
+    float *dts = lds, *dqs = lds + C, *red = dqs + Cse; // red: [RP][Cse]
+    const int n = blockIdx.x, part = blockIdx.y, tid = threadIdx.x;
+    for (int c = tid; c < C; c += 256) {
+        const float gv = a.g[(size_t)n * C + c];
+        const float v = a.dg[(size_t)n * C + c] * gv * (1.f - gv);
+        dts[c] = v;
+        if (part == 0)
+            a.dt[(size_t)n * C + c] = v;
+    }
+    __syncthreads();
+    const int JQ = Cse >> 2, RP = 256 / JQ;
+    const int jq = tid % JQ, r0 = tid / JQ;
+    if (r0 < RP) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int cb = r0; cb < C; cb += 16 * RP) { // 16 independent loads per round
+            float4 w[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int c = cb + u * RP;
+                w[u] = c < C ? *reinterpret_cast<const float4 *>(a.w2 + (size_t)c * Cse + 4 * jq)
+                             : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int c = cb + u * RP;
+                const float d = c < C ? dts[c] : 0.f;
+                acc.x = fmaf(w[u].x, d, acc.x);
+                acc.y = fmaf(w[u].y, d, acc.y);
+                acc.z = fmaf(w[u].z, d, acc.z);
+                acc.w = fmaf(w[u].w, d, acc.w);
+            }
+        }
+        *reinterpret_cast<float4 *>(red + (size_t)r0 * Cse + 4 * jq) = acc;
+    }
+    __syncthreads();
+    if (tid < Cse) {
+        float s = 0.f;
+        for (int r = 0; r < RP; ++r)
+            s += red[(size_t)r * Cse + tid];
+        float val, grad;
+        swish_both(a.q[(size_t)n * Cse + tid], val, grad);
+        const float v = s * grad;
+        dqs[tid] = v;
+        if (part == 0)
+            a.dq[(size_t)n * Cse + tid] = v;
+    }
+    __syncthreads();
+    const float inv = 1.f / (float)a.HW;
+    const int cend = min(C, (part + 1) * slice);
+    for (int c = part * slice + tid; c < cend; c += 256) {
+        float w[64];
+#pragma unroll
+        for (int j = 0; j < 64; ++j)
+            w[j] = j < Cse ? a.w1[(size_t)j * C + c] : 0.f;
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < 64; ++j)
+            if (j < Cse)
+                acc = fmaf(w[j], dqs[j], acc);
+        a.dzs[(size_t)n * C + c] = acc * inv;
+    }
+}
+
+// Sums over the batch for a tile of 32 channels: thread (c, jg) owns dW2[c][j] and dW1[j][c]
+// for j = jg, jg+8, ...; the batch is walked 32 images at a time through LDS, always in the
+// same order.  The first 32 threads also produce db2 and BN2's dbeta/dgamma/coef for their
+// channel; workgroup 0 adds db1.
+__global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
+{
+    constexpr int TC = 32, TN = 32, JMAX = 8; // Cse <= 8*JMAX
+    __shared__ float dtL[TN][TC], zL[TN][TC], rL[TN][64], dqL[TN][64];
+    const int C = a.C, Cse = a.Cse, N = a.N;
+    const int tid = threadIdx.x, cl = tid & 31, jg = tid >> 5;
+    const int c0 = blockIdx.x * TC, c = c0 + cl;
+    float acc2[JMAX], acc1[JMAX];
+#pragma unroll
+    for (int u = 0; u < JMAX; ++u)
+        acc2[u] = acc1[u] = 0.f;
+    for (int n0 = 0; n0 < N; n0 += TN) {
+        __syncthreads();
+        float t0[4], t1[4], t2[8], t3[8]; // all loads of the round in flight together
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = tid + 256 * u, nn = i >> 5, cc = i & 31;
+            const bool ok = n0 + nn < N && c0 + cc < C;
+            t0[u] = ok ? a.dt[(size_t)(n0 + nn) * C + c0 + cc] : 0.f;
+            t1[u] = ok ? a.z[(size_t)(n0 + nn) * C + c0 + cc] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = tid + 256 * u, nn = i >> 6, j = i & 63;
+            const bool ok = n0 + nn < N && j < Cse;
+            t2[u] = ok ? a.q[(size_t)(n0 + nn) * Cse + j] : 0.f;
+            t3[u] = ok ? a.dq[(size_t)(n0 + nn) * Cse + j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = tid + 256 * u;
+            dtL[i >> 5][i & 31] = t0[u];
+            zL[i >> 5][i & 31] = t1[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = tid + 256 * u;
+            rL[i >> 6][i & 63] = swishf(t2[u]);
+            dqL[i >> 6][i & 63] = t3[u];
+        }
+        __syncthreads();
+        for (int nn = 0; nn < TN; ++nn) {
+            const float dtv = dtL[nn][cl], zv = zL[nn][cl];
+#pragma unroll
+            for (int u = 0; u < JMAX; ++u) {
+                const int j = jg + 8 * u;
+                if (j < Cse) {
+                    acc2[u] = fmaf(dtv, rL[nn][j], acc2[u]);
+                    acc1[u] = fmaf(dqL[nn][j], zv, acc1[u]);
+                }
+            }
+        }
+    }
+    if (c < C) {
+#pragma unroll
+        for (int u = 0; u < JMAX; ++u) {
+            const int j = jg + 8 * u;
+            if (j < Cse) {
+                a.dw2[(size_t)c * Cse + j] = acc2[u];
+                a.dw1[(size_t)j * C + c] = acc1[u];
+            }
+        }
+    }
+    // per-channel sums: the eight thread groups take every eighth image, then group 0 adds
+    // the eight partial sums in order
+    {
+        __shared__ float sbL[8][TC];
+        __shared__ double dbL[8][TC], dgL[8][TC];
+        float sb = 0.f;
+        double dbeta = 0.0, dgamma = 0.0;
+        if (c < C) {
+#pragma unroll 4
+            for (int n = jg; n < N; n += 8) {
+                const size_t o = (size_t)n * C + c;
+                const float dtv = a.dt[o], gv = a.g[o], a1 = a.A1[o], a2 = a.A2[o];
+                const float dz = a.dzs[o], s3 = a.s3[o], s4 = a.s4[o];
+                sb += dtv;
+                dbeta += (double)gv * a1 + (double)dz * s3;
+                dgamma += (double)gv * a2 + (double)dz * s4;
+            }
+        }
+        sbL[jg][cl] = sb;
+        dbL[jg][cl] = dbeta;
+        dgL[jg][cl] = dgamma;
+        __syncthreads();
+        if (jg == 0 && c < C) {
+            sb = 0.f;
+            dbeta = dgamma = 0.0;
+            for (int u = 0; u < 8; ++u) {
+                sb += sbL[u][cl];
+                dbeta += dbL[u][cl];
+                dgamma += dgL[u][cl];
+            }
+            a.db2[c] = sb;
+            a.dbeta2[c] = (float)dbeta;
+            a.dgamma2[c] = (float)dgamma;
+            bn_bwd_coef(C, c, (double)N * a.HW, dgamma, dbeta, a.gamma2[c], a.bn2, a.coef2);
+        }
+    }
+    if (blockIdx.x == 0 && tid >= 64 && tid - 64 < Cse) {
+        const int j = tid - 64;
+        float sb = 0.f;
+        for (int n = 0; n < N; ++n)
+            sb += a.dq[(size_t)n * Cse + j];
+        a.db1[j] = sb;
+    }
+}
+
 hipError_t launch_se_bwd(const SeBwdArgs &a, hipStream_t st)
 {
+    if (se_wide(a.C, a.Cse)) {
+        const int G = se_slices(a.N, a.C), slice = (a.C + G - 1) / G;
+        const int RP = 256 / (a.Cse / 4);
+        const size_t lds = sizeof(float) * ((size_t)a.C + a.Cse + (size_t)RP * a.Cse);
+        hipLaunchKernelGGL(se_bwd_image_wide_kernel, dim3(a.N, G), dim3(256), lds, st, a, slice);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL(se_bwd_batch_wide_kernel, dim3((a.C + 31) / 32), dim3(256), 0, st, a);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(se_bwd_image_kernel, dim3(a.N), dim3(256), sizeof(float) * (a.C + a.Cse), st,
                        a);
     hipError_t e = hipGetLastError();
@@ -283,26 +580,40 @@ hipError_t launch_se_bwd(const SeBwdArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-// out[c*inner+i] = sum_n in[(c*N+n)*inner+i]
+// out[c*inner+i] = sum_n in[(c*N+n)*inner+i].  Eight lanes share an output: lane s adds
+// the images s, s+8, ... and the eight partial sums are combined by a fixed butterfly.
 __global__ void reduce_planes_kernel(const float *__restrict__ in, int C, int N, int inner,
                                      float *__restrict__ out)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= C * inner)
-        return;
-    const int c = i / inner, t = i - c * inner;
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = gid >> 3, sub = gid & 7;
     float s = 0.f;
-    for (int n = 0; n < N; ++n)
-        s += in[((size_t)c * N + n) * inner + t];
-    out[i] = s;
+    if (i < C * inner) {
+        const int c = i / inner, t = i - c * inner;
+        const float *src = in + (size_t)c * N * inner + t;
+        float s0 = 0.f, s1 = 0.f;
+        int n = sub;
+        for (; n + 8 < N; n += 16) {
+            s0 += src[(size_t)n * inner];
+            s1 += src[(size_t)(n + 8) * inner];
+        }
+        if (n < N)
+            s0 += src[(size_t)n * inner];
+        s = s0 + s1;
+    }
+    s += __shfl_xor(s, 4, kWave);
+    s += __shfl_xor(s, 2, kWave);
+    s += __shfl_xor(s, 1, kWave);
+    if (sub == 0 && i < C * inner)
+        out[i] = s;
 }
 
 hipError_t launch_reduce_planes(const float *in, int C, int N, int inner, float *out,
                                 hipStream_t st)
 {
-    const int total = C * inner;
-    hipLaunchKernelGGL(reduce_planes_kernel, dim3((total + 255) / 256), dim3(256), 0, st, in, C, N,
-                       inner, out);
+    const long long total = (long long)C * inner * 8;
+    hipLaunchKernelGGL(reduce_planes_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       in, C, N, inner, out);
     return hipGetLastError();
 }
 

@@ -135,6 +135,13 @@ Plan make_plan(const mbconv_desc *d)
     size_t wg = (size_t)wgrad_splits(P.Cout, P.Cexp, P.N, P.HWo) * P.Cout * P.Cexp;
     if (P.expand)
         wg = std::max(wg, (size_t)wgrad_splits(P.Cexp, P.Cin, P.N, P.HW) * P.Cexp * P.Cin);
+    // the same region holds the partial tiles of a split 1x1 convolution
+    wg = std::max(wg, conv1x1_splitk_floats(P.N, P.Cout, P.Cexp, P.HWo, P.store));
+    wg = std::max(wg, conv1x1_splitk_floats(P.N, P.Cexp, P.Cout, P.HWo, false));
+    if (P.expand) {
+        wg = std::max(wg, conv1x1_splitk_floats(P.N, P.Cexp, P.Cin, P.HW, false));
+        wg = std::max(wg, conv1x1_splitk_floats(P.N, P.Cin, P.Cexp, P.HW, false));
+    }
     P.o_wg = take(wg * f);
     P.scratch_bytes = o;
     return P;
@@ -284,6 +291,7 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
     const bool bf = P.bf16;
     float *psum = at<float>(scratch, P.o_part);
     float *psq = psum + P.part_floats;
+    float *wg = at<float>(scratch, P.o_wg);
     float *bn2 = at<float>(saved, P.o_bn2), *bn3 = at<float>(saved, P.o_bn3);
     float *bn1 = P.expand ? at<float>(saved, P.o_bn1) : nullptr;
     void *d = at<char>(saved, P.o_d), *p = at<char>(saved, P.o_p);
@@ -297,7 +305,7 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
         B.p0 = x;
         B.pro = PRO_NONE;
         MBK_STEP(MBCONV_STEP_EXPAND_CONV, launch_conv1x1(bf, P.N, P.Cexp, P.Cin, P.HW, prm->w_expand, P.Cin, 1, B, e,
-                               EPI_STATS, nullptr, psum, psq, nullptr, st));
+                               EPI_STATS, nullptr, psum, psq, nullptr, wg, st));
         MBK_STEP(MBCONV_STEP_BN1_FINALIZE, launch_bn_finalize(P.Cexp, P.NT1, (double)P.N * P.HW, psum, psq, prm->bn1_gamma,
                                    prm->bn1_beta, eps, mom, run ? run->bn1_mean : nullptr,
                                    run ? run->bn1_var : nullptr, bn1, st));
@@ -326,7 +334,7 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
         B.pro = PRO_BNSWISH_GATE;
         void *sc_store = P.store ? at<char>(saved, P.o_sc) : nullptr;
         MBK_STEP(MBCONV_STEP_PROJ_CONV, launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p,
-                               EPI_STATS, nullptr, psum, psq, sc_store, st));
+                               EPI_STATS, nullptr, psum, psq, sc_store, wg, st));
         MBK_STEP(MBCONV_STEP_BN3_FINALIZE, launch_bn_finalize(P.Cout, P.NT5, (double)P.N * P.HWo, psum, psq, prm->bn3_gamma,
                                    prm->bn3_beta, eps, mom, run ? run->bn3_mean : nullptr,
                                    run ? run->bn3_var : nullptr, bn3, st));
@@ -397,7 +405,7 @@ mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_param
     dp.c2 = coef3 + 2 * P.Cout;
     dp.pro = PRO_BNBWD;
     MBK_STEP(MBCONV_STEP_PROJ_DGRAD, launch_conv1x1(bf, P.N, P.Cexp, P.Cout, P.HWo, prm->w_proj, 1, P.Cexp, dp, G, EPI_NONE,
-                           nullptr, nullptr, nullptr, nullptr, st));
+                           nullptr, nullptr, nullptr, nullptr, wg, st));
     {
         Operand sc;
         if (P.store) {
@@ -484,7 +492,7 @@ mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_param
         // dx = W_e^T de (+ dout), dW_e = de * x^T
         MBK_STEP(MBCONV_STEP_EXPAND_DGRAD, launch_conv1x1(bf, P.N, P.Cin, P.Cexp, P.HW, prm->w_expand, 1, P.Cin, de, dx,
                                P.res ? EPI_RES : EPI_NONE, P.res ? dout : nullptr, nullptr, nullptr,
-                               nullptr, st));
+                               nullptr, wg, st));
         Operand xo;
         xo.p0 = x;
         xo.pro = PRO_NONE;

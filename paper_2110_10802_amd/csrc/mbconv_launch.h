@@ -13,6 +13,7 @@ namespace mbk {
 //   PRO_BNBWD        c0[c]*p0 + c1[c]*p1 + c2[c]             (BN backward: p0 = dy, p1 = raw input)
 enum { PRO_NONE = 0, PRO_BNSWISH_GATE = 1, PRO_BNBWD = 2 };
 enum { EPI_NONE = 0, EPI_STATS = 1, EPI_RES = 2 };
+constexpr int EPI_PARTIAL = 3; // internal: raw partial sums of a split contraction
 
 struct Operand {
     const void *p0 = nullptr;
@@ -30,10 +31,13 @@ inline int conv1x1_num_qtiles(int N, int HW) { return (int)(((long long)N * HW +
 // epi: EPI_STATS writes partial sums of out and out^2 to psum/psq laid out
 // [M][conv1x1_num_partials(...)]; EPI_RES adds res[n,m,q] before the store.
 // sc_store (optional) receives the operand after its prologue (STORE policy).
+// Long contractions with few output tiles are split over workgroups; `splitk_ws` then needs
+// conv1x1_splitk_floats(...) floats (0 when the launch does not split).
 int conv1x1_num_partials(int N, int M, int K, int HW, bool stores_operand);
+size_t conv1x1_splitk_floats(int N, int M, int K, int HW, bool stores_operand);
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
-                          float *psq, void *sc_store, hipStream_t st);
+                          float *psq, void *sc_store, float *splitk_ws, hipStream_t st);
 
 // Weight gradient of a 1x1 conv: dW[a,b] = sum_{n,q} op(U)[n,a,q] * op(V)[n,b,q].
 // `partial` needs wgrad_splits(...)*Ma*Mb floats.
