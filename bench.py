@@ -141,6 +141,8 @@ def run_chain(args) -> int:
     e0, e1 = ev.create(), ev.create()
     survey = []
     for i, c in enumerate(ctx):
+        if args.no_survey:
+            break
         row = {}
         for name, sid in B.STEPS.items():
             if not shapes[i].has_expand and name in NO_EXPAND_STEPS:
@@ -160,8 +162,8 @@ def run_chain(args) -> int:
     ev.destroy(e1)
     cand = [(i, n) for i, row in enumerate(survey) for n in row
             if algorithmic_bytes(shapes[i], n) is not None]
-    if args.probe_step:
-        bi, dominant = args.probe_step.split(":")
+    if args.probe_step or args.no_survey:
+        bi, dominant = (args.probe_step or "2:dw_bwd").split(":")
         bi = int(bi) - 1
     else:
         bi, dominant = max(cand, key=lambda c: survey[c[0]][c[1]])
@@ -204,6 +206,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe-step", default=None,
                     help="time this step for the roofline instead of the slowest one")
+    ap.add_argument("--no-survey", action="store_true",
+                    help="config 4 only: skip the per-block survey (the roofline kernel is then "
+                         "--probe-step BLOCK:STEP, default 2:dw_bwd)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling rocprofv3 "
                          "FETCH_SIZE/WRITE_SIZE readings)")

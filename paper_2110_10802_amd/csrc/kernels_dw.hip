@@ -25,6 +25,19 @@ bool dw4_supported(const DwShape &s);
 hipError_t launch_dw4_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
                           const void *w_dw, void *d, float *psum, float *psq, hipStream_t st);
 hipError_t launch_dw4_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st);
+// kernels_dwr.hip
+bool dwr_supported(const DwShape &s);
+int dwr_num_partials(const DwShape &s);
+hipError_t launch_dwr_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
+                          const void *w_dw, void *d, float *psum, float *psq, hipStream_t st);
+hipError_t launch_dwr_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st);
+
+int dw_num_partials(const DwShape &s, bool stores_a1)
+{
+    if (!stores_a1 && !dw4_supported(s) && dwr_supported(s))
+        return dwr_num_partials(s);
+    return s.N;
+}
 
 // Threads per plane: a wavefront for planes up to 16x16, a 256-thread workgroup up to
 // 64x64, 1024 threads above.
@@ -188,6 +201,8 @@ hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float
 {
     if (!a1_store && dw4_supported(s))
         return launch_dw4_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
+    if (!a1_store && dwr_supported(s))
+        return launch_dwr_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
     DwFwdDev a;
     a.s = s;
     a.divC = make_div((uint32_t)s.C);
@@ -434,6 +449,8 @@ hipError_t launch_dw_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st)
 {
     if (!h.a1_saved && dw4_supported(h.s))
         return launch_dw4_bwd(bf16, h, st);
+    if (!h.a1_saved && dwr_supported(h.s))
+        return launch_dwr_bwd(bf16, h, st);
     DwBwdDev a;
     a.s = h.s;
     const int p = h.s.p;

@@ -29,6 +29,7 @@ struct Plan {
     size_t o_G, o_dy1, o_coef3, o_coef2, o_coef1, o_dg, o_A1, o_A2, o_dt, o_dq, o_dzs, o_pdw, o_wg;
     size_t scratch_bytes;
     int NT1, NT5; // q-tiles of the expansion / projection conv
+    int NPdw;     // partial results per channel of the depthwise kernels
 };
 
 mbconv_status check_desc(const mbconv_desc *d)
@@ -87,6 +88,10 @@ Plan make_plan(const mbconv_desc *d)
     P.nE = (size_t)P.N * P.Cexp * P.HW;
     P.nD = (size_t)P.N * P.Cexp * P.HWo;
     P.nP = (size_t)P.N * P.Cout * P.HWo;
+    {
+        const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
+        P.NPdw = dw_num_partials(ds, P.store && P.expand);
+    }
     P.NT1 = conv1x1_num_partials(P.N, P.Cexp, P.Cin, P.HW, false);
     P.NT5 = conv1x1_num_partials(P.N, P.Cout, P.Cexp, P.HWo, d->policy == MBCONV_STORE);
 
@@ -315,7 +320,7 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
     const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
     void *a1_store = (P.store && P.expand) ? at<char>(saved, P.o_a1) : nullptr;
     MBK_STEP(MBCONV_STEP_DW_FWD, launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum, psq, a1_store, st));
-    MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.N, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
+    MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.NPdw, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
                                prm->bn2_beta, eps, mom, run ? run->bn2_mean : nullptr,
                                run ? run->bn2_var : nullptr, bn2, st));
     // BN2 + Swish + SE squeeze, SE excite
@@ -474,13 +479,13 @@ mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_param
         a.psb = pa;
         a.psr = pb;
         MBK_STEP(MBCONV_STEP_DW_BWD, launch_dw_bwd(bf, a, st));
-        MBK_STEP(MBCONV_STEP_DW_WGRAD_REDUCE, launch_reduce_planes(a.pdw, P.Cexp, P.N, P.k * P.k, gr->w_dw, st));
+        MBK_STEP(MBCONV_STEP_DW_WGRAD_REDUCE, launch_reduce_planes(a.pdw, P.Cexp, P.NPdw, P.k * P.k, gr->w_dw, st));
     }
     if (P.expand) {
         float *coef1 = at<float>(scratch, P.o_coef1);
         const void *e = at<char>(saved, P.o_e);
         const void *dy1 = at<char>(scratch, P.o_dy1);
-        MBK_STEP(MBCONV_STEP_BN1_BWD_FINALIZE, launch_bn_bwd_finalize(P.Cexp, P.N, (double)P.N * P.HW, pa, pb, prm->bn1_gamma, bn1,
+        MBK_STEP(MBCONV_STEP_BN1_BWD_FINALIZE, launch_bn_bwd_finalize(P.Cexp, P.NPdw, (double)P.N * P.HW, pa, pb, prm->bn1_gamma, bn1,
                                        gr->bn1_gamma, gr->bn1_beta, coef1, st));
         Operand de;
         de.p0 = dy1;

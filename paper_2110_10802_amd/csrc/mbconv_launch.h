@@ -63,6 +63,10 @@ hipError_t launch_bn_bwd_finalize(int C, int NP, double m, const float *psb, con
 struct DwShape {
     int N, C, H, W, Ho, Wo, k, s, p;
 };
+// Partial results per channel that launch_dw_fwd / launch_dw_bwd write (psum, psq, pdw, psb,
+// psr are laid out [C][dw_num_partials]): one per image, or one per image range for the
+// kernels that keep their accumulators across images.  `stores_a1`: the STORE policy is on.
+int dw_num_partials(const DwShape &s, bool stores_a1);
 size_t dw_fwd_lds_bytes(const DwShape &s);
 size_t dw_bwd_lds_bytes(const DwShape &s);
 
