@@ -105,17 +105,17 @@ struct BigConvArgs {
     float *psum, *psq;
     int QT, MT; // tiles along q and m
     float *partial;     // EPI_PARTIAL: [splits][M][Q]
-    int chunksPerSplit; // EPI_PARTIAL: chunks of 16 of the contraction per blockIdx.y
+    int chunksPerSplit; // EPI_PARTIAL: chunks of BK of the contraction per blockIdx.y
 };
 
 // out[n,m,pix] = sum_k A(m,k) * op(B)[n,k,pix].  Requirements (checked by the host):
 // K % 4 == 0, M % 4 == 0, HW % VEC == 0, one of sAm/sAk equal to 1.
-template <typename T, int PRO, int EPI, int WM, int WP, int VEC>
+template <typename T, int PRO, int EPI, int WM, int WP, int VEC, int D>
 __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
 {
-    constexpr int BM = 64 * WM, BP = 64 * WP, BK = 16;
+    constexpr int BM = 64 * WM, BP = 64 * WP, BK = 16, KP = 1;
     constexpr int PA = BM + 4; // pitch = 4 mod 8: the transposing stores of A are 2-way at worst
-    constexpr int NB = VEC == 4 ? WP : 4 * WP; // staged runs of B per thread
+    constexpr int NB = (VEC == 4 ? WP : 4 * WP) * KP; // staged runs of B per thread
     constexpr int BCOLS = BP / VEC;            // runs per row of the B tile
     constexpr int BROWS = 256 / BCOLS;         // rows staged per pass
     __shared__ __attribute__((aligned(16))) float As[2][BK][PA];
@@ -134,35 +134,39 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
     const bool kcontig = a.sAk == 1;
 
     // ---- A staging ----
-    float4 ra[WM];
-    auto load_a = [&](int k0) {
+    float4 ra[D - 1][WM * KP];
+    // All staging loads are unconditional (indices clamped into the tensor, results masked
+    // afterwards): straight-line code lets every load of a chunk be in flight at once, whereas
+    // a branch per run makes the compiler wait for the previous run's data first.
+    auto load_a = [&](int slot, int k0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < WM; ++i) {
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < WM * KP; ++i) {
+            float v[4];
+            bool ok;
             if (kcontig) {
-                const int m = m0 + (tid >> 2) + 64 * i, k = k0 + 4 * (tid & 3);
-                if (m < a.M && k < a.K)
-                    big_ld<T, 4>((const T *)a.w, (size_t)m * a.sAm + k, v);
+                const int m = m0 + (tid >> 2) + 64 * (i % WM), k = k0 + 16 * (i / WM) + 4 * (tid & 3);
+                ok = m < a.M && k < a.K;
+                big_ld<T, 4>((const T *)a.w, (size_t)min(m, a.M - 1) * a.sAm + min(k, a.K - 4), v);
             } else {
                 const int m = m0 + 4 * (tid % (BM / 4)), k = k0 + tid / (BM / 4) + (1024 / BM) * i;
-                if (m < a.M && k < a.K)
-                    big_ld<T, 4>((const T *)a.w, (size_t)k * a.sAk + m, v);
+                ok = m < a.M && k < a.K;
+                big_ld<T, 4>((const T *)a.w, (size_t)min(k, a.K - 1) * a.sAk + min(m, a.M - 4), v);
             }
-            ra[i] = make_float4(v[0], v[1], v[2], v[3]);
+            ra[slot][i] = ok ? make_float4(v[0], v[1], v[2], v[3]) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
-    auto store_a = [&](int buf) {
+    auto store_a = [&](int slot, int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < WM; ++i) {
+        for (int i = 0; i < WM * KP; ++i) {
             if (kcontig) {
-                const int m = (tid >> 2) + 64 * i, kk = 4 * (tid & 3);
-                As[buf][kk + 0][m] = ra[i].x;
-                As[buf][kk + 1][m] = ra[i].y;
-                As[buf][kk + 2][m] = ra[i].z;
-                As[buf][kk + 3][m] = ra[i].w;
+                const int m = (tid >> 2) + 64 * (i % WM), kk = 16 * (i / WM) + 4 * (tid & 3);
+                As[buf][kk + 0][m] = ra[slot][i].x;
+                As[buf][kk + 1][m] = ra[slot][i].y;
+                As[buf][kk + 2][m] = ra[slot][i].z;
+                As[buf][kk + 3][m] = ra[slot][i].w;
             } else {
                 const int m = 4 * (tid % (BM / 4)), kk = tid / (BM / 4) + (1024 / BM) * i;
-                *reinterpret_cast<float4 *>(&As[buf][kk][m]) = ra[i];
+                *reinterpret_cast<float4 *>(&As[buf][kk][m]) = ra[slot][i];
             }
         }
     };
@@ -171,43 +175,40 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
     const int bcol = tid % BCOLS, brow = tid / BCOLS;
     const uint32_t qb = q0 + (uint32_t)bcol * VEC;
     const bool bvalid = qb < a.Q;
-    uint32_t bn = 0;
-    size_t bbase = 0;
-    if (bvalid) {
-        bn = fdiv(qb, a.divHW);
-        bbase = (size_t)bn * a.K * a.HW + (qb - bn * (uint32_t)a.HW);
-    }
-    Staged<PRO, VEC> rb[NB];
-    auto load_b = [&](int k0) {
+    const uint32_t bn = bvalid ? fdiv(qb, a.divHW) : 0u; // an invalid column reads image 0, pixel 0
+    const size_t bbase = (size_t)bn * a.K * a.HW + (bvalid ? qb - bn * (uint32_t)a.HW : 0u);
+    Staged<PRO, VEC> rb[D - 1][NB];
+    bool rbok[D - 1][NB];
+    auto load_b = [&](int slot, int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int k = k0 + brow + BROWS * i;
-            if (bvalid && k < a.K) {
-                rb[i].template load<T>(a.B, bbase + (size_t)k * a.HW);
-                if (PRO == PRO_BNSWISH_GATE) {
-                    rb[i].k0 = a.B.c0[k];
-                    rb[i].k1 = a.B.c1[k];
-                    rb[i].k2 = a.B.gate[(size_t)bn * a.K + k];
-                } else if (PRO == PRO_BNBWD) {
-                    rb[i].k0 = a.B.c0[k];
-                    rb[i].k1 = a.B.c1[k];
-                    rb[i].k2 = a.B.c2[k];
-                }
-            } else {
-                rb[i].zero();
+            const int kc = min(k, a.K - 1);
+            rbok[slot][i] = bvalid && k < a.K;
+            rb[slot][i].template load<T>(a.B, bbase + (size_t)kc * a.HW);
+            if (PRO == PRO_BNSWISH_GATE) {
+                rb[slot][i].k0 = a.B.c0[kc];
+                rb[slot][i].k1 = a.B.c1[kc];
+                rb[slot][i].k2 = a.B.gate[(size_t)bn * a.K + kc];
+            } else if (PRO == PRO_BNBWD) {
+                rb[slot][i].k0 = a.B.c0[kc];
+                rb[slot][i].k1 = a.B.c1[kc];
+                rb[slot][i].k2 = a.B.c2[kc];
             }
         }
     };
-    auto store_b = [&](int buf) {
+    auto store_b = [&](int slot, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int kk = brow + BROWS * i;
             if (VEC == 4) {
+                const bool ok = rbok[slot][i];
                 *reinterpret_cast<float4 *>(&Bs[buf][kk][4 * bcol]) =
-                    make_float4(rb[i].apply(0), rb[i].apply(VEC == 4 ? 1 : 0),
-                                rb[i].apply(VEC == 4 ? 2 : 0), rb[i].apply(VEC == 4 ? 3 : 0));
+                    make_float4(ok ? rb[slot][i].apply(0) : 0.f, ok ? rb[slot][i].apply(VEC == 4 ? 1 : 0) : 0.f,
+                                ok ? rb[slot][i].apply(VEC == 4 ? 2 : 0) : 0.f,
+                                ok ? rb[slot][i].apply(VEC == 4 ? 3 : 0) : 0.f);
             } else {
-                Bs[buf][kk][bcol] = rb[i].apply(0);
+                Bs[buf][kk][bcol] = rbok[slot][i] ? rb[slot][i].apply(0) : 0.f;
             }
         }
     };
@@ -226,18 +227,10 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
         cbeg = blockIdx.y * a.chunksPerSplit;
         cend = min(cbeg + a.chunksPerSplit, cend);
     }
-    load_a(cbeg * BK);
-    load_b(cbeg * BK);
-    store_a(0);
-    store_b(0);
-    __syncthreads();
-    for (int c = cbeg; c < cend; ++c) {
-        const int buf = (c - cbeg) & 1;
-        const bool more = c + 1 < cend;
-        if (more) {
-            load_a((c + 1) * BK);
-            load_b((c + 1) * BK);
-        }
+    // Register ring of D-1 staged chunks: chunk j lives in slot (j - cbeg) % (D-1) from its load
+    // until it is written to LDS, one iteration before it is consumed; its loads are issued D-1
+    // iterations before that, so their latency is covered by D-2 iterations of MFMA work.
+    auto mfma_chunk = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             float av[WM], bv[WP];
@@ -253,11 +246,35 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
                 for (int j = 0; j < WP; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
-        if (more) {
-            store_a(buf ^ 1);
-            store_b(buf ^ 1);
+    };
+#pragma unroll
+    for (int u = 0; u < D - 1; ++u) {
+        if (cbeg + u < cend) {
+            load_a(u, (cbeg + u) * BK);
+            load_b(u, (cbeg + u) * BK);
         }
-        __syncthreads();
+    }
+    store_a(0, 0);
+    store_b(0, 0);
+    __syncthreads();
+    for (int c = cbeg; c < cend; c += D - 1) {
+#pragma unroll
+        for (int u = 0; u < D - 1; ++u) {
+            const int cc = c + u;
+            if (cc < cend) { // uniform over the workgroup
+                const int buf = (cc - cbeg) & 1;
+                if (cc + D - 1 < cend) { // chunk cc's slot is free: it went to LDS last iteration
+                    load_a(u, (cc + D - 1) * BK);
+                    load_b(u, (cc + D - 1) * BK);
+                }
+                mfma_chunk(buf);
+                if (cc + 1 < cend) {
+                    store_a((u + 1) % (D - 1), buf ^ 1);
+                    store_b((u + 1) % (D - 1), buf ^ 1);
+                }
+                __syncthreads();
+            }
+        }
     }
 
     // ---- epilogue: register r of lane l is row 8*(r/4)+4*(l/32)+r%4, column l%32 ----
@@ -306,8 +323,8 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
         for (int i = 0; i < WM; ++i) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float s = half_wave_sum(rs[i][r]);
-                const float s2 = half_wave_sum(rq[i][r]);
+                const float s = half_wave_sum_dpp(rs[i][r]);
+                const float s2 = half_wave_sum_dpp(rq[i][r]);
                 if ((lane & 31) == 0) {
                     const int row = wm * 32 * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     red[0][row][wp] = s;
@@ -338,9 +355,20 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restr
     for (int i = 0; i < 4; ++i) {
         const uint32_t q = blockIdx.x * 1024u + 256u * i + tid;
         if (q < Q) {
-            float v = 0.f;
-            for (int s = 0; s < S; ++s)
-                v += partial[((size_t)s * M + m) * Q + q];
+            // four independent running sums keep the loads of a round in flight together
+            float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+            const float *src = partial + (size_t)m * Q + q;
+            const size_t step = (size_t)M * Q;
+            int s = 0;
+            for (; s + 3 < S; s += 4) {
+                v0 += src[(size_t)s * step];
+                v1 += src[(size_t)(s + 1) * step];
+                v2 += src[(size_t)(s + 2) * step];
+                v3 += src[(size_t)(s + 3) * step];
+            }
+            for (; s < S; ++s)
+                v0 += src[(size_t)s * step];
+            float v = (v0 + v1) + (v2 + v3);
             const uint32_t n = fdiv(q, divHW), pix = q - n * (uint32_t)HW;
             const size_t idx = ((size_t)n * M + m) * HW + pix;
             if (EPI == EPI_RES)
@@ -383,8 +411,7 @@ static BigOperand to_big(const Operand &o)
 // 128 rows per tile when that pads the channel count no further than 64 would
 static int big_rows(int M) { return ((M + 127) / 128) * 128 == ((M + 63) / 64) * 64 ? 2 : 1; }
 
-// Tile choice: 128 pixel columns when that still gives every CU work, else 64.  `wt` packs
-// the row and column factors as 4*WM + WP.  When even the 64-column tiles are too few to fill
+// Tile choice; `wt` packs the row and column factors as 4*WM + WP.  When the tiles are too few to fill
 // the chip and the contraction is long, it is split `splits` ways (each at least four chunks of
 // 16) and a second kernel adds the partial tiles; `qtiles` is then that kernel's count of
 // 1024-pixel groups.
@@ -393,9 +420,10 @@ bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles, int *split
     const long long Q = (long long)N * HW;
     if (K % 4 != 0 || M % 4 != 0 || Q >= (1ll << 31) || K < 16)
         return false;
-    const int wm = big_rows(M);
-    const long long t128 = ((Q + 127) / 128) * ((M + 64 * wm - 1) / (64 * wm));
-    const int wp = (t128 >= 384 && HW % 4 == 0) ? 2 : 1;
+    // measured: 64-column tiles are never slower than 128-column ones (more workgroups in
+    // flight matter more than operand reuse); 128 rows pay only for very wide outputs
+    const int wm = M >= 512 ? big_rows(M) : 1;
+    const int wp = 1;
     *wt = 4 * wm + wp;
     *qtiles = (int)((Q + 64 * wp - 1) / (64 * wp));
     *splits = 1;
@@ -415,12 +443,13 @@ bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles, int *split
     return true;
 }
 
-template <typename T, int WM, int WP, int VEC>
+template <typename T, int WM, int WP, int VEC, int D = 2>
 static hipError_t big_conv_dispatch(const BigConvArgs &a, int pro, int epi, dim3 grid, hipStream_t st)
 {
 #define MBK_CASE(P, E)                                                                            \
     if (pro == P && epi == E) {                                                                   \
-        hipLaunchKernelGGL((conv_big_kernel<T, P, E, WM, WP, VEC>), grid, dim3(256), 0, st, a);   \
+        hipLaunchKernelGGL((conv_big_kernel<T, P, E, WM, WP, VEC, D>), grid, dim3(256), 0, st,    \
+                           a);                                                                    \
         return hipGetLastError();                                                                 \
     }
     MBK_CASE(PRO_NONE, EPI_STATS)
@@ -503,10 +532,10 @@ hipError_t launch_big_conv1x1(bool bf16, int N, int M, int K, int HW, const void
 #define MBK_GO(TT)                                                                                \
     (!v4 ? (wm == 2 ? big_conv_dispatch<TT, 2, 1, 1>(a, B.pro, epi, grid, st)                     \
                     : big_conv_dispatch<TT, 1, 1, 1>(a, B.pro, epi, grid, st))                    \
-         : wm == 2 ? (wp == 2 ? big_conv_dispatch<TT, 2, 2, 4>(a, B.pro, epi, grid, st)           \
-                              : big_conv_dispatch<TT, 2, 1, 4>(a, B.pro, epi, grid, st))          \
-                   : (wp == 2 ? big_conv_dispatch<TT, 1, 2, 4>(a, B.pro, epi, grid, st)           \
-                              : big_conv_dispatch<TT, 1, 1, 4>(a, B.pro, epi, grid, st)))
+         : (wm == 2 ? big_conv_dispatch<TT, 2, 1, 4>(a, B.pro, epi, grid, st)                     \
+                    : big_conv_dispatch<TT, 1, 1, 4>(a, B.pro, epi, grid, st)))
+    if (wp != 1)
+        return hipErrorInvalidValue;
     const hipError_t e = bf16 ? MBK_GO(bf16_t) : MBK_GO(float);
 #undef MBK_GO
     if (e != hipSuccess || splits == 1)
@@ -583,44 +612,43 @@ __global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
         }
     }
     bool staged_valid = false; // the staged pixel run lies inside the tensor
-    auto load = [&](int chunk) {
+    // Unconditional loads with clamped indices (see conv_big_kernel): rows past the end read
+    // the last row and are zeroed by their coefficients / masks, a run past the end reads pixel 0.
+    auto load = [&](int chunk) __attribute__((always_inline)) {
         const uint32_t q = (uint32_t)chunk * BQ + (uint32_t)qcol * VEC;
         staged_valid = q < a.Q;
-        if (!staged_valid)
-            return;
-        const uint32_t n = fdiv(q, a.divHW);
-        const uint32_t pix = q - n * (uint32_t)a.HW;
+        const uint32_t qc = staged_valid ? q : 0u;
+        const uint32_t n = fdiv(qc, a.divHW);
+        const uint32_t pix = qc - n * (uint32_t)a.HW;
 #pragma unroll
         for (int i = 0; i < NRU; ++i) {
-            const int ra = a0 + rrow + RROWS * i;
-            if (ra < a.Ma) {
-                ru[i].template load<T>(a.U, ((size_t)n * a.Ma + ra) * a.HW + pix);
-                if (PROU == PRO_BNSWISH_GATE)
-                    ru[i].k2 = a.U.gate[(size_t)n * a.Ma + ra];
-            }
+            const int ra = min(a0 + rrow + RROWS * i, a.Ma - 1);
+            ru[i].template load<T>(a.U, ((size_t)n * a.Ma + ra) * a.HW + pix);
+            if (PROU == PRO_BNSWISH_GATE)
+                ru[i].k2 = a.U.gate[(size_t)n * a.Ma + ra];
         }
 #pragma unroll
         for (int i = 0; i < NRV; ++i) {
-            const int rb = b0 + rrow + RROWS * i;
-            if (rb < a.Mb) {
-                rv[i].template load<T>(a.V, ((size_t)n * a.Mb + rb) * a.HW + pix);
-                if (PROV == PRO_BNSWISH_GATE)
-                    rv[i].k2 = a.V.gate[(size_t)n * a.Mb + rb];
-            }
+            const int rb = min(b0 + rrow + RROWS * i, a.Mb - 1);
+            rv[i].template load<T>(a.V, ((size_t)n * a.Mb + rb) * a.HW + pix);
+            if (PROV == PRO_BNSWISH_GATE)
+                rv[i].k2 = a.V.gate[(size_t)n * a.Mb + rb];
         }
     };
-    auto store = [&](int buf) {
+    auto store = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NRU; ++i) {
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
-                Us[buf][qcol * VEC + j][rrow + RROWS * i] = staged_valid ? ru[i].apply(j) : 0.f;
+                Us[buf][qcol * VEC + j][rrow + RROWS * i] =
+                    (staged_valid && a0 + rrow + RROWS * i < a.Ma) ? ru[i].apply(j) : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < NRV; ++i) {
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
-                Vs[buf][qcol * VEC + j][rrow + RROWS * i] = staged_valid ? rv[i].apply(j) : 0.f;
+                Vs[buf][qcol * VEC + j][rrow + RROWS * i] =
+                    (staged_valid && b0 + rrow + RROWS * i < a.Mb) ? rv[i].apply(j) : 0.f;
         }
     };
 
@@ -684,12 +712,13 @@ bool big_wgrad_plan(int Ma, int Mb, int N, int HW, int *wt, int *splits)
     const long long Q = (long long)N * HW;
     if (Q >= (1ll << 31))
         return false;
-    // the scalar-load variant (HW not a multiple of 4) is built for 64x64 tiles only
-    const int wa = HW % 4 == 0 ? big_rows(Ma) : 1, wb = HW % 4 == 0 ? big_rows(Mb) : 1;
+    // measured: 64x64 tiles with many contraction splits beat larger tiles on every shape of
+    // the late EfficientNet stages (workgroups in flight hide the staging latency)
+    const int wa = 1, wb = 1;
     *wt = 4 * wa + wb;
-    const long long tiles = (long long)((Ma + 64 * wa - 1) / (64 * wa)) * ((Mb + 64 * wb - 1) / (64 * wb));
+    const long long tiles = (long long)((Ma + 63) / 64) * ((Mb + 63) / 64);
     const long long chunks = (Q + 31) / 32;
-    long long s = (512 + tiles - 1) / tiles;
+    long long s = (640 + tiles - 1) / tiles;
     const long long smax = (chunks + 3) / 4; // at least four chunks per split
     if (s > smax)
         s = smax;
@@ -738,10 +767,9 @@ hipError_t launch_big_wgrad(bool bf16, int N, int Ma, int Mb, int HW, const Oper
     const bool v4 = HW % 4 == 0;
 #define MBK_GO(TT)                                                                                \
     (!v4 ? big_wgrad_dispatch<TT, 1, 1, 1>(a, U.pro, V.pro, grid, st)                             \
-         : wa == 2 ? (wb == 2 ? big_wgrad_dispatch<TT, 2, 2, 4>(a, U.pro, V.pro, grid, st)        \
-                              : big_wgrad_dispatch<TT, 2, 1, 4>(a, U.pro, V.pro, grid, st))       \
-                   : (wb == 2 ? big_wgrad_dispatch<TT, 1, 2, 4>(a, U.pro, V.pro, grid, st)        \
-                              : big_wgrad_dispatch<TT, 1, 1, 4>(a, U.pro, V.pro, grid, st)))
+         : big_wgrad_dispatch<TT, 1, 1, 4>(a, U.pro, V.pro, grid, st))
+    if (wa != 1 || wb != 1)
+        return hipErrorInvalidValue;
     return bf16 ? MBK_GO(bf16_t) : MBK_GO(float);
 #undef MBK_GO
 }

@@ -87,16 +87,6 @@ __device__ __forceinline__ void pv_store4<bf16_t>(bf16_t *p, size_t i, const flo
     *reinterpret_cast<uint2 *>(&p[i]) = t;
 }
 
-// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
-__device__ __forceinline__ float row16_sum(float v)
-{
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, false)); // row_ror:8
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xf, 0xf, false)); // row_ror:4
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x122, 0xf, 0xf, false)); // row_ror:2
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x121, 0xf, 0xf, false)); // row_ror:1
-    return v;
-}
-
 // One float4 of activations of input channel k, image n, with its prologue (PRO_* in the header).
 template <typename T, int PRO>
 __device__ __forceinline__ void pv_load_act(const PvArgs &a, size_t idx, uint32_t n, int k,

@@ -69,8 +69,9 @@ __device__ __forceinline__ float as_stored<bf16_t>(float v)
 
 __device__ __forceinline__ float sigmoidf_fast(float t)
 {
-    // 1/(1+2^(-t*log2 e)); v_exp_f32 and v_rcp_f32 are accurate to about 1 ulp
-    return __frcp_rn(1.0f + __expf(-t));
+    // 1/(1+2^(-t*log2 e)) with the hardware v_exp_f32 and v_rcp_f32, each accurate to about
+    // 1 ulp (a correctly rounded division would cost ten more instructions per element)
+    return __builtin_amdgcn_rcpf(1.0f + __expf(-t));
 }
 
 __device__ __forceinline__ float swishf(float t) { return t * sigmoidf_fast(t); }
@@ -116,6 +117,23 @@ __device__ __forceinline__ float wave_sum(float v)
     for (int o = 32; o > 0; o >>= 1)
         v += __shfl_xor(v, o, kWave);
     return v;
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, false)); // row_ror:8
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xf, 0xf, false)); // row_ror:4
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x122, 0xf, 0xf, false)); // row_ror:2
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x121, 0xf, 0xf, false)); // row_ror:1
+    return v;
+}
+
+// Sum over the 32 lanes that share lane/32, by DPP row rotations plus one cross-row exchange.
+__device__ __forceinline__ float half_wave_sum_dpp(float v)
+{
+    v = row16_sum(v);
+    return v + __shfl_xor(v, 16, kWave);
 }
 
 // sum over the 32 lanes that share lane/32
