@@ -585,21 +585,45 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void plane_reduce_kernel(Pla
         const float sc = a.bn[pl.c], sh = a.bn[a.C + pl.c];
         const float mu = a.bn[2 * a.C + pl.c], rs = a.bn[3 * a.C + pl.c];
         const size_t base = pl.plane * (size_t)a.HW;
+        // Four strides of the plane per round: all loads of a round are issued before any of
+        // them is consumed (the scheduler fence keeps the compiler from pairing each load with
+        // its arithmetic, which would cost one memory round trip per stride).
         if ((a.HW & 3) == 0) {
-            for (int idx = 4 * lt; idx < a.HW; idx += 4 * TPP) {
-                float v0[4], v1[4] = {0.f, 0.f, 0.f, 0.f};
-                ldvec4<T>((const T *)a.t0, base + idx, v0);
-                if (OP::kTwo)
-                    ldvec4<T>((const T *)a.t1, base + idx, v1);
+            for (int idx0 = 4 * lt; idx0 < a.HW; idx0 += 16 * TPP) {
+                float v0[4][4], v1[4][4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    OP::eval(v0[r], v1[r], sc, sh, mu, rs, acc);
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = idx0 + 4 * TPP * u;
+                    const int ic = idx < a.HW ? idx : idx0; // past the end: reread, masked below
+                    ldvec4<T>((const T *)a.t0, base + ic, v0[u]);
+                    if (OP::kTwo)
+                        ldvec4<T>((const T *)a.t1, base + ic, v1[u]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (idx0 + 4 * TPP * u < a.HW) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            OP::eval(v0[u][r], OP::kTwo ? v1[u][r] : 0.f, sc, sh, mu, rs, acc);
+                    }
+                }
             }
         } else {
-            for (int idx = lt; idx < a.HW; idx += TPP) {
-                const float v0 = ld<T>((const T *)a.t0, base + idx);
-                const float v1 = OP::kTwo ? ld<T>((const T *)a.t1, base + idx) : 0.f;
-                OP::eval(v0, v1, sc, sh, mu, rs, acc);
+            for (int idx0 = lt; idx0 < a.HW; idx0 += 4 * TPP) {
+                float v0[4], v1[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = idx0 + TPP * u;
+                    const int ic = idx < a.HW ? idx : idx0;
+                    v0[u] = ld<T>((const T *)a.t0, base + ic);
+                    v1[u] = OP::kTwo ? ld<T>((const T *)a.t1, base + ic) : 0.f;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (idx0 + TPP * u < a.HW)
+                        OP::eval(v0[u], v1[u], sc, sh, mu, rs, acc);
             }
         }
     }
@@ -623,20 +647,30 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void bn_apply_kernel(PlaneAr
     const float sc = a.bn[pl.c], sh = a.bn[a.C + pl.c];
     const size_t base = pl.plane * (size_t)a.HW;
     if ((a.HW & 3) == 0) {
-        for (int idx = 4 * lt; idx < a.HW; idx += 4 * TPP) {
-            float v[4];
-            ldvec4<T>((const T *)a.t0, base + idx, v);
+        for (int idx0 = 4 * lt; idx0 < a.HW; idx0 += 16 * TPP) {
+            float v[4][4], rr[4][4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                v[r] = fmaf(v[r], sc, sh);
-            if (a.res) {
-                float rr[4];
-                ldvec4<T>((const T *)a.res, base + idx, rr);
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    v[r] += rr[r];
+            for (int u = 0; u < 4; ++u) {
+                const int idx = idx0 + 4 * TPP * u;
+                const int ic = idx < a.HW ? idx : idx0;
+                ldvec4<T>((const T *)a.t0, base + ic, v[u]);
+                if (a.res)
+                    ldvec4<T>((const T *)a.res, base + ic, rr[u]);
             }
-            stvec4<T>((T *)a.out, base + idx, v);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = idx0 + 4 * TPP * u;
+                if (idx < a.HW) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        v[u][r] = fmaf(v[u][r], sc, sh);
+                        if (a.res)
+                            v[u][r] += rr[u][r];
+                    }
+                    stvec4<T>((T *)a.out, base + idx, v[u]);
+                }
+            }
         }
     } else {
         for (int idx = lt; idx < a.HW; idx += TPP) {

@@ -161,6 +161,15 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_fwd_kernel(Dw4Args 
             wt[t] = ld<T>((const T *)a.w, (size_t)c * K * K + t);
         zero_border<P, TPP>(tile, H, W, WP, lt);
         const size_t base = plane * (size_t)H * W;
+        // all runs of the thread are loaded before any is transformed (one memory round trip,
+        // not one per run; the fence keeps the scheduler from re-pairing load and use)
+        float ev[NG][4];
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            gload4<T>((const T *)a.e, base + 4 * (size_t)(gidx < a.groups ? gidx : 0), ev[i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NG; ++i) {
             const int gidx = lt + TPP * i;
@@ -168,7 +177,9 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_fwd_kernel(Dw4Args 
                 const int h = (int)fdiv((uint32_t)gidx, a.divW4);
                 const int w = 4 * (gidx - h * (W >> 2));
                 float v[4];
-                gload4<T>((const T *)a.e, base + 4 * (size_t)gidx, v);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    v[r] = ev[i][r];
                 if (EXPAND) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
@@ -256,16 +267,26 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_bwd_kernel(Dw4Args 
         zero_border<P, TPP>(a1t, H, W, WP, lt);
         zero_border<P, TPP>(ddt, H, W, WP, lt);
         const size_t base = plane * (size_t)H * W;
+        float evA[NG][4], GvA[NG][4], dvA[NG][4]; // all loads first (see the forward kernel)
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            const size_t at = base + 4 * (size_t)(gidx < a.groups ? gidx : 0);
+            gload4<T>((const T *)a.e, at, evA[i]);
+            gload4<T>((const T *)a.G, at, GvA[i]);
+            gload4<T>((const T *)a.d, at, dvA[i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NG; ++i) {
             const int gidx = lt + TPP * i;
             if (gidx < a.groups) {
                 const int h = (int)fdiv((uint32_t)gidx, a.divW4);
                 const int w = 4 * (gidx - h * (W >> 2));
-                float ev[4], Gv[4], dv[4], av[4], ddv[4];
-                gload4<T>((const T *)a.e, base + 4 * (size_t)gidx, ev);
-                gload4<T>((const T *)a.G, base + 4 * (size_t)gidx, Gv);
-                gload4<T>((const T *)a.d, base + 4 * (size_t)gidx, dv);
+                float av[4], ddv[4];
+                const float(&ev)[4] = evA[i];
+                const float(&Gv)[4] = GvA[i];
+                const float(&dv)[4] = dvA[i];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     if (EXPAND) {

@@ -87,25 +87,44 @@ __device__ __forceinline__ void pv_store4<bf16_t>(bf16_t *p, size_t i, const flo
     *reinterpret_cast<uint2 *>(&p[i]) = t;
 }
 
-// One float4 of activations of input channel k, image n, with its prologue (PRO_* in the header).
+// One float4 of activations of input channel k, image n, in two steps: the raw loads, and the
+// prologue (PRO_* in the header) applied to them.  The kernels issue the raw loads of a whole
+// batch first and fence the instruction scheduler before the arithmetic: left alone, the
+// compiler sinks every load next to its use to save registers, which serialises the batch into
+// one memory round trip per load.
+template <int PRO>
+struct PvRaw {
+    float v[4];
+    float r[PRO == PRO_BNBWD ? 4 : 1];
+    float g;
+};
 template <typename T, int PRO>
-__device__ __forceinline__ void pv_load_act(const PvArgs &a, size_t idx, uint32_t n, int k,
-                                            const float *coef, int cstride, float (&v)[4])
+__device__ __forceinline__ void pv_load_raw(const PvArgs &a, size_t idx, uint32_t n, int k, PvRaw<PRO> &o)
 {
-    pv_load4<T>((const T *)a.p0, idx, v);
+    pv_load4<T>((const T *)a.p0, idx, o.v);
+    if constexpr (PRO == PRO_BNBWD)
+        pv_load4<T>((const T *)a.p1, idx, o.r);
+    if (PRO == PRO_BNSWISH_GATE)
+        o.g = a.gate[(size_t)n * a.K + k];
+}
+template <int PRO>
+__device__ __forceinline__ void pv_apply(const PvRaw<PRO> &o, int k, const float *coef, int cstride,
+                                         float (&v)[4])
+{
     if (PRO == PRO_BNBWD) {
-        float raw[4];
-        pv_load4<T>((const T *)a.p1, idx, raw);
         const float c0 = coef[k], c1 = coef[cstride + k], c2 = coef[2 * cstride + k];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            v[r] = fmaf(c0, v[r], fmaf(c1, raw[r], c2));
+            v[r] = fmaf(c0, o.v[r], fmaf(c1, o.r[PRO == PRO_BNBWD ? r : 0], c2));
     } else if (PRO == PRO_BNSWISH_GATE) {
         const float sc = coef[k], sh = coef[cstride + k];
-        const float g = a.gate[(size_t)n * a.K + k];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            v[r] = swishf(fmaf(v[r], sc, sh)) * g;
+            v[r] = swishf(fmaf(o.v[r], sc, sh)) * o.g;
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            v[r] = o.v[r];
     }
 }
 
@@ -161,15 +180,23 @@ __global__ __launch_bounds__(64 * kPeMaxWaves) void conv_pe_kernel(PvArgs a)
         const bool valid = qv < a.Q;
         const uint32_t n = valid ? fdiv(qv, a.divHW) : 0;
         const uint32_t pix = valid ? qv - n * (uint32_t)a.HW : 0;
+        PvRaw<PRO> raw[KS4];
+#pragma unroll
+        for (int s = 0; s < KS4; ++s) {
+            const int k = min(4 * s + kk, a.K - 1); // past the end: a valid address, masked below
+            pv_load_raw<T, PRO>(a, ((size_t)n * a.K + k) * a.HW + pix, n, k, raw[s]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         float bv[KS4][4];
 #pragma unroll
         for (int s = 0; s < KS4; ++s) {
             const int k = 4 * s + kk;
+            pv_apply<PRO>(raw[s], min(k, a.K - 1), coef, 4 * KS4, bv[s]);
+            if (!(valid && k < a.K)) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                bv[s][r] = 0.f;
-            if (valid && k < a.K)
-                pv_load_act<T, PRO>(a, ((size_t)n * a.K + k) * a.HW + pix, n, k, coef, 4 * KS4, bv[s]);
+                for (int r = 0; r < 4; ++r)
+                    bv[s][r] = 0.f;
+            }
         }
 #pragma unroll
         for (int t = 0; t < kPeTT; ++t) {
@@ -275,23 +302,27 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
                 acc[t][r] = (float4v){0.f, 0.f, 0.f, 0.f};
 
         for (int u0 = 0; u0 < KSWp; u0 += U) {
-            float bv[U][4];
+            PvRaw<PRO> raw[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 int k = 4 * (sBeg + u0 + u) + kk;
                 k = k < kLast ? k : kLast;
-                pv_load_act<T, PRO>(a, base + (size_t)k * a.HW, n, k, coef, 4 * KS4p, bv[u]);
+                pv_load_raw<T, PRO>(a, base + (size_t)k * a.HW, n, k, raw[u]);
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int s = sBeg + u0 + u;
+                int k = 4 * s + kk;
+                k = k < kLast ? k : kLast;
+                float bv[4];
+                pv_apply<PRO>(raw[u], k, coef, 4 * KS4p, bv);
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
                     const float wv = wl[(s * 2 + t) * 64 + lane];
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        acc[t][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv, bv[u][r], acc[t][r], 0,
-                                                                         0, 0);
+                        acc[t][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv, bv[r], acc[t][r], 0, 0, 0);
                 }
             }
         }
