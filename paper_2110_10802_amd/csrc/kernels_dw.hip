@@ -25,6 +25,11 @@ bool dw4_supported(const DwShape &s);
 hipError_t launch_dw4_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
                           const void *w_dw, void *d, float *psum, float *psq, hipStream_t st);
 hipError_t launch_dw4_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st);
+// kernels_dw2.hip
+bool dw2_supported(const DwShape &s);
+hipError_t launch_dw2_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
+                          const void *w_dw, void *d, float *psum, float *psq, hipStream_t st);
+hipError_t launch_dw2_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st);
 // kernels_dwr.hip
 bool dwr_supported(const DwShape &s);
 int dwr_num_partials(const DwShape &s);
@@ -203,6 +208,8 @@ hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float
         return launch_dw4_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
     if (!a1_store && dwr_supported(s))
         return launch_dwr_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
+    if (!a1_store && dw2_supported(s))
+        return launch_dw2_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
     DwFwdDev a;
     a.s = s;
     a.divC = make_div((uint32_t)s.C);
@@ -451,6 +458,8 @@ hipError_t launch_dw_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st)
         return launch_dw4_bwd(bf16, h, st);
     if (!h.a1_saved && dwr_supported(h.s))
         return launch_dwr_bwd(bf16, h, st);
+    if (!h.a1_saved && !h.res && dw2_supported(h.s))
+        return launch_dw2_bwd(bf16, h, st);
     DwBwdDev a;
     a.s = h.s;
     const int p = h.s.p;
