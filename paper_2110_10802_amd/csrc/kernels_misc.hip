@@ -28,10 +28,29 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(int C, int NP, double 
     const int c = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (c >= C)
         return;
+    // everything the last step needs is requested up front, and the partials are read four
+    // strides at a time, so the kernel costs a few memory round trips whatever NP is
+    const float gm = gamma[c], bt = beta[c];
+    // (a null running-stat pointer reads gamma instead: no branch in front of the loads)
+    const float rm = (run_mean ? run_mean : gamma)[c], rv = (run_var ? run_var : gamma)[c];
+    const float *ps = psum + (size_t)c * NP, *pq = psq + (size_t)c * NP;
     double s = 0.0, s2 = 0.0;
-    for (int i = lane; i < NP; i += kWave) {
-        s += (double)psum[(size_t)c * NP + i];
-        s2 += (double)psq[(size_t)c * NP + i];
+    for (int i0 = lane; i0 < NP; i0 += 4 * kWave) {
+        float a0[4], a1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = min(i0 + kWave * u, NP - 1); // unconditional loads, masked below
+            a0[u] = ps[i];
+            a1[u] = pq[i];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (i0 + kWave * u < NP) {
+                s += (double)a0[u];
+                s2 += (double)a1[u];
+            }
+        }
     }
     s = wave_sum_d(s);
     s2 = wave_sum_d(s2);
@@ -41,16 +60,16 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(int C, int NP, double 
         if (var < 0.0)
             var = 0.0;
         const double rstd = 1.0 / sqrt(var + (double)eps);
-        const double scale = (double)gamma[c] * rstd;
+        const double scale = (double)gm * rstd;
         bn[c] = (float)scale;
-        bn[C + c] = (float)((double)beta[c] - mean * scale);
+        bn[C + c] = (float)((double)bt - mean * scale);
         bn[2 * C + c] = (float)mean;
         bn[3 * C + c] = (float)rstd;
         if (run_mean)
-            run_mean[c] = (float)((1.0 - (double)momentum) * (double)run_mean[c] + (double)momentum * mean);
+            run_mean[c] = (float)((1.0 - (double)momentum) * (double)rm + (double)momentum * mean);
         if (run_var) {
             const double unbiased = m > 1.0 ? var * m / (m - 1.0) : var;
-            run_var[c] = (float)((1.0 - (double)momentum) * (double)run_var[c] + (double)momentum * unbiased);
+            run_var[c] = (float)((1.0 - (double)momentum) * (double)rv + (double)momentum * unbiased);
         }
     }
 }
@@ -66,16 +85,61 @@ hipError_t launch_bn_finalize(int C, int NP, double m, const float *psum, const 
 
 // dx = gamma*rstd*(dy - dbeta/m - xhat*dgamma/m) with xhat = (raw-mean)*rstd, rewritten as
 // c0*dy + c1*raw + c2 so the consumer's prologue is two fused multiply-adds.
-__device__ __forceinline__ void bn_bwd_coef(int C, int c, double m, double dgamma, double dbeta,
-                                            float gamma, const float *bn, float *coef)
+__device__ __forceinline__ void bn_bwd_coef_vals(int C, int c, double m, double dgamma, double dbeta,
+                                                 float gamma, double mean, double rstd, float *coef)
 {
-    const double mean = bn[2 * C + c], rstd = bn[3 * C + c];
     const double c0 = (double)gamma * rstd;
     const double c1 = -c0 * rstd * dgamma / m;
     const double c2 = -c0 * dbeta / m - c1 * mean;
     coef[c] = (float)c0;
     coef[C + c] = (float)c1;
     coef[2 * C + c] = (float)c2;
+}
+__device__ __forceinline__ void bn_bwd_coef(int C, int c, double m, double dgamma, double dbeta,
+                                            float gamma, const float *bn, float *coef)
+{
+    bn_bwd_coef_vals(C, c, m, dgamma, dbeta, gamma, bn[2 * C + c], bn[3 * C + c], coef);
+}
+
+__device__ __forceinline__ void bn_bwd_finalize_body(int block, int C, int NP, double m,
+                                                     const float *__restrict__ psb,
+                                                     const float *__restrict__ psr,
+                                                     const float *__restrict__ gamma,
+                                                     const float *__restrict__ bn, float *dgamma,
+                                                     float *dbeta, float *coef)
+{
+    const int c = block * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (c >= C)
+        return;
+    const float gm = gamma[c], mean = bn[2 * C + c], rstd = bn[3 * C + c]; // requested up front
+    const float *pb = psb + (size_t)c * NP, *pr = psr + (size_t)c * NP;
+    double sb = 0.0, sr = 0.0;
+    for (int i0 = lane; i0 < NP; i0 += 4 * kWave) {
+        float a0[4], a1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = min(i0 + kWave * u, NP - 1); // unconditional loads, masked below
+            a0[u] = pb[i];
+            a1[u] = pr[i];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (i0 + kWave * u < NP) {
+                sb += (double)a0[u];
+                sr += (double)a1[u];
+            }
+        }
+    }
+    sb = wave_sum_d(sb);
+    sr = wave_sum_d(sr);
+    if (lane == 0) {
+        if (dbeta)
+            dbeta[c] = (float)sb;
+        if (dgamma)
+            dgamma[c] = (float)sr;
+        bn_bwd_coef_vals(C, c, m, sr, sb, gm, mean, rstd, coef);
+    }
 }
 
 __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(int C, int NP, double m,
@@ -86,23 +150,7 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(int C, int NP, dou
                                                               float *dgamma, float *dbeta,
                                                               float *coef)
 {
-    const int c = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (c >= C)
-        return;
-    double sb = 0.0, sr = 0.0;
-    for (int i = lane; i < NP; i += kWave) {
-        sb += (double)psb[(size_t)c * NP + i];
-        sr += (double)psr[(size_t)c * NP + i];
-    }
-    sb = wave_sum_d(sb);
-    sr = wave_sum_d(sr);
-    if (lane == 0) {
-        if (dbeta)
-            dbeta[c] = (float)sb;
-        if (dgamma)
-            dgamma[c] = (float)sr;
-        bn_bwd_coef(C, c, m, sr, sb, gamma[c], bn, coef);
-    }
+    bn_bwd_finalize_body(blockIdx.x, C, NP, m, psb, psr, gamma, bn, dgamma, dbeta, coef);
 }
 
 hipError_t launch_bn_bwd_finalize(int C, int NP, double m, const float *psb, const float *psr,
@@ -445,27 +493,28 @@ __global__ __launch_bounds__(256) void se_bwd_image_wide_kernel(SeBwdArgs a, int
     }
 }
 
-// Sums over the batch for a tile of 32 channels: thread (c, jg) owns dW2[c][j] and dW1[j][c]
-// for j = jg, jg+8, ...; the batch is walked 32 images at a time through LDS, always in the
-// same order.  The first 32 threads also produce db2 and BN2's dbeta/dgamma/coef for their
-// channel; workgroup 0 adds db1.
+// Sums over the batch for a tile of 16 channels: thread (c, jq) owns dW2[c][4jq..4jq+3] and
+// dW1[4jq..4jq+3][c]; the batch is walked 32 images at a time through LDS, always in the same
+// order, and the j-contiguous operands are read as one 16-byte LDS access per image.  The
+// per-channel sums (db2, BN2's dbeta/dgamma/coef) are split over the 16 jq groups and combined
+// in a fixed order; workgroup 0 adds db1.
 __global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
 {
-    constexpr int TC = 32, TN = 32, JMAX = 8; // Cse <= 8*JMAX
-    __shared__ float dtL[TN][TC], zL[TN][TC], rL[TN][64], dqL[TN][64];
+    constexpr int TC = 16, TN = 32, JQ = 16; // Cse <= 4*JQ
+    __shared__ float dtL[TN][TC], zL[TN][TC];
+    __shared__ __attribute__((aligned(16))) float rL[TN][4 * JQ], dqL[TN][4 * JQ];
+    __shared__ float sbL[JQ][TC];
+    __shared__ double dbL[JQ][TC], dgL[JQ][TC];
     const int C = a.C, Cse = a.Cse, N = a.N;
-    const int tid = threadIdx.x, cl = tid & 31, jg = tid >> 5;
+    const int tid = threadIdx.x, cl = tid & 15, jq = tid >> 4;
     const int c0 = blockIdx.x * TC, c = c0 + cl;
-    float acc2[JMAX], acc1[JMAX];
-#pragma unroll
-    for (int u = 0; u < JMAX; ++u)
-        acc2[u] = acc1[u] = 0.f;
+    float acc2[4] = {0.f, 0.f, 0.f, 0.f}, acc1[4] = {0.f, 0.f, 0.f, 0.f};
     for (int n0 = 0; n0 < N; n0 += TN) {
         __syncthreads();
-        float t0[4], t1[4], t2[8], t3[8]; // all loads of the round in flight together
+        float t0[2], t1[2], t2[8], t3[8]; // all loads of the round in flight together
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = tid + 256 * u, nn = i >> 5, cc = i & 31;
+        for (int u = 0; u < 2; ++u) {
+            const int i = tid + 256 * u, nn = i >> 4, cc = i & 15;
             const bool ok = n0 + nn < N && c0 + cc < C;
             t0[u] = ok ? a.dt[(size_t)(n0 + nn) * C + c0 + cc] : 0.f;
             t1[u] = ok ? a.z[(size_t)(n0 + nn) * C + c0 + cc] : 0.f;
@@ -478,50 +527,51 @@ __global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
             t3[u] = ok ? a.dq[(size_t)(n0 + nn) * Cse + j] : 0.f;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 2; ++u) {
             const int i = tid + 256 * u;
-            dtL[i >> 5][i & 31] = t0[u];
-            zL[i >> 5][i & 31] = t1[u];
+            dtL[i >> 4][i & 15] = t0[u];
+            zL[i >> 4][i & 15] = t1[u];
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int i = tid + 256 * u;
-            rL[i >> 6][i & 63] = swishf(t2[u]);
+            rL[i >> 6][i & 63] = (i & 63) < Cse ? swishf(t2[u]) : 0.f;
             dqL[i >> 6][i & 63] = t3[u];
         }
         __syncthreads();
+#pragma unroll 8
         for (int nn = 0; nn < TN; ++nn) {
             const float dtv = dtL[nn][cl], zv = zL[nn][cl];
-#pragma unroll
-            for (int u = 0; u < JMAX; ++u) {
-                const int j = jg + 8 * u;
-                if (j < Cse) {
-                    acc2[u] = fmaf(dtv, rL[nn][j], acc2[u]);
-                    acc1[u] = fmaf(dqL[nn][j], zv, acc1[u]);
-                }
-            }
+            const float4 r4 = *reinterpret_cast<const float4 *>(&rL[nn][4 * jq]);
+            const float4 q4 = *reinterpret_cast<const float4 *>(&dqL[nn][4 * jq]);
+            acc2[0] = fmaf(dtv, r4.x, acc2[0]);
+            acc2[1] = fmaf(dtv, r4.y, acc2[1]);
+            acc2[2] = fmaf(dtv, r4.z, acc2[2]);
+            acc2[3] = fmaf(dtv, r4.w, acc2[3]);
+            acc1[0] = fmaf(q4.x, zv, acc1[0]);
+            acc1[1] = fmaf(q4.y, zv, acc1[1]);
+            acc1[2] = fmaf(q4.z, zv, acc1[2]);
+            acc1[3] = fmaf(q4.w, zv, acc1[3]);
         }
     }
     if (c < C) {
 #pragma unroll
-        for (int u = 0; u < JMAX; ++u) {
-            const int j = jg + 8 * u;
+        for (int u = 0; u < 4; ++u) {
+            const int j = 4 * jq + u;
             if (j < Cse) {
                 a.dw2[(size_t)c * Cse + j] = acc2[u];
                 a.dw1[(size_t)j * C + c] = acc1[u];
             }
         }
     }
-    // per-channel sums: the eight thread groups take every eighth image, then group 0 adds
-    // the eight partial sums in order
+    // per-channel sums: the 16 thread groups take every 16th image, then group 0 adds the
+    // partial sums in order
     {
-        __shared__ float sbL[8][TC];
-        __shared__ double dbL[8][TC], dgL[8][TC];
         float sb = 0.f;
         double dbeta = 0.0, dgamma = 0.0;
         if (c < C) {
 #pragma unroll 4
-            for (int n = jg; n < N; n += 8) {
+            for (int n = jq; n < N; n += JQ) {
                 const size_t o = (size_t)n * C + c;
                 const float dtv = a.dt[o], gv = a.g[o], a1 = a.A1[o], a2 = a.A2[o];
                 const float dz = a.dzs[o], s3 = a.s3[o], s4 = a.s4[o];
@@ -530,14 +580,14 @@ __global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
                 dgamma += (double)gv * a2 + (double)dz * s4;
             }
         }
-        sbL[jg][cl] = sb;
-        dbL[jg][cl] = dbeta;
-        dgL[jg][cl] = dgamma;
+        sbL[jq][cl] = sb;
+        dbL[jq][cl] = dbeta;
+        dgL[jq][cl] = dgamma;
         __syncthreads();
-        if (jg == 0 && c < C) {
+        if (jq == 0 && c < C) {
             sb = 0.f;
             dbeta = dgamma = 0.0;
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < JQ; ++u) {
                 sb += sbL[u][cl];
                 dbeta += dbL[u][cl];
                 dgamma += dgL[u][cl];
@@ -550,10 +600,15 @@ __global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
     }
     if (blockIdx.x == 0 && tid >= 64 && tid - 64 < Cse) {
         const int j = tid - 64;
-        float sb = 0.f;
-        for (int n = 0; n < N; ++n)
-            sb += a.dq[(size_t)n * Cse + j];
-        a.db1[j] = sb;
+        float s0 = 0.f, s1 = 0.f;
+        int n = 0;
+        for (; n + 1 < N; n += 2) {
+            s0 += a.dq[(size_t)n * Cse + j];
+            s1 += a.dq[(size_t)(n + 1) * Cse + j];
+        }
+        if (n < N)
+            s0 += a.dq[(size_t)n * Cse + j];
+        a.db1[j] = s0 + s1;
     }
 }
 
@@ -567,7 +622,7 @@ hipError_t launch_se_bwd(const SeBwdArgs &a, hipStream_t st)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return e;
-        hipLaunchKernelGGL(se_bwd_batch_wide_kernel, dim3((a.C + 31) / 32), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(se_bwd_batch_wide_kernel, dim3((a.C + 15) / 16), dim3(256), 0, st, a);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(se_bwd_image_kernel, dim3(a.N), dim3(256), sizeof(float) * (a.C + a.Cse), st,
@@ -582,10 +637,10 @@ hipError_t launch_se_bwd(const SeBwdArgs &a, hipStream_t st)
 
 // out[c*inner+i] = sum_n in[(c*N+n)*inner+i].  Eight lanes share an output: lane s adds
 // the images s, s+8, ... and the eight partial sums are combined by a fixed butterfly.
-__global__ void reduce_planes_kernel(const float *__restrict__ in, int C, int N, int inner,
-                                     float *__restrict__ out)
+__device__ __forceinline__ void reduce_planes_body(int block, const float *__restrict__ in, int C,
+                                                   int N, int inner, float *__restrict__ out)
 {
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int gid = block * 256 + threadIdx.x;
     const int i = gid >> 3, sub = gid & 7;
     float s = 0.f;
     if (i < C * inner) {
@@ -606,6 +661,43 @@ __global__ void reduce_planes_kernel(const float *__restrict__ in, int C, int N,
     s += __shfl_xor(s, 1, kWave);
     if (sub == 0 && i < C * inner)
         out[i] = s;
+}
+
+__global__ __launch_bounds__(256) void reduce_planes_kernel(const float *__restrict__ in, int C,
+                                                            int N, int inner,
+                                                            float *__restrict__ out)
+{
+    reduce_planes_body(blockIdx.x, in, C, N, inner, out);
+}
+
+// The two second stages that follow the fused depthwise backward, in one launch: the first nb1
+// workgroups add the filter-gradient partials, the others finalise BN1's backward.
+__global__ __launch_bounds__(256) void dw_bwd_finalize_kernel(int nb1, const float *__restrict__ pdw,
+                                                              int C, int NP, int inner,
+                                                              float *__restrict__ dw, double m,
+                                                              const float *__restrict__ psb,
+                                                              const float *__restrict__ psr,
+                                                              const float *__restrict__ gamma,
+                                                              const float *__restrict__ bn,
+                                                              float *dgamma, float *dbeta,
+                                                              float *coef)
+{
+    if ((int)blockIdx.x < nb1)
+        reduce_planes_body(blockIdx.x, pdw, C, NP, inner, dw);
+    else
+        bn_bwd_finalize_body(blockIdx.x - nb1, C, NP, m, psb, psr, gamma, bn, dgamma, dbeta, coef);
+}
+
+hipError_t launch_dw_bwd_finalize(const float *pdw, int C, int NP, int inner, float *dw, double m,
+                                  const float *psb, const float *psr, const float *gamma,
+                                  const float *bn, float *dgamma, float *dbeta, float *coef,
+                                  hipStream_t st)
+{
+    const long long total = (long long)C * inner * 8;
+    const int nb1 = (int)((total + 255) / 256), nb2 = (C + 3) / 4;
+    hipLaunchKernelGGL(dw_bwd_finalize_kernel, dim3((unsigned)(nb1 + nb2)), dim3(256), 0, st, nb1, pdw,
+                       C, NP, inner, dw, m, psb, psr, gamma, bn, dgamma, dbeta, coef);
+    return hipGetLastError();
 }
 
 hipError_t launch_reduce_planes(const float *in, int C, int N, int inner, float *out,

@@ -479,14 +479,21 @@ mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_param
         a.psb = pa;
         a.psr = pb;
         MBK_STEP(MBCONV_STEP_DW_BWD, launch_dw_bwd(bf, a, st));
-        MBK_STEP(MBCONV_STEP_DW_WGRAD_REDUCE, launch_reduce_planes(a.pdw, P.Cexp, P.NPdw, P.k * P.k, gr->w_dw, st));
+        if (P.expand) {
+            // one launch: filter-gradient partials and BN1's backward finalisation
+            MBK_STEP(MBCONV_STEP_DW_WGRAD_REDUCE,
+                     launch_dw_bwd_finalize(a.pdw, P.Cexp, P.NPdw, P.k * P.k, gr->w_dw, (double)P.N * P.HW, pa,
+                                            pb, prm->bn1_gamma, bn1, gr->bn1_gamma, gr->bn1_beta,
+                                            at<float>(scratch, P.o_coef1), st));
+        } else {
+            MBK_STEP(MBCONV_STEP_DW_WGRAD_REDUCE, launch_reduce_planes(a.pdw, P.Cexp, P.NPdw, P.k * P.k, gr->w_dw, st));
+        }
     }
     if (P.expand) {
         float *coef1 = at<float>(scratch, P.o_coef1);
         const void *e = at<char>(saved, P.o_e);
         const void *dy1 = at<char>(scratch, P.o_dy1);
-        MBK_STEP(MBCONV_STEP_BN1_BWD_FINALIZE, launch_bn_bwd_finalize(P.Cexp, P.NPdw, (double)P.N * P.HW, pa, pb, prm->bn1_gamma, bn1,
-                                       gr->bn1_gamma, gr->bn1_beta, coef1, st));
+        MBK_STEP(MBCONV_STEP_BN1_BWD_FINALIZE, hipSuccess); // done by the launch above
         Operand de;
         de.p0 = dy1;
         de.p1 = e;

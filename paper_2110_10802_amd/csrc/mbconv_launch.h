@@ -129,5 +129,11 @@ hipError_t launch_dw_bwd(bool bf16, const DwBwdArgs &a, hipStream_t st);
 hipError_t launch_reduce_splits(const float *in, int S, size_t count, float *out, hipStream_t st);
 hipError_t launch_reduce_planes(const float *in, int C, int N, int inner, float *out,
                                 hipStream_t st);
+// launch_reduce_planes(pdw, C, NP, inner, dw) and launch_bn_bwd_finalize(C, NP, m, psb, ...)
+// in one launch (both consume the partial results of the fused depthwise backward).
+hipError_t launch_dw_bwd_finalize(const float *pdw, int C, int NP, int inner, float *dw, double m,
+                                  const float *psb, const float *psr, const float *gamma,
+                                  const float *bn, float *dgamma, float *dbeta, float *coef,
+                                  hipStream_t st);
 
 } // namespace mbk
