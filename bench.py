@@ -8,7 +8,8 @@ inputs that are already resident in HBM.  The default workload is benchmark conf
 (EfficientNet-B0 stage-2 repeat block, fp32, batch 32).  Prints ONE JSON line:
   value      images/s over the whole job
   roofline   the slowest kernel of the step, timed live with HIP events recorded on the launch
-             stream inside the timed region, against the HBM roofline (algorithmic bytes)
+             stream inside the timed region (less the measured gap of an empty event pair),
+             against the HBM roofline (algorithmic bytes)
   cpu_baseline  the fp64 CPU oracle timed on this host (a reported baseline, not a target)
 """
 from __future__ import annotations
@@ -28,7 +29,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # HBM bytes measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
 # counters' reading on a plain copy kernel of known size; per launch, keyed by
 # (workload, step).  Filled from the summaries under profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/config1_fp32_kernel_stats.md: dw4_bwd fetch 165.9 MiB + write 55.4 MiB
+    ("config1", "dw_bwd"): int((165.9 + 55.4) * 2 ** 20),
+}
 
 
 def algorithmic_bytes(s, step: str):
@@ -58,6 +62,7 @@ class HipEvents:
         self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
         self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
 
     def create(self) -> C.c_void_p:
         ev = C.c_void_p()
@@ -75,6 +80,27 @@ class HipEvents:
 
     def destroy(self, ev):
         self.hip.hipEventDestroy(ev)
+
+    def record(self, ev, stream):
+        rc = self.hip.hipEventRecord(ev, C.c_void_p(stream))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed ({rc})")
+
+    def pair_overhead_ms(self, stream, work, reps=20) -> float:
+        """Time between two events recorded back to back behind queued work: the part of an
+        event-bracketed kernel time that is not the kernel (median of `reps`)."""
+        import torch
+        a, b = self.create(), self.create()
+        vals = []
+        for _ in range(reps):
+            work()
+            self.record(a, stream)
+            self.record(b, stream)
+            torch.cuda.synchronize()
+            vals.append(self.elapsed_ms(a, b))
+        self.destroy(a)
+        self.destroy(b)
+        return sorted(vals)[len(vals) // 2]
 
 
 def cpu_baseline(shape, tensors):
@@ -176,7 +202,9 @@ def run_chain(args) -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = sum(ev.elapsed_ms(a, b) for a, b in pairs) / args.steps
+    kern_ms_raw = sum(ev.elapsed_ms(a, b) for a, b in pairs) / args.steps
+    overhead_ms = ev.pair_overhead_ms(stream, step, reps=5)
+    kern_ms = max(kern_ms_raw - overhead_ms, 1e-6)
     nbytes = algorithmic_bytes(shapes[bi], dominant)
     achieved = nbytes / (kern_ms * 1e-3) / 1e9
     N = shapes[0].N
@@ -189,7 +217,8 @@ def run_chain(args) -> int:
                    "32ch 112x112 in", "policy": args.policy},
         "roofline": {"bound": "hbm", "kernel": f"block{bi + 1}:{dominant}", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel_ms": kern_ms, "algorithmic_bytes": nbytes},
+                     "traffic": None, "kernel_ms": kern_ms, "kernel_ms_with_event_gap": kern_ms_raw,
+                     "event_gap_ms": overhead_ms, "algorithmic_bytes": nbytes},
         "block_ms_survey": [round(sum(r.values()), 5) for r in survey],
     }
     print(json.dumps(result))
@@ -283,10 +312,14 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = sum(ev.elapsed_ms(a, b) for a, b in pairs) / args.steps
+    kern_ms_raw = sum(ev.elapsed_ms(a, b) for a, b in pairs) / args.steps
     for a, b in pairs:
         ev.destroy(a)
         ev.destroy(b)
+    # an event pair around a kernel also spans the gap between two event records; that gap is
+    # measured with an empty pair behind the same queued work and taken off
+    overhead_ms = ev.pair_overhead_ms(stream, step)
+    kern_ms = max(kern_ms_raw - overhead_ms, 1e-6)
 
     if args.pmc_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -317,7 +350,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((workload, dominant)),
-                     "kernel_ms": kern_ms, "algorithmic_bytes": nbytes},
+                     "kernel_ms": kern_ms, "kernel_ms_with_event_gap": kern_ms_raw,
+                     "event_gap_ms": overhead_ms, "algorithmic_bytes": nbytes},
         "step_ms_survey": {n: round(v, 5) for n, v in survey.items()},
     }
     if not args.no_cpu_baseline:

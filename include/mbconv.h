@@ -171,8 +171,9 @@ typedef enum {
     MBCONV_STEP_GATE_SUMS = 14,
     MBCONV_STEP_SE_BWD = 15,
     MBCONV_STEP_DW_BWD = 16,       /* BN2 backward + depthwise dgrad/wgrad + Swish' + BN1 partials */
-    MBCONV_STEP_DW_WGRAD_REDUCE = 17,
-    MBCONV_STEP_BN1_BWD_FINALIZE = 18,
+    MBCONV_STEP_DW_WGRAD_REDUCE = 17,  /* sum of the filter-gradient partials; with an expansion conv the same
+                                          launch also finalises BN1's backward */
+    MBCONV_STEP_BN1_BWD_FINALIZE = 18, /* launches nothing (see step 17): a probe on it times an empty event pair */
     MBCONV_STEP_EXPAND_DGRAD = 19,
     MBCONV_STEP_EXPAND_WGRAD = 20,
     MBCONV_STEP_COUNT = 21
