@@ -1,0 +1,590 @@
+// bf16 storage on the bf16 matrix cores: 1x1 convolutions and weight gradients for the wide
+// blocks when activations and conv weights are stored as bf16 (benchmark config 3).
+//
+// Same decomposition as kernels_big.hip (flattened batch, 64x64 output tile per workgroup of four
+// wavefronts, two LDS buffers, next chunk's global loads issued before the current chunk's
+// MFMAs, fixed-order split reductions), but the operands are kept as bf16 in LDS and contracted
+// with v_mfma_f32_32x32x16_bf16 (fp32 accumulation), which is 16 times the fp32 MFMA rate: these
+// GEMMs then cost what their HBM traffic costs.  The elementwise prologue (Swish(BN(.))*gate or
+// the BN-backward expression) is evaluated in fp32 and rounded to bf16 once, on the way into LDS.
+//
+// Operand layout of the instruction (checked on the device): lane l holds, of A, row l%32 and the
+// eight contraction indices 8*(l/32)..+7; of B, column l%32 and the same eight indices.  Both
+// LDS tiles are therefore stored [row or column][k] with k contiguous, pitch BK+8 elements
+// (80 or 144 bytes: 16-byte aligned rows whose 16-byte reads fall on distinct banks).
+#include "mbconv_dev.h"
+#include "mbconv_launch.h"
+
+namespace mbk {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct BfOperand {
+    const bf16_t *p0, *p1;
+    const float *c0, *c1, *c2, *gate;
+};
+
+__device__ __forceinline__ uint32_t bf_pack2(float lo, float hi)
+{
+    return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+}
+__device__ __forceinline__ void bf_unpack4(uint2 t, float (&v)[4])
+{
+    v[0] = bf16_bits_to_float(t.x & 0xffffu);
+    v[1] = bf16_bits_to_float(t.x >> 16);
+    v[2] = bf16_bits_to_float(t.y & 0xffffu);
+    v[3] = bf16_bits_to_float(t.y >> 16);
+}
+template <int PRO>
+__device__ __forceinline__ float bf_apply(float v0, float v1, float k0, float k1, float k2)
+{
+    if (PRO == PRO_NONE)
+        return v0;
+    if (PRO == PRO_BNSWISH_GATE)
+        return swishf(fmaf(v0, k0, k1)) * k2;
+    return fmaf(k0, v0, fmaf(k1, v1, k2));
+}
+__device__ __forceinline__ bf16x8 bf_lds8(const uint16_t *p)
+{
+    return *reinterpret_cast<const bf16x8 *>(p);
+}
+
+// ---- convolution ---------------------------------------------------------------------------
+struct BfConvArgs {
+    int M, K, HW;
+    uint32_t Q;
+    FastDiv divHW;
+    const bf16_t *w;
+    int sAm, sAk;
+    BfOperand B;
+    bf16_t *out;
+    const bf16_t *res;
+    float *psum, *psq;
+    int QT, MT;
+    float *partial;
+    int chunksPerSplit;
+};
+
+// out[n,m,pix] = sum_k A(m,k) * op(B)[n,k,pix].  Requirements (checked by the host):
+// K % 8 == 0, M % 8 == 0, HW % 4 == 0, one of sAm/sAk equal to 1.
+template <int PRO, int EPI>
+__global__ __launch_bounds__(256) void conv_bf_kernel(BfConvArgs a)
+{
+    constexpr int BM = 64, BP = 64, BK = 32, PK = BK + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM][PK];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BP][PK];
+    __shared__ float red[2][BM][2];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wp = wave & 1;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int qt = (slot / a.MT) * 8 + xcd, mt = slot % a.MT;
+    if (qt >= a.QT)
+        return;
+    const int m0 = mt * BM;
+    const uint32_t q0 = (uint32_t)qt * BP;
+    const bool kcontig = a.sAk == 1;
+
+    // A staging.  k-contiguous weights: thread -> (row tid/4, eight k at 8*(tid%4)), a straight
+    // 16-byte copy.  m-contiguous weights (data gradients): thread -> (k = tid%32, eight rows at
+    // 8*(tid/32)), transposed with 2-byte LDS stores.
+    uint4 ra;
+    bool ra_ok;
+    auto load_a = [&](int k0) __attribute__((always_inline)) {
+        if (kcontig) {
+            const int m = m0 + (tid >> 2), k = k0 + 8 * (tid & 3);
+            ra_ok = m < a.M && k < a.K;
+            ra = *reinterpret_cast<const uint4 *>(a.w + (size_t)min(m, a.M - 1) * a.sAm + min(k, a.K - 8));
+        } else {
+            const int k = k0 + (tid & 31), m = m0 + 8 * (tid >> 5);
+            ra_ok = m < a.M && k < a.K;
+            ra = *reinterpret_cast<const uint4 *>(a.w + (size_t)min(k, a.K - 1) * a.sAk + min(m, a.M - 8));
+        }
+    };
+    auto store_a = [&](int buf) __attribute__((always_inline)) {
+        const uint4 v = ra_ok ? ra : make_uint4(0u, 0u, 0u, 0u);
+        if (kcontig) {
+            *reinterpret_cast<uint4 *>(&As[buf][tid >> 2][8 * (tid & 3)]) = v;
+        } else {
+            const int kk = tid & 31, mm = 8 * (tid >> 5);
+            As[buf][mm + 0][kk] = (uint16_t)(v.x & 0xffffu);
+            As[buf][mm + 1][kk] = (uint16_t)(v.x >> 16);
+            As[buf][mm + 2][kk] = (uint16_t)(v.y & 0xffffu);
+            As[buf][mm + 3][kk] = (uint16_t)(v.y >> 16);
+            As[buf][mm + 4][kk] = (uint16_t)(v.z & 0xffffu);
+            As[buf][mm + 5][kk] = (uint16_t)(v.z >> 16);
+            As[buf][mm + 6][kk] = (uint16_t)(v.w & 0xffffu);
+            As[buf][mm + 7][kk] = (uint16_t)(v.w >> 16);
+        }
+    };
+
+    // B staging: thread -> (four pixels at 4*(tid%16), channel pair 2*(tid/16)); the pair of a
+    // pixel is packed into one 32-bit LDS store.  The pixel run is the same for every chunk.
+    const int pg = tid & 15, kp = tid >> 4;
+    const uint32_t qb = q0 + 4u * pg;
+    const bool bvalid = qb < a.Q;
+    const uint32_t bn = bvalid ? fdiv(qb, a.divHW) : 0u;
+    const size_t bbase = (size_t)bn * a.K * a.HW + (bvalid ? qb - bn * (uint32_t)a.HW : 0u);
+    uint2 rb0[2], rb1[2];
+    float bk0[2], bk1[2], bk2[2];
+    bool rb_ok[2];
+    auto load_b = [&](int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int k = k0 + 2 * kp + i, kc = min(k, a.K - 1);
+            rb_ok[i] = bvalid && k < a.K;
+            rb0[i] = *reinterpret_cast<const uint2 *>(a.B.p0 + bbase + (size_t)kc * a.HW);
+            if (PRO == PRO_BNBWD)
+                rb1[i] = *reinterpret_cast<const uint2 *>(a.B.p1 + bbase + (size_t)kc * a.HW);
+            if (PRO != PRO_NONE) {
+                bk0[i] = a.B.c0[kc];
+                bk1[i] = a.B.c1[kc];
+                bk2[i] = PRO == PRO_BNBWD ? a.B.c2[kc] : a.B.gate[(size_t)bn * a.K + kc];
+            }
+        }
+    };
+    auto store_b = [&](int buf) __attribute__((always_inline)) {
+        float v[2][4];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            float x0[4], x1[4] = {0.f, 0.f, 0.f, 0.f};
+            bf_unpack4(rb0[i], x0);
+            if (PRO == PRO_BNBWD)
+                bf_unpack4(rb1[i], x1);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                v[i][r] = rb_ok[i] ? bf_apply<PRO>(x0[r], x1[r], bk0[i], bk1[i], bk2[i]) : 0.f;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + r][2 * kp]) = bf_pack2(v[0][r], v[1][r]);
+    };
+
+    float16v acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        acc[r] = 0.f;
+
+    int cbeg = 0, cend = (a.K + BK - 1) / BK;
+    if (EPI == EPI_PARTIAL) {
+        cbeg = blockIdx.y * a.chunksPerSplit;
+        cend = min(cbeg + a.chunksPerSplit, cend);
+    }
+    load_a(cbeg * BK);
+    load_b(cbeg * BK);
+    store_a(0);
+    store_b(0);
+    __syncthreads();
+    for (int c = cbeg; c < cend; ++c) {
+        const int buf = (c - cbeg) & 1;
+        const bool more = c + 1 < cend;
+        if (more) {
+            load_a((c + 1) * BK);
+            load_b((c + 1) * BK);
+        }
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            const bf16x8 av = bf_lds8(&As[buf][wm * 32 + (lane & 31)][16 * s + 8 * (lane >> 5)]);
+            const bf16x8 bv = bf_lds8(&Bs[buf][wp * 32 + (lane & 31)][16 * s + 8 * (lane >> 5)]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+        }
+        if (more) {
+            store_a(buf ^ 1);
+            store_b(buf ^ 1);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: register r of lane l is row 8*(r/4)+4*(l/32)+r%4, column l%32
+    float rs[16], rq[16];
+    const uint32_t q = q0 + wp * 32 + (lane & 31);
+    const bool valid = q < a.Q;
+    const uint32_t n = valid ? fdiv(q, a.divHW) : 0u;
+    const uint32_t pix = valid ? q - n * (uint32_t)a.HW : 0u;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        rs[r] = rq[r] = 0.f;
+        const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (EPI == EPI_PARTIAL) {
+            if (valid && m < a.M)
+                a.partial[((size_t)blockIdx.y * a.M + m) * a.Q + q] = acc[r];
+        } else if (valid && m < a.M) {
+            float v = acc[r];
+            const size_t idx = ((size_t)n * a.M + m) * a.HW + pix;
+            if (EPI == EPI_RES)
+                v += ld<bf16_t>(a.res, idx);
+            st<bf16_t>(a.out, idx, v);
+            if (EPI == EPI_STATS) {
+                const float sv = as_stored<bf16_t>(v);
+                rs[r] = sv;
+                rq[r] = sv * sv;
+            }
+        }
+    }
+    if (EPI == EPI_STATS) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float s = half_wave_sum_dpp(rs[r]);
+            const float s2 = half_wave_sum_dpp(rq[r]);
+            if ((lane & 31) == 0) {
+                const int row = wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                red[0][row][wp] = s;
+                red[1][row][wp] = s2;
+            }
+        }
+        __syncthreads();
+        if (tid < BM && m0 + tid < a.M) {
+            a.psum[(size_t)(m0 + tid) * a.QT + qt] = red[0][tid][0] + red[0][tid][1];
+            a.psq[(size_t)(m0 + tid) * a.QT + qt] = red[1][tid][0] + red[1][tid][1];
+        }
+    }
+}
+
+// second stage of a split convolution (see splitk_finish_kernel in kernels_big.hip)
+template <int EPI>
+__global__ __launch_bounds__(256) void bf_splitk_finish_kernel(const float *__restrict__ partial, int S,
+                                                               int M, uint32_t Q, FastDiv divHW, int HW,
+                                                               bf16_t *out, const bf16_t *res,
+                                                               float *psum, float *psq, int NT)
+{
+    __shared__ float red[2][4];
+    const int m = blockIdx.y, tid = threadIdx.x;
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t q = blockIdx.x * 1024u + 256u * i + tid;
+        if (q < Q) {
+            float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+            const float *src = partial + (size_t)m * Q + q;
+            const size_t step = (size_t)M * Q;
+            int s = 0;
+            for (; s + 3 < S; s += 4) {
+                v0 += src[(size_t)s * step];
+                v1 += src[(size_t)(s + 1) * step];
+                v2 += src[(size_t)(s + 2) * step];
+                v3 += src[(size_t)(s + 3) * step];
+            }
+            for (; s < S; ++s)
+                v0 += src[(size_t)s * step];
+            float v = (v0 + v1) + (v2 + v3);
+            const uint32_t n = fdiv(q, divHW), pix = q - n * (uint32_t)HW;
+            const size_t idx = ((size_t)n * M + m) * HW + pix;
+            if (EPI == EPI_RES)
+                v += ld<bf16_t>(res, idx);
+            st<bf16_t>(out, idx, v);
+            if (EPI == EPI_STATS) {
+                const float sv = as_stored<bf16_t>(v);
+                s1 += sv;
+                s2 = fmaf(sv, sv, s2);
+            }
+        }
+    }
+    if (EPI == EPI_STATS) {
+        s1 = wave_sum(s1);
+        s2 = wave_sum(s2);
+        if ((tid & 63) == 0) {
+            red[0][tid >> 6] = s1;
+            red[1][tid >> 6] = s2;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            psum[(size_t)m * NT + blockIdx.x] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+            psq[(size_t)m * NT + blockIdx.x] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+        }
+    }
+}
+
+// Plan: 64x64 tiles; the contraction is split when the tiles alone cannot fill the chip.
+bool bf_conv_plan(int N, int M, int K, int HW, int *qtiles, int *splits)
+{
+    const long long Q = (long long)N * HW;
+    if (K % 8 != 0 || M % 8 != 0 || HW % 4 != 0 || Q >= (1ll << 31) || K < 32)
+        return false;
+    *qtiles = (int)((Q + 63) / 64);
+    *splits = 1;
+    const long long tiles = (long long)*qtiles * ((M + 63) / 64);
+    const int chunks = (K + 31) / 32;
+    if (tiles < 384 && chunks >= 8) {
+        long long s = (768 + tiles - 1) / tiles;
+        if (s > chunks / 2)
+            s = chunks / 2;
+        if (s > 16)
+            s = 16;
+        const int per = (int)((chunks + s - 1) / s);
+        *splits = (chunks + per - 1) / per;
+        if (*splits > 1)
+            *qtiles = (int)((Q + 1023) / 1024);
+    }
+    return true;
+}
+
+size_t bf_conv_splitk_floats(int N, int M, int K, int HW)
+{
+    int qtiles, splits;
+    if (!bf_conv_plan(N, M, K, HW, &qtiles, &splits) || splits == 1)
+        return 0;
+    return (size_t)splits * M * N * HW;
+}
+
+hipError_t launch_bf_conv1x1(int N, int M, int K, int HW, const void *w, int sAm, int sAk,
+                             const Operand &B, void *out, int epi, const void *res, float *psum,
+                             float *psq, float *splitk_ws, hipStream_t st)
+{
+    int qtiles, splits;
+    if (!bf_conv_plan(N, M, K, HW, &qtiles, &splits) || (sAm != 1 && sAk != 1))
+        return hipErrorInvalidValue;
+    if (splits > 1 && !splitk_ws)
+        return hipErrorInvalidValue;
+    BfConvArgs a;
+    a.M = M;
+    a.K = K;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    a.divHW = make_div((uint32_t)HW);
+    a.w = (const bf16_t *)w;
+    a.sAm = sAm;
+    a.sAk = sAk;
+    a.B.p0 = (const bf16_t *)B.p0;
+    a.B.p1 = (const bf16_t *)B.p1;
+    a.B.c0 = B.c0;
+    a.B.c1 = B.c1;
+    a.B.c2 = B.c2;
+    a.B.gate = B.gate;
+    a.out = (bf16_t *)out;
+    a.res = (const bf16_t *)res;
+    a.psum = psum;
+    a.psq = psq;
+    a.QT = (int)((a.Q + 63u) / 64u);
+    a.MT = (M + 63) / 64;
+    a.partial = splitk_ws;
+    const int chunks = (K + 31) / 32;
+    a.chunksPerSplit = (chunks + splits - 1) / splits;
+    dim3 grid((unsigned)(((a.QT + 7) / 8) * 8 * a.MT), (unsigned)splits);
+    const int kepi = splits > 1 ? EPI_PARTIAL : epi;
+    hipError_t e = hipErrorInvalidValue;
+#define MBK_CASE(P, E)                                                                            \
+    if (B.pro == P && kepi == E) {                                                                \
+        hipLaunchKernelGGL((conv_bf_kernel<P, E>), grid, dim3(256), 0, st, a);                    \
+        e = hipGetLastError();                                                                    \
+    }
+    MBK_CASE(PRO_NONE, EPI_STATS)
+    MBK_CASE(PRO_BNSWISH_GATE, EPI_STATS)
+    MBK_CASE(PRO_BNBWD, EPI_NONE)
+    MBK_CASE(PRO_BNBWD, EPI_RES)
+    MBK_CASE(PRO_NONE, EPI_PARTIAL)
+    MBK_CASE(PRO_BNSWISH_GATE, EPI_PARTIAL)
+    MBK_CASE(PRO_BNBWD, EPI_PARTIAL)
+#undef MBK_CASE
+    if (e != hipSuccess || splits == 1)
+        return e;
+    dim3 fgrid((unsigned)qtiles, (unsigned)M);
+    const FastDiv dv = make_div((uint32_t)HW);
+#define MBK_CASE(E)                                                                               \
+    if (epi == E) {                                                                               \
+        hipLaunchKernelGGL((bf_splitk_finish_kernel<E>), fgrid, dim3(256), 0, st, splitk_ws, splits, \
+                           M, a.Q, dv, HW, a.out, a.res, psum, psq, qtiles);                      \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(EPI_NONE)
+    MBK_CASE(EPI_STATS)
+    MBK_CASE(EPI_RES)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+// ---- weight gradient -------------------------------------------------------------------------
+// dW[a,b] = sum_q op(U)[a,q] * op(V)[b,q]: both operands are pixel-contiguous, which is exactly
+// the [row][k] layout the instruction wants, so the tiles go into LDS untransposed (8-byte runs
+// of four pixels per thread).  64 pixels per chunk; the contraction is split over blockIdx.z.
+struct BfWgradArgs {
+    int Ma, Mb, HW;
+    uint32_t Q;
+    int chunksPerSplit; // chunks of 64 pixels
+    FastDiv divHW;
+    BfOperand U, V;
+    float *partial;
+};
+
+template <int PROU, int PROV>
+__global__ __launch_bounds__(256) void wgrad_bf_kernel(BfWgradArgs a)
+{
+    constexpr int BA = 64, BQ = 64, PQ = BQ + 8, NR = 4; // 16 rows per pass, four passes
+    __shared__ __attribute__((aligned(16))) uint16_t Us[2][BA][PQ];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[2][BA][PQ];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wa = wave >> 1, wb = wave & 1;
+    const int a0 = blockIdx.x * BA, b0 = blockIdx.y * BA;
+    const int numChunks = (int)((a.Q + BQ - 1) / BQ);
+    const int cbeg = blockIdx.z * a.chunksPerSplit;
+    const int cend = min(cbeg + a.chunksPerSplit, numChunks);
+
+    const int qg = tid & 15, rrow = tid >> 4;
+    float uk[NR][3], vk[NR][3];
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        const int ra = a0 + rrow + 16 * i, rb = b0 + rrow + 16 * i;
+        uk[i][0] = uk[i][1] = uk[i][2] = vk[i][0] = vk[i][1] = vk[i][2] = 0.f;
+        if (PROU != PRO_NONE && ra < a.Ma) {
+            uk[i][0] = a.U.c0[ra];
+            uk[i][1] = a.U.c1[ra];
+            if (PROU == PRO_BNBWD)
+                uk[i][2] = a.U.c2[ra];
+        }
+        if (PROV != PRO_NONE && rb < a.Mb) {
+            vk[i][0] = a.V.c0[rb];
+            vk[i][1] = a.V.c1[rb];
+            if (PROV == PRO_BNBWD)
+                vk[i][2] = a.V.c2[rb];
+        }
+    }
+    uint2 u0[NR], u1[NR], v0[NR], v1[NR];
+    float ug[NR], vg[NR];
+    bool staged_valid = false;
+    auto load = [&](int chunk) __attribute__((always_inline)) {
+        const uint32_t q = (uint32_t)chunk * BQ + 4u * qg;
+        staged_valid = q < a.Q;
+        const uint32_t qc = staged_valid ? q : 0u;
+        const uint32_t n = fdiv(qc, a.divHW);
+        const uint32_t pix = qc - n * (uint32_t)a.HW;
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const int ra = min(a0 + rrow + 16 * i, a.Ma - 1), rb = min(b0 + rrow + 16 * i, a.Mb - 1);
+            const size_t iu = ((size_t)n * a.Ma + ra) * a.HW + pix, iv = ((size_t)n * a.Mb + rb) * a.HW + pix;
+            u0[i] = *reinterpret_cast<const uint2 *>(a.U.p0 + iu);
+            if (PROU == PRO_BNBWD)
+                u1[i] = *reinterpret_cast<const uint2 *>(a.U.p1 + iu);
+            if (PROU == PRO_BNSWISH_GATE)
+                ug[i] = a.U.gate[(size_t)n * a.Ma + ra];
+            v0[i] = *reinterpret_cast<const uint2 *>(a.V.p0 + iv);
+            if (PROV == PRO_BNBWD)
+                v1[i] = *reinterpret_cast<const uint2 *>(a.V.p1 + iv);
+            if (PROV == PRO_BNSWISH_GATE)
+                vg[i] = a.V.gate[(size_t)n * a.Mb + rb];
+        }
+    };
+    auto store = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const int row = rrow + 16 * i;
+            float x0[4], x1[4] = {0.f, 0.f, 0.f, 0.f}, y[4];
+            bf_unpack4(u0[i], x0);
+            if (PROU == PRO_BNBWD)
+                bf_unpack4(u1[i], x1);
+            const bool uok = staged_valid && a0 + row < a.Ma;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                y[r] = uok ? bf_apply<PROU>(x0[r], x1[r], uk[i][0], uk[i][1],
+                                            PROU == PRO_BNSWISH_GATE ? ug[i] : uk[i][2])
+                           : 0.f;
+            *reinterpret_cast<uint2 *>(&Us[buf][row][4 * qg]) =
+                make_uint2(bf_pack2(y[0], y[1]), bf_pack2(y[2], y[3]));
+            bf_unpack4(v0[i], x0);
+            if (PROV == PRO_BNBWD)
+                bf_unpack4(v1[i], x1);
+            const bool vok = staged_valid && b0 + row < a.Mb;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                y[r] = vok ? bf_apply<PROV>(x0[r], x1[r], vk[i][0], vk[i][1],
+                                            PROV == PRO_BNSWISH_GATE ? vg[i] : vk[i][2])
+                           : 0.f;
+            *reinterpret_cast<uint2 *>(&Vs[buf][row][4 * qg]) =
+                make_uint2(bf_pack2(y[0], y[1]), bf_pack2(y[2], y[3]));
+        }
+    };
+
+    float16v acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        acc[r] = 0.f;
+    if (cbeg < cend) {
+        load(cbeg);
+        store(0);
+    }
+    __syncthreads();
+    for (int c = cbeg; c < cend; ++c) {
+        const int buf = (c - cbeg) & 1;
+        const bool more = c + 1 < cend;
+        if (more)
+            load(c + 1);
+#pragma unroll
+        for (int s = 0; s < BQ / 16; ++s) {
+            const bf16x8 av = bf_lds8(&Us[buf][wa * 32 + (lane & 31)][16 * s + 8 * (lane >> 5)]);
+            const bf16x8 bv = bf_lds8(&Vs[buf][wb * 32 + (lane & 31)][16 * s + 8 * (lane >> 5)]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+        }
+        if (more)
+            store(buf ^ 1);
+        __syncthreads();
+    }
+    float *dst = a.partial + (size_t)blockIdx.z * a.Ma * a.Mb;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int ai = a0 + wa * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int bi = b0 + wb * 32 + (lane & 31);
+        if (ai < a.Ma && bi < a.Mb)
+            dst[(size_t)ai * a.Mb + bi] = acc[r];
+    }
+}
+
+bool bf_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits)
+{
+    const long long Q = (long long)N * HW;
+    if (HW % 4 != 0 || Q >= (1ll << 31))
+        return false;
+    const long long tiles = (long long)((Ma + 63) / 64) * ((Mb + 63) / 64);
+    const long long chunks = (Q + 63) / 64;
+    long long s = (640 + tiles - 1) / tiles;
+    const long long smax = (chunks + 3) / 4; // at least four chunks per split
+    if (s > smax)
+        s = smax;
+    if (s < 1)
+        s = 1;
+    const long long per = (chunks + s - 1) / s;
+    *splits = (int)((chunks + per - 1) / per);
+    return true;
+}
+
+hipError_t launch_bf_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
+                           float *partial, int *splits_out, hipStream_t st)
+{
+    int splits;
+    if (!bf_wgrad_plan(Ma, Mb, N, HW, &splits))
+        return hipErrorInvalidValue;
+    BfWgradArgs a;
+    a.Ma = Ma;
+    a.Mb = Mb;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    const int chunks = (int)((a.Q + 63u) / 64u);
+    a.chunksPerSplit = (chunks + splits - 1) / splits;
+    a.divHW = make_div((uint32_t)HW);
+    a.U.p0 = (const bf16_t *)U.p0;
+    a.U.p1 = (const bf16_t *)U.p1;
+    a.U.c0 = U.c0;
+    a.U.c1 = U.c1;
+    a.U.c2 = U.c2;
+    a.U.gate = U.gate;
+    a.V.p0 = (const bf16_t *)V.p0;
+    a.V.p1 = (const bf16_t *)V.p1;
+    a.V.c0 = V.c0;
+    a.V.c1 = V.c1;
+    a.V.c2 = V.c2;
+    a.V.gate = V.gate;
+    a.partial = partial;
+    *splits_out = splits;
+    dim3 grid((unsigned)((Ma + 63) / 64), (unsigned)((Mb + 63) / 64), (unsigned)splits);
+#define MBK_CASE(PU, PV)                                                                          \
+    if (U.pro == PU && V.pro == PV) {                                                             \
+        hipLaunchKernelGGL((wgrad_bf_kernel<PU, PV>), grid, dim3(256), 0, st, a);                 \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(PRO_BNBWD, PRO_NONE)
+    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+} // namespace mbk

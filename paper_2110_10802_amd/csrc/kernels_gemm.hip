@@ -213,21 +213,36 @@ bool big_wgrad_plan(int Ma, int Mb, int N, int HW, int *wt, int *splits);
 hipError_t launch_big_wgrad(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
                             const Operand &V, float *partial, int *splits_out, hipStream_t st);
 
-int conv1x1_num_partials(int N, int M, int K, int HW, bool stores_operand)
+// kernels_bf.hip
+bool bf_conv_plan(int N, int M, int K, int HW, int *qtiles, int *splits);
+size_t bf_conv_splitk_floats(int N, int M, int K, int HW);
+hipError_t launch_bf_conv1x1(int N, int M, int K, int HW, const void *w, int sAm, int sAk,
+                             const Operand &B, void *out, int epi, const void *res, float *psum,
+                             float *psq, float *splitk_ws, hipStream_t st);
+bool bf_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits);
+hipError_t launch_bf_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
+                           float *partial, int *splits_out, hipStream_t st);
+
+int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand)
 {
     const int kind = stores_operand ? 0 : wave_conv_kind(M, K, HW);
     if (kind)
         return wave_conv_num_partials(kind, N, HW);
     int wt, qtiles, splits;
+    if (bf16 && !stores_operand && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
+        return qtiles;
     if (!stores_operand && big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits))
         return qtiles;
     return conv1x1_num_qtiles(N, HW);
 }
 
-size_t conv1x1_splitk_floats(int N, int M, int K, int HW, bool stores_operand)
+size_t conv1x1_splitk_floats(bool bf16, int N, int M, int K, int HW, bool stores_operand)
 {
     if (stores_operand || wave_conv_kind(M, K, HW))
         return 0;
+    int qtiles, splits;
+    if (bf16 && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
+        return bf_conv_splitk_floats(N, M, K, HW);
     return big_conv_splitk_floats(N, M, K, HW);
 }
 
@@ -241,6 +256,9 @@ hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w,
                                    psq, st);
     {
         int wt, qtiles, splits;
+        if (bf16 && !sc_store && (sAm == 1 || sAk == 1) && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
+            return launch_bf_conv1x1(N, M, K, HW, w, sAm, sAk, B, out, epi, res, psum, psq, splitk_ws,
+                                     st);
         if (!sc_store && (sAm == 1 || sAk == 1) &&
             big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits))
             return launch_big_conv1x1(bf16, N, M, K, HW, w, sAm, sAk, B, out, epi, res, psum, psq,
@@ -347,11 +365,13 @@ static long long wgrad_chunk(int Ma, int Mb, long long Q)
     return chunk;
 }
 
-int wgrad_splits(int Ma, int Mb, int N, int HW)
+int wgrad_splits(bool bf16, int Ma, int Mb, int N, int HW)
 {
     bool swap;
     int splits;
     if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits))
+        return splits;
+    if (bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &splits))
         return splits;
     int wt;
     if (big_wgrad_plan(Ma, Mb, N, HW, &wt, &splits))
@@ -423,6 +443,12 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
         int splits;
         if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits)) {
             hipError_t e = launch_wgrad_cl(bf16, N, Ma, Mb, HW, U, V, partial, &splits, st);
+            if (e != hipSuccess)
+                return e;
+            return launch_reduce_splits(partial, splits, (size_t)Ma * Mb, dW, st);
+        }
+        if (bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &splits)) {
+            hipError_t e = launch_bf_wgrad(N, Ma, Mb, HW, U, V, partial, &splits, st);
             if (e != hipSuccess)
                 return e;
             return launch_reduce_splits(partial, splits, (size_t)Ma * Mb, dW, st);

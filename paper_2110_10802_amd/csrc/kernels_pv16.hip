@@ -287,55 +287,67 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
     const int tOwn = w >> 1, vOwn = 2 * (w & 1);
     const int kLast = a.K - 1;
 
-    for (int tile = blockIdx.x; tile < a.numTiles; tile += gridDim.x) {
+    // geometry of this lane's four pixels in a tile
+    struct Geo {
+        bool valid;
+        uint32_t n, pix;
+        size_t base;
+    };
+    auto geo_of = [&](int tile) __attribute__((always_inline)) {
+        Geo g;
         const uint32_t qv = (uint32_t)tile * 64u + 4u * j;
-        const bool valid = qv < a.Q;
-        const uint32_t qs = valid ? qv : 0u; // lanes past the end read pixel 0 and store nothing
-        const uint32_t n = fdiv(qs, a.divHW);
-        const uint32_t pix = qs - n * (uint32_t)a.HW;
-        const size_t base = (size_t)n * a.K * a.HW + pix;
-        float4v acc[2][4];
+        g.valid = tile < a.numTiles && qv < a.Q;
+        const uint32_t qs = g.valid ? qv : 0u; // lanes past the end read pixel 0 and store nothing
+        g.n = fdiv(qs, a.divHW);
+        g.pix = qs - g.n * (uint32_t)a.HW;
+        g.base = (size_t)g.n * a.K * a.HW + g.pix;
+        return g;
+    };
+    auto load_batch = [&](const Geo &g, int u0, PvRaw<PRO>(&raw)[U]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int u = 0; u < U; ++u) {
+            int k = 4 * (sBeg + u0 + u) + kk;
+            k = k < kLast ? k : kLast;
+            pv_load_raw<T, PRO>(a, g.base + (size_t)k * a.HW, g.n, k, raw[u]);
+        }
+    };
+    auto compute_batch = [&](int u0, const PvRaw<PRO>(&raw)[U], float4v(&acc)[2][4]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                acc[t][r] = (float4v){0.f, 0.f, 0.f, 0.f};
-
-        for (int u0 = 0; u0 < KSWp; u0 += U) {
-            PvRaw<PRO> raw[U];
+        for (int u = 0; u < U; ++u) {
+            const int s = sBeg + u0 + u;
+            int k = 4 * s + kk;
+            k = k < kLast ? k : kLast;
+            float bv[4];
+            pv_apply<PRO>(raw[u], k, coef, 4 * KS4p, bv);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                int k = 4 * (sBeg + u0 + u) + kk;
-                k = k < kLast ? k : kLast;
-                pv_load_raw<T, PRO>(a, base + (size_t)k * a.HW, n, k, raw[u]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
+            for (int t = 0; t < 2; ++t) {
+                const float wv = wl[(s * 2 + t) * 64 + lane];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int s = sBeg + u0 + u;
-                int k = 4 * s + kk;
-                k = k < kLast ? k : kLast;
-                float bv[4];
-                pv_apply<PRO>(raw[u], k, coef, 4 * KS4p, bv);
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const float wv = wl[(s * 2 + t) * 64 + lane];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        acc[t][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv, bv[r], acc[t][r], 0, 0, 0);
-                }
+                for (int r = 0; r < 4; ++r)
+                    acc[t][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv, bv[r], acc[t][r], 0, 0, 0);
             }
         }
-        // exchange partial tiles: every wavefront publishes, per destination g, the two
-        // accumulator registers that g finishes (tile g/2, registers 2*(g%2) + {0,1})
+    };
+    // residual rows this wavefront finishes (EPI_RES), loaded together with the tile's batch
+    auto load_res = [&](const Geo &g, float(&rr)[2][4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int dv = 0; dv < 2; ++dv) {
+            int m = 16 * tOwn + 4 * kk + vOwn + dv;
+            m = m < a.M ? m : a.M - 1;
+            pv_load4<T>((const T *)a.res, ((size_t)g.n * a.M + m) * a.HW + g.pix, rr[dv]);
+        }
+    };
+    // exchange partial tiles: every wavefront publishes, per destination g, the two accumulator
+    // registers that g finishes (tile g/2, registers 2*(g%2) + {0,1}); then finish, store, stats
+    auto finish_tile = [&](const Geo &g, const float4v(&acc)[2][4], const float(&rr)[2][4]) __attribute__((always_inline)) {
         __syncthreads(); // the previous tile's buffer has been consumed
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+        for (int gd = 0; gd < 4; ++gd)
 #pragma unroll
             for (int dv = 0; dv < 2; ++dv)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    xch[(((w * 4 + g) * 8) + dv * 4 + r) * 64 + lane] = acc[g >> 1][r][2 * (g & 1) + dv];
+                    xch[(((w * 4 + gd) * 8) + dv * 4 + r) * 64 + lane] = acc[gd >> 1][r][2 * (gd & 1) + dv];
         __syncthreads();
 #pragma unroll
         for (int dv = 0; dv < 2; ++dv) {
@@ -349,14 +361,12 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
                 o[r] = sacc;
             }
             const int m = 16 * tOwn + 4 * kk + vOwn + dv;
-            if (valid && m < a.M) {
-                const size_t idx = ((size_t)n * a.M + m) * a.HW + pix;
+            if (g.valid && m < a.M) {
+                const size_t idx = ((size_t)g.n * a.M + m) * a.HW + g.pix;
                 if (EPI == EPI_RES) {
-                    float rr[4];
-                    pv_load4<T>((const T *)a.res, idx, rr);
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        o[r] += rr[r];
+                        o[r] += rr[dv][r];
                 }
                 pv_store4<T>((T *)a.out, idx, o);
                 if (EPI == EPI_STATS) {
@@ -368,6 +378,67 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
                     }
                 }
             }
+        }
+    };
+
+    if (KSWp == U) {
+        // One batch per tile: the next tile's loads are issued right after this tile's MFMAs,
+        // so they are in flight during the exchange, the stores and the two barriers.
+        PvRaw<PRO> raw[U];
+        float rnext[2][4];
+        Geo g = geo_of(blockIdx.x);
+        if ((int)blockIdx.x < a.numTiles) {
+            load_batch(g, 0, raw);
+            if (EPI == EPI_RES)
+                load_res(g, rnext);
+        }
+        for (int tile = blockIdx.x; tile < a.numTiles; tile += gridDim.x) {
+            __builtin_amdgcn_sched_barrier(0);
+            float4v acc[2][4];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[t][r] = (float4v){0.f, 0.f, 0.f, 0.f};
+            compute_batch(0, raw, acc);
+            float rcur[2][4];
+            if (EPI == EPI_RES) {
+#pragma unroll
+                for (int dv = 0; dv < 2; ++dv)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        rcur[dv][r] = rnext[dv][r];
+            }
+            const int next = tile + gridDim.x;
+            const Geo gn = geo_of(next);
+            if (next < a.numTiles) {
+                load_batch(gn, 0, raw);
+                if (EPI == EPI_RES)
+                    load_res(gn, rnext);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            finish_tile(g, acc, rcur);
+            g = gn;
+        }
+    } else {
+        for (int tile = blockIdx.x; tile < a.numTiles; tile += gridDim.x) {
+            const Geo g = geo_of(tile);
+            float4v acc[2][4];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[t][r] = (float4v){0.f, 0.f, 0.f, 0.f};
+            float rr[2][4];
+            if (EPI == EPI_RES)
+                load_res(g, rr);
+            for (int u0 = 0; u0 < KSWp; u0 += U) {
+                PvRaw<PRO> raw[U];
+                load_batch(g, u0, raw);
+                __builtin_amdgcn_sched_barrier(0);
+                compute_batch(u0, raw, acc);
+            }
+            finish_tile(g, acc, rr);
         }
     }
     if (EPI == EPI_STATS) {

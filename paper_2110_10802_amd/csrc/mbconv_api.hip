@@ -92,8 +92,8 @@ Plan make_plan(const mbconv_desc *d)
         const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
         P.NPdw = dw_num_partials(ds, P.store && P.expand);
     }
-    P.NT1 = conv1x1_num_partials(P.N, P.Cexp, P.Cin, P.HW, false);
-    P.NT5 = conv1x1_num_partials(P.N, P.Cout, P.Cexp, P.HWo, d->policy == MBCONV_STORE);
+    P.NT1 = conv1x1_num_partials(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false);
+    P.NT5 = conv1x1_num_partials(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, d->policy == MBCONV_STORE);
 
     size_t o = 0;
     auto take = [&o](size_t bytes) {
@@ -137,15 +137,15 @@ Plan make_plan(const mbconv_desc *d)
     P.o_dq = take((size_t)P.N * P.Cse * f);
     P.o_dzs = take((size_t)P.N * P.Cexp * f);
     P.o_pdw = take((size_t)P.N * P.Cexp * P.k * P.k * f);
-    size_t wg = (size_t)wgrad_splits(P.Cout, P.Cexp, P.N, P.HWo) * P.Cout * P.Cexp;
+    size_t wg = (size_t)wgrad_splits(P.bf16, P.Cout, P.Cexp, P.N, P.HWo) * P.Cout * P.Cexp;
     if (P.expand)
-        wg = std::max(wg, (size_t)wgrad_splits(P.Cexp, P.Cin, P.N, P.HW) * P.Cexp * P.Cin);
+        wg = std::max(wg, (size_t)wgrad_splits(P.bf16, P.Cexp, P.Cin, P.N, P.HW) * P.Cexp * P.Cin);
     // the same region holds the partial tiles of a split 1x1 convolution
-    wg = std::max(wg, conv1x1_splitk_floats(P.N, P.Cout, P.Cexp, P.HWo, P.store));
-    wg = std::max(wg, conv1x1_splitk_floats(P.N, P.Cexp, P.Cout, P.HWo, false));
+    wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, P.store));
+    wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cexp, P.Cout, P.HWo, false));
     if (P.expand) {
-        wg = std::max(wg, conv1x1_splitk_floats(P.N, P.Cexp, P.Cin, P.HW, false));
-        wg = std::max(wg, conv1x1_splitk_floats(P.N, P.Cin, P.Cexp, P.HW, false));
+        wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false));
+        wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false));
     }
     P.o_wg = take(wg * f);
     P.scratch_bytes = o;

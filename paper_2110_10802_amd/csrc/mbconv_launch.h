@@ -33,15 +33,15 @@ inline int conv1x1_num_qtiles(int N, int HW) { return (int)(((long long)N * HW +
 // sc_store (optional) receives the operand after its prologue (STORE policy).
 // Long contractions with few output tiles are split over workgroups; `splitk_ws` then needs
 // conv1x1_splitk_floats(...) floats (0 when the launch does not split).
-int conv1x1_num_partials(int N, int M, int K, int HW, bool stores_operand);
-size_t conv1x1_splitk_floats(int N, int M, int K, int HW, bool stores_operand);
+int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand);
+size_t conv1x1_splitk_floats(bool bf16, int N, int M, int K, int HW, bool stores_operand);
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
                           float *psq, void *sc_store, float *splitk_ws, hipStream_t st);
 
 // Weight gradient of a 1x1 conv: dW[a,b] = sum_{n,q} op(U)[n,a,q] * op(V)[n,b,q].
 // `partial` needs wgrad_splits(...)*Ma*Mb floats.
-int wgrad_splits(int Ma, int Mb, int N, int HW);
+int wgrad_splits(bool bf16, int Ma, int Mb, int N, int HW);
 hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
                            const Operand &V, float *partial, float *dW, hipStream_t st);
 
