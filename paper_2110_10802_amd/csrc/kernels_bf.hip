@@ -71,10 +71,13 @@ struct BfConvArgs {
 template <int PRO, int EPI>
 __global__ __launch_bounds__(256) void conv_bf_kernel(BfConvArgs a)
 {
-    constexpr int BM = 64, BP = 64, BK = 32, PK = BK + 8;
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM][PK];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BP][PK];
-    __shared__ float red[2][BM][2];
+    constexpr int BM = 64, BP = 64, BK = 32, PK = BK + 8, PC = BP + 4;
+    // one LDS block: the two operand rings during the contraction, the fp32 output tile after it
+    constexpr int kOperandBytes = 2 * (BM + BP) * PK * 2, kTileBytes = BM * PC * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kOperandBytes > kTileBytes ? kOperandBytes : kTileBytes];
+    uint16_t(*As)[BM][PK] = reinterpret_cast<uint16_t(*)[BM][PK]>(smem);
+    uint16_t(*Bs)[BP][PK] = reinterpret_cast<uint16_t(*)[BP][PK]>(smem + 2 * BM * PK * 2);
+    float(*Ct)[PC] = reinterpret_cast<float(*)[PC]>(smem);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -198,46 +201,58 @@ __global__ __launch_bounds__(256) void conv_bf_kernel(BfConvArgs a)
     }
 
     // epilogue: register r of lane l is row 8*(r/4)+4*(l/32)+r%4, column l%32
-    float rs[16], rq[16];
-    const uint32_t q = q0 + wp * 32 + (lane & 31);
+    if (EPI == EPI_PARTIAL) {
+        const uint32_t q = q0 + wp * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (q < a.Q && m < a.M)
+                a.partial[((size_t)blockIdx.y * a.M + m) * a.Q + q] = acc[r];
+        }
+        return;
+    }
+    // The tile goes through LDS so that a thread ends up with four consecutive pixels of a row:
+    // 8-byte global accesses, 128 contiguous bytes per row and instruction, one pixel-index
+    // division per thread, and the BN statistics of a row reduced inside 16 lanes.
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        Ct[wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)][wp * 32 + (lane & 31)] = acc[r];
+    __syncthreads();
+    const uint32_t q = q0 + 4u * pg; // pg = tid % 16: the same pixel run as in the staging
     const bool valid = q < a.Q;
     const uint32_t n = valid ? fdiv(q, a.divHW) : 0u;
     const uint32_t pix = valid ? q - n * (uint32_t)a.HW : 0u;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        rs[r] = rq[r] = 0.f;
-        const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (EPI == EPI_PARTIAL) {
-            if (valid && m < a.M)
-                a.partial[((size_t)blockIdx.y * a.M + m) * a.Q + q] = acc[r];
-        } else if (valid && m < a.M) {
-            float v = acc[r];
-            const size_t idx = ((size_t)n * a.M + m) * a.HW + pix;
-            if (EPI == EPI_RES)
-                v += ld<bf16_t>(a.res, idx);
-            st<bf16_t>(a.out, idx, v);
-            if (EPI == EPI_STATS) {
-                const float sv = as_stored<bf16_t>(v);
-                rs[r] = sv;
-                rq[r] = sv * sv;
-            }
-        }
-    }
-    if (EPI == EPI_STATS) {
+    for (int i = 0; i < 4; ++i) {
+        const int row = (tid >> 4) + 16 * i, m = m0 + row;
+        const float4 c4 = *reinterpret_cast<const float4 *>(&Ct[row][4 * pg]);
+        float v[4] = {c4.x, c4.y, c4.z, c4.w};
+        const bool ok = valid && m < a.M;
+        const size_t idx = ((size_t)n * a.M + (ok ? m : 0)) * a.HW + pix;
+        if (EPI == EPI_RES) {
+            float rr[4];
+            bf_unpack4(*reinterpret_cast<const uint2 *>(a.res + idx), rr);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float s = half_wave_sum_dpp(rs[r]);
-            const float s2 = half_wave_sum_dpp(rq[r]);
-            if ((lane & 31) == 0) {
-                const int row = wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                red[0][row][wp] = s;
-                red[1][row][wp] = s2;
-            }
+            for (int r = 0; r < 4; ++r)
+                v[r] += rr[r];
         }
-        __syncthreads();
-        if (tid < BM && m0 + tid < a.M) {
-            a.psum[(size_t)(m0 + tid) * a.QT + qt] = red[0][tid][0] + red[0][tid][1];
-            a.psq[(size_t)(m0 + tid) * a.QT + qt] = red[1][tid][0] + red[1][tid][1];
+        const uint2 packed = make_uint2(bf_pack2(v[0], v[1]), bf_pack2(v[2], v[3]));
+        if (ok)
+            *reinterpret_cast<uint2 *>(a.out + idx) = packed;
+        if (EPI == EPI_STATS) {
+            float sv[4], s1 = 0.f, s2 = 0.f;
+            bf_unpack4(packed, sv);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s1 += ok ? sv[r] : 0.f;
+                s2 = fmaf(ok ? sv[r] : 0.f, sv[r], s2);
+            }
+            s1 = row16_sum(s1);
+            s2 = row16_sum(s2);
+            if (pg == 0 && m < a.M) {
+                a.psum[(size_t)m * a.QT + qt] = s1;
+                a.psq[(size_t)m * a.QT + qt] = s2;
+            }
         }
     }
 }
