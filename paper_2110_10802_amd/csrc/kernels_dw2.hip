@@ -1,5 +1,5 @@
-// Vectorised depthwise chain for stride 2 (the down-sampling blocks), input width a multiple
-// of 4.  Same plan as the stride-1 kernels in kernels_dw4.hip: the whole input plane is staged
+// Vectorised depthwise chain for stride 2 (the down-sampling blocks), even input height and
+// width (16-byte global accesses when the width is a multiple of 4, else masked pairs).  Same plan as the stride-1 kernels in kernels_dw4.hip: the whole input plane is staged
 // into LDS with a zero border, BN + Swish evaluated once per input element, every thread keeps
 // the runs of four pixels it staged; the output plane is a quarter of the input, so a thread
 // owns up to four input runs and one output run.
@@ -24,7 +24,8 @@ struct Dw2Args {
     int WP;      // a1 tile pitch  = 8*Wo4 + 8 (>= W + 8), interior at column 4
     int WQ;      // dd tile pitch  = 4*Wo4 + 8, interior at column 4
     int Wo4;     // output runs per row = ceil(Wo/4)
-    int inRuns;  // H*W/4
+    int W4;      // input runs per row = ceil(W/4)
+    int inRuns;  // H*W4
     int outRuns; // Ho*Wo4
     FastDiv divC, divW4, divWo4;
     const void *e;
@@ -75,6 +76,36 @@ __device__ __forceinline__ void d2_store4<bf16_t>(bf16_t *p, size_t i, const flo
     t.x = (uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16);
     t.y = (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16);
     *reinterpret_cast<uint2 *>(&p[i]) = t;
+}
+
+// An input run of four columns x0..x0+3; GVI = 4: the width is a multiple of 4; GVI = 2: it is
+// even, so the run is two pairs of which the second may lie past the end.
+template <typename T, int GVI>
+__device__ __forceinline__ void d2_in_load(const T *p, size_t idx, int x0, int W, float (&v)[4])
+{
+    if (GVI == 4) {
+        d2_load4<T>(p, idx, v);
+    } else {
+        v[0] = ld<T>(p, idx);
+        v[1] = ld<T>(p, idx + 1);
+        const bool hi = x0 + 2 < W;
+        v[2] = hi ? ld<T>(p, idx + 2) : 0.f;
+        v[3] = hi ? ld<T>(p, idx + 3) : 0.f;
+    }
+}
+template <typename T, int GVI>
+__device__ __forceinline__ void d2_in_store(T *p, size_t idx, int x0, int W, const float (&v)[4])
+{
+    if (GVI == 4) {
+        d2_store4<T>(p, idx, v);
+    } else {
+        st<T>(p, idx, v[0]);
+        st<T>(p, idx + 1, v[1]);
+        if (x0 + 2 < W) {
+            st<T>(p, idx + 2, v[2]);
+            st<T>(p, idx + 3, v[3]);
+        }
+    }
 }
 
 // An output run of four columns j0..j0+3 (those >= Wo masked); Wo is even, so pairs are whole.
@@ -163,7 +194,7 @@ __device__ __forceinline__ void d2_window(const float *tile, int row, int WP, in
 }
 
 // ---- forward ---------------------------------------------------------------------------------
-template <typename T, int K, int TPP, bool EXPAND, int GVO>
+template <typename T, int K, int TPP, bool EXPAND, int GVO, int GVI>
 __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_fwd_kernel(Dw2Args a)
 {
     constexpr int P = (K - 1) / 2, NGI = 4;
@@ -189,13 +220,15 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_fwd_kernel(Dw2Args 
 #pragma unroll
         for (int t = 0; t < K * K; ++t)
             wt[t] = ld<T>((const T *)a.w, (size_t)c * K * K + t);
-        d2_zero_border<TPP>(tile, H, P, P, W, WP, lt);
+        d2_zero_border<TPP>(tile, H, P, P, 4 * a.W4, WP, lt);
         const size_t base = plane * (size_t)H * W;
         float ev[NGI][4]; // all loads first, then the arithmetic (one memory round trip)
 #pragma unroll
         for (int i = 0; i < NGI; ++i) {
-            const int gidx = lt + TPP * i;
-            d2_load4<T>((const T *)a.e, base + 4 * (size_t)(gidx < a.inRuns ? gidx : 0), ev[i]);
+            const int gidx = lt + TPP * i < a.inRuns ? lt + TPP * i : 0;
+            const int h = (int)fdiv((uint32_t)gidx, a.divW4);
+            const int x0 = 4 * (gidx - h * a.W4);
+            d2_in_load<T, GVI>((const T *)a.e, base + (size_t)h * W + x0, x0, W, ev[i]);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -203,11 +236,11 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_fwd_kernel(Dw2Args 
             const int gidx = lt + TPP * i;
             if (gidx < a.inRuns) {
                 const int h = (int)fdiv((uint32_t)gidx, a.divW4);
-                const int x0 = 4 * (gidx - h * (W >> 2));
+                const int x0 = 4 * (gidx - h * a.W4);
                 float v[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    v[r] = EXPAND ? swishf(fmaf(ev[i][r], scale, shift)) : ev[i][r];
+                    v[r] = x0 + r < W ? (EXPAND ? swishf(fmaf(ev[i][r], scale, shift)) : ev[i][r]) : 0.f;
                 *reinterpret_cast<float4v *>(tile + (h + P) * WP + 4 + x0) =
                     float4v{v[0], v[1], v[2], v[3]};
             }
@@ -247,7 +280,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_fwd_kernel(Dw2Args 
 }
 
 // ---- backward (the fused kernel described in mbconv_launch.h, DwBwdArgs) -----------------------
-template <typename T, int K, int TPP, bool EXPAND, int GVO>
+template <typename T, int K, int TPP, bool EXPAND, int GVO, int GVI>
 __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args a)
 {
     constexpr int P = (K - 1) / 2, NGI = 4, PB = kDw2PB;
@@ -286,7 +319,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
         const float scale2 = a.bn2[c], shift2 = a.bn2[C + c];
         const float c0 = a.coef2[c], c1 = a.coef2[C + c], c2 = a.coef2[2 * C + c];
         const float gate = a.g[plane], dzs = a.dzs[plane];
-        d2_zero_border<TPP>(a1t, H, P, P, W, WP, lt);
+        d2_zero_border<TPP>(a1t, H, P, P, 4 * a.W4, WP, lt);
         // the dd tile is small: clear all of it, the interior is written after the barrier
         for (int i = lt; i < ddElems / 4; i += TPP)
             reinterpret_cast<float4v *>(ddt)[i] = float4v{0.f, 0.f, 0.f, 0.f};
@@ -295,8 +328,10 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
         float evA[NGI][4], Gv[4], dv[4]; // all loads first (one memory round trip)
 #pragma unroll
         for (int i = 0; i < NGI; ++i) {
-            const int gidx = lt + TPP * i;
-            d2_load4<T>((const T *)a.e, ebase + 4 * (size_t)(gidx < a.inRuns ? gidx : 0), evA[i]);
+            const int gidx = lt + TPP * i < a.inRuns ? lt + TPP * i : 0;
+            const int h = (int)fdiv((uint32_t)gidx, a.divW4);
+            const int x0 = 4 * (gidx - h * a.W4);
+            d2_in_load<T, GVI>((const T *)a.e, ebase + (size_t)h * W + x0, x0, W, evA[i]);
         }
         d2_out_load<T, GVO>((const T *)a.G, dbase, has_out ? oj0 : Wo, Wo, Gv);
         d2_out_load<T, GVO>((const T *)a.d, dbase, has_out ? oj0 : Wo, Wo, dv);
@@ -306,7 +341,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
             const int gidx = lt + TPP * i;
             if (gidx < a.inRuns) {
                 const int h = (int)fdiv((uint32_t)gidx, a.divW4);
-                const int x0 = 4 * (gidx - h * (W >> 2));
+                const int x0 = 4 * (gidx - h * a.W4);
                 float av[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -319,6 +354,8 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
                     } else {
                         av[r] = evA[i][r];
                     }
+                    if (x0 + r >= W)
+                        av[r] = 0.f; // pad columns of a ragged row stay zero in the tile
                 }
                 *reinterpret_cast<float4v *>(a1t + (h + P) * WP + 4 + x0) =
                     float4v{av[0], av[1], av[2], av[3]};
@@ -366,7 +403,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
             const int gidx = lt + TPP * i;
             if (gidx < a.inRuns) {
                 const int h = (int)fdiv((uint32_t)gidx, a.divW4);
-                const int x0 = 4 * (gidx - h * (W >> 2));
+                const int x0 = 4 * (gidx - h * a.W4);
                 const int ph = (h + P) & 1;
                 const int hh = (h + P - ph) >> 1; // row tap t reads dd row hh - t with filter row ph + 2t
                 const int cq = x0 >> 1;
@@ -405,16 +442,18 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
                         const float raw = rawk[i][r], sg = sgk[i][r];
                         const float y = fmaf(raw, scale1, shift1);
                         o[r] = da[r] * (sg * (1.f + y * (1.f - sg)));
-                        const float sv = as_stored<T>(o[r]);
-                        acc[K * K] += sv;
-                        acc[K * K + 1] = fmaf(sv, (raw - mean1) * rstd1, acc[K * K + 1]);
+                        if (x0 + r < W) {
+                            const float sv = as_stored<T>(o[r]);
+                            acc[K * K] += sv;
+                            acc[K * K + 1] = fmaf(sv, (raw - mean1) * rstd1, acc[K * K + 1]);
+                        }
                     }
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
                         o[r] = da[r];
                 }
-                d2_store4<T>((T *)a.dy1_out, ebase + 4 * (size_t)gidx, o);
+                d2_in_store<T, GVI>((T *)a.dy1_out, ebase + (size_t)h * W + x0, x0, W, o);
             }
         }
     }
@@ -435,7 +474,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
 
 static bool dw2_shape(const DwShape &s, int *tpp)
 {
-    const int inRuns = s.H * s.W / 4, outRuns = s.Ho * ((s.Wo + 3) / 4);
+    const int inRuns = s.H * ((s.W + 3) / 4), outRuns = s.Ho * ((s.Wo + 3) / 4);
     for (int t : {64, 256, 1024}) {
         if (inRuns <= 4 * t && outRuns <= t) {
             *tpp = t;
@@ -448,7 +487,7 @@ static bool dw2_shape(const DwShape &s, int *tpp)
 bool dw2_supported(const DwShape &s)
 {
     int tpp;
-    return s.s == 2 && (s.k == 3 || s.k == 5) && s.W % 4 == 0 && s.H % 2 == 0 && s.Ho == s.H / 2 &&
+    return s.s == 2 && (s.k == 3 || s.k == 5) && s.W % 2 == 0 && s.H % 2 == 0 && s.Ho == s.H / 2 &&
            s.Wo == s.W / 2 && dw2_shape(s, &tpp);
 }
 
@@ -464,10 +503,11 @@ static Dw2Args dw2_args(const DwShape &s)
     a.Wo4 = (s.Wo + 3) / 4;
     a.WP = 8 * a.Wo4 + 8;
     a.WQ = 4 * a.Wo4 + 8;
-    a.inRuns = s.H * s.W / 4;
+    a.W4 = (s.W + 3) / 4;
+    a.inRuns = s.H * a.W4;
     a.outRuns = s.Ho * a.Wo4;
     a.divC = make_div((uint32_t)s.C);
-    a.divW4 = make_div((uint32_t)(s.W / 4));
+    a.divW4 = make_div((uint32_t)a.W4);
     a.divWo4 = make_div((uint32_t)a.Wo4);
     return a;
 }
@@ -498,11 +538,14 @@ static hipError_t dw2_launch(KERN kern, const Dw2Args &a, int tpp, size_t lds, h
 
 #define MBK_DW2_TPP(KERNEL, T, K, EXP, GVO)                                                       \
     {                                                                                             \
+        if (s.W % 4 != 0) /* ragged rows: only the small planes of the late stages */             \
+            return tpp == 64 ? dw2_launch(KERNEL<T, K, 64, EXP, 1, 2>, a, tpp, lds, st)           \
+                             : dw2_launch(KERNEL<T, K, 256, EXP, 1, 2>, a, tpp, lds, st);         \
         if (tpp == 64)                                                                            \
-            return dw2_launch(KERNEL<T, K, 64, EXP, GVO>, a, tpp, lds, st);                       \
+            return dw2_launch(KERNEL<T, K, 64, EXP, GVO, 4>, a, tpp, lds, st);                    \
         if (tpp == 256)                                                                           \
-            return dw2_launch(KERNEL<T, K, 256, EXP, GVO>, a, tpp, lds, st);                      \
-        return dw2_launch(KERNEL<T, K, 1024, EXP, GVO>, a, tpp, lds, st);                         \
+            return dw2_launch(KERNEL<T, K, 256, EXP, GVO, 4>, a, tpp, lds, st);                   \
+        return dw2_launch(KERNEL<T, K, 1024, EXP, GVO, 4>, a, tpp, lds, st);                      \
     }
 #define MBK_DW2_GO(KERNEL, T, K)                                                                  \
     {                                                                                             \
