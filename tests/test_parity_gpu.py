@@ -28,6 +28,11 @@ SMALL = {
     "plane_1024_threads": _shape(N=1, Cin=8, Cexp=16, Cout=8, H=70, W=66),
     "plane_256_threads": _shape(N=2, Cin=8, Cexp=16, Cout=8, H=28, W=28, k=5),
     "n1_tiny": _shape(N=1, Cin=1, Cexp=1, Cse=1, Cout=1, H=3, W=3, has_expand=False),
+    # the largest plane the library accepts (128x128), on each depthwise kernel family
+    "max_plane_k5": _shape(N=1, Cin=8, Cexp=8, Cout=8, H=128, W=128, k=5),
+    "max_plane_s2": _shape(N=1, Cin=8, Cexp=8, Cout=8, H=128, W=128, k=5, stride=2, residual=False),
+    "max_plane_ragged": _shape(N=1, Cin=8, Cexp=8, Cout=8, H=127, W=125, k=5),
+    "one_pixel": _shape(N=3, Cin=4, Cexp=8, Cse=2, Cout=4, H=1, W=1),
     "bf16_small": _shape(dtype="bf16", H=14, W=14, k=5, Cin=16, Cexp=64, Cout=16, N=4),
     "bf16_s2": _shape(dtype="bf16", H=16, W=16, k=3, stride=2, Cin=16, Cexp=32, Cout=24, N=4,
                       residual=False),
