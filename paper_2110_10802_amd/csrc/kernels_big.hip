@@ -56,6 +56,28 @@ __device__ __forceinline__ void big_ld<bf16_t, 1>(const bf16_t *p, size_t i, flo
     v[0] = bf16_bits_to_float(p[i].bits);
 }
 
+// v where the mask is all ones, +0 where it is zero (one v_and_b32, never a branch)
+__device__ __forceinline__ float and_mask(float v, uint32_t mask)
+{
+    return __uint_as_float(__float_as_uint(v) & mask);
+}
+
+// four consecutive elements stored as T
+template <typename T>
+__device__ __forceinline__ void big_st4(T *p, size_t i, const float (&v)[4]);
+template <>
+__device__ __forceinline__ void big_st4<float>(float *p, size_t i, const float (&v)[4])
+{
+    *reinterpret_cast<float4 *>(p + i) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <>
+__device__ __forceinline__ void big_st4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
+{
+    *reinterpret_cast<uint2 *>(&p[i]) =
+        make_uint2((uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16),
+                   (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16));
+}
+
 // Raw registers of one staged run of VEC elements of an operand row, with the row's
 // prologue coefficients.  zero() makes apply() return 0 for every element.
 template <int PRO, int VEC>
@@ -118,9 +140,14 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
     constexpr int NB = (VEC == 4 ? WP : 4 * WP) * KP; // staged runs of B per thread
     constexpr int BCOLS = BP / VEC;            // runs per row of the B tile
     constexpr int BROWS = 256 / BCOLS;         // rows staged per pass
-    __shared__ __attribute__((aligned(16))) float As[2][BK][PA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BP];
+    // One LDS block: the two operand buffers during the contraction, a 64 x 64 tile of results
+    // (pitch CP) in the epilogue.
+    constexpr int CP = 68;
+    constexpr int OPER = 2 * BK * (PA + BP), TILE = 64 * CP;
+    __shared__ __attribute__((aligned(16))) float smem[OPER > TILE ? OPER : TILE];
     __shared__ float red[2][BM][2];
+    float(*As)[BK][PA] = reinterpret_cast<float(*)[BK][PA]>(smem);
+    float(*Bs)[BK][BP] = reinterpret_cast<float(*)[BK][BP]>(smem + 2 * BK * PA);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -135,6 +162,7 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
 
     // ---- A staging ----
     float4 ra[D - 1][WM * KP];
+    uint32_t raok[D - 1][WM * KP];
     // All staging loads are unconditional (indices clamped into the tensor, results masked
     // afterwards): straight-line code lets every load of a chunk be in flight at once, whereas
     // a branch per run makes the compiler wait for the previous run's data first.
@@ -152,21 +180,27 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
                 ok = m < a.M && k < a.K;
                 big_ld<T, 4>((const T *)a.w, (size_t)min(k, a.K - 1) * a.sAk + min(m, a.M - 4), v);
             }
-            ra[slot][i] = ok ? make_float4(v[0], v[1], v[2], v[3]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            // the mask is applied when the run goes to LDS: touching the data here would make
+            // the wavefront wait for the load it has just issued
+            ra[slot][i] = make_float4(v[0], v[1], v[2], v[3]);
+            raok[slot][i] = ok ? 0xffffffffu : 0u;
         }
     };
     auto store_a = [&](int slot, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < WM * KP; ++i) {
+            const uint32_t mk = raok[slot][i];
+            const float4 t = make_float4(and_mask(ra[slot][i].x, mk), and_mask(ra[slot][i].y, mk),
+                                         and_mask(ra[slot][i].z, mk), and_mask(ra[slot][i].w, mk));
             if (kcontig) {
                 const int m = (tid >> 2) + 64 * (i % WM), kk = 16 * (i / WM) + 4 * (tid & 3);
-                As[buf][kk + 0][m] = ra[slot][i].x;
-                As[buf][kk + 1][m] = ra[slot][i].y;
-                As[buf][kk + 2][m] = ra[slot][i].z;
-                As[buf][kk + 3][m] = ra[slot][i].w;
+                As[buf][kk + 0][m] = t.x;
+                As[buf][kk + 1][m] = t.y;
+                As[buf][kk + 2][m] = t.z;
+                As[buf][kk + 3][m] = t.w;
             } else {
                 const int m = 4 * (tid % (BM / 4)), kk = tid / (BM / 4) + (1024 / BM) * i;
-                *reinterpret_cast<float4 *>(&As[buf][kk][m]) = ra[slot][i];
+                *reinterpret_cast<float4 *>(&As[buf][kk][m]) = t;
             }
         }
     };
@@ -178,13 +212,13 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
     const uint32_t bn = bvalid ? fdiv(qb, a.divHW) : 0u; // an invalid column reads image 0, pixel 0
     const size_t bbase = (size_t)bn * a.K * a.HW + (bvalid ? qb - bn * (uint32_t)a.HW : 0u);
     Staged<PRO, VEC> rb[D - 1][NB];
-    bool rbok[D - 1][NB];
+    uint32_t rbok[D - 1][NB]; // all ones / zero: masking by AND keeps the staging code branch-free
     auto load_b = [&](int slot, int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int k = k0 + brow + BROWS * i;
             const int kc = min(k, a.K - 1);
-            rbok[slot][i] = bvalid && k < a.K;
+            rbok[slot][i] = (bvalid && k < a.K) ? 0xffffffffu : 0u;
             rb[slot][i].template load<T>(a.B, bbase + (size_t)kc * a.HW);
             if (PRO == PRO_BNSWISH_GATE) {
                 rb[slot][i].k0 = a.B.c0[kc];
@@ -201,14 +235,15 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int kk = brow + BROWS * i;
+            const uint32_t mk = rbok[slot][i];
             if (VEC == 4) {
-                const bool ok = rbok[slot][i];
                 *reinterpret_cast<float4 *>(&Bs[buf][kk][4 * bcol]) =
-                    make_float4(ok ? rb[slot][i].apply(0) : 0.f, ok ? rb[slot][i].apply(VEC == 4 ? 1 : 0) : 0.f,
-                                ok ? rb[slot][i].apply(VEC == 4 ? 2 : 0) : 0.f,
-                                ok ? rb[slot][i].apply(VEC == 4 ? 3 : 0) : 0.f);
+                    make_float4(and_mask(rb[slot][i].apply(0), mk),
+                                and_mask(rb[slot][i].apply(VEC == 4 ? 1 : 0), mk),
+                                and_mask(rb[slot][i].apply(VEC == 4 ? 2 : 0), mk),
+                                and_mask(rb[slot][i].apply(VEC == 4 ? 3 : 0), mk));
             } else {
-                Bs[buf][kk][bcol] = rbok[slot][i] ? rb[slot][i].apply(0) : 0.f;
+                Bs[buf][kk][bcol] = and_mask(rb[slot][i].apply(0), mk);
             }
         }
     };
@@ -230,6 +265,10 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
     // Register ring of D-1 staged chunks: chunk j lives in slot (j - cbeg) % (D-1) from its load
     // until it is written to LDS, one iteration before it is consumed; its loads are issued D-1
     // iterations before that, so their latency is covered by D-2 iterations of MFMA work.
+    // Every load and LDS store is unconditional (chunk indices clamped to the last chunk, whose
+    // repeated copy is never consumed): with no branch between a load and its use the compiler's
+    // wait counts stay exact, so the younger chunks really remain in flight while chunk cc+1 is
+    // written to LDS.
     auto mfma_chunk = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
@@ -249,35 +288,97 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
     };
 #pragma unroll
     for (int u = 0; u < D - 1; ++u) {
-        if (cbeg + u < cend) {
-            load_a(u, (cbeg + u) * BK);
-            load_b(u, (cbeg + u) * BK);
-        }
+        const int cl = min(cbeg + u, cend - 1);
+        load_a(u, cl * BK);
+        load_b(u, cl * BK);
     }
     store_a(0, 0);
     store_b(0, 0);
     __syncthreads();
-    for (int c = cbeg; c < cend; c += D - 1) {
+    auto step = [&](int u, int cc) __attribute__((always_inline)) {
+        const int buf = (cc - cbeg) & 1;
+        const int cl = min(cc + D - 1, cend - 1); // slot u is free: it went to LDS last iteration
+        load_a(u, cl * BK);
+        load_b(u, cl * BK);
+        mfma_chunk(buf);
+        store_a((u + 1) % (D - 1), buf ^ 1);
+        store_b((u + 1) % (D - 1), buf ^ 1);
+        __syncthreads();
+    };
+    // whole turns of the ring without any branch, then the remaining chunks
+    const int turns = (cend - cbeg) / (D - 1), rest = (cend - cbeg) % (D - 1);
+    int cc = cbeg;
+    for (int g = 0; g < turns; ++g) {
 #pragma unroll
-        for (int u = 0; u < D - 1; ++u) {
-            const int cc = c + u;
-            if (cc < cend) { // uniform over the workgroup
-                const int buf = (cc - cbeg) & 1;
-                if (cc + D - 1 < cend) { // chunk cc's slot is free: it went to LDS last iteration
-                    load_a(u, (cc + D - 1) * BK);
-                    load_b(u, (cc + D - 1) * BK);
-                }
-                mfma_chunk(buf);
-                if (cc + 1 < cend) {
-                    store_a((u + 1) % (D - 1), buf ^ 1);
-                    store_b((u + 1) % (D - 1), buf ^ 1);
-                }
-                __syncthreads();
-            }
-        }
+        for (int u = 0; u < D - 1; ++u)
+            step(u, cc + u);
+        cc += D - 1;
     }
+#pragma unroll
+    for (int u = 0; u < D - 2; ++u)
+        if (u < rest) // uniform over the workgroup
+            step(u, cc + u);
 
     // ---- epilogue: register r of lane l is row 8*(r/4)+4*(l/32)+r%4, column l%32 ----
+    if constexpr (VEC == 4 && WP == 1 && EPI != EPI_PARTIAL) {
+        // Through LDS, 64 rows at a time: 16 lanes then own 64 consecutive pixels of one output
+        // row, so the residual is read and the result written in 16-byte (fp32) or 8-byte
+        // (bf16) pieces, and a row's statistics are a sum inside those 16 lanes.  (The last
+        // chunk's barrier has passed: nobody reads the operand buffers any more.)
+        float(*Ct)[CP] = reinterpret_cast<float(*)[CP]>(smem);
+        const int pg = tid & 15;
+        const uint32_t q = q0 + 4 * pg;
+        const bool valid = q < a.Q;
+        const uint32_t n = valid ? fdiv(q, a.divHW) : 0u;
+        const uint32_t pix = valid ? q - n * (uint32_t)a.HW : 0u;
+#pragma unroll
+        for (int h = 0; h < WM; ++h) {
+            if (h)
+                __syncthreads();
+            if (WM == 1 || wm == h) {
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        Ct[(WM == 1 ? wm * 32 : 32 * i) + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)]
+                          [wp * 32 + (lane & 31)] = acc[i][0][r];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = (tid >> 4) + 16 * i, m = m0 + 64 * h + row;
+                const bool ok = valid && m < a.M;
+                const float4 c = *reinterpret_cast<const float4 *>(&Ct[row][4 * pg]);
+                float v[4] = {c.x, c.y, c.z, c.w};
+                const size_t idx = ((size_t)n * a.M + min(m, a.M - 1)) * a.HW + pix;
+                if (EPI == EPI_RES) {
+                    float rr[4];
+                    big_ld<T, 4>((const T *)a.res, idx, rr);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[j] += rr[j];
+                }
+                if (ok)
+                    big_st4<T>((T *)a.out, idx, v);
+                if (EPI == EPI_STATS) {
+                    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float sv = ok ? as_stored<T>(v[j]) : 0.f;
+                        s1 += sv;
+                        s2 = fmaf(sv, sv, s2);
+                    }
+                    s1 = row16_sum(s1);
+                    s2 = row16_sum(s2);
+                    if (pg == 0 && m < a.M) {
+                        a.psum[(size_t)m * a.QT + qt] = s1;
+                        a.psq[(size_t)m * a.QT + qt] = s2;
+                    }
+                }
+            }
+        }
+        return;
+    }
     float rs[WM][16], rq[WM][16];
     if (EPI == EPI_STATS) {
 #pragma unroll
@@ -443,7 +544,7 @@ bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles, int *split
     return true;
 }
 
-template <typename T, int WM, int WP, int VEC, int D = 2>
+template <typename T, int WM, int WP, int VEC, int D = 3>
 static hipError_t big_conv_dispatch(const BigConvArgs &a, int pro, int epi, dim3 grid, hipStream_t st)
 {
 #define MBK_CASE(P, E)                                                                            \
@@ -611,13 +712,21 @@ __global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
                 rv[i].k2 = a.V.c2[rb];
         }
     }
-    bool staged_valid = false; // the staged pixel run lies inside the tensor
     // Unconditional loads with clamped indices (see conv_big_kernel): rows past the end read
-    // the last row and are zeroed by their coefficients / masks, a run past the end reads pixel 0.
+    // the last row, a run past the end reads pixel 0; both are zeroed by an AND mask on their
+    // way into LDS, so there is no branch between a load and its use.
+    uint32_t umask[NRU], vmask[NRV], qmask = 0u;
+#pragma unroll
+    for (int i = 0; i < NRU; ++i)
+        umask[i] = a0 + rrow + RROWS * i < a.Ma ? 0xffffffffu : 0u;
+#pragma unroll
+    for (int i = 0; i < NRV; ++i)
+        vmask[i] = b0 + rrow + RROWS * i < a.Mb ? 0xffffffffu : 0u;
     auto load = [&](int chunk) __attribute__((always_inline)) {
         const uint32_t q = (uint32_t)chunk * BQ + (uint32_t)qcol * VEC;
-        staged_valid = q < a.Q;
-        const uint32_t qc = staged_valid ? q : 0u;
+        const bool valid = q < a.Q;
+        qmask = valid ? 0xffffffffu : 0u;
+        const uint32_t qc = valid ? q : 0u;
         const uint32_t n = fdiv(qc, a.divHW);
         const uint32_t pix = qc - n * (uint32_t)a.HW;
 #pragma unroll
@@ -640,15 +749,13 @@ __global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
         for (int i = 0; i < NRU; ++i) {
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
-                Us[buf][qcol * VEC + j][rrow + RROWS * i] =
-                    (staged_valid && a0 + rrow + RROWS * i < a.Ma) ? ru[i].apply(j) : 0.f;
+                Us[buf][qcol * VEC + j][rrow + RROWS * i] = and_mask(ru[i].apply(j), qmask & umask[i]);
         }
 #pragma unroll
         for (int i = 0; i < NRV; ++i) {
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
-                Vs[buf][qcol * VEC + j][rrow + RROWS * i] =
-                    (staged_valid && b0 + rrow + RROWS * i < a.Mb) ? rv[i].apply(j) : 0.f;
+                Vs[buf][qcol * VEC + j][rrow + RROWS * i] = and_mask(rv[i].apply(j), qmask & vmask[i]);
         }
     };
 
@@ -661,36 +768,33 @@ __global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
             for (int r = 0; r < 16; ++r)
                 acc[i][j][r] = 0.f;
 
-    if (cbeg < cend) {
+    if (cbeg < cend) { // uniform over the workgroup; an empty split writes zeros
         load(cbeg);
         store(0);
-    }
-    __syncthreads();
-    for (int c = cbeg; c < cend; ++c) {
-        const int buf = NBUF == 2 ? (c - cbeg) & 1 : 0;
-        const bool more = c + 1 < cend;
-        if (more)
-            load(c + 1);
+        __syncthreads();
+        for (int c = cbeg; c < cend; ++c) {
+            const int buf = NBUF == 2 ? (c - cbeg) & 1 : 0;
+            load(min(c + 1, cend - 1)); // the repeated last chunk is stored but never consumed
 #pragma unroll
-        for (int kk = 0; kk < BQ; kk += 2) {
-            float av[WA], bv[WB];
+            for (int kk = 0; kk < BQ; kk += 2) {
+                float av[WA], bv[WB];
 #pragma unroll
-            for (int i = 0; i < WA; ++i)
-                av[i] = Us[buf][kk + (lane >> 5)][wa * 32 * WA + 32 * i + (lane & 31)];
-#pragma unroll
-            for (int j = 0; j < WB; ++j)
-                bv[j] = Vs[buf][kk + (lane >> 5)][wb * 32 * WB + 32 * j + (lane & 31)];
-#pragma unroll
-            for (int i = 0; i < WA; ++i)
+                for (int i = 0; i < WA; ++i)
+                    av[i] = Us[buf][kk + (lane >> 5)][wa * 32 * WA + 32 * i + (lane & 31)];
 #pragma unroll
                 for (int j = 0; j < WB; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
-        if (NBUF == 1)
-            __syncthreads();
-        if (more)
+                    bv[j] = Vs[buf][kk + (lane >> 5)][wb * 32 * WB + 32 * j + (lane & 31)];
+#pragma unroll
+                for (int i = 0; i < WA; ++i)
+#pragma unroll
+                    for (int j = 0; j < WB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+            }
+            if (NBUF == 1)
+                __syncthreads();
             store(NBUF == 2 ? buf ^ 1 : 0);
-        __syncthreads();
+            __syncthreads();
+        }
     }
     float *dst = a.partial + (size_t)blockIdx.z * a.Ma * a.Mb;
 #pragma unroll
