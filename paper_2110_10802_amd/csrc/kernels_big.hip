@@ -56,12 +56,6 @@ __device__ __forceinline__ void big_ld<bf16_t, 1>(const bf16_t *p, size_t i, flo
     v[0] = bf16_bits_to_float(p[i].bits);
 }
 
-// v where the mask is all ones, +0 where it is zero (one v_and_b32, never a branch)
-__device__ __forceinline__ float and_mask(float v, uint32_t mask)
-{
-    return __uint_as_float(__float_as_uint(v) & mask);
-}
-
 // four consecutive elements stored as T
 template <typename T>
 __device__ __forceinline__ void big_st4(T *p, size_t i, const float (&v)[4]);
@@ -74,8 +68,8 @@ template <>
 __device__ __forceinline__ void big_st4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
 {
     *reinterpret_cast<uint2 *>(&p[i]) =
-        make_uint2((uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16),
-                   (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16));
+        make_uint2(bf16_pack2(v[0], v[1]),
+                   bf16_pack2(v[2], v[3]));
 }
 
 // Raw registers of one staged run of VEC elements of an operand row, with the row's

@@ -534,8 +534,8 @@ template <>
 __device__ __forceinline__ void stvec4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
 {
     uint2 t;
-    t.x = (uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16);
-    t.y = (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16);
+    t.x = bf16_pack2(v[0], v[1]);
+    t.y = bf16_pack2(v[2], v[3]);
     *reinterpret_cast<uint2 *>(&p[i]) = t;
 }
 

@@ -133,8 +133,8 @@ template <>
 __device__ __forceinline__ void run_store<bf16_t, 4>(bf16_t *p, size_t idx, int, int, const float (&v)[4])
 {
     uint2 t;
-    t.x = (uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16);
-    t.y = (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16);
+    t.x = bf16_pack2(v[0], v[1]);
+    t.y = bf16_pack2(v[2], v[3]);
     *reinterpret_cast<uint2 *>(&p[idx]) = t;
 }
 template <>
@@ -142,10 +142,10 @@ __device__ __forceinline__ void run_store<bf16_t, 2>(bf16_t *p, size_t idx, int 
 {
     if (x0 < W)
         *reinterpret_cast<uint32_t *>(&p[idx]) =
-            (uint32_t)float_to_bf16_bits(v[0]) | ((uint32_t)float_to_bf16_bits(v[1]) << 16);
+            bf16_pack2(v[0], v[1]);
     if (x0 + 2 < W)
         *reinterpret_cast<uint32_t *>(&p[idx + 2]) =
-            (uint32_t)float_to_bf16_bits(v[2]) | ((uint32_t)float_to_bf16_bits(v[3]) << 16);
+            bf16_pack2(v[2], v[3]);
 }
 template <>
 __device__ __forceinline__ void run_store<bf16_t, 1>(bf16_t *p, size_t idx, int x0, int W, const float (&v)[4])

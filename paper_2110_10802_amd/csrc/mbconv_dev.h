@@ -15,14 +15,25 @@ struct bf16_t {
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
-// round-to-nearest-even; NaN stays NaN
+// round-to-nearest-even by the hardware conversion (v_cvt_pk_bf16_f32, one instruction per
+// pair instead of five integer operations per value); NaN stays NaN
 __device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u)
-        return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+// two values rounded to bf16 and packed, lo in bits 0-15
+__device__ __forceinline__ uint32_t bf16_pack2(float lo, float hi)
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+    const float2v v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
+}
+
+// v where the mask is all ones, +0 where it is zero (one v_and_b32, never a branch)
+__device__ __forceinline__ float and_mask(float v, uint32_t mask)
+{
+    return __uint_as_float(__float_as_uint(v) & mask);
 }
 
 template <typename T>
