@@ -28,7 +28,10 @@
  * invariants and the running-statistics closed form, Swish closed forms,
  * SE on a spatially constant input, residual with gamma3 = 0, central finite
  * differences for every gradient, linearity of backward in dOut, and an
- * independently assembled PyTorch-CPU fp64 autograd block.
+ * independently assembled PyTorch-CPU fp64 autograd block.  Evaluation mode:
+ * the evaluation-mode block fed with a training batch's own (biased) statistics
+ * reproduces the training-mode output, the single-value closed form of
+ * orc_bn_eval, and the same PyTorch block in eval() mode.
  * Parity unpinned: whether the conventions chosen where the paper is silent
  * (eps, momentum, SE activation and biases, symmetric padding) are those of
  * the model source the paper's authors ran; nothing numeric in the paper
@@ -467,6 +470,87 @@ int orc_mbconv_forward(const orc_desc *D, const orc_params *P, orc_running *R, c
     if (D->residual)
         for (size_t i = 0; i < nP; ++i)
             out[i] += x[i];
+    return 0;
+}
+
+/* ---- evaluation mode ------------------------------------------------------- */
+/* The paper notes that batch normalisation behaves differently in training and in
+ * inference (section "Background and Related Work", paragraph "Training vs. inference
+ * compilation"): training normalises with the batch statistics and stores running
+ * statistics; inference normalises with those stored statistics,
+ *   y = gamma*(x - run_mean)/sqrt(run_var + eps) + beta,
+ * so no reduction over the batch is involved and nothing is written back. */
+void orc_bn_eval(int N, int C, int HW, const double *x, const double *gamma, const double *beta,
+                 double eps, const double *run_mean, const double *run_var, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int c = 0; c < C; ++c) {
+        const double rstd = 1.0 / sqrt(run_var[c] + eps);
+        for (int n = 0; n < N; ++n) {
+            const size_t off = ((size_t)n * C + c) * HW;
+            for (int q = 0; q < HW; ++q)
+                y[off + q] = gamma[c] * ((x[off + q] - run_mean[c]) * rstd) + beta[c];
+        }
+    }
+}
+
+/* The block of orc_mbconv_forward with every BN in evaluation mode.  R is read only. */
+int orc_mbconv_forward_eval(const orc_desc *D, const orc_params *P, const orc_running *R,
+                            const double *x, double *out)
+{
+    if (!desc_ok(D) || !R)
+        return -1;
+    const int N = D->N, HW = D->H * D->W;
+    const int Ho = (D->H + 2 * D->pad - D->k) / D->stride + 1;
+    const int Wo = (D->W + 2 * D->pad - D->k) / D->stride + 1;
+    const int HWo = Ho * Wo;
+    const size_t nE = (size_t)N * D->Cexp * HW, nD = (size_t)N * D->Cexp * HWo;
+    const size_t nP = (size_t)N * D->Cout * HWo;
+    double *a1 = (double *)malloc(sizeof(double) * nE);
+    double *e = (double *)malloc(sizeof(double) * nE);
+    double *d = (double *)malloc(sizeof(double) * nD);
+    double *a2 = (double *)malloc(sizeof(double) * nD);
+    double *sc = (double *)malloc(sizeof(double) * nD);
+    double *p = (double *)malloc(sizeof(double) * nP);
+    double *z = (double *)malloc(sizeof(double) * (size_t)N * D->Cexp);
+    double *t = (double *)malloc(sizeof(double) * (size_t)N * D->Cexp);
+    double *g = (double *)malloc(sizeof(double) * (size_t)N * D->Cexp);
+    double *q = (double *)malloc(sizeof(double) * (size_t)N * D->Cse);
+    double *r = (double *)malloc(sizeof(double) * (size_t)N * D->Cse);
+    if (!a1 || !e || !d || !a2 || !sc || !p || !z || !t || !g || !q || !r)
+        return -2;
+    if (D->has_expand) {
+        orc_conv1x1(N, D->Cin, D->Cexp, HW, P->w_expand, x, e);
+        orc_bn_eval(N, D->Cexp, HW, e, P->bn1_gamma, P->bn1_beta, D->eps, R->bn1_mean, R->bn1_var, a1);
+#pragma omp parallel for schedule(static)
+        for (size_t i = 0; i < nE; ++i)
+            a1[i] = orc_swish(a1[i]);
+    } else {
+        memcpy(a1, x, sizeof(double) * nE);
+    }
+    orc_depthwise_fwd(N, D->Cexp, D->H, D->W, D->k, D->stride, D->pad, P->w_dw, a1, d);
+    orc_bn_eval(N, D->Cexp, HWo, d, P->bn2_gamma, P->bn2_beta, D->eps, R->bn2_mean, R->bn2_var, a2);
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < nD; ++i)
+        a2[i] = orc_swish(a2[i]);
+    orc_se_fwd(N, D->Cexp, D->Cse, HWo, a2, P->se_w1, P->se_b1, P->se_w2, P->se_b2, z, q, r, t, g,
+               sc);
+    orc_conv1x1(N, D->Cexp, D->Cout, HWo, P->w_proj, sc, p);
+    orc_bn_eval(N, D->Cout, HWo, p, P->bn3_gamma, P->bn3_beta, D->eps, R->bn3_mean, R->bn3_var, out);
+    if (D->residual)
+        for (size_t i = 0; i < nP; ++i)
+            out[i] += x[i];
+    free(a1);
+    free(e);
+    free(d);
+    free(a2);
+    free(sc);
+    free(p);
+    free(z);
+    free(t);
+    free(g);
+    free(q);
+    free(r);
     return 0;
 }
 

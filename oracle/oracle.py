@@ -263,6 +263,38 @@ def mbconv_forward(s, t):
     return SimpleNamespace(out=out, tape=tape, running=running)
 
 
+def bn_eval(x, gamma, beta, eps, run_mean, run_var):
+    """Evaluation-mode BN: gamma*(x-run_mean)/sqrt(run_var+eps)+beta."""
+    x = _f64(x)
+    N, Cc, H, W = x.shape
+    y = np.empty_like(x)
+    lib().orc_bn_eval(N, Cc, H * W, _p(x), _p(_f64(gamma)), _p(_f64(beta)), C.c_double(eps),
+                      _p(_f64(run_mean)), _p(_f64(run_var)), _p(y))
+    return y
+
+
+def mbconv_forward_eval(s, t, running=None):
+    """Evaluation-mode forward: every BN uses the running statistics (``running`` dict, else the
+    entries of ``t``, else mean 0 / variance 1).  Returns out."""
+    keep = []
+    x = _f64(t["x"])
+    ps = _params_struct(s, t, keep)
+    rs = _Running()
+    for n in _RUNNING:
+        C_ = s.Cout if n.startswith("bn3") else s.Cexp
+        default = np.ones(C_) if n.endswith("var") else np.zeros(C_)
+        src = running if (running is not None and n in running) else t
+        a = _f64(src[n]).copy() if n in src else default
+        keep.append(a)
+        setattr(rs, n, _p(a))
+    out = np.empty((s.N, s.Cout, s.Ho, s.Wo))
+    d = _desc(s)
+    rc = lib().orc_mbconv_forward_eval(C.byref(d), C.byref(ps), C.byref(rs), _p(x), _p(out))
+    if rc != 0:
+        raise ValueError(f"orc_mbconv_forward_eval returned {rc}")
+    return out
+
+
 def mbconv_backward(s, t, tape, dout=None):
     """Backward of ``mbconv_forward``.  Returns a namespace: dx, grads (dict)."""
     keep = []

@@ -396,3 +396,83 @@ def test_block_vs_pytorch_fp64_autograd(s):
     for n in orc._RUNNING:
         if s.has_expand or not n.startswith("bn1"):
             assert np.allclose(f.running[n], run[n], rtol=1e-12, atol=1e-13), n
+
+
+# ------------------------------------------------------ evaluation mode ------
+
+def _random_running(s, seed):
+    """Running statistics that are neither (0, 1) nor the batch's own."""
+    rng = np.random.default_rng(seed)
+    run = {}
+    for i, C_ in ((1, s.Cexp), (2, s.Cexp), (3, s.Cout)):
+        run[f"bn{i}_mean"] = 0.3 * rng.standard_normal(C_)
+        run[f"bn{i}_var"] = 0.5 + rng.random(C_)
+    return run
+
+
+def test_bn_eval_closed_form():
+    # one value per channel: (x - m)/sqrt(v + eps) written out by hand
+    x = np.array([[[[2.0]], [[-1.0]]]])
+    y = orc.bn_eval(x, np.array([3.0, 0.5]), np.array([0.25, -2.0]), 0.21,
+                    np.array([0.5, 1.0]), np.array([0.04, 1.0]))
+    assert abs(y[0, 0, 0, 0] - (3.0 * (2.0 - 0.5) / 0.5 + 0.25)) < 1e-14
+    assert abs(y[0, 1, 0, 0] - (0.5 * (-1.0 - 1.0) / 1.1 - 2.0)) < 1e-14
+    # running statistics (0, 1 - eps) make it the affine map gamma*x + beta
+    x = RNG.standard_normal((2, 3, 4, 5))
+    g, b = RNG.standard_normal(3), RNG.standard_normal(3)
+    y = orc.bn_eval(x, g, b, 1e-3, np.zeros(3), np.full(3, 1.0 - 1e-3))
+    assert np.allclose(y, g[None, :, None, None] * x + b[None, :, None, None], atol=1e-13)
+
+
+@pytest.mark.parametrize("s", [CONFIG0, _tiny(Cout=3, residual=False, stride=2, k=5, H=8, W=8),
+                               BlockShape(N=3, Cin=8, H=9, W=9, Cexp=8, Cse=2, Cout=8, k=3,
+                                          stride=1, has_expand=False, residual=True)],
+                         ids=["config0", "k5s2", "noexpand"])
+def test_eval_block_with_batch_statistics_is_the_training_block(s):
+    # Training mode normalises with the batch mean and the biased batch variance; handing
+    # exactly those to the evaluation-mode block must reproduce the training output.
+    t = make_block_inputs(s, 3)
+    f = orc.mbconv_forward(s, t)
+    run = {}
+    for i in (1, 2, 3):
+        if i == 1 and not s.has_expand:
+            continue
+        run[f"bn{i}_mean"] = f.tape[f"mean{i}"]
+        run[f"bn{i}_var"] = f.tape[f"var{i}"]
+    out = orc.mbconv_forward_eval(s, t, run)
+    assert np.allclose(out, f.out, rtol=1e-11, atol=1e-12)
+    # and different statistics must change it (the argument is really used)
+    other = orc.mbconv_forward_eval(s, t, _random_running(s, 5))
+    assert np.abs(other - f.out).max() > 1e-3
+
+
+@pytest.mark.parametrize("s", [CONFIG0, _tiny(Cout=3, residual=False, stride=2, k=5, H=8, W=8),
+                               BlockShape(N=3, Cin=8, H=9, W=9, Cexp=8, Cse=2, Cout=8, k=3,
+                                          stride=1, has_expand=False, residual=True)],
+                         ids=["config0", "k5s2", "noexpand"])
+def test_eval_block_vs_pytorch_fp64(s):
+    import torch
+    import torch.nn.functional as F
+
+    t = make_block_inputs(s, 0)
+    run = _random_running(s, 11)
+    tt = {k: torch.tensor(np.asarray(v, dtype=np.float64)) for k, v in {**t, **run}.items()}
+
+    def bn(v, i):
+        return F.batch_norm(v, tt[f"bn{i}_mean"], tt[f"bn{i}_var"], tt[f"bn{i}_gamma"],
+                            tt[f"bn{i}_beta"], training=False, eps=s.eps)
+
+    x = tt["x"]
+    a = x
+    if s.has_expand:
+        a = F.silu(bn(F.conv2d(a, tt["w_expand"][:, :, None, None]), 1))
+    a = F.conv2d(a, tt["w_dw"][:, None], stride=s.stride, padding=s.pad, groups=s.Cexp)
+    a = F.silu(bn(a, 2))
+    z = a.mean(dim=(2, 3))
+    r = F.silu(z @ tt["se_w1"].T + tt["se_b1"])
+    g = torch.sigmoid(r @ tt["se_w2"].T + tt["se_b2"])
+    out = bn(F.conv2d(a * g[:, :, None, None], tt["w_proj"][:, :, None, None]), 3)
+    if s.residual:
+        out = out + x
+    got = orc.mbconv_forward_eval(s, t, run)
+    assert np.allclose(got, out.numpy(), rtol=1e-10, atol=1e-11)
