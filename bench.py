@@ -2,6 +2,7 @@
 """Benchmark of the MBConv training step (forward + backward) on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--policy recompute|store]
+                    [--mode train|eval]
 
 A step is one forward plus one backward of the block through the C ABI, on seeded synthetic
 inputs that are already resident in HBM.  The default workload is benchmark config 1
@@ -103,14 +104,18 @@ class HipEvents:
         return sorted(vals)[len(vals) // 2]
 
 
-def cpu_baseline(shape, tensors):
-    """The oracle, as it stands, on this host: one forward+backward of the same workload."""
+def cpu_baseline(shape, tensors, eval_mode=False):
+    """The oracle, as it stands, on this host: one pass of the same workload."""
     from oracle import oracle as orc
     t0 = time.perf_counter()
-    orc.mbconv_step(shape, tensors)
+    if eval_mode:
+        orc.mbconv_forward_eval(shape, tensors)
+    else:
+        orc.mbconv_step(shape, tensors)
     dt = time.perf_counter() - t0
+    what = "evaluation-mode forward" if eval_mode else "forward+backward"
     return {"value": shape.N / dt, "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"one fp64 forward+backward of the full workload batch ({shape.N} images), "
+            "sample": f"one fp64 {what} of the full workload batch ({shape.N} images), "
                       f"{dt:.1f} s wall"}
 
 
@@ -232,6 +237,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--policy", default="recompute", choices=["recompute", "store"])
+    ap.add_argument("--mode", default="train", choices=["train", "eval"],
+                    help="train: forward+backward (the headline metric); eval: the evaluation-mode "
+                         "forward alone (BN with running statistics), configs 0-3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe-step", default=None,
                     help="time this step for the roofline instead of the slowest one")
@@ -256,6 +264,9 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     if args.config == 4:
+        if args.mode != "train":
+            print("bench.py: --mode eval covers the single-block configs 0-3", file=sys.stderr)
+            return 2
         return run_chain(args)
     B.load()  # fails loudly if the HIP library has not been built
     shape = CONFIGS[args.config]
@@ -270,7 +281,14 @@ def main() -> int:
     grads = B._fill(B.Grads(), blk.grads)
     desc = blk.desc
 
+    evalm = args.mode == "eval"
+    if evalm:
+        eval_ws = torch.empty(B.mbconv_eval_workspace_size(desc), dtype=torch.uint8, device="cuda")
+
     def step(probe=None):
+        if evalm:
+            B.mbconv_forward_eval_probed(desc, params, running, x, blk.out, eval_ws, stream, probe)
+            return
         fprobe = probe if probe is not None and probe.step <= 9 else None
         bprobe = probe if probe is not None and probe.step > 9 else None
         B.mbconv_forward_probed(desc, params, running, x, blk.out, blk.saved, blk.scratch, stream,
@@ -289,6 +307,9 @@ def main() -> int:
     for name, sid in B.STEPS.items():
         if not shape.has_expand and name in NO_EXPAND_STEPS:
             continue
+        if evalm and (sid > 9 or name in ("bn2_finalize", "bn3_finalize")
+                      or (name == "bn1_finalize" and not shape.has_expand)):
+            continue  # backward steps, and finalise steps that do not occur in evaluation mode
         reps = []
         for _ in range(3):
             step(B.Probe(sid, e0, e1))
@@ -332,7 +353,7 @@ def main() -> int:
     achieved = nbytes / (kern_ms * 1e-3) / 1e9
     workload = f"config{args.config}"
     result = {
-        "metric": "mbconv_fwd_bwd_images_per_sec",
+        "metric": "mbconv_eval_fwd_images_per_sec" if evalm else "mbconv_fwd_bwd_images_per_sec",
         "value": shape.N / (ms_per_step * 1e-3),
         "unit": "images/s",
         "n_gpus": 1,
@@ -346,7 +367,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": workload, "block": f"N{shape.N} {shape.Cin}->{shape.Cexp}->{shape.Cout} "
                    f"{shape.H}x{shape.W} k{shape.k}s{shape.stride} se{shape.Cse} "
-                   f"res{int(shape.residual)}", "policy": args.policy},
+                   f"res{int(shape.residual)}", "policy": args.policy, "mode": args.mode},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((workload, dominant)),
@@ -355,7 +376,7 @@ def main() -> int:
         "step_ms_survey": {n: round(v, 5) for n, v in survey.items()},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(shape, tensors)
+        result["cpu_baseline"] = cpu_baseline(shape, tensors, evalm)
     print(json.dumps(result))
     return 0
 

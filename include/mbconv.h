@@ -136,6 +136,25 @@ mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *param
                              mbconv_bn_state *running, const void *x, void *out, void *saved_ws,
                              void *scratch_ws, void *hip_stream);
 
+/* Evaluation-mode forward: every BN normalises with the running statistics instead of the
+ * batch's (the paper lists BN among the operators that behave differently in inference and
+ * notes that inference stores no activations for backpropagation: section "Background and
+ * Related Work", paragraph "Training vs. inference compilation").  Computes
+ *   y = gamma*(v - run_mean)/sqrt(run_var + bn_eps) + beta
+ * at the three normalisations and otherwise the same block as mbconv_forward.
+ *   running: read only, required; bn1_* may be NULL iff !has_expand.
+ *   x, out: as for mbconv_forward.   desc->policy is ignored (nothing is saved).
+ *   workspace: at least the byte count mbconv_eval_workspace_size reports (host-only query,
+ *   same descriptor checks as mbconv_workspace_size); overwritten, nothing in it needs to
+ *   survive the call.
+ * The _probed variant brackets one step like mbconv_forward_probed; the coefficient blocks of
+ * all three normalisations come from one launch attributed to MBCONV_STEP_BN1_FINALIZE
+ * (MBCONV_STEP_BN2_FINALIZE when has_expand == 0), the other finalise steps do not occur. */
+mbconv_status mbconv_eval_workspace_size(const mbconv_desc *desc, size_t *workspace_bytes);
+mbconv_status mbconv_forward_eval(const mbconv_desc *desc, const mbconv_params *params,
+                                  const mbconv_bn_state *running, const void *x, void *out,
+                                  void *workspace, void *hip_stream);
+
 /* Backward of the forward call that wrote saved_ws (same desc, params and x).
  *   dout [N,Cout,Ho,Wo] dtype, read-only.   dx [N,Cin,H,W] dtype, written.
  *   grads: every non-NULL member is overwritten with the gradient of sum(out*dout).
@@ -195,6 +214,11 @@ mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_param
                                      const void *x, const void *dout, const void *saved_ws,
                                      void *scratch_ws, void *dx, mbconv_grads *grads,
                                      void *hip_stream, const mbconv_probe *probe);
+
+mbconv_status mbconv_forward_eval_probed(const mbconv_desc *desc, const mbconv_params *params,
+                                         const mbconv_bn_state *running, const void *x, void *out,
+                                         void *workspace, void *hip_stream,
+                                         const mbconv_probe *probe);
 
 /* Static string for a status code. */
 const char *mbconv_status_string(mbconv_status status);

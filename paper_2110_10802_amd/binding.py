@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libmbconv.so")
 
 MBCONV_F32, MBCONV_BF16 = 0, 1
 MBCONV_RECOMPUTE, MBCONV_STORE = 0, 1
-ABI_VERSION = 1
+ABI_VERSION = 2
 ABSENT = C.c_size_t(-1).value
 
 PARAM_NAMES = ["w_expand", "bn1_gamma", "bn1_beta", "w_dw", "bn2_gamma", "bn2_beta", "se_w1",
@@ -24,7 +24,8 @@ PARAM_NAMES = ["w_expand", "bn1_gamma", "bn1_beta", "w_dw", "bn2_gamma", "bn2_be
 RUNNING_NAMES = ["bn1_mean", "bn1_var", "bn2_mean", "bn2_var", "bn3_mean", "bn3_var"]
 SAVED_NAMES = ["e", "d", "p", "bn1", "bn2", "bn3", "z", "g", "q", "a1", "sc"]
 EXPORTS = ["mbconv_workspace_size", "mbconv_saved_offsets", "mbconv_forward", "mbconv_backward",
-           "mbconv_forward_probed", "mbconv_backward_probed", "mbconv_status_string",
+           "mbconv_forward_probed", "mbconv_backward_probed", "mbconv_eval_workspace_size",
+           "mbconv_forward_eval", "mbconv_forward_eval_probed", "mbconv_status_string",
            "mbconv_abi_version"]
 # mbconv_step values (launch order of the two calls)
 STEPS = {"expand_conv": 1, "bn1_finalize": 2, "dw_fwd": 3, "bn2_finalize": 4, "se_pool": 5,
@@ -98,6 +99,13 @@ def load() -> C.CDLL:
         lib.mbconv_forward_probed.argtypes = lib.mbconv_forward.argtypes + [C.POINTER(Probe)]
         lib.mbconv_backward_probed.restype = C.c_int
         lib.mbconv_backward_probed.argtypes = lib.mbconv_backward.argtypes + [C.POINTER(Probe)]
+        lib.mbconv_eval_workspace_size.restype = C.c_int
+        lib.mbconv_eval_workspace_size.argtypes = [C.POINTER(Desc), C.POINTER(C.c_size_t)]
+        lib.mbconv_forward_eval.restype = C.c_int
+        lib.mbconv_forward_eval.argtypes = [C.POINTER(Desc), C.POINTER(Params), C.POINTER(BNState),
+                                            vp, vp, vp, vp]
+        lib.mbconv_forward_eval_probed.restype = C.c_int
+        lib.mbconv_forward_eval_probed.argtypes = lib.mbconv_forward_eval.argtypes + [C.POINTER(Probe)]
         if lib.mbconv_abi_version() != ABI_VERSION:
             raise RuntimeError("libmbconv.so ABI version mismatch; rebuild")
         _lib = lib
@@ -173,6 +181,36 @@ def mbconv_forward_probed(desc: Desc, params: Any, running: Any, x: Any, out: An
                                        C.byref(probe))
     if rc != 0:
         raise MBConvError(rc, "mbconv_forward")
+
+
+def mbconv_eval_workspace_size(desc: Desc) -> int:
+    nbytes = C.c_size_t(0)
+    rc = load().mbconv_eval_workspace_size(C.byref(desc), C.byref(nbytes))
+    if rc != 0:
+        raise MBConvError(rc, "mbconv_eval_workspace_size")
+    return nbytes.value
+
+
+def mbconv_forward_eval(desc: Desc, params: Any, running: Any, x: Any, out: Any, workspace: Any,
+                        stream: int = 0) -> None:
+    mbconv_forward_eval_probed(desc, params, running, x, out, workspace, stream, None)
+
+
+def mbconv_forward_eval_probed(desc: Desc, params: Any, running: Any, x: Any, out: Any,
+                               workspace: Any, stream: int = 0,
+                               probe: Optional[Probe] = None) -> None:
+    ps = params if isinstance(params, Params) else _fill(Params(), params)
+    rs = running if isinstance(running, BNState) or running is None else _fill(BNState(), running)
+    lib = load()
+    rsp = C.byref(rs) if rs is not None else None
+    if probe is None:
+        rc = lib.mbconv_forward_eval(C.byref(desc), C.byref(ps), rsp, _ptr(x), _ptr(out),
+                                     _ptr(workspace), stream or None)
+    else:
+        rc = lib.mbconv_forward_eval_probed(C.byref(desc), C.byref(ps), rsp, _ptr(x), _ptr(out),
+                                            _ptr(workspace), stream or None, C.byref(probe))
+    if rc != 0:
+        raise MBConvError(rc, "mbconv_forward_eval")
 
 
 def mbconv_backward_probed(desc: Desc, params: Any, x: Any, dout: Any, saved_ws: Any,

@@ -83,6 +83,54 @@ hipError_t launch_bn_finalize(int C, int NP, double m, const float *psum, const 
     return hipGetLastError();
 }
 
+// Evaluation mode: the same {scale, shift, mean, rstd} blocks from the stored running
+// statistics, for up to three normalisations in one launch (a batch-norm layer with fixed
+// statistics is an affine map per channel; section "Background and Related Work", paragraph
+// "Training vs. inference compilation": BN behaves differently in inference).
+struct BnEvalOne {
+    int C;
+    const float *gamma, *beta, *run_mean, *run_var;
+    float *bn;
+};
+struct BnEvalArgs {
+    BnEvalOne b[3];
+    float eps;
+};
+__global__ __launch_bounds__(256) void bn_eval_coef_kernel(BnEvalArgs a)
+{
+    int i = blockIdx.x * 256 + threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const BnEvalOne &b = a.b[k];
+        if (i >= 0 && i < b.C) {
+            const double mean = (double)b.run_mean[i];
+            const double rstd = 1.0 / sqrt((double)b.run_var[i] + (double)a.eps);
+            const double scale = (double)b.gamma[i] * rstd;
+            b.bn[i] = (float)scale;
+            b.bn[b.C + i] = (float)((double)b.beta[i] - mean * scale);
+            b.bn[2 * b.C + i] = (float)mean;
+            b.bn[3 * b.C + i] = (float)rstd;
+        }
+        i -= b.C;
+    }
+}
+
+hipError_t launch_bn_eval_coef(int C1, const float *gamma1, const float *beta1, const float *rm1,
+                               const float *rv1, float *bn1, int C2, const float *gamma2,
+                               const float *beta2, const float *rm2, const float *rv2, float *bn2,
+                               int C3, const float *gamma3, const float *beta3, const float *rm3,
+                               const float *rv3, float *bn3, float eps, hipStream_t st)
+{
+    BnEvalArgs a;
+    a.b[0] = {C1, gamma1, beta1, rm1, rv1, bn1};
+    a.b[1] = {C2, gamma2, beta2, rm2, rv2, bn2};
+    a.b[2] = {C3, gamma3, beta3, rm3, rv3, bn3};
+    a.eps = eps;
+    const int total = C1 + C2 + C3;
+    hipLaunchKernelGGL(bn_eval_coef_kernel, dim3((total + 255) / 256), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 // dx = gamma*rstd*(dy - dbeta/m - xhat*dgamma/m) with xhat = (raw-mean)*rstd, rewritten as
 // c0*dy + c1*raw + c2 so the consumer's prologue is two fused multiply-adds.
 __device__ __forceinline__ void bn_bwd_coef_vals(int C, int c, double m, double dgamma, double dbeta,

@@ -203,11 +203,15 @@ mbconv_status check_params(const mbconv_desc *d, const mbconv_params *p)
     return MBCONV_OK;
 }
 
+mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mbconv_bn_state *run,
+                           bool eval, const void *x, void *out, void *saved, void *scratch,
+                           void *hip_stream, const mbconv_probe *probe);
+
 } // namespace
 
 extern "C" {
 
-int32_t mbconv_abi_version(void) { return 1; }
+int32_t mbconv_abi_version(void) { return 2; }
 
 const char *mbconv_status_string(mbconv_status s)
 {
@@ -275,6 +279,60 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
                                     mbconv_bn_state *run, const void *x, void *out, void *saved,
                                     void *scratch, void *hip_stream, const mbconv_probe *probe)
 {
+    return forward_impl(desc, prm, run, false, x, out, saved, scratch, hip_stream, probe);
+}
+
+mbconv_status mbconv_eval_workspace_size(const mbconv_desc *desc, size_t *workspace_bytes)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!workspace_bytes)
+        return MBCONV_EINVAL;
+    const Plan P = make_plan(desc);
+    *workspace_bytes = align_up(P.saved_bytes) + P.scratch_bytes;
+    return MBCONV_OK;
+}
+
+mbconv_status mbconv_forward_eval(const mbconv_desc *desc, const mbconv_params *prm,
+                                  const mbconv_bn_state *running, const void *x, void *out,
+                                  void *workspace, void *hip_stream)
+{
+    return mbconv_forward_eval_probed(desc, prm, running, x, out, workspace, hip_stream, nullptr);
+}
+
+mbconv_status mbconv_forward_eval_probed(const mbconv_desc *desc, const mbconv_params *prm,
+                                         const mbconv_bn_state *running, const void *x, void *out,
+                                         void *workspace, void *hip_stream,
+                                         const mbconv_probe *probe)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!running || !workspace)
+        return MBCONV_EINVAL;
+    if (misaligned(workspace))
+        return MBCONV_EALIGN;
+    const Plan P = make_plan(desc);
+    // the intermediates a training call would save, then its scratch region
+    char *saved = static_cast<char *>(workspace);
+    char *scratch = saved + align_up(P.saved_bytes);
+    return forward_impl(desc, prm, const_cast<mbconv_bn_state *>(running), true, x, out, saved, scratch,
+                        hip_stream, probe);
+}
+
+} // extern "C"
+
+namespace {
+
+// Training mode (eval == false): batch statistics, running statistics updated when run != NULL.
+// Evaluation mode: run is read only and supplies the statistics of all three normalisations;
+// their coefficient blocks come from one launch ahead of everything else, attributed to the
+// first BN-finalise step the block has, and the other finalise steps launch nothing.
+mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mbconv_bn_state *run,
+                           bool eval, const void *x, void *out, void *saved, void *scratch,
+                           void *hip_stream, const mbconv_probe *probe)
+{
     mbconv_status s = check_desc(desc);
     if (s != MBCONV_OK)
         return s;
@@ -285,11 +343,18 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
         return MBCONV_EINVAL;
     if (misaligned(x) || misaligned(out) || misaligned(saved) || misaligned(scratch))
         return MBCONV_EALIGN;
+    if (eval && !run)
+        return MBCONV_EINVAL;
     if (run) {
         if (!run->bn2_mean || !run->bn2_var || !run->bn3_mean || !run->bn3_var)
             return MBCONV_EINVAL;
         if (desc->has_expand && (!run->bn1_mean || !run->bn1_var))
             return MBCONV_EINVAL;
+        const void *all[] = {run->bn1_mean, run->bn1_var, run->bn2_mean,
+                             run->bn2_var,  run->bn3_mean, run->bn3_var};
+        for (const void *q : all)
+            if (q && ((uintptr_t)q & 3u))
+                return MBCONV_EALIGN;
     }
     const Plan P = make_plan(desc);
     hipStream_t st = (hipStream_t)hip_stream;
@@ -302,6 +367,14 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
     void *d = at<char>(saved, P.o_d), *p = at<char>(saved, P.o_p);
     const float eps = desc->bn_eps, mom = desc->bn_momentum;
 
+    const auto eval_coefs = [&]() {
+        return launch_bn_eval_coef(P.expand ? P.Cexp : 0, prm->bn1_gamma, prm->bn1_beta, run->bn1_mean,
+                                   run->bn1_var, bn1, P.Cexp, prm->bn2_gamma, prm->bn2_beta,
+                                   run->bn2_mean, run->bn2_var, bn2, P.Cout, prm->bn3_gamma,
+                                   prm->bn3_beta, run->bn3_mean, run->bn3_var, bn3, eps, st);
+    };
+    if (eval)
+        MBK_STEP(P.expand ? MBCONV_STEP_BN1_FINALIZE : MBCONV_STEP_BN2_FINALIZE, eval_coefs());
     // expansion conv + BN1 statistics
     const void *dw_in = x;
     if (P.expand) {
@@ -311,18 +384,20 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
         B.pro = PRO_NONE;
         MBK_STEP(MBCONV_STEP_EXPAND_CONV, launch_conv1x1(bf, P.N, P.Cexp, P.Cin, P.HW, prm->w_expand, P.Cin, 1, B, e,
                                EPI_STATS, nullptr, psum, psq, nullptr, wg, st));
-        MBK_STEP(MBCONV_STEP_BN1_FINALIZE, launch_bn_finalize(P.Cexp, P.NT1, (double)P.N * P.HW, psum, psq, prm->bn1_gamma,
-                                   prm->bn1_beta, eps, mom, run ? run->bn1_mean : nullptr,
-                                   run ? run->bn1_var : nullptr, bn1, st));
+        if (!eval)
+            MBK_STEP(MBCONV_STEP_BN1_FINALIZE, launch_bn_finalize(P.Cexp, P.NT1, (double)P.N * P.HW, psum, psq, prm->bn1_gamma,
+                                       prm->bn1_beta, eps, mom, run ? run->bn1_mean : nullptr,
+                                       run ? run->bn1_var : nullptr, bn1, st));
         dw_in = e;
     }
     // BN1 + Swish + depthwise + BN2 statistics
     const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
     void *a1_store = (P.store && P.expand) ? at<char>(saved, P.o_a1) : nullptr;
     MBK_STEP(MBCONV_STEP_DW_FWD, launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum, psq, a1_store, st));
-    MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.NPdw, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
-                               prm->bn2_beta, eps, mom, run ? run->bn2_mean : nullptr,
-                               run ? run->bn2_var : nullptr, bn2, st));
+    if (!eval)
+        MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.NPdw, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
+                                   prm->bn2_beta, eps, mom, run ? run->bn2_mean : nullptr,
+                                   run ? run->bn2_var : nullptr, bn2, st));
     // BN2 + Swish + SE squeeze, SE excite
     float *z = at<float>(saved, P.o_z), *g = at<float>(saved, P.o_g), *q = at<float>(saved, P.o_q);
     MBK_STEP(MBCONV_STEP_SE_POOL, launch_pool(bf, P.N, P.Cexp, P.HWo, d, bn2, z, at<float>(saved, P.o_s3),
@@ -340,14 +415,19 @@ mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params
         void *sc_store = P.store ? at<char>(saved, P.o_sc) : nullptr;
         MBK_STEP(MBCONV_STEP_PROJ_CONV, launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p,
                                EPI_STATS, nullptr, psum, psq, sc_store, wg, st));
-        MBK_STEP(MBCONV_STEP_BN3_FINALIZE, launch_bn_finalize(P.Cout, P.NT5, (double)P.N * P.HWo, psum, psq, prm->bn3_gamma,
-                                   prm->bn3_beta, eps, mom, run ? run->bn3_mean : nullptr,
-                                   run ? run->bn3_var : nullptr, bn3, st));
+        if (!eval)
+            MBK_STEP(MBCONV_STEP_BN3_FINALIZE, launch_bn_finalize(P.Cout, P.NT5, (double)P.N * P.HWo, psum, psq, prm->bn3_gamma,
+                                       prm->bn3_beta, eps, mom, run ? run->bn3_mean : nullptr,
+                                       run ? run->bn3_var : nullptr, bn3, st));
     }
     // BN3 (+ residual)
     MBK_STEP(MBCONV_STEP_BN3_APPLY, launch_bn_apply(bf, P.N, P.Cout, P.HWo, p, bn3, P.res ? x : nullptr, out, st));
     return MBCONV_OK;
 }
+
+} // namespace
+
+extern "C" {
 
 mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm, const void *x,
                               const void *dout, const void *saved, void *scratch, void *dx,

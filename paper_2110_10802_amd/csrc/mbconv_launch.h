@@ -52,6 +52,14 @@ hipError_t launch_bn_finalize(int C, int NP, double m, const float *psum, const 
                               const float *gamma, const float *beta, float eps, float momentum,
                               float *run_mean, float *run_var, float *bn, hipStream_t st);
 
+// Evaluation mode: the same blocks from running statistics, three normalisations per launch
+// (C1 = 0 skips the first).
+hipError_t launch_bn_eval_coef(int C1, const float *gamma1, const float *beta1, const float *rm1,
+                               const float *rv1, float *bn1, int C2, const float *gamma2,
+                               const float *beta2, const float *rm2, const float *rv2, float *bn2,
+                               int C3, const float *gamma3, const float *beta3, const float *rm3,
+                               const float *rv3, float *bn3, float eps, hipStream_t st);
+
 // BN backward finalise from partial sums [C][NP] of dy (psb) and dy*xhat (psr):
 //   dbeta = sum psb, dgamma = sum psr, and coef = {c0,c1,c2}[C] such that
 //   dx = c0*dy + c1*raw + c2  equals  gamma*rstd*(dy - dbeta/m - xhat*dgamma/m).

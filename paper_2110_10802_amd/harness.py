@@ -60,6 +60,14 @@ class DeviceBlock:
                          self.scratch, stream)
         return self.out
 
+    def forward_eval(self, x: torch.Tensor, stream: int = 0) -> torch.Tensor:
+        """Evaluation-mode forward (running statistics, nothing saved)."""
+        if getattr(self, "eval_ws", None) is None:
+            nbytes = B.mbconv_eval_workspace_size(self.desc)
+            self.eval_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        B.mbconv_forward_eval(self.desc, self.params, self.running, x, self.out, self.eval_ws, stream)
+        return self.out
+
     def backward(self, x: torch.Tensor, dout: torch.Tensor, stream: int = 0) -> torch.Tensor:
         B.mbconv_backward(self.desc, self.params, x, dout, self.saved, self.scratch, self.dx,
                           self.grads, stream)

@@ -248,3 +248,48 @@ def test_b0_chain_blocks_full_batch(index):
     res, blk = run_gpu_block(s, t)
     f, b = orc.mbconv_step(s, t)
     compare_block(s, t, res, f, b, blk)
+
+
+# ------------------------------------------------------------ evaluation mode ------
+
+def _with_running(s, t, seed):
+    """The block's inputs with running statistics that are neither (0, 1) nor the batch's."""
+    rng = np.random.default_rng(seed)
+    t = dict(t)
+    for i, C_ in ((1, s.Cexp), (2, s.Cexp), (3, s.Cout)):
+        if i == 1 and not s.has_expand:
+            continue
+        t[f"bn{i}_mean"] = (0.3 * rng.standard_normal(C_)).astype(np.float32)
+        t[f"bn{i}_var"] = (0.5 + rng.random(C_)).astype(np.float32)
+    return t
+
+
+@pytest.mark.parametrize("name", ["k3s1_ragged", "k5s1", "k5s2_odd", "noexpand_res", "wide",
+                                  "plane_1024_threads", "max_plane_ragged", "one_pixel",
+                                  "n1_tiny", "bf16_small", "bf16_s2", "config1", "config3"])
+def test_eval_forward_matches_oracle(name):
+    import torch
+    from paper_2110_10802_amd.harness import DeviceBlock, to_numpy
+    from parity_util import metric_for
+
+    s = {"config1": CONFIG1, "config3": CONFIG3}.get(name) or SMALL[name]
+    t = _with_running(s, make_block_inputs(s, seed=5), seed=17)
+    print(f"[parity/eval] {name} {s}", flush=True)
+    ref = orc.mbconv_forward_eval(s, t)
+    blk = DeviceBlock(s, t)
+    x = blk.to_device(t["x"])
+    out = to_numpy(blk.forward_eval(x))
+    torch.cuda.synchronize()
+    err = metric_for(s)(out, ref)
+    print(f"[parity/eval] {name} err {err:.2e}", flush=True)
+    assert err <= TOL[s.dtype]["fwd"], err
+    # the running statistics are inputs here: unchanged, bit for bit
+    for n, r in blk.running.items():
+        assert np.array_equal(to_numpy(r), np.asarray(t[n], dtype=np.float32)), n
+    # a training step in between (it owns other workspaces) does not disturb a second call
+    blk.forward(x)
+    for n, r in blk.running.items():  # restore what the training call updated
+        r.copy_(torch.from_numpy(np.asarray(t[n], dtype=np.float32)))
+    out2 = to_numpy(blk.forward_eval(x))
+    torch.cuda.synchronize()
+    assert np.array_equal(out, out2)
