@@ -11,8 +11,8 @@ beta3, dOut):
   fan_in = Cin (W_e), k*k (w_dw), Cexp (W_p, W1), Cse (W2);
   BN gamma = 1 + 0.1 N(0,1), beta = 0.1 N(0,1); SE biases 0.1 N(0,1);
   running mean 0, running variance 1.
-The shapes are those of EfficientNet-B0's MBConv blocks; the values stand in for
-the ImageNet activations and trained weights the paper's measurement ran on.
+The shapes are those of EfficientNet-B0's MBConv blocks (and one MobileNet-V2 block); the
+values stand in for the ImageNet activations and trained weights the paper's measurement ran on.
 """
 from __future__ import annotations
 
@@ -41,6 +41,8 @@ class BlockShape:
     dtype: str = "f32"  # activation / conv-weight storage: "f32" or "bf16"
     eps: float = BN_EPS
     momentum: float = BN_MOMENTUM
+    activation: str = "swish"  # "swish" (EfficientNet MBConv) or "relu6" (MobileNet-V2 block)
+    has_se: bool = True        # False: no squeeze-and-excitation stage (Cse is ignored)
 
     @property
     def pad(self) -> int:
@@ -90,6 +92,12 @@ def b0_chain(N: int = 64, Cin: int = 32, H: int = 112, dtype: str = "f32") -> Li
 
 CONFIGS = {0: CONFIG0, 1: CONFIG1, 2: CONFIG2, 3: CONFIG3}
 
+# MobileNet-V2 inverted-residual block (ReLU6, no squeeze-and-excitation), the network the paper
+# also times: the stride-1 repeat of its 56x56 stage (24 -> 144 -> 24, 3x3), batch 32 -- the same
+# tensor shapes as config 1, so the two activations can be compared kernel by kernel.
+MBV2_BLOCK = BlockShape(N=32, Cin=24, H=56, W=56, Cexp=144, Cse=1, Cout=24, k=3, stride=1,
+                        residual=True, activation="relu6", has_se=False)
+
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Round fp32 values to the nearest bf16 (ties to even); result stays fp32."""
@@ -132,10 +140,10 @@ def make_block_inputs(s: BlockShape, seed: int = 0, with_x: bool = True,
     t["w_dw"] = normal((s.Cexp, s.k, s.k), np.sqrt(2.0 / (s.k * s.k)))
     t["bn2_gamma"] = normal((s.Cexp,), 0.1, 1.0)
     t["bn2_beta"] = normal((s.Cexp,), 0.1)
-    t["se_w1"] = normal((s.Cse, s.Cexp), np.sqrt(2.0 / s.Cexp))
-    t["se_b1"] = normal((s.Cse,), 0.1)
-    t["se_w2"] = normal((s.Cexp, s.Cse), np.sqrt(2.0 / s.Cse))
-    t["se_b2"] = normal((s.Cexp,), 0.1)
+    se = {"se_w1": normal((s.Cse, s.Cexp), np.sqrt(2.0 / s.Cexp)), "se_b1": normal((s.Cse,), 0.1),
+          "se_w2": normal((s.Cexp, s.Cse), np.sqrt(2.0 / s.Cse)), "se_b2": normal((s.Cexp,), 0.1)}
+    if s.has_se:  # (the draws are made anyway so later tensors do not depend on has_se)
+        t.update(se)
     t["w_proj"] = normal((s.Cout, s.Cexp), np.sqrt(2.0 / s.Cexp))
     t["bn3_gamma"] = normal((s.Cout,), 0.1, 1.0)
     t["bn3_beta"] = normal((s.Cout,), 0.1)

@@ -14,6 +14,9 @@
  *   1x1 expansion conv -> BN(batch statistics) -> Swish ->
  *   kxk depthwise conv -> BN -> Swish -> squeeze-and-excitation ->
  *   1x1 projection conv -> BN -> optional residual.
+ * The MobileNet-V2 inverted-residual block, which the paper also times (table
+ * "Automatic optimization results"), is the same chain with ReLU6 in place of
+ * Swish and no squeeze-and-excitation stage (desc.activation = 1, has_se = 0).
  * Batch normalisation follows the paper's formula in section "Statistical
  * Normalization": gamma*(x-E[x])/sqrt(Var(x)+eps)+beta, with E and Var taken
  * over (N,H,W) per channel, and the running mean/variance written back as that
@@ -52,6 +55,8 @@ typedef struct {
     int k, stride, pad;
     int has_expand, residual;
     double eps, momentum;
+    int activation; /* 0: Swish (EfficientNet MBConv), 1: ReLU6 (MobileNet-V2 inverted residual) */
+    int has_se;     /* 0: no squeeze-and-excitation stage (sc = a2); Cse and the SE parameters are ignored */
 } orc_desc;
 
 typedef struct {
@@ -97,6 +102,23 @@ double orc_swish_grad(double t)
 {
     double s = orc_sigmoid(t);
     return s * (1.0 + t * (1.0 - s));
+}
+
+/* ReLU6(t) = min(max(t, 0), 6), the activation of the MobileNet-V2 inverted-residual block
+ * (one of the networks the paper times, table "Automatic optimization results"); its
+ * derivative is 1 strictly inside (0, 6) and 0 elsewhere, kinks included. */
+double orc_relu6(double t) { return t < 0.0 ? 0.0 : (t > 6.0 ? 6.0 : t); }
+double orc_relu6_grad(double t) { return (t > 0.0 && t < 6.0) ? 1.0 : 0.0; }
+
+/* The block's two activations (after BN1 and after BN2); the SE stage keeps its own Swish
+ * and sigmoid. */
+static double orc_act(int activation, double t)
+{
+    return activation == 1 ? orc_relu6(t) : orc_swish(t);
+}
+static double orc_act_grad(int activation, double t)
+{
+    return activation == 1 ? orc_relu6_grad(t) : orc_swish_grad(t);
 }
 
 /* ---- 1x1 convolution: y[n,o,q] = sum_i W[o,i] x[n,i,q] ------------------- */
@@ -418,8 +440,10 @@ void orc_se_bwd(int N, int C, int Cse, int HW, const double *a2, const double *W
 
 static int desc_ok(const orc_desc *D)
 {
-    if (!D || D->N < 1 || D->Cin < 1 || D->H < 1 || D->W < 1 || D->Cexp < 1 || D->Cse < 1 ||
-        D->Cout < 1 || D->k < 1 || D->stride < 1 || D->pad < 0)
+    if (!D || D->N < 1 || D->Cin < 1 || D->H < 1 || D->W < 1 || D->Cexp < 1 ||
+        (D->has_se && D->Cse < 1) || D->Cout < 1 || D->k < 1 || D->stride < 1 || D->pad < 0)
+        return 0;
+    if (D->activation != 0 && D->activation != 1)
         return 0;
     if (!D->has_expand && D->Cexp != D->Cin)
         return 0;
@@ -449,20 +473,23 @@ int orc_mbconv_forward(const orc_desc *D, const orc_params *P, orc_running *R, c
                    T->var1, R ? R->bn1_mean : NULL, R ? R->bn1_var : NULL, T->xhat1, T->y1);
 #pragma omp parallel for schedule(static)
         for (size_t i = 0; i < nE; ++i)
-            T->a1[i] = orc_swish(T->y1[i]);
+            T->a1[i] = orc_act(D->activation, T->y1[i]);
     } else {
         memcpy(T->a1, x, sizeof(double) * nE);
     }
-    /* depthwise conv, BN2, Swish */
+    /* depthwise conv, BN2, activation */
     orc_depthwise_fwd(N, D->Cexp, D->H, D->W, D->k, D->stride, D->pad, P->w_dw, T->a1, T->d);
     orc_bn_fwd(N, D->Cexp, HWo, T->d, P->bn2_gamma, P->bn2_beta, D->eps, D->momentum, T->mean2,
                T->var2, R ? R->bn2_mean : NULL, R ? R->bn2_var : NULL, T->xhat2, T->y2);
 #pragma omp parallel for schedule(static)
     for (size_t i = 0; i < nD; ++i)
-        T->a2[i] = orc_swish(T->y2[i]);
-    /* squeeze-and-excitation */
-    orc_se_fwd(N, D->Cexp, D->Cse, HWo, T->a2, P->se_w1, P->se_b1, P->se_w2, P->se_b2, T->z, T->q,
-               T->r, T->t, T->g, T->sc);
+        T->a2[i] = orc_act(D->activation, T->y2[i]);
+    /* squeeze-and-excitation (absent in the MobileNet-V2 block: sc = a2) */
+    if (D->has_se)
+        orc_se_fwd(N, D->Cexp, D->Cse, HWo, T->a2, P->se_w1, P->se_b1, P->se_w2, P->se_b2, T->z,
+                   T->q, T->r, T->t, T->g, T->sc);
+    else
+        memcpy(T->sc, T->a2, sizeof(double) * nD);
     /* projection: 1x1 conv, BN3 (no activation), optional residual */
     orc_conv1x1(N, D->Cexp, D->Cout, HWo, P->w_proj, T->sc, T->p);
     orc_bn_fwd(N, D->Cout, HWo, T->p, P->bn3_gamma, P->bn3_beta, D->eps, D->momentum, T->mean3,
@@ -515,8 +542,9 @@ int orc_mbconv_forward_eval(const orc_desc *D, const orc_params *P, const orc_ru
     double *z = (double *)malloc(sizeof(double) * (size_t)N * D->Cexp);
     double *t = (double *)malloc(sizeof(double) * (size_t)N * D->Cexp);
     double *g = (double *)malloc(sizeof(double) * (size_t)N * D->Cexp);
-    double *q = (double *)malloc(sizeof(double) * (size_t)N * D->Cse);
-    double *r = (double *)malloc(sizeof(double) * (size_t)N * D->Cse);
+    const size_t nQ = (size_t)N * (D->has_se ? D->Cse : 1);
+    double *q = (double *)malloc(sizeof(double) * nQ);
+    double *r = (double *)malloc(sizeof(double) * nQ);
     if (!a1 || !e || !d || !a2 || !sc || !p || !z || !t || !g || !q || !r)
         return -2;
     if (D->has_expand) {
@@ -524,7 +552,7 @@ int orc_mbconv_forward_eval(const orc_desc *D, const orc_params *P, const orc_ru
         orc_bn_eval(N, D->Cexp, HW, e, P->bn1_gamma, P->bn1_beta, D->eps, R->bn1_mean, R->bn1_var, a1);
 #pragma omp parallel for schedule(static)
         for (size_t i = 0; i < nE; ++i)
-            a1[i] = orc_swish(a1[i]);
+            a1[i] = orc_act(D->activation, a1[i]);
     } else {
         memcpy(a1, x, sizeof(double) * nE);
     }
@@ -532,9 +560,12 @@ int orc_mbconv_forward_eval(const orc_desc *D, const orc_params *P, const orc_ru
     orc_bn_eval(N, D->Cexp, HWo, d, P->bn2_gamma, P->bn2_beta, D->eps, R->bn2_mean, R->bn2_var, a2);
 #pragma omp parallel for schedule(static)
     for (size_t i = 0; i < nD; ++i)
-        a2[i] = orc_swish(a2[i]);
-    orc_se_fwd(N, D->Cexp, D->Cse, HWo, a2, P->se_w1, P->se_b1, P->se_w2, P->se_b2, z, q, r, t, g,
-               sc);
+        a2[i] = orc_act(D->activation, a2[i]);
+    if (D->has_se)
+        orc_se_fwd(N, D->Cexp, D->Cse, HWo, a2, P->se_w1, P->se_b1, P->se_w2, P->se_b2, z, q, r, t,
+                   g, sc);
+    else
+        memcpy(sc, a2, sizeof(double) * nD);
     orc_conv1x1(N, D->Cexp, D->Cout, HWo, P->w_proj, sc, p);
     orc_bn_eval(N, D->Cout, HWo, p, P->bn3_gamma, P->bn3_beta, D->eps, R->bn3_mean, R->bn3_var, out);
     if (D->residual)
@@ -583,12 +614,15 @@ int orc_mbconv_backward(const orc_desc *D, const orc_params *P, const double *x,
     orc_conv1x1_bwd_input(N, D->Cexp, D->Cout, HWo, P->w_proj, dp, dsc);
     orc_conv1x1_bwd_weight(N, D->Cexp, D->Cout, HWo, T->sc, dp, G->w_proj);
     /* squeeze-and-excitation */
-    orc_se_bwd(N, D->Cexp, D->Cse, HWo, T->a2, P->se_w1, P->se_w2, T->z, T->q, T->r, T->g, dsc,
-               da2, G->se_w1, G->se_b1, G->se_w2, G->se_b2);
-    /* Swish, BN2 */
+    if (D->has_se)
+        orc_se_bwd(N, D->Cexp, D->Cse, HWo, T->a2, P->se_w1, P->se_w2, T->z, T->q, T->r, T->g, dsc,
+                   da2, G->se_w1, G->se_b1, G->se_w2, G->se_b2);
+    else
+        memcpy(da2, dsc, sizeof(double) * nD);
+    /* activation, BN2 */
 #pragma omp parallel for schedule(static)
     for (size_t i = 0; i < nD; ++i)
-        dy2[i] = da2[i] * orc_swish_grad(T->y2[i]);
+        dy2[i] = da2[i] * orc_act_grad(D->activation, T->y2[i]);
     orc_bn_bwd(N, D->Cexp, HWo, dy2, T->xhat2, P->bn2_gamma, T->var2, D->eps, dd, G->bn2_gamma,
                G->bn2_beta);
     /* depthwise conv */
@@ -602,7 +636,7 @@ int orc_mbconv_backward(const orc_desc *D, const orc_params *P, const double *x,
             return -2;
 #pragma omp parallel for schedule(static)
         for (size_t i = 0; i < nE; ++i)
-            dy1[i] = da1[i] * orc_swish_grad(T->y1[i]);
+            dy1[i] = da1[i] * orc_act_grad(D->activation, T->y1[i]);
         orc_bn_bwd(N, D->Cexp, HW, dy1, T->xhat1, P->bn1_gamma, T->var1, D->eps, de,
                    G->bn1_gamma, G->bn1_beta);
         orc_conv1x1_bwd_weight(N, D->Cin, D->Cexp, HW, x, de, G->w_expand);

@@ -33,7 +33,8 @@ def build(force: bool = False) -> str:
 class _Desc(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("N", "Cin", "H", "W", "Cexp", "Cse", "Cout", "k", "stride",
                                         "pad", "has_expand", "residual")] + \
-               [("eps", C.c_double), ("momentum", C.c_double)]
+               [("eps", C.c_double), ("momentum", C.c_double), ("activation", C.c_int),
+                ("has_se", C.c_int)]
 
 
 _PARAMS = ["w_expand", "bn1_gamma", "bn1_beta", "w_dw", "bn2_gamma", "bn2_beta", "se_w1", "se_b1",
@@ -66,7 +67,7 @@ def lib():
     global _lib
     if _lib is None:
         _lib = C.CDLL(build())
-        for name in ("orc_sigmoid", "orc_swish", "orc_swish_grad"):
+        for name in ("orc_sigmoid", "orc_swish", "orc_swish_grad", "orc_relu6", "orc_relu6_grad"):
             f = getattr(_lib, name)
             f.restype = C.c_double
             f.argtypes = [C.c_double]
@@ -88,6 +89,14 @@ def num_threads() -> int:
 
 
 # ---- scalar functions ---------------------------------------------------------
+
+def relu6(t: float) -> float:
+    return float(lib().orc_relu6(float(t)))
+
+
+def relu6_grad(t: float) -> float:
+    return float(lib().orc_relu6_grad(float(t)))
+
 
 def sigmoid(t: float) -> float:
     return lib().orc_sigmoid(float(t))
@@ -211,7 +220,9 @@ def se_bwd(a2, w1, w2, fwd, dsc):
 
 def _desc(s) -> _Desc:
     return _Desc(s.N, s.Cin, s.H, s.W, s.Cexp, s.Cse, s.Cout, s.k, s.stride, s.pad,
-                 int(s.has_expand), int(s.residual), float(s.eps), float(s.momentum))
+                 int(s.has_expand), int(s.residual), float(s.eps), float(s.momentum),
+                 1 if getattr(s, "activation", "swish") == "relu6" else 0,
+                 int(getattr(s, "has_se", True)))
 
 
 def _params_struct(s, t, keep):

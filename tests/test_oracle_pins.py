@@ -349,6 +349,20 @@ def test_block_bn_invariants_inside_the_block():
                        (1 - s.momentum) + s.momentum * f.tape["var3"] * m / (m - 1))
 
 
+_MBV2 = [BlockShape(N=2, Cin=8, H=10, W=12, Cexp=48, Cse=1, Cout=8, k=3, stride=1, residual=True,
+                    activation="relu6", has_se=False),
+         BlockShape(N=3, Cin=8, H=9, W=9, Cexp=24, Cse=1, Cout=12, k=3, stride=2, residual=False,
+                    activation="relu6", has_se=False),
+         BlockShape(N=2, Cin=16, H=8, W=8, Cexp=16, Cse=1, Cout=8, k=3, stride=1, has_expand=False,
+                    residual=False, activation="relu6", has_se=False),
+         # the two switches are independent: ReLU6 with the SE stage, Swish without it
+         BlockShape(N=2, Cin=8, H=7, W=7, Cexp=24, Cse=2, Cout=8, k=5, stride=1, residual=True,
+                    activation="relu6"),
+         BlockShape(N=2, Cin=8, H=7, W=7, Cexp=24, Cse=1, Cout=8, k=3, stride=1, residual=True,
+                    has_se=False)]
+_MBV2_IDS = ["mbv2_s1", "mbv2_s2", "mbv2_t1", "relu6_se", "swish_nose"]
+
+
 def _torch_block(s, t):
     """The same block assembled from PyTorch CPU float64 library ops with autograd."""
     import torch
@@ -364,15 +378,17 @@ def _torch_block(s, t):
         return F.batch_norm(v, run[f"bn{i}_mean"], run[f"bn{i}_var"], tt[f"bn{i}_gamma"],
                             tt[f"bn{i}_beta"], training=True, momentum=s.momentum, eps=s.eps)
 
+    act = F.relu6 if s.activation == "relu6" else F.silu
     a = x
     if s.has_expand:
-        a = F.silu(bn(F.conv2d(a, tt["w_expand"][:, :, None, None]), 1))
+        a = act(bn(F.conv2d(a, tt["w_expand"][:, :, None, None]), 1))
     a = F.conv2d(a, tt["w_dw"][:, None], stride=s.stride, padding=s.pad, groups=s.Cexp)
-    a = F.silu(bn(a, 2))
-    z = a.mean(dim=(2, 3))
-    r = F.silu(z @ tt["se_w1"].T + tt["se_b1"])
-    g = torch.sigmoid(r @ tt["se_w2"].T + tt["se_b2"])
-    a = a * g[:, :, None, None]
+    a = act(bn(a, 2))
+    if s.has_se:
+        z = a.mean(dim=(2, 3))
+        r = F.silu(z @ tt["se_w1"].T + tt["se_b1"])
+        g = torch.sigmoid(r @ tt["se_w2"].T + tt["se_b2"])
+        a = a * g[:, :, None, None]
     out = bn(F.conv2d(a, tt["w_proj"][:, :, None, None]), 3)
     if s.residual:
         out = out + x
@@ -383,8 +399,8 @@ def _torch_block(s, t):
 
 @pytest.mark.parametrize("s", [CONFIG0, _tiny(Cout=3, residual=False, stride=2, k=5, H=8, W=8),
                                BlockShape(N=3, Cin=8, H=9, W=9, Cexp=8, Cse=2, Cout=8, k=3,
-                                          stride=1, has_expand=False, residual=True)],
-                         ids=["config0", "k5s2", "noexpand"])
+                                          stride=1, has_expand=False, residual=True)] + _MBV2,
+                         ids=["config0", "k5s2", "noexpand"] + _MBV2_IDS)
 def test_block_vs_pytorch_fp64_autograd(s):
     t = make_block_inputs(s, 0)
     f, b = orc.mbconv_step(s, t)
@@ -426,8 +442,8 @@ def test_bn_eval_closed_form():
 
 @pytest.mark.parametrize("s", [CONFIG0, _tiny(Cout=3, residual=False, stride=2, k=5, H=8, W=8),
                                BlockShape(N=3, Cin=8, H=9, W=9, Cexp=8, Cse=2, Cout=8, k=3,
-                                          stride=1, has_expand=False, residual=True)],
-                         ids=["config0", "k5s2", "noexpand"])
+                                          stride=1, has_expand=False, residual=True)] + _MBV2,
+                         ids=["config0", "k5s2", "noexpand"] + _MBV2_IDS)
 def test_eval_block_with_batch_statistics_is_the_training_block(s):
     # Training mode normalises with the batch mean and the biased batch variance; handing
     # exactly those to the evaluation-mode block must reproduce the training output.
@@ -448,8 +464,8 @@ def test_eval_block_with_batch_statistics_is_the_training_block(s):
 
 @pytest.mark.parametrize("s", [CONFIG0, _tiny(Cout=3, residual=False, stride=2, k=5, H=8, W=8),
                                BlockShape(N=3, Cin=8, H=9, W=9, Cexp=8, Cse=2, Cout=8, k=3,
-                                          stride=1, has_expand=False, residual=True)],
-                         ids=["config0", "k5s2", "noexpand"])
+                                          stride=1, has_expand=False, residual=True)] + _MBV2,
+                         ids=["config0", "k5s2", "noexpand"] + _MBV2_IDS)
 def test_eval_block_vs_pytorch_fp64(s):
     import torch
     import torch.nn.functional as F
@@ -463,16 +479,69 @@ def test_eval_block_vs_pytorch_fp64(s):
                             tt[f"bn{i}_beta"], training=False, eps=s.eps)
 
     x = tt["x"]
+    act = F.relu6 if s.activation == "relu6" else F.silu
     a = x
     if s.has_expand:
-        a = F.silu(bn(F.conv2d(a, tt["w_expand"][:, :, None, None]), 1))
+        a = act(bn(F.conv2d(a, tt["w_expand"][:, :, None, None]), 1))
     a = F.conv2d(a, tt["w_dw"][:, None], stride=s.stride, padding=s.pad, groups=s.Cexp)
-    a = F.silu(bn(a, 2))
-    z = a.mean(dim=(2, 3))
-    r = F.silu(z @ tt["se_w1"].T + tt["se_b1"])
-    g = torch.sigmoid(r @ tt["se_w2"].T + tt["se_b2"])
-    out = bn(F.conv2d(a * g[:, :, None, None], tt["w_proj"][:, :, None, None]), 3)
+    a = act(bn(a, 2))
+    if s.has_se:
+        z = a.mean(dim=(2, 3))
+        r = F.silu(z @ tt["se_w1"].T + tt["se_b1"])
+        g = torch.sigmoid(r @ tt["se_w2"].T + tt["se_b2"])
+        a = a * g[:, :, None, None]
+    out = bn(F.conv2d(a, tt["w_proj"][:, :, None, None]), 3)
     if s.residual:
         out = out + x
     got = orc.mbconv_forward_eval(s, t, run)
     assert np.allclose(got, out.numpy(), rtol=1e-10, atol=1e-11)
+
+
+# ------------------------------------------- ReLU6, no squeeze-and-excitation ------
+
+def test_relu6_closed_forms():
+    for t, v, g in ((-2.0, 0.0, 0.0), (-1e-9, 0.0, 0.0), (0.0, 0.0, 0.0), (1e-9, 1e-9, 1.0),
+                    (3.25, 3.25, 1.0), (6.0 - 1e-9, 6.0 - 1e-9, 1.0), (6.0, 6.0, 0.0),
+                    (7.5, 6.0, 0.0)):
+        assert orc.relu6(t) == v
+        assert orc.relu6_grad(t) == g
+
+
+def test_block_without_se_is_the_se_block_with_gate_one():
+    # W2 = 0 and b2 = 40 make the gate sigmoid(40) = 1 - 4e-18: the block with the SE stage
+    # then computes what the block without it computes, and the remaining gradients agree.
+    s = _tiny()
+    t = make_block_inputs(s, 9)
+    t["se_w2"] = np.zeros_like(t["se_w2"])
+    t["se_b2"] = np.full_like(t["se_b2"], 40.0)
+    f1, b1 = orc.mbconv_step(s, t)
+    from dataclasses import replace
+    s0 = replace(s, has_se=False)
+    t0 = {k: v for k, v in t.items() if not k.startswith("se_")}
+    f0, b0 = orc.mbconv_step(s0, t0)
+    assert np.allclose(f0.out, f1.out, rtol=1e-13, atol=1e-13)
+    assert np.allclose(b0.dx, b1.dx, rtol=1e-12, atol=1e-13)
+    for n, g in b0.grads.items():
+        assert np.allclose(g, b1.grads[n], rtol=1e-12, atol=1e-12), n
+
+
+def test_relu6_block_inside_the_linear_range_is_the_linear_block():
+    # Betas of 3 and small gammas keep every pre-activation inside (0, 6), where ReLU6 is the
+    # identity: the block is then conv -> BN -> depthwise -> BN -> conv -> BN assembled from
+    # the separately pinned primitives.
+    s = BlockShape(N=2, Cin=6, H=7, W=7, Cexp=12, Cse=1, Cout=6, k=3, stride=1, residual=True,
+                   activation="relu6", has_se=False)
+    t = make_block_inputs(s, 4)
+    for i in (1, 2):
+        t[f"bn{i}_gamma"] = (0.2 * t[f"bn{i}_gamma"]).astype(np.float32)
+        t[f"bn{i}_beta"] = np.full_like(t[f"bn{i}_beta"], 3.0)
+    f = orc.mbconv_forward(s, t)
+    assert f.tape["y1"].min() > 0 and f.tape["y1"].max() < 6
+    assert f.tape["y2"].min() > 0 and f.tape["y2"].max() < 6
+    e = orc.conv1x1(t["w_expand"], t["x"])
+    y1 = orc.bn_fwd(e, t["bn1_gamma"], t["bn1_beta"], s.eps, s.momentum)[0]
+    d = orc.depthwise_fwd(t["w_dw"], y1, s.stride, s.pad)
+    y2 = orc.bn_fwd(d, t["bn2_gamma"], t["bn2_beta"], s.eps, s.momentum)[0]
+    p = orc.conv1x1(t["w_proj"], y2)
+    out = orc.bn_fwd(p, t["bn3_gamma"], t["bn3_beta"], s.eps, s.momentum)[0] + t["x"]
+    assert np.allclose(f.out, out, rtol=1e-12, atol=1e-12)
