@@ -235,7 +235,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4])
+    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4, 5],
+                    help="0-3: single MBConv blocks, 4: the EfficientNet-B0 chain, 5: a MobileNet-V2 "
+                         "inverted-residual block (ReLU6, no SE) with config 1's tensor shapes")
     ap.add_argument("--policy", default="recompute", choices=["recompute", "store"])
     ap.add_argument("--mode", default="train", choices=["train", "eval"],
                     help="train: forward+backward (the headline metric); eval: the evaluation-mode "
@@ -307,6 +309,8 @@ def main() -> int:
     for name, sid in B.STEPS.items():
         if not shape.has_expand and name in NO_EXPAND_STEPS:
             continue
+        if not getattr(shape, "has_se", True) and name == "se_pool":
+            continue
         if evalm and (sid > 9 or name in ("bn2_finalize", "bn3_finalize")
                       or (name == "bn1_finalize" and not shape.has_expand)):
             continue  # backward steps, and finalise steps that do not occur in evaluation mode
@@ -367,7 +371,9 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": workload, "block": f"N{shape.N} {shape.Cin}->{shape.Cexp}->{shape.Cout} "
                    f"{shape.H}x{shape.W} k{shape.k}s{shape.stride} se{shape.Cse} "
-                   f"res{int(shape.residual)}", "policy": args.policy, "mode": args.mode},
+                   f"res{int(shape.residual)}" + ("" if getattr(shape, "has_se", True) else " no-se") +
+                   (" relu6" if getattr(shape, "activation", "swish") == "relu6" else ""),
+                   "policy": args.policy, "mode": args.mode},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((workload, dominant)),

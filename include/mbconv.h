@@ -56,6 +56,12 @@ typedef enum { MBCONV_F32 = 0, MBCONV_BF16 = 1 } mbconv_dtype;
  * backward reads those instead of rebuilding them. */
 typedef enum { MBCONV_RECOMPUTE = 0, MBCONV_STORE = 1 } mbconv_policy;
 
+/* The block's activation after BN1 and after BN2.  Swish is the EfficientNet MBConv block;
+ * ReLU6 = min(max(t,0),6) (derivative 1 strictly inside (0,6), else 0) together with no_se = 1
+ * is the MobileNet-V2 inverted-residual block, which the paper also times (table "Automatic
+ * optimization results").  The SE stage, when present, keeps its own Swish and sigmoid. */
+typedef enum { MBCONV_ACT_SWISH = 0, MBCONV_ACT_RELU6 = 1 } mbconv_activation;
+
 typedef struct {
     int32_t N, Cin, H, W; /* input x is [N,Cin,H,W] */
     int32_t Cexp;         /* expanded channels; must equal Cin when has_expand == 0 */
@@ -67,6 +73,9 @@ typedef struct {
     int32_t policy;       /* mbconv_policy */
     float bn_eps;         /* added to the biased batch variance */
     float bn_momentum;    /* running <- (1-momentum)*running + momentum*batch */
+    int32_t activation;   /* mbconv_activation */
+    int32_t no_se;        /* 1: no squeeze-and-excitation stage (the projection conv consumes the
+                             activation of BN2 directly); Cse and the se_* members are ignored */
 } mbconv_desc;
 
 /* Parameters, read-only in both calls. */
@@ -75,8 +84,8 @@ typedef struct {
     const float *bn1_gamma, *bn1_beta;  /* [Cexp]; NULL iff !has_expand */
     const void *w_dw;                   /* [Cexp,k,k]   dtype */
     const float *bn2_gamma, *bn2_beta;  /* [Cexp] */
-    const float *se_w1, *se_b1;         /* [Cse,Cexp], [Cse] */
-    const float *se_w2, *se_b2;         /* [Cexp,Cse], [Cexp] */
+    const float *se_w1, *se_b1;         /* [Cse,Cexp], [Cse]; ignored (may be NULL) when no_se */
+    const float *se_w2, *se_b2;         /* [Cexp,Cse], [Cexp]; ignored (may be NULL) when no_se */
     const void *w_proj;                 /* [Cout,Cexp]  dtype */
     const float *bn3_gamma, *bn3_beta;  /* [Cout] */
 } mbconv_params;
@@ -90,7 +99,8 @@ typedef struct {
 } mbconv_bn_state;
 
 /* Parameter gradients, all fp32, same shapes as mbconv_params; OVERWRITTEN, never
- * accumulated.  w_expand, bn1_gamma, bn1_beta may be NULL iff !has_expand. */
+ * accumulated.  w_expand, bn1_gamma, bn1_beta may be NULL iff !has_expand; the se_* members
+ * are not touched (may be NULL) when no_se. */
 typedef struct {
     float *w_expand;
     float *bn1_gamma, *bn1_beta;
@@ -177,8 +187,8 @@ typedef enum {
     MBCONV_STEP_BN1_FINALIZE = 2,
     MBCONV_STEP_DW_FWD = 3,        /* BN1 + Swish + depthwise conv + BN2 partial statistics */
     MBCONV_STEP_BN2_FINALIZE = 4,
-    MBCONV_STEP_SE_POOL = 5,       /* BN2 + Swish + plane means */
-    MBCONV_STEP_SE_FC = 6,
+    MBCONV_STEP_SE_POOL = 5,       /* BN2 + Swish + plane means; does not occur when no_se */
+    MBCONV_STEP_SE_FC = 6,         /* when no_se: fills the gate with ones */
     MBCONV_STEP_PROJ_CONV = 7,     /* (BN2 + Swish)*gate + 1x1 projection conv + BN3 partials */
     MBCONV_STEP_BN3_FINALIZE = 8,
     MBCONV_STEP_BN3_APPLY = 9,     /* BN3 (+ residual) */
@@ -188,7 +198,7 @@ typedef enum {
     MBCONV_STEP_PROJ_DGRAD = 12,
     MBCONV_STEP_PROJ_WGRAD = 13,
     MBCONV_STEP_GATE_SUMS = 14,
-    MBCONV_STEP_SE_BWD = 15,
+    MBCONV_STEP_SE_BWD = 15,       /* when no_se: BN2's parameter gradients and backward coefficients only */
     MBCONV_STEP_DW_BWD = 16,       /* BN2 backward + depthwise dgrad/wgrad + Swish' + BN1 partials */
     MBCONV_STEP_DW_WGRAD_REDUCE = 17,  /* sum of the filter-gradient partials; with an expansion conv the same
                                           launch also finalises BN1's backward */

@@ -90,13 +90,15 @@ def b0_chain(N: int = 64, Cin: int = 32, H: int = 112, dtype: str = "f32") -> Li
     return blocks
 
 
-CONFIGS = {0: CONFIG0, 1: CONFIG1, 2: CONFIG2, 3: CONFIG3}
 
 # MobileNet-V2 inverted-residual block (ReLU6, no squeeze-and-excitation), the network the paper
 # also times: the stride-1 repeat of its 56x56 stage (24 -> 144 -> 24, 3x3), batch 32 -- the same
 # tensor shapes as config 1, so the two activations can be compared kernel by kernel.
 MBV2_BLOCK = BlockShape(N=32, Cin=24, H=56, W=56, Cexp=144, Cse=1, Cout=24, k=3, stride=1,
                         residual=True, activation="relu6", has_se=False)
+
+# 0-3: the single-block benchmark configurations; 5: the MobileNet-V2 block (4 is the chain)
+CONFIGS = {0: CONFIG0, 1: CONFIG1, 2: CONFIG2, 3: CONFIG3, 5: MBV2_BLOCK}
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:

@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libmbconv.so")
 
 MBCONV_F32, MBCONV_BF16 = 0, 1
 MBCONV_RECOMPUTE, MBCONV_STORE = 0, 1
-ABI_VERSION = 2
+MBCONV_ACT_SWISH, MBCONV_ACT_RELU6 = 0, 1
+ABI_VERSION = 3
 ABSENT = C.c_size_t(-1).value
 
 PARAM_NAMES = ["w_expand", "bn1_gamma", "bn1_beta", "w_dw", "bn2_gamma", "bn2_beta", "se_w1",
@@ -45,7 +46,8 @@ class MBConvError(RuntimeError):
 class Desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("N", "Cin", "H", "W", "Cexp", "Cse", "Cout", "k", "stride",
                                           "pad", "has_expand", "residual", "dtype", "policy")] + \
-               [("bn_eps", C.c_float), ("bn_momentum", C.c_float)]
+               [("bn_eps", C.c_float), ("bn_momentum", C.c_float), ("activation", C.c_int32),
+                ("no_se", C.c_int32)]
 
 
 class Params(C.Structure):
@@ -129,7 +131,9 @@ def make_desc(shape: Any, policy: int = MBCONV_RECOMPUTE) -> Desc:
     return Desc(shape.N, shape.Cin, shape.H, shape.W, shape.Cexp, shape.Cse, shape.Cout, shape.k,
                 shape.stride, shape.pad, int(shape.has_expand), int(shape.residual),
                 MBCONV_BF16 if shape.dtype == "bf16" else MBCONV_F32, int(policy),
-                float(shape.eps), float(shape.momentum))
+                float(shape.eps), float(shape.momentum),
+                MBCONV_ACT_RELU6 if getattr(shape, "activation", "swish") == "relu6" else MBCONV_ACT_SWISH,
+                0 if getattr(shape, "has_se", True) else 1)
 
 
 def _fill(struct, tensors: Optional[Dict[str, Any]]):

@@ -31,12 +31,15 @@ def build(force: bool = True, verbose: bool = False) -> str:
     headers.append(os.path.join(HERE, "..", "include", "mbconv.h"))
     newest_hdr = max(os.path.getmtime(h) for h in headers)
 
-    def compile_one(src: str) -> str:
+    def compile_one(job) -> str:
+        src, relu6 = job
         s = os.path.join(CSRC, src)
-        o = os.path.join(OBJ, src.replace(".hip", ".o"))
+        o = os.path.join(OBJ, src.replace(".hip", "_r6.o" if relu6 else ".o"))
         if not force and os.path.exists(o) and os.path.getmtime(o) > max(os.path.getmtime(s), newest_hdr):
             return o
-        cmd = [hipcc, *FLAGS, "-c", s, "-o", o]
+        # second pass: the same sources with ReLU6 as the block activation, in namespace mbk_r6
+        extra = ["-DMBK_ACT_RELU6=1", "-Dmbk=mbk_r6"] if relu6 else []
+        cmd = [hipcc, *FLAGS, *extra, "-c", s, "-o", o]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0 or verbose:
             sys.stderr.write(r.stdout + r.stderr)
@@ -44,8 +47,9 @@ def build(force: bool = True, verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}")
         return o
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
+    jobs = [(src, relu6) for relu6 in (False, True) for src in SOURCES]
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 4)) as ex:
+        objs = list(ex.map(compile_one, jobs))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

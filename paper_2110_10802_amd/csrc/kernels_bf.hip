@@ -43,7 +43,7 @@ __device__ __forceinline__ float bf_apply(float v0, float v1, float k0, float k1
     if (PRO == PRO_NONE)
         return v0;
     if (PRO == PRO_BNSWISH_GATE)
-        return swishf(fmaf(v0, k0, k1)) * k2;
+        return actf(fmaf(v0, k0, k1)) * k2;
     return fmaf(k0, v0, fmaf(k1, v1, k2));
 }
 __device__ __forceinline__ bf16x8 bf_lds8(const uint16_t *p)

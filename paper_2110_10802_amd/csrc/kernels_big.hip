@@ -104,7 +104,7 @@ struct Staged {
         if (PRO == PRO_NONE)
             return v0[j];
         if (PRO == PRO_BNSWISH_GATE)
-            return swishf(fmaf(v0[j], k0, k1)) * k2;
+            return actf(fmaf(v0[j], k0, k1)) * k2;
         return fmaf(k0, v0[j], fmaf(k1, v1[PRO == PRO_BNBWD ? j : 0], k2));
     }
 };

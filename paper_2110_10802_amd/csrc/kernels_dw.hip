@@ -115,7 +115,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw_fwd_kernel(DwFwdDev 
             if (h >= 0 && h < H && x >= 0 && x < W) {
                 v = ld<T>((const T *)a.e, base + (size_t)h * W + x);
                 if (bn)
-                    v = swishf(fmaf(v, scale, shift));
+                    v = actf(fmaf(v, scale, shift));
                 if (a.a1_store)
                     st<T>((T *)a.a1_store, base + (size_t)h * W + x, v);
             }
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw_bwd_kernel(DwBwdDev 
                 } else {
                     v = ld<T>((const T *)a.e, ebase + (size_t)h * W + x);
                     if (bn)
-                        v = swishf(fmaf(v, scale1, shift1));
+                        v = actf(fmaf(v, scale1, shift1));
                 }
             }
             a1t[idx] = v;
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw_bwd_kernel(DwBwdDev 
                 const float Gv = ld<T>((const T *)a.G, dbase + (size_t)i * Wo + j);
                 const float dv = ld<T>((const T *)a.d, dbase + (size_t)i * Wo + j);
                 float val, grad;
-                swish_both(fmaf(dv, scale2, shift2), val, grad);
+                act_both(fmaf(dv, scale2, shift2), val, grad);
                 const float dy2 = fmaf(Gv, gate, dzs) * grad;
                 v = fmaf(c0, dy2, fmaf(c1, dv, c2));
             }
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw_bwd_kernel(DwBwdDev 
             if (bn) {
                 const float raw = ld<T>((const T *)a.e, ebase + idx);
                 float val, grad;
-                swish_both(fmaf(raw, scale1, shift1), val, grad);
+                act_both(fmaf(raw, scale1, shift1), val, grad);
                 const float dy1 = da * grad;
                 st<T>((T *)a.dy1_out, ebase + idx, dy1);
                 const float sv = as_stored<T>(dy1);
@@ -547,7 +547,7 @@ struct OpPool {
                                                 float rs, float (&acc)[NV])
     {
         float val, grad;
-        swish_both(fmaf(v, sc, sh), val, grad);
+        act_both(fmaf(v, sc, sh), val, grad);
         acc[0] += val;
         acc[1] += grad;
         acc[2] = fmaf(grad, (v - mu) * rs, acc[2]);
@@ -572,7 +572,7 @@ struct OpGate {
                                                 float rs, float (&acc)[NV])
     {
         float val, grad;
-        swish_both(fmaf(v, sc, sh), val, grad);
+        act_both(fmaf(v, sc, sh), val, grad);
         acc[0] = fmaf(Gv, val, acc[0]);
         acc[1] = fmaf(Gv, grad, acc[1]);
         acc[2] = fmaf(Gv * grad, (v - mu) * rs, acc[2]);

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_fwd_kernel(Dw2Args 
                 float v[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    v[r] = x0 + r < W ? (EXPAND ? swishf(fmaf(ev[i][r], scale, shift)) : ev[i][r]) : 0.f;
+                    v[r] = x0 + r < W ? (EXPAND ? actf(fmaf(ev[i][r], scale, shift)) : ev[i][r]) : 0.f;
                 *reinterpret_cast<float4v *>(tile + (h + P) * WP + 4 + x0) =
                     float4v{v[0], v[1], v[2], v[3]};
             }
@@ -347,10 +347,10 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
                 for (int r = 0; r < 4; ++r) {
                     if (EXPAND) {
                         const float y = fmaf(evA[i][r], scale1, shift1);
-                        const float sg = sigmoidf_fast(y);
+                        const float sg = act_aux(y);
                         rawk[i][r] = evA[i][r];
                         sgk[i][r] = sg;
-                        av[r] = y * sg;
+                        av[r] = act_val(y, sg);
                     } else {
                         av[r] = evA[i][r];
                     }
@@ -365,8 +365,8 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float y2 = fmaf(dv[r], scale2, shift2);
-                const float s2 = sigmoidf_fast(y2);
-                const float grad2 = s2 * (1.f + y2 * (1.f - s2));
+                const float s2 = act_aux(y2);
+                const float grad2 = act_grad(y2, s2);
                 const float dy2 = fmaf(Gv[r], gate, dzs) * grad2;
                 ddv[r] = oj0 + r < Wo ? fmaf(c0, dy2, fmaf(c1, dv[r], c2)) : 0.f;
             }
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
                     for (int r = 0; r < 4; ++r) {
                         const float raw = rawk[i][r], sg = sgk[i][r];
                         const float y = fmaf(raw, scale1, shift1);
-                        o[r] = da[r] * (sg * (1.f + y * (1.f - sg)));
+                        o[r] = da[r] * act_grad(y, sg);
                         if (x0 + r < W) {
                             const float sv = as_stored<T>(o[r]);
                             acc[K * K] += sv;

@@ -183,7 +183,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_fwd_kernel(Dw4Args 
                 if (EXPAND) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        v[r] = swishf(fmaf(v[r], scale, shift));
+                        v[r] = actf(fmaf(v[r], scale, shift));
                 }
                 float4v t4 = {v[0], v[1], v[2], v[3]};
                 *reinterpret_cast<float4v *>(tile + (h + P) * WP + 4 + w) = t4;
@@ -291,16 +291,16 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_bwd_kernel(Dw4Args 
                 for (int r = 0; r < 4; ++r) {
                     if (EXPAND) {
                         const float y = fmaf(ev[r], scale1, shift1);
-                        const float sg = sigmoidf_fast(y);
+                        const float sg = act_aux(y);
                         rawk[i][r] = ev[r];
                         sgk[i][r] = sg;
-                        av[r] = y * sg;
+                        av[r] = act_val(y, sg);
                     } else {
                         av[r] = ev[r];
                     }
                     const float y2 = fmaf(dv[r], scale2, shift2);
-                    const float s2 = sigmoidf_fast(y2);
-                    const float grad2 = s2 * (1.f + y2 * (1.f - s2));
+                    const float s2 = act_aux(y2);
+                    const float grad2 = act_grad(y2, s2);
                     const float dy2 = fmaf(Gv[r], gate, dzs) * grad2;
                     ddv[r] = fmaf(c0, dy2, fmaf(c1, dv[r], c2));
                 }
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_bwd_kernel(Dw4Args 
                     for (int r = 0; r < 4; ++r) {
                         const float raw = rawk[i][r], sg = sgk[i][r];
                         const float y = fmaf(raw, scale1, shift1);
-                        o[r] = da[r] * (sg * (1.f + y * (1.f - sg)));
+                        o[r] = da[r] * act_grad(y, sg);
                         const float sv = as_stored<T>(o[r]);
                         acc[K * K] += sv;
                         acc[K * K + 1] = fmaf(sv, (raw - mean1) * rstd1, acc[K * K + 1]);

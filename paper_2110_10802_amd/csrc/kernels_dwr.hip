@@ -255,7 +255,7 @@ __global__ __launch_bounds__(256) void dwr_fwd_kernel(DwrArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const bool m = ok && L.x0 + r < W;
-                const float v = EXPAND ? swishf(fmaf(pe[r], scale, shift)) : pe[r];
+                const float v = EXPAND ? actf(fmaf(pe[r], scale, shift)) : pe[r];
                 av[r] = m ? v : 0.f;
             }
             *reinterpret_cast<float4v *>(tile + (L.h + P) * WP + 4 + L.x0) =
@@ -362,15 +362,15 @@ __global__ __launch_bounds__(256) void dwr_bwd_kernel(DwrArgs a)
                 float v = pe[r];
                 if (EXPAND) {
                     const float y = fmaf(pe[r], scale1, shift1);
-                    const float sg = sigmoidf_fast(y);
+                    const float sg = act_aux(y);
                     rawk[r] = pe[r];
                     sgk[r] = sg;
-                    v = y * sg;
+                    v = act_val(y, sg);
                 }
                 av[r] = m ? v : 0.f;
                 const float y2 = fmaf(pd[r], scale2, shift2);
-                const float s2 = sigmoidf_fast(y2);
-                const float grad2 = s2 * (1.f + y2 * (1.f - s2));
+                const float s2 = act_aux(y2);
+                const float grad2 = act_grad(y2, s2);
                 const float dy2 = fmaf(pG[r], pgate, pdzs) * grad2;
                 ddv[r] = m ? fmaf(c0, dy2, fmaf(c1, pd[r], c2)) : 0.f;
             }
@@ -420,7 +420,7 @@ __global__ __launch_bounds__(256) void dwr_bwd_kernel(DwrArgs a)
                 for (int r = 0; r < 4; ++r) {
                     const float raw = rawk[r], sg = sgk[r];
                     const float y = fmaf(raw, scale1, shift1);
-                    o[r] = da[r] * (sg * (1.f + y * (1.f - sg)));
+                    o[r] = da[r] * act_grad(y, sg);
                     if (L.x0 + r < W) {
                         const float sv = as_stored<T>(o[r]);
                         acc[K * K] += sv;

@@ -33,7 +33,7 @@ __device__ __forceinline__ float load_operand(const DevOperand &o, int n, int c,
         return v;
     } else if (PRO == PRO_BNSWISH_GATE) {
         const float y = fmaf(v, o.c0[c], o.c1[c]);
-        return swishf(y) * o.gate[(size_t)n * C + c];
+        return actf(y) * o.gate[(size_t)n * C + c];
     } else {
         const float raw = ld<T>((const T *)o.p1, idx);
         return fmaf(o.c0[c], v, fmaf(o.c1[c], raw, o.c2[c]));

@@ -131,6 +131,20 @@ hipError_t launch_bn_eval_coef(int C1, const float *gamma1, const float *beta1, 
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void fill_kernel(float *out, float value, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count)
+        out[i] = value;
+}
+
+hipError_t launch_fill(float *out, float value, size_t count, hipStream_t st)
+{
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, out,
+                       value, count);
+    return hipGetLastError();
+}
+
 // dx = gamma*rstd*(dy - dbeta/m - xhat*dgamma/m) with xhat = (raw-mean)*rstd, rewritten as
 // c0*dy + c1*raw + c2 so the consumer's prologue is two fused multiply-adds.
 __device__ __forceinline__ void bn_bwd_coef_vals(int C, int c, double m, double dgamma, double dbeta,
@@ -199,6 +213,44 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(int C, int NP, dou
                                                               float *coef)
 {
     bn_bwd_finalize_body(blockIdx.x, C, NP, m, psb, psr, gamma, bn, dgamma, dbeta, coef);
+}
+
+// Block without squeeze-and-excitation: one wavefront per channel adds the plane sums of the
+// batch in a fixed order (lane l takes images l, l+64, ...; fp64 butterfly), writes BN2's
+// parameter gradients and backward coefficients, and zeroes the channel's column of dzs.
+__global__ __launch_bounds__(256) void bn2_bwd_nose_kernel(int N, int C, double m,
+                                                           const float *__restrict__ A1,
+                                                           const float *__restrict__ A2,
+                                                           const float *__restrict__ gamma,
+                                                           const float *__restrict__ bn,
+                                                           float *dgamma, float *dbeta, float *coef,
+                                                           float *dzs)
+{
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (c >= C)
+        return;
+    double sb = 0.0, sr = 0.0;
+    for (int n = lane; n < N; n += kWave) {
+        sb += (double)A1[(size_t)n * C + c];
+        sr += (double)A2[(size_t)n * C + c];
+        dzs[(size_t)n * C + c] = 0.f;
+    }
+    sb = wave_sum_d(sb);
+    sr = wave_sum_d(sr);
+    if (lane == 0) {
+        dbeta[c] = (float)sb;
+        dgamma[c] = (float)sr;
+        bn_bwd_coef(C, c, m, sr, sb, gamma[c], bn, coef);
+    }
+}
+
+hipError_t launch_bn2_bwd_nose(int N, int C, double m, const float *A1, const float *A2,
+                               const float *gamma, const float *bn, float *dgamma, float *dbeta,
+                               float *coef, float *dzs, hipStream_t st)
+{
+    hipLaunchKernelGGL(bn2_bwd_nose_kernel, dim3((C + 3) / 4), dim3(256), 0, st, N, C, m, A1, A2,
+                       gamma, bn, dgamma, dbeta, coef, dzs);
+    return hipGetLastError();
 }
 
 hipError_t launch_bn_bwd_finalize(int C, int NP, double m, const float *psb, const float *psr,

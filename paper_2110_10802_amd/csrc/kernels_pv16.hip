@@ -120,7 +120,7 @@ __device__ __forceinline__ void pv_apply(const PvRaw<PRO> &o, int k, const float
         const float sc = coef[k], sh = coef[cstride + k];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            v[r] = swishf(fmaf(o.v[r], sc, sh)) * o.g;
+            v[r] = actf(fmaf(o.v[r], sc, sh)) * o.g;
     } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r)

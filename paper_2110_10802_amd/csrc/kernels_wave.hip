@@ -78,7 +78,7 @@ __device__ __forceinline__ void load_chan4(const void *p0, const void *p1, const
         const float g = gate[(size_t)n * C + c];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            v[r] = swishf(fmaf(v[r], k0, k1)) * g;
+            v[r] = actf(fmaf(v[r], k0, k1)) * g;
     }
 }
 
@@ -224,7 +224,7 @@ __device__ __forceinline__ void lt_prologue(float (&v)[4], const float (&raw)[4]
     } else if (PRO == PRO_BNSWISH_GATE) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            v[r] = swishf(fmaf(v[r], k0, k1)) * g;
+            v[r] = actf(fmaf(v[r], k0, k1)) * g;
     }
 }
 

@@ -6,7 +6,10 @@
 #include <algorithm>
 #include <cstdint>
 
-using namespace mbk;
+// The launch sequence below is compiled twice: once as is (namespace mbk, Swish) and once with
+// -Dmbk=mbk_r6 -DMBK_ACT_RELU6 (ReLU6 kernels); the C entry points exist in the first build
+// only and pick the namespace by desc->activation.
+namespace mbk {
 
 namespace {
 
@@ -17,7 +20,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     int N, Cin, H, W, Cexp, Cse, Cout, k, s, p, Ho, Wo;
-    bool expand, res, bf16, store;
+    bool expand, res, bf16, store, se;
     size_t esz;
     size_t nX, nE, nD, nP;
     int HW, HWo;
@@ -36,7 +39,13 @@ mbconv_status check_desc(const mbconv_desc *d)
 {
     if (!d)
         return MBCONV_EINVAL;
-    if (d->N < 1 || d->Cin < 1 || d->H < 1 || d->W < 1 || d->Cexp < 1 || d->Cse < 1 || d->Cout < 1)
+    if (d->N < 1 || d->Cin < 1 || d->H < 1 || d->W < 1 || d->Cexp < 1 || d->Cout < 1)
+        return MBCONV_EINVAL;
+    if (d->no_se != 0 && d->no_se != 1)
+        return MBCONV_EINVAL;
+    if (!d->no_se && d->Cse < 1)
+        return MBCONV_EINVAL;
+    if (d->activation != MBCONV_ACT_SWISH && d->activation != MBCONV_ACT_RELU6)
         return MBCONV_EINVAL;
     if (d->dtype != MBCONV_F32 && d->dtype != MBCONV_BF16)
         return MBCONV_EINVAL;
@@ -70,7 +79,8 @@ Plan make_plan(const mbconv_desc *d)
     P.H = d->H;
     P.W = d->W;
     P.Cexp = d->Cexp;
-    P.Cse = d->Cse;
+    P.Cse = d->no_se ? 1 : d->Cse;
+    P.se = !d->no_se;
     P.Cout = d->Cout;
     P.k = d->k;
     P.s = d->stride;
@@ -187,11 +197,12 @@ mbconv_status check_params(const mbconv_desc *d, const mbconv_params *p)
 {
     if (!p)
         return MBCONV_EINVAL;
-    const void *req[] = {p->w_dw,  p->bn2_gamma, p->bn2_beta, p->se_w1,     p->se_b1,   p->se_w2,
-                         p->se_b2, p->w_proj,    p->bn3_gamma, p->bn3_beta};
+    const void *req[] = {p->w_dw, p->bn2_gamma, p->bn2_beta, p->w_proj, p->bn3_gamma, p->bn3_beta};
     for (const void *q : req)
         if (!q)
             return MBCONV_EINVAL;
+    if (!d->no_se && (!p->se_w1 || !p->se_b1 || !p->se_w2 || !p->se_b2))
+        return MBCONV_EINVAL;
     if (d->has_expand && (!p->w_expand || !p->bn1_gamma || !p->bn1_beta))
         return MBCONV_EINVAL;
     const void *all[] = {p->w_expand, p->bn1_gamma, p->bn1_beta, p->w_dw,  p->bn2_gamma,
@@ -203,127 +214,10 @@ mbconv_status check_params(const mbconv_desc *d, const mbconv_params *p)
     return MBCONV_OK;
 }
 
-mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mbconv_bn_state *run,
-                           bool eval, const void *x, void *out, void *saved, void *scratch,
-                           void *hip_stream, const mbconv_probe *probe);
+
 
 } // namespace
 
-extern "C" {
-
-int32_t mbconv_abi_version(void) { return 2; }
-
-const char *mbconv_status_string(mbconv_status s)
-{
-    switch (s) {
-    case MBCONV_OK:
-        return "ok";
-    case MBCONV_EINVAL:
-        return "invalid argument";
-    case MBCONV_EUNSUPPORTED:
-        return "unsupported shape";
-    case MBCONV_EWORKSPACE:
-        return "workspace too small";
-    case MBCONV_EALIGN:
-        return "pointer not 16-byte aligned";
-    case MBCONV_EHIP:
-        return "HIP launch failed";
-    }
-    return "unknown status";
-}
-
-mbconv_status mbconv_workspace_size(const mbconv_desc *desc, size_t *saved_bytes,
-                                    size_t *scratch_bytes)
-{
-    mbconv_status s = check_desc(desc);
-    if (s != MBCONV_OK)
-        return s;
-    if (!saved_bytes || !scratch_bytes)
-        return MBCONV_EINVAL;
-    const Plan P = make_plan(desc);
-    *saved_bytes = P.saved_bytes;
-    *scratch_bytes = P.scratch_bytes;
-    return MBCONV_OK;
-}
-
-mbconv_status mbconv_saved_offsets(const mbconv_desc *desc, mbconv_saved_layout *L)
-{
-    mbconv_status s = check_desc(desc);
-    if (s != MBCONV_OK)
-        return s;
-    if (!L)
-        return MBCONV_EINVAL;
-    const Plan P = make_plan(desc);
-    L->e = P.o_e;
-    L->d = P.o_d;
-    L->p = P.o_p;
-    L->bn1 = P.o_bn1;
-    L->bn2 = P.o_bn2;
-    L->bn3 = P.o_bn3;
-    L->z = P.o_z;
-    L->g = P.o_g;
-    L->q = P.o_q;
-    L->a1 = P.o_a1;
-    L->sc = P.o_sc;
-    return MBCONV_OK;
-}
-
-mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *prm,
-                             mbconv_bn_state *run, const void *x, void *out, void *saved,
-                             void *scratch, void *hip_stream)
-{
-    return mbconv_forward_probed(desc, prm, run, x, out, saved, scratch, hip_stream, nullptr);
-}
-
-mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params *prm,
-                                    mbconv_bn_state *run, const void *x, void *out, void *saved,
-                                    void *scratch, void *hip_stream, const mbconv_probe *probe)
-{
-    return forward_impl(desc, prm, run, false, x, out, saved, scratch, hip_stream, probe);
-}
-
-mbconv_status mbconv_eval_workspace_size(const mbconv_desc *desc, size_t *workspace_bytes)
-{
-    mbconv_status s = check_desc(desc);
-    if (s != MBCONV_OK)
-        return s;
-    if (!workspace_bytes)
-        return MBCONV_EINVAL;
-    const Plan P = make_plan(desc);
-    *workspace_bytes = align_up(P.saved_bytes) + P.scratch_bytes;
-    return MBCONV_OK;
-}
-
-mbconv_status mbconv_forward_eval(const mbconv_desc *desc, const mbconv_params *prm,
-                                  const mbconv_bn_state *running, const void *x, void *out,
-                                  void *workspace, void *hip_stream)
-{
-    return mbconv_forward_eval_probed(desc, prm, running, x, out, workspace, hip_stream, nullptr);
-}
-
-mbconv_status mbconv_forward_eval_probed(const mbconv_desc *desc, const mbconv_params *prm,
-                                         const mbconv_bn_state *running, const void *x, void *out,
-                                         void *workspace, void *hip_stream,
-                                         const mbconv_probe *probe)
-{
-    mbconv_status s = check_desc(desc);
-    if (s != MBCONV_OK)
-        return s;
-    if (!running || !workspace)
-        return MBCONV_EINVAL;
-    if (misaligned(workspace))
-        return MBCONV_EALIGN;
-    const Plan P = make_plan(desc);
-    // the intermediates a training call would save, then its scratch region
-    char *saved = static_cast<char *>(workspace);
-    char *scratch = saved + align_up(P.saved_bytes);
-    return forward_impl(desc, prm, const_cast<mbconv_bn_state *>(running), true, x, out, saved, scratch,
-                        hip_stream, probe);
-}
-
-} // extern "C"
-
-namespace {
 
 // Training mode (eval == false): batch statistics, running statistics updated when run != NULL.
 // Evaluation mode: run is read only and supplies the statistics of all three normalisations;
@@ -400,10 +294,15 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
                                    run ? run->bn2_var : nullptr, bn2, st));
     // BN2 + Swish + SE squeeze, SE excite
     float *z = at<float>(saved, P.o_z), *g = at<float>(saved, P.o_g), *q = at<float>(saved, P.o_q);
-    MBK_STEP(MBCONV_STEP_SE_POOL, launch_pool(bf, P.N, P.Cexp, P.HWo, d, bn2, z, at<float>(saved, P.o_s3),
-                        at<float>(saved, P.o_s4), st));
-    MBK_STEP(MBCONV_STEP_SE_FC, launch_se_fwd(P.N, P.Cexp, P.Cse, z, prm->se_w1, prm->se_b1, prm->se_w2, prm->se_b2, q,
-                          g, st));
+    if (P.se) {
+        MBK_STEP(MBCONV_STEP_SE_POOL, launch_pool(bf, P.N, P.Cexp, P.HWo, d, bn2, z, at<float>(saved, P.o_s3),
+                            at<float>(saved, P.o_s4), st));
+        MBK_STEP(MBCONV_STEP_SE_FC, launch_se_fwd(P.N, P.Cexp, P.Cse, z, prm->se_w1, prm->se_b1, prm->se_w2, prm->se_b2, q,
+                              g, st));
+    } else {
+        // no squeeze-and-excitation stage: the gate every later prologue multiplies by is one
+        MBK_STEP(MBCONV_STEP_SE_FC, launch_fill(g, 1.0f, (size_t)P.N * P.Cexp, st));
+    }
     // projection conv on Swish(BN2(d))*g + BN3 statistics
     {
         Operand B;
@@ -425,21 +324,10 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
     return MBCONV_OK;
 }
 
-} // namespace
 
-extern "C" {
-
-mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm, const void *x,
-                              const void *dout, const void *saved, void *scratch, void *dx,
-                              mbconv_grads *gr, void *hip_stream)
-{
-    return mbconv_backward_probed(desc, prm, x, dout, saved, scratch, dx, gr, hip_stream, nullptr);
-}
-
-mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_params *prm,
-                                     const void *x, const void *dout, const void *saved,
-                                     void *scratch, void *dx, mbconv_grads *gr, void *hip_stream,
-                                     const mbconv_probe *probe)
+mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, const void *x,
+                            const void *dout, const void *saved, void *scratch, void *dx,
+                            mbconv_grads *gr, void *hip_stream, const mbconv_probe *probe)
 {
     mbconv_status s = check_desc(desc);
     if (s != MBCONV_OK)
@@ -453,11 +341,12 @@ mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_param
         misaligned(dx))
         return MBCONV_EALIGN;
     {
-        const void *req[] = {gr->w_dw,  gr->bn2_gamma, gr->bn2_beta,  gr->se_w1,   gr->se_b1,
-                             gr->se_w2, gr->se_b2,     gr->w_proj,    gr->bn3_gamma, gr->bn3_beta};
+        const void *req[] = {gr->w_dw, gr->bn2_gamma, gr->bn2_beta, gr->w_proj, gr->bn3_gamma, gr->bn3_beta};
         for (const void *q : req)
             if (!q)
                 return MBCONV_EINVAL;
+        if (!desc->no_se && (!gr->se_w1 || !gr->se_b1 || !gr->se_w2 || !gr->se_b2))
+            return MBCONV_EINVAL;
         if (desc->has_expand && (!gr->w_expand || !gr->bn1_gamma || !gr->bn1_beta))
             return MBCONV_EINVAL;
     }
@@ -509,7 +398,11 @@ mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_param
     float *dg = at<float>(scratch, P.o_dg), *A1 = at<float>(scratch, P.o_A1);
     float *A2 = at<float>(scratch, P.o_A2), *dzs = at<float>(scratch, P.o_dzs);
     MBK_STEP(MBCONV_STEP_GATE_SUMS, launch_gate_sums(bf, P.N, P.Cexp, P.HWo, G, d, bn2, dg, A1, A2, st));
-    {
+    if (!P.se) {
+        // gate = 1, dz = 0: BN2's parameter gradients are the batch sums of the plane sums
+        MBK_STEP(MBCONV_STEP_SE_BWD, launch_bn2_bwd_nose(P.N, P.Cexp, (double)P.N * P.HWo, A1, A2, prm->bn2_gamma, bn2,
+                                                         gr->bn2_gamma, gr->bn2_beta, coef2, dzs, st));
+    } else {
         SeBwdArgs a;
         a.N = P.N;
         a.C = P.Cexp;
@@ -593,4 +486,154 @@ mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_param
     return MBCONV_OK;
 }
 
+
+} // namespace mbk
+
+#ifndef MBK_ACT_RELU6
+using namespace mbk;
+
+namespace mbk_r6 {
+mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mbconv_bn_state *run,
+                           bool eval, const void *x, void *out, void *saved, void *scratch,
+                           void *hip_stream, const mbconv_probe *probe);
+mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, const void *x,
+                            const void *dout, const void *saved, void *scratch, void *dx,
+                            mbconv_grads *gr, void *hip_stream, const mbconv_probe *probe);
+} // namespace mbk_r6
+
+namespace {
+bool relu6(const mbconv_desc *d) { return d && d->activation == MBCONV_ACT_RELU6; }
+} // namespace
+
+extern "C" {
+
+int32_t mbconv_abi_version(void) { return 3; }
+
+const char *mbconv_status_string(mbconv_status s)
+{
+    switch (s) {
+    case MBCONV_OK:
+        return "ok";
+    case MBCONV_EINVAL:
+        return "invalid argument";
+    case MBCONV_EUNSUPPORTED:
+        return "unsupported shape";
+    case MBCONV_EWORKSPACE:
+        return "workspace too small";
+    case MBCONV_EALIGN:
+        return "pointer not 16-byte aligned";
+    case MBCONV_EHIP:
+        return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+mbconv_status mbconv_workspace_size(const mbconv_desc *desc, size_t *saved_bytes,
+                                    size_t *scratch_bytes)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!saved_bytes || !scratch_bytes)
+        return MBCONV_EINVAL;
+    const Plan P = make_plan(desc);
+    *saved_bytes = P.saved_bytes;
+    *scratch_bytes = P.scratch_bytes;
+    return MBCONV_OK;
+}
+
+mbconv_status mbconv_saved_offsets(const mbconv_desc *desc, mbconv_saved_layout *L)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!L)
+        return MBCONV_EINVAL;
+    const Plan P = make_plan(desc);
+    L->e = P.o_e;
+    L->d = P.o_d;
+    L->p = P.o_p;
+    L->bn1 = P.o_bn1;
+    L->bn2 = P.o_bn2;
+    L->bn3 = P.o_bn3;
+    L->z = P.o_z;
+    L->g = P.o_g;
+    L->q = P.o_q;
+    L->a1 = P.o_a1;
+    L->sc = P.o_sc;
+    return MBCONV_OK;
+}
+
+mbconv_status mbconv_forward(const mbconv_desc *desc, const mbconv_params *prm,
+                             mbconv_bn_state *run, const void *x, void *out, void *saved,
+                             void *scratch, void *hip_stream)
+{
+    return mbconv_forward_probed(desc, prm, run, x, out, saved, scratch, hip_stream, nullptr);
+}
+
+mbconv_status mbconv_forward_probed(const mbconv_desc *desc, const mbconv_params *prm,
+                                    mbconv_bn_state *run, const void *x, void *out, void *saved,
+                                    void *scratch, void *hip_stream, const mbconv_probe *probe)
+{
+    return relu6(desc) ? mbk_r6::forward_impl(desc, prm, run, false, x, out, saved, scratch, hip_stream, probe)
+                       : mbk::forward_impl(desc, prm, run, false, x, out, saved, scratch, hip_stream, probe);
+}
+
+mbconv_status mbconv_eval_workspace_size(const mbconv_desc *desc, size_t *workspace_bytes)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!workspace_bytes)
+        return MBCONV_EINVAL;
+    const Plan P = make_plan(desc);
+    *workspace_bytes = align_up(P.saved_bytes) + P.scratch_bytes;
+    return MBCONV_OK;
+}
+
+mbconv_status mbconv_forward_eval(const mbconv_desc *desc, const mbconv_params *prm,
+                                  const mbconv_bn_state *running, const void *x, void *out,
+                                  void *workspace, void *hip_stream)
+{
+    return mbconv_forward_eval_probed(desc, prm, running, x, out, workspace, hip_stream, nullptr);
+}
+
+mbconv_status mbconv_forward_eval_probed(const mbconv_desc *desc, const mbconv_params *prm,
+                                         const mbconv_bn_state *running, const void *x, void *out,
+                                         void *workspace, void *hip_stream,
+                                         const mbconv_probe *probe)
+{
+    mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!running || !workspace)
+        return MBCONV_EINVAL;
+    if (misaligned(workspace))
+        return MBCONV_EALIGN;
+    const Plan P = make_plan(desc);
+    // the intermediates a training call would save, then its scratch region
+    char *saved = static_cast<char *>(workspace);
+    char *scratch = saved + align_up(P.saved_bytes);
+    mbconv_bn_state *run = const_cast<mbconv_bn_state *>(running); // read only in evaluation mode
+    return relu6(desc) ? mbk_r6::forward_impl(desc, prm, run, true, x, out, saved, scratch, hip_stream, probe)
+                       : mbk::forward_impl(desc, prm, run, true, x, out, saved, scratch, hip_stream, probe);
+}
+
+mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *prm, const void *x,
+                              const void *dout, const void *saved, void *scratch, void *dx,
+                              mbconv_grads *gr, void *hip_stream)
+{
+    return mbconv_backward_probed(desc, prm, x, dout, saved, scratch, dx, gr, hip_stream, nullptr);
+}
+
+mbconv_status mbconv_backward_probed(const mbconv_desc *desc, const mbconv_params *prm,
+                                     const void *x, const void *dout, const void *saved,
+                                     void *scratch, void *dx, mbconv_grads *gr, void *hip_stream,
+                                     const mbconv_probe *probe)
+{
+    return relu6(desc) ? mbk_r6::backward_impl(desc, prm, x, dout, saved, scratch, dx, gr, hip_stream, probe)
+                       : mbk::backward_impl(desc, prm, x, dout, saved, scratch, dx, gr, hip_stream, probe);
+}
+
 } // extern "C"
+#endif // MBK_ACT_RELU6

@@ -95,6 +95,30 @@ __device__ __forceinline__ void swish_both(float t, float &val, float &grad)
     grad = s * (1.0f + t * (1.0f - s));
 }
 
+// The block's activation after BN1 and BN2, fixed at compile time: Swish (EfficientNet MBConv),
+// or ReLU6 when the translation unit is built with MBK_ACT_RELU6 (MobileNet-V2 inverted
+// residual; the whole kernel set is compiled a second time into its own namespace).  The
+// squeeze-and-excitation stage keeps swishf / sigmoidf_fast in both builds.
+//   act_aux(y)        what is worth keeping of y for a later derivative (sigmoid(y) for Swish)
+//   act_val(y, aux)   the activation
+//   act_grad(y, aux)  its derivative; ReLU6: 1 strictly inside (0, 6), 0 elsewhere
+#ifdef MBK_ACT_RELU6
+__device__ __forceinline__ float act_aux(float y) { return y; }
+__device__ __forceinline__ float act_val(float y, float) { return fminf(fmaxf(y, 0.0f), 6.0f); }
+__device__ __forceinline__ float act_grad(float y, float) { return (y > 0.0f && y < 6.0f) ? 1.0f : 0.0f; }
+#else
+__device__ __forceinline__ float act_aux(float y) { return sigmoidf_fast(y); }
+__device__ __forceinline__ float act_val(float y, float aux) { return y * aux; }
+__device__ __forceinline__ float act_grad(float y, float aux) { return aux * (1.0f + y * (1.0f - aux)); }
+#endif
+__device__ __forceinline__ float actf(float y) { return act_val(y, act_aux(y)); }
+__device__ __forceinline__ void act_both(float y, float &val, float &grad)
+{
+    const float aux = act_aux(y);
+    val = act_val(y, aux);
+    grad = act_grad(y, aux);
+}
+
 // ---- integer division by a per-launch constant ------------------------------------------
 // Exact for every 32-bit numerator (the round-up multiply-shift scheme of Granlund and
 // Montgomery): with l = ceil(log2 d) and m = floor(2^32*(2^l-d)/d)+1,

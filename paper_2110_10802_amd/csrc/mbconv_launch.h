@@ -60,6 +60,16 @@ hipError_t launch_bn_eval_coef(int C1, const float *gamma1, const float *beta1, 
                                int C3, const float *gamma3, const float *beta3, const float *rm3,
                                const float *rv3, float *bn3, float eps, hipStream_t st);
 
+// out[i] = value, i < count.
+hipError_t launch_fill(float *out, float value, size_t count, hipStream_t st);
+
+// Block without a squeeze-and-excitation stage (gate = 1, dz = 0): BN2's backward from the
+// plane sums A1 = sum G*act'(y2), A2 = sum G*act'(y2)*dhat, both [N][C]:
+//   dbeta = sum_n A1, dgamma = sum_n A2, coef as in launch_bn_bwd_finalize; dzs[N*C] is zeroed.
+hipError_t launch_bn2_bwd_nose(int N, int C, double m, const float *A1, const float *A2,
+                               const float *gamma, const float *bn, float *dgamma, float *dbeta,
+                               float *coef, float *dzs, hipStream_t st);
+
 // BN backward finalise from partial sums [C][NP] of dy (psb) and dy*xhat (psr):
 //   dbeta = sum psb, dgamma = sum psr, and coef = {c0,c1,c2}[C] such that
 //   dx = c0*dy + c1*raw + c2  equals  gamma*rstd*(dy - dbeta/m - xhat*dgamma/m).
