@@ -230,6 +230,114 @@ def run_chain(args) -> int:
     return 0
 
 
+# Workloads of the operator benchmarks (--op).  The paper gives no tensor sizes for these in its
+# text; the shapes are those of the networks it takes them from: a YOLOv4 backbone activation
+# for Mish, BERT-large's hidden states for layer normalisation, its attention scores for softmax.
+OP_WORKLOADS = {
+    "mish": {"n": 8 * 64 * 304 * 304, "what": "8x64x304x304 activation"},
+    "layernorm": {"rows": 8 * 512, "cols": 1024, "what": "4096 rows x 1024 (batch 8, sequence 512, hidden 1024)"},
+    "softmax": {"rows": 8 * 16 * 512, "cols": 512, "what": "65536 rows x 512 (batch 8, 16 heads, 512x512 scores)"},
+}
+
+
+def run_op(args) -> int:
+    """One step = forward + backward of the operator on resident fp32 tensors."""
+    import numpy as np
+    import torch
+    from paper_2110_10802_amd import dnnops as D
+
+    D.load()
+    w = OP_WORKLOADS[args.op]
+    rng = np.random.default_rng(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    dev = "cuda:0"
+    if args.op == "mish":
+        n = w["n"]
+        x = torch.from_numpy((rng.standard_normal(n) * 2).astype(np.float32)).to(dev)
+        dy = torch.from_numpy(rng.standard_normal(n).astype(np.float32)).to(dev)
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        fwd = lambda: D.mish_forward(x, y, n, stream)
+        bwd = lambda: D.mish_backward(x, dy, dx, n, stream)
+        elems, fbytes, bbytes = n, 8 * n, 12 * n
+    else:
+        rows, cols = w["rows"], w["cols"]
+        x = torch.from_numpy((rng.standard_normal((rows, cols)) * 2).astype(np.float32)).to(dev)
+        dy = torch.from_numpy(rng.standard_normal((rows, cols)).astype(np.float32)).to(dev)
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        elems = rows * cols
+        if args.op == "layernorm":
+            g = torch.from_numpy((1 + 0.1 * rng.standard_normal(cols)).astype(np.float32)).to(dev)
+            b = torch.from_numpy((0.1 * rng.standard_normal(cols)).astype(np.float32)).to(dev)
+            mean, rstd = torch.empty(rows, device=dev), torch.empty(rows, device=dev)
+            dg, db = torch.empty_like(g), torch.empty_like(g)
+            scratch = torch.empty(D.layernorm_backward_scratch_bytes(rows, cols), dtype=torch.uint8,
+                                  device=dev)
+            fwd = lambda: D.layernorm_forward(x, g, b, 1e-5, rows, cols, y, mean, rstd, stream)
+            bwd = lambda: D.layernorm_backward(x, dy, g, mean, rstd, rows, cols, dx, dg, db, scratch,
+                                               stream)
+        else:
+            fwd = lambda: D.softmax_forward(x, y, rows, cols, stream)
+            bwd = lambda: D.softmax_backward(y, dy, dx, rows, cols, stream)
+        fbytes, bbytes = 8 * elems, 12 * elems
+    for _ in range(max(args.warmup, 1)):
+        fwd()
+        bwd()
+    torch.cuda.synchronize()
+    ev = HipEvents()
+    pairs = [(ev.create(), ev.create(), ev.create()) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, m, b_ in pairs:
+        ev.record(a, stream)
+        fwd()
+        ev.record(m, stream)
+        bwd()
+        ev.record(b_, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    f_ms = sorted(ev.elapsed_ms(a, m) for a, m, _ in pairs)[len(pairs) // 2]
+    b_ms = sorted(ev.elapsed_ms(m, b_) for _, m, b_ in pairs)[len(pairs) // 2]
+    # the slower direction is the roofline kernel (one launch per direction; the layer-norm
+    # backward adds two small second-stage launches, counted in its time)
+    kname, kms, kbytes = ("backward", b_ms, bbytes) if b_ms >= f_ms else ("forward", f_ms, fbytes)
+    achieved = kbytes / (kms * 1e-3) / 1e9
+    result = {
+        "metric": f"{args.op}_fwd_bwd_gelements_per_sec", "value": elems / (ms_per_step * 1e-3) / 1e9,
+        "unit": "Gelements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.op}: {w['what']}"},
+        "roofline": {"bound": "hbm", "kernel": f"{args.op}_{kname}", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "kernel_ms": kms, "algorithmic_bytes": kbytes,
+                     "forward_ms": f_ms, "backward_ms": b_ms,
+                     "forward_gbs": fbytes / (f_ms * 1e-3) / 1e9,
+                     "backward_gbs": bbytes / (b_ms * 1e-3) / 1e9},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import dnnops as orc
+        xs = x.detach().cpu().numpy().astype(np.float64)
+        dys = dy.detach().cpu().numpy().astype(np.float64)
+        if args.op == "mish":
+            xs, dys = xs[:1 << 24], dys[:1 << 24]  # a bounded sample: 16 Mi elements
+        c0 = time.perf_counter()
+        if args.op == "mish":
+            orc.mish_fwd(xs)
+            orc.mish_bwd(xs, dys)
+        elif args.op == "layernorm":
+            gam = g.cpu().numpy().astype(np.float64)
+            _, mo, ro = orc.layernorm_fwd(xs, gam, b.cpu().numpy().astype(np.float64), 1e-5)
+            orc.layernorm_bwd(xs, dys, gam, mo, ro)
+        else:
+            orc.softmax_bwd(orc.softmax_fwd(xs), dys)
+        dt = time.perf_counter() - c0
+        result["cpu_baseline"] = {"value": xs.size / dt / 1e9, "unit": "Gelements/s",
+                                  "cores": os.cpu_count(), "kind": "oracle",
+                                  "sample": f"one fp64 forward+backward over {xs.size} elements, {dt:.1f} s wall"}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,6 +350,9 @@ def main() -> int:
     ap.add_argument("--mode", default="train", choices=["train", "eval"],
                     help="train: forward+backward (the headline metric); eval: the evaluation-mode "
                          "forward alone (BN with running statistics), configs 0-3")
+    ap.add_argument("--op", default=None, choices=["mish", "layernorm", "softmax"],
+                    help="benchmark one of the paper's other memory-bound operators (forward + "
+                         "backward) instead of the MBConv step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe-step", default=None,
                     help="time this step for the roofline instead of the slowest one")
@@ -265,6 +376,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.op:
+        return run_op(args)
     if args.config == 4:
         if args.mode != "train":
             print("bench.py: --mode eval covers the single-block configs 0-3", file=sys.stderr)

@@ -11,6 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmbconv.so")
 SOURCES = ["mbconv_api.hip", "kernels_gemm.hip", "kernels_big.hip", "kernels_bf.hip", "kernels_wave.hip", "kernels_pv16.hip", "kernels_dw.hip", "kernels_dw4.hip", "kernels_dw2.hip", "kernels_dwr.hip", "kernels_misc.hip"]
+# sources without a block activation (Mish, layer normalisation, softmax): compiled once
+SOURCES_ONCE = ["kernels_ops.hip"]
 # packed fp32 VALU ops are disabled for the device pass (the host pass does not know the
 # feature and says so; harmless)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
@@ -48,6 +50,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         return o
 
     jobs = [(src, relu6) for relu6 in (False, True) for src in SOURCES]
+    jobs += [(src, False) for src in SOURCES_ONCE]
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 4)) as ex:
         objs = list(ex.map(compile_one, jobs))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]

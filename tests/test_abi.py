@@ -22,6 +22,27 @@ def test_library_exports_every_declared_symbol():
     assert lib.mbconv_abi_version() == B.ABI_VERSION
 
 
+def test_library_exports_every_dnnops_symbol():
+    from paper_2110_10802_amd import dnnops as D
+    hdr = open(os.path.join(ROOT, "include", "dnnops.h")).read()
+    declared = set(re.findall(r"\b(dnnops_[a-z_]+)\s*\(", hdr))
+    assert declared == set(D.EXPORTS), declared ^ set(D.EXPORTS)
+    lib = D.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert int(re.search(r"#define DNNOPS_MAX_COLS (\d+)", hdr).group(1)) == D.MAX_COLS
+    # host-side argument checks: nothing reaches the GPU
+    assert lib.dnnops_mish_forward(None, None, 16, None) == -1
+    assert lib.dnnops_mish_forward(16, 32, 0, None) == -1
+    assert lib.dnnops_mish_forward(16, 36, 8, None) == -4
+    assert lib.dnnops_softmax_forward(16, 32, 4, D.MAX_COLS + 1, None) == -2
+    assert lib.dnnops_softmax_forward(16, 32, 0, 8, None) == -1
+    assert lib.dnnops_layernorm_forward(16, 32, 48, -1.0, 4, 8, 64, 80, 96, None) == -1
+    assert D.layernorm_backward_scratch_bytes(0, 8) == 0
+    assert D.layernorm_backward_scratch_bytes(4096, 1024) == 2 * 256 * 1024 * 4
+    assert D.layernorm_backward_scratch_bytes(100000, 1024) == 2 * 512 * 1024 * 4
+
+
 def test_status_strings():
     assert B.status_string(0) == "ok"
     for code in (-1, -2, -3, -4, -5):
