@@ -51,23 +51,36 @@ __device__ __forceinline__ float mish_grad(float x)
     return fmaf(x * s, w * (2.0f - w), t);
 }
 
+// Four 16-byte runs per thread and round, all loads of a round issued before the first use (a
+// load-use-store loop would pay one memory round trip per run).
 template <bool BWD>
 __global__ __launch_bounds__(256) void mish_kernel(const float *__restrict__ x, const float *dy,
                                                    float *out, size_t n)
 {
+    constexpr int U = 4;
     const size_t n4 = n / 4;
     const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
-        const float4 xv = reinterpret_cast<const float4 *>(x)[i];
-        float4 r;
-        if (BWD) {
-            const float4 g = reinterpret_cast<const float4 *>(dy)[i];
-            r = make_float4(g.x * mish_grad(xv.x), g.y * mish_grad(xv.y), g.z * mish_grad(xv.z),
-                            g.w * mish_grad(xv.w));
-        } else {
-            r = make_float4(mish_val(xv.x), mish_val(xv.y), mish_val(xv.z), mish_val(xv.w));
+    for (size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x; i0 < n4; i0 += U * stride) {
+        float4 xv[U], g[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t i = min(i0 + u * stride, n4 - 1); // clamped: always a valid run
+            xv[u] = reinterpret_cast<const float4 *>(x)[i];
+            if (BWD)
+                g[u] = reinterpret_cast<const float4 *>(dy)[i];
         }
-        reinterpret_cast<float4 *>(out)[i] = r;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float4 r;
+            if (BWD)
+                r = make_float4(g[u].x * mish_grad(xv[u].x), g[u].y * mish_grad(xv[u].y),
+                                g[u].z * mish_grad(xv[u].z), g[u].w * mish_grad(xv[u].w));
+            else
+                r = make_float4(mish_val(xv[u].x), mish_val(xv[u].y), mish_val(xv[u].z), mish_val(xv[u].w));
+            if (i0 + u * stride < n4)
+                reinterpret_cast<float4 *>(out)[i0 + u * stride] = r;
+        }
     }
     if (blockIdx.x == 0) { // at most three trailing elements
         const size_t i = 4 * n4 + threadIdx.x;
@@ -425,8 +438,8 @@ dnnops_status dnnops_mish_forward(const float *x, float *y, size_t n, void *hip_
         return DNNOPS_EINVAL;
     if (bad_align(x) || bad_align(y))
         return DNNOPS_EALIGN;
-    const size_t wg = (n / 4 + 255) / 256;
-    const unsigned grid = (unsigned)(wg < 1 ? 1 : (wg > 8192 ? 8192 : wg));
+    const size_t wg = (n / 4 + 1023) / 1024; // four runs per thread
+    const unsigned grid = (unsigned)(wg < 1 ? 1 : (wg > 65536 ? 65536 : wg));
     hipLaunchKernelGGL(mish_kernel<false>, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream, x,
                        (const float *)nullptr, y, n);
     return hipGetLastError() == hipSuccess ? DNNOPS_OK : DNNOPS_EHIP;
@@ -439,8 +452,8 @@ dnnops_status dnnops_mish_backward(const float *x, const float *dy, float *dx, s
         return DNNOPS_EINVAL;
     if (bad_align(x) || bad_align(dy) || bad_align(dx))
         return DNNOPS_EALIGN;
-    const size_t wg = (n / 4 + 255) / 256;
-    const unsigned grid = (unsigned)(wg < 1 ? 1 : (wg > 8192 ? 8192 : wg));
+    const size_t wg = (n / 4 + 1023) / 1024;
+    const unsigned grid = (unsigned)(wg < 1 ? 1 : (wg > 65536 ? 65536 : wg));
     hipLaunchKernelGGL(mish_kernel<true>, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream, x, dy,
                        dx, n);
     return hipGetLastError() == hipSuccess ? DNNOPS_OK : DNNOPS_EHIP;
