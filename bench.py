@@ -119,6 +119,28 @@ def cpu_baseline(shape, tensors, eval_mode=False):
                       f"{dt:.1f} s wall"}
 
 
+def cpu_baseline_one_thread(shape, eval_mode=False):
+    """The oracle on ONE thread, in a child process (OMP_NUM_THREADS=1), on a quarter of the batch."""
+    import subprocess
+    n = max(shape.N // 4, 1)
+    code = (
+        "import sys, time; sys.path.insert(0, %r)\n"
+        "from dataclasses import replace\n"
+        "from mbconv_inputs import CONFIGS, make_block_inputs\n"
+        "from oracle import oracle as orc\n"
+        "s = replace(CONFIGS[%d], N=%d); t = make_block_inputs(s, 0)\n"
+        "t0 = time.perf_counter()\n"
+        "%s\n"
+        "print(time.perf_counter() - t0, orc.num_threads())\n"
+    ) % (ROOT, next(k for k, v in __import__("mbconv_inputs").CONFIGS.items() if v == shape), n,
+         "orc.mbconv_forward_eval(s, t)" if eval_mode else "orc.mbconv_step(s, t)")
+    env = dict(os.environ, OMP_NUM_THREADS="1")
+    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, check=True)
+    dt, threads = out.stdout.split()
+    return {"value": n / float(dt), "unit": "images/s", "cores": int(threads),
+            "sample": f"{n} images, {float(dt):.1f} s wall"}
+
+
 NO_EXPAND_STEPS = ("expand_conv", "bn1_finalize", "bn1_bwd_finalize", "expand_dgrad", "expand_wgrad")
 
 
@@ -354,6 +376,8 @@ def main() -> int:
                     help="benchmark one of the paper's other memory-bound operators (forward + "
                          "backward) instead of the MBConv step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-1thread", action="store_true",
+                    help="also time the oracle on one thread (on a quarter of the batch; slow)")
     ap.add_argument("--probe-step", default=None,
                     help="time this step for the roofline instead of the slowest one")
     ap.add_argument("--no-survey", action="store_true",
@@ -454,6 +478,23 @@ def main() -> int:
     for a, b in pairs:
         ev.destroy(a)
         ev.destroy(b)
+    # distribution of the step time: a second, separate pass with one event between consecutive
+    # steps (kept out of the timed loop, whose wall clock it would stretch); median and a 95 %
+    # non-parametric confidence interval of the median from the order statistics
+    marks = [ev.create() for _ in range(args.steps + 1)]
+    ev.record(marks[0], stream)
+    for i in range(args.steps):
+        step()
+        ev.record(marks[i + 1], stream)
+    torch.cuda.synchronize()
+    per_step = sorted(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(args.steps))
+    for m in marks:
+        ev.destroy(m)
+    k = len(per_step)
+    half = 0.98 * (k ** 0.5)  # 1.96 * sqrt(k) / 2
+    lo_i, hi_i = max(int(k / 2 - half), 0), min(int(k / 2 + half) + 1, k - 1)
+    step_stats = {"median": per_step[k // 2], "ci95": [per_step[lo_i], per_step[hi_i]],
+                  "min": per_step[0], "max": per_step[-1]}
     # an event pair around a kernel also spans the gap between two event records; that gap is
     # measured with an empty pair behind the same queued work and taken off
     overhead_ms = ev.pair_overhead_ms(stream, step)
@@ -493,9 +534,13 @@ def main() -> int:
                      "kernel_ms": kern_ms, "kernel_ms_with_event_gap": kern_ms_raw,
                      "event_gap_ms": overhead_ms, "algorithmic_bytes": nbytes},
         "step_ms_survey": {n: round(v, 5) for n, v in survey.items()},
+        "step_ms_distribution": {k_: ([round(x, 5) for x in v] if isinstance(v, list) else round(v, 5))
+                                 for k_, v in step_stats.items()},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(shape, tensors, evalm)
+        if args.cpu_1thread:
+            result["cpu_baseline"]["one_thread"] = cpu_baseline_one_thread(shape, evalm)
     print(json.dumps(result))
     return 0
 

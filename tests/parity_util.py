@@ -65,11 +65,11 @@ def run_gpu_block(shape, t, policy=0, device="cuda:0"):
 
 
 def _dump_report(shape, errs):
-    """Leave the error table where a GPU run's caller can read it (best effort)."""
+    """Write the error table as JSON into $MBCONV_PARITY_REPORT_DIR when that is set (best effort)."""
     import json
     import os
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
+    d = os.environ.get("MBCONV_PARITY_REPORT_DIR", "")
+    if d and os.path.isdir(d):
         name = (f"parity_N{shape.N}_{shape.Cin}-{shape.Cexp}-{shape.Cout}_{shape.H}x{shape.W}_"
                 f"k{shape.k}s{shape.stride}_{shape.dtype}.json")
         try:
