@@ -443,6 +443,7 @@ def main() -> int:
     # untimed survey: duration of every step, to find the slowest kernel
     survey = {}
     e0, e1 = ev.create(), ev.create()
+    prev_reps = None
     for name, sid in B.STEPS.items():
         if not shape.has_expand and name in NO_EXPAND_STEPS:
             continue
@@ -456,6 +457,9 @@ def main() -> int:
             step(B.Probe(sid, e0, e1))
             torch.cuda.synchronize()
             reps.append(ev.elapsed_ms(e0, e1))
+        if prev_reps is not None and reps == prev_reps:
+            continue  # the step did not occur (its events still hold the previous step's times)
+        prev_reps = reps
         survey[name] = sorted(reps)[1]
     ev.destroy(e0)
     ev.destroy(e1)

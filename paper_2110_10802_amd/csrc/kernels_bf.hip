@@ -295,6 +295,15 @@ __global__ __launch_bounds__(256) void conv_bf_kernel(BfConvArgs a)
                 for (int r = 0; r < 4; ++r)
                     v[r] += rr[r];
             }
+            if (EPI == EPI_AFFINE) { // psum / psq carry the row's scale and shift
+                const float osc = a.psum[ok ? m : 0], osh = a.psq[ok ? m : 0];
+                float rr[4] = {0.f, 0.f, 0.f, 0.f};
+                if (a.res)
+                    bf_unpack4(*reinterpret_cast<const uint2 *>(a.res + idx), rr);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    v[r] = fmaf(v[r], osc, osh) + rr[r];
+            }
             const uint2 packed = make_uint2(bf_pack2(v[0], v[1]), bf_pack2(v[2], v[3]));
             if (ok)
                 *reinterpret_cast<uint2 *>(a.out + idx) = packed;
@@ -460,6 +469,7 @@ hipError_t launch_bf_conv1x1(int N, int M, int K, int HW, const void *w, int sAm
     MBK_ROWS(PRO_BNSWISH_GATE, EPI_STATS)
     MBK_ROWS(PRO_BNBWD, EPI_NONE)
     MBK_ROWS(PRO_BNBWD, EPI_RES)
+    MBK_ROWS(PRO_BNSWISH_GATE, EPI_AFFINE)
     MBK_CASE(PRO_NONE, EPI_PARTIAL, 1)
     MBK_CASE(PRO_BNSWISH_GATE, EPI_PARTIAL, 1)
     MBK_CASE(PRO_BNBWD, EPI_PARTIAL, 1)

@@ -352,6 +352,15 @@ __global__ __launch_bounds__(256) void conv_big_kernel(BigConvArgs a)
                     for (int j = 0; j < 4; ++j)
                         v[j] += rr[j];
                 }
+                if (EPI == EPI_AFFINE) { // psum / psq carry the row's scale and shift
+                    const float osc = a.psum[min(m, a.M - 1)], osh = a.psq[min(m, a.M - 1)];
+                    float rr[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (a.res)
+                        big_ld<T, 4>((const T *)a.res, idx, rr);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[j] = fmaf(v[j], osc, osh) + rr[j];
+                }
                 if (ok)
                     big_st4<T>((T *)a.out, idx, v);
                 if (EPI == EPI_STATS) {
@@ -551,6 +560,9 @@ static hipError_t big_conv_dispatch(const BigConvArgs &a, int pro, int epi, dim3
     MBK_CASE(PRO_BNSWISH_GATE, EPI_STATS)
     MBK_CASE(PRO_BNBWD, EPI_NONE)
     MBK_CASE(PRO_BNBWD, EPI_RES)
+    if constexpr (WP == 1 && VEC == 4) {
+        MBK_CASE(PRO_BNSWISH_GATE, EPI_AFFINE)
+    }
     if constexpr (WP == 1) {
         MBK_CASE(PRO_NONE, EPI_PARTIAL)
         MBK_CASE(PRO_BNSWISH_GATE, EPI_PARTIAL)

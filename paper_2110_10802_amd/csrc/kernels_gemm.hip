@@ -286,6 +286,29 @@ hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w,
                 : conv1x1_dispatch<float>(a, B.pro, epi, grid, st);
 }
 
+hipError_t launch_conv1x1_affine(bool bf16, int N, int M, int K, int HW, const void *w, int sAm,
+                                 int sAk, const Operand &B, void *out, const void *res,
+                                 const float *scale, const float *shift, hipStream_t st)
+{
+    if (B.pro != PRO_BNSWISH_GATE)
+        return hipErrorNotSupported;
+    float *sc = const_cast<float *>(scale), *sh = const_cast<float *>(shift); // read only
+    if (wave_conv_kind(M, K, HW) == 2)
+        return launch_wave_conv1x1(bf16, 2, N, M, K, HW, w, sAm, sAk, B, out, EPI_AFFINE, res, sc, sh,
+                                   st);
+    if (wave_conv_kind(M, K, HW) || (sAm != 1 && sAk != 1) || HW % 4 != 0)
+        return hipErrorNotSupported;
+    int wt, qtiles, splits;
+    if (bf16 && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
+        return splits == 1 ? launch_bf_conv1x1(N, M, K, HW, w, sAm, sAk, B, out, EPI_AFFINE, res, sc,
+                                               sh, nullptr, st)
+                           : hipErrorNotSupported;
+    if (big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits) && splits == 1)
+        return launch_big_conv1x1(bf16, N, M, K, HW, w, sAm, sAk, B, out, EPI_AFFINE, res, sc, sh,
+                                  nullptr, st);
+    return hipErrorNotSupported;
+}
+
 // ---- weight gradient ------------------------------------------------------------------------
 // dW[a,b] = sum_q U[a,q]*V[b,q]: the contraction runs over all N*HW pixels, so it is
 // split across workgroups; every workgroup writes its own partial tile and a second

@@ -368,6 +368,12 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
                     for (int r = 0; r < 4; ++r)
                         o[r] += rr[dv][r];
                 }
+                if (EPI == EPI_AFFINE) { // psum / psq carry the row's scale and shift
+                    const float osc = a.psum[m], osh = a.psq[m];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        o[r] = fmaf(o[r], osc, osh) + (a.res ? rr[dv][r] : 0.f);
+                }
                 pv_store4<T>((T *)a.out, idx, o);
                 if (EPI == EPI_STATS) {
 #pragma unroll
@@ -385,11 +391,11 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
         // One batch per tile: the next tile's loads are issued right after this tile's MFMAs,
         // so they are in flight during the exchange, the stores and the two barriers.
         PvRaw<PRO> raw[U];
-        float rnext[2][4];
+        float rnext[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
         Geo g = geo_of(blockIdx.x);
         if ((int)blockIdx.x < a.numTiles) {
             load_batch(g, 0, raw);
-            if (EPI == EPI_RES)
+            if (EPI == EPI_RES || (EPI == EPI_AFFINE && a.res))
                 load_res(g, rnext);
         }
         for (int tile = blockIdx.x; tile < a.numTiles; tile += gridDim.x) {
@@ -402,7 +408,7 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
                     acc[t][r] = (float4v){0.f, 0.f, 0.f, 0.f};
             compute_batch(0, raw, acc);
             float rcur[2][4];
-            if (EPI == EPI_RES) {
+            if (EPI == EPI_RES || EPI == EPI_AFFINE) {
 #pragma unroll
                 for (int dv = 0; dv < 2; ++dv)
 #pragma unroll
@@ -413,7 +419,7 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
             const Geo gn = geo_of(next);
             if (next < a.numTiles) {
                 load_batch(gn, 0, raw);
-                if (EPI == EPI_RES)
+                if (EPI == EPI_RES || (EPI == EPI_AFFINE && a.res))
                     load_res(gn, rnext);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -429,8 +435,8 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     acc[t][r] = (float4v){0.f, 0.f, 0.f, 0.f};
-            float rr[2][4];
-            if (EPI == EPI_RES)
+            float rr[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+            if (EPI == EPI_RES || (EPI == EPI_AFFINE && a.res))
                 load_res(g, rr);
             for (int u0 = 0; u0 < KSWp; u0 += U) {
                 PvRaw<PRO> raw[U];
@@ -578,7 +584,9 @@ static hipError_t pv_dispatch(const PvArgs &a, int kind, int pro, int epi, int g
     MBK_CASE(PRO_BNBWD, EPI_NONE)
     MBK_CASE(PRO_BNBWD, EPI_RES)
 #undef MBK_CASE
-    return hipErrorInvalidValue;
+    if (kind == 2 && pro == PRO_BNSWISH_GATE && epi == EPI_AFFINE)
+        return launch_pr<T, PRO_BNSWISH_GATE, EPI_AFFINE>(a, grid, st);
+    return hipErrorNotSupported;
 }
 
 hipError_t launch_wave_conv1x1(bool bf16, int kind, int N, int M, int K, int HW, const void *w,

@@ -286,7 +286,7 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
     }
     // BN1 + Swish + depthwise + BN2 statistics
     const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
-    void *a1_store = (P.store && P.expand) ? at<char>(saved, P.o_a1) : nullptr;
+    void *a1_store = (P.store && P.expand && !eval) ? at<char>(saved, P.o_a1) : nullptr;
     MBK_STEP(MBCONV_STEP_DW_FWD, launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum, psq, a1_store, st));
     if (!eval)
         MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.NPdw, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
@@ -311,7 +311,20 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
         B.c1 = bn2 + P.Cexp;
         B.gate = g;
         B.pro = PRO_BNSWISH_GATE;
-        void *sc_store = P.store ? at<char>(saved, P.o_sc) : nullptr;
+        if (eval) {
+            // BN3 with fixed statistics is an affine map per output channel: it and the residual
+            // go into the convolution's epilogue where the kernel family has one
+            hipError_t fused = hipSuccess;
+            const auto try_fused = [&]() {
+                fused = launch_conv1x1_affine(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B,
+                                              out, P.res ? x : nullptr, bn3, bn3 + P.Cout, st);
+                return fused == hipErrorNotSupported ? hipSuccess : fused;
+            };
+            MBK_STEP(MBCONV_STEP_PROJ_CONV, try_fused());
+            if (fused == hipSuccess)
+                return MBCONV_OK;
+        }
+        void *sc_store = (P.store && !eval) ? at<char>(saved, P.o_sc) : nullptr;
         MBK_STEP(MBCONV_STEP_PROJ_CONV, launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p,
                                EPI_STATS, nullptr, psum, psq, sc_store, wg, st));
         if (!eval)

@@ -14,6 +14,10 @@ namespace mbk {
 enum { PRO_NONE = 0, PRO_BNSWISH_GATE = 1, PRO_BNBWD = 2 };
 enum { EPI_NONE = 0, EPI_STATS = 1, EPI_RES = 2 };
 constexpr int EPI_PARTIAL = 3; // internal: raw partial sums of a split contraction
+// out = acc*scale[m] + shift[m] (+ res when res != NULL): a normalisation with fixed statistics
+// folded into the epilogue (evaluation mode).  scale/shift travel in the psum/psq arguments of
+// the internal launchers, read only.
+constexpr int EPI_AFFINE = 4;
 
 struct Operand {
     const void *p0 = nullptr;
@@ -38,6 +42,14 @@ size_t conv1x1_splitk_floats(bool bf16, int N, int M, int K, int HW, bool stores
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
                           float *psq, void *sc_store, float *splitk_ws, hipStream_t st);
+
+// The same convolution with out = acc*scale[m] + shift[m] (+ res if non-null) as its epilogue.
+// Returns hipErrorNotSupported (nothing launched) when the kernel family that serves this
+// shape has no such epilogue; the caller then runs the convolution and the affine map as two
+// steps.
+hipError_t launch_conv1x1_affine(bool bf16, int N, int M, int K, int HW, const void *w, int sAm,
+                                 int sAk, const Operand &B, void *out, const void *res,
+                                 const float *scale, const float *shift, hipStream_t st);
 
 // Weight gradient of a 1x1 conv: dW[a,b] = sum_{n,q} op(U)[n,a,q] * op(V)[n,b,q].
 // `partial` needs wgrad_splits(...)*Ma*Mb floats.

@@ -34,6 +34,8 @@ SMALL = {
     "max_plane_s2": _shape(N=1, Cin=8, Cexp=8, Cout=8, H=128, W=128, k=5, stride=2, residual=False),
     "max_plane_ragged": _shape(N=1, Cin=8, Cexp=8, Cout=8, H=127, W=125, k=5),
     "one_pixel": _shape(N=3, Cin=4, Cexp=8, Cse=2, Cout=4, H=1, W=1),
+    # 64 <-> 192 channels on 14x14: the wide fp32 conv kernels without a split contraction
+    "mid_14x14": _shape(N=4, Cin=64, Cexp=192, Cse=16, Cout=64, H=14, W=14),
     "bf16_small": _shape(dtype="bf16", H=14, W=14, k=5, Cin=16, Cexp=64, Cout=16, N=4),
     "bf16_s2": _shape(dtype="bf16", H=16, W=16, k=3, stride=2, Cin=16, Cexp=32, Cout=24, N=4,
                       residual=False),
@@ -278,7 +280,7 @@ def _with_running(s, t, seed):
 
 
 @pytest.mark.parametrize("name", ["k3s1_ragged", "k5s1", "k5s2_odd", "noexpand_res", "wide",
-                                  "plane_1024_threads", "max_plane_ragged", "one_pixel",
+                                  "mid_14x14", "plane_1024_threads", "max_plane_ragged", "one_pixel",
                                   "n1_tiny", "bf16_small", "bf16_s2", "config1", "config3"])
 def test_eval_forward_matches_oracle(name):
     import torch
