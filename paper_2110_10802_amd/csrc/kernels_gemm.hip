@@ -404,43 +404,74 @@ int wgrad_splits(bool bf16, int Ma, int Mb, int N, int HW)
     return (int)((Q + chunk - 1) / chunk);
 }
 
-// Second stage of a split reduction: out[i] = sum_k in[k*count+i].  A workgroup owns 32
-// outputs; its 32 thread groups each add every 32nd partial in ascending order (four
-// independent running sums per thread to keep loads in flight), then the groups are combined
-// by a fixed-shape tree in LDS.  No atomics, bitwise repeatable.
+// Second stage of a split reduction: out[i] = sum_k in[k*count+i].  A workgroup owns 32*V
+// consecutive outputs (V = 4 when count is a multiple of four: 16-byte loads, 512 contiguous
+// bytes per partial row); its 32 thread groups each add every 32nd partial in ascending order
+// (four independent running sums per thread to keep loads in flight), then the groups are
+// combined by a fixed-shape tree in LDS.  No atomics, bitwise repeatable.
+template <int V>
 __global__ __launch_bounds__(1024) void reduce_splits_kernel(const float *__restrict__ in, int S,
                                                              size_t count, float *__restrict__ out)
 {
-    __shared__ float part[32][33];
+    __shared__ float part[32][32 * V + 1];
     const int e = threadIdx.x & 31, grp = threadIdx.x >> 5;
-    const size_t i = (size_t)blockIdx.x * 32 + e;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    const size_t i = ((size_t)blockIdx.x * 32 + e) * V;
+    float s[4][V];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            s[u][v] = 0.f;
+    auto add = [&](int u, int k) __attribute__((always_inline)) {
+        const float *p = in + (size_t)k * count + i;
+        if (V == 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(p);
+            s[u][0] += t.x;
+            s[u][V > 1 ? 1 : 0] += t.y;
+            s[u][V > 2 ? 2 : 0] += t.z;
+            s[u][V > 3 ? 3 : 0] += t.w;
+        } else {
+            s[u][0] += p[0];
+        }
+    };
     if (i < count) {
         int k = grp;
         for (; k + 96 < S; k += 128) {
-            s0 += in[(size_t)k * count + i];
-            s1 += in[(size_t)(k + 32) * count + i];
-            s2 += in[(size_t)(k + 64) * count + i];
-            s3 += in[(size_t)(k + 96) * count + i];
+            add(0, k);
+            add(1, k + 32);
+            add(2, k + 64);
+            add(3, k + 96);
         }
         for (; k < S; k += 32)
-            s0 += in[(size_t)k * count + i];
+            add(0, k);
     }
-    part[grp][e] = (s0 + s1) + (s2 + s3);
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+        part[grp][e * V + v] = (s[0][v] + s[1][v]) + (s[2][v] + s[3][v]);
     __syncthreads();
     for (int half = 16; half > 0; half >>= 1) {
-        if (grp < half)
-            part[grp][e] += part[grp + half][e];
+        if (grp < half) {
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                part[grp][e * V + v] += part[grp + half][e * V + v];
+        }
         __syncthreads();
     }
-    if (grp == 0 && i < count)
-        out[i] = part[0][e];
+    if (grp == 0 && i < count) {
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            out[i + v] = part[0][e * V + v];
+    }
 }
 
 hipError_t launch_reduce_splits(const float *in, int S, size_t count, float *out, hipStream_t st)
 {
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((count + 31) / 32)), dim3(1024), 0, st,
-                       in, S, count, out);
+    if (count % 4 == 0 && (((uintptr_t)in | (uintptr_t)out) & 15u) == 0)
+        hipLaunchKernelGGL(reduce_splits_kernel<4>, dim3((unsigned)((count / 4 + 31) / 32)), dim3(1024), 0,
+                           st, in, S, count, out);
+    else
+        hipLaunchKernelGGL(reduce_splits_kernel<1>, dim3((unsigned)((count + 31) / 32)), dim3(1024), 0, st,
+                           in, S, count, out);
     return hipGetLastError();
 }
 
