@@ -326,13 +326,16 @@ __global__ __launch_bounds__(256) void se_fwd_wide_kernel(int C, int Cse, int sl
     }
     for (int jb = 0; jb < Cse; jb += 16) {
         float wv[16][CI];
+        // unconditional loads from clamped indices: rows past Cse repeat the last row (their
+        // sums are never read), columns past C meet zv = 0
 #pragma unroll
         for (int u = 0; u < 16; ++u)
 #pragma unroll
             for (int i = 0; i < CI; ++i) {
-                const int c = tid + 256 * i;
-                wv[u][i] = (jb + u < Cse && c < C) ? w1[(size_t)(jb + u) * C + c] : 0.f;
+                const int c = min(tid + 256 * i, C - 1);
+                wv[u][i] = w1[(size_t)min(jb + u, Cse - 1) * C + c];
             }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             float acc = 0.f;
@@ -355,19 +358,23 @@ __global__ __launch_bounds__(256) void se_fwd_wide_kernel(int C, int Cse, int sl
     const int cend = min(C, (sl + 1) * slice);
     for (int c = sl * slice + tid; c < cend; c += 256) {
         const float4 *row = reinterpret_cast<const float4 *>(w2 + (size_t)c * Cse);
+        // unconditional loads (a quad past the end re-reads the last one and is masked): a
+        // branch around each load would make every load wait for the previous one
+        const int lastq = (Cse >> 2) - 1;
         float4 w[16];
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj)
-            w[jj] = 4 * jj < Cse ? row[jj] : make_float4(0.f, 0.f, 0.f, 0.f);
+            w[jj] = row[min(jj, lastq)];
         float acc = b2[c];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
-            if (4 * jj < Cse) {
-                acc = fmaf(w[jj].x, rs[4 * jj], acc);
-                acc = fmaf(w[jj].y, rs[4 * jj + 1], acc);
-                acc = fmaf(w[jj].z, rs[4 * jj + 2], acc);
-                acc = fmaf(w[jj].w, rs[4 * jj + 3], acc);
-            }
+            const bool ok = jj <= lastq;
+            const int j4 = 4 * min(jj, lastq);
+            acc = fmaf(ok ? w[jj].x : 0.f, rs[j4], acc);
+            acc = fmaf(ok ? w[jj].y : 0.f, rs[j4 + 1], acc);
+            acc = fmaf(ok ? w[jj].z : 0.f, rs[j4 + 2], acc);
+            acc = fmaf(ok ? w[jj].w : 0.f, rs[j4 + 3], acc);
         }
         g[(size_t)n * C + c] = sigmoidf_fast(acc);
     }
@@ -580,15 +587,17 @@ __global__ __launch_bounds__(256) void se_bwd_image_wide_kernel(SeBwdArgs a, int
     const float inv = 1.f / (float)a.HW;
     const int cend = min(C, (part + 1) * slice);
     for (int c = part * slice + tid; c < cend; c += 256) {
-        float w[64];
-#pragma unroll
-        for (int j = 0; j < 64; ++j)
-            w[j] = j < Cse ? a.w1[(size_t)j * C + c] : 0.f;
         float acc = 0.f;
+        for (int j0 = 0; j0 < Cse; j0 += 16) { // sixteen unconditional loads per round
+            float w[16];
 #pragma unroll
-        for (int j = 0; j < 64; ++j)
-            if (j < Cse)
-                acc = fmaf(w[j], dqs[j], acc);
+            for (int u = 0; u < 16; ++u)
+                w[u] = a.w1[(size_t)min(j0 + u, Cse - 1) * C + c];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                acc = fmaf(j0 + u < Cse ? w[u] : 0.f, dqs[min(j0 + u, Cse - 1)], acc);
+        }
         a.dzs[(size_t)n * C + c] = acc * inv;
     }
 }
@@ -698,17 +707,22 @@ __global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
             bn_bwd_coef(C, c, (double)N * a.HW, dgamma, dbeta, a.gamma2[c], a.bn2, a.coef2);
         }
     }
-    if (blockIdx.x == 0 && tid >= 64 && tid - 64 < Cse) {
-        const int j = tid - 64;
-        float s0 = 0.f, s1 = 0.f;
-        int n = 0;
-        for (; n + 1 < N; n += 2) {
-            s0 += a.dq[(size_t)n * Cse + j];
-            s1 += a.dq[(size_t)(n + 1) * Cse + j];
+    // db1[j] = sum_n dq[n][j], by workgroup 0: four thread groups take every fourth image (eight
+    // loads in flight each: a plain loop here would pay one memory round trip per image and
+    // make this workgroup the tail of the whole launch), combined in a fixed order
+    if (blockIdx.x == 0) {
+        __shared__ float db1L[4][64];
+        const int j = tid & 63, part = tid >> 6;
+        float s = 0.f;
+        if (j < Cse) {
+#pragma unroll 8
+            for (int n = part; n < N; n += 4)
+                s += a.dq[(size_t)n * Cse + j];
         }
-        if (n < N)
-            s0 += a.dq[(size_t)n * Cse + j];
-        a.db1[j] = s0 + s1;
+        db1L[part][j] = s;
+        __syncthreads();
+        if (tid < Cse)
+            a.db1[tid] = (db1L[0][tid] + db1L[1][tid]) + (db1L[2][tid] + db1L[3][tid]);
     }
 }
 
