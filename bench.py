@@ -457,8 +457,8 @@ def main() -> int:
             step(B.Probe(sid, e0, e1))
             torch.cuda.synchronize()
             reps.append(ev.elapsed_ms(e0, e1))
-        if prev_reps is not None and reps == prev_reps:
-            continue  # the step did not occur (its events still hold the previous step's times)
+        if prev_reps is not None and all(r == prev_reps[-1] for r in reps):
+            continue  # the step did not occur (its events still hold the previous step's last times)
         prev_reps = reps
         survey[name] = sorted(reps)[1]
     ev.destroy(e0)

@@ -184,7 +184,10 @@ typedef enum {
     MBCONV_STEP_NONE = 0,
     /* forward */
     MBCONV_STEP_EXPAND_CONV = 1,   /* 1x1 expansion conv + BN1 partial statistics */
-    MBCONV_STEP_BN1_FINALIZE = 2,
+    MBCONV_STEP_BN1_FINALIZE = 2,  /* BN1_FINALIZE and BN3_FINALIZE do not occur where the kernel
+                                      that consumes the statistics finalises them itself: DW_FWD
+                                      and BN3_APPLY do for planes of 1024 elements or more (DW_FWD:
+                                      stride 1, W % 4 == 0, recompute policy) */
     MBCONV_STEP_DW_FWD = 3,        /* BN1 + Swish + depthwise conv + BN2 partial statistics */
     MBCONV_STEP_BN2_FINALIZE = 4,
     MBCONV_STEP_SE_POOL = 5,       /* BN2 + Swish + plane means; does not occur when no_se */
@@ -196,7 +199,8 @@ typedef enum {
     MBCONV_STEP_BN3_BWD_REDUCE = 10,
     MBCONV_STEP_BN3_BWD_FINALIZE = 11,
     MBCONV_STEP_PROJ_DGRAD = 12,
-    MBCONV_STEP_PROJ_WGRAD = 13,
+    MBCONV_STEP_PROJ_WGRAD = 13,   /* with an expansion conv: the split partial sums only, their sum is
+                                      part of EXPAND_WGRAD's last launch */
     MBCONV_STEP_GATE_SUMS = 14,
     MBCONV_STEP_SE_BWD = 15,       /* when no_se: BN2's parameter gradients and backward coefficients only */
     MBCONV_STEP_DW_BWD = 16,       /* BN2 backward + depthwise dgrad/wgrad + Swish' + BN1 partials */
@@ -204,7 +208,7 @@ typedef enum {
                                           launch also finalises BN1's backward */
     MBCONV_STEP_BN1_BWD_FINALIZE = 18, /* launches nothing (see step 17): a probe on it times an empty event pair */
     MBCONV_STEP_EXPAND_DGRAD = 19,
-    MBCONV_STEP_EXPAND_WGRAD = 20,
+    MBCONV_STEP_EXPAND_WGRAD = 20, /* and the sums over the splits of both 1x1 weight gradients */
     MBCONV_STEP_COUNT = 21
 } mbconv_step;
 

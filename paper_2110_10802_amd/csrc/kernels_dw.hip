@@ -15,6 +15,7 @@
 // atomics anywhere (the same section's "Map fission" step).
 #include "mbconv_dev.h"
 #include "mbconv_launch.h"
+#include "mbconv_bnfin.h"
 
 #include <algorithm>
 
@@ -23,7 +24,8 @@ namespace mbk {
 // kernels_dw4.hip: vectorised variants for stride 1 and W % 4 == 0
 bool dw4_supported(const DwShape &s);
 hipError_t launch_dw4_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
-                          const void *w_dw, void *d, float *psum, float *psq, hipStream_t st);
+                          const void *w_dw, void *d, float *psum, float *psq, const BnFin *fin,
+                          hipStream_t st);
 hipError_t launch_dw4_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st);
 // kernels_dw2.hip
 bool dw2_supported(const DwShape &s);
@@ -200,12 +202,23 @@ static hipError_t dw_fwd_ks(const DwFwdDev &a, hipStream_t st)
     return hipErrorInvalidValue;
 }
 
+// A consumer finalises a normalisation itself where its planes are large enough that the extra
+// reduction per plane (overlapped with the plane's first loads) costs less than a launch.
+bool plane_finalize_pays(int HW) { return HW >= 1024; }
+
+bool dw_fwd_finalizes_bn1(const DwShape &s, bool stores_a1)
+{
+    return !stores_a1 && dw4_supported(s) && plane_finalize_pays(s.H * s.W);
+}
+
 hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
                          const void *w_dw, void *d, float *psum, float *psq, void *a1_store,
-                         hipStream_t st)
+                         const BnFin *fin, hipStream_t st)
 {
+    if (fin && !dw_fwd_finalizes_bn1(s, a1_store != nullptr))
+        return hipErrorInvalidValue;
     if (!a1_store && dw4_supported(s))
-        return launch_dw4_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
+        return launch_dw4_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, fin, st);
     if (!a1_store && dwr_supported(s))
         return launch_dwr_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
     if (!a1_store && dw2_supported(s))
@@ -500,6 +513,7 @@ struct PlaneArgs {
     float o0_scale; // multiplies the first output (1/HW turns a plane sum into a mean)
     void *out;    // elementwise output (bn_apply)
     const void *res;
+    BnFin fin;    // bn_apply, fin.psum non-null: `bn` is derived there from the partial sums
 };
 
 // Four consecutive elements at once (16 bytes per lane for fp32, 8 for bf16).
@@ -598,17 +612,22 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void plane_reduce_kernel(Pla
         // them is consumed (the scheduler fence keeps the compiler from pairing each load with
         // its arithmetic, which would cost one memory round trip per stride).
         if ((a.HW & 3) == 0) {
-            for (int idx0 = 4 * lt; idx0 < a.HW; idx0 += 16 * TPP) {
-                float v0[4][4], v1[4][4];
+            float v0[4][4], v1[4][4];
+            const auto load_round = [&](int idx0) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int idx = idx0 + 4 * TPP * u;
-                    const int ic = idx < a.HW ? idx : idx0; // past the end: reread, masked below
+                    // past the end: reread an element of the plane, masked when consumed
+                    const int ic = idx < a.HW ? idx : (idx0 < a.HW ? idx0 : 0);
                     ldvec4<T>((const T *)a.t0, base + ic, v0[u]);
                     if (OP::kTwo)
                         ldvec4<T>((const T *)a.t1, base + ic, v1[u]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
+            };
+            int idx0 = 4 * lt;
+            load_round(idx0);
+            while (true) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (idx0 + 4 * TPP * u < a.HW) {
@@ -617,6 +636,10 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void plane_reduce_kernel(Pla
                             OP::eval(v0[u][r], OP::kTwo ? v1[u][r] : 0.f, sc, sh, mu, rs, acc);
                     }
                 }
+                idx0 += 16 * TPP;
+                if (idx0 >= a.HW)
+                    break;
+                load_round(idx0);
             }
         } else {
             for (int idx0 = lt; idx0 < a.HW; idx0 += 4 * TPP) {
@@ -649,24 +672,46 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void plane_reduce_kernel(Pla
 template <typename T, int TPP>
 __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void bn_apply_kernel(PlaneArgs a)
 {
+    constexpr int BLOCK = TPP > 256 ? TPP : 256;
+    __shared__ double redd[2 * (BLOCK / 64)];
     const int lt = threadIdx.x % TPP;
     const PlaneId pl = plane_of_group<TPP>(a.N, a.C, a.divC);
-    if (!pl.active)
+    if (!pl.active) // (TPP > 64: one plane per workgroup, always active)
         return;
-    const float sc = a.bn[pl.c], sh = a.bn[a.C + pl.c];
+    float sc, sh;
+    BnFinRegs fr;
+    if (a.fin.psum) {
+        bn_fin_issue<TPP>(a.fin, pl.c, lt, fr);
+    } else {
+        sc = a.bn[pl.c];
+        sh = a.bn[a.C + pl.c];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const auto coefs = [&]() {
+        float mu, rs;
+        if (a.fin.psum)
+            bn_fin_finish<TPP>(a.fin, a.C, pl.c, lt, pl.n == 0, redd, fr, sc, sh, mu, rs);
+    };
     const size_t base = pl.plane * (size_t)a.HW;
     if ((a.HW & 3) == 0) {
-        for (int idx0 = 4 * lt; idx0 < a.HW; idx0 += 16 * TPP) {
-            float v[4][4], rr[4][4];
+        // (coefficient requests in front of the first round's loads, as in plane_reduce_kernel)
+        float v[4][4], rr[4][4];
+        const auto load_round = [&](int idx0) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int idx = idx0 + 4 * TPP * u;
-                const int ic = idx < a.HW ? idx : idx0;
+                const int ic = idx < a.HW ? idx : (idx0 < a.HW ? idx0 : 0);
                 ldvec4<T>((const T *)a.t0, base + ic, v[u]);
                 if (a.res)
                     ldvec4<T>((const T *)a.res, base + ic, rr[u]);
             }
             __builtin_amdgcn_sched_barrier(0);
+        };
+        int idx0 = 4 * lt;
+        load_round(idx0);
+        coefs();
+        __builtin_amdgcn_sched_barrier(0);
+        while (true) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int idx = idx0 + 4 * TPP * u;
@@ -680,8 +725,13 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void bn_apply_kernel(PlaneAr
                     stvec4<T>((T *)a.out, base + idx, v[u]);
                 }
             }
+            idx0 += 16 * TPP;
+            if (idx0 >= a.HW)
+                break;
+            load_round(idx0);
         }
     } else {
+        coefs();
         for (int idx = lt; idx < a.HW; idx += TPP) {
             float v = fmaf(ld<T>((const T *)a.t0, base + idx), sc, sh);
             if (a.res)
@@ -759,9 +809,11 @@ hipError_t launch_gate_sums(bool bf16, int N, int C, int HW, const void *G, cons
 }
 
 hipError_t launch_bn_apply(bool bf16, int N, int C, int HW, const void *p, const float *bn3,
-                           const void *res, void *out, hipStream_t st)
+                           const void *res, void *out, const BnFin *fin, hipStream_t st)
 {
     PlaneArgs a = plane_args(N, C, HW, p, nullptr, bn3);
+    if (fin)
+        a.fin = *fin;
     a.out = out;
     a.res = res;
     const int tpp = pick_tpp(HW);

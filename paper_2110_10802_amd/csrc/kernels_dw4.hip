@@ -14,6 +14,7 @@
 //     load; section "Backpropagation and Data Movement" of the paper).
 #include "mbconv_dev.h"
 #include "mbconv_launch.h"
+#include "mbconv_bnfin.h"
 
 namespace mbk {
 
@@ -67,6 +68,7 @@ struct Dw4Args {
     const void *w;
     void *d;
     float *psum, *psq;
+    BnFin fin; // fin.psum non-null: bn1 is derived in the forward kernel from the partial sums
     // backward
     const void *G;
     const float *g, *dzs, *bn2, *coef2;
@@ -145,20 +147,30 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_fwd_kernel(Dw4Args 
     const int lt = threadIdx.x % TPP;
     float *tile = lds + (threadIdx.x / TPP) * tileElems;
     float *red = lds + PPB * tileElems;
+    __shared__ double redd[2 * (BLOCK / 64)];
     size_t plane;
     int n, c;
     const bool active = plane_of<TPP>(a, plane, n, c);
 
     float wt[K * K];
-    if (active) {
+    if (active) { // (TPP > 64: one plane per workgroup, always active)
+        // BN1's coefficients are requested first (or the partial sums they are finalised from),
+        // then the plane: loads return in order, so the finalisation runs while the plane's data
+        // is still on its way
         float scale = 1.f, shift = 0.f;
+        BnFinRegs fr;
         if (EXPAND) {
-            scale = a.bn1[c];
-            shift = a.bn1[a.C + c];
+            if (a.fin.psum) {
+                bn_fin_issue<TPP>(a.fin, c, lt, fr);
+            } else {
+                scale = a.bn1[c];
+                shift = a.bn1[a.C + c];
+            }
         }
 #pragma unroll
         for (int t = 0; t < K * K; ++t)
             wt[t] = ld<T>((const T *)a.w, (size_t)c * K * K + t);
+        __builtin_amdgcn_sched_barrier(0);
         zero_border<P, TPP>(tile, H, W, WP, lt);
         const size_t base = plane * (size_t)H * W;
         // all runs of the thread are loaded before any is transformed (one memory round trip,
@@ -168,6 +180,11 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_fwd_kernel(Dw4Args 
         for (int i = 0; i < NG; ++i) {
             const int gidx = lt + TPP * i;
             gload4<T>((const T *)a.e, base + 4 * (size_t)(gidx < a.groups ? gidx : 0), ev[i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (EXPAND && a.fin.psum) {
+            float mu, rs;
+            bn_fin_finish<TPP>(a.fin, a.C, c, lt, n == 0, redd, fr, scale, shift, mu, rs);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -484,9 +501,12 @@ static hipError_t dw4_bwd_go(const Dw4Args &a, int tpp, int ng, size_t lds, hipS
 }
 
 hipError_t launch_dw4_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
-                          const void *w_dw, void *d, float *psum, float *psq, hipStream_t st)
+                          const void *w_dw, void *d, float *psum, float *psq, const BnFin *fin,
+                          hipStream_t st)
 {
     Dw4Args a = dw4_args(s);
+    if (fin)
+        a.fin = *fin;
     a.e = e;
     a.bn1 = bn1;
     a.w = w_dw;

@@ -410,12 +410,12 @@ int wgrad_splits(bool bf16, int Ma, int Mb, int N, int HW)
 // (four independent running sums per thread to keep loads in flight), then the groups are
 // combined by a fixed-shape tree in LDS.  No atomics, bitwise repeatable.
 template <int V>
-__global__ __launch_bounds__(1024) void reduce_splits_kernel(const float *__restrict__ in, int S,
-                                                             size_t count, float *__restrict__ out)
+__device__ __forceinline__ void reduce_splits_body(const float *__restrict__ in, int S, size_t count,
+                                                   float *__restrict__ out, unsigned block)
 {
     __shared__ float part[32][32 * V + 1];
     const int e = threadIdx.x & 31, grp = threadIdx.x >> 5;
-    const size_t i = ((size_t)blockIdx.x * 32 + e) * V;
+    const size_t i = ((size_t)block * 32 + e) * V;
     float s[4][V];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
@@ -464,15 +464,39 @@ __global__ __launch_bounds__(1024) void reduce_splits_kernel(const float *__rest
     }
 }
 
+// Up to two independent reductions in one launch (the workgroups of the second follow those of
+// the first): two launches cost a launch latency more than the reductions themselves take.
+template <int V>
+__global__ __launch_bounds__(1024) void reduce_splits_kernel(SplitReduce a, SplitReduce b,
+                                                             unsigned blocks_a)
+{
+    if (blockIdx.x < blocks_a)
+        reduce_splits_body<V>(a.in, a.S, a.count, a.out, blockIdx.x);
+    else
+        reduce_splits_body<V>(b.in, b.S, b.count, b.out, blockIdx.x - blocks_a);
+}
+
+hipError_t launch_reduce_splits2(const SplitReduce &a, const SplitReduce &b, hipStream_t st)
+{
+    const auto wide = [](const SplitReduce &r) {
+        return r.count % 4 == 0 && (((uintptr_t)r.in | (uintptr_t)r.out) & 15u) == 0;
+    };
+    const bool two = b.count > 0;
+    if (wide(a) && (!two || wide(b))) {
+        const unsigned ba = (unsigned)((a.count / 4 + 31) / 32);
+        const unsigned bb = two ? (unsigned)((b.count / 4 + 31) / 32) : 0u;
+        hipLaunchKernelGGL(reduce_splits_kernel<4>, dim3(ba + bb), dim3(1024), 0, st, a, b, ba);
+    } else {
+        const unsigned ba = (unsigned)((a.count + 31) / 32);
+        const unsigned bb = two ? (unsigned)((b.count + 31) / 32) : 0u;
+        hipLaunchKernelGGL(reduce_splits_kernel<1>, dim3(ba + bb), dim3(1024), 0, st, a, b, ba);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_reduce_splits(const float *in, int S, size_t count, float *out, hipStream_t st)
 {
-    if (count % 4 == 0 && (((uintptr_t)in | (uintptr_t)out) & 15u) == 0)
-        hipLaunchKernelGGL(reduce_splits_kernel<4>, dim3((unsigned)((count / 4 + 31) / 32)), dim3(1024), 0,
-                           st, in, S, count, out);
-    else
-        hipLaunchKernelGGL(reduce_splits_kernel<1>, dim3((unsigned)((count + 31) / 32)), dim3(1024), 0, st,
-                           in, S, count, out);
-    return hipGetLastError();
+    return launch_reduce_splits2({in, S, count, out}, {nullptr, 0, 0, nullptr}, st);
 }
 
 template <typename T>
@@ -490,8 +514,18 @@ static hipError_t wgrad_dispatch(const WgradArgs &a, int pu, int pv, dim3 grid, 
 }
 
 hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
-                           const Operand &V, float *partial, float *dW, hipStream_t st)
+                           const Operand &V, float *partial, float *dW, SplitReduce *defer,
+                           hipStream_t st)
 {
+    // second stage: launched here, or handed back for the caller to launch with another one
+    const auto finish = [&](int splits) {
+        const SplitReduce r = {partial, splits, (size_t)Ma * Mb, dW};
+        if (defer) {
+            *defer = r;
+            return hipSuccess;
+        }
+        return launch_reduce_splits2(r, {nullptr, 0, 0, nullptr}, st);
+    };
     {
         bool swap;
         int splits;
@@ -499,20 +533,20 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
             hipError_t e = launch_wgrad_cl(bf16, N, Ma, Mb, HW, U, V, partial, &splits, st);
             if (e != hipSuccess)
                 return e;
-            return launch_reduce_splits(partial, splits, (size_t)Ma * Mb, dW, st);
+            return finish(splits);
         }
         if (bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &splits)) {
             hipError_t e = launch_bf_wgrad(N, Ma, Mb, HW, U, V, partial, &splits, st);
             if (e != hipSuccess)
                 return e;
-            return launch_reduce_splits(partial, splits, (size_t)Ma * Mb, dW, st);
+            return finish(splits);
         }
         int wt;
         if (big_wgrad_plan(Ma, Mb, N, HW, &wt, &splits)) {
             hipError_t e = launch_big_wgrad(bf16, N, Ma, Mb, HW, U, V, partial, &splits, st);
             if (e != hipSuccess)
                 return e;
-            return launch_reduce_splits(partial, splits, (size_t)Ma * Mb, dW, st);
+            return finish(splits);
         }
     }
     WgradArgs a;
@@ -532,7 +566,7 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
                           : wgrad_dispatch<float>(a, U.pro, V.pro, grid, st);
     if (err != hipSuccess)
         return err;
-    return launch_reduce_splits(partial, S, (size_t)Ma * Mb, dW, st);
+    return finish(S);
 }
 
 } // namespace mbk

@@ -532,8 +532,8 @@ dnnops_status dnnops_layernorm_backward(const float *x, const float *dy, const f
     if (hipGetLastError() != hipSuccess)
         return DNNOPS_EHIP;
     float *pb = pg + (size_t)parts * cols;
-    if (launch_reduce_splits(pg, parts, (size_t)cols, dgamma, st) != hipSuccess ||
-        launch_reduce_splits(pb, parts, (size_t)cols, dbeta, st) != hipSuccess)
+    if (launch_reduce_splits2({pg, parts, (size_t)cols, dgamma}, {pb, parts, (size_t)cols, dbeta}, st) !=
+        hipSuccess)
         return DNNOPS_EHIP;
     return DNNOPS_OK;
 }

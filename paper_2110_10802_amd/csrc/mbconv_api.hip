@@ -28,6 +28,8 @@ struct Plan {
     size_t o_e, o_d, o_p, o_bn1, o_bn2, o_bn3, o_z, o_g, o_q, o_s3, o_s4, o_a1, o_sc, saved_bytes;
     // scratch workspace (byte offsets)
     size_t o_part;  // partial sums: 2 arrays of part_floats
+    size_t o_wg2;   // projection weight gradient's partials while their reduction is deferred
+    size_t o_part2; // partial sums of the depthwise output: 2 arrays of Cexp*NPdw
     size_t part_floats;
     size_t o_G, o_dy1, o_coef3, o_coef2, o_coef1, o_dg, o_A1, o_A2, o_dt, o_dq, o_dzs, o_pdw, o_wg;
     size_t scratch_bytes;
@@ -135,6 +137,9 @@ Plan make_plan(const mbconv_desc *d)
         part = std::max(part, (size_t)P.Cexp * P.NT1);        // expansion conv tiles
     P.part_floats = part;
     P.o_part = take(2 * part * f);
+    // the depthwise output's partial statistics live apart from the expansion conv's, which the
+    // depthwise kernel may still be reading (it finalises BN1 itself)
+    P.o_part2 = take(2 * (size_t)P.Cexp * P.NPdw * f);
     P.o_G = take(P.nD * P.esz);
     P.o_dy1 = P.expand ? take(P.nE * P.esz) : kAbsent;
     P.o_coef3 = take(3 * P.Cout * f);
@@ -158,6 +163,8 @@ Plan make_plan(const mbconv_desc *d)
         wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false));
     }
     P.o_wg = take(wg * f);
+    P.o_wg2 = P.expand ? take((size_t)wgrad_splits(P.bf16, P.Cout, P.Cexp, P.N, P.HWo) * P.Cout * P.Cexp * f)
+                       : kAbsent;
     P.scratch_bytes = o;
     return P;
 }
@@ -255,6 +262,8 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
     const bool bf = P.bf16;
     float *psum = at<float>(scratch, P.o_part);
     float *psq = psum + P.part_floats;
+    float *psum2 = at<float>(scratch, P.o_part2);
+    float *psq2 = psum2 + (size_t)P.Cexp * P.NPdw;
     float *wg = at<float>(scratch, P.o_wg);
     float *bn2 = at<float>(saved, P.o_bn2), *bn3 = at<float>(saved, P.o_bn3);
     float *bn1 = P.expand ? at<float>(saved, P.o_bn1) : nullptr;
@@ -278,18 +287,29 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
         B.pro = PRO_NONE;
         MBK_STEP(MBCONV_STEP_EXPAND_CONV, launch_conv1x1(bf, P.N, P.Cexp, P.Cin, P.HW, prm->w_expand, P.Cin, 1, B, e,
                                EPI_STATS, nullptr, psum, psq, nullptr, wg, st));
-        if (!eval)
-            MBK_STEP(MBCONV_STEP_BN1_FINALIZE, launch_bn_finalize(P.Cexp, P.NT1, (double)P.N * P.HW, psum, psq, prm->bn1_gamma,
-                                       prm->bn1_beta, eps, mom, run ? run->bn1_mean : nullptr,
-                                       run ? run->bn1_var : nullptr, bn1, st));
         dw_in = e;
     }
-    // BN1 + Swish + depthwise + BN2 statistics
+    // A normalisation's finalise step (partial sums -> scale, shift, mean, rstd, running
+    // statistics) runs inside the kernel that first consumes the statistics where that pays (BN1
+    // in the vectorised depthwise kernel, BN3 in the final elementwise pass, both for large
+    // planes; measured for BN2 in the pooling kernel: no gain); otherwise it is a launch of its own.
     const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
     void *a1_store = (P.store && P.expand && !eval) ? at<char>(saved, P.o_a1) : nullptr;
-    MBK_STEP(MBCONV_STEP_DW_FWD, launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum, psq, a1_store, st));
+    const double m1 = (double)P.N * P.HW, m2 = (double)P.N * P.HWo;
+    const BnFin fin1 = make_bn_fin(psum, psq, prm->bn1_gamma, prm->bn1_beta, run ? run->bn1_mean : nullptr,
+                                   run ? run->bn1_var : nullptr, bn1, P.NT1, eps, mom, m1);
+    const BnFin fin3 = make_bn_fin(psum, psq, prm->bn3_gamma, prm->bn3_beta, run ? run->bn3_mean : nullptr,
+                                   run ? run->bn3_var : nullptr, bn3, P.NT5, eps, mom, m2);
+    const bool fuse1 = !eval && P.expand && dw_fwd_finalizes_bn1(ds, a1_store != nullptr);
+    const bool fuse3 = !eval && plane_finalize_pays(P.HWo);
+    if (P.expand && !eval && !fuse1)
+        MBK_STEP(MBCONV_STEP_BN1_FINALIZE, launch_bn_finalize(P.Cexp, P.NT1, m1, psum, psq, prm->bn1_gamma,
+                                   prm->bn1_beta, eps, mom, fin1.run_mean, fin1.run_var, bn1, st));
+    // BN1 + Swish + depthwise + BN2 statistics
+    MBK_STEP(MBCONV_STEP_DW_FWD, launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum2, psq2, a1_store,
+                                               fuse1 ? &fin1 : nullptr, st));
     if (!eval)
-        MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.NPdw, (double)P.N * P.HWo, psum, psq, prm->bn2_gamma,
+        MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.NPdw, m2, psum2, psq2, prm->bn2_gamma,
                                    prm->bn2_beta, eps, mom, run ? run->bn2_mean : nullptr,
                                    run ? run->bn2_var : nullptr, bn2, st));
     // BN2 + Swish + SE squeeze, SE excite
@@ -327,13 +347,13 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
         void *sc_store = (P.store && !eval) ? at<char>(saved, P.o_sc) : nullptr;
         MBK_STEP(MBCONV_STEP_PROJ_CONV, launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p,
                                EPI_STATS, nullptr, psum, psq, sc_store, wg, st));
-        if (!eval)
-            MBK_STEP(MBCONV_STEP_BN3_FINALIZE, launch_bn_finalize(P.Cout, P.NT5, (double)P.N * P.HWo, psum, psq, prm->bn3_gamma,
-                                       prm->bn3_beta, eps, mom, run ? run->bn3_mean : nullptr,
-                                       run ? run->bn3_var : nullptr, bn3, st));
+        if (!eval && !fuse3)
+            MBK_STEP(MBCONV_STEP_BN3_FINALIZE, launch_bn_finalize(P.Cout, P.NT5, m2, psum, psq, prm->bn3_gamma,
+                                       prm->bn3_beta, eps, mom, fin3.run_mean, fin3.run_var, bn3, st));
     }
-    // BN3 (+ residual)
-    MBK_STEP(MBCONV_STEP_BN3_APPLY, launch_bn_apply(bf, P.N, P.Cout, P.HWo, p, bn3, P.res ? x : nullptr, out, st));
+    // BN3 (+ residual), finalising BN3's statistics on the way in training mode
+    MBK_STEP(MBCONV_STEP_BN3_APPLY, launch_bn_apply(bf, P.N, P.Cout, P.HWo, p, bn3, P.res ? x : nullptr, out,
+                                                    fuse3 ? &fin3 : nullptr, st));
     return MBCONV_OK;
 }
 
@@ -384,6 +404,7 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
                                    gr->bn3_beta, coef3, st));
     // projection conv: data gradient G = W_p^T dp and weight gradient dW_p = dp * sc^T,
     // dp rebuilt in the prologue from dout and p
+    SplitReduce proj_reduce = {nullptr, 0, 0, nullptr};
     Operand dp;
     dp.p0 = dout;
     dp.p1 = p;
@@ -405,7 +426,11 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
             sc.gate = g;
             sc.pro = PRO_BNSWISH_GATE;
         }
-        MBK_STEP(MBCONV_STEP_PROJ_WGRAD, launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, wg, gr->w_proj, st));
+        // with an expansion conv, the sum over this weight gradient's splits waits for the
+        // other's and shares its launch (the partials then live in a region of their own)
+        MBK_STEP(MBCONV_STEP_PROJ_WGRAD,
+                 launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, P.expand ? at<float>(scratch, P.o_wg2) : wg,
+                                 gr->w_proj, P.expand ? &proj_reduce : nullptr, st));
     }
     // SE backward and BN2 backward reductions
     float *dg = at<float>(scratch, P.o_dg), *A1 = at<float>(scratch, P.o_A1);
@@ -494,7 +519,13 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
         Operand xo;
         xo.p0 = x;
         xo.pro = PRO_NONE;
-        MBK_STEP(MBCONV_STEP_EXPAND_WGRAD, launch_wgrad1x1(bf, P.N, P.Cexp, P.Cin, P.HW, de, xo, wg, gr->w_expand, st));
+        const auto both = [&]() {
+            SplitReduce exp_reduce;
+            const hipError_t e = launch_wgrad1x1(bf, P.N, P.Cexp, P.Cin, P.HW, de, xo, wg, gr->w_expand,
+                                                 &exp_reduce, st);
+            return e != hipSuccess ? e : launch_reduce_splits2(exp_reduce, proj_reduce, st);
+        };
+        MBK_STEP(MBCONV_STEP_EXPAND_WGRAD, both());
     }
     return MBCONV_OK;
 }

@@ -54,10 +54,41 @@ hipError_t launch_conv1x1_affine(bool bf16, int N, int M, int K, int HW, const v
 // Weight gradient of a 1x1 conv: dW[a,b] = sum_{n,q} op(U)[n,a,q] * op(V)[n,b,q].
 // `partial` needs wgrad_splits(...)*Ma*Mb floats.
 int wgrad_splits(bool bf16, int Ma, int Mb, int N, int HW);
+// With `defer` non-null the second stage (the sum over the splits) is not launched: it is
+// described in *defer, and the caller launches it later (launch_reduce_splits2, together with
+// another one); `partial` must stay untouched until then.
+struct SplitReduce {
+    const float *in; // [S][count]
+    int S;
+    size_t count;    // 0: no reduction
+    float *out;      // [count]
+};
 hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,
-                           const Operand &V, float *partial, float *dW, hipStream_t st);
+                           const Operand &V, float *partial, float *dW, SplitReduce *defer,
+                           hipStream_t st);
+hipError_t launch_reduce_splits2(const SplitReduce &a, const SplitReduce &b, hipStream_t st);
 
 // ---- batch-norm statistics ---------------------------------------------------------------
+// Training-mode statistics that the consuming kernel finalises itself (no launch for the finalise
+// step): the partial sums of the producer, and what the finalise step needs besides.
+struct BnFin {
+    const float *psum, *psq;   // [C][NP] partial sums and sums of squares
+    const float *gamma, *beta; // [C]
+    float *run_mean, *run_var; // [C] running statistics to update, or null
+    float *bn_out;             // {scale, shift, mean, rstd}[C], written once per channel
+    int NP;
+    float eps, momentum;
+    double inv_m;              // 1 / elements per channel
+    double unbias;             // m/(m-1) (1 when m == 1): biased -> unbiased variance
+};
+inline BnFin make_bn_fin(const float *psum, const float *psq, const float *gamma, const float *beta,
+                         float *run_mean, float *run_var, float *bn_out, int NP, float eps,
+                         float momentum, double m)
+{
+    return {psum, psq, gamma, beta, run_mean, run_var, bn_out, NP, eps, momentum,
+            1.0 / m, m > 1.0 ? m / (m - 1.0) : 1.0};
+}
+
 // psum/psq: [C][NP] partial sums.  Writes bn = {scale[C], shift[C], mean[C], rstd[C]} and
 // updates running statistics (if non-null) with momentum.
 hipError_t launch_bn_finalize(int C, int NP, double m, const float *psum, const float *psq,
@@ -102,9 +133,13 @@ size_t dw_bwd_lds_bytes(const DwShape &s);
 
 // d = depthwise(swish(e*scale1+shift1)) (or depthwise(e) when bn1 == nullptr), plus per-plane
 // partial sums of d and d^2 laid out [C][N].  a1_store (optional) receives swish(bn1(e)).
+// With `fin` non-null (only when dw_fwd_finalizes_bn1 says so) the kernel derives bn1 from fin's
+// partial sums and writes it to fin->bn_out; psum/psq must not overlap fin's partials.
+bool dw_fwd_finalizes_bn1(const DwShape &s, bool stores_a1);
+bool plane_finalize_pays(int HW); // launch_bn_apply: worth passing `fin` for planes of HW elements
 hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
                          const void *w_dw, void *d, float *psum, float *psq, void *a1_store,
-                         hipStream_t st);
+                         const BnFin *fin, hipStream_t st);
 
 // Per plane of d: z = mean swish(y2), s3 = sum swish'(y2), s4 = sum swish'(y2)*dhat.
 hipError_t launch_pool(bool bf16, int N, int C, int HW, const void *d, const float *bn2, float *z,
@@ -115,8 +150,9 @@ hipError_t launch_se_fwd(int N, int C, int Cse, const float *z, const float *w1,
                          const float *w2, const float *b2, float *q, float *g, hipStream_t st);
 
 // out = p*scale3+shift3 (+ x).
+// With `fin` non-null the kernel derives bn3 from fin's partial sums and writes it to fin->bn_out.
 hipError_t launch_bn_apply(bool bf16, int N, int C, int HW, const void *p, const float *bn3,
-                           const void *res, void *out, hipStream_t st);
+                           const void *res, void *out, const BnFin *fin, hipStream_t st);
 
 // Per plane: sums of dy and dy*xhat with xhat = (raw-mean)*rstd, laid out [C][N].
 hipError_t launch_plane_dot(bool bf16, int N, int C, int HW, const void *dy, const void *raw,
