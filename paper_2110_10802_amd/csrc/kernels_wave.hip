@@ -362,6 +362,241 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
         }
 }
 
+// ---- bwd1x1_lt: data and weight gradient of a narrow->wide 1x1 convolution in one pass ---------
+// The expansion conv's two gradients, dx = W^T de (+ dout) and dW = de x^T, both consume
+// de = c0*dy1 + c1*e + c2 (BN1's backward applied on the fly), two wide tensors that are by far
+// the largest operands; computing them in separate kernels reads both twice.  This kernel is
+// wgrad_lt (U = x, the narrow input; V = de, the wide side) that also multiplies each wavefront's
+// parked 32-channel x 32-pixel tile of de by its 32 rows of W:
+//   P_t[j][pix] = sum_{c in wavefront t} W[c][j] * de[c][pix]     (MFMA: A = W^T from registers,
+//                                                                   B = de read pixel-lane from LDS)
+// The wavefronts' P_t go through LDS and are added in wavefront order by the threads that staged
+// x: thread (row j, four pixels) owns exactly that element group of dx, so its address, its
+// validity and the residual it adds are those of its x load.  All wide channels of a pixel live
+// in one workgroup: dx needs no second stage.  Fixed summation order, no atomics.
+// (Section "Guided Optimization Case Study: EfficientNet": fusing the consumers of a tensor.)
+
+struct Bwd1x1Args {
+    WgradClArgs g; // U = x (PRO_NONE), V = de (PRO_BNBWD); partial: weight-gradient splits
+    const void *w; // [Mb][Ma] in the activation dtype (wide-major, as the layer stores it)
+    void *dx;      // [N][Ma][HW]
+    const void *res; // optional, added to dx
+};
+
+template <typename T>
+__device__ __forceinline__ void store4(T *p, size_t i, const float (&v)[4]);
+template <>
+__device__ __forceinline__ void store4<float>(float *p, size_t i, const float (&v)[4])
+{
+    *reinterpret_cast<float4v *>(p + i) = (float4v){v[0], v[1], v[2], v[3]};
+}
+template <>
+__device__ __forceinline__ void store4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
+{
+    uint2 t;
+    t.x = bf16_pack2(v[0], v[1]);
+    t.y = bf16_pack2(v[2], v[3]);
+    *reinterpret_cast<uint2 *>(&p[i]) = t;
+}
+
+template <typename T, int MTA>
+__global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
+{
+    const WgradClArgs &a = b.g;
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x & 63;
+    const int t = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform
+    const int nw = blockDim.x >> 6, R = 32 * nw;
+    const int h = lane >> 5, c = lane & 31;
+    float *Us = lds;                                               // [2][32*MTA][pitch]
+    float *Vs = lds + 2 * 32 * MTA * kLtPitch + t * 32 * kLtPitch;   // this wave's [32][pitch]
+    float *Pd = lds + (2 * 32 * MTA + R) * kLtPitch;                 // [nw][32*MTA][pitch]
+    float *Wl = Pd + (size_t)R * MTA * kLtPitch + (size_t)t * MTA * 16 * 64; // this wave's [MTA][16][64]
+    float *Cl = Pd + (size_t)R * MTA * kLtPitch + (size_t)nw * MTA * 16 * 64; // [3][R]
+    // (registers are what limits the workgroups per CU here: everything that is constant over the
+    // pixel loop and not needed every cycle waits in LDS)
+
+    // V tile (de), row-wise: this lane loads pixels [vcol, vcol+4) of rows lane/8 + 8i, i = 0..3
+    const int vcol = 4 * (lane & 7);
+    const int vrow = 32 * t + (lane >> 3);
+    int vch[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int ch = vrow + 8 * i;
+        vch[i] = ch < a.Mb ? ch : a.Mb - 1; // rows past the end meet zero weights, and are never stored
+    }
+    // BN-backward coefficients of every wide row
+    for (int r = threadIdx.x; r < R; r += blockDim.x) {
+        const int ch = r < a.Mb ? r : a.Mb - 1;
+        Cl[r] = a.vc0[ch];
+        Cl[R + r] = a.vc1[ch];
+        Cl[2 * R + r] = a.vc2[ch];
+    }
+    // this wave's rows of W as the MFMA's A operand: lane (h, c), step kk holds
+    // W[32t + 2kk + h][32ta + c]; zero outside the matrix
+    const int kvalid = a.Mb - 32 * t; // wide channels this wave really has (wave-uniform)
+#pragma unroll
+    for (int ta = 0; ta < MTA; ++ta)
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const int cw = 32 * t + 2 * kk + h, jn = 32 * ta + c;
+            const bool ok = cw < a.Mb && jn < a.Ma;
+            const float wv = ld<T>((const T *)b.w, ok ? (size_t)cw * a.Ma + jn : 0);
+            Wl[(ta * 16 + kk) * 64 + lane] = ok ? wv : 0.f;
+        }
+    // U tile (x), row-wise, by the first 256 threads: row = tid/8 (+32 per extra tile)
+    const bool ustager = threadIdx.x < 256;
+    const int urow = (threadIdx.x >> 3) & 31;
+    int uch[MTA];
+#pragma unroll
+    for (int ta = 0; ta < MTA; ++ta) {
+        const int ch = 32 * ta + urow;
+        uch[ta] = ch < a.Ma ? ch : a.Ma - 1;
+    }
+
+    float16v acc[MTA];
+#pragma unroll
+    for (int ta = 0; ta < MTA; ++ta)
+        acc[ta] = (float16v){0};
+
+    const int cBeg = blockIdx.x * a.chunksPerWg;
+    const int cEnd = (cBeg + a.chunksPerWg < a.numChunks) ? cBeg + a.chunksPerWg : a.numChunks;
+
+    float vv[4][4], vr[4][4], uu[MTA][4];
+    size_t uidx[MTA];
+    bool pok = true; // this lane's four pixels exist (false only in a ragged last chunk)
+    auto fetch = [&](int ch) {
+        const uint32_t q = (uint32_t)ch * 32u + (uint32_t)vcol;
+        pok = q < a.Q;
+        const uint32_t qs = pok ? q : 0u;
+        const uint32_t n = fdiv(qs, a.divHW);
+        const uint32_t pix = qs - n * (uint32_t)a.HW;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const size_t idx = ((size_t)n * a.Mb + vch[i]) * a.HW + pix;
+            load4<T>((const T *)a.v0, idx, vv[i]);
+            load4<T>((const T *)a.v1, idx, vr[i]);
+        }
+        if (ustager) {
+#pragma unroll
+            for (int ta = 0; ta < MTA; ++ta) {
+                uidx[ta] = ((size_t)n * a.Ma + uch[ta]) * a.HW + pix;
+                load4<T>((const T *)a.u0, uidx[ta], uu[ta]);
+            }
+        }
+    };
+
+    if (cBeg < cEnd)
+        fetch(cBeg);
+    __syncthreads(); // Cl, Wl
+    for (int ch = cBeg; ch < cEnd; ++ch) {
+        float *Ub = Us + ((ch - cBeg) & 1) * (32 * MTA * kLtPitch);
+        // finish the prologue on the fetched registers and park the tiles in LDS
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = vrow + 8 * i;
+            lt_prologue<T, PRO_BNBWD>(vv[i], vr[i], Cl[r], Cl[R + r], Cl[2 * R + r], 0.f);
+            float4v w4 = {vv[i][0], vv[i][1], vv[i][2], vv[i][3]};
+            if (!pok)
+                w4 = (float4v){0.f, 0.f, 0.f, 0.f};
+            *reinterpret_cast<float4v *>(Vs + ((lane >> 3) + 8 * i) * kLtPitch + vcol) = w4;
+        }
+        // what this thread needs later to finish its element group of dx for this chunk
+        size_t oidx[MTA];
+        const bool ook = pok;
+        if (ustager) {
+#pragma unroll
+            for (int ta = 0; ta < MTA; ++ta) {
+                float4v w4 = {uu[ta][0], uu[ta][1], uu[ta][2], uu[ta][3]};
+                if (!pok)
+                    w4 = (float4v){0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<float4v *>(Ub + (32 * ta + urow) * kLtPitch + vcol) = w4;
+                oidx[ta] = uidx[ta];
+            }
+        }
+        __syncthreads();
+        // the residual of this chunk's dx elements, then the next chunk's operands: both in
+        // flight while this chunk is multiplied
+        float ores[MTA][4];
+        if (ustager) {
+#pragma unroll
+            for (int ta = 0; ta < MTA; ++ta) {
+                if (b.res) {
+                    load4<T>((const T *)b.res, oidx[ta], ores[ta]);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        ores[ta][r] = 0.f;
+                }
+            }
+        }
+        if (ch + 1 < cEnd)
+            fetch(ch + 1);
+        // weight gradient: channel-lane reads, lane (c, h) takes pixels 8*jj + 4*h + {0..3} of
+        // its channel row
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const float4v bvv = *reinterpret_cast<const float4v *>(Vs + c * kLtPitch + 8 * jj + 4 * h);
+#pragma unroll
+            for (int ta = 0; ta < MTA; ++ta) {
+                const float4v avv =
+                    *reinterpret_cast<const float4v *>(Ub + (32 * ta + c) * kLtPitch + 8 * jj + 4 * h);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[ta] = __builtin_amdgcn_mfma_f32_32x32x2f32(avv[r], bvv[r], acc[ta], 0, 0, 0);
+            }
+        }
+        // data gradient of this wave's channels: pixel-lane reads, lane (h, c) takes de[2kk+h][c]
+        float16v accd[MTA];
+#pragma unroll
+        for (int ta = 0; ta < MTA; ++ta)
+            accd[ta] = (float16v){0};
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            if (2 * kk < kvalid) { // wave-uniform: the last wave may own fewer than 32 channels
+                const float dv = Vs[(2 * kk + h) * kLtPitch + c];
+#pragma unroll
+                for (int ta = 0; ta < MTA; ++ta)
+                    accd[ta] = __builtin_amdgcn_mfma_f32_32x32x2f32(Wl[(ta * 16 + kk) * 64 + lane], dv,
+                                                                    accd[ta], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int ta = 0; ta < MTA; ++ta)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int j = 32 * ta + 8 * (q >> 2) + 4 * h + (q & 3);
+                Pd[((size_t)t * 32 * MTA + j) * kLtPitch + c] = accd[ta][q];
+            }
+        __syncthreads();
+        if (ustager) {
+#pragma unroll
+            for (int ta = 0; ta < MTA; ++ta) {
+                float o[4] = {ores[ta][0], ores[ta][1], ores[ta][2], ores[ta][3]};
+                for (int w = 0; w < nw; ++w) {
+                    const float4v pv = *reinterpret_cast<const float4v *>(
+                        Pd + ((size_t)w * 32 * MTA + 32 * ta + urow) * kLtPitch + vcol);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        o[r] += pv[r];
+                }
+                if (ook && 32 * ta + urow < a.Ma)
+                    store4<T>((T *)b.dx, oidx[ta], o);
+            }
+        }
+    }
+    const int bcol = 32 * t + c;
+    float *dst = a.partial + (size_t)blockIdx.x * a.Ma * a.Mb;
+#pragma unroll
+    for (int ta = 0; ta < MTA; ++ta)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int ai = 32 * ta + 8 * (q >> 2) + 4 * h + (q & 3);
+            if (ai < a.Ma && bcol < a.Mb)
+                dst[(size_t)ai * a.sOa + (size_t)bcol * a.sOb] = acc[ta][q];
+        }
+}
+
 // Orientation and split count; returns false when the shape is not covered.
 bool wgrad_cl_plan(int Ma, int Mb, int N, int HW, bool *swap, int *splits)
 {
@@ -439,6 +674,65 @@ hipError_t launch_wgrad_cl(bool bf16, int N, int Ma, int Mb, int HW, const Opera
     dim3 grid((unsigned)splits), block((unsigned)(64 * (mtb < 4 ? 4 : mtb))); // >= 256 threads stage U
     return bf16 ? wgrad_cl_dispatch<bf16_t>(a, mta, u.pro, v.pro, grid, block, st)
                 : wgrad_cl_dispatch<float>(a, mta, u.pro, v.pro, grid, block, st);
+}
+
+bool bwd1x1_fused_plan(int N, int Cw, int Cn, int HW, int *splits)
+{
+    bool swap;
+    // the narrow side must be the convolution's input and fit one 32-row tile (two tiles would
+    // need more registers and LDS than two workgroups per CU leave); other shapes go the
+    // ordinary way, as two kernels
+    return Cn <= 32 && Cn < Cw && wgrad_cl_plan(Cw, Cn, N, HW, &swap, splits) && swap;
+}
+
+hipError_t launch_bwd1x1_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &de,
+                               const void *xin, const void *w, void *dx, const void *res,
+                               float *partial, int *splits_out, hipStream_t st)
+{
+    int splits;
+    if (!bwd1x1_fused_plan(N, Cw, Cn, HW, &splits) || de.pro != PRO_BNBWD)
+        return hipErrorInvalidValue;
+    Bwd1x1Args b = {};
+    WgradClArgs &a = b.g;
+    a.N = N;
+    a.Ma = Cn;
+    a.Mb = Cw;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    a.numChunks = (int)((a.Q + 31u) / 32u);
+    a.chunksPerWg = (a.numChunks + splits - 1) / splits;
+    a.divHW = make_div((uint32_t)HW);
+    a.u0 = xin;
+    a.v0 = de.p0;
+    a.v1 = de.p1;
+    a.vc0 = de.c0;
+    a.vc1 = de.c1;
+    a.vc2 = de.c2;
+    a.sOa = 1; // the caller's dW is [Cw][Cn] row-major
+    a.sOb = Cn;
+    a.partial = partial;
+    b.w = w;
+    b.dx = dx;
+    b.res = res;
+    *splits_out = splits;
+    const int mta = (Cn + 31) / 32, mtb = (Cw + 31) / 32;
+    const int nw = mtb < 4 ? 4 : mtb; // >= 256 threads stage x and finish dx
+    const size_t lds = sizeof(float) * (kLtPitch * 32 * (2 * mta + nw + (size_t)nw * mta) +
+                                        (size_t)nw * mta * 16 * 64 + 3 * 32 * nw);
+    dim3 grid((unsigned)splits), block((unsigned)(64 * nw));
+#define MBK_CASE(T, MTA)                                                                          \
+    {                                                                                             \
+        hipError_t e = hipFuncSetAttribute((const void *)bwd1x1_lt_kernel<T, MTA>,                \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        if (e != hipSuccess)                                                                      \
+            return e;                                                                             \
+        hipLaunchKernelGGL((bwd1x1_lt_kernel<T, MTA>), grid, block, lds, st, b);                  \
+        return hipGetLastError();                                                                 \
+    }
+    if (bf16)
+        MBK_CASE(bf16_t, 1)
+    MBK_CASE(float, 1)
+#undef MBK_CASE
 }
 
 } // namespace mbk

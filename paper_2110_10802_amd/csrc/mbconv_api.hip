@@ -512,7 +512,17 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
         de.c1 = coef1 + P.Cexp;
         de.c2 = coef1 + 2 * P.Cexp;
         de.pro = PRO_BNBWD;
-        // dx = W_e^T de (+ dout), dW_e = de * x^T
+        // dx = W_e^T de (+ dout), dW_e = de * x^T: one pass over de where the fused kernel covers
+        // the shape (its launch is the EXPAND_DGRAD step, the sums over the splits EXPAND_WGRAD)
+        int fsplits = 0;
+        if (bwd1x1_fused_plan(P.N, P.Cexp, P.Cin, P.HW, &fsplits)) {
+            MBK_STEP(MBCONV_STEP_EXPAND_DGRAD,
+                     launch_bwd1x1_fused(bf, P.N, P.Cexp, P.Cin, P.HW, de, x, prm->w_expand, dx,
+                                         P.res ? dout : nullptr, wg, &fsplits, st));
+            const SplitReduce exp_reduce = {wg, fsplits, (size_t)P.Cexp * P.Cin, gr->w_expand};
+            MBK_STEP(MBCONV_STEP_EXPAND_WGRAD, launch_reduce_splits2(exp_reduce, proj_reduce, st));
+            return MBCONV_OK;
+        }
         MBK_STEP(MBCONV_STEP_EXPAND_DGRAD, launch_conv1x1(bf, P.N, P.Cin, P.Cexp, P.HW, prm->w_expand, 1, P.Cin, de, dx,
                                P.res ? EPI_RES : EPI_NONE, P.res ? dout : nullptr, nullptr, nullptr,
                                nullptr, wg, st));

@@ -68,6 +68,17 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
                            hipStream_t st);
 hipError_t launch_reduce_splits2(const SplitReduce &a, const SplitReduce &b, hipStream_t st);
 
+// Both gradients of a 1x1 convolution from Cn (narrow) to Cw (wide) channels in one pass over
+// de, the gradient at its output (PRO_BNBWD operand, [N,Cw,HW]):
+//   dx[n,j,q] = sum_c w[c*Cn+j] * de[n,c,q] (+ res[n,j,q]),   dW[c][j] = sum_{n,q} de[n,c,q] * x[n,j,q]
+// bwd1x1_fused_plan tells whether the shape is covered (Cn <= 32, Cn < Cw <= 256, HW % 4 == 0) and
+// how many splits of dW land in `partial` ([splits][Cw*Cn] floats, the count wgrad_splits gives);
+// the caller sums them (launch_reduce_splits2).
+bool bwd1x1_fused_plan(int N, int Cw, int Cn, int HW, int *splits);
+hipError_t launch_bwd1x1_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &de,
+                               const void *xin, const void *w, void *dx, const void *res,
+                               float *partial, int *splits_out, hipStream_t st);
+
 // ---- batch-norm statistics ---------------------------------------------------------------
 // Training-mode statistics that the consuming kernel finalises itself (no launch for the finalise
 // step): the partial sums of the producer, and what the finalise step needs besides.
