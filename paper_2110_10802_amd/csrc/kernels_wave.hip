@@ -14,6 +14,7 @@
 // step, section "Guided Optimization Case Study: EfficientNet").
 #include "mbconv_dev.h"
 #include "mbconv_launch.h"
+#include <type_traits>
 
 namespace mbk {
 
@@ -241,11 +242,13 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
     // V tile, row-wise: this lane loads pixels [vcol, vcol+4) of rows lane/8 + 8i, i = 0..3
     const int vcol = 4 * (lane & 7);
     int vch[4];
+    uint32_t vro[4]; // element offset of the row within an image (32 bits)
     float vk0[4], vk1[4], vk2[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int ch = 32 * t + (lane >> 3) + 8 * i;
         vch[i] = ch < a.Mb ? ch : a.Mb - 1; // rows past the end are computed but never stored
+        vro[i] = (uint32_t)vch[i] * (uint32_t)a.HW;
         vk0[i] = vk1[i] = vk2[i] = 0.f;
         if (PROV != PRO_NONE) {
             vk0[i] = a.vc0[vch[i]];
@@ -254,15 +257,18 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
                 vk2[i] = a.vc2[vch[i]];
         }
     }
+    const uint32_t vimg = (uint32_t)a.Mb * (uint32_t)a.HW, uimg = (uint32_t)a.Ma * (uint32_t)a.HW;
     // U tile, row-wise, by the first 256 threads: row = tid/8 (+32 per extra tile), same columns
     const bool ustager = threadIdx.x < 256;
     const int urow = (threadIdx.x >> 3) & 31;
     int uch[MTA];
+    uint32_t uro[MTA];
     float uk0[MTA], uk1[MTA], uk2[MTA];
 #pragma unroll
     for (int ta = 0; ta < MTA; ++ta) {
         const int ch = 32 * ta + urow;
         uch[ta] = ch < a.Ma ? ch : a.Ma - 1;
+        uro[ta] = (uint32_t)uch[ta] * (uint32_t)a.HW;
         uk0[ta] = uk1[ta] = uk2[ta] = 0.f;
         if (PROU != PRO_NONE) {
             uk0[ta] = a.uc0[uch[ta]];
@@ -277,8 +283,9 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
     for (int ta = 0; ta < MTA; ++ta)
         acc[ta] = (float16v){0};
 
-    const int cBeg = blockIdx.x * a.chunksPerWg;
-    const int cEnd = (cBeg + a.chunksPerWg < a.numChunks) ? cBeg + a.chunksPerWg : a.numChunks;
+    // Chunks are dealt out round-robin: at any moment the workgroups in flight read neighbouring
+    // 128-byte pieces of every channel row instead of pieces chunksPerWg*128 bytes apart.
+    const int cBeg = blockIdx.x, cStep = gridDim.x, cEnd = a.numChunks;
 
     float vv[4][4], vr[4][4], vg[4], uu[MTA][4], ur[MTA][4], ug[MTA];
     bool pok = true; // this lane's four pixels exist (false only in a ragged last chunk)
@@ -288,9 +295,11 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
         const uint32_t qs = pok ? q : 0u;
         const uint32_t n = fdiv(qs, a.divHW);
         const uint32_t pix = qs - n * (uint32_t)a.HW;
+        // (one 64-bit multiply-add per chunk and an addition per load)
+        const size_t vbase = (size_t)n * vimg + pix;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const size_t idx = ((size_t)n * a.Mb + vch[i]) * a.HW + pix;
+            const size_t idx = vbase + vro[i];
             load4<T>((const T *)a.v0, idx, vv[i]);
             if (PROV == PRO_BNBWD)
                 load4<T>((const T *)a.v1, idx, vr[i]);
@@ -298,9 +307,10 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
                 vg[i] = a.vgate[(size_t)n * a.Mb + vch[i]];
         }
         if (ustager) {
+            const size_t ubase = (size_t)n * uimg + pix;
 #pragma unroll
             for (int ta = 0; ta < MTA; ++ta) {
-                const size_t idx = ((size_t)n * a.Ma + uch[ta]) * a.HW + pix;
+                const size_t idx = ubase + uro[ta];
                 load4<T>((const T *)a.u0, idx, uu[ta]);
                 if (PROU == PRO_BNBWD)
                     load4<T>((const T *)a.u1, idx, ur[ta]);
@@ -310,10 +320,12 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
         }
     };
 
-    if (cBeg < cEnd)
-        fetch(cBeg);
-    for (int ch = cBeg; ch < cEnd; ++ch) {
-        float *Ub = Us + ((ch - cBeg) & 1) * (32 * MTA * kLtPitch);
+    // One chunk.  `more` (a compile-time flag: the last chunk gets a copy of the body without the
+    // loads, so that every wait in both copies counts a fixed number of outstanding loads) says
+    // whether another chunk follows; its operands are requested as soon as this chunk's have been
+    // parked, before the barrier.
+    const auto body = [&](int ch, int it, auto more) {
+        float *Ub = Us + (it & 1) * (32 * MTA * kLtPitch);
         // finish the prologue on the fetched registers and park the tiles in LDS
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -333,9 +345,9 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
                 *reinterpret_cast<float4v *>(Ub + (32 * ta + urow) * kLtPitch + vcol) = w4;
             }
         }
+        if (decltype(more)::value)
+            fetch(ch + cStep); // in flight while this chunk is multiplied
         __syncthreads();
-        if (ch + 1 < cEnd)
-            fetch(ch + 1); // in flight while this chunk is multiplied
         // channel-lane reads: lane (c, h) takes pixels 8*jj + 4*h + {0..3} of its channel row
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
@@ -349,6 +361,13 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
                     acc[ta] = __builtin_amdgcn_mfma_f32_32x32x2f32(avv[r], bvv[r], acc[ta], 0, 0, 0);
             }
         }
+    };
+    if (cBeg < cEnd) {
+        fetch(cBeg);
+        int it = 0, ch = cBeg;
+        for (; ch + cStep < cEnd; ch += cStep, ++it)
+            body(ch, it, std::true_type{});
+        body(ch, it, std::false_type{});
     }
     const int b = 32 * t + c;
     float *dst = a.partial + (size_t)blockIdx.x * a.Ma * a.Mb;
@@ -370,7 +389,10 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
 // parked 32-channel x 32-pixel tile of de by its 32 rows of W:
 //   P_t[j][pix] = sum_{c in wavefront t} W[c][j] * de[c][pix]     (MFMA: A = W^T from registers,
 //                                                                   B = de read pixel-lane from LDS)
-// The wavefronts' P_t go through LDS and are added in wavefront order by the threads that staged
+// (any wavefront can take any step of that contraction, the tiles being in LDS: the steps are
+// dealt out so that the four SIMDs of a CU, which the wavefronts of a workgroup occupy in turn,
+// get equal numbers of MFMAs although only the first ceil(Mb/32) wavefronts have weight-gradient
+// work.)  The wavefronts' P_t go through LDS and are added in wavefront order by the threads that staged
 // x: thread (row j, four pixels) owns exactly that element group of dx, so its address, its
 // validity and the residual it adds are those of its x load.  All wide channels of a pixel live
 // in one workgroup: dx needs no second stage.  Fixed summation order, no atomics.
@@ -378,6 +400,7 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
 
 struct Bwd1x1Args {
     WgradClArgs g; // U = x (PRO_NONE), V = de (PRO_BNBWD); partial: weight-gradient splits
+    int kbeg[9];   // wavefront t multiplies contraction steps [kbeg[t], kbeg[t+1]) of the data gradient
     const void *w; // [Mb][Ma] in the activation dtype (wide-major, as the layer stores it)
     void *dx;      // [N][Ma][HW]
     const void *res; // optional, added to dx
@@ -411,47 +434,34 @@ __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
     float *Us = lds;                                               // [2][32*MTA][pitch]
     float *Vs = lds + 2 * 32 * MTA * kLtPitch + t * 32 * kLtPitch;   // this wave's [32][pitch]
     float *Pd = lds + (2 * 32 * MTA + R) * kLtPitch;                 // [nw][32*MTA][pitch]
-    float *Wl = Pd + (size_t)R * MTA * kLtPitch + (size_t)t * MTA * 16 * 64; // this wave's [MTA][16][64]
-    float *Cl = Pd + (size_t)R * MTA * kLtPitch + (size_t)nw * MTA * 16 * 64; // [3][R]
+    const float *Vall = lds + 2 * 32 * MTA * kLtPitch;               // all waves' tiles: [R][pitch]
+    float *Wl = Pd + (size_t)R * MTA * kLtPitch;                     // [R/2 steps][MTA][64]
+    float *Cl = Wl + (size_t)(R / 2) * MTA * 64;                     // [3][R]
     // (registers are what limits the workgroups per CU here: everything that is constant over the
     // pixel loop and not needed every cycle waits in LDS)
 
     // V tile (de), row-wise: this lane loads pixels [vcol, vcol+4) of rows lane/8 + 8i, i = 0..3
     const int vcol = 4 * (lane & 7);
     const int vrow = 32 * t + (lane >> 3);
-    int vch[4];
+    // (element offsets of this lane's rows within an image, 32 bits: the per-chunk address
+    // arithmetic is one 64-bit multiply-add and an addition per load)
+    uint32_t vro[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int ch = vrow + 8 * i;
-        vch[i] = ch < a.Mb ? ch : a.Mb - 1; // rows past the end meet zero weights, and are never stored
+        // rows past the end meet zero weights, and are never stored
+        vro[i] = (uint32_t)(ch < a.Mb ? ch : a.Mb - 1) * (uint32_t)a.HW;
     }
-    // BN-backward coefficients of every wide row
-    for (int r = threadIdx.x; r < R; r += blockDim.x) {
-        const int ch = r < a.Mb ? r : a.Mb - 1;
-        Cl[r] = a.vc0[ch];
-        Cl[R + r] = a.vc1[ch];
-        Cl[2 * R + r] = a.vc2[ch];
-    }
-    // this wave's rows of W as the MFMA's A operand: lane (h, c), step kk holds
-    // W[32t + 2kk + h][32ta + c]; zero outside the matrix
-    const int kvalid = a.Mb - 32 * t; // wide channels this wave really has (wave-uniform)
-#pragma unroll
-    for (int ta = 0; ta < MTA; ++ta)
-#pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-            const int cw = 32 * t + 2 * kk + h, jn = 32 * ta + c;
-            const bool ok = cw < a.Mb && jn < a.Ma;
-            const float wv = ld<T>((const T *)b.w, ok ? (size_t)cw * a.Ma + jn : 0);
-            Wl[(ta * 16 + kk) * 64 + lane] = ok ? wv : 0.f;
-        }
+    const uint32_t vimg = (uint32_t)a.Mb * (uint32_t)a.HW, uimg = (uint32_t)a.Ma * (uint32_t)a.HW;
+    const int kb = b.kbeg[t], ke = b.kbeg[t + 1]; // wave-uniform
     // U tile (x), row-wise, by the first 256 threads: row = tid/8 (+32 per extra tile)
     const bool ustager = threadIdx.x < 256;
     const int urow = (threadIdx.x >> 3) & 31;
-    int uch[MTA];
+    uint32_t uro[MTA];
 #pragma unroll
     for (int ta = 0; ta < MTA; ++ta) {
         const int ch = 32 * ta + urow;
-        uch[ta] = ch < a.Ma ? ch : a.Ma - 1;
+        uro[ta] = (uint32_t)(ch < a.Ma ? ch : a.Ma - 1) * (uint32_t)a.HW;
     }
 
     float16v acc[MTA];
@@ -459,8 +469,10 @@ __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
     for (int ta = 0; ta < MTA; ++ta)
         acc[ta] = (float16v){0};
 
-    const int cBeg = blockIdx.x * a.chunksPerWg;
-    const int cEnd = (cBeg + a.chunksPerWg < a.numChunks) ? cBeg + a.chunksPerWg : a.numChunks;
+    // Chunks are dealt out round-robin: at any moment the workgroups in flight read neighbouring
+    // 128-byte pieces of every channel row (DRAM pages and cache sectors are shared between them)
+    // instead of pieces chunksPerWg*128 bytes apart.
+    const int cBeg = blockIdx.x, cStep = gridDim.x, cEnd = a.numChunks;
 
     float vv[4][4], vr[4][4], uu[MTA][4];
     size_t uidx[MTA];
@@ -471,26 +483,60 @@ __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
         const uint32_t qs = pok ? q : 0u;
         const uint32_t n = fdiv(qs, a.divHW);
         const uint32_t pix = qs - n * (uint32_t)a.HW;
+        const size_t vbase = (size_t)n * vimg + pix;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const size_t idx = ((size_t)n * a.Mb + vch[i]) * a.HW + pix;
+            const size_t idx = vbase + vro[i];
             load4<T>((const T *)a.v0, idx, vv[i]);
             load4<T>((const T *)a.v1, idx, vr[i]);
         }
         if (ustager) {
+            const size_t ubase = (size_t)n * uimg + pix;
 #pragma unroll
             for (int ta = 0; ta < MTA; ++ta) {
-                uidx[ta] = ((size_t)n * a.Ma + uch[ta]) * a.HW + pix;
+                uidx[ta] = ubase + uro[ta];
                 load4<T>((const T *)a.u0, uidx[ta], uu[ta]);
             }
         }
     };
 
+    // BN-backward coefficients of every wide row
+    for (int r = threadIdx.x; r < R; r += blockDim.x) {
+        const int ch = r < a.Mb ? r : a.Mb - 1;
+        Cl[r] = a.vc0[ch];
+        Cl[R + r] = a.vc1[ch];
+        Cl[2 * R + r] = a.vc2[ch];
+    }
+    // W as the data gradient's MFMA A operand: for contraction step k, lane (h, c) holds
+    // W[2k + h][32ta + c]; zero outside the matrix.  (R/2)*MTA*64 entries, blockDim = 2R threads:
+    // 16*MTA per thread, all loads issued before the first store (one memory round trip, not
+    // sixteen).  (Measured: requesting the first chunk's operands ahead of these tables, or
+    // together with them, is slower than after them.)
+    {
+        float wreg[16 * MTA];
+#pragma unroll
+        for (int i = 0; i < 16 * MTA; ++i) {
+            const int e = threadIdx.x + i * (int)blockDim.x;
+            const int l = e & 63, ta = (e >> 6) % MTA, k = (e >> 6) / MTA;
+            const int cw = 2 * k + (l >> 5), jn = 32 * ta + (l & 31);
+            const bool ok = cw < a.Mb && jn < a.Ma;
+            wreg[i] = and_mask(ld<T>((const T *)b.w, ok ? (size_t)cw * a.Ma + jn : 0),
+                               ok ? 0xffffffffu : 0u);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 16 * MTA; ++i)
+            Wl[threadIdx.x + i * (int)blockDim.x] = wreg[i];
+    }
     if (cBeg < cEnd)
         fetch(cBeg);
     __syncthreads(); // Cl, Wl
-    for (int ch = cBeg; ch < cEnd; ++ch) {
-        float *Ub = Us + ((ch - cBeg) & 1) * (32 * MTA * kLtPitch);
+    // One chunk.  `more` (a compile-time flag: the last chunk gets a copy of the body without the
+    // loads, so that every wait in both copies counts a fixed number of outstanding loads) says
+    // whether another chunk follows; its operands are requested as soon as this chunk's have been
+    // parked, before the barrier.
+    const auto body = [&](int ch, int it, auto more) {
+        float *Ub = Us + (it & 1) * (32 * MTA * kLtPitch);
         // finish the prologue on the fetched registers and park the tiles in LDS
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -514,7 +560,6 @@ __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
                 oidx[ta] = uidx[ta];
             }
         }
-        __syncthreads();
         // the residual of this chunk's dx elements, then the next chunk's operands: both in
         // flight while this chunk is multiplied
         float ores[MTA][4];
@@ -530,8 +575,9 @@ __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
                 }
             }
         }
-        if (ch + 1 < cEnd)
-            fetch(ch + 1);
+        if (decltype(more)::value)
+            fetch(ch + cStep);
+        __syncthreads();
         // weight gradient: channel-lane reads, lane (c, h) takes pixels 8*jj + 4*h + {0..3} of
         // its channel row
 #pragma unroll
@@ -546,18 +592,35 @@ __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
                     acc[ta] = __builtin_amdgcn_mfma_f32_32x32x2f32(avv[r], bvv[r], acc[ta], 0, 0, 0);
             }
         }
-        // data gradient of this wave's channels: pixel-lane reads, lane (h, c) takes de[2kk+h][c]
+        // data gradient, this wave's share of the contraction: pixel-lane reads, lane (h, c)
+        // takes de[2k+h][c]
         float16v accd[MTA];
 #pragma unroll
         for (int ta = 0; ta < MTA; ++ta)
             accd[ta] = (float16v){0};
+        {
+            // four steps at a time: their LDS reads go out together, ahead of the four MFMAs
+            int k = kb;
+            for (; k + 4 <= ke; k += 4) {
+                float dv[4], wv[4][MTA];
 #pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-            if (2 * kk < kvalid) { // wave-uniform: the last wave may own fewer than 32 channels
-                const float dv = Vs[(2 * kk + h) * kLtPitch + c];
+                for (int u = 0; u < 4; ++u) {
+                    dv[u] = Vall[(2 * (k + u) + h) * kLtPitch + c];
+#pragma unroll
+                    for (int ta = 0; ta < MTA; ++ta)
+                        wv[u][ta] = Wl[((k + u) * MTA + ta) * 64 + lane];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int ta = 0; ta < MTA; ++ta)
+                        accd[ta] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[u][ta], dv[u], accd[ta], 0, 0, 0);
+            }
+            for (; k < ke; ++k) {
+                const float dv = Vall[(2 * k + h) * kLtPitch + c];
 #pragma unroll
                 for (int ta = 0; ta < MTA; ++ta)
-                    accd[ta] = __builtin_amdgcn_mfma_f32_32x32x2f32(Wl[(ta * 16 + kk) * 64 + lane], dv,
+                    accd[ta] = __builtin_amdgcn_mfma_f32_32x32x2f32(Wl[(k * MTA + ta) * 64 + lane], dv,
                                                                     accd[ta], 0, 0, 0);
             }
         }
@@ -584,6 +647,12 @@ __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
                     store4<T>((T *)b.dx, oidx[ta], o);
             }
         }
+    };
+    if (cBeg < cEnd) {
+        int it = 0, ch = cBeg;
+        for (; ch + cStep < cEnd; ch += cStep, ++it)
+            body(ch, it, std::true_type{});
+        body(ch, it, std::false_type{});
     }
     const int bcol = 32 * t + c;
     float *dst = a.partial + (size_t)blockIdx.x * a.Ma * a.Mb;
@@ -719,6 +788,31 @@ hipError_t launch_bwd1x1_fused(bool bf16, int N, int Cw, int Cn, int HW, const O
     const int nw = mtb < 4 ? 4 : mtb; // >= 256 threads stage x and finish dx
     const size_t lds = sizeof(float) * (kLtPitch * 32 * (2 * mta + nw + (size_t)nw * mta) +
                                         (size_t)nw * mta * 16 * 64 + 3 * 32 * nw);
+    // Deal the data gradient's ceil(Cw/2) contraction steps out to the wavefronts so that the
+    // SIMDs (wavefront t runs on SIMD t % 4) end up with equal MFMA counts; a wavefront with a
+    // weight-gradient tile already has 16 per narrow tile.
+    {
+        const int K = (Cw + 1) / 2;
+        int load[4] = {0, 0, 0, 0}, cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int t = 0; t < nw; ++t)
+            if (t < mtb)
+                load[t % 4] += 16;
+        for (int k = 0; k < K; ++k) { // one step at a time to the least loaded SIMD's least loaded wave
+            int sbest = 0;
+            for (int sd = 1; sd < 4; ++sd)
+                if (load[sd] < load[sbest])
+                    sbest = sd;
+            int tbest = sbest;
+            for (int t = sbest; t < nw; t += 4)
+                if (cnt[t] < cnt[tbest])
+                    tbest = t;
+            ++cnt[tbest];
+            ++load[sbest];
+        }
+        b.kbeg[0] = 0;
+        for (int t = 0; t < 8; ++t)
+            b.kbeg[t + 1] = b.kbeg[t] + (t < nw ? cnt[t] : 0);
+    }
     dim3 grid((unsigned)splits), block((unsigned)(64 * nw));
 #define MBK_CASE(T, MTA)                                                                          \
     {                                                                                             \
