@@ -271,12 +271,24 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, keep it scalar
     const int kk = lane >> 4, j = lane & 15;
     // wl[(s*2+t)*64 + l] = W(ch = 16t + l%16, k = 4s + l/16), zero outside M x K
-    for (int idx = threadIdx.x; idx < KS4p * 2 * 64; idx += 256) {
-        const int ln = idx & 63, st_ = idx >> 6;
-        const int m = 16 * (st_ & 1) + (ln & 15), k = 4 * (st_ >> 1) + (ln >> 4);
-        wl[idx] = (m < a.M && k < a.K)
-                      ? ld<T>((const T *)a.w, (size_t)m * a.sAm + (size_t)k * a.sAk)
-                      : 0.f;
+    // (KS4p*128 entries, 256 threads: KS4p/2 = 2*KSWp per thread, six loads in flight at a time:
+    // a load-store loop would pay one memory round trip per entry)
+    for (int i0 = 0; i0 < 2 * KSWp; i0 += 6) {
+        float wv[6];
+#pragma unroll
+        for (int u = 0; u < 6; ++u) {
+            const int idx = (int)threadIdx.x + 256 * (i0 + u);
+            const int ln = idx & 63, st_ = idx >> 6;
+            const int m = 16 * (st_ & 1) + (ln & 15), k = 4 * (st_ >> 1) + (ln >> 4);
+            const bool ok = i0 + u < 2 * KSWp && m < a.M && k < a.K;
+            wv[u] = and_mask(ld<T>((const T *)a.w, ok ? (size_t)m * a.sAm + (size_t)k * a.sAk : 0),
+                             ok ? 0xffffffffu : 0u);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 6; ++u)
+            if (i0 + u < 2 * KSWp)
+                wl[(int)threadIdx.x + 256 * (i0 + u)] = wv[u];
     }
     if (PRO == PRO_NONE)
         __syncthreads();
