@@ -22,6 +22,11 @@ SMALL = {
     "k3s1_ragged": _shape(),
     "k5s1": _shape(k=5, H=14, W=14, Cin=16, Cexp=40, Cout=16),
     "k3s2": _shape(stride=2, residual=False, Cout=12, H=16, W=16),
+    # expansion-conv backward in one pass (narrow input <= 32 channels, HW % 4 == 0): full tiles on
+    # both sides with eight wavefronts and 32-pixel chunks that straddle images; and a ragged case
+    # (5 and 100 channels: a wavefront without weight-gradient work, a last chunk of 12 pixels)
+    "fused_bwd_full": _shape(N=3, Cin=32, Cexp=256, Cse=8, Cout=32, H=6, W=6),
+    "fused_bwd_ragged": _shape(N=5, Cin=5, Cexp=100, Cse=4, Cout=5, H=6, W=10),
     "k5s2_odd": _shape(k=5, stride=2, residual=False, Cout=20, H=15, W=13),
     "noexpand": _shape(Cin=24, Cexp=24, Cout=16, has_expand=False, residual=False, H=20, W=20),
     "noexpand_res": _shape(Cin=16, Cexp=16, Cout=16, has_expand=False, residual=True, k=5),
@@ -63,6 +68,20 @@ def test_store_policy_matches_oracle(name):
     tol = TOL[s.dtype]["fwd"]
     assert rel_err(blk.saved_tensor("a1"), f.tape["a1"]) <= tol
     assert rel_err(blk.saved_tensor("sc"), f.tape["sc"]) <= tol
+
+
+def test_bn_finalised_by_consumer_with_many_partials():
+    """BN3's statistics are finalised inside the final elementwise pass for planes of 1024
+    elements or more.  With the STORE policy the projection conv leaves one partial sum per
+    128 pixels: 48*56*56/128 = 1176 per channel, more than the 4*256 a thread group of that
+    kernel takes in its first round, so the loop over further rounds runs too; BN1 goes through
+    the separate finalise launch here (STORE), BN3's running statistics through the fused one."""
+    s = _shape(N=48, Cin=8, Cexp=16, Cse=4, Cout=8, H=56, W=56)
+    t = make_block_inputs(s, seed=21)
+    print(f"[parity/bn-consumer] {s}", flush=True)
+    res, blk = run_gpu_block(s, t, policy=1)
+    f, b = orc.mbconv_step(s, t)
+    compare_block(s, t, res, f, b, blk)
 
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3])
