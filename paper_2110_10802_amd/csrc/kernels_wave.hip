@@ -42,6 +42,22 @@ __device__ __forceinline__ void load4<bf16_t>(const bf16_t *p, size_t i, float (
     v[3] = bf16_bits_to_float(t.y >> 16);
 }
 
+template <typename T>
+__device__ __forceinline__ void store4(T *p, size_t i, const float (&v)[4]);
+template <>
+__device__ __forceinline__ void store4<float>(float *p, size_t i, const float (&v)[4])
+{
+    *reinterpret_cast<float4v *>(p + i) = (float4v){v[0], v[1], v[2], v[3]};
+}
+template <>
+__device__ __forceinline__ void store4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
+{
+    uint2 t;
+    t.x = bf16_pack2(v[0], v[1]);
+    t.y = bf16_pack2(v[2], v[3]);
+    *reinterpret_cast<uint2 *>(&p[i]) = t;
+}
+
 // ---- wgrad_cl ------------------------------------------------------------------------------------
 // dW[a][b] = sum_{n,pix} U[n,a,pix] * V[n,b,pix], Ma <= 32*MTA (MTA <= 2, the narrow side),
 // Mb <= 256 (one wavefront per 32 channels of the wide side).  Output element (a,b) is
@@ -58,6 +74,11 @@ struct WgradClArgs {
     const float *vc0, *vc1, *vc2, *vgate;
     int sOa, sOb;
     float *partial;
+    // wgrad_lt with its data-gradient option (narrow -> wide convolution, U = gradient at the
+    // narrow output, V = the convolution's wide input): dgw[a*Mb + b] are the weights, the
+    // gradient with respect to V's tensor, sum_a dgw[a][b] * U[a][pix], goes to dgout [N,Mb,HW]
+    const void *dgw;
+    void *dgout;
 };
 
 // Loads this lane's channel `c` of an operand for pixels [q, q+4) and applies its prologue.
@@ -229,15 +250,24 @@ __device__ __forceinline__ void lt_prologue(float (&v)[4], const float (&raw)[4]
     }
 }
 
-template <typename T, int MTA, int PROU, int PROV>
-__global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
+// DG (the projection conv's backward in one kernel): the same pass also produces the gradient
+// with respect to the wide operand's tensor, G[b][pix] = sum_a W[a][b] * U[a][pix].  Every
+// wavefront owns its 32 wide channels, so nothing crosses wavefronts: MFMA with A = W^T (an LDS
+// table in operand order) and B = the parked U tile read pixel-lane; the 32x32 result is turned
+// row-wise through the wavefront's own V tile (which its weight-gradient reads have left by
+// then: LDS operations of a wavefront execute in order, no barrier) and stored 16 bytes per lane.
+template <typename T, int MTA, int PROU, int PROV, bool DG>
+__global__ __launch_bounds__(512, DG ? 4 : 1) void wgrad_lt_kernel(WgradClArgs a)
 {
+    static_assert(!DG || MTA == 1, "the data-gradient option takes one narrow tile");
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63;
     const int t = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform
     const int h = lane >> 5, c = lane & 31;
     float *Us = lds;                                             // [2][32*MTA][pitch]
     float *Vs = lds + 2 * 32 * MTA * kLtPitch + t * 32 * kLtPitch; // this wave's [32][pitch]
+    // DG: this wave's [16 steps][64 lanes] of W^T, behind all the tiles
+    float *Wl = lds + (2 * 32 * MTA + 32 * (blockDim.x >> 6)) * kLtPitch + t * 16 * 64;
 
     // V tile, row-wise: this lane loads pixels [vcol, vcol+4) of rows lane/8 + 8i, i = 0..3
     const int vcol = 4 * (lane & 7);
@@ -287,7 +317,26 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
     // 128-byte pieces of every channel row instead of pieces chunksPerWg*128 bytes apart.
     const int cBeg = blockIdx.x, cStep = gridDim.x, cEnd = a.numChunks;
 
+    if (DG) {
+        // lane (h, c), step kk holds W[a = 2kk + h][b = 32t + c], zero outside the matrix; all
+        // sixteen loads issued before the first store
+        float wreg[16];
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const int aa = 2 * kk + h, bb = 32 * t + c;
+            const bool ok = aa < a.Ma && bb < a.Mb;
+            wreg[kk] = and_mask(ld<T>((const T *)a.dgw, ok ? (size_t)aa * a.Mb + bb : 0),
+                                ok ? 0xffffffffu : 0u);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk)
+            Wl[kk * 64 + lane] = wreg[kk]; // read back by this wavefront only
+    }
+    const int kdg = (a.Ma + 1) >> 1; // contraction steps of the data gradient
+
     float vv[4][4], vr[4][4], vg[4], uu[MTA][4], ur[MTA][4], ug[MTA];
+    size_t vbase_cur = 0; // DG: where this lane's rows of the current chunk start
     bool pok = true; // this lane's four pixels exist (false only in a ragged last chunk)
     auto fetch = [&](int ch) {
         const uint32_t q = (uint32_t)ch * 32u + (uint32_t)vcol;
@@ -297,6 +346,7 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
         const uint32_t pix = qs - n * (uint32_t)a.HW;
         // (one 64-bit multiply-add per chunk and an addition per load)
         const size_t vbase = (size_t)n * vimg + pix;
+        vbase_cur = vbase;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const size_t idx = vbase + vro[i];
@@ -345,6 +395,8 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
                 *reinterpret_cast<float4v *>(Ub + (32 * ta + urow) * kLtPitch + vcol) = w4;
             }
         }
+        const size_t gbase = vbase_cur;
+        const bool gok = pok;
         if (decltype(more)::value)
             fetch(ch + cStep); // in flight while this chunk is multiplied
         __syncthreads();
@@ -359,6 +411,38 @@ __global__ __launch_bounds__(512) void wgrad_lt_kernel(WgradClArgs a)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     acc[ta] = __builtin_amdgcn_mfma_f32_32x32x2f32(avv[r], bvv[r], acc[ta], 0, 0, 0);
+            }
+        }
+        if (DG) {
+            // pixel-lane reads of the U tile: lane (h, c) takes U[2kk + h][pixel c]
+            float16v accd = (float16v){0};
+            int kk = 0;
+            for (; kk + 4 <= kdg; kk += 4) {
+                float dv[4], wv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    dv[u] = Ub[(2 * (kk + u) + h) * kLtPitch + c];
+                    wv[u] = Wl[(kk + u) * 64 + lane];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    accd = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[u], dv[u], accd, 0, 0, 0);
+            }
+            for (; kk < kdg; ++kk)
+                accd = __builtin_amdgcn_mfma_f32_32x32x2f32(Wl[kk * 64 + lane], Ub[(2 * kk + h) * kLtPitch + c],
+                                                            accd, 0, 0, 0);
+            // accumulator register q holds channel row 8*(q/4) + 4h + q%4, pixel c
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                Vs[(8 * (q >> 2) + 4 * h + (q & 3)) * kLtPitch + c] = accd[q];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = (lane >> 3) + 8 * i;
+                const float4v g4 = *reinterpret_cast<const float4v *>(Vs + row * kLtPitch + vcol);
+                if (gok && 32 * t + row < a.Mb) {
+                    const float o[4] = {g4[0], g4[1], g4[2], g4[3]};
+                    store4<T>((T *)a.dgout, gbase + vro[i], o);
+                }
             }
         }
     };
@@ -405,22 +489,6 @@ struct Bwd1x1Args {
     void *dx;      // [N][Ma][HW]
     const void *res; // optional, added to dx
 };
-
-template <typename T>
-__device__ __forceinline__ void store4(T *p, size_t i, const float (&v)[4]);
-template <>
-__device__ __forceinline__ void store4<float>(float *p, size_t i, const float (&v)[4])
-{
-    *reinterpret_cast<float4v *>(p + i) = (float4v){v[0], v[1], v[2], v[3]};
-}
-template <>
-__device__ __forceinline__ void store4<bf16_t>(bf16_t *p, size_t i, const float (&v)[4])
-{
-    uint2 t;
-    t.x = bf16_pack2(v[0], v[1]);
-    t.y = bf16_pack2(v[2], v[3]);
-    *reinterpret_cast<uint2 *>(&p[i]) = t;
-}
 
 template <typename T, int MTA>
 __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
@@ -689,7 +757,7 @@ static hipError_t wgrad_cl_dispatch(const WgradClArgs &a, int mta, int pu, int p
 #define MBK_CASE(MTA, PU, PV)                                                                     \
     if (mta == MTA && pu == PU && pv == PV) {                                                     \
         const size_t lds = sizeof(float) * kLtPitch * 32 * (2 * MTA + block.x / 64);              \
-        hipLaunchKernelGGL((wgrad_lt_kernel<T, MTA, PU, PV>), grid, block, lds, st, a);           \
+        hipLaunchKernelGGL((wgrad_lt_kernel<T, MTA, PU, PV, false>), grid, block, lds, st, a);    \
         return hipGetLastError();                                                                 \
     }
     MBK_CASE(1, PRO_BNBWD, PRO_NONE)
@@ -743,6 +811,68 @@ hipError_t launch_wgrad_cl(bool bf16, int N, int Ma, int Mb, int HW, const Opera
     dim3 grid((unsigned)splits), block((unsigned)(64 * (mtb < 4 ? 4 : mtb))); // >= 256 threads stage U
     return bf16 ? wgrad_cl_dispatch<bf16_t>(a, mta, u.pro, v.pro, grid, block, st)
                 : wgrad_cl_dispatch<float>(a, mta, u.pro, v.pro, grid, block, st);
+}
+
+bool projbwd_fused_plan(int N, int Cw, int Cn, int HW, int *splits)
+{
+    bool swap;
+    return Cn <= 32 && Cn < Cw && wgrad_cl_plan(Cn, Cw, N, HW, &swap, splits) && !swap;
+}
+
+hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &dp,
+                                const Operand &sc, const void *w, void *G, float *partial,
+                                int *splits_out, hipStream_t st)
+{
+    int splits;
+    if (!projbwd_fused_plan(N, Cw, Cn, HW, &splits) || dp.pro != PRO_BNBWD ||
+        (sc.pro != PRO_BNSWISH_GATE && sc.pro != PRO_NONE))
+        return hipErrorInvalidValue;
+    WgradClArgs a = {};
+    a.N = N;
+    a.Ma = Cn;
+    a.Mb = Cw;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    a.numChunks = (int)((a.Q + 31u) / 32u);
+    a.chunksPerWg = (a.numChunks + splits - 1) / splits;
+    a.divHW = make_div((uint32_t)HW);
+    a.u0 = dp.p0;
+    a.u1 = dp.p1;
+    a.uc0 = dp.c0;
+    a.uc1 = dp.c1;
+    a.uc2 = dp.c2;
+    a.v0 = sc.p0;
+    a.vc0 = sc.c0;
+    a.vc1 = sc.c1;
+    a.vgate = sc.gate;
+    a.sOa = Cw; // dW is [Cn][Cw] row-major
+    a.sOb = 1;
+    a.partial = partial;
+    a.dgw = w;
+    a.dgout = G;
+    *splits_out = splits;
+    const int mtb = (Cw + 31) / 32, nw = mtb < 4 ? 4 : mtb;
+    const size_t lds = sizeof(float) * ((size_t)kLtPitch * 32 * (2 + nw) + (size_t)nw * 16 * 64);
+    dim3 grid((unsigned)splits), block((unsigned)(64 * nw));
+#define MBK_CASE(T, PV)                                                                           \
+    {                                                                                             \
+        auto kern = wgrad_lt_kernel<T, 1, PRO_BNBWD, PV, true>;                                   \
+        hipError_t e = hipFuncSetAttribute((const void *)kern,                                    \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        if (e != hipSuccess)                                                                      \
+            return e;                                                                             \
+        hipLaunchKernelGGL(kern, grid, block, lds, st, a);                                        \
+        return hipGetLastError();                                                                 \
+    }
+    if (bf16) {
+        if (sc.pro == PRO_NONE)
+            MBK_CASE(bf16_t, PRO_NONE)
+        MBK_CASE(bf16_t, PRO_BNSWISH_GATE)
+    }
+    if (sc.pro == PRO_NONE)
+        MBK_CASE(float, PRO_NONE)
+    MBK_CASE(float, PRO_BNSWISH_GATE)
+#undef MBK_CASE
 }
 
 bool bwd1x1_fused_plan(int N, int Cw, int Cn, int HW, int *splits)

@@ -412,8 +412,6 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
     dp.c1 = coef3 + P.Cout;
     dp.c2 = coef3 + 2 * P.Cout;
     dp.pro = PRO_BNBWD;
-    MBK_STEP(MBCONV_STEP_PROJ_DGRAD, launch_conv1x1(bf, P.N, P.Cexp, P.Cout, P.HWo, prm->w_proj, 1, P.Cexp, dp, G, EPI_NONE,
-                           nullptr, nullptr, nullptr, nullptr, wg, st));
     {
         Operand sc;
         if (P.store) {
@@ -428,9 +426,23 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
         }
         // with an expansion conv, the sum over this weight gradient's splits waits for the
         // other's and shares its launch (the partials then live in a region of their own)
-        MBK_STEP(MBCONV_STEP_PROJ_WGRAD,
-                 launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, P.expand ? at<float>(scratch, P.o_wg2) : wg,
-                                 gr->w_proj, P.expand ? &proj_reduce : nullptr, st));
+        float *pwg = P.expand ? at<float>(scratch, P.o_wg2) : wg;
+        int psplits = 0;
+        if (projbwd_fused_plan(P.N, P.Cexp, P.Cout, P.HWo, &psplits)) {
+            // one kernel for both gradients (its launch is the PROJ_DGRAD step)
+            MBK_STEP(MBCONV_STEP_PROJ_DGRAD, launch_projbwd_fused(bf, P.N, P.Cexp, P.Cout, P.HWo, dp, sc, prm->w_proj,
+                                                                  G, pwg, &psplits, st));
+            proj_reduce = {pwg, psplits, (size_t)P.Cout * P.Cexp, gr->w_proj};
+            if (!P.expand)
+                MBK_STEP(MBCONV_STEP_PROJ_WGRAD,
+                         launch_reduce_splits2(proj_reduce, {nullptr, 0, 0, nullptr}, st));
+        } else {
+            MBK_STEP(MBCONV_STEP_PROJ_DGRAD, launch_conv1x1(bf, P.N, P.Cexp, P.Cout, P.HWo, prm->w_proj, 1, P.Cexp, dp,
+                                                            G, EPI_NONE, nullptr, nullptr, nullptr, nullptr, wg, st));
+            MBK_STEP(MBCONV_STEP_PROJ_WGRAD,
+                     launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, pwg, gr->w_proj,
+                                     P.expand ? &proj_reduce : nullptr, st));
+        }
     }
     // SE backward and BN2 backward reductions
     float *dg = at<float>(scratch, P.o_dg), *A1 = at<float>(scratch, P.o_A1);

@@ -74,6 +74,13 @@ hipError_t launch_reduce_splits2(const SplitReduce &a, const SplitReduce &b, hip
 // bwd1x1_fused_plan tells whether the shape is covered (Cn <= 32, Cn < Cw <= 256, HW % 4 == 0) and
 // how many splits of dW land in `partial` ([splits][Cw*Cn] floats, the count wgrad_splits gives);
 // the caller sums them (launch_reduce_splits2).
+// The mirror image for a convolution from Cw (wide) to Cn (narrow) channels, whose input sc is a
+// PRO_BNSWISH_GATE or PRO_NONE operand [N,Cw,HW] and whose output gradient dp is PRO_BNBWD [N,Cn,HW]:
+//   G[n,c,q] = sum_j w[j*Cw+c] * dp[n,j,q],   dW[j][c] = sum_{n,q} dp[n,j,q] * sc[n,c,q]
+bool projbwd_fused_plan(int N, int Cw, int Cn, int HW, int *splits);
+hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &dp,
+                                const Operand &sc, const void *w, void *G, float *partial,
+                                int *splits_out, hipStream_t st);
 bool bwd1x1_fused_plan(int N, int Cw, int Cn, int HW, int *splits);
 hipError_t launch_bwd1x1_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &de,
                                const void *xin, const void *w, void *dx, const void *res,
