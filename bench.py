@@ -45,13 +45,23 @@ def algorithmic_bytes(s, step: str):
     D = s.N * s.Cexp * s.Ho * s.Wo
     P = s.N * s.Cout * s.Ho * s.Wo
     res = P if s.residual else 0
+    # shapes for which one kernel computes both gradients of a 1x1 conv (narrow side <= 32
+    # channels, wide side <= 256, plane a multiple of four): the step named *_dgrad is that kernel
+    fused_proj = s.Cout <= 32 and s.Cout < s.Cexp <= 256 and (s.Ho * s.Wo) % 4 == 0
+    fused_exp = s.has_expand and s.Cin <= 32 and s.Cin < s.Cexp <= 256 and (s.H * s.W) % 4 == 0
     table = {
         "expand_conv": X + E, "dw_fwd": E + D, "se_pool": D, "proj_conv": D + P,
-        "bn3_apply": 2 * P + res, "bn3_bwd_reduce": 2 * P, "proj_dgrad": 2 * P + D,
+        "bn3_apply": 2 * P + res, "bn3_bwd_reduce": 2 * P,
+        "proj_dgrad": 2 * P + 2 * D if fused_proj else 2 * P + D,
         "proj_wgrad": 2 * P + D, "gate_sums": 2 * D,
         "dw_bwd": (2 * D + 2 * E) if s.has_expand else (2 * D + 2 * X + res),
-        "expand_dgrad": 2 * E + X + res, "expand_wgrad": 2 * E + X,
+        "expand_dgrad": 2 * E + 2 * X + res if fused_exp else 2 * E + X + res,
+        "expand_wgrad": 2 * E + X,
     }
+    if fused_proj:
+        del table["proj_wgrad"]  # what is left of the step is the sum over the splits
+    if fused_exp:
+        del table["expand_wgrad"]
     return table[step] * b if step in table else None
 
 
