@@ -258,15 +258,19 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_bwd_kernel(Dw4Args 
     const int H = a.H, W = a.W, WP = a.WP, C = a.C;
     const int tileElems = (H + 2 * P) * WP;
     const int lt = threadIdx.x % TPP;
-    float *a1t = lds + (threadIdx.x / TPP) * (2 * tileElems);
-    float *ddt = a1t + tileElems;
-    float *red = lds + PPB * 2 * tileElems;
+    // Only dd lives in LDS.  The filter gradient dW[u][v] = sum_p dd[p] * a1[p + (u,v) - P] is
+    // summed over q = p + (u,v) - P instead: sum_q a1[q] * dd[q - (u,v) + P], which pairs each
+    // thread's own a1 values (registers) with exactly the dd window elements the input gradient
+    // reads anyway; the zero border of the dd tile supplies the out-of-plane terms.  (An a1 tile
+    // would double the LDS footprint and the window reads.)
+    float *ddt = lds + (threadIdx.x / TPP) * tileElems;
+    float *red = lds + PPB * tileElems;
     size_t plane;
     int n, c;
     const bool active = plane_of<TPP>(a, plane, n, c);
 
     float wt[K * K];
-    float rawk[NG][4], sgk[NG][4]; // e and sigmoid(y1) of the runs this thread staged
+    float rawk[NG][4], sgk[NG][4]; // e (and sigmoid(y1) with an expansion) of the runs this thread staged
     float mean1 = 0.f, rstd1 = 0.f, scale1 = 1.f, shift1 = 0.f;
     if (active) {
 #pragma unroll
@@ -281,7 +285,6 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_bwd_kernel(Dw4Args 
         const float scale2 = a.bn2[c], shift2 = a.bn2[C + c];
         const float c0 = a.coef2[c], c1 = a.coef2[C + c], c2 = a.coef2[2 * C + c];
         const float gate = a.g[plane], dzs = a.dzs[plane];
-        zero_border<P, TPP>(a1t, H, W, WP, lt);
         zero_border<P, TPP>(ddt, H, W, WP, lt);
         const size_t base = plane * (size_t)H * W;
         float evA[NG][4], GvA[NG][4], dvA[NG][4]; // all loads first (see the forward kernel)
@@ -300,29 +303,21 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_bwd_kernel(Dw4Args 
             if (gidx < a.groups) {
                 const int h = (int)fdiv((uint32_t)gidx, a.divW4);
                 const int w = 4 * (gidx - h * (W >> 2));
-                float av[4], ddv[4];
+                float ddv[4];
                 const float(&ev)[4] = evA[i];
                 const float(&Gv)[4] = GvA[i];
                 const float(&dv)[4] = dvA[i];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    if (EXPAND) {
-                        const float y = fmaf(ev[r], scale1, shift1);
-                        const float sg = act_aux(y);
-                        rawk[i][r] = ev[r];
-                        sgk[i][r] = sg;
-                        av[r] = act_val(y, sg);
-                    } else {
-                        av[r] = ev[r];
-                    }
+                    rawk[i][r] = ev[r];
+                    if (EXPAND)
+                        sgk[i][r] = act_aux(fmaf(ev[r], scale1, shift1));
                     const float y2 = fmaf(dv[r], scale2, shift2);
                     const float s2 = act_aux(y2);
                     const float grad2 = act_grad(y2, s2);
                     const float dy2 = fmaf(Gv[r], gate, dzs) * grad2;
                     ddv[r] = fmaf(c0, dy2, fmaf(c1, dv[r], c2));
                 }
-                float4v t4 = {av[0], av[1], av[2], av[3]};
-                *reinterpret_cast<float4v *>(a1t + (h + P) * WP + 4 + w) = t4;
                 float4v u4 = {ddv[0], ddv[1], ddv[2], ddv[3]};
                 *reinterpret_cast<float4v *>(ddt + (h + P) * WP + 4 + w) = u4;
             }
@@ -343,41 +338,34 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_bwd_kernel(Dw4Args 
                 const int h = (int)fdiv((uint32_t)gidx, a.divW4);
                 const int w = 4 * (gidx - h * (W >> 2));
                 float da[4] = {0.f, 0.f, 0.f, 0.f};
-                float ddc[4];
-                // input gradient: da[r] = sum_{u,v} wt[u][v] * ddwin[K-1-u][r+K-1-v]
+                // this thread's a1 values (the depthwise conv's input at its own four pixels)
+                float a1c[4], y1[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    y1[r] = fmaf(rawk[i][r], scale1, shift1);
+                    a1c[r] = EXPAND ? act_val(y1[r], sgk[i][r]) : rawk[i][r];
+                }
+                // input gradient  da[r]     = sum_{u,v} wt[u][v] * ddwin[K-1-u][r+K-1-v]
+                // filter gradient acc[u][v] += sum_r   a1c[r]   * ddwin[K-1-u][r+K-1-v]
 #pragma unroll
                 for (int rr = 0; rr < K; ++rr) {
                     float row[K + 3];
                     read_window_row<K>(ddt, h + rr, WP, w, row);
-                    if (rr == P) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            ddc[r] = row[P + r];
-                    }
                     const int u = K - 1 - rr;
 #pragma unroll
                     for (int v = 0; v < K; ++v)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
+                        for (int r = 0; r < 4; ++r) {
                             da[r] = fmaf(wt[u * K + v], row[r + K - 1 - v], da[r]);
-                }
-                // filter gradient: acc[u][v] += sum_r dd[h][w+r] * a1win[u][r+v]
-#pragma unroll
-                for (int u = 0; u < K; ++u) {
-                    float row[K + 3];
-                    read_window_row<K>(a1t, h + u, WP, w, row);
-#pragma unroll
-                    for (int v = 0; v < K; ++v)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            acc[u * K + v] = fmaf(ddc[r], row[r + v], acc[u * K + v]);
+                            acc[u * K + v] = fmaf(a1c[r], row[r + K - 1 - v], acc[u * K + v]);
+                        }
                 }
                 float o[4];
                 if (EXPAND) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const float raw = rawk[i][r], sg = sgk[i][r];
-                        const float y = fmaf(raw, scale1, shift1);
+                        const float y = y1[r];
                         o[r] = da[r] * act_grad(y, sg);
                         const float sv = as_stored<T>(o[r]);
                         acc[K * K] += sv;
@@ -549,7 +537,7 @@ hipError_t launch_dw4_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st)
     a.psr = h.psr;
     int tpp, ng;
     dw4_shape(a.groups, &tpp, &ng);
-    const size_t lds = dw4_lds(h.s, 2, h.s.k * h.s.k + 2);
+    const size_t lds = dw4_lds(h.s, 1, h.s.k * h.s.k + 2);
     const bool ex = h.bn1 != nullptr;
 #define MBK_GO(T, K)                                                                              \
     return ex ? dw4_bwd_go<T, K, true>(a, tpp, ng, lds, st) : dw4_bwd_go<T, K, false>(a, tpp, ng, lds, st);
