@@ -306,9 +306,11 @@ __global__ __launch_bounds__(256) void dwr_bwd_kernel(DwrArgs a)
     const int tileElems = (H + 2 * P) * WP;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const DwrLane L = dwr_lane(a);
-    // per wavefront: two buffers, each PW tiles of a1 followed by PW tiles of dd
-    float *mine = lds + wave * (4 * a.PW * tileElems);
-    for (int i = lane; i < 4 * a.PW * tileElems / 4; i += 64)
+    // per wavefront: two buffers of PW dd tiles.  There is no a1 tile: the filter gradient
+    // dW[u][v] = sum_p dd[p] * a1[p + (u,v) - P] is summed over q = p + (u,v) - P, which pairs each
+    // lane's own a1 values (registers) with the dd window elements the input gradient reads anyway.
+    float *mine = lds + wave * (2 * a.PW * tileElems);
+    for (int i = lane; i < 2 * a.PW * tileElems / 4; i += 64)
         reinterpret_cast<float4v *>(mine)[i] = float4v{0.f, 0.f, 0.f, 0.f};
 
     float wt[K * K];
@@ -349,13 +351,12 @@ __global__ __launch_bounds__(256) void dwr_bwd_kernel(DwrArgs a)
         acc[t] = 0.f;
     __syncthreads();
     for (int it = 0; it < L.iters; ++it) {
-        float *a1t = mine + ((it & 1) * 2 * a.PW + (L.lane_ok ? L.pw : 0)) * tileElems;
-        float *ddt = a1t + a.PW * tileElems;
+        float *ddt = mine + ((it & 1) * a.PW + (L.lane_ok ? L.pw : 0)) * tileElems;
         const int n = L.n_begin + it * a.PW + L.pw;
         const bool ok = cur_ok;
-        float rawk[4], sgk[4];
+        float rawk[4], sgk[4], a1c[4];
         if (L.lane_ok) {
-            float av[4], ddv[4];
+            float ddv[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const bool m = ok && L.x0 + r < W;
@@ -367,15 +368,13 @@ __global__ __launch_bounds__(256) void dwr_bwd_kernel(DwrArgs a)
                     sgk[r] = sg;
                     v = act_val(y, sg);
                 }
-                av[r] = m ? v : 0.f;
+                a1c[r] = m ? v : 0.f;
                 const float y2 = fmaf(pd[r], scale2, shift2);
                 const float s2 = act_aux(y2);
                 const float grad2 = act_grad(y2, s2);
                 const float dy2 = fmaf(pG[r], pgate, pdzs) * grad2;
                 ddv[r] = m ? fmaf(c0, dy2, fmaf(c1, pd[r], c2)) : 0.f;
             }
-            *reinterpret_cast<float4v *>(a1t + (L.h + P) * WP + 4 + L.x0) =
-                float4v{av[0], av[1], av[2], av[3]};
             *reinterpret_cast<float4v *>(ddt + (L.h + P) * WP + 4 + L.x0) =
                 float4v{ddv[0], ddv[1], ddv[2], ddv[3]};
         }
@@ -384,34 +383,20 @@ __global__ __launch_bounds__(256) void dwr_bwd_kernel(DwrArgs a)
         __syncthreads();
         if (ok) {
             float da[4] = {0.f, 0.f, 0.f, 0.f};
-            float ddc[4];
-            // input gradient: da[r] = sum_{u,v} wt[u][v] * ddwin[K-1-u][r+K-1-v]
+            // input gradient  da[r]     = sum_{u,v} wt[u][v] * ddwin[K-1-u][r+K-1-v]
+            // filter gradient acc[u][v] += sum_r   a1c[r]   * ddwin[K-1-u][r+K-1-v]
 #pragma unroll
             for (int rr = 0; rr < K; ++rr) {
                 float row[K + 3];
                 window_row<K>(ddt, L.h + rr, WP, L.x0, row);
-                if (rr == P) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        ddc[r] = row[P + r];
-                }
                 const int u = K - 1 - rr;
 #pragma unroll
                 for (int v = 0; v < K; ++v)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
+                    for (int r = 0; r < 4; ++r) {
                         da[r] = fmaf(wt[u * K + v], row[r + K - 1 - v], da[r]);
-            }
-            // filter gradient: acc[u][v] += sum_r dd[h][x0+r] * a1win[u][r+v]
-#pragma unroll
-            for (int u = 0; u < K; ++u) {
-                float row[K + 3];
-                window_row<K>(a1t, L.h + u, WP, L.x0, row);
-#pragma unroll
-                for (int v = 0; v < K; ++v)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        acc[u * K + v] = fmaf(ddc[r], row[r + v], acc[u * K + v]);
+                        acc[u * K + v] = fmaf(a1c[r], row[r + K - 1 - v], acc[u * K + v]);
+                    }
             }
             const size_t base = ((size_t)n * C + L.c) * hw + off;
             float o[4];
@@ -567,7 +552,7 @@ hipError_t launch_dwr_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st)
     a.psb = h.psb;
     a.psr = h.psr;
     const DwShape &s = h.s;
-    const size_t lds = dwr_lds(a, s.k, 2);
+    const size_t lds = dwr_lds(a, s.k, 1);
     const bool ex = h.bn1 != nullptr;
     const int gv = s.W % 4 == 0 ? 4 : (s.W % 2 == 0 ? 2 : 1);
     if (bf16) {
