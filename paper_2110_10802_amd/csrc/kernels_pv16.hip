@@ -484,12 +484,15 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
 
 // ---- dispatch ---------------------------------------------------------------------------------
 
-// At most 1024 workgroups, each taking the same number of tiles (up to rounding).
-static int pv_grid(int numTiles)
+// At most `cap` workgroups, each taking the same number of tiles (up to rounding): 1024 for
+// conv_pr, 512 for conv_pe (measured on the 24 -> 144 channel, 100 k pixel layer: 392 workgroups
+// of four tiles 23.4 us; 784 of two 24.5; 523 of three 26.3; 314 of five 26.4; 262 of six 28).
+static int pv_grid(int numTiles, int kind)
 {
-    if (numTiles <= 1024)
+    const int cap = kind == 1 ? 512 : 1024;
+    if (numTiles <= cap)
         return numTiles < 1 ? 1 : numTiles;
-    const int per = (numTiles + 1023) / 1024;
+    const int per = (numTiles + cap - 1) / cap;
     return (numTiles + per - 1) / per;
 }
 
@@ -524,8 +527,7 @@ int wave_conv_kind(int M, int K, int HW)
 
 int wave_conv_num_partials(int kind, int N, int HW)
 {
-    (void)kind;
-    return pv_grid((int)(((long long)N * HW + 63) / 64));
+    return pv_grid((int)(((long long)N * HW + 63) / 64), kind);
 }
 
 template <typename T, int PRO, int EPI>
@@ -626,7 +628,7 @@ hipError_t launch_wave_conv1x1(bool bf16, int kind, int N, int M, int K, int HW,
     a.res = res;
     a.psum = psum;
     a.psq = psq;
-    const int grid = pv_grid(a.numTiles);
+    const int grid = pv_grid(a.numTiles, kind);
     a.NP = grid;
     return bf16 ? pv_dispatch<bf16_t>(a, kind, B.pro, epi, grid, st)
                 : pv_dispatch<float>(a, kind, B.pro, epi, grid, st);
