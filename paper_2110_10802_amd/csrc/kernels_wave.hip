@@ -79,6 +79,7 @@ struct WgradClArgs {
     // gradient with respect to V's tensor, sum_a dgw[a][b] * U[a][pix], goes to dgout [N,Mb,HW]
     const void *dgw;
     void *dgout;
+    int dgtiles[8]; // bit tt of dgtiles[t]: wavefront t computes the data gradient of wide tile tt
 };
 
 // Loads this lane's channel `c` of an operand for pixels [q, q+4) and applies its prologue.
@@ -251,11 +252,14 @@ __device__ __forceinline__ void lt_prologue(float (&v)[4], const float (&raw)[4]
 }
 
 // DG (the projection conv's backward in one kernel): the same pass also produces the gradient
-// with respect to the wide operand's tensor, G[b][pix] = sum_a W[a][b] * U[a][pix].  Every
-// wavefront owns its 32 wide channels, so nothing crosses wavefronts: MFMA with A = W^T (an LDS
-// table in operand order) and B = the parked U tile read pixel-lane; the 32x32 result is turned
-// row-wise through the wavefront's own V tile (which its weight-gradient reads have left by
-// then: LDS operations of a wavefront execute in order, no barrier) and stored 16 bytes per lane.
+// with respect to the wide operand's tensor, G[b][pix] = sum_a W[a][b] * U[a][pix].  A 32-channel
+// tile of G needs only W^T (an LDS table in MFMA operand order, A) and the parked U tile read
+// pixel-lane (B), so any wavefront can compute any tile and nothing is added across wavefronts.
+// The tiles are dealt out by the host so that the four SIMDs, which the wavefronts of a
+// workgroup occupy in turn, get equal MFMA counts (with five wavefronts the SIMD that hosts two of
+// them would otherwise carry twice the load of the others and set the pace).  The 32x32 result is
+// turned row-wise through the wavefront's own V tile (which its weight-gradient reads have left
+// by then: LDS operations of a wavefront execute in order, no barrier) and stored 16 bytes per lane.
 template <typename T, int MTA, int PROU, int PROV, bool DG>
 __global__ __launch_bounds__(512, DG ? 4 : 1) void wgrad_lt_kernel(WgradClArgs a)
 {
@@ -266,8 +270,9 @@ __global__ __launch_bounds__(512, DG ? 4 : 1) void wgrad_lt_kernel(WgradClArgs a
     const int h = lane >> 5, c = lane & 31;
     float *Us = lds;                                             // [2][32*MTA][pitch]
     float *Vs = lds + 2 * 32 * MTA * kLtPitch + t * 32 * kLtPitch; // this wave's [32][pitch]
-    // DG: this wave's [16 steps][64 lanes] of W^T, behind all the tiles
-    float *Wl = lds + (2 * 32 * MTA + 32 * (blockDim.x >> 6)) * kLtPitch + t * 16 * 64;
+    // DG: [tile][16 steps][64 lanes] of W^T, behind all the tiles; each wave fills its own tile's
+    float *WlAll = lds + (2 * 32 * MTA + 32 * (blockDim.x >> 6)) * kLtPitch;
+    float *Wl = WlAll + t * 16 * 64;
 
     // V tile, row-wise: this lane loads pixels [vcol, vcol+4) of rows lane/8 + 8i, i = 0..3
     const int vcol = 4 * (lane & 7);
@@ -331,9 +336,10 @@ __global__ __launch_bounds__(512, DG ? 4 : 1) void wgrad_lt_kernel(WgradClArgs a
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < 16; ++kk)
-            Wl[kk * 64 + lane] = wreg[kk]; // read back by this wavefront only
+            Wl[kk * 64 + lane] = wreg[kk]; // first read after the first chunk's barrier
     }
     const int kdg = (a.Ma + 1) >> 1; // contraction steps of the data gradient
+    const int dgmask = DG ? a.dgtiles[t] : 0; // wave-uniform
 
     float vv[4][4], vr[4][4], vg[4], uu[MTA][4], ur[MTA][4], ug[MTA];
     size_t vbase_cur = 0; // DG: where this lane's rows of the current chunk start
@@ -414,34 +420,39 @@ __global__ __launch_bounds__(512, DG ? 4 : 1) void wgrad_lt_kernel(WgradClArgs a
             }
         }
         if (DG) {
-            // pixel-lane reads of the U tile: lane (h, c) takes U[2kk + h][pixel c]
-            float16v accd = (float16v){0};
-            int kk = 0;
-            for (; kk + 4 <= kdg; kk += 4) {
-                float dv[4], wv[4];
+            for (int tt = 0; (dgmask >> tt) != 0; ++tt) {
+                if (!((dgmask >> tt) & 1))
+                    continue;
+                const float *Wt = WlAll + tt * 16 * 64;
+                // pixel-lane reads of the U tile: lane (h, c) takes U[2kk + h][pixel c]
+                float16v accd = (float16v){0};
+                int kk = 0;
+                for (; kk + 4 <= kdg; kk += 4) {
+                    float dv[4], wv[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    dv[u] = Ub[(2 * (kk + u) + h) * kLtPitch + c];
-                    wv[u] = Wl[(kk + u) * 64 + lane];
+                    for (int u = 0; u < 4; ++u) {
+                        dv[u] = Ub[(2 * (kk + u) + h) * kLtPitch + c];
+                        wv[u] = Wt[(kk + u) * 64 + lane];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        accd = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[u], dv[u], accd, 0, 0, 0);
                 }
+                for (; kk < kdg; ++kk)
+                    accd = __builtin_amdgcn_mfma_f32_32x32x2f32(Wt[kk * 64 + lane],
+                                                                Ub[(2 * kk + h) * kLtPitch + c], accd, 0, 0, 0);
+                // accumulator register q holds channel row 8*(q/4) + 4h + q%4, pixel c
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    accd = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[u], dv[u], accd, 0, 0, 0);
-            }
-            for (; kk < kdg; ++kk)
-                accd = __builtin_amdgcn_mfma_f32_32x32x2f32(Wl[kk * 64 + lane], Ub[(2 * kk + h) * kLtPitch + c],
-                                                            accd, 0, 0, 0);
-            // accumulator register q holds channel row 8*(q/4) + 4h + q%4, pixel c
+                for (int q = 0; q < 16; ++q)
+                    Vs[(8 * (q >> 2) + 4 * h + (q & 3)) * kLtPitch + c] = accd[q];
 #pragma unroll
-            for (int q = 0; q < 16; ++q)
-                Vs[(8 * (q >> 2) + 4 * h + (q & 3)) * kLtPitch + c] = accd[q];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = (lane >> 3) + 8 * i;
-                const float4v g4 = *reinterpret_cast<const float4v *>(Vs + row * kLtPitch + vcol);
-                if (gok && 32 * t + row < a.Mb) {
-                    const float o[4] = {g4[0], g4[1], g4[2], g4[3]};
-                    store4<T>((T *)a.dgout, gbase + vro[i], o);
+                for (int i = 0; i < 4; ++i) {
+                    const int row = (lane >> 3) + 8 * i, ch = 32 * tt + row;
+                    const float4v g4 = *reinterpret_cast<const float4v *>(Vs + row * kLtPitch + vcol);
+                    if (gok && ch < a.Mb) {
+                        const float o[4] = {g4[0], g4[1], g4[2], g4[3]};
+                        store4<T>((T *)a.dgout, gbase + (uint32_t)ch * (uint32_t)a.HW, o);
+                    }
                 }
             }
         }
@@ -853,6 +864,31 @@ hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const 
     *splits_out = splits;
     const int mtb = (Cw + 31) / 32, nw = mtb < 4 ? 4 : mtb;
     const size_t lds = sizeof(float) * ((size_t)kLtPitch * 32 * (2 + nw) + (size_t)nw * 16 * 64);
+    // Deal the data gradient's tiles out to the wavefronts: wavefront t runs on SIMD t % 4 and
+    // already has 16 MFMAs per chunk if it owns a weight-gradient tile; a data-gradient tile is
+    // ceil(Cn/2) more.  Each tile goes to the least loaded wavefront of the least loaded SIMD.
+    {
+        const int cost = (Cn + 1) / 2;
+        int load[4] = {0, 0, 0, 0}, wload[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int t = 0; t < nw; ++t)
+            if (t < mtb) {
+                load[t % 4] += 16;
+                wload[t] = 16;
+            }
+        for (int tt = 0; tt < mtb; ++tt) {
+            int sbest = 0;
+            for (int sd = 1; sd < 4; ++sd)
+                if (load[sd] < load[sbest])
+                    sbest = sd;
+            int tbest = sbest;
+            for (int t = sbest; t < nw; t += 4)
+                if (wload[t] < wload[tbest])
+                    tbest = t;
+            a.dgtiles[tbest] |= 1 << tt;
+            load[sbest] += cost;
+            wload[tbest] += cost;
+        }
+    }
     dim3 grid((unsigned)splits), block((unsigned)(64 * nw));
 #define MBK_CASE(T, PV)                                                                           \
     {                                                                                             \
