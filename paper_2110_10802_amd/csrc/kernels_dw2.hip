@@ -5,12 +5,13 @@
 // owns up to four input runs and one output run.
 //   forward      an output run (4 columns) reads, per filter row, the K+6 consecutive input
 //                columns it touches as two 16-byte LDS reads plus the edge values;
-//   filter grad  the same windows, multiplied by the thread's own four dd values;
 //   input grad   an input pixel only meets the taps u = (h+P) mod 2, v = (x+P) mod 2 (section
 //                "Backpropagation and Data Movement": the transposed stencil).  Inside a run
-//                the column parity is fixed by the position, so the column taps are
-//                compile-time; the row parity is per run and selects the filter rows, with
-//                a zero row standing in for the tap that does not exist.
+//                the column parity is fixed by the position and a thread's runs alternate
+//                between even and odd rows, so both the column and the row taps are
+//                compile-time;
+//   filter grad  summed over the input position: the thread's own a1 values times the dd
+//                elements the input gradient reads (no a1 tile in the backward kernel).
 // Partial sums per (channel, image); no atomics.
 #include "mbconv_dev.h"
 #include "mbconv_launch.h"
@@ -280,6 +281,14 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_fwd_kernel(Dw2Args 
 }
 
 // ---- backward (the fused kernel described in mbconv_launch.h, DwBwdArgs) -----------------------
+// Backward.  Only dd (a quarter of the input plane) lives in LDS.  The filter gradient
+// dW[u][v] = sum_{i,j} dd[i][j] * a1[2i+u-P][2j+v-P] is summed over the input position instead:
+// an input pixel (h, x) meets exactly the taps and the dd elements its input gradient meets
+// (u = (h+P) mod 2 + 2t, v = (x+P) mod 2 + 2s), so each thread multiplies its own a1 values
+// (registers) by the dd elements it reads anyway and no a1 tile exists.  A thread's four input
+// runs alternate between even and odd rows (run i lies in row 2*rp + (i & 1)), which makes the
+// row parity, like the column parity inside a run, a compile-time property: the filter rows
+// and the accumulators a run touches are fixed, nothing is selected at run time.
 template <typename T, int K, int TPP, bool EXPAND, int GVO, int GVI>
 __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args a)
 {
@@ -287,14 +296,13 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
     constexpr int BLOCK = TPP > 256 ? TPP : 256;
     constexpr int PPB = BLOCK / TPP;
     constexpr int NV = K * K + 2;
-    constexpr int NT = (K + 1) / 2; // row taps of the input gradient (one may be the zero row)
+    constexpr int NT = (K + 1) / 2; // row taps of the input gradient
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    const int H = a.H, W = a.W, Ho = a.Ho, Wo = a.Wo, WP = a.WP, WQ = a.WQ, C = a.C;
-    const int a1Elems = (H + 2 * P) * WP, ddElems = (Ho + 2 * PB) * WQ;
+    const int H = a.H, W = a.W, Ho = a.Ho, Wo = a.Wo, WQ = a.WQ, C = a.C;
+    const int ddElems = (Ho + 2 * PB) * WQ;
     const int lt = threadIdx.x % TPP;
-    float *a1t = lds + (threadIdx.x / TPP) * (a1Elems + ddElems);
-    float *ddt = a1t + a1Elems;
-    float *red = lds + PPB * (a1Elems + ddElems);
+    float *ddt = lds + (threadIdx.x / TPP) * ddElems;
+    float *red = lds + PPB * ddElems;
     size_t plane;
     int n, c;
     const bool active = d2_plane<TPP>(a, plane, n, c);
@@ -306,6 +314,20 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
     const bool has_out = lt < a.outRuns;
     const int oi = has_out ? (int)fdiv((uint32_t)lt, a.divWo4) : 0;
     const int oj0 = has_out ? 4 * (lt - oi * a.Wo4) : 0;
+    // input run i of this thread: slot lt + TPP*(i/2) among the runs of the rows of parity i & 1
+    // (H is even: each parity class holds inRuns/2 runs)
+    const int halfRuns = a.inRuns >> 1;
+    int rh[NGI], rx[NGI];
+    bool rok[NGI];
+#pragma unroll
+    for (int i = 0; i < NGI; ++i) {
+        const int slot = lt + TPP * (i >> 1);
+        rok[i] = slot < halfRuns;
+        const int sl = rok[i] ? slot : 0;
+        const int rp = (int)fdiv((uint32_t)sl, a.divW4);
+        rh[i] = 2 * rp + (i & 1);
+        rx[i] = 4 * (sl - rp * a.W4);
+    }
     if (active) {
 #pragma unroll
         for (int t = 0; t < K * K; ++t)
@@ -319,47 +341,24 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
         const float scale2 = a.bn2[c], shift2 = a.bn2[C + c];
         const float c0 = a.coef2[c], c1 = a.coef2[C + c], c2 = a.coef2[2 * C + c];
         const float gate = a.g[plane], dzs = a.dzs[plane];
-        d2_zero_border<TPP>(a1t, H, P, P, 4 * a.W4, WP, lt);
         // the dd tile is small: clear all of it, the interior is written after the barrier
         for (int i = lt; i < ddElems / 4; i += TPP)
             reinterpret_cast<float4v *>(ddt)[i] = float4v{0.f, 0.f, 0.f, 0.f};
         const size_t ebase = plane * (size_t)H * W;
         const size_t dbase = plane * (size_t)Ho * Wo + (size_t)oi * Wo + oj0;
-        float evA[NGI][4], Gv[4], dv[4]; // all loads first (one memory round trip)
+        float Gv[4], dv[4]; // all loads first (one memory round trip)
 #pragma unroll
-        for (int i = 0; i < NGI; ++i) {
-            const int gidx = lt + TPP * i < a.inRuns ? lt + TPP * i : 0;
-            const int h = (int)fdiv((uint32_t)gidx, a.divW4);
-            const int x0 = 4 * (gidx - h * a.W4);
-            d2_in_load<T, GVI>((const T *)a.e, ebase + (size_t)h * W + x0, x0, W, evA[i]);
-        }
+        for (int i = 0; i < NGI; ++i)
+            d2_in_load<T, GVI>((const T *)a.e, ebase + (size_t)rh[i] * W + rx[i], rx[i], W, rawk[i]);
         d2_out_load<T, GVO>((const T *)a.G, dbase, has_out ? oj0 : Wo, Wo, Gv);
         d2_out_load<T, GVO>((const T *)a.d, dbase, has_out ? oj0 : Wo, Wo, dv);
         __builtin_amdgcn_sched_barrier(0);
+        if (EXPAND) {
 #pragma unroll
-        for (int i = 0; i < NGI; ++i) {
-            const int gidx = lt + TPP * i;
-            if (gidx < a.inRuns) {
-                const int h = (int)fdiv((uint32_t)gidx, a.divW4);
-                const int x0 = 4 * (gidx - h * a.W4);
-                float av[4];
+            for (int i = 0; i < NGI; ++i)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (EXPAND) {
-                        const float y = fmaf(evA[i][r], scale1, shift1);
-                        const float sg = act_aux(y);
-                        rawk[i][r] = evA[i][r];
-                        sgk[i][r] = sg;
-                        av[r] = act_val(y, sg);
-                    } else {
-                        av[r] = evA[i][r];
-                    }
-                    if (x0 + r >= W)
-                        av[r] = 0.f; // pad columns of a ragged row stay zero in the tile
-                }
-                *reinterpret_cast<float4v *>(a1t + (h + P) * WP + 4 + x0) =
-                    float4v{av[0], av[1], av[2], av[3]};
-            }
+                for (int r = 0; r < 4; ++r)
+                    sgk[i][r] = act_aux(fmaf(rawk[i][r], scale1, shift1));
         }
         if (has_out) {
 #pragma unroll
@@ -383,56 +382,54 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
     for (int t = 0; t < NV; ++t)
         acc[t] = 0.f;
     if (active) {
-        // filter gradient: acc[u][v] += sum_r dd[i][j0+r] * a1[2i+u-P][2(j0+r)+v-P]
-        if (has_out) {
-#pragma unroll
-            for (int u = 0; u < K; ++u) {
-                float win[K + 6];
-                d2_window<K>(a1t, 2 * oi + u, WP, oj0, win);
-#pragma unroll
-                for (int v = 0; v < K; ++v)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        acc[u * K + v] = fmaf(ddv[r], win[2 * r + v], acc[u * K + v]);
-            }
-        }
-        // input gradient per staged input run
         const size_t ebase = plane * (size_t)H * W;
 #pragma unroll
         for (int i = 0; i < NGI; ++i) {
-            const int gidx = lt + TPP * i;
-            if (gidx < a.inRuns) {
-                const int h = (int)fdiv((uint32_t)gidx, a.divW4);
-                const int x0 = 4 * (gidx - h * a.W4);
-                const int ph = (h + P) & 1;
+            if (rok[i]) {
+                const int h = rh[i], x0 = rx[i];
+                const int ph = ((i & 1) + P) & 1; // (h + P) mod 2, known at compile time after unrolling
                 const int hh = (h + P - ph) >> 1; // row tap t reads dd row hh - t with filter row ph + 2t
                 const int cq = x0 >> 1;
+                // this thread's a1 values at the run (zero in the pad columns of a ragged row)
+                float a1c[4], y1[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    y1[r] = fmaf(rawk[i][r], scale1, shift1);
+                    const float v = EXPAND ? act_val(y1[r], sgk[i][r]) : rawk[i][r];
+                    a1c[r] = x0 + r < W ? v : 0.f;
+                }
                 float da[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    float wr[K];
-#pragma unroll
-                    for (int v = 0; v < K; ++v) {
-                        const float w0 = wt[(2 * t) * K + v];
-                        const float w1 = (2 * t + 1 < K) ? wt[(2 * t + 1) * K + v] : 0.f;
-                        wr[v] = ph ? w1 : w0;
-                    }
-                    const float *q = ddt + (hh - t + PB) * WQ + 4 + cq;
-                    const float2 qm = *reinterpret_cast<const float2 *>(q); // columns cq, cq+1
-                    const float q2 = q[2];
-                    if (K == 3) {
-                        // x even meets v = 1 (column x/2); x odd meets v = 0 ((x+1)/2) and v = 2 ((x-1)/2)
-                        da[0] = fmaf(wr[1], qm.x, da[0]);
-                        da[1] = fmaf(wr[0], qm.y, fmaf(wr[2], qm.x, da[1]));
-                        da[2] = fmaf(wr[1], qm.y, da[2]);
-                        da[3] = fmaf(wr[0], q2, fmaf(wr[2], qm.y, da[3]));
-                    } else {
-                        // x even meets v = 0, 2, 4 (columns x/2+1, x/2, x/2-1); x odd v = 1, 3
-                        const float qn = q[-1];
-                        da[0] = fmaf(wr[0], qm.y, fmaf(wr[2], qm.x, fmaf(wr[4], qn, da[0])));
-                        da[1] = fmaf(wr[1], qm.y, fmaf(wr[3], qm.x, da[1]));
-                        da[2] = fmaf(wr[0], q2, fmaf(wr[2], qm.y, fmaf(wr[4], qm.x, da[2])));
-                        da[3] = fmaf(wr[1], q2, fmaf(wr[3], qm.y, da[3]));
+                    const int u = ph + 2 * t;
+                    if (u < K) { // (the odd parity has one row tap fewer)
+                        const float *wr = &wt[u * K];
+                        float *ar = &acc[u * K];
+                        const float *q = ddt + (hh - t + PB) * WQ + 4 + cq;
+                        const float2 qm = *reinterpret_cast<const float2 *>(q); // columns cq, cq+1
+                        const float q2 = q[2];
+                        if (K == 3) {
+                            // x even meets v = 1 (column x/2); x odd meets v = 0 ((x+1)/2) and v = 2 ((x-1)/2)
+                            da[0] = fmaf(wr[1], qm.x, da[0]);
+                            da[1] = fmaf(wr[0], qm.y, fmaf(wr[2], qm.x, da[1]));
+                            da[2] = fmaf(wr[1], qm.y, da[2]);
+                            da[3] = fmaf(wr[0], q2, fmaf(wr[2], qm.y, da[3]));
+                            ar[1] = fmaf(a1c[0], qm.x, fmaf(a1c[2], qm.y, ar[1]));
+                            ar[0] = fmaf(a1c[1], qm.y, fmaf(a1c[3], q2, ar[0]));
+                            ar[2] = fmaf(a1c[1], qm.x, fmaf(a1c[3], qm.y, ar[2]));
+                        } else {
+                            // x even meets v = 0, 2, 4 (columns x/2+1, x/2, x/2-1); x odd v = 1, 3
+                            const float qn = q[-1];
+                            da[0] = fmaf(wr[0], qm.y, fmaf(wr[2], qm.x, fmaf(wr[4], qn, da[0])));
+                            da[1] = fmaf(wr[1], qm.y, fmaf(wr[3], qm.x, da[1]));
+                            da[2] = fmaf(wr[0], q2, fmaf(wr[2], qm.y, fmaf(wr[4], qm.x, da[2])));
+                            da[3] = fmaf(wr[1], q2, fmaf(wr[3], qm.y, da[3]));
+                            ar[0] = fmaf(a1c[0], qm.y, fmaf(a1c[2], q2, ar[0]));
+                            ar[2] = fmaf(a1c[0], qm.x, fmaf(a1c[2], qm.y, ar[2]));
+                            ar[4] = fmaf(a1c[0], qn, fmaf(a1c[2], qm.x, ar[4]));
+                            ar[1] = fmaf(a1c[1], qm.y, fmaf(a1c[3], q2, ar[1]));
+                            ar[3] = fmaf(a1c[1], qm.x, fmaf(a1c[3], qm.y, ar[3]));
+                        }
                     }
                 }
                 float o[4];
@@ -440,8 +437,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_bwd_kernel(Dw2Args 
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const float raw = rawk[i][r], sg = sgk[i][r];
-                        const float y = fmaf(raw, scale1, shift1);
-                        o[r] = da[r] * act_grad(y, sg);
+                        o[r] = da[r] * act_grad(y1[r], sg);
                         if (x0 + r < W) {
                             const float sv = as_stored<T>(o[r]);
                             acc[K * K] += sv;
@@ -516,9 +512,8 @@ static size_t dw2_lds(const Dw2Args &a, int k, int tpp, bool bwd)
 {
     const int p = (k - 1) / 2;
     const int block = tpp > 256 ? tpp : 256, ppb = block / tpp;
-    size_t per = (size_t)(a.H + 2 * p) * a.WP;
-    if (bwd)
-        per += (size_t)(a.Ho + 2 * kDw2PB) * a.WQ;
+    // forward: the a1 tile; backward: the dd tile only
+    const size_t per = bwd ? (size_t)(a.Ho + 2 * kDw2PB) * a.WQ : (size_t)(a.H + 2 * p) * a.WP;
     const int nv = bwd ? k * k + 2 : 2;
     return sizeof(float) * (ppb * per + (size_t)(block / 64) * nv);
 }
