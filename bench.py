@@ -31,8 +31,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # counters' reading on a plain copy kernel of known size; per launch, keyed by
 # (workload, step).  Filled from the summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/config1_fp32_kernel_stats.md: dw4_bwd fetch 165.9 MiB + write 55.4 MiB
-    ("config1", "dw_bwd"): int((165.9 + 55.4) * 2 ** 20),
+    # profiles/config1_fp32_kernel_stats.md, fetch + write MiB per dispatch of the three kernels
+    # that can come out slowest: dw4_bwd, wgrad_lt<..., DG> (the proj_dgrad step), bwd1x1_lt (the
+    # expand_dgrad step)
+    ("config1", "dw_bwd"): int((165.8 + 55.4) * 2 ** 20),
+    ("config1", "proj_dgrad"): int((73.9 + 61.0) * 2 ** 20),
+    ("config1", "expand_dgrad"): int((128.9 + 15.1) * 2 ** 20),
 }
 
 
