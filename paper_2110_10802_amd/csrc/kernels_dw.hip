@@ -49,6 +49,10 @@ int dw_num_partials(const DwShape &s, bool stores_a1)
 // Threads per plane: a wavefront for planes up to 16x16, a 256-thread workgroup up to
 // 64x64, 1024 threads above.
 static int pick_tpp(int plane_elems) { return plane_elems <= 256 ? 64 : plane_elems <= 4096 ? 256 : 1024; }
+// The plane reductions and the final elementwise pass give a plane of at most 256 elements to
+// 16 lanes (a DPP row): four planes per wavefront share the per-plane overhead (index
+// arithmetic, coefficient loads, the reduction), which is most of the work on 14x14 and 7x7 planes.
+static int pick_tpp_plane(int plane_elems) { return plane_elems <= 256 ? 16 : pick_tpp(plane_elems); }
 
 struct PlaneId {
     bool active;
@@ -680,7 +684,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void bn_apply_kernel(PlaneAr
         return;
     float sc, sh;
     BnFinRegs fr;
-    if (a.fin.psum) {
+    if (TPP >= 64 && a.fin.psum) { // (a 16-lane group never finalises: its planes are small)
         bn_fin_issue<TPP>(a.fin, pl.c, lt, fr);
     } else {
         sc = a.bn[pl.c];
@@ -689,8 +693,10 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void bn_apply_kernel(PlaneAr
     __builtin_amdgcn_sched_barrier(0);
     const auto coefs = [&]() {
         float mu, rs;
-        if (a.fin.psum)
-            bn_fin_finish<TPP>(a.fin, a.C, pl.c, lt, pl.n == 0, redd, fr, sc, sh, mu, rs);
+        if constexpr (TPP >= 64) {
+            if (a.fin.psum)
+                bn_fin_finish<TPP>(a.fin, a.C, pl.c, lt, pl.n == 0, redd, fr, sc, sh, mu, rs);
+        }
     };
     const size_t base = pl.plane * (size_t)a.HW;
     if ((a.HW & 3) == 0) {
@@ -744,7 +750,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void bn_apply_kernel(PlaneAr
 template <typename T, typename OP>
 static hipError_t plane_reduce_launch(const PlaneArgs &a, hipStream_t st)
 {
-    const int tpp = pick_tpp(a.HW);
+    const int tpp = pick_tpp_plane(a.HW);
     const size_t planes = (size_t)a.N * a.C;
 #define MBK_LAUNCH(TPP)                                                                           \
     {                                                                                             \
@@ -753,6 +759,8 @@ static hipError_t plane_reduce_launch(const PlaneArgs &a, hipStream_t st)
         hipLaunchKernelGGL((plane_reduce_kernel<T, TPP, OP>), dim3(grid), dim3(BLOCK), 0, st, a); \
         return hipGetLastError();                                                                 \
     }
+    if (tpp == 16)
+        MBK_LAUNCH(16)
     if (tpp == 64)
         MBK_LAUNCH(64)
     if (tpp == 256)
@@ -816,7 +824,7 @@ hipError_t launch_bn_apply(bool bf16, int N, int C, int HW, const void *p, const
         a.fin = *fin;
     a.out = out;
     a.res = res;
-    const int tpp = pick_tpp(HW);
+    const int tpp = pick_tpp_plane(HW);
     const size_t planes = (size_t)N * C;
 #define MBK_LAUNCH(TPP)                                                                           \
     {                                                                                             \
@@ -828,6 +836,8 @@ hipError_t launch_bn_apply(bool bf16, int N, int C, int HW, const void *p, const
             hipLaunchKernelGGL((bn_apply_kernel<float, TPP>), dim3(grid), dim3(BLOCK), 0, st, a); \
         return hipGetLastError();                                                                 \
     }
+    if (tpp == 16)
+        MBK_LAUNCH(16)
     if (tpp == 64)
         MBK_LAUNCH(64)
     if (tpp == 256)

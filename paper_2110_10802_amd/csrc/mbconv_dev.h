@@ -181,13 +181,19 @@ __device__ __forceinline__ float half_wave_sum(float v)
 }
 
 // Sum of NV per-thread values over a group of TPP consecutive threads of the block
-// (TPP a multiple of 64, groups aligned).  `red` is LDS scratch of at least
+// (TPP = 16 or a multiple of 64, groups aligned).  `red` is LDS scratch of at least
 // (blockDim/64)*NV floats.  The result is valid in every thread of the group whose
 // lane index within the group is < NV... for simplicity it is returned in all threads.
 // All threads of the block must call it (it synchronises the block).
 template <int NV, int TPP>
 __device__ __forceinline__ void group_sum(float (&v)[NV], float *red)
 {
+    if (TPP == 16) { // a DPP row per group: four rotations, no LDS, no cross-lane permute
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            v[i] = row16_sum(v[i]);
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < NV; ++i)
         v[i] = wave_sum(v[i]);
