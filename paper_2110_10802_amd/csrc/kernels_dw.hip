@@ -52,7 +52,10 @@ static int pick_tpp(int plane_elems) { return plane_elems <= 256 ? 64 : plane_el
 // The plane reductions and the final elementwise pass give a plane of at most 256 elements to
 // 16 lanes (a DPP row): four planes per wavefront share the per-plane overhead (index
 // arithmetic, coefficient loads, the reduction), which is most of the work on 14x14 and 7x7 planes.
-static int pick_tpp_plane(int plane_elems) { return plane_elems <= 256 ? 16 : pick_tpp(plane_elems); }
+static int pick_tpp_plane(int plane_elems)
+{
+    return plane_elems <= 256 ? 16 : plane_elems <= 1024 ? 64 : pick_tpp(plane_elems);
+}
 
 struct PlaneId {
     bool active;
