@@ -36,7 +36,8 @@ hipError_t launch_dw2_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st);
 bool dwr_supported(const DwShape &s);
 int dwr_num_partials(const DwShape &s);
 hipError_t launch_dwr_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
-                          const void *w_dw, void *d, float *psum, float *psq, hipStream_t st);
+                          const void *w_dw, void *d, float *psum, float *psq, const BnFin *fin,
+                          hipStream_t st);
 hipError_t launch_dwr_bwd(bool bf16, const DwBwdArgs &h, hipStream_t st);
 
 int dw_num_partials(const DwShape &s, bool stores_a1)
@@ -215,7 +216,11 @@ bool plane_finalize_pays(int HW) { return HW >= 1024; }
 
 bool dw_fwd_finalizes_bn1(const DwShape &s, bool stores_a1)
 {
-    return !stores_a1 && dw4_supported(s) && plane_finalize_pays(s.H * s.W);
+    if (stores_a1)
+        return false;
+    if (dw4_supported(s)) // (launch_dw_fwd's order of preference)
+        return plane_finalize_pays(s.H * s.W);
+    return dwr_supported(s); // a wavefront per channel and image range: once per wavefront
 }
 
 hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
@@ -227,7 +232,7 @@ hipError_t launch_dw_fwd(bool bf16, const DwShape &s, const void *e, const float
     if (!a1_store && dw4_supported(s))
         return launch_dw4_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, fin, st);
     if (!a1_store && dwr_supported(s))
-        return launch_dwr_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
+        return launch_dwr_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, fin, st);
     if (!a1_store && dw2_supported(s))
         return launch_dw2_fwd(bf16, s, e, bn1, w_dw, d, psum, psq, st);
     DwFwdDev a;

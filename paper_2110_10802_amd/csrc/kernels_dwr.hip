@@ -16,6 +16,7 @@
 // are 16, 8 or 4 bytes per lane depending on the divisibility of the width.
 #include "mbconv_dev.h"
 #include "mbconv_launch.h"
+#include "mbconv_bnfin.h"
 
 namespace mbk {
 
@@ -34,6 +35,7 @@ struct DwrArgs {
     const void *w;
     void *d;
     float *psum, *psq;
+    BnFin fin; // forward, fin.psum non-null: bn1 is derived in the kernel from the partial sums
     const void *G;
     const float *g, *dzs, *bn2, *coef2;
     void *dy1_out;
@@ -228,10 +230,19 @@ __global__ __launch_bounds__(256) void dwr_fwd_kernel(DwrArgs a)
 #pragma unroll
     for (int t = 0; t < K * K; ++t)
         wt[t] = ld<T>((const T *)a.w, (size_t)L.c * K * K + t);
+    // BN1's coefficients: fetched, or finalised here from the expansion conv's partial sums.  A
+    // wavefront owns a channel and a range of images, so the finalise step is paid once per
+    // wavefront, not once per plane; the wavefront of the channel's first range stores the block.
     float scale = 1.f, shift = 0.f;
+    BnFinRegs fr;
+    const bool fuse = EXPAND && a.fin.psum != nullptr;
     if (EXPAND) {
-        scale = a.bn1[L.c];
-        shift = a.bn1[a.C + L.c];
+        if (fuse) {
+            bn_fin_issue<64>(a.fin, L.c, lane, fr);
+        } else {
+            scale = a.bn1[L.c];
+            shift = a.bn1[a.C + L.c];
+        }
     }
     const size_t hw = (size_t)H * W;
     const int off = L.h * W + L.x0;
@@ -244,6 +255,10 @@ __global__ __launch_bounds__(256) void dwr_fwd_kernel(DwrArgs a)
         return ok;
     };
     bool cur_ok = prefetch(0);
+    if (fuse) {
+        float mu, rs;
+        bn_fin_finish<64>(a.fin, a.C, L.c, lane, L.wave_ok && L.seg == 0, nullptr, fr, scale, shift, mu, rs);
+    }
     float acc0 = 0.f, acc1 = 0.f;
     __syncthreads();
     for (int it = 0; it < L.iters; ++it) {
@@ -512,9 +527,12 @@ static hipError_t dwr_launch(KERN kern, const DwrArgs &a, size_t lds, hipStream_
     }
 
 hipError_t launch_dwr_fwd(bool bf16, const DwShape &s, const void *e, const float *bn1,
-                          const void *w_dw, void *d, float *psum, float *psq, hipStream_t st)
+                          const void *w_dw, void *d, float *psum, float *psq, const BnFin *fin,
+                          hipStream_t st)
 {
     DwrArgs a = dwr_args(s);
+    if (fin)
+        a.fin = *fin;
     a.e = e;
     a.bn1 = bn1;
     a.w = w_dw;
