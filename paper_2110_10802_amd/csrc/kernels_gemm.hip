@@ -487,9 +487,24 @@ hipError_t launch_reduce_splits2(const SplitReduce &a, const SplitReduce &b, hip
     };
     const bool two = b.count > 0;
     if (wide(a) && (!two || wide(b))) {
-        const unsigned ba = (unsigned)((a.count / 4 + 15) / 16);
-        const unsigned bb = two ? (unsigned)((b.count / 4 + 15) / 16) : 0u;
-        hipLaunchKernelGGL((reduce_splits_kernel<4, 16>), dim3(ba + bb), dim3(1024), 0, st, a, b, ba);
+        // lanes per thread group by the number of partial rows: a group adds every (1024/E)-th row,
+        // so few rows want few, wide groups (with 64 groups and 16 rows three quarters of the
+        // threads would idle)
+        const int S = two ? (a.S < b.S ? a.S : b.S) : a.S;
+#define MBK_GO(E)                                                                                 \
+    {                                                                                             \
+        const unsigned ba = (unsigned)((a.count / 4 + (E)-1) / (E));                              \
+        const unsigned bb = two ? (unsigned)((b.count / 4 + (E)-1) / (E)) : 0u;                   \
+        hipLaunchKernelGGL((reduce_splits_kernel<4, E>), dim3(ba + bb), dim3(1024), 0, st, a, b,  \
+                           ba);                                                                   \
+    }
+        if (S >= 128)
+            MBK_GO(16)
+        else if (S >= 32)
+            MBK_GO(32)
+        else
+            MBK_GO(64)
+#undef MBK_GO
     } else {
         const unsigned ba = (unsigned)((a.count + 31) / 32);
         const unsigned bb = two ? (unsigned)((b.count + 31) / 32) : 0u;
