@@ -606,7 +606,10 @@ __global__ __launch_bounds__(256) void se_bwd_image_wide_kernel(SeBwdArgs a, int
 // dW1[4jq..4jq+3][c]; the batch is walked 32 images at a time through LDS, always in the same
 // order, and the j-contiguous operands are read as one 16-byte LDS access per image.  The
 // per-channel sums (db2, BN2's dbeta/dgamma/coef) are split over the 16 jq groups and combined
-// in a fixed order; workgroup 0 adds db1.
+// in a fixed order.  The three kinds of sums are independent chains of memory round trips and
+// there are far fewer channel tiles than compute units, so each kind has workgroups of its own
+// (blockIdx.y: 0 the weight gradients, 1 the per-channel sums, 2 db1 in one workgroup) and the
+// launch lasts as long as the longest chain, not their sum.
 __global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
 {
     constexpr int TC = 16, TN = 32, JQ = 16; // Cse <= 4*JQ
@@ -617,69 +620,80 @@ __global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
     const int C = a.C, Cse = a.Cse, N = a.N;
     const int tid = threadIdx.x, cl = tid & 15, jq = tid >> 4;
     const int c0 = blockIdx.x * TC, c = c0 + cl;
-    float acc2[4] = {0.f, 0.f, 0.f, 0.f}, acc1[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int n0 = 0; n0 < N; n0 += TN) {
-        __syncthreads();
-        float t0[2], t1[2], t2[8], t3[8]; // all loads of the round in flight together
+    const int role = blockIdx.y;
+    if (role == 0) {
+        float acc2[4] = {0.f, 0.f, 0.f, 0.f}, acc1[4] = {0.f, 0.f, 0.f, 0.f};
+        // A round's loads (all in flight together, clamped addresses and masks instead of branches)
+        // are issued one round ahead: they travel while the previous round is multiplied.
+        float t0[2], t1[2], t2[8], t3[8];
+        const auto fetch = [&](int n0) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int i = tid + 256 * u, nn = i >> 4, cc = i & 15;
-            const bool ok = n0 + nn < N && c0 + cc < C;
-            t0[u] = ok ? a.dt[(size_t)(n0 + nn) * C + c0 + cc] : 0.f;
-            t1[u] = ok ? a.z[(size_t)(n0 + nn) * C + c0 + cc] : 0.f;
-        }
+            for (int u = 0; u < 2; ++u) {
+                const int i = tid + 256 * u, nn = i >> 4, cc = i & 15;
+                const bool ok = n0 + nn < N && c0 + cc < C;
+                const size_t at = ok ? (size_t)(n0 + nn) * C + c0 + cc : 0;
+                t0[u] = and_mask(a.dt[at], ok ? 0xffffffffu : 0u);
+                t1[u] = and_mask(a.z[at], ok ? 0xffffffffu : 0u);
+            }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int i = tid + 256 * u, nn = i >> 6, j = i & 63;
-            const bool ok = n0 + nn < N && j < Cse;
-            t2[u] = ok ? a.q[(size_t)(n0 + nn) * Cse + j] : 0.f;
-            t3[u] = ok ? a.dq[(size_t)(n0 + nn) * Cse + j] : 0.f;
-        }
+            for (int u = 0; u < 8; ++u) {
+                const int i = tid + 256 * u, nn = i >> 6, j = i & 63;
+                const bool ok = n0 + nn < N && j < Cse;
+                const size_t at = ok ? (size_t)(n0 + nn) * Cse + j : 0;
+                t2[u] = and_mask(a.q[at], ok ? 0xffffffffu : 0u);
+                t3[u] = and_mask(a.dq[at], ok ? 0xffffffffu : 0u);
+            }
+        };
+        fetch(0);
+        for (int n0 = 0; n0 < N; n0 += TN) {
+            __syncthreads();
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int i = tid + 256 * u;
-            dtL[i >> 4][i & 15] = t0[u];
-            zL[i >> 4][i & 15] = t1[u];
-        }
+            for (int u = 0; u < 2; ++u) {
+                const int i = tid + 256 * u;
+                dtL[i >> 4][i & 15] = t0[u];
+                zL[i >> 4][i & 15] = t1[u];
+            }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int i = tid + 256 * u;
-            rL[i >> 6][i & 63] = (i & 63) < Cse ? swishf(t2[u]) : 0.f;
-            dqL[i >> 6][i & 63] = t3[u];
-        }
-        __syncthreads();
+            for (int u = 0; u < 8; ++u) {
+                const int i = tid + 256 * u;
+                rL[i >> 6][i & 63] = (i & 63) < Cse ? swishf(t2[u]) : 0.f;
+                dqL[i >> 6][i & 63] = t3[u];
+            }
+            if (n0 + TN < N)
+                fetch(n0 + TN);
+            __syncthreads();
 #pragma unroll 8
-        for (int nn = 0; nn < TN; ++nn) {
-            const float dtv = dtL[nn][cl], zv = zL[nn][cl];
-            const float4 r4 = *reinterpret_cast<const float4 *>(&rL[nn][4 * jq]);
-            const float4 q4 = *reinterpret_cast<const float4 *>(&dqL[nn][4 * jq]);
-            acc2[0] = fmaf(dtv, r4.x, acc2[0]);
-            acc2[1] = fmaf(dtv, r4.y, acc2[1]);
-            acc2[2] = fmaf(dtv, r4.z, acc2[2]);
-            acc2[3] = fmaf(dtv, r4.w, acc2[3]);
-            acc1[0] = fmaf(q4.x, zv, acc1[0]);
-            acc1[1] = fmaf(q4.y, zv, acc1[1]);
-            acc1[2] = fmaf(q4.z, zv, acc1[2]);
-            acc1[3] = fmaf(q4.w, zv, acc1[3]);
-        }
-    }
-    if (c < C) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int j = 4 * jq + u;
-            if (j < Cse) {
-                a.dw2[(size_t)c * Cse + j] = acc2[u];
-                a.dw1[(size_t)j * C + c] = acc1[u];
+            for (int nn = 0; nn < TN; ++nn) {
+                const float dtv = dtL[nn][cl], zv = zL[nn][cl];
+                const float4 r4 = *reinterpret_cast<const float4 *>(&rL[nn][4 * jq]);
+                const float4 q4 = *reinterpret_cast<const float4 *>(&dqL[nn][4 * jq]);
+                acc2[0] = fmaf(dtv, r4.x, acc2[0]);
+                acc2[1] = fmaf(dtv, r4.y, acc2[1]);
+                acc2[2] = fmaf(dtv, r4.z, acc2[2]);
+                acc2[3] = fmaf(dtv, r4.w, acc2[3]);
+                acc1[0] = fmaf(q4.x, zv, acc1[0]);
+                acc1[1] = fmaf(q4.y, zv, acc1[1]);
+                acc1[2] = fmaf(q4.z, zv, acc1[2]);
+                acc1[3] = fmaf(q4.w, zv, acc1[3]);
             }
         }
-    }
-    // per-channel sums: the 16 thread groups take every 16th image, then group 0 adds the
-    // partial sums in order
-    {
+        if (c < C) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = 4 * jq + u;
+                if (j < Cse) {
+                    a.dw2[(size_t)c * Cse + j] = acc2[u];
+                    a.dw1[(size_t)j * C + c] = acc1[u];
+                }
+            }
+        }
+    } else if (role == 1) {
+        // per-channel sums: the 16 thread groups take every 16th image, then group 0 adds the
+        // partial sums in order
         float sb = 0.f;
         double dbeta = 0.0, dgamma = 0.0;
         if (c < C) {
-#pragma unroll 4
+#pragma unroll 8
             for (int n = jq; n < N; n += JQ) {
                 const size_t o = (size_t)n * C + c;
                 const float dtv = a.dt[o], gv = a.g[o], a1 = a.A1[o], a2 = a.A2[o];
@@ -706,16 +720,15 @@ __global__ __launch_bounds__(256) void se_bwd_batch_wide_kernel(SeBwdArgs a)
             a.dgamma2[c] = (float)dgamma;
             bn_bwd_coef(C, c, (double)N * a.HW, dgamma, dbeta, a.gamma2[c], a.bn2, a.coef2);
         }
-    }
-    // db1[j] = sum_n dq[n][j], by workgroup 0: four thread groups take every fourth image (eight
-    // loads in flight each: a plain loop here would pay one memory round trip per image and
-    // make this workgroup the tail of the whole launch), combined in a fixed order
-    if (blockIdx.x == 0) {
+    } else if (blockIdx.x == 0) {
+        // db1[j] = sum_n dq[n][j]: four thread groups take every fourth image (sixteen loads in
+        // flight each: a plain loop would pay one memory round trip per image), combined in a
+        // fixed order
         __shared__ float db1L[4][64];
         const int j = tid & 63, part = tid >> 6;
         float s = 0.f;
         if (j < Cse) {
-#pragma unroll 8
+#pragma unroll 16
             for (int n = part; n < N; n += 4)
                 s += a.dq[(size_t)n * Cse + j];
         }
@@ -736,7 +749,7 @@ hipError_t launch_se_bwd(const SeBwdArgs &a, hipStream_t st)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return e;
-        hipLaunchKernelGGL(se_bwd_batch_wide_kernel, dim3((a.C + 15) / 16), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(se_bwd_batch_wide_kernel, dim3((a.C + 15) / 16, 3), dim3(256), 0, st, a);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(se_bwd_image_kernel, dim3(a.N), dim3(256), sizeof(float) * (a.C + a.Cse), st,
