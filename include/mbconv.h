@@ -189,9 +189,10 @@ typedef enum {
                                       and BN3_APPLY do for planes of 1024 elements or more (DW_FWD:
                                       stride 1, W % 4 == 0, recompute policy) */
     MBCONV_STEP_DW_FWD = 3,        /* BN1 + Swish + depthwise conv + BN2 partial statistics */
-    MBCONV_STEP_BN2_FINALIZE = 4,
+    MBCONV_STEP_BN2_FINALIZE = 4,  /* when no_se, in training: also fills the gate with ones */
     MBCONV_STEP_SE_POOL = 5,       /* BN2 + Swish + plane means; does not occur when no_se */
-    MBCONV_STEP_SE_FC = 6,         /* when no_se: fills the gate with ones */
+    MBCONV_STEP_SE_FC = 6,         /* when no_se: fills the gate with ones in evaluation mode and does not
+                                      occur in training */
     MBCONV_STEP_PROJ_CONV = 7,     /* (BN2 + Swish)*gate + 1x1 projection conv + BN3 partials */
     MBCONV_STEP_BN3_FINALIZE = 8,
     MBCONV_STEP_BN3_APPLY = 9,     /* BN3 (+ residual) */

@@ -23,8 +23,13 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(int C, int NP, double 
                                                           const float *__restrict__ gamma,
                                                           const float *__restrict__ beta, float eps,
                                                           float momentum, float *run_mean,
-                                                          float *run_var, float *bn)
+                                                          float *run_var, float *bn, float *ones,
+                                                          size_t ones_count)
 {
+    // a block without squeeze-and-excitation has its gate buffer set to one here, by the launch
+    // that precedes the gate's first reader anyway
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < ones_count; i += (size_t)gridDim.x * 256)
+        ones[i] = 1.0f;
     const int c = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (c >= C)
         return;
@@ -76,10 +81,11 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(int C, int NP, double 
 
 hipError_t launch_bn_finalize(int C, int NP, double m, const float *psum, const float *psq,
                               const float *gamma, const float *beta, float eps, float momentum,
-                              float *run_mean, float *run_var, float *bn, hipStream_t st)
+                              float *run_mean, float *run_var, float *bn, hipStream_t st,
+                              float *ones, size_t ones_count)
 {
     hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 3) / 4), dim3(256), 0, st, C, NP, m, psum, psq,
-                       gamma, beta, eps, momentum, run_mean, run_var, bn);
+                       gamma, beta, eps, momentum, run_mean, run_var, bn, ones, ones ? ones_count : 0);
     return hipGetLastError();
 }
 

@@ -308,19 +308,21 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
     // BN1 + Swish + depthwise + BN2 statistics
     MBK_STEP(MBCONV_STEP_DW_FWD, launch_dw_fwd(bf, ds, dw_in, bn1, prm->w_dw, d, psum2, psq2, a1_store,
                                                fuse1 ? &fin1 : nullptr, st));
+    // BN2 + Swish + SE squeeze, SE excite
+    float *z = at<float>(saved, P.o_z), *g = at<float>(saved, P.o_g), *q = at<float>(saved, P.o_q);
+    // no squeeze-and-excitation stage: the gate every later prologue multiplies by is one; in
+    // training BN2's finalisation writes it
     if (!eval)
         MBK_STEP(MBCONV_STEP_BN2_FINALIZE, launch_bn_finalize(P.Cexp, P.NPdw, m2, psum2, psq2, prm->bn2_gamma,
                                    prm->bn2_beta, eps, mom, run ? run->bn2_mean : nullptr,
-                                   run ? run->bn2_var : nullptr, bn2, st));
-    // BN2 + Swish + SE squeeze, SE excite
-    float *z = at<float>(saved, P.o_z), *g = at<float>(saved, P.o_g), *q = at<float>(saved, P.o_q);
+                                   run ? run->bn2_var : nullptr, bn2, st, P.se ? nullptr : g,
+                                   (size_t)P.N * P.Cexp));
     if (P.se) {
         MBK_STEP(MBCONV_STEP_SE_POOL, launch_pool(bf, P.N, P.Cexp, P.HWo, d, bn2, z, at<float>(saved, P.o_s3),
                             at<float>(saved, P.o_s4), st));
         MBK_STEP(MBCONV_STEP_SE_FC, launch_se_fwd(P.N, P.Cexp, P.Cse, z, prm->se_w1, prm->se_b1, prm->se_w2, prm->se_b2, q,
                               g, st));
-    } else {
-        // no squeeze-and-excitation stage: the gate every later prologue multiplies by is one
+    } else if (eval) {
         MBK_STEP(MBCONV_STEP_SE_FC, launch_fill(g, 1.0f, (size_t)P.N * P.Cexp, st));
     }
     // projection conv on Swish(BN2(d))*g + BN3 statistics

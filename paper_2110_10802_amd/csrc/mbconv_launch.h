@@ -108,10 +108,12 @@ inline BnFin make_bn_fin(const float *psum, const float *psq, const float *gamma
 }
 
 // psum/psq: [C][NP] partial sums.  Writes bn = {scale[C], shift[C], mean[C], rstd[C]} and
-// updates running statistics (if non-null) with momentum.
+// updates running statistics (if non-null) with momentum.  If ones is non-null the same launch
+// also sets ones[0..ones_count) to 1.
 hipError_t launch_bn_finalize(int C, int NP, double m, const float *psum, const float *psq,
                               const float *gamma, const float *beta, float eps, float momentum,
-                              float *run_mean, float *run_var, float *bn, hipStream_t st);
+                              float *run_mean, float *run_var, float *bn, hipStream_t st,
+                              float *ones = nullptr, size_t ones_count = 0);
 
 // Evaluation mode: the same blocks from running statistics, three normalisations per launch
 // (C1 = 0 skips the first).
