@@ -211,6 +211,7 @@ def run_chain(args) -> int:
         if args.no_survey:
             break
         row = {}
+        prev_reps = None
         for name, sid in B.STEPS.items():
             if not shapes[i].has_expand and name in NO_EXPAND_STEPS:
                 continue
@@ -219,6 +220,9 @@ def run_chain(args) -> int:
                 step(B.Probe(sid, e0, e1), i)
                 torch.cuda.synchronize()
                 reps.append(ev.elapsed_ms(e0, e1))
+            if prev_reps is not None and all(r == prev_reps[-1] for r in reps):
+                continue  # the step did not occur (its events still hold the previous step's last times)
+            prev_reps = reps
             row[name] = sorted(reps)[1]
         survey.append(row)
         s = shapes[i]

@@ -195,7 +195,7 @@ static hipError_t conv1x1_dispatch(const Conv1x1Args &a, int pro, int epi, dim3 
 
 // kernels_wave.hip
 int wave_conv_kind(int M, int K, int HW);
-int wave_conv_num_partials(int kind, int N, int HW);
+int wave_conv_num_partials(int kind, int N, int M, int HW);
 hipError_t launch_wave_conv1x1(bool bf16, int kind, int N, int M, int K, int HW, const void *w,
                                int sAm, int sAk, const Operand &B, void *out, int epi,
                                const void *res, float *psum, float *psq, hipStream_t st);
@@ -227,7 +227,7 @@ int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_ope
 {
     const int kind = stores_operand ? 0 : wave_conv_kind(M, K, HW);
     if (kind)
-        return wave_conv_num_partials(kind, N, HW);
+        return wave_conv_num_partials(kind, N, M, HW);
     int wt, qtiles, splits;
     if (bf16 && !stores_operand && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
         return qtiles;

@@ -486,10 +486,17 @@ __global__ __launch_bounds__(256) void conv_pr_kernel(PvArgs a, int KSWp)
 
 // At most `cap` workgroups, each taking the same number of tiles (up to rounding): 1024 for
 // conv_pr, 512 for conv_pe (measured on the 24 -> 144 channel, 100 k pixel layer: 392 workgroups
-// of four tiles 23.4 us; 784 of two 24.5; 523 of three 26.3; 314 of five 26.4; 262 of six 28).
-static int pv_grid(int numTiles, int kind)
+// of four tiles 23.4 us; 784 of two 24.5; 523 of three 26.3; 314 of five 26.4; 262 of six 28),
+// 1024 and 2048 for conv_pe workgroups of two and of one wavefront (32 -> 16 channels, 803 k
+// pixels: 75 us with 512 workgroups, 65 with 1024, 49 with 1536, 43 with 2048, 44 with 3072;
+// 16 -> 96 channels: 106 us with 256, 85 with 512, 83 with 768, 79 with 1024, 86 with 1536).
+static int pv_grid(int numTiles, int kind, int M)
 {
-    const int cap = kind == 1 ? 512 : 1024;
+    // conv_pe: a workgroup has one wavefront per 48 output channels, so a narrow output gets
+    // more workgroups for the same number of wavefronts
+    const int waves = ((M + 15) / 16 + kPeTT - 1) / kPeTT;
+    const int pe_cap = waves >= 3 ? 512 : 2048 / waves;
+    const int cap = kind == 1 ? pe_cap : 1024;
     if (numTiles <= cap)
         return numTiles < 1 ? 1 : numTiles;
     const int per = (numTiles + cap - 1) / cap;
@@ -525,9 +532,9 @@ int wave_conv_kind(int M, int K, int HW)
     return 0;
 }
 
-int wave_conv_num_partials(int kind, int N, int HW)
+int wave_conv_num_partials(int kind, int N, int M, int HW)
 {
-    return pv_grid((int)(((long long)N * HW + 63) / 64), kind);
+    return pv_grid((int)(((long long)N * HW + 63) / 64), kind, M);
 }
 
 template <typename T, int PRO, int EPI>
@@ -628,7 +635,7 @@ hipError_t launch_wave_conv1x1(bool bf16, int kind, int N, int M, int K, int HW,
     a.res = res;
     a.psum = psum;
     a.psq = psq;
-    const int grid = pv_grid(a.numTiles, kind);
+    const int grid = pv_grid(a.numTiles, kind, M);
     a.NP = grid;
     return bf16 ? pv_dispatch<bf16_t>(a, kind, B.pro, epi, grid, st)
                 : pv_dispatch<float>(a, kind, B.pro, epi, grid, st);
