@@ -84,6 +84,76 @@ def test_bn_finalised_by_consumer_with_many_partials():
     compare_block(s, t, res, f, b, blk)
 
 
+def _random_shapes(count, seed):
+    """Seeded random block shapes, drawn so that every kernel family is reached: ragged and
+    4-divisible planes, the plane sizes of the depthwise variants (56, 28, 14, 7 and a few
+    pixels), narrow and wide channel counts on either side of the 1x1 kernels' switch points,
+    both activations, with and without expansion / SE / residual, both policies.  At least two
+    input channels: with one, the expansion weight gradient is a difference that cancels to
+    O(eps) and no relative bound holds for it."""
+    import random
+    rng = random.Random(seed)
+    out = []
+    for _ in range(count):
+        k, stride = rng.choice([3, 5]), rng.choice([1, 1, 2])
+        fam = rng.choice(["ragged", "mult4", "p56", "p28", "p14", "p7", "tiny", "wide"])
+        if fam == "ragged":
+            H, W = rng.randint(3, 24), rng.randint(3, 24)
+        elif fam == "mult4":
+            H, W = 4 * rng.randint(1, 10), 4 * rng.randint(1, 10)
+        elif fam == "tiny":
+            H, W = rng.randint(1, 4), rng.randint(1, 4)
+        elif fam == "wide":
+            H, W = rng.choice([(7, 7), (14, 14), (8, 8), (6, 10)])
+        else:
+            H = W = int(fam[1:])
+        if fam == "wide":
+            Cin = rng.choice([40, 48, 64, 72, 80, 112])
+            ratio = rng.choice([3, 6])
+            Cout = rng.choice([Cin, 40, 96, 112, 192])
+        else:
+            Cin = rng.choice([2, 3, 5, 8, 16, 17, 24, 32, 33, 40])
+            ratio = rng.choice([1, 1, 3, 4, 6])
+            Cout = rng.choice([Cin, 1, 7, 16, 24, 32, 33, 40, 48])
+        N = rng.randint(1, 6)
+        Cexp = Cin * ratio
+        N = max(1, min(N, 3_000_000 // (H * W * Cexp)))
+        # at least eight samples per channel behind BN2 and BN3: batch normalisation over a
+        # handful of samples amplifies rounding noise without bound (over one sample the
+        # gradient is exactly zero and no relative error is defined)
+        pad = (k - 1) // 2
+        HoWo = ((H + 2 * pad - k) // stride + 1) * ((W + 2 * pad - k) // stride + 1)
+        N = max(N, -(-8 // HoWo))
+        out.append((BlockShape(N=N, Cin=Cin, H=H, W=W, Cexp=Cexp, Cse=max(1, Cin // 4), Cout=Cout, k=k,
+                               stride=stride, has_expand=(ratio != 1 or rng.random() < 0.3),
+                               residual=(stride == 1 and Cin == Cout and rng.random() < 0.7),
+                               activation=rng.choice(["swish", "swish", "relu6"]),
+                               has_se=rng.random() < 0.8),
+                    rng.choice([0, 0, 1])))
+    return out
+
+
+@pytest.mark.parametrize("index", range(48))
+def test_random_shape_matches_oracle(index):
+    """Training step and evaluation-mode forward on a seeded random shape (fp32)."""
+    import torch
+    from paper_2110_10802_amd.harness import DeviceBlock, to_numpy
+    from parity_util import metric_for
+
+    s, policy = _random_shapes(48, seed=20211020)[index]
+    t = make_block_inputs(s, seed=300 + index)
+    print(f"[parity/random {index}] policy={policy} {s}", flush=True)
+    res, blk = run_gpu_block(s, t, policy=policy)
+    f, b = orc.mbconv_step(s, t)
+    compare_block(s, t, res, f, b, blk)
+    te = _with_running(s, t, seed=400 + index)
+    ref = orc.mbconv_forward_eval(s, te)
+    blk2 = DeviceBlock(s, te)
+    out = to_numpy(blk2.forward_eval(blk2.to_device(te["x"])))
+    torch.cuda.synchronize()
+    assert metric_for(s)(out, ref) <= TOL[s.dtype]["fwd"]
+
+
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3])
 def test_benchmark_config_matches_oracle(cfg):
     s = [CONFIG0, CONFIG1, CONFIG2, CONFIG3][cfg]
