@@ -43,6 +43,17 @@ ROW_SHAPES = [(1, 4), (3, 8), (5, 252), (7, 256), (4096, 1024), (33, 2048), (9, 
               (11, 2052), (3, 8192)]
 
 
+def _random_rows(count, seed):
+    """Seeded random (rows, cols): row lengths log-uniform from 1 to 9000, so every row-kernel
+    variant and its ragged tail is reached."""
+    import random
+    rng = random.Random(seed)
+    return [(rng.randint(1, 200), max(1, int(round(9000 ** rng.random())))) for _ in range(count)]
+
+
+ROW_SHAPES += _random_rows(24, seed=20211020)
+
+
 @pytest.mark.parametrize("rows,cols", ROW_SHAPES)
 def test_layernorm_matches_oracle(rows, cols):
     import torch
