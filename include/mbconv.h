@@ -198,7 +198,8 @@ typedef enum {
     MBCONV_STEP_BN3_APPLY = 9,     /* BN3 (+ residual) */
     /* backward */
     MBCONV_STEP_BN3_BWD_REDUCE = 10,
-    MBCONV_STEP_BN3_BWD_FINALIZE = 11,
+    MBCONV_STEP_BN3_BWD_FINALIZE = 11, /* does not occur where PROJ_DGRAD is the one-kernel form, which
+                                          finalises BN3's backward itself */
     MBCONV_STEP_PROJ_DGRAD = 12,   /* for Cout <= 32 (and H*W a multiple of 4) one kernel computes the
                                       data gradient and the weight gradient's split partial sums */
     MBCONV_STEP_PROJ_WGRAD = 13,   /* with an expansion conv: the split partial sums only, their sum is

@@ -80,6 +80,7 @@ struct WgradClArgs {
     const void *dgw;
     void *dgout;
     int dgtiles[8]; // bit tt of dgtiles[t]: wavefront t computes the data gradient of wide tile tt
+    BnBwdFin ufin;  // ufin.psb non-null: U's BN-backward coefficients are derived in the kernel
 };
 
 // Loads this lane's channel `c` of an operand for pixels [q, q+4) and applies its prologue.
@@ -305,7 +306,54 @@ __global__ __launch_bounds__(512, DG ? 4 : 1) void wgrad_lt_kernel(WgradClArgs a
         uch[ta] = ch < a.Ma ? ch : a.Ma - 1;
         uro[ta] = (uint32_t)uch[ta] * (uint32_t)a.HW;
         uk0[ta] = uk1[ta] = uk2[ta] = 0.f;
-        if (PROU != PRO_NONE) {
+        if (DG && PROU == PRO_BNBWD && a.ufin.psb) {
+            // The normalisation's backward finalise step, here instead of in a launch of its own:
+            // the eight lanes that stage a row of U add that channel's partial sums (lane s takes
+            // partials s, s+8, ...; fp64; a fixed butterfly over the eight), every workgroup in
+            // the same order, so all arrive at the same coefficients; workgroup 0 stores them.
+            if (ustager) { // whole wavefronts
+                const int ch = uch[ta], sub = threadIdx.x & 7, NP = a.ufin.NP, Cn = a.Ma;
+                const float gm = a.ufin.gamma[ch], mean = a.ufin.bn[2 * Cn + ch];
+                const float rstd = a.ufin.bn[3 * Cn + ch];
+                const float *pb = a.ufin.psb + (size_t)ch * NP, *pr = a.ufin.psr + (size_t)ch * NP;
+                double sb = 0.0, sr = 0.0;
+                for (int i0 = sub; i0 < NP; i0 += 32) {
+                    float b0[4], b1[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = min(i0 + 8 * u, NP - 1); // unconditional loads, masked below
+                        b0[u] = pb[i];
+                        b1[u] = pr[i];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (i0 + 8 * u < NP) {
+                            sb += (double)b0[u];
+                            sr += (double)b1[u];
+                        }
+                }
+#pragma unroll
+                for (int o = 4; o > 0; o >>= 1) {
+                    sb += __shfl_xor(sb, o, kWave);
+                    sr += __shfl_xor(sr, o, kWave);
+                }
+                // c0*dy + c1*raw + c2 (see launch_bn_bwd_finalize): dgamma = sr, dbeta = sb
+                const double c0 = (double)gm * rstd;
+                const double c1 = -c0 * rstd * sr / a.ufin.m;
+                const double c2 = -c0 * sb / a.ufin.m - c1 * mean;
+                uk0[ta] = (float)c0;
+                uk1[ta] = (float)c1;
+                uk2[ta] = (float)c2;
+                if (blockIdx.x == 0 && sub == 0 && 32 * ta + urow < Cn) {
+                    a.ufin.dbeta[ch] = (float)sb;
+                    a.ufin.dgamma[ch] = (float)sr;
+                    a.ufin.coef[ch] = uk0[ta];
+                    a.ufin.coef[Cn + ch] = uk1[ta];
+                    a.ufin.coef[2 * Cn + ch] = uk2[ta];
+                }
+            }
+        } else if (PROU != PRO_NONE) {
             uk0[ta] = a.uc0[uch[ta]];
             uk1[ta] = a.uc1[uch[ta]];
             if (PROU == PRO_BNBWD)
@@ -832,7 +880,7 @@ bool projbwd_fused_plan(int N, int Cw, int Cn, int HW, int *splits)
 
 hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &dp,
                                 const Operand &sc, const void *w, void *G, float *partial,
-                                int *splits_out, hipStream_t st)
+                                int *splits_out, const BnBwdFin *fin, hipStream_t st)
 {
     int splits;
     if (!projbwd_fused_plan(N, Cw, Cn, HW, &splits) || dp.pro != PRO_BNBWD ||
@@ -861,6 +909,8 @@ hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const 
     a.partial = partial;
     a.dgw = w;
     a.dgout = G;
+    if (fin)
+        a.ufin = *fin;
     *splits_out = splits;
     const int mtb = (Cw + 31) / 32, nw = mtb < 4 ? 4 : mtb;
     const size_t lds = sizeof(float) * ((size_t)kLtPitch * 32 * (2 + nw) + (size_t)nw * 16 * 64);

@@ -402,8 +402,14 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
 
     // BN3 backward reductions
     MBK_STEP(MBCONV_STEP_BN3_BWD_REDUCE, launch_plane_dot(bf, P.N, P.Cout, P.HWo, dout, p, bn3, pa, pb, st));
-    MBK_STEP(MBCONV_STEP_BN3_BWD_FINALIZE, launch_bn_bwd_finalize(P.Cout, P.N, m2, pa, pb, prm->bn3_gamma, bn3, gr->bn3_gamma,
-                                   gr->bn3_beta, coef3, st));
+    // (where one kernel computes both gradients of the projection conv, it also finalises BN3's
+    // backward: no launch for that step)
+    int psplits = 0;
+    const bool proj_fused = projbwd_fused_plan(P.N, P.Cexp, P.Cout, P.HWo, &psplits);
+    const BnBwdFin fin3 = {pa, pb, prm->bn3_gamma, bn3, gr->bn3_gamma, gr->bn3_beta, coef3, P.N, m2};
+    if (!proj_fused)
+        MBK_STEP(MBCONV_STEP_BN3_BWD_FINALIZE, launch_bn_bwd_finalize(P.Cout, P.N, m2, pa, pb, prm->bn3_gamma, bn3,
+                                       gr->bn3_gamma, gr->bn3_beta, coef3, st));
     // projection conv: data gradient G = W_p^T dp and weight gradient dW_p = dp * sc^T,
     // dp rebuilt in the prologue from dout and p
     SplitReduce proj_reduce = {nullptr, 0, 0, nullptr};
@@ -429,11 +435,10 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
         // with an expansion conv, the sum over this weight gradient's splits waits for the
         // other's and shares its launch (the partials then live in a region of their own)
         float *pwg = P.expand ? at<float>(scratch, P.o_wg2) : wg;
-        int psplits = 0;
-        if (projbwd_fused_plan(P.N, P.Cexp, P.Cout, P.HWo, &psplits)) {
+        if (proj_fused) {
             // one kernel for both gradients (its launch is the PROJ_DGRAD step)
             MBK_STEP(MBCONV_STEP_PROJ_DGRAD, launch_projbwd_fused(bf, P.N, P.Cexp, P.Cout, P.HWo, dp, sc, prm->w_proj,
-                                                                  G, pwg, &psplits, st));
+                                                                  G, pwg, &psplits, &fin3, st));
             proj_reduce = {pwg, psplits, (size_t)P.Cout * P.Cexp, gr->w_proj};
             if (!P.expand)
                 MBK_STEP(MBCONV_STEP_PROJ_WGRAD,

@@ -77,10 +77,19 @@ hipError_t launch_reduce_splits2(const SplitReduce &a, const SplitReduce &b, hip
 // The mirror image for a convolution from Cw (wide) to Cn (narrow) channels, whose input sc is a
 // PRO_BNSWISH_GATE or PRO_NONE operand [N,Cw,HW] and whose output gradient dp is PRO_BNBWD [N,Cn,HW]:
 //   G[n,c,q] = sum_j w[j*Cw+c] * dp[n,j,q],   dW[j][c] = sum_{n,q} dp[n,j,q] * sc[n,c,q]
+// `fin` (optional): dp's BN-backward coefficients are not read from dp.c0/c1/c2 but derived in
+// the kernel from the per-plane partial sums, as launch_bn_bwd_finalize would (psb/psr: [Cn][NP],
+// m elements per channel); workgroup 0 also stores dgamma, dbeta and the coefficient triple.
+struct BnBwdFin {
+    const float *psb, *psr, *gamma, *bn;
+    float *dgamma, *dbeta, *coef;
+    int NP;
+    double m;
+};
 bool projbwd_fused_plan(int N, int Cw, int Cn, int HW, int *splits);
 hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &dp,
                                 const Operand &sc, const void *w, void *G, float *partial,
-                                int *splits_out, hipStream_t st);
+                                int *splits_out, const BnBwdFin *fin, hipStream_t st);
 bool bwd1x1_fused_plan(int N, int Cw, int Cn, int HW, int *splits);
 hipError_t launch_bwd1x1_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &de,
                                const void *xin, const void *w, void *dx, const void *res,
