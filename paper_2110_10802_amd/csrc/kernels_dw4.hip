@@ -69,6 +69,7 @@ struct Dw4Args {
     void *d;
     float *psum, *psq;
     BnFin fin; // fin.psum non-null: bn1 is derived in the forward kernel from the partial sums
+    int PL;    // forward, planes per workgroup (images n0..n0+PL-1 of one channel), 1: a plane each
     // backward
     const void *G;
     const float *g, *dzs, *bn2, *coef2;
@@ -242,6 +243,112 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw4_fwd_kernel(Dw4Args 
     if (active && lt == 0) {
         a.psum[(size_t)c * a.N + n] = acc2[0];
         a.psq[(size_t)c * a.N + n] = acc2[1];
+    }
+}
+
+// The same for a workgroup of 256 threads that walks PL images of one channel: the filter, the
+// BN1 constants (or their finalisation from the partial sums), and the tile's zero border are set
+// up once, and the next plane's loads are issued before the current plane is convolved, so they
+// travel under the arithmetic.
+template <typename T, int K, int NG, bool EXPAND>
+__global__ __launch_bounds__(256) void dw4_fwd_multi_kernel(Dw4Args a)
+{
+    constexpr int P = (K - 1) / 2, TPP = 256;
+    extern __shared__ float lds[];
+    const int H = a.H, W = a.W, WP = a.WP;
+    const int tileElems = (H + 2 * P) * WP;
+    const int lt = threadIdx.x;
+    float *tile = lds;
+    float *red = lds + tileElems;
+    __shared__ double redd[2 * (TPP / 64)];
+    const int ngrp = (int)fdiv(blockIdx.x, a.divC), c = (int)blockIdx.x - ngrp * a.C;
+    const int n0 = ngrp * a.PL, n1 = min(a.N, n0 + a.PL);
+    const size_t HW = (size_t)H * W;
+
+    float wt[K * K];
+    float scale = 1.f, shift = 0.f;
+    BnFinRegs fr;
+    if (EXPAND) {
+        if (a.fin.psum) {
+            bn_fin_issue<TPP>(a.fin, c, lt, fr);
+        } else {
+            scale = a.bn1[c];
+            shift = a.bn1[a.C + c];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < K * K; ++t)
+        wt[t] = ld<T>((const T *)a.w, (size_t)c * K * K + t);
+    __builtin_amdgcn_sched_barrier(0);
+    zero_border<P, TPP>(tile, H, W, WP, lt);
+    float ev[NG][4];
+    const auto fetch = [&](int n) {
+        const size_t base = ((size_t)n * a.C + c) * HW;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            gload4<T>((const T *)a.e, base + 4 * (size_t)(gidx < a.groups ? gidx : 0), ev[i]);
+        }
+    };
+    fetch(n0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (EXPAND && a.fin.psum) {
+        float mu, rs;
+        bn_fin_finish<TPP>(a.fin, a.C, c, lt, n0 == 0, redd, fr, scale, shift, mu, rs);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    for (int n = n0; n < n1; ++n) {
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            if (gidx < a.groups) {
+                const int h = (int)fdiv((uint32_t)gidx, a.divW4);
+                const int w = 4 * (gidx - h * (W >> 2));
+                float v[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    v[r] = EXPAND ? actf(fmaf(ev[i][r], scale, shift)) : ev[i][r];
+                float4v t4 = {v[0], v[1], v[2], v[3]};
+                *reinterpret_cast<float4v *>(tile + (h + P) * WP + 4 + w) = t4;
+            }
+        }
+        __syncthreads();
+        if (n + 1 < n1)
+            fetch(n + 1);
+        float acc2[2] = {0.f, 0.f};
+        const size_t base = ((size_t)n * a.C + c) * HW;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int gidx = lt + TPP * i;
+            if (gidx < a.groups) {
+                const int h = (int)fdiv((uint32_t)gidx, a.divW4);
+                const int w = 4 * (gidx - h * (W >> 2));
+                float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u < K; ++u) {
+                    float row[K + 3];
+                    read_window_row<K>(tile, h + u, WP, w, row);
+#pragma unroll
+                    for (int v = 0; v < K; ++v)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            o[r] = fmaf(wt[u * K + v], row[r + v], o[r]);
+                }
+                gstore4<T>((T *)a.d, base + 4 * (size_t)gidx, o);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float sv = as_stored<T>(o[r]);
+                    acc2[0] += sv;
+                    acc2[1] = fmaf(sv, sv, acc2[1]);
+                }
+            }
+        }
+        // (two barriers inside: every read of this plane's tile precedes the next plane's stores)
+        group_sum<2, TPP>(acc2, red);
+        if (lt == 0) {
+            a.psum[(size_t)c * a.N + n] = acc2[0];
+            a.psq[(size_t)c * a.N + n] = acc2[1];
+        }
     }
 }
 
@@ -507,6 +614,39 @@ hipError_t launch_dw4_fwd(bool bf16, const DwShape &s, const void *e, const floa
     dw4_shape(a.groups, &tpp, &ng);
     const size_t lds = dw4_lds(s, 1, 2);
     const bool ex = bn1 != nullptr;
+    // 56x56-class planes (a workgroup of 256 threads per plane): two images of a channel per
+    // workgroup where that still leaves eight workgroups per CU (config 1: 26.4 us against 29.5
+    // for the step; four images 26.6, eight 29.5)
+    a.PL = (tpp == 256 && ng == 4 && (long long)a.C * ((a.N + 1) / 2) >= 2048) ? 2 : 1;
+    if (a.PL > 1) {
+        const unsigned grid = (unsigned)(a.C * ((a.N + a.PL - 1) / a.PL));
+#define MBK_MULTI(T, K, EXP)                                                                      \
+    {                                                                                             \
+        auto kern = dw4_fwd_multi_kernel<T, K, 4, EXP>;                                           \
+        hipError_t e_ = hipFuncSetAttribute((const void *)kern,                                   \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        if (e_ != hipSuccess)                                                                     \
+            return e_;                                                                            \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);                              \
+        return hipGetLastError();                                                                 \
+    }
+#define MBK_MULTI_K(T, EXP)                                                                       \
+    {                                                                                             \
+        if (s.k == 3)                                                                             \
+            MBK_MULTI(T, 3, EXP)                                                                  \
+        MBK_MULTI(T, 5, EXP)                                                                      \
+    }
+        if (bf16) {
+            if (ex)
+                MBK_MULTI_K(bf16_t, true)
+            MBK_MULTI_K(bf16_t, false)
+        }
+        if (ex)
+            MBK_MULTI_K(float, true)
+        MBK_MULTI_K(float, false)
+#undef MBK_MULTI_K
+#undef MBK_MULTI
+    }
 #define MBK_GO(T, K)                                                                              \
     return ex ? dw4_fwd_go<T, K, true>(a, tpp, ng, lds, st) : dw4_fwd_go<T, K, false>(a, tpp, ng, lds, st);
     if (bf16) {

@@ -41,6 +41,13 @@ SMALL = {
     "one_pixel": _shape(N=3, Cin=4, Cexp=8, Cse=2, Cout=4, H=1, W=1),
     # 64 <-> 192 channels on 14x14: the wide fp32 conv kernels without a split contraction
     "mid_14x14": _shape(N=4, Cin=64, Cexp=192, Cse=16, Cout=64, H=14, W=14),
+    # depthwise forward with two images of a channel per workgroup (planes of 1025..4096 elements,
+    # at least 2048 such workgroups): an odd batch (the last workgroup of a channel has one image),
+    # 5x5 and 3x3, with and without the expansion conv, fp32 and bf16
+    "dw_two_images_k5": _shape(N=5, Cin=24, Cexp=684, Cse=6, Cout=24, H=36, W=36, k=5),
+    "dw_two_images_noexpand": _shape(N=5, Cin=684, Cexp=684, Cse=6, Cout=24, H=36, W=36,
+                                     has_expand=False, residual=False),
+    "dw_two_images_bf16": _shape(dtype="bf16", N=5, Cin=24, Cexp=684, Cse=6, Cout=24, H=36, W=36),
     "bf16_small": _shape(dtype="bf16", H=14, W=14, k=5, Cin=16, Cexp=64, Cout=16, N=4),
     "bf16_s2": _shape(dtype="bf16", H=16, W=16, k=3, stride=2, Cin=16, Cexp=32, Cout=24, N=4,
                       residual=False),
