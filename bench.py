@@ -1,16 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the MBConv training step (forward + backward) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--policy recompute|store]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--policy recompute|store]
                     [--mode train|eval]
 
-A step is one forward plus one backward of the block through the C ABI, on seeded synthetic
-inputs that are already resident in HBM.  The default workload is benchmark config 1
-(EfficientNet-B0 stage-2 repeat block, fp32, batch 32).  Prints ONE JSON line:
-  value      images/s over the whole job
-  roofline   the slowest kernel of the step, timed live with HIP events recorded on the launch
-             stream inside the timed region (less the measured gap of an empty event pair),
-             against the HBM roofline (algorithmic bytes)
+A step is one forward plus one backward through the C ABI on seeded synthetic inputs that are
+already resident in HBM.  The default workload is benchmark config 4, the largest one: the 16
+MBConv blocks of EfficientNet-B0 chained at batch 64 (block i's output is block i+1's input,
+backward in reverse order, one scratch workspace shared by all blocks); its first block is the
+layer the paper measured.  Prints ONE JSON line:
+  value         images/s over the whole job
+  roofline      the slowest kernel of the step, timed live with HIP events recorded on the launch
+                stream inside the timed region (less the measured gap of an empty event pair),
+                against the HBM roofline (algorithmic bytes); `traffic` is the HBM byte count
+                rocprofv3 measured for that launch, read from profiles/hbm_traffic_per_step.md
+  roofline_next the next slowest steps, from the untimed survey
+  step_roofline algorithmic bytes of the whole step / ms_per_step against the HBM peak
+  gemm          the 1x1 convolutions of the blocks whose GEMMs lie above the fp32 ridge
+                (chain blocks 7-16): flops, time and fraction of the fp32 MFMA peak
+  other_configs the single-block configs 1-3 (images/s, slowest kernel, roofline fraction)
   cpu_baseline  the fp64 CPU oracle timed on this host (a reported baseline, not a target)
 """
 from __future__ import annotations
@@ -19,40 +27,57 @@ import argparse
 import ctypes as C
 import json
 import os
+import re
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_F32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate, published
+F32_RIDGE = MFMA_F32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)  # flop per byte
 
-# HBM bytes measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
-# counters' reading on a plain copy kernel of known size; per launch, keyed by
-# (workload, step).  Filled from the summaries under profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/config1_fp32_kernel_stats.md, fetch + write MiB per dispatch of the three kernels
-    # that can come out slowest: dw4_bwd, wgrad_lt<..., DG> (the proj_dgrad step), bwd1x1_lt (the
-    # expand_dgrad step)
-    ("config1", "dw_bwd"): int((165.8 + 55.4) * 2 ** 20),
-    ("config1", "proj_dgrad"): int((73.9 + 61.0) * 2 ** 20),
-    ("config1", "expand_dgrad"): int((128.9 + 15.1) * 2 ** 20),
-}
+# HBM bytes per launch as rocprofv3 --pmc measured them (FETCH_SIZE, WRITE_SIZE, scaled by the
+# same counters' reading on a plain copy of known size): one Markdown table row per
+# (workload, step), written from the profiler's output; bench.py only reads it.
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_step.md")
+
+NO_EXPAND_STEPS = ("expand_conv", "bn1_finalize", "bn1_bwd_finalize", "expand_dgrad", "expand_wgrad")
+GEMM_STEPS = ("expand_conv", "proj_conv", "proj_dgrad", "proj_wgrad", "expand_dgrad", "expand_wgrad")
 
 
-def algorithmic_bytes(s, step: str):
-    """Bytes the step must move by the fusion plan (each tensor it consumes or produces
-    crosses HBM once); None for the O(N*C) steps."""
+def measured_traffic(workload: str, step: str):
+    """Bytes (fetch + write) the profiler counted for one launch of `step`, or None."""
+    try:
+        with open(TRAFFIC_TABLE) as fh:
+            for line in fh:
+                cells = [c.strip() for c in line.split("|")]
+                if len(cells) >= 8 and cells[1] == workload and cells[2] == step:
+                    return int(round((float(cells[5]) + float(cells[6])) * 2 ** 20))
+    except (OSError, ValueError):
+        pass
+    return None
+
+
+def _fused(s):
+    """Shapes for which one kernel computes both gradients of a 1x1 conv (narrow side <= 32
+    channels, wide side <= 256, plane a multiple of four): the step named *_dgrad is that kernel."""
+    fused_proj = s.Cout <= 32 and s.Cout < s.Cexp <= 256 and (s.Ho * s.Wo) % 4 == 0
+    fused_exp = s.has_expand and s.Cin <= 32 and s.Cin < s.Cexp <= 256 and (s.H * s.W) % 4 == 0
+    return fused_proj, fused_exp
+
+
+def step_bytes(s) -> dict:
+    """Bytes each step must move by the fusion plan (each tensor it consumes or produces
+    crosses HBM once), for the steps with an activation-sized operand."""
     b = 2 if s.dtype == "bf16" else 4
     X = s.N * s.Cin * s.H * s.W
     E = s.N * s.Cexp * s.H * s.W
     D = s.N * s.Cexp * s.Ho * s.Wo
     P = s.N * s.Cout * s.Ho * s.Wo
     res = P if s.residual else 0
-    # shapes for which one kernel computes both gradients of a 1x1 conv (narrow side <= 32
-    # channels, wide side <= 256, plane a multiple of four): the step named *_dgrad is that kernel
-    fused_proj = s.Cout <= 32 and s.Cout < s.Cexp <= 256 and (s.Ho * s.Wo) % 4 == 0
-    fused_exp = s.has_expand and s.Cin <= 32 and s.Cin < s.Cexp <= 256 and (s.H * s.W) % 4 == 0
+    fused_proj, fused_exp = _fused(s)
     table = {
         "expand_conv": X + E, "dw_fwd": E + D, "se_pool": D, "proj_conv": D + P,
         "bn3_apply": 2 * P + res, "bn3_bwd_reduce": 2 * P,
@@ -66,7 +91,39 @@ def algorithmic_bytes(s, step: str):
         del table["proj_wgrad"]  # what is left of the step is the sum over the splits
     if fused_exp:
         del table["expand_wgrad"]
-    return table[step] * b if step in table else None
+    if not s.has_expand:
+        for n in ("expand_conv", "expand_dgrad", "expand_wgrad"):
+            table.pop(n, None)
+    if not getattr(s, "has_se", True):
+        table.pop("se_pool", None)
+    return {n: v * b for n, v in table.items()}
+
+
+def algorithmic_bytes(s, step: str):
+    return step_bytes(s).get(step)
+
+
+def step_flops(s) -> dict:
+    """Multiply-add flops of the 1x1-convolution steps (2 per multiply-add)."""
+    fe = 2 * s.N * s.H * s.W * s.Cin * s.Cexp
+    fp = 2 * s.N * s.Ho * s.Wo * s.Cexp * s.Cout
+    fused_proj, fused_exp = _fused(s)
+    t = {"proj_conv": fp, "proj_dgrad": 2 * fp if fused_proj else fp}
+    if not fused_proj:
+        t["proj_wgrad"] = fp
+    if s.has_expand:
+        t.update({"expand_conv": fe, "expand_dgrad": 2 * fe if fused_exp else fe})
+        if not fused_exp:
+            t["expand_wgrad"] = fe
+    return t
+
+
+def gemm_is_mfma_bound(s) -> bool:
+    """True when the block's 1x1 convolutions lie above the fp32 ridge (flops per byte of a
+    1x1 conv: 2*Ci*Co per pixel over (Ci+Co)*4 bytes)."""
+    if s.dtype != "f32" or not s.has_expand:
+        return False
+    return 2.0 * s.Cin * s.Cexp / ((s.Cin + s.Cexp) * 4.0) > F32_RIDGE
 
 
 class HipEvents:
@@ -137,6 +194,34 @@ def cpu_baseline(shape, tensors, eval_mode=False):
                       f"{len(times)} passes, {dt:.2f} s wall each"}
 
 
+def cpu_baseline_chain(batch: int):
+    """One fp64 oracle pass (forward through the 16 blocks, then backward) over the chain at
+    `batch` images, same seeds as the GPU run; every tape is freed as soon as its block's
+    backward has run."""
+    import numpy as np
+    from mbconv_inputs import b0_chain, make_block_inputs
+    from oracle import oracle as orc
+    shapes = b0_chain(N=batch)
+    t0 = time.perf_counter()
+    recs, x = [], None
+    for i, s in enumerate(shapes):
+        t = make_block_inputs(s, seed=i, with_x=(i == 0), with_dout=(i == len(shapes) - 1))
+        if i > 0:
+            t["x"] = x
+        f = orc.mbconv_forward(s, t)
+        x = f.out
+        recs.append((s, t, f.tape))
+    dout = np.asarray(recs[-1][1]["dout"], dtype=np.float64)
+    while recs:
+        s, t, tape = recs.pop()
+        dout = orc.mbconv_backward(s, t, tape, dout).dx
+        del tape, t
+    dt = time.perf_counter() - t0
+    return {"value": batch / dt, "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"one fp64 forward+backward pass over the 16-block chain at batch {batch} "
+                      f"(seeded input generation included), {dt:.1f} s wall"}
+
+
 def cpu_baseline_one_thread(shape, eval_mode=False):
     """The oracle on ONE thread, in a child process (OMP_NUM_THREADS=1), on a quarter of the batch."""
     import subprocess
@@ -159,10 +244,13 @@ def cpu_baseline_one_thread(shape, eval_mode=False):
             "sample": f"{n} images, {float(dt):.1f} s wall"}
 
 
-NO_EXPAND_STEPS = ("expand_conv", "bn1_finalize", "bn1_bwd_finalize", "expand_dgrad", "expand_wgrad")
+def _roofline_entry(kernel, nbytes, ms):
+    ach = nbytes / (ms * 1e-3) / 1e9
+    return {"kernel": kernel, "kernel_ms": round(ms, 5), "achieved": round(ach, 1),
+            "frac": round(ach / HBM_PEAK_GBS, 4), "algorithmic_bytes": nbytes}
 
 
-def run_chain(args) -> int:
+def run_chain(args) -> dict:
     """Benchmark config 4: the 16 MBConv blocks of EfficientNet-B0 chained (block i's output is
     block i+1's input; backward in reverse order), one scratch workspace shared by all blocks."""
     import torch
@@ -193,28 +281,46 @@ def run_chain(args) -> int:
             "x": x0 if i == 0 else blocks[i - 1].out,
             "dout": dlast if i == len(blocks) - 1 else blocks[i + 1].dx,
         })
+    only = args.only_block - 1 if args.only_block else None
 
     def step(probe=None, probe_block=-1):
         for i, c in enumerate(ctx):
+            if only is not None and i != only:
+                continue
             pr = probe if (i == probe_block and probe.step <= 9) else None
             B.mbconv_forward_probed(c["desc"], c["params"], c["running"], c["x"], c["blk"].out,
                                     c["blk"].saved, scratch, stream, pr)
         for i in range(len(ctx) - 1, -1, -1):
+            if only is not None and i != only:
+                continue
             c = ctx[i]
             pr = probe if (i == probe_block and probe.step > 9) else None
             B.mbconv_backward_probed(c["desc"], c["params"], c["x"], c["dout"], c["blk"].saved,
                                      scratch, c["blk"].dx, c["grads"], stream, pr)
 
+    if only is not None:
+        # one block of the chain alone, at its real shape and on its real input (for profiling):
+        # the blocks before it run once to produce that input, the block after it is given a
+        # random upstream gradient
+        for i, c in enumerate(ctx[:only]):
+            B.mbconv_forward_probed(c["desc"], c["params"], c["running"], c["x"], c["blk"].out,
+                                    c["blk"].saved, scratch, stream, None)
+        if only < len(ctx) - 1:
+            ctx[only]["dout"].normal_()
     for _ in range(max(args.warmup, 1)):
         step()
     torch.cuda.synchronize()
     ev = HipEvents()
+    overhead_ms = ev.pair_overhead_ms(stream, step, reps=5)
     e0, e1 = ev.create(), ev.create()
     survey = []
     for i, c in enumerate(ctx):
         if args.no_survey:
             break
         row = {}
+        if only is not None and i != only:
+            survey.append(row)
+            continue
         prev_reps = None
         for name, sid in B.STEPS.items():
             if not shapes[i].has_expand and name in NO_EXPAND_STEPS:
@@ -242,36 +348,87 @@ def run_chain(args) -> int:
         bi = int(bi) - 1
     else:
         bi, dominant = max(cand, key=lambda c: survey[c[0]][c[1]])
-    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    # the dominant kernel is timed inside the timed region on every fourth step (an event pair
+    # stretches its step by the gap between two event records)
+    pairs = [(ev.create(), ev.create()) for _ in range((args.steps + 3) // 4)]
     probes = [B.Probe(B.STEPS[dominant], a, b) for a, b in pairs]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(probes[i], bi)
+        if i % 4 == 0:
+            step(probes[i // 4], bi)
+        else:
+            step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms_raw = sum(ev.elapsed_ms(a, b) for a, b in pairs) / args.steps
-    overhead_ms = ev.pair_overhead_ms(stream, step, reps=5)
+    kern_ms_raw = sum(ev.elapsed_ms(a, b) for a, b in pairs) / len(pairs)
+    for a, b in pairs:
+        ev.destroy(a)
+        ev.destroy(b)
     kern_ms = max(kern_ms_raw - overhead_ms, 1e-6)
     nbytes = algorithmic_bytes(shapes[bi], dominant)
     achieved = nbytes / (kern_ms * 1e-3) / 1e9
     N = shapes[0].N
+    active = [s for i, s in enumerate(shapes) if only is None or i == only]
+    total_bytes = sum(sum(step_bytes(s).values()) for s in active)
+    workload = "config4" if only is None else f"config4-block{only + 1}"
     result = {
         "metric": "mbconv_fwd_bwd_images_per_sec", "value": N / (ms_per_step * 1e-3),
         "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config4", "block": f"N{N} EfficientNet-B0 chain of 16 MBConv blocks, "
-                   "32ch 112x112 in", "policy": args.policy},
+        "config": {"workload": workload, "block": f"N{N} EfficientNet-B0 chain of 16 MBConv blocks, "
+                   "32ch 112x112 in" + ("" if only is None else f"; block {only + 1} alone"),
+                   "policy": args.policy},
         "roofline": {"bound": "hbm", "kernel": f"block{bi + 1}:{dominant}", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel_ms": kern_ms, "kernel_ms_with_event_gap": kern_ms_raw,
+                     "traffic": measured_traffic("config4", f"block{bi + 1}:{dominant}"),
+                     "kernel_ms": kern_ms, "kernel_ms_with_event_gap": kern_ms_raw,
                      "event_gap_ms": overhead_ms, "algorithmic_bytes": nbytes},
-        "block_ms_survey": [round(sum(r.values()), 5) for r in survey],
+        # bytes of every step of every block by the fusion plan over the measured step time: how
+        # far the whole step is from streaming its tensors once at the HBM peak
+        "step_roofline": {"bound": "hbm", "algorithmic_bytes": total_bytes,
+                          "achieved": round(total_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                          "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": round(total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
     }
-    print(json.dumps(result))
-    return 0
+    if survey:
+        net = lambda i, n: max(survey[i][n] - overhead_ms, 1e-6)
+        nxt = sorted((c for c in cand if c != (bi, dominant)), key=lambda c: -survey[c[0]][c[1]])[:3]
+        result["roofline_next"] = [_roofline_entry(f"block{i + 1}:{n}", algorithmic_bytes(shapes[i], n),
+                                                   net(i, n)) for i, n in nxt]
+        # 1x1 convolutions above the fp32 ridge: the matrix-core roofline applies to these
+        rows = []
+        for i, s in enumerate(shapes):
+            if not gemm_is_mfma_bound(s) or not survey[i]:
+                continue
+            fl = step_flops(s)
+            for n in GEMM_STEPS:
+                if n in fl and n in survey[i]:
+                    rows.append((i, n, fl[n], net(i, n)))
+        if rows:
+            tot_f, tot_ms = sum(r[2] for r in rows), sum(r[3] for r in rows)
+            slow = max(rows, key=lambda r: r[3])
+            worst = min(rows, key=lambda r: r[2] / r[3])
+            best = max(rows, key=lambda r: r[2] / r[3])
+            ent = lambda r: {"kernel": f"block{r[0] + 1}:{r[1]}", "flops": r[2], "kernel_ms": round(r[3], 5),
+                             "achieved": round(r[2] / (r[3] * 1e-3) / 1e12, 1),
+                             "frac": round(r[2] / (r[3] * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4)}
+            result["gemm"] = {"bound": "mfma", "dtype": "f32", "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                              "blocks": sorted({r[0] + 1 for r in rows}), "launches": len(rows),
+                              "flops": tot_f, "ms": round(tot_ms, 5),
+                              "achieved": round(tot_f / (tot_ms * 1e-3) / 1e12, 1),
+                              "frac": round(tot_f / (tot_ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
+                              "slowest": ent(slow), "lowest_frac": ent(worst), "highest_frac": ent(best)}
+        result["block_ms_survey"] = [round(sum(max(v - overhead_ms, 0.0) for v in r.values()), 5)
+                                     for r in survey]
+        result["launch_steps"] = sum(len(r) for r in survey)
+    del blocks, ctx, scratch
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline and only is None:
+        result["cpu_baseline"] = cpu_baseline_chain(N)
+    return result
 
 
 # Workloads of the operator benchmarks (--op).  The paper gives no tensor sizes for these in its
@@ -284,7 +441,7 @@ OP_WORKLOADS = {
 }
 
 
-def run_op(args) -> int:
+def run_op(args) -> dict:
     """One step = forward + backward of the operator on resident fp32 tensors."""
     import numpy as np
     import torch
@@ -378,59 +535,18 @@ def run_op(args) -> int:
         result["cpu_baseline"] = {"value": xs.size / dt / 1e9, "unit": "Gelements/s",
                                   "cores": os.cpu_count(), "kind": "oracle",
                                   "sample": f"one fp64 forward+backward over {xs.size} elements, {dt:.1f} s wall"}
-    print(json.dumps(result))
-    return 0
+    return result
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4, 5],
-                    help="0-3: single MBConv blocks, 4: the EfficientNet-B0 chain, 5: a MobileNet-V2 "
-                         "inverted-residual block (ReLU6, no SE) with config 1's tensor shapes")
-    ap.add_argument("--policy", default="recompute", choices=["recompute", "store"])
-    ap.add_argument("--mode", default="train", choices=["train", "eval"],
-                    help="train: forward+backward (the headline metric); eval: the evaluation-mode "
-                         "forward alone (BN with running statistics), configs 0-3")
-    ap.add_argument("--op", default=None, choices=["mish", "layernorm", "softmax"],
-                    help="benchmark one of the paper's other memory-bound operators (forward + "
-                         "backward) instead of the MBConv step")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-1thread", action="store_true",
-                    help="also time the oracle on one thread (on a quarter of the batch; slow)")
-    ap.add_argument("--probe-step", default=None,
-                    help="time this step for the roofline instead of the slowest one")
-    ap.add_argument("--no-survey", action="store_true",
-                    help="config 4 only: skip the per-block survey (the roofline kernel is then "
-                         "--probe-step BLOCK:STEP, default 2:dw_bwd)")
-    ap.add_argument("--pmc-calibration", action="store_true",
-                    help="also run a plain 256 MiB device copy (for scaling rocprofv3 "
-                         "FETCH_SIZE/WRITE_SIZE readings)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "run it with --gpus 1", file=sys.stderr)
-        return 2
-
+def run_block(args, config: int, steps: int, warmup: int, with_cpu: bool, distribution: bool = True) -> dict:
+    """One of the single-block workloads (configs 0-3 and the MobileNet-V2 block)."""
     import torch
     from mbconv_inputs import CONFIGS, make_block_inputs
     from paper_2110_10802_amd import binding as B
     from paper_2110_10802_amd.harness import DeviceBlock
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 1
-    if args.op:
-        return run_op(args)
-    if args.config == 4:
-        if args.mode != "train":
-            print("bench.py: --mode eval covers the single-block configs 0-3", file=sys.stderr)
-            return 2
-        return run_chain(args)
     B.load()  # fails loudly if the HIP library has not been built
-    shape = CONFIGS[args.config]
+    shape = CONFIGS[config]
     tensors = make_block_inputs(shape, seed=0)
     policy = B.MBCONV_STORE if args.policy == "store" else B.MBCONV_RECOMPUTE
     blk = DeviceBlock(shape, tensors, policy=policy)
@@ -457,7 +573,7 @@ def main() -> int:
         B.mbconv_backward_probed(desc, params, x, dout, blk.saved, blk.scratch, blk.dx, grads,
                                  stream, bprobe)
 
-    for _ in range(max(args.warmup, 1)):
+    for _ in range(max(warmup, 1)):
         step()
     torch.cuda.synchronize()
 
@@ -487,42 +603,44 @@ def main() -> int:
     ev.destroy(e1)
     dominant = args.probe_step or max(
         (n for n in survey if algorithmic_bytes(shape, n) is not None), key=lambda n: survey[n])
-    print("per-step ms (untimed survey): " +
+    print(f"config {config} per-step ms (untimed survey): " +
           ", ".join(f"{n}={v * 1e3:.1f}us" for n, v in survey.items()), file=sys.stderr)
 
     # the dominant kernel is timed inside the timed region on every fourth step (an event pair
     # stretches the step by the gap between two event records, about 2 % of this one)
-    pairs = [(ev.create(), ev.create()) for _ in range((args.steps + 3) // 4)]
+    pairs = [(ev.create(), ev.create()) for _ in range((steps + 3) // 4)]
     sid = B.STEPS[dominant]
     probes = [B.Probe(sid, a, b) for a, b in pairs]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(probes[i // 4] if i % 4 == 0 else None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     kern_ms_raw = sum(ev.elapsed_ms(a, b) for a, b in pairs) / len(pairs)
     for a, b in pairs:
         ev.destroy(a)
         ev.destroy(b)
-    # distribution of the step time: a second, separate pass with one event between consecutive
-    # steps (kept out of the timed loop, whose wall clock it would stretch); median and a 95 %
-    # non-parametric confidence interval of the median from the order statistics
-    marks = [ev.create() for _ in range(args.steps + 1)]
-    ev.record(marks[0], stream)
-    for i in range(args.steps):
-        step()
-        ev.record(marks[i + 1], stream)
-    torch.cuda.synchronize()
-    per_step = sorted(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(args.steps))
-    for m in marks:
-        ev.destroy(m)
-    k = len(per_step)
-    half = 0.98 * (k ** 0.5)  # 1.96 * sqrt(k) / 2
-    lo_i, hi_i = max(int(k / 2 - half), 0), min(int(k / 2 + half) + 1, k - 1)
-    step_stats = {"median": per_step[k // 2], "ci95": [per_step[lo_i], per_step[hi_i]],
-                  "min": per_step[0], "max": per_step[-1]}
+    step_stats = None
+    if distribution:
+        # distribution of the step time: a second, separate pass with one event between
+        # consecutive steps (kept out of the timed loop, whose wall clock it would stretch); median
+        # and a 95 % non-parametric confidence interval of the median from the order statistics
+        marks = [ev.create() for _ in range(steps + 1)]
+        ev.record(marks[0], stream)
+        for i in range(steps):
+            step()
+            ev.record(marks[i + 1], stream)
+        torch.cuda.synchronize()
+        per_step = sorted(ev.elapsed_ms(marks[i], marks[i + 1]) for i in range(steps))
+        for m in marks:
+            ev.destroy(m)
+        k = len(per_step)
+        half = 0.98 * (k ** 0.5)  # 1.96 * sqrt(k) / 2
+        lo_i, hi_i = max(int(k / 2 - half), 0), min(int(k / 2 + half) + 1, k - 1)
+        step_stats = {"median": per_step[k // 2], "ci95": [per_step[lo_i], per_step[hi_i]],
+                      "min": per_step[0], "max": per_step[-1]}
     # an event pair around a kernel also spans the gap between two event records; that gap is
     # measured with an empty pair behind the same queued work and taken off
     overhead_ms = ev.pair_overhead_ms(stream, step)
@@ -537,14 +655,16 @@ def main() -> int:
 
     nbytes = algorithmic_bytes(shape, dominant)
     achieved = nbytes / (kern_ms * 1e-3) / 1e9
-    workload = f"config{args.config}"
+    workload = f"config{config}"
+    total_bytes = sum(v for n, v in step_bytes(shape).items() if not evalm or B.STEPS[n] <= 9)
+    net = lambda n: max(survey[n] - overhead_ms, 1e-6)
     result = {
         "metric": "mbconv_eval_fwd_images_per_sec" if evalm else "mbconv_fwd_bwd_images_per_sec",
         "value": shape.N / (ms_per_step * 1e-3),
         "unit": "images/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -558,28 +678,115 @@ def main() -> int:
                    "policy": args.policy, "mode": args.mode},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((workload, dominant)),
+                     "traffic": measured_traffic(workload if args.policy == "recompute" and not evalm
+                                                 else f"{workload}-{args.policy}-{args.mode}", dominant),
                      "kernel_ms": kern_ms, "kernel_ms_with_event_gap": kern_ms_raw,
                      "event_gap_ms": overhead_ms, "algorithmic_bytes": nbytes},
         # the next slowest steps, from the untimed survey (event gap taken off): on config 1 three
         # kernels lie within 2 us of each other and the survey's order among them varies from run
         # to run, so the line shows all of them whichever one `roofline` names
         "roofline_next": [
-            {"kernel": n, "kernel_ms": round(max(survey[n] - overhead_ms, 1e-6), 5),
-             "achieved": round(algorithmic_bytes(shape, n) / (max(survey[n] - overhead_ms, 1e-6) * 1e-3) / 1e9, 1),
-             "frac": round(algorithmic_bytes(shape, n) / (max(survey[n] - overhead_ms, 1e-6) * 1e-3) / 1e9
-                           / HBM_PEAK_GBS, 4),
-             "algorithmic_bytes": algorithmic_bytes(shape, n)}
+            _roofline_entry(n, algorithmic_bytes(shape, n), net(n))
             for n in sorted((m for m in survey if m != dominant and algorithmic_bytes(shape, m) is not None),
                             key=lambda m: -survey[m])[:3]],
+        "step_roofline": {"bound": "hbm", "algorithmic_bytes": total_bytes,
+                          "achieved": round(total_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                          "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": round(total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "step_ms_survey": {n: round(v, 5) for n, v in survey.items()},
-        "step_ms_distribution": {k_: ([round(x, 5) for x in v] if isinstance(v, list) else round(v, 5))
-                                 for k_, v in step_stats.items()},
+        "launch_steps": len(survey),
     }
-    if not args.no_cpu_baseline:
+    if step_stats is not None:
+        result["step_ms_distribution"] = {
+            k_: ([round(v_, 5) for v_ in v] if isinstance(v, list) else round(v, 5))
+            for k_, v in step_stats.items()}
+    if with_cpu:
         result["cpu_baseline"] = cpu_baseline(shape, tensors, evalm)
         if args.cpu_1thread:
             result["cpu_baseline"]["one_thread"] = cpu_baseline_one_thread(shape, evalm)
+    del blk
+    torch.cuda.empty_cache()
+    return result
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, choices=[0, 1, 2, 3, 4, 5],
+                    help="4 (default): the EfficientNet-B0 chain of 16 MBConv blocks, the largest "
+                         "workload; 0-3: single MBConv blocks; 5: a MobileNet-V2 inverted-residual "
+                         "block (ReLU6, no SE) with config 1's tensor shapes")
+    ap.add_argument("--policy", default="recompute", choices=["recompute", "store"])
+    ap.add_argument("--mode", default="train", choices=["train", "eval"],
+                    help="train: forward+backward (the headline metric); eval: the evaluation-mode "
+                         "forward alone (BN with running statistics), configs 0-3")
+    ap.add_argument("--op", default=None, choices=["mish", "layernorm", "softmax"],
+                    help="benchmark one of the paper's other memory-bound operators (forward + "
+                         "backward) instead of the MBConv step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="config 4 only: do not also run the single-block configs 1-3")
+    ap.add_argument("--cpu-1thread", action="store_true",
+                    help="also time the oracle on one thread (on a quarter of the batch; slow)")
+    ap.add_argument("--probe-step", default=None,
+                    help="time this step for the roofline instead of the slowest one "
+                         "(config 4: BLOCK:STEP)")
+    ap.add_argument("--no-survey", action="store_true",
+                    help="config 4 only: skip the per-block survey (the roofline kernel is then "
+                         "--probe-step BLOCK:STEP, default 2:dw_bwd)")
+    ap.add_argument("--only-block", type=int, default=0,
+                    help="config 4 only: time block B (1-16) of the chain alone, at its real shape "
+                         "and on its real input (for profiling one block)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (for scaling rocprofv3 "
+                         "FETCH_SIZE/WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    if args.op:
+        print(json.dumps(run_op(args)))
+        return 0
+    if args.config != 4:
+        print(json.dumps(run_block(args, args.config, args.steps, args.warmup,
+                                   not args.no_cpu_baseline)))
+        return 0
+    if args.mode != "train":
+        print("bench.py: --mode eval covers the single-block configs 0-3", file=sys.stderr)
+        return 2
+    result = run_chain(args)
+    if args.pmc_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    if not args.no_others and not args.only_block:
+        # the single-block configs in the same run, so that one line shows every workload
+        others = {}
+        saved_probe, args.probe_step = args.probe_step, None
+        for cfg in (1, 2, 3):
+            r = run_block(args, cfg, max(args.steps, 50), max(args.warmup, 5),
+                          not args.no_cpu_baseline, distribution=False)
+            keep = {k: r[k] for k in ("value", "unit", "ms_per_step", "dtype", "steps", "roofline_next",
+                                      "step_roofline", "launch_steps") if k in r}
+            keep["block"] = r["config"]["block"]
+            keep["roofline"] = {k: r["roofline"][k] for k in ("kernel", "achieved", "frac", "traffic",
+                                                              "kernel_ms", "algorithmic_bytes")}
+            if "cpu_baseline" in r:
+                keep["cpu_baseline"] = r["cpu_baseline"]
+            others[f"config{cfg}"] = keep
+        args.probe_step = saved_probe
+        result["other_configs"] = others
     print(json.dumps(result))
     return 0
 

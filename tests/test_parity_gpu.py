@@ -184,96 +184,70 @@ def test_backward_is_bitwise_repeatable():
 
 
 def _rounding_model(s, t, mfma_bf16=False):
-    """The oracle's steps with bf16 rounding inserted at exactly the places where the HIP
-    path stores an activation-sized tensor (e, d, p, out, G, dy1, dx); everything else fp64.
-    `mfma_bf16`: the block's 1x1 convolutions run on the bf16 matrix cores, whose operands are
-    rounded to bf16 once after the fp32 prologue (sc = Swish(BN2(d))*g, dp and de, the
-    BN-backward outputs); accumulation stays fp32."""
-    from mbconv_inputs import round_to_bf16
-
-    def rb(a):
-        return round_to_bf16(a.astype(np.float32)).astype(np.float64)
-
-    if getattr(s, "activation", "swish") == "relu6":
-        def swish(v):  # the block's activation: ReLU6 here
-            return np.minimum(np.maximum(v, 0.0), 6.0)
-
-        def swish_grad(v):
-            return ((v > 0.0) & (v < 6.0)).astype(np.float64)
-    else:
-        def swish(v):
-            return v / (1.0 + np.exp(-v))
-
-        def swish_grad(v):
-            sg = 1.0 / (1.0 + np.exp(-v))
-            return sg * (1.0 + v * (1.0 - sg))
-
-    x, dout = t["x"].astype(np.float64), t["dout"].astype(np.float64)
-    e = rb(orc.conv1x1(t["w_expand"], x))
-    y1, xh1, _, v1, _, _ = orc.bn_fwd(e, t["bn1_gamma"], t["bn1_beta"], s.eps, s.momentum)
-    a1 = swish(y1)
-    d = rb(orc.depthwise_fwd(t["w_dw"], a1, s.stride, s.pad))
-    y2, xh2, _, v2, _, _ = orc.bn_fwd(d, t["bn2_gamma"], t["bn2_beta"], s.eps, s.momentum)
-    a2 = swish(y2)
-    has_se = getattr(s, "has_se", True)
-    se = orc.se_fwd(a2, t["se_w1"], t["se_b1"], t["se_w2"], t["se_b2"]) if has_se else None
-    ro = rb if mfma_bf16 else (lambda v: v)  # rounding of matrix-core operands
-    sc_op = ro(se.sc if has_se else a2)
-    p = rb(orc.conv1x1(t["w_proj"], sc_op))
-    y3, xh3, _, v3, _, _ = orc.bn_fwd(p, t["bn3_gamma"], t["bn3_beta"], s.eps, s.momentum)
-    out = rb(y3 + (x if s.residual else 0.0))
-    dp, dg3, db3 = orc.bn_bwd(dout, xh3, t["bn3_gamma"], v3, s.eps)
-    dp_op = ro(dp)
-    G = rb(orc.conv1x1_bwd_input(t["w_proj"], dp_op))
-    g = {"w_proj": orc.conv1x1_bwd_weight(sc_op, dp_op), "bn3_gamma": dg3, "bn3_beta": db3}
-    if has_se:
-        sb = orc.se_bwd(a2, t["se_w1"], t["se_w2"], se, G)
-        g.update(se_w1=sb.dw1, se_b1=sb.db1, se_w2=sb.dw2, se_b2=sb.db2)
-        da2 = sb.da2
-    else:
-        da2 = G
-    dd, g["bn2_gamma"], g["bn2_beta"] = orc.bn_bwd(da2 * swish_grad(y2), xh2, t["bn2_gamma"], v2,
-                                                   s.eps)
-    g["w_dw"] = orc.depthwise_bwd_weight(a1, dd, s.k, s.stride, s.pad)
-    da1 = orc.depthwise_bwd_input(t["w_dw"], dd, s.H, s.W, s.stride, s.pad)
-    dy1 = rb(da1 * swish_grad(y1))
-    de, g["bn1_gamma"], g["bn1_beta"] = orc.bn_bwd(dy1, xh1, t["bn1_gamma"], v1, s.eps)
-    de_op = ro(de)
-    g["w_expand"] = orc.conv1x1_bwd_weight(x, de_op)
-    dx = rb(orc.conv1x1_bwd_input(t["w_expand"], de_op) + (dout if s.residual else 0.0))
-    return {"out": out, "e": e, "d": d, "p": p, "dx": dx, "grads": g}
+    """The oracle's steps with bf16 rounding at the HIP path's storage points (and, with
+    `mfma_bf16`, at the operands of the bf16 matrix-core kernels): tests/rounding_model.py."""
+    from rounding_model import rounding_model
+    return rounding_model(s, t, storage=True, mfma_bf16=mfma_bf16)
 
 
-@pytest.mark.parametrize("name", ["bf16_small", "config3_n16"])
+@pytest.mark.parametrize("name", ["bf16_small", "config3_n16", "config3"])
 def test_bf16_matches_rounding_model(name):
     """bf16 storage: element-wise agreement with the oracle steps once the same storage
     rounding is applied.  A value within fp32 noise of a bf16 rounding boundary may round the
     other way (one bf16 ulp = 2^-7 of the value) and a flipped input can flip the tensor stored
     after it, so the bound is two bf16 ulps, 2^-6, under the element-wise metric that the
-    unrounded oracle cannot be held to."""
-    s = SMALL["bf16_small"] if name == "bf16_small" else CONFIG3.with_batch(16)
+    unrounded oracle cannot be held to.  Every bound used here is fixed by a CPU test that
+    involves no HIP code (tests/test_bf16_bounds.py): noise of fp32 size ahead of the roundings
+    of the fp64 model itself moves `out` by up to 2^-6 + 1.5e-3 (a flip of p is scaled by BN3
+    before out is rounded again) and BN1's gamma gradient, the small residual of a heavily
+    cancelling sum, by more than 2^-6 at batch 16 but never by 2^-5; everything else stays within
+    2^-6.  "config3" is the benchmark configuration at its stated batch of 128; for it the
+    distance of the HIP path and of the model from the UNROUNDED oracle is reported under both
+    metrics (element-wise rms-floored / relative to the largest magnitude)."""
+    s = {"bf16_small": SMALL["bf16_small"], "config3_n16": CONFIG3.with_batch(16),
+         "config3": CONFIG3}[name]
     t = make_block_inputs(s, seed=5)
     print(f"[parity/bf16-model] {name}", flush=True)
     res, blk = run_gpu_block(s, t)
     # config 3's channel counts route every 1x1 convolution and weight gradient through the bf16
     # matrix-core kernels; the small shape stays on the register-direct fp32-MFMA kernels
-    m = _rounding_model(s, t, mfma_bf16=(name == "config3_n16"))
-    errs = {"out": rel_err(res["out"], m["out"]), "dx": rel_err(res["dx"], m["dx"])}
-    for n in ("e", "d", "p"):
-        errs[n] = rel_err(blk.saved_tensor(n), m[n])
+    m = _rounding_model(s, t, mfma_bf16=(name != "bf16_small"))
+    got = {"out": res["out"], "dx": res["dx"], **{n: blk.saved_tensor(n) for n in ("e", "d", "p")}}
+    errs = {n: rel_err(got[n], m[n]) for n in got}
     gerrs = {n: rel_err(res["grads"][n], m["grads"][n]) for n in res["grads"]}
     print(errs, gerrs, flush=True)
-    assert max(errs.values()) <= 2.0 ** -6, errs
-    # BN1's gamma gradient is the small residual of a heavily cancelling sum (BN2 makes the loss
-    # almost invariant to the scale of a1).  With the three extra operand roundings of the
-    # matrix-core path, fp32-level noise (1e-7 relative) ahead of the roundings of the fp64 model
-    # itself moves that tensor by 2.1e-2 to 2.7e-2 under this metric (boundary flips act as
-    # independent rounding noise), so no fp32 implementation can be held to two ulps there: four.
-    bounds = {n: 2.0 ** -6 for n in gerrs}
-    if name == "config3_n16":
+    two = 2.0 ** -6
+    sbounds = {"out": two + 1.5e-3, "e": two, "d": two, "p": two, "dx": two}
+    bad = {n: (v, sbounds[n]) for n, v in errs.items() if v > sbounds[n]}
+    assert not bad, bad
+    bounds = {n: two for n in gerrs}
+    if name != "bf16_small":
         bounds["bn1_gamma"] = 2.0 ** -5
     bad = {n: (v, bounds[n]) for n, v in gerrs.items() if v > bounds[n]}
     assert not bad, bad
+    if name == "config3":
+        from parity_util import linf_err
+        f, b = orc.mbconv_step(s, t)
+        ref = {"out": f.out, "e": f.tape["e"], "d": f.tape["d"], "p": f.tape["p"], "dx": b.dx}
+        table = {}
+        for n, r in list(ref.items()) + list(b.grads.items()):
+            g_ = got[n] if n in got else res["grads"][n]
+            m_ = m[n] if n in m else m["grads"][n]
+            table[n] = {"hip_elementwise": rel_err(g_, r), "hip_linf": linf_err(g_, r),
+                        "model_elementwise": rel_err(m_, r), "model_linf": linf_err(m_, r)}
+        print("[parity/bf16-model] config 3 at batch 128 against the unrounded oracle "
+              "(HIP element-wise / linf; rounding model element-wise / linf):", flush=True)
+        for n, v in table.items():
+            print(f"  {n:10s} {v['hip_elementwise']:.4f} / {v['hip_linf']:.4f}    "
+                  f"{v['model_elementwise']:.4f} / {v['model_linf']:.4f}", flush=True)
+        import json
+        import os
+        d = os.environ.get("MBCONV_PARITY_REPORT_DIR", "")
+        if d and os.path.isdir(d):
+            with open(os.path.join(d, "config3_bf16_both_metrics.json"), "w") as fh:
+                json.dump(table, fh, indent=1)
+        # relative to the largest magnitude the HIP path is inside the benchmark's 2e-2
+        assert all(v["hip_linf"] <= TOL["bf16"]["grad"] for v in table.values()), table
 
 
 def _oracle_chain(blocks, seed0=100):
