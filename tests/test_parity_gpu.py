@@ -269,15 +269,21 @@ def _oracle_chain(blocks, seed0=100):
     return recs
 
 
-def test_b0_chain_matches_oracle():
-    """The 16 MBConv blocks of EfficientNet-B0 (benchmark config 4) at batch 4: every block is
-    run on the GPU from the oracle's input and upstream gradient (isolated, standard tolerances),
-    and the chain is also run end to end on the GPU (block i fed by GPU block i-1)."""
+@pytest.mark.parametrize("batch", [4, 64])
+def test_b0_chain_matches_oracle(batch):
+    """The 16 MBConv blocks of EfficientNet-B0 (benchmark config 4), at batch 4 and at the
+    stated batch of 64 (kernel selection, tile shapes and split counts depend on the batch):
+    every block is run on the GPU from the oracle's input and upstream gradient (isolated,
+    standard tolerances), and the chain is also run end to end on the GPU (block i fed by GPU
+    block i-1) with ONE scratch workspace shared by all blocks, sized to the largest request:
+    the arrangement bench.py times."""
     import torch
+    from paper_2110_10802_amd import binding as B
     from paper_2110_10802_amd.harness import DeviceBlock, to_numpy
 
-    blocks = b0_chain(N=4)
+    blocks = b0_chain(N=batch)
     recs = _oracle_chain(blocks)
+    print(f"[parity/chain] oracle chain at batch {batch} done", flush=True)
     # isolated
     failures = []
     for i, r in enumerate(recs):
@@ -285,40 +291,57 @@ def test_b0_chain_matches_oracle():
         t = dict(r["t"])
         t["x"] = np.asarray(t["x"], dtype=np.float32)
         t["dout"] = np.asarray(r["dout"], dtype=np.float32)
-        print(f"[parity/chain] block {i + 1} {s.Cin}->{s.Cexp}->{s.Cout} {s.H}x{s.W} k{s.k}s{s.stride}",
-              flush=True)
+        print(f"[parity/chain] N={batch} block {i + 1} {s.Cin}->{s.Cexp}->{s.Cout} {s.H}x{s.W} "
+              f"k{s.k}s{s.stride}", flush=True)
         res, blk = run_gpu_block(s, t)
         # the oracle saw float64 x/dout; the GPU their float32 roundings (1e-7, far below tolerance)
         try:
             compare_block(s, t, res, r["f"], r["b"], blk)
         except AssertionError as exc:  # keep going: report every failing block at once
             failures.append(f"block {i + 1}: {str(exc).splitlines()[0]}")
-        del blk
+        del blk, res
+        # only the block's output, input gradient and parameter gradients are needed below
+        r["f"].tape = None
+    torch.cuda.empty_cache()
     assert not failures, "\n".join(failures)
-    # end to end
+    # end to end, one shared scratch workspace
+    scratch_bytes = max(B.mbconv_workspace_size(B.make_desc(r["shape"]))[1] for r in recs)
+    scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device="cuda")
     dev = []
     x = None
     for i, r in enumerate(recs):
-        blk = DeviceBlock(r["shape"], r["t"])
+        blk = DeviceBlock(r["shape"], r["t"], scratch=scratch)
+        assert blk.scratch.data_ptr() == scratch.data_ptr()
         xin = blk.to_device(r["t"]["x"]) if i == 0 else x
         blk.forward(xin)
         dev.append((blk, xin))
         x = blk.out
     torch.cuda.synchronize()
-    assert rel_err(to_numpy(dev[-1][0].out), recs[-1]["f"].out) <= 1e-3
+    e2e = {"out": rel_err(to_numpy(dev[-1][0].out), recs[-1]["f"].out)}
     dout = dev[-1][0].to_device(recs[-1]["t"]["dout"])
     for blk, xin in reversed(dev):
         blk.backward(xin, dout)
         dout = blk.dx
     torch.cuda.synchronize()
-    assert rel_err(to_numpy(dev[0][0].dx), recs[0]["b"].dx) <= 1e-2
-    for (blk, _), r in zip(dev, recs):
+    e2e["dx"] = rel_err(to_numpy(dev[0][0].dx), recs[0]["b"].dx)
+    worst = ("", 0.0)
+    for i, ((blk, _), r) in enumerate(zip(dev, recs)):
         # d(beta3) of an inner block is zero by invariance (see compare_block): absolute floor
         d = np.asarray(r["dout"], dtype=np.float64)
         beta_floor = float(np.sqrt(np.mean(d * d)) * np.sqrt(d.size / d.shape[1]))
         for n, g in blk.grads.items():
             floor = beta_floor if n == "bn3_beta" else 0.0
-            assert rel_err(to_numpy(g), r["b"].grads[n], floor) <= 1e-2, (r["shape"], n)
+            err = rel_err(to_numpy(g), r["b"].grads[n], floor)
+            if err > worst[1]:
+                worst = (f"block{i + 1}.{n}", err)
+    e2e["worst_grad"] = worst
+    print(f"[parity/chain] N={batch} end to end (shared scratch): {e2e}", flush=True)
+    # End to end the GPU blocks see each other's outputs, so rounding differences compound over
+    # 16 blocks forward and 16 back (each block's BN renormalises, which keeps the growth about
+    # linear in depth): ten times the single-block bounds.
+    assert e2e["out"] <= 1e-3, e2e
+    assert e2e["dx"] <= 1e-2, e2e
+    assert worst[1] <= 1e-2, e2e
 
 
 @pytest.mark.parametrize("index", [0, 1, 4, 6])
