@@ -29,6 +29,7 @@ typedef enum {
     DNNOPS_OK = 0,
     DNNOPS_EINVAL = -1,       /* NULL pointer, non-positive size */
     DNNOPS_EUNSUPPORTED = -2, /* cols > DNNOPS_MAX_COLS */
+    DNNOPS_ESCRATCH = -3,     /* the shape needs more scratch than the library's static buffer holds */
     DNNOPS_EALIGN = -4,       /* pointer not 16-byte aligned */
     DNNOPS_EHIP = -5          /* a launch failed */
 } dnnops_status;
@@ -61,6 +62,22 @@ dnnops_status dnnops_layernorm_backward(const float *x, const float *dy, const f
                                         const float *mean, const float *rstd, int32_t rows,
                                         int32_t cols, float *dx, float *dgamma, float *dbeta,
                                         void *scratch, void *hip_stream);
+
+/* The same backward pass for callers that cannot allocate device memory or pass a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and kernels as dnnops_layernorm_backward without `scratch`: the partial
+ * sums live in a buffer of dnnops_layernorm_backward_noalloc_max_scratch_bytes() (8 MiB) that is
+ * part of the library's device code, one copy per GPU, held until the process ends.  The call
+ * allocates and frees nothing.  A shape for which dnnops_layernorm_backward_scratch_bytes(rows,
+ * cols) exceeds that size is rejected with DNNOPS_ESCRATCH on the host, before any launch (every
+ * shape with cols <= 2048 fits, whatever rows is).  All calls on one GPU share that GPU's buffer:
+ * the buffer keeps the previous call's contents, every value a call reads it has written itself
+ * first, and calls that overlap on one GPU (different streams, or threads) race: serialise them. */
+size_t dnnops_layernorm_backward_noalloc_max_scratch_bytes(void);
+dnnops_status dnnops_layernorm_backward_noalloc(const float *x, const float *dy, const float *gamma,
+                                                const float *mean, const float *rstd, int32_t rows,
+                                                int32_t cols, float *dx, float *dgamma,
+                                                float *dbeta, void *hip_stream);
 
 /* y[r][c] = exp(x[r][c] - max_c x[r][.]) / sum_c exp(x[r][c] - max_c x[r][.]).  y may alias x. */
 dnnops_status dnnops_softmax_forward(const float *x, float *y, int32_t rows, int32_t cols,

@@ -17,6 +17,8 @@
 #include "mbconv_dev.h"
 #include "mbconv_launch.h"
 
+#include <mutex>
+
 namespace mbk {
 namespace {
 
@@ -430,6 +432,38 @@ int ln_slices(int rows) // row slices of the generic column sums
 
 using namespace mbk;
 
+// ---- scratch for callers that cannot allocate --------------------------------------------------
+// dnnops_layernorm_backward_noalloc keeps the partial sums of the two weight gradients in this
+// array instead of a caller's workspace.  One copy exists on every GPU the library runs on, from
+// the time the code object is loaded until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress: the device address is looked up once per device, with
+// that device current, and kept in g_ln_scratch_ptr; kernels and the second stage receive that
+// address as an ordinary pointer argument.
+#define DNNOPS_STATIC_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) unsigned char ln_static_scratch[DNNOPS_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_ln_scratch_mutex;
+void *g_ln_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of ln_static_scratch (nullptr on failure).
+void *ln_static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return nullptr;
+    std::lock_guard<std::mutex> lock(g_ln_scratch_mutex);
+    if (!g_ln_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(ln_static_scratch)) != hipSuccess || !ptr)
+            return nullptr;
+        g_ln_scratch_ptr[dev] = ptr;
+    }
+    return g_ln_scratch_ptr[dev];
+}
+} // namespace
+
 extern "C" {
 
 dnnops_status dnnops_mish_forward(const float *x, float *y, size_t n, void *hip_stream)
@@ -498,19 +532,26 @@ size_t dnnops_layernorm_backward_scratch_bytes(int32_t rows, int32_t cols)
     return 2 * parts * (size_t)cols * sizeof(float);
 }
 
-dnnops_status dnnops_layernorm_backward(const float *x, const float *dy, const float *gamma,
-                                        const float *mean, const float *rstd, int32_t rows,
-                                        int32_t cols, float *dx, float *dgamma, float *dbeta,
-                                        void *scratch, void *hip_stream)
+static dnnops_status layernorm_backward_check(const float *x, const float *dy, const float *gamma,
+                                              const float *mean, const float *rstd, int32_t rows,
+                                              int32_t cols, float *dx, float *dgamma, float *dbeta)
 {
-    if (!x || !dy || !gamma || !mean || !rstd || !dx || !dgamma || !dbeta || !scratch || rows < 1 ||
-        cols < 1)
+    if (!x || !dy || !gamma || !mean || !rstd || !dx || !dgamma || !dbeta || rows < 1 || cols < 1)
         return DNNOPS_EINVAL;
     if (cols > DNNOPS_MAX_COLS)
         return DNNOPS_EUNSUPPORTED;
-    if (bad_align(x) || bad_align(dy) || bad_align(gamma) || bad_align(dx) || bad_align(scratch))
+    if (bad_align(x) || bad_align(dy) || bad_align(gamma) || bad_align(dx))
         return DNNOPS_EALIGN;
-    hipStream_t st = (hipStream_t)hip_stream;
+    return DNNOPS_OK;
+}
+
+// Both entry points: dx and the per-workgroup partial sums of dgamma, dbeta into `scratch`, then
+// their fixed-order sum.  Every partial the second stage reads is written by the first.
+static dnnops_status layernorm_backward_launch(const float *x, const float *dy, const float *gamma,
+                                               const float *mean, const float *rstd, int32_t rows,
+                                               int32_t cols, float *dx, float *dgamma, float *dbeta,
+                                               void *scratch, hipStream_t st)
+{
     const int nv = row_nv(cols);
     int parts;
     float *pg = (float *)scratch;
@@ -536,6 +577,42 @@ dnnops_status dnnops_layernorm_backward(const float *x, const float *dy, const f
         hipSuccess)
         return DNNOPS_EHIP;
     return DNNOPS_OK;
+}
+
+dnnops_status dnnops_layernorm_backward(const float *x, const float *dy, const float *gamma,
+                                        const float *mean, const float *rstd, int32_t rows,
+                                        int32_t cols, float *dx, float *dgamma, float *dbeta,
+                                        void *scratch, void *hip_stream)
+{
+    if (!scratch)
+        return DNNOPS_EINVAL;
+    const dnnops_status s = layernorm_backward_check(x, dy, gamma, mean, rstd, rows, cols, dx, dgamma, dbeta);
+    if (s != DNNOPS_OK)
+        return s;
+    if (bad_align(scratch))
+        return DNNOPS_EALIGN;
+    return layernorm_backward_launch(x, dy, gamma, mean, rstd, rows, cols, dx, dgamma, dbeta, scratch,
+                                     (hipStream_t)hip_stream);
+}
+
+size_t dnnops_layernorm_backward_noalloc_max_scratch_bytes(void) { return DNNOPS_STATIC_SCRATCH_BYTES; }
+
+dnnops_status dnnops_layernorm_backward_noalloc(const float *x, const float *dy, const float *gamma,
+                                                const float *mean, const float *rstd, int32_t rows,
+                                                int32_t cols, float *dx, float *dgamma,
+                                                float *dbeta, void *hip_stream)
+{
+    const dnnops_status s = layernorm_backward_check(x, dy, gamma, mean, rstd, rows, cols, dx, dgamma, dbeta);
+    if (s != DNNOPS_OK)
+        return s;
+    // host-side size check ahead of any HIP call
+    if (dnnops_layernorm_backward_scratch_bytes(rows, cols) > DNNOPS_STATIC_SCRATCH_BYTES)
+        return DNNOPS_ESCRATCH;
+    void *scratch = ln_static_scratch_ptr();
+    if (!scratch)
+        return DNNOPS_EHIP;
+    return layernorm_backward_launch(x, dy, gamma, mean, rstd, rows, cols, dx, dgamma, dbeta, scratch,
+                                     (hipStream_t)hip_stream);
 }
 
 static dnnops_status softmax_launch(bool bwd, const float *in0, const float *in1, float *out,

@@ -10,6 +10,7 @@ from . import binding as _B
 
 EXPORTS = ["dnnops_mish_forward", "dnnops_mish_backward", "dnnops_layernorm_forward",
            "dnnops_layernorm_backward_scratch_bytes", "dnnops_layernorm_backward",
+           "dnnops_layernorm_backward_noalloc_max_scratch_bytes", "dnnops_layernorm_backward_noalloc",
            "dnnops_softmax_forward", "dnnops_softmax_backward"]
 MAX_COLS = 8192
 _ready = False
@@ -32,10 +33,13 @@ def load():
         lib.dnnops_layernorm_backward_scratch_bytes.argtypes = [i32, i32]
         lib.dnnops_layernorm_backward_scratch_bytes.restype = C.c_size_t
         lib.dnnops_layernorm_backward.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+        lib.dnnops_layernorm_backward_noalloc.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+        lib.dnnops_layernorm_backward_noalloc_max_scratch_bytes.argtypes = []
+        lib.dnnops_layernorm_backward_noalloc_max_scratch_bytes.restype = C.c_size_t
         lib.dnnops_softmax_forward.argtypes = [vp, vp, i32, i32, vp]
         lib.dnnops_softmax_backward.argtypes = [vp, vp, vp, i32, i32, vp]
         for n in EXPORTS:
-            if n != "dnnops_layernorm_backward_scratch_bytes":
+            if not n.endswith("scratch_bytes"):
                 getattr(lib, n).restype = C.c_int
         _ready = True
     return lib
@@ -78,6 +82,18 @@ def layernorm_backward(x, dy, gamma, mean, rstd, rows: int, cols: int, dx, dgamm
                                             rows, cols, _ptr(dx), _ptr(dgamma), _ptr(dbeta),
                                             _ptr(scratch), stream or None),
            "dnnops_layernorm_backward")
+
+
+def layernorm_backward_noalloc_max_scratch_bytes() -> int:
+    return int(load().dnnops_layernorm_backward_noalloc_max_scratch_bytes())
+
+
+def layernorm_backward_noalloc(x, dy, gamma, mean, rstd, rows: int, cols: int, dx, dgamma, dbeta,
+                               stream: int = 0) -> None:
+    _check(load().dnnops_layernorm_backward_noalloc(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean),
+                                                    _ptr(rstd), rows, cols, _ptr(dx), _ptr(dgamma),
+                                                    _ptr(dbeta), stream or None),
+           "dnnops_layernorm_backward_noalloc")
 
 
 def softmax_forward(x, y, rows: int, cols: int, stream: int = 0) -> None:

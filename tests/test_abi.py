@@ -41,6 +41,11 @@ def test_library_exports_every_dnnops_symbol():
     assert D.layernorm_backward_scratch_bytes(0, 8) == 0
     assert D.layernorm_backward_scratch_bytes(4096, 1024) == 2 * 256 * 1024 * 4
     assert D.layernorm_backward_scratch_bytes(100000, 1024) == 2 * 512 * 1024 * 4
+    # the entry point without a workspace argument: its size limit is checked on the host
+    assert D.layernorm_backward_noalloc_max_scratch_bytes() == 8 << 20
+    assert lib.dnnops_layernorm_backward_noalloc(16, 32, 48, 64, 80, 100000, 8192, 96, 112, 128, None) == -3
+    assert lib.dnnops_layernorm_backward_noalloc(16, 32, 48, 64, 80, 0, 8, 96, 112, 128, None) == -1
+    assert lib.dnnops_layernorm_backward_noalloc(16, 36, 48, 64, 80, 4, 8, 96, 112, 128, None) == -4
 
 
 def test_status_strings():
