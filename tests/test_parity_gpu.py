@@ -426,12 +426,12 @@ def test_b0_chain_matches_oracle(batch):
                 worst = (f"block{i + 1}.{n}", err)
     e2e["worst_grad"] = worst
     print(f"[parity/chain] N={batch} end to end (shared scratch): {e2e}", flush=True)
-    # End to end the GPU blocks see each other's outputs, so rounding differences compound over
-    # 16 blocks forward and 16 back (each block's BN renormalises, which keeps the growth about
-    # linear in depth): ten times the single-block bounds.
-    assert e2e["out"] <= 1e-3, e2e
-    assert e2e["dx"] <= 1e-2, e2e
-    assert worst[1] <= 1e-2, e2e
+    # End to end the GPU blocks see each other's outputs, so rounding differences could compound
+    # over 16 blocks forward and 16 back; each block's BN renormalises and they do not: the chain
+    # is held to the single-block bounds (measured: out 2.5e-5, dx 1.1e-4, worst gradient 6.5e-5).
+    assert e2e["out"] <= TOL["f32"]["fwd"], e2e
+    assert e2e["dx"] <= TOL["f32"]["grad"], e2e
+    assert worst[1] <= TOL["f32"]["grad"], e2e
 
 
 @pytest.mark.parametrize("index", [0, 1, 4, 6])
