@@ -547,7 +547,10 @@ bool big_conv_plan(int N, int M, int K, int HW, int *wt, int *qtiles, int *split
     return true;
 }
 
-template <typename T, int WM, int WP, int VEC, int D = 3>
+#ifndef MBK_BIG_D
+#define MBK_BIG_D 3
+#endif
+template <typename T, int WM, int WP, int VEC, int D = MBK_BIG_D>
 static hipError_t big_conv_dispatch(const BigConvArgs &a, int pro, int epi, dim3 grid, hipStream_t st)
 {
 #define MBK_CASE(P, E)                                                                            \

@@ -474,7 +474,9 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256, (TPP > 256 && K == 3) ? 8 : 
 static bool dw2_shape(const DwShape &s, int *tpp)
 {
     const int inRuns = s.H * ((s.W + 3) / 4), outRuns = s.Ho * ((s.Wo + 3) / 4);
-    for (int t : {64, 256, 1024}) {
+    // (16 threads per plane: the 14x14 -> 7x7 planes of the late stages, four planes per
+    // wavefront with nearly every lane busy; with 64 threads 28 of them had input runs)
+    for (int t : {16, 64, 256, 1024}) {
         if (inRuns <= 4 * t && outRuns <= t) {
             *tpp = t;
             return true;
@@ -537,8 +539,11 @@ static hipError_t dw2_launch(KERN kern, const Dw2Args &a, int tpp, size_t lds, h
 #define MBK_DW2_TPP(KERNEL, T, K, EXP, GVO)                                                       \
     {                                                                                             \
         if (s.W % 4 != 0) /* ragged rows: only the small planes of the late stages */             \
-            return tpp == 64 ? dw2_launch(KERNEL<T, K, 64, EXP, 1, 2>, a, tpp, lds, st)           \
-                             : dw2_launch(KERNEL<T, K, 256, EXP, 1, 2>, a, tpp, lds, st);         \
+            return tpp == 16   ? dw2_launch(KERNEL<T, K, 16, EXP, 1, 2>, a, tpp, lds, st)         \
+                   : tpp == 64 ? dw2_launch(KERNEL<T, K, 64, EXP, 1, 2>, a, tpp, lds, st)         \
+                               : dw2_launch(KERNEL<T, K, 256, EXP, 1, 2>, a, tpp, lds, st);       \
+        if (tpp == 16)                                                                            \
+            return dw2_launch(KERNEL<T, K, 16, EXP, GVO, 4>, a, tpp, lds, st);                    \
         if (tpp == 64)                                                                            \
             return dw2_launch(KERNEL<T, K, 64, EXP, GVO, 4>, a, tpp, lds, st);                    \
         if (tpp == 256)                                                                           \

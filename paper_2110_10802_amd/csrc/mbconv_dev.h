@@ -146,14 +146,6 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, FastDiv f)
 
 // ---- reductions ------------------------------------------------------------------------
 
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-        v += __shfl_xor(v, o, kWave);
-    return v;
-}
-
 // Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
 __device__ __forceinline__ float row16_sum(float v)
 {
@@ -162,6 +154,24 @@ __device__ __forceinline__ float row16_sum(float v)
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x122, 0xf, 0xf, false)); // row_ror:2
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x121, 0xf, 0xf, false)); // row_ror:1
     return v;
+}
+
+// Sum over the 64 lanes of the wavefront with DPP only (no LDS crossbar traffic, unlike a
+// butterfly of __shfl_xor, which costs a ds_bpermute per step): four rotations inside each row
+// of 16 lanes, then lane 15 of rows 0 and 2 is added into rows 1 and 3 (row_bcast:15) and lane 31
+// into rows 2 and 3 (row_bcast:31).  Lanes 48..63 end with the total.  Every lane of the
+// wavefront must be active.
+__device__ __forceinline__ float wave_sum_lane63(float v)
+{
+    v = row16_sum(v);
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xa, 0xf, false)); // row_bcast:15
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xc, 0xf, false)); // row_bcast:31
+    return v;
+}
+// The same, with the total broadcast to every lane (v_readlane of lane 63).
+__device__ __forceinline__ float wave_sum(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_sum_lane63(v)), 63));
 }
 
 // Sum over the 32 lanes that share lane/32, by DPP row rotations plus one cross-row exchange.
@@ -182,9 +192,9 @@ __device__ __forceinline__ float half_wave_sum(float v)
 
 // Sum of NV per-thread values over a group of TPP consecutive threads of the block
 // (TPP = 16 or a multiple of 64, groups aligned).  `red` is LDS scratch of at least
-// (blockDim/64)*NV floats.  The result is valid in every thread of the group whose
-// lane index within the group is < NV... for simplicity it is returned in all threads.
-// All threads of the block must call it (it synchronises the block).
+// (blockDim/64)*NV floats.  The result is valid in the first wavefront of every group (callers
+// use it in the group's first thread).  All threads of the block must call it (it synchronises
+// the block when TPP > 64).
 template <int NV, int TPP>
 __device__ __forceinline__ void group_sum(float (&v)[NV], float *red)
 {
@@ -194,25 +204,33 @@ __device__ __forceinline__ void group_sum(float (&v)[NV], float *red)
             v[i] = row16_sum(v[i]);
         return;
     }
+    if (TPP == kWave) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            v[i] = wave_sum(v[i]);
+        return;
+    }
+    // several wavefronts per group: lane 63 of each leaves its wavefront's totals in LDS and the
+    // group's first wavefront adds them in wavefront order
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    constexpr int WPG = TPP / kWave;
 #pragma unroll
     for (int i = 0; i < NV; ++i)
-        v[i] = wave_sum(v[i]);
-    if (TPP > kWave) {
-        const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-        constexpr int WPG = TPP / kWave;
-        __syncthreads();
-        if (lane == 0) {
+        v[i] = wave_sum_lane63(v[i]);
+    __syncthreads();
+    if (lane == kWave - 1) {
 #pragma unroll
-            for (int i = 0; i < NV; ++i)
-                red[wave * NV + i] = v[i];
-        }
-        __syncthreads();
-        const int g0 = (wave / WPG) * WPG;
+        for (int i = 0; i < NV; ++i)
+            red[wave * NV + i] = v[i];
+    }
+    __syncthreads();
+    if (wave % WPG == 0) { // uniform over the wavefront
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             float s = 0.f;
+#pragma unroll
             for (int w = 0; w < WPG; ++w)
-                s += red[(g0 + w) * NV + i];
+                s += red[(wave + w) * NV + i];
             v[i] = s;
         }
     }
