@@ -266,7 +266,7 @@ struct DwBwdDev {
 };
 
 template <typename T, int K, int S, int TPP>
-__global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw_bwd_kernel(DwBwdDev a)
+__global__ __launch_bounds__(TPP > 256 ? TPP : 256, (K == 3 && TPP == 1024) ? 8 : 1) void dw_bwd_kernel(DwBwdDev a)
 {
     constexpr int P = (K - 1) / 2;
     constexpr int BLOCK = TPP > 256 ? TPP : 256;

@@ -355,9 +355,11 @@ __global__ __launch_bounds__(256) void dw4_fwd_multi_kernel(Dw4Args a)
 // ---- backward ----------------------------------------------------------------------------------
 
 // (3x3, up to 256 threads per plane: register allocation held to six wavefronts per SIMD, which
-// the single LDS tile allows; no spills, 0.5 us on the 56x56 plane)
+// the single LDS tile allows; no spills, 0.5 us on the 56x56 plane.  3x3 without BN1 on 1024
+// threads per plane: held to 64 registers so that two of these 16-wavefront workgroups share a
+// CU, as the kernel needs no more than 61 when the allocator is asked to be frugal)
 template <typename T, int K, int TPP, int NG, bool EXPAND>
-__global__ __launch_bounds__(TPP > 256 ? TPP : 256, (K == 3 && TPP <= 256) ? 6 : 1) void dw4_bwd_kernel(Dw4Args a)
+__global__ __launch_bounds__(TPP > 256 ? TPP : 256, (K == 3 && TPP <= 256) ? 6 : ((K == 3 && !EXPAND) ? 8 : 1)) void dw4_bwd_kernel(Dw4Args a)
 {
     constexpr int P = (K - 1) / 2;
     constexpr int BLOCK = TPP > 256 ? TPP : 256;

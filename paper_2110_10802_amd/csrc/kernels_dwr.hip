@@ -182,6 +182,16 @@ __device__ __forceinline__ void window_row(const float *tile, int row, int WP, i
     o[P + 3] = m.w;
 }
 
+// Every wavefront of these kernels works on LDS tiles of its own, so no workgroup barrier is
+// needed: a wavefront's LDS operations execute in order, and this fence keeps the compiler from
+// moving the tile reads above the tile writes of other lanes.  The four wavefronts of a
+// workgroup then run independently instead of at the pace of the slowest.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Lane geometry shared by forward and backward.
 struct DwrLane {
     int c, seg;      // channel and image range of this wavefront
@@ -207,7 +217,7 @@ __device__ __forceinline__ DwrLane dwr_lane(const DwrArgs &a)
     L.lane_ok = L.pw < a.PW;
     L.n_begin = L.seg * a.nper;
     L.n_end = min(a.N, L.n_begin + a.nper);
-    L.iters = (a.nper + a.PW - 1) / a.PW; // the same for every wavefront: barriers stay uniform
+    L.iters = (a.nper + a.PW - 1) / a.PW;
     return L;
 }
 
@@ -260,7 +270,7 @@ __global__ __launch_bounds__(256) void dwr_fwd_kernel(DwrArgs a)
         bn_fin_finish<64>(a.fin, a.C, L.c, lane, L.wave_ok && L.seg == 0, nullptr, fr, scale, shift, mu, rs);
     }
     float acc0 = 0.f, acc1 = 0.f;
-    __syncthreads();
+    wave_lds_sync();
     for (int it = 0; it < L.iters; ++it) {
         float *tile = mine + ((it & 1) * a.PW + (L.lane_ok ? L.pw : 0)) * tileElems;
         const int n = L.n_begin + it * a.PW + L.pw;
@@ -278,7 +288,7 @@ __global__ __launch_bounds__(256) void dwr_fwd_kernel(DwrArgs a)
         }
         if (it + 1 < L.iters)
             cur_ok = prefetch(it + 1);
-        __syncthreads();
+        wave_lds_sync();
         if (ok) {
             float o[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -364,7 +374,7 @@ __global__ __launch_bounds__(256) void dwr_bwd_kernel(DwrArgs a)
 #pragma unroll
     for (int t = 0; t < NV; ++t)
         acc[t] = 0.f;
-    __syncthreads();
+    wave_lds_sync();
     for (int it = 0; it < L.iters; ++it) {
         float *ddt = mine + ((it & 1) * a.PW + (L.lane_ok ? L.pw : 0)) * tileElems;
         const int n = L.n_begin + it * a.PW + L.pw;
@@ -395,7 +405,7 @@ __global__ __launch_bounds__(256) void dwr_bwd_kernel(DwrArgs a)
         }
         if (it + 1 < L.iters)
             cur_ok = prefetch(it + 1);
-        __syncthreads();
+        wave_lds_sync();
         if (ok) {
             float da[4] = {0.f, 0.f, 0.f, 0.f};
             // input gradient  da[r]     = sum_{u,v} wt[u][v] * ddwin[K-1-u][r+K-1-v]

@@ -228,7 +228,6 @@ __device__ __forceinline__ void group_sum(float (&v)[NV], float *red)
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             float s = 0.f;
-#pragma unroll
             for (int w = 0; w < WPG; ++w)
                 s += red[(wave + w) * NV + i];
             v[i] = s;
