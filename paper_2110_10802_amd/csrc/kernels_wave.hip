@@ -524,6 +524,244 @@ __global__ __launch_bounds__(512, DG ? 4 : 1) void wgrad_lt_kernel(WgradClArgs a
         }
 }
 
+// ---- projbwd_nn: the projection conv's backward when BOTH sides fit one 32-channel tile -----------
+// (the block without an expansion conv: 32 -> 16 channels on 112x112 planes in EfficientNet-B0, the
+// layer the paper measured.)  In wgrad_lt a wavefront owns 32 wide channels, so with at most 32 of
+// them one wavefront of the workgroup would stage and multiply everything while the others wait
+// at its barriers.  Here every wavefront is on its own: it takes 32-pixel chunks round-robin,
+// stages the U (dp = BN3's backward of dout, p) and V (sc = Swish(BN2(d))*gate) tiles of its chunk
+// row-wise into LDS tiles of its own, multiplies them channel-lane for the weight gradient (16
+// MFMAs), multiplies W^T (registers) by the U tile read pixel-lane for the data gradient
+// G = W^T dp (ceil(Cn/2) MFMAs), turns G row-wise through its V tile and stores 16 bytes per
+// lane.  No workgroup barrier inside the pixel loop (a wavefront's LDS operations execute in
+// order); the four wavefronts' weight-gradient tiles are added in wavefront order at the end and
+// the workgroups' partial tiles by reduce_splits: fixed order, no atomics.  BN3's backward
+// finalise step runs in the kernel's first 256 threads as in wgrad_lt<..., DG>.
+template <typename T, int PROV>
+__global__ __launch_bounds__(256, 3) void projbwd_nn_kernel(WgradClArgs a)
+{
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x & 63;
+    const int t = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform
+    const int h = lane >> 5, c = lane & 31;
+    float *Ut = lds + t * (2 * 32 * kLtPitch); // this wavefront's [32][pitch]
+    float *Vt = Ut + 32 * kLtPitch;            // this wavefront's [32][pitch]
+    // (registers are what limits the wavefronts per SIMD here: what is constant over the pixel
+    // loop waits in LDS)
+    float *Cl = lds + 4 * (2 * 32 * kLtPitch); // [5][32]: c0, c1, c2 of U's rows, scale and shift of V's
+    float *Wl = Cl + 5 * 32;                   // [16 steps][64 lanes] of W^T in MFMA operand order
+
+    // ---- BN3 backward coefficients of the (at most 32) rows of U: thread (row = tid/8, sub = tid%8)
+    {
+        const int row = threadIdx.x >> 3, sub = threadIdx.x & 7, Cn = a.Ma;
+        const int ch = row < Cn ? row : Cn - 1;
+        float k0, k1, k2;
+        if (a.ufin.psb) {
+            const int NP = a.ufin.NP;
+            const float gm = a.ufin.gamma[ch], mean = a.ufin.bn[2 * Cn + ch];
+            const float rstd = a.ufin.bn[3 * Cn + ch];
+            const float *pb = a.ufin.psb + (size_t)ch * NP, *pr = a.ufin.psr + (size_t)ch * NP;
+            double sb = 0.0, sr = 0.0;
+            for (int i0 = sub; i0 < NP; i0 += 32) {
+                float b0[4], b1[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = min(i0 + 8 * u, NP - 1); // unconditional loads, masked below
+                    b0[u] = pb[i];
+                    b1[u] = pr[i];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (i0 + 8 * u < NP) {
+                        sb += (double)b0[u];
+                        sr += (double)b1[u];
+                    }
+            }
+#pragma unroll
+            for (int o = 4; o > 0; o >>= 1) {
+                sb += __shfl_xor(sb, o, kWave);
+                sr += __shfl_xor(sr, o, kWave);
+            }
+            // c0*dy + c1*raw + c2 (see launch_bn_bwd_finalize): dgamma = sr, dbeta = sb
+            const double c0 = (double)gm * rstd;
+            const double c1 = -c0 * rstd * sr / a.ufin.m;
+            const double c2 = -c0 * sb / a.ufin.m - c1 * mean;
+            k0 = (float)c0;
+            k1 = (float)c1;
+            k2 = (float)c2;
+            if (blockIdx.x == 0 && sub == 0 && row < Cn) {
+                a.ufin.dbeta[ch] = (float)sb;
+                a.ufin.dgamma[ch] = (float)sr;
+                a.ufin.coef[ch] = k0;
+                a.ufin.coef[Cn + ch] = k1;
+                a.ufin.coef[2 * Cn + ch] = k2;
+            }
+        } else {
+            k0 = a.uc0[ch];
+            k1 = a.uc1[ch];
+            k2 = a.uc2[ch];
+        }
+        if (sub == 0) {
+            Cl[row] = k0;
+            Cl[32 + row] = k1;
+            Cl[64 + row] = k2;
+        }
+    }
+    // W^T as the data gradient's A operand: lane (h, c), step kk holds W[a = 2kk + h][b = c]; the
+    // 1024 entries are filled by the 256 threads, four each, loads before stores
+    {
+        float wreg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = threadIdx.x + 256 * i, l = e & 63, kk = e >> 6;
+            const int aa = 2 * kk + (l >> 5), bb = l & 31;
+            const bool ok = aa < a.Ma && bb < a.Mb;
+            wreg[i] = and_mask(ld<T>((const T *)a.dgw, ok ? (size_t)aa * a.Mb + bb : 0), ok ? 0xffffffffu : 0u);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            Wl[threadIdx.x + 256 * i] = wreg[i];
+        if (threadIdx.x < 32) {
+            const int ch = threadIdx.x < a.Mb ? threadIdx.x : a.Mb - 1;
+            Cl[96 + threadIdx.x] = PROV != PRO_NONE ? a.vc0[ch] : 0.f;
+            Cl[128 + threadIdx.x] = PROV != PRO_NONE ? a.vc1[ch] : 0.f;
+        }
+    }
+    // rows this lane stages: lane/8 + 8i of both tiles, pixels [vcol, vcol+4) of the chunk
+    const int vcol = 4 * (lane & 7);
+    int vch[4];
+    uint32_t vro[4], uro[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = (lane >> 3) + 8 * i;
+        vch[i] = row < a.Mb ? row : a.Mb - 1; // rows past the end are computed but never stored
+        vro[i] = (uint32_t)vch[i] * (uint32_t)a.HW;
+        uro[i] = (uint32_t)(row < a.Ma ? row : a.Ma - 1) * (uint32_t)a.HW;
+    }
+    // rows past the end of U must contribute zero to both products: zero coefficients
+    if (threadIdx.x >= 8 * a.Ma && (threadIdx.x & 7) == 0) {
+        const int row = threadIdx.x >> 3;
+        Cl[row] = 0.f;
+        Cl[32 + row] = 0.f;
+        Cl[64 + row] = 0.f;
+    }
+    __syncthreads(); // Cl, Wl
+    const uint32_t vimg = (uint32_t)a.Mb * (uint32_t)a.HW, uimg = (uint32_t)a.Ma * (uint32_t)a.HW;
+    const int kdg = (a.Ma + 1) >> 1;
+
+    float16v acc = (float16v){0};
+    float vv[4][4], vg[4], uu[4][4], ur[4][4];
+    size_t vbase_cur = 0;
+    bool pok = true; // this lane's four pixels exist (false only in a ragged last chunk)
+    auto fetch = [&](int ch) {
+        const uint32_t q = (uint32_t)ch * 32u + (uint32_t)vcol;
+        pok = q < a.Q;
+        const uint32_t qs = pok ? q : 0u;
+        const uint32_t n = fdiv(qs, a.divHW);
+        const uint32_t pix = qs - n * (uint32_t)a.HW;
+        const size_t vbase = (size_t)n * vimg + pix, ubase = (size_t)n * uimg + pix;
+        vbase_cur = vbase;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            load4<T>((const T *)a.v0, vbase + vro[i], vv[i]);
+            if (PROV == PRO_BNSWISH_GATE)
+                vg[i] = a.vgate[(size_t)n * a.Mb + vch[i]];
+            load4<T>((const T *)a.u0, ubase + uro[i], uu[i]);
+            load4<T>((const T *)a.u1, ubase + uro[i], ur[i]);
+        }
+    };
+    const auto body = [&](int ch, auto more) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = (lane >> 3) + 8 * i;
+            lt_prologue<T, PROV>(vv[i], vv[i], Cl[96 + row], Cl[128 + row], 0.f, vg[i]);
+            lt_prologue<T, PRO_BNBWD>(uu[i], ur[i], Cl[row], Cl[32 + row], Cl[64 + row], 0.f);
+            float4v v4 = {vv[i][0], vv[i][1], vv[i][2], vv[i][3]};
+            float4v u4 = {uu[i][0], uu[i][1], uu[i][2], uu[i][3]};
+            if (!pok) {
+                v4 = (float4v){0.f, 0.f, 0.f, 0.f};
+                u4 = (float4v){0.f, 0.f, 0.f, 0.f};
+            }
+            *reinterpret_cast<float4v *>(Vt + ((lane >> 3) + 8 * i) * kLtPitch + vcol) = v4;
+            *reinterpret_cast<float4v *>(Ut + ((lane >> 3) + 8 * i) * kLtPitch + vcol) = u4;
+        }
+        const size_t gbase = vbase_cur;
+        const bool gok = pok;
+        if (decltype(more)::value)
+            fetch(ch + 4 * (int)gridDim.x); // in flight while this chunk is multiplied
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        // weight gradient, channel-lane reads: lane (c, h) takes pixels 8*jj + 4*h + {0..3} of row c
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const float4v bvv = *reinterpret_cast<const float4v *>(Vt + c * kLtPitch + 8 * jj + 4 * h);
+            const float4v avv = *reinterpret_cast<const float4v *>(Ut + c * kLtPitch + 8 * jj + 4 * h);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(avv[r], bvv[r], acc, 0, 0, 0);
+        }
+        // data gradient, pixel-lane reads of the U tile: lane (h, c) takes U[2kk + h][pixel c]
+        float16v accd = (float16v){0};
+#pragma unroll
+        for (int k4 = 0; k4 < 16; k4 += 4) {
+            if (k4 < kdg) { // wave-uniform
+                float dv[4], wv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    dv[u] = Ut[(2 * (k4 + u) + h) * kLtPitch + c];
+                    wv[u] = Wl[(k4 + u) * 64 + lane];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    accd = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[u], dv[u], accd, 0, 0, 0);
+            }
+        }
+        // accumulator register q holds channel row 8*(q/4) + 4h + q%4, pixel c: through the V tile
+        // (its reads are behind us: LDS operations of a wavefront execute in order)
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            Vt[(8 * (q >> 2) + 4 * h + (q & 3)) * kLtPitch + c] = accd[q];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = (lane >> 3) + 8 * i;
+            const float4v g4 = *reinterpret_cast<const float4v *>(Vt + row * kLtPitch + vcol);
+            if (gok && row < a.Mb) {
+                const float o[4] = {g4[0], g4[1], g4[2], g4[3]};
+                store4<T>((T *)a.dgout, gbase + (uint32_t)row * (uint32_t)a.HW, o);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    const int cStep = 4 * (int)gridDim.x, cEnd = a.numChunks;
+    int ch = 4 * (int)blockIdx.x + t;
+    if (ch < cEnd) {
+        fetch(ch);
+        for (; ch + cStep < cEnd; ch += cStep)
+            body(ch, std::true_type{});
+        body(ch, std::false_type{});
+    }
+    // the four wavefronts' tiles, added in wavefront order
+    __syncthreads();
+    float *Rd = lds; // [4][16][64]
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+        Rd[(t * 16 + q) * 64 + lane] = acc[q];
+    __syncthreads();
+    float *dst = a.partial + (size_t)blockIdx.x * a.Ma * a.Mb;
+    for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+        const int q = e >> 6, l = e & 63;
+        const float s = (Rd[e] + Rd[1024 + e]) + (Rd[2048 + e] + Rd[3072 + e]);
+        const int ai = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), bi = l & 31;
+        if (ai < a.Ma && bi < a.Mb)
+            dst[(size_t)ai * a.sOa + (size_t)bi * a.sOb] = s;
+    }
+}
+
 // ---- bwd1x1_lt: data and weight gradient of a narrow->wide 1x1 convolution in one pass ---------
 // The expansion conv's two gradients, dx = W^T de (+ dout) and dW = de x^T, both consume
 // de = c0*dy1 + c1*e + c2 (BN1's backward applied on the fly), two wide tensors that are by far
@@ -940,6 +1178,24 @@ hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const 
         }
     }
     dim3 grid((unsigned)splits), block((unsigned)(64 * nw));
+    if (Cw <= 32 && fin) {
+        // both sides within one tile: every wavefront on its own chunk (projbwd_nn_kernel)
+        const size_t nn_lds = sizeof(float) * (4 * 2 * 32 * kLtPitch + 5 * 32 + 16 * 64);
+#define MBK_NN(T, PV)                                                                             \
+    {                                                                                             \
+        hipLaunchKernelGGL((projbwd_nn_kernel<T, PV>), grid, dim3(256), nn_lds, st, a);           \
+        return hipGetLastError();                                                                 \
+    }
+        if (bf16) {
+            if (sc.pro == PRO_NONE)
+                MBK_NN(bf16_t, PRO_NONE)
+            MBK_NN(bf16_t, PRO_BNSWISH_GATE)
+        }
+        if (sc.pro == PRO_NONE)
+            MBK_NN(float, PRO_NONE)
+        MBK_NN(float, PRO_BNSWISH_GATE)
+#undef MBK_NN
+    }
 #define MBK_CASE(T, PV)                                                                           \
     {                                                                                             \
         auto kern = wgrad_lt_kernel<T, 1, PRO_BNBWD, PV, true>;                                   \

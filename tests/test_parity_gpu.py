@@ -30,6 +30,14 @@ SMALL = {
     "k5s2_odd": _shape(k=5, stride=2, residual=False, Cout=20, H=15, W=13),
     "noexpand": _shape(Cin=24, Cexp=24, Cout=16, has_expand=False, residual=False, H=20, W=20),
     "noexpand_res": _shape(Cin=16, Cexp=16, Cout=16, has_expand=False, residual=True, k=5),
+    # both sides of the projection conv within one 32-channel tile: its backward runs with a
+    # wavefront per pixel chunk (full tiles, ragged channel counts, a ragged last chunk, bf16)
+    "noexpand_32_16": _shape(N=3, Cin=32, Cexp=32, Cse=8, Cout=16, has_expand=False, residual=False,
+                             H=12, W=20),
+    "noexpand_ragged_nn": _shape(N=5, Cin=21, Cexp=21, Cse=5, Cout=10, has_expand=False,
+                                 residual=False, H=6, W=6, k=5),
+    "bf16_noexpand": _shape(dtype="bf16", N=32, Cin=32, Cexp=32, Cse=8, Cout=16, has_expand=False,
+                            residual=False, H=12, W=12),
     "wide": _shape(N=3, Cin=72, Cexp=200, Cse=18, Cout=72, H=7, W=7, k=5),
     "plane_1024_threads": _shape(N=1, Cin=8, Cexp=16, Cout=8, H=70, W=66),
     "plane_256_threads": _shape(N=2, Cin=8, Cexp=16, Cout=8, H=28, W=28, k=5),
@@ -75,7 +83,8 @@ def test_small_block_matches_oracle(name):
     compare_block(s, t, res, f, b, blk)
 
 
-@pytest.mark.parametrize("name", ["k3s1_ragged", "k5s2_odd", "bf16_small", "bf16_ragged"])
+@pytest.mark.parametrize("name", ["k3s1_ragged", "k5s2_odd", "bf16_small", "bf16_ragged",
+                                  "noexpand_32_16"])
 def test_store_policy_matches_oracle(name):
     s = SMALL[name]
     # (bf16_ragged: a seed for which the storage-rounding noise of BN1's gamma gradient, measured
@@ -87,7 +96,8 @@ def test_store_policy_matches_oracle(name):
     compare_block(s, t, res, f, b, blk)
     from parity_util import metric_for
     tol = TOL[s.dtype]["fwd"]
-    assert metric_for(s)(blk.saved_tensor("a1"), f.tape["a1"]) <= tol
+    if s.has_expand:  # (without an expansion conv the depthwise input is x itself: nothing is kept)
+        assert metric_for(s)(blk.saved_tensor("a1"), f.tape["a1"]) <= tol
     assert metric_for(s)(blk.saved_tensor("sc"), f.tape["sc"]) <= tol
 
 
@@ -187,7 +197,7 @@ def test_benchmark_config_matches_oracle(cfg):
     print({k: f"{v[0]:.2e}" for k, v in errs.items()}, flush=True)
 
 
-@pytest.mark.parametrize("name", ["k5s1", "fused_bwd_full", "wide", "k3s2"])
+@pytest.mark.parametrize("name", ["k5s1", "fused_bwd_full", "wide", "k3s2", "noexpand_32_16"])
 def test_backward_is_bitwise_repeatable(name):
     """No floating-point atomics anywhere and every reduction in a fixed order: ten runs of the
     same step give the same bits (each run in freshly allocated buffers)."""
