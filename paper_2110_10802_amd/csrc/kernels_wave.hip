@@ -524,32 +524,77 @@ __global__ __launch_bounds__(512, DG ? 4 : 1) void wgrad_lt_kernel(WgradClArgs a
         }
 }
 
-// ---- projbwd_nn: the projection conv's backward when BOTH sides fit one 32-channel tile -----------
-// (the block without an expansion conv: 32 -> 16 channels on 112x112 planes in EfficientNet-B0, the
-// layer the paper measured.)  In wgrad_lt a wavefront owns 32 wide channels, so with at most 32 of
-// them one wavefront of the workgroup would stage and multiply everything while the others wait
-// at its barriers.  Here every wavefront is on its own: it takes 32-pixel chunks round-robin,
-// stages the U (dp = BN3's backward of dout, p) and V (sc = Swish(BN2(d))*gate) tiles of its chunk
-// row-wise into LDS tiles of its own, multiplies them channel-lane for the weight gradient (16
-// MFMAs), multiplies W^T (registers) by the U tile read pixel-lane for the data gradient
-// G = W^T dp (ceil(Cn/2) MFMAs), turns G row-wise through its V tile and stores 16 bytes per
-// lane.  No workgroup barrier inside the pixel loop (a wavefront's LDS operations execute in
-// order); the four wavefronts' weight-gradient tiles are added in wavefront order at the end and
-// the workgroups' partial tiles by reduce_splits: fixed order, no atomics.  BN3's backward
-// finalise step runs in the kernel's first 256 threads as in wgrad_lt<..., DG>.
-template <typename T, int PROV>
-__global__ __launch_bounds__(256, 3) void projbwd_nn_kernel(WgradClArgs a)
+// Arguments of the expansion conv's fused backward kernel (bwd1x1_lt).
+struct Bwd1x1Args {
+    WgradClArgs g; // U = x (PRO_NONE), V = de (PRO_BNBWD); partial: weight-gradient splits
+    int kbeg[9];   // wavefront t multiplies contraction steps [kbeg[t], kbeg[t+1]) of the data gradient
+    const void *w; // [Mb][Ma] in the activation dtype (wide-major, as the layer stores it)
+    void *dx;      // [N][Ma][HW]
+    const void *res; // optional, added to dx
+};
+
+// ---- wave-per-chunk form of the projection conv's fused backward ---------------------------------
+// In wgrad_lt<..., DG> a workgroup shares one 32-pixel chunk: every wavefront
+// stages 32 wide channels of it and two workgroup barriers per chunk hold all of them to the
+// pace of the slowest (with at most 32 wide channels, the block without an expansion conv, one
+// wavefront did all the work while the others waited).  Here every wavefront is on its own: it
+// takes 32-pixel chunks round-robin and walks the NTW 32-channel tiles of the wide side itself,
+// with LDS tiles of its own, so the pixel loop has no workgroup barrier at all (a wavefront's
+// LDS operations execute in order; a wave-scope fence keeps the compiler from reordering them).
+// The next tile's (and the next chunk's) operands are requested before the current tile is
+// multiplied.  What is constant over the loop (W in MFMA operand order, BN coefficients) waits
+// in LDS tables shared by the workgroup.  The four wavefronts' weight-gradient tiles are added
+// in wavefront order at the end and the workgroups' partial tiles by reduce_splits: fixed
+// order, no atomics.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Adds the four wavefronts' NTW accumulator tiles (rows = narrow channels, columns = wide) in
+// wavefront order, one tile at a time through 16 KB of LDS, and stores them to `dst`.
+template <int NTW>
+__device__ __forceinline__ void wave_tiles_reduce_store(const float16v (&acc)[NTW], float *Rd, int t,
+                                                        int lane, int Ma, int Mb, int sOa, int sOb,
+                                                        float *dst)
+{
+#pragma unroll
+    for (int tt = 0; tt < NTW; ++tt) {
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            Rd[(t * 16 + q) * 64 + lane] = acc[tt][q];
+        __syncthreads();
+        for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+            const int q = e >> 6, l = e & 63;
+            const float s = (Rd[e] + Rd[1024 + e]) + (Rd[2048 + e] + Rd[3072 + e]);
+            const int ai = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), bi = 32 * tt + (l & 31);
+            if (ai < Ma && bi < Mb)
+                dst[(size_t)ai * sOa + (size_t)bi * sOb] = s;
+        }
+    }
+}
+
+// Projection conv backward, Cn <= 32 narrow output channels, Cw <= 32*NTW wide input channels:
+// U = dp (BN3's backward of dout and p, coefficients finalised here from the partial sums as in
+// wgrad_lt<..., DG>), V = sc = act(BN2(d))*gate.  Per chunk and wide tile: the weight gradient
+// dW[a][b] += sum_pix dp[a][pix]*sc[b][pix] (16 MFMAs, both tiles read channel-lane) and the data
+// gradient G[b][pix] = sum_a W[a][b]*dp[a][pix] (ceil(Cn/2) MFMAs, W^T from the LDS table, the U
+// tile read pixel-lane), turned row-wise through the V tile and stored 16 bytes per lane.
+template <typename T, int PROV, int NTW>
+__global__ __launch_bounds__(256, NTW == 1 ? 3 : 2) void projbwd_wave_kernel(WgradClArgs a)
 {
     extern __shared__ float lds[];
+    constexpr int R = 32 * NTW;
     const int lane = threadIdx.x & 63;
     const int t = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform
     const int h = lane >> 5, c = lane & 31;
     float *Ut = lds + t * (2 * 32 * kLtPitch); // this wavefront's [32][pitch]
     float *Vt = Ut + 32 * kLtPitch;            // this wavefront's [32][pitch]
-    // (registers are what limits the wavefronts per SIMD here: what is constant over the pixel
-    // loop waits in LDS)
-    float *Cl = lds + 4 * (2 * 32 * kLtPitch); // [5][32]: c0, c1, c2 of U's rows, scale and shift of V's
-    float *Wl = Cl + 5 * 32;                   // [16 steps][64 lanes] of W^T in MFMA operand order
+    float *Cl = lds + 4 * (2 * 32 * kLtPitch); // [3][32]: c0, c1, c2 of U's rows
+    float *Cv = Cl + 96;                       // [2][R]: scale and shift of V's rows
+    float *Wl = Cv + 2 * R;                    // [NTW][16 steps][64 lanes] of W^T in MFMA operand order
 
     // ---- BN3 backward coefficients of the (at most 32) rows of U: thread (row = tid/8, sub = tid%8)
     {
@@ -602,164 +647,169 @@ __global__ __launch_bounds__(256, 3) void projbwd_nn_kernel(WgradClArgs a)
             k1 = a.uc1[ch];
             k2 = a.uc2[ch];
         }
-        if (sub == 0) {
-            Cl[row] = k0;
-            Cl[32 + row] = k1;
-            Cl[64 + row] = k2;
+        if (sub == 0) { // rows past the end of U must contribute zero to both products
+            Cl[row] = row < Cn ? k0 : 0.f;
+            Cl[32 + row] = row < Cn ? k1 : 0.f;
+            Cl[64 + row] = row < Cn ? k2 : 0.f;
         }
     }
-    // W^T as the data gradient's A operand: lane (h, c), step kk holds W[a = 2kk + h][b = c]; the
-    // 1024 entries are filled by the 256 threads, four each, loads before stores
+    // W^T as the data gradient's A operand: lane (h, c), tile tt, step kk holds
+    // W[a = 2kk + h][b = 32tt + c]; 4*NTW entries per thread, loads before stores
     {
-        float wreg[4];
+        float wreg[4 * NTW];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int e = threadIdx.x + 256 * i, l = e & 63, kk = e >> 6;
-            const int aa = 2 * kk + (l >> 5), bb = l & 31;
+        for (int i = 0; i < 4 * NTW; ++i) {
+            const int e = threadIdx.x + 256 * i, l = e & 63, kk = (e >> 6) & 15, tt = e >> 10;
+            const int aa = 2 * kk + (l >> 5), bb = 32 * tt + (l & 31);
             const bool ok = aa < a.Ma && bb < a.Mb;
             wreg[i] = and_mask(ld<T>((const T *)a.dgw, ok ? (size_t)aa * a.Mb + bb : 0), ok ? 0xffffffffu : 0u);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4 * NTW; ++i)
             Wl[threadIdx.x + 256 * i] = wreg[i];
-        if (threadIdx.x < 32) {
-            const int ch = threadIdx.x < a.Mb ? threadIdx.x : a.Mb - 1;
-            Cl[96 + threadIdx.x] = PROV != PRO_NONE ? a.vc0[ch] : 0.f;
-            Cl[128 + threadIdx.x] = PROV != PRO_NONE ? a.vc1[ch] : 0.f;
+        for (int r = threadIdx.x; r < R; r += 256) {
+            const int ch = r < a.Mb ? r : a.Mb - 1;
+            Cv[r] = PROV != PRO_NONE ? a.vc0[ch] : 0.f;
+            Cv[R + r] = PROV != PRO_NONE ? a.vc1[ch] : 0.f;
         }
     }
-    // rows this lane stages: lane/8 + 8i of both tiles, pixels [vcol, vcol+4) of the chunk
-    const int vcol = 4 * (lane & 7);
-    int vch[4];
-    uint32_t vro[4], uro[4];
+    // rows this lane stages: lane/8 + 8i of a tile, pixels [vcol, vcol+4) of the chunk
+    const int vcol = 4 * (lane & 7), lrow = lane >> 3;
+    uint32_t uro[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int row = (lane >> 3) + 8 * i;
-        vch[i] = row < a.Mb ? row : a.Mb - 1; // rows past the end are computed but never stored
-        vro[i] = (uint32_t)vch[i] * (uint32_t)a.HW;
+        const int row = lrow + 8 * i;
         uro[i] = (uint32_t)(row < a.Ma ? row : a.Ma - 1) * (uint32_t)a.HW;
     }
-    // rows past the end of U must contribute zero to both products: zero coefficients
-    if (threadIdx.x >= 8 * a.Ma && (threadIdx.x & 7) == 0) {
-        const int row = threadIdx.x >> 3;
-        Cl[row] = 0.f;
-        Cl[32 + row] = 0.f;
-        Cl[64 + row] = 0.f;
-    }
-    __syncthreads(); // Cl, Wl
+    __syncthreads(); // Cl, Cv, Wl
     const uint32_t vimg = (uint32_t)a.Mb * (uint32_t)a.HW, uimg = (uint32_t)a.Ma * (uint32_t)a.HW;
     const int kdg = (a.Ma + 1) >> 1;
 
-    float16v acc = (float16v){0};
+    float16v acc[NTW];
+#pragma unroll
+    for (int tt = 0; tt < NTW; ++tt)
+        acc[tt] = (float16v){0};
     float vv[4][4], vg[4], uu[4][4], ur[4][4];
-    size_t vbase_cur = 0;
-    bool pok = true; // this lane's four pixels exist (false only in a ragged last chunk)
-    auto fetch = [&](int ch) {
+    struct Geom {
+        uint32_t n, pix;
+        bool ok; // this lane's four pixels exist (false only in a ragged last chunk)
+    };
+    auto geom = [&](int ch) {
+        Geom g;
         const uint32_t q = (uint32_t)ch * 32u + (uint32_t)vcol;
-        pok = q < a.Q;
-        const uint32_t qs = pok ? q : 0u;
-        const uint32_t n = fdiv(qs, a.divHW);
-        const uint32_t pix = qs - n * (uint32_t)a.HW;
-        const size_t vbase = (size_t)n * vimg + pix, ubase = (size_t)n * uimg + pix;
-        vbase_cur = vbase;
+        g.ok = q < a.Q;
+        const uint32_t qs = g.ok ? q : 0u;
+        g.n = fdiv(qs, a.divHW);
+        g.pix = qs - g.n * (uint32_t)a.HW;
+        return g;
+    };
+    auto fetchU = [&](const Geom &g) {
+        const size_t ubase = (size_t)g.n * uimg + g.pix;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            load4<T>((const T *)a.v0, vbase + vro[i], vv[i]);
-            if (PROV == PRO_BNSWISH_GATE)
-                vg[i] = a.vgate[(size_t)n * a.Mb + vch[i]];
             load4<T>((const T *)a.u0, ubase + uro[i], uu[i]);
             load4<T>((const T *)a.u1, ubase + uro[i], ur[i]);
         }
     };
-    const auto body = [&](int ch, auto more) {
+    auto fetchV = [&](const Geom &g, int tt) {
+        const size_t vbase = (size_t)g.n * vimg + g.pix;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int row = (lane >> 3) + 8 * i;
-            lt_prologue<T, PROV>(vv[i], vv[i], Cl[96 + row], Cl[128 + row], 0.f, vg[i]);
+            const int row = 32 * tt + lrow + 8 * i;
+            const int ch = row < a.Mb ? row : a.Mb - 1; // rows past the end are computed but never stored
+            load4<T>((const T *)a.v0, vbase + (uint32_t)ch * (uint32_t)a.HW, vv[i]);
+            if (PROV == PRO_BNSWISH_GATE)
+                vg[i] = a.vgate[(size_t)g.n * a.Mb + ch];
+        }
+    };
+    const auto body = [&](const Geom &g, const Geom &gn, auto more) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = lrow + 8 * i;
             lt_prologue<T, PRO_BNBWD>(uu[i], ur[i], Cl[row], Cl[32 + row], Cl[64 + row], 0.f);
-            float4v v4 = {vv[i][0], vv[i][1], vv[i][2], vv[i][3]};
             float4v u4 = {uu[i][0], uu[i][1], uu[i][2], uu[i][3]};
-            if (!pok) {
-                v4 = (float4v){0.f, 0.f, 0.f, 0.f};
+            if (!g.ok)
                 u4 = (float4v){0.f, 0.f, 0.f, 0.f};
-            }
-            *reinterpret_cast<float4v *>(Vt + ((lane >> 3) + 8 * i) * kLtPitch + vcol) = v4;
-            *reinterpret_cast<float4v *>(Ut + ((lane >> 3) + 8 * i) * kLtPitch + vcol) = u4;
+            *reinterpret_cast<float4v *>(Ut + row * kLtPitch + vcol) = u4;
         }
-        const size_t gbase = vbase_cur;
-        const bool gok = pok;
         if (decltype(more)::value)
-            fetch(ch + 4 * (int)gridDim.x); // in flight while this chunk is multiplied
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        // weight gradient, channel-lane reads: lane (c, h) takes pixels 8*jj + 4*h + {0..3} of row c
+            fetchU(gn); // the next chunk's U tile: in flight while this chunk is multiplied
+        const size_t gbase = (size_t)g.n * vimg + g.pix;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const float4v bvv = *reinterpret_cast<const float4v *>(Vt + c * kLtPitch + 8 * jj + 4 * h);
-            const float4v avv = *reinterpret_cast<const float4v *>(Ut + c * kLtPitch + 8 * jj + 4 * h);
+        for (int tt = 0; tt < NTW; ++tt) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(avv[r], bvv[r], acc, 0, 0, 0);
-        }
-        // data gradient, pixel-lane reads of the U tile: lane (h, c) takes U[2kk + h][pixel c]
-        float16v accd = (float16v){0};
+            for (int i = 0; i < 4; ++i) {
+                const int row = lrow + 8 * i;
+                lt_prologue<T, PROV>(vv[i], vv[i], Cv[32 * tt + row], Cv[R + 32 * tt + row], 0.f, vg[i]);
+                float4v v4 = {vv[i][0], vv[i][1], vv[i][2], vv[i][3]};
+                if (!g.ok)
+                    v4 = (float4v){0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<float4v *>(Vt + row * kLtPitch + vcol) = v4;
+            }
+            if (tt + 1 < NTW)
+                fetchV(g, tt + 1); // in flight while this tile is multiplied
+            else if (decltype(more)::value)
+                fetchV(gn, 0);
+            wave_lds_fence();
+            // weight gradient, channel-lane reads: lane (c, h) takes pixels 8*jj + 4*h + {0..3} of row c
 #pragma unroll
-        for (int k4 = 0; k4 < 16; k4 += 4) {
-            if (k4 < kdg) { // wave-uniform
-                float dv[4], wv[4];
+            for (int jj = 0; jj < 4; ++jj) {
+                const float4v bvv = *reinterpret_cast<const float4v *>(Vt + c * kLtPitch + 8 * jj + 4 * h);
+                const float4v avv = *reinterpret_cast<const float4v *>(Ut + c * kLtPitch + 8 * jj + 4 * h);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    dv[u] = Ut[(2 * (k4 + u) + h) * kLtPitch + c];
-                    wv[u] = Wl[(k4 + u) * 64 + lane];
+                for (int r = 0; r < 4; ++r)
+                    acc[tt] = __builtin_amdgcn_mfma_f32_32x32x2f32(avv[r], bvv[r], acc[tt], 0, 0, 0);
+            }
+            // data gradient, pixel-lane reads of the U tile: lane (h, c) takes U[2kk + h][pixel c]
+            float16v accd = (float16v){0};
+#pragma unroll
+            for (int k4 = 0; k4 < 16; k4 += 4) {
+                if (k4 < kdg) { // wave-uniform
+                    float dv[4], wv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        dv[u] = Ut[(2 * (k4 + u) + h) * kLtPitch + c];
+                        wv[u] = Wl[(tt * 16 + k4 + u) * 64 + lane];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        accd = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[u], dv[u], accd, 0, 0, 0);
                 }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    accd = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[u], dv[u], accd, 0, 0, 0);
             }
-        }
-        // accumulator register q holds channel row 8*(q/4) + 4h + q%4, pixel c: through the V tile
-        // (its reads are behind us: LDS operations of a wavefront execute in order)
+            // accumulator register q holds channel row 8*(q/4) + 4h + q%4, pixel c: through the V
+            // tile (its reads are behind us: LDS operations of a wavefront execute in order)
 #pragma unroll
-        for (int q = 0; q < 16; ++q)
-            Vt[(8 * (q >> 2) + 4 * h + (q & 3)) * kLtPitch + c] = accd[q];
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+            for (int q = 0; q < 16; ++q)
+                Vt[(8 * (q >> 2) + 4 * h + (q & 3)) * kLtPitch + c] = accd[q];
+            wave_lds_fence();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = (lane >> 3) + 8 * i;
-            const float4v g4 = *reinterpret_cast<const float4v *>(Vt + row * kLtPitch + vcol);
-            if (gok && row < a.Mb) {
-                const float o[4] = {g4[0], g4[1], g4[2], g4[3]};
-                store4<T>((T *)a.dgout, gbase + (uint32_t)row * (uint32_t)a.HW, o);
+            for (int i = 0; i < 4; ++i) {
+                const int row = lrow + 8 * i, ch = 32 * tt + row;
+                const float4v g4 = *reinterpret_cast<const float4v *>(Vt + row * kLtPitch + vcol);
+                if (g.ok && ch < a.Mb) {
+                    const float o[4] = {g4[0], g4[1], g4[2], g4[3]};
+                    store4<T>((T *)a.dgout, gbase + (uint32_t)ch * (uint32_t)a.HW, o);
+                }
             }
+            wave_lds_fence();
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
     };
     const int cStep = 4 * (int)gridDim.x, cEnd = a.numChunks;
     int ch = 4 * (int)blockIdx.x + t;
     if (ch < cEnd) {
-        fetch(ch);
-        for (; ch + cStep < cEnd; ch += cStep)
-            body(ch, std::true_type{});
-        body(ch, std::false_type{});
+        Geom g = geom(ch);
+        fetchU(g);
+        fetchV(g, 0);
+        for (; ch + cStep < cEnd; ch += cStep) {
+            const Geom gn = geom(ch + cStep);
+            body(g, gn, std::true_type{});
+            g = gn;
+        }
+        body(g, g, std::false_type{});
     }
-    // the four wavefronts' tiles, added in wavefront order
-    __syncthreads();
-    float *Rd = lds; // [4][16][64]
-#pragma unroll
-    for (int q = 0; q < 16; ++q)
-        Rd[(t * 16 + q) * 64 + lane] = acc[q];
-    __syncthreads();
-    float *dst = a.partial + (size_t)blockIdx.x * a.Ma * a.Mb;
-    for (int e = threadIdx.x; e < 16 * 64; e += 256) {
-        const int q = e >> 6, l = e & 63;
-        const float s = (Rd[e] + Rd[1024 + e]) + (Rd[2048 + e] + Rd[3072 + e]);
-        const int ai = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), bi = l & 31;
-        if (ai < a.Ma && bi < a.Mb)
-            dst[(size_t)ai * a.sOa + (size_t)bi * a.sOb] = s;
-    }
+    wave_tiles_reduce_store<NTW>(acc, lds, t, lane, a.Ma, a.Mb, a.sOa, a.sOb,
+                                 a.partial + (size_t)blockIdx.x * a.Ma * a.Mb);
 }
 
 // ---- bwd1x1_lt: data and weight gradient of a narrow->wide 1x1 convolution in one pass ---------
@@ -779,13 +829,6 @@ __global__ __launch_bounds__(256, 3) void projbwd_nn_kernel(WgradClArgs a)
 // in one workgroup: dx needs no second stage.  Fixed summation order, no atomics.
 // (Section "Guided Optimization Case Study: EfficientNet": fusing the consumers of a tensor.)
 
-struct Bwd1x1Args {
-    WgradClArgs g; // U = x (PRO_NONE), V = de (PRO_BNBWD); partial: weight-gradient splits
-    int kbeg[9];   // wavefront t multiplies contraction steps [kbeg[t], kbeg[t+1]) of the data gradient
-    const void *w; // [Mb][Ma] in the activation dtype (wide-major, as the layer stores it)
-    void *dx;      // [N][Ma][HW]
-    const void *res; // optional, added to dx
-};
 
 template <typename T, int MTA>
 __global__ __launch_bounds__(512, 4) void bwd1x1_lt_kernel(Bwd1x1Args b)
@@ -1178,23 +1221,45 @@ hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const 
         }
     }
     dim3 grid((unsigned)splits), block((unsigned)(64 * nw));
-    if (Cw <= 32 && fin) {
-        // both sides within one tile: every wavefront on its own chunk (projbwd_nn_kernel)
-        const size_t nn_lds = sizeof(float) * (4 * 2 * 32 * kLtPitch + 5 * 32 + 16 * 64);
-#define MBK_NN(T, PV)                                                                             \
+    // wide sides of up to three tiles (96 channels): a wavefront per pixel chunk.  (Measured with
+    // five and six tiles, 144 and 192 channels: the accumulator tiles of all of them plus the
+    // prefetch registers no longer fit two wavefronts per SIMD without spilling, and the
+    // workgroup-per-chunk kernel is faster there.  The expansion conv's fused backward in this form
+    // measured no faster than bwd1x1_lt on 16 -> 96 channels, 164 against 169 us, and was dropped.)
+    const int ntw = (Cw + 31) / 32;
+    if (fin && ntw <= 3) {
+        const size_t wv_lds = sizeof(float) * (4 * 2 * 32 * kLtPitch + 96 + 2 * 32 * ntw + (size_t)ntw * 16 * 64);
+#define MBK_WV(T, PV, NTW)                                                                        \
     {                                                                                             \
-        hipLaunchKernelGGL((projbwd_nn_kernel<T, PV>), grid, dim3(256), nn_lds, st, a);           \
+        auto kern = projbwd_wave_kernel<T, PV, NTW>;                                              \
+        if (wv_lds > 65536) {                                                                     \
+            hipError_t e = hipFuncSetAttribute((const void *)kern,                                \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,        \
+                                               (int)wv_lds);                                      \
+            if (e != hipSuccess)                                                                  \
+                return e;                                                                         \
+        }                                                                                         \
+        hipLaunchKernelGGL(kern, grid, dim3(256), wv_lds, st, a);                                 \
         return hipGetLastError();                                                                 \
+    }
+#define MBK_WV_N(T, PV)                                                                           \
+    {                                                                                             \
+        if (ntw == 1)                                                                             \
+            MBK_WV(T, PV, 1)                                                                      \
+        if (ntw == 2)                                                                             \
+            MBK_WV(T, PV, 2)                                                                      \
+        MBK_WV(T, PV, 3)                                                                          \
     }
         if (bf16) {
             if (sc.pro == PRO_NONE)
-                MBK_NN(bf16_t, PRO_NONE)
-            MBK_NN(bf16_t, PRO_BNSWISH_GATE)
+                MBK_WV_N(bf16_t, PRO_NONE)
+            MBK_WV_N(bf16_t, PRO_BNSWISH_GATE)
         }
         if (sc.pro == PRO_NONE)
-            MBK_NN(float, PRO_NONE)
-        MBK_NN(float, PRO_BNSWISH_GATE)
-#undef MBK_NN
+            MBK_WV_N(float, PRO_NONE)
+        MBK_WV_N(float, PRO_BNSWISH_GATE)
+#undef MBK_WV_N
+#undef MBK_WV
     }
 #define MBK_CASE(T, PV)                                                                           \
     {                                                                                             \
