@@ -344,7 +344,8 @@ def run_chain(args) -> dict:
     cand = [(i, n) for i, row in enumerate(survey) for n in row
             if algorithmic_bytes(shapes[i], n) is not None]
     if args.probe_step or args.no_survey:
-        bi, dominant = (args.probe_step or "2:dw_bwd").split(":")
+        default_probe = f"{only + 1}:dw_bwd" if only is not None else "2:dw_bwd"
+        bi, dominant = (args.probe_step or default_probe).split(":")
         bi = int(bi) - 1
     else:
         bi, dominant = max(cand, key=lambda c: survey[c[0]][c[1]])

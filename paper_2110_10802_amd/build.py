@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmbconv.so")
-SOURCES = ["mbconv_api.hip", "kernels_gemm.hip", "kernels_big.hip", "kernels_bf.hip", "kernels_wave.hip", "kernels_pv16.hip", "kernels_dw.hip", "kernels_dw4.hip", "kernels_dw2.hip", "kernels_dwr.hip", "kernels_misc.hip"]
+SOURCES = ["mbconv_api.hip", "kernels_gemm.hip", "kernels_big.hip", "kernels_bf.hip", "kernels_x3.hip", "kernels_wave.hip", "kernels_pv16.hip", "kernels_dw.hip", "kernels_dw4.hip", "kernels_dw2.hip", "kernels_dwr.hip", "kernels_misc.hip"]
 # sources without a block activation (Mish, layer normalisation, softmax): compiled once
 SOURCES_ONCE = ["kernels_ops.hip"]
 # packed fp32 VALU ops are disabled for the device pass (the host pass does not know the

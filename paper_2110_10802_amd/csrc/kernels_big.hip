@@ -595,6 +595,13 @@ static hipError_t splitk_finish(const float *partial, int S, int M, uint32_t Q, 
     return hipErrorInvalidValue;
 }
 
+hipError_t launch_splitk_finish_f32(const float *partial, int S, int M, uint32_t Q, int HW, void *out,
+                                    const void *res, int epi, float *psum, float *psq, int NT,
+                                    hipStream_t st)
+{
+    return splitk_finish<float>(partial, S, M, Q, HW, out, res, epi, psum, psq, NT, st);
+}
+
 size_t big_conv_splitk_floats(int N, int M, int K, int HW)
 {
     int wt, qtiles, splits;

@@ -223,6 +223,30 @@ bool bf_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits);
 hipError_t launch_bf_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
                            float *partial, int *splits_out, hipStream_t st);
 
+// kernels_x3.hip
+bool x3_conv_plan(int N, int M, int K, int HW, int *qtiles, int *splits);
+size_t x3_conv_splitk_floats(int N, int M, int K, int HW);
+hipError_t launch_x3_conv1x1(int N, int M, int K, int HW, const void *wimg, const Operand &B,
+                             void *out, int epi, const void *res, float *psum, float *psq,
+                             float *splitk_ws, hipStream_t st);
+bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits);
+hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
+                           float *partial, int *splits_out, hipStream_t st);
+#ifndef MBK_X3
+#define MBK_X3 1
+#endif
+#ifndef MBK_X3W
+#define MBK_X3W 1
+#endif
+
+// fp32 convolutions of the wide blocks run on the bf16 matrix cores from a weight image
+bool conv1x1_uses_weight_image(bool bf16, int N, int M, int K, int HW, bool stores_operand)
+{
+    int qtiles, splits;
+    return MBK_X3 && !bf16 && !stores_operand && !wave_conv_kind(M, K, HW) &&
+           x3_conv_plan(N, M, K, HW, &qtiles, &splits);
+}
+
 int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand)
 {
     const int kind = stores_operand ? 0 : wave_conv_kind(M, K, HW);
@@ -231,6 +255,10 @@ int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_ope
     int wt, qtiles, splits;
     if (bf16 && !stores_operand && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
         return qtiles;
+    if (conv1x1_uses_weight_image(bf16, N, M, K, HW, stores_operand)) {
+        x3_conv_plan(N, M, K, HW, &qtiles, &splits);
+        return qtiles;
+    }
     if (!stores_operand && big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits))
         return qtiles;
     return conv1x1_num_qtiles(N, HW);
@@ -243,13 +271,21 @@ size_t conv1x1_splitk_floats(bool bf16, int N, int M, int K, int HW, bool stores
     int qtiles, splits;
     if (bf16 && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
         return bf_conv_splitk_floats(N, M, K, HW);
+    if (conv1x1_uses_weight_image(bf16, N, M, K, HW, stores_operand))
+        return x3_conv_splitk_floats(N, M, K, HW);
     return big_conv_splitk_floats(N, M, K, HW);
 }
 
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
-                          float *psq, void *sc_store, float *splitk_ws, hipStream_t st)
+                          float *psq, void *sc_store, float *splitk_ws, hipStream_t st,
+                          const void *wimg)
 {
+    if (conv1x1_uses_weight_image(bf16, N, M, K, HW, sc_store != nullptr)) {
+        if (!wimg)
+            return hipErrorInvalidValue;
+        return launch_x3_conv1x1(N, M, K, HW, wimg, B, out, epi, res, psum, psq, splitk_ws, st);
+    }
     const int kind = sc_store ? 0 : wave_conv_kind(M, K, HW);
     if (kind)
         return launch_wave_conv1x1(bf16, kind, N, M, K, HW, w, sAm, sAk, B, out, epi, res, psum,
@@ -288,7 +324,8 @@ hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w,
 
 hipError_t launch_conv1x1_affine(bool bf16, int N, int M, int K, int HW, const void *w, int sAm,
                                  int sAk, const Operand &B, void *out, const void *res,
-                                 const float *scale, const float *shift, hipStream_t st)
+                                 const float *scale, const float *shift, hipStream_t st,
+                                 const void *wimg)
 {
     if (B.pro != PRO_BNSWISH_GATE)
         return hipErrorNotSupported;
@@ -303,6 +340,12 @@ hipError_t launch_conv1x1_affine(bool bf16, int N, int M, int K, int HW, const v
         return splits == 1 ? launch_bf_conv1x1(N, M, K, HW, w, sAm, sAk, B, out, EPI_AFFINE, res, sc,
                                                sh, nullptr, st)
                            : hipErrorNotSupported;
+    if (conv1x1_uses_weight_image(bf16, N, M, K, HW, false)) {
+        x3_conv_plan(N, M, K, HW, &qtiles, &splits);
+        if (splits != 1 || !wimg)
+            return hipErrorNotSupported;
+        return launch_x3_conv1x1(N, M, K, HW, wimg, B, out, EPI_AFFINE, res, sc, sh, nullptr, st);
+    }
     if (big_conv_plan(N, M, K, HW, &wt, &qtiles, &splits) && splits == 1)
         return launch_big_conv1x1(bf16, N, M, K, HW, w, sAm, sAk, B, out, EPI_AFFINE, res, sc, sh,
                                   nullptr, st);
@@ -395,6 +438,8 @@ int wgrad_splits(bool bf16, int Ma, int Mb, int N, int HW)
     if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits))
         return splits;
     if (bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &splits))
+        return splits;
+    if (MBK_X3W && !bf16 && x3_wgrad_plan(Ma, Mb, N, HW, &splits))
         return splits;
     int wt;
     if (big_wgrad_plan(Ma, Mb, N, HW, &wt, &splits))
@@ -556,6 +601,12 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
         }
         if (bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &splits)) {
             hipError_t e = launch_bf_wgrad(N, Ma, Mb, HW, U, V, partial, &splits, st);
+            if (e != hipSuccess)
+                return e;
+            return finish(splits);
+        }
+        if (MBK_X3W && !bf16 && x3_wgrad_plan(Ma, Mb, N, HW, &splits)) {
+            hipError_t e = launch_x3_wgrad(N, Ma, Mb, HW, U, V, partial, &splits, st);
             if (e != hipSuccess)
                 return e;
             return finish(splits);

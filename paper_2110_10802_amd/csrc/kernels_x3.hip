@@ -1,0 +1,766 @@
+// fp32 1x1 convolutions and weight gradients of the wide blocks on the bf16 matrix cores.
+//
+// An fp32 MFMA (v_mfma_f32_32x32x2_f32) runs at the rate of the vector ALU and blocks it; the
+// bf16 MFMA (v_mfma_f32_32x32x16_bf16) does sixteen times the work per cycle and runs beside
+// the vector ALU.  An fp32 value is the exact sum of three bf16 values (8 + 8 + 8 significant
+// bits: h = bf16(x), m = bf16(x - h), l = bf16(x - h - m), every subtraction exact), and a
+// product of two bf16 values is exact in fp32, so
+//     a*b = ah*bh + (ah*bm + am*bh) + (am*bm + ah*bl + al*bh) + O(2^-24 |a*b|):
+// six bf16 MFMAs with fp32 accumulation reproduce the fp32 contraction to fp32 rounding level
+// (the dropped terms are of the size of one fp32 rounding of the product) at 6/16 of the fp32
+// MFMA's matrix-core time, and that time overlaps with the staging arithmetic.  Storage stays
+// fp32 in HBM; the three planes of an activation exist in LDS only, those of the conv weights
+// are written once per forward pass (x3_prep_kernel) in the order the kernels keep them in LDS.
+//
+// Same decomposition as kernels_big.hip / kernels_bf.hip: flattened batch (column q = n*HW +
+// pixel), 64 x 64 output tiles per workgroup of four wavefronts, the contraction 32 at a time
+// through two LDS buffers fed from a two-slot register ring, fixed-order split reductions.
+// Operand layout of the instruction: lane l holds, of A, row l%32 and the contraction indices
+// 8*(l/32)..+7; of B, column l%32 and the same indices; so both LDS tiles are [row or column][k]
+// with k contiguous (pitch BK+8 halfwords = 80 bytes: 16-byte reads of a quarter wavefront fall
+// on distinct banks), one such tile per plane.
+#include <algorithm>
+#include "mbconv_dev.h"
+#include "mbconv_launch.h"
+
+
+namespace mbk {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct X3Operand {
+    const float *p0, *p1;
+    const float *c0, *c1, *c2, *gate;
+};
+
+// (x0, x1) -> three words, each the bf16 pair (plane value of x0 in bits 0-15, of x1 in 16-31)
+__device__ __forceinline__ void x3_split2(float x0, float x1, uint32_t (&w)[3])
+{
+    w[0] = bf16_pack2(x0, x1);
+    float r0 = x0 - __uint_as_float(w[0] << 16), r1 = x1 - __uint_as_float(w[0] & 0xffff0000u);
+    w[1] = bf16_pack2(r0, r1);
+    r0 -= __uint_as_float(w[1] << 16);
+    r1 -= __uint_as_float(w[1] & 0xffff0000u);
+    w[2] = bf16_pack2(r0, r1);
+}
+
+template <int PRO>
+__device__ __forceinline__ float x3_apply(float v0, float v1, float k0, float k1, float k2)
+{
+    if (PRO == PRO_NONE)
+        return v0;
+    if (PRO == PRO_BNSWISH_GATE)
+        return actf(fmaf(v0, k0, k1)) * k2;
+    return fmaf(k0, v0, fmaf(k1, v1, k2));
+}
+
+__device__ __forceinline__ void x3_ld4(const float *p, size_t i, float (&v)[4])
+{
+    const float4 t = *reinterpret_cast<const float4 *>(p + i);
+    v[0] = t.x;
+    v[1] = t.y;
+    v[2] = t.z;
+    v[3] = t.w;
+}
+
+// Halfword offset of element (row, k) in a [rows][BK = 32] plane of pitch 40 halfwords (80 bytes).
+// The four 16-byte groups of a row are permuted by bits 4-5 of the row: the transposing stores
+// (a wavefront writes one 32-bit k pair to each of 16 rows that are four apart, or to 64
+// consecutive rows) then fall on 64 distinct banks instead of 16, and the 16-byte reads of 16
+// consecutive rows stay conflict-free.
+__device__ __forceinline__ int x3_at(int row, int k)
+{
+    return row * 40 + ((((k >> 3) ^ (row >> 4)) & 3) << 3) + (k & 7);
+}
+
+__device__ __forceinline__ bf16x8 x3_lds8(const uint16_t *p)
+{
+    return *reinterpret_cast<const bf16x8 *>(p);
+}
+
+// acc += a*b for the three-plane operands (small terms first)
+__device__ __forceinline__ float16v x3_mfma6(const bf16x8 (&a)[3], const bf16x8 (&b)[3], float16v acc)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[2], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], acc, 0, 0, 0);
+    return acc;
+}
+
+// ---- weight images -------------------------------------------------------------------------
+// The A operand of a convolution (rows m, contraction index k) as bf16 planes, cut into tiles
+// of 64 rows x 32 k: tile (mt, ch), plane pl starts at halfword ((mt*CH + ch)*3 + pl)*2048 and
+// holds element (row, k) at x3_img_at(row, k): rows of 64 bytes whose four 16-byte groups are
+// permuted by bits 2-3 of the row, which keeps the 16-byte fragment reads of 16 consecutive
+// rows on distinct banks without padding.  A workgroup copies a tile to LDS as it is (one 16-byte
+// piece per thread and plane).  Rows and k past the end are zeros.
+__device__ __forceinline__ int x3_img_at(int row, int k)
+{
+    return row * 32 + ((((k >> 3) ^ (row >> 2)) & 3) << 3) + (k & 7);
+}
+
+struct X3PrepSet {
+    const float *w; // A(m, k) = w[m*sm + k*sk]
+    int M, K, sm, sk;
+    uint16_t *img;
+    int CH, firstTile;
+};
+struct X3PrepArgs {
+    X3PrepSet s[4];
+    int nsets;
+};
+
+// one workgroup per tile: thread -> (row tid/4, eight k at 8*(tid%4))
+__global__ __launch_bounds__(256) void x3_prep_kernel(X3PrepArgs a)
+{
+    int si = 0;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        if (i < a.nsets && (int)blockIdx.x >= a.s[i].firstTile)
+            si = i;
+    const X3PrepSet S = a.s[si];
+    const int local = blockIdx.x - S.firstTile, mt = local / S.CH, ch = local % S.CH;
+    const int tid = threadIdx.x, r = tid >> 2, g = tid & 3;
+    const int m = mt * 64 + r, k0 = ch * 32 + 8 * g;
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int k = k0 + j;
+        v[j] = (m < S.M && k < S.K) ? S.w[(size_t)m * S.sm + (size_t)k * S.sk] : 0.f;
+    }
+    uint32_t w[4][3];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        x3_split2(v[2 * j], v[2 * j + 1], w[j]);
+    uint16_t *tile = S.img + ((size_t)mt * S.CH + ch) * 3 * 2048;
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl)
+        *reinterpret_cast<uint4 *>(tile + pl * 2048 + x3_img_at(r, 8 * g)) =
+            make_uint4(w[0][pl], w[1][pl], w[2][pl], w[3][pl]);
+}
+
+size_t x3_weight_image_bytes(int M, int K)
+{
+    return (size_t)((M + 63) / 64) * ((K + 31) / 32) * 3 * 2048 * sizeof(uint16_t);
+}
+
+// Writes up to four images in one launch; set i: A(m,k) = w[i][m*sm[i] + k*sk[i]], M[i] x K[i].
+hipError_t launch_x3_prep(int nsets, const float *const *w, const int *M, const int *K, const int *sm,
+                          const int *sk, void *const *img, hipStream_t st)
+{
+    if (nsets < 1 || nsets > 4)
+        return hipErrorInvalidValue;
+    X3PrepArgs a = {};
+    int tiles = 0;
+    for (int i = 0; i < nsets; ++i) {
+        a.s[i].w = w[i];
+        a.s[i].M = M[i];
+        a.s[i].K = K[i];
+        a.s[i].sm = sm[i];
+        a.s[i].sk = sk[i];
+        a.s[i].img = (uint16_t *)img[i];
+        a.s[i].CH = (K[i] + 31) / 32;
+        a.s[i].firstTile = tiles;
+        tiles += ((M[i] + 63) / 64) * a.s[i].CH;
+    }
+    a.nsets = nsets;
+    hipLaunchKernelGGL(x3_prep_kernel, dim3((unsigned)tiles), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// ---- convolution ---------------------------------------------------------------------------
+struct X3ConvArgs {
+    int M, K, HW;
+    uint32_t Q;
+    FastDiv divHW;
+    const uint16_t *img; // weight image of this convolution's A operand
+    int CH;              // its chunks of 32 along k
+    X3Operand B;
+    float *out;
+    const float *res;
+    float *psum, *psq;
+    int QT, MT;
+    float *partial;
+    int chunksPerSplit;
+};
+
+// out[n,m,pix] = sum_k A(m,k) * op(B)[n,k,pix], A given as a weight image.  Requirements
+// (checked by the host): K % 8 == 0, M % 4 == 0, HW % 4 == 0.
+//
+// Persistent workgroups.  Output tiles are dealt out per XCD (blockIdx.x mod 8): XCD x owns the
+// pixel tiles qt = x, x+8, ... with all their row tiles, so the workgroups that read the same
+// activation tile share an L2; workgroup i of the XCD's Gx takes that list's tiles i, i+Gx, ...
+// The (tile, chunk) items of a workgroup form one stream: the register ring prefetches two
+// items ahead across tile boundaries, so the first chunks of the next tile are in flight while
+// the current tile's results leave, and the start-up latency is paid once per workgroup.
+template <int PRO, int EPI>
+__global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
+{
+    constexpr int BM = 64, BP = 64, BK = 32, PK = BK + 8, PC = BP + 4;
+    static_assert(PK == 40, "x3_at assumes a pitch of 40 halfwords");
+    constexpr int kPlaneA = BM * BK, kPlaneB = BP * PK; // halfwords
+    constexpr int kBuf = 3 * (kPlaneA + kPlaneB);
+    // one operand buffer during the contraction, the fp32 output tile after it
+    __shared__ __attribute__((aligned(16))) uint16_t smem[kBuf];
+    static_assert(kBuf * 2 >= 64 * PC * 4, "output tile must fit into the operand buffer");
+    float(*Ct)[PC] = reinterpret_cast<float(*)[PC]>(smem);
+    auto As = [&](int pl) __attribute__((always_inline)) { return smem + pl * kPlaneA; };
+    auto Bs = [&](int pl) __attribute__((always_inline)) { return smem + 3 * kPlaneA + pl * kPlaneB; };
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wp = wave & 1;
+    const int xcd = blockIdx.x & 7, wi = blockIdx.x >> 3, Gx = gridDim.x >> 3;
+    const int nTx = a.QT > xcd ? ((a.QT - xcd + 7) >> 3) * a.MT : 0; // tiles of this XCD
+    if (wi >= nTx)
+        return;
+    const int nT = (nTx - wi + Gx - 1) / Gx; // tiles of this workgroup
+    int cbeg = 0, cend = (a.K + BK - 1) / BK;
+    if (EPI == EPI_PARTIAL) {
+        cbeg = blockIdx.y * a.chunksPerSplit;
+        cend = min(cbeg + a.chunksPerSplit, cend);
+    }
+    const int nch = cend - cbeg, total = nT * nch;
+    if (nch <= 0) // cannot happen with the host's split plan; keeps every image access in bounds
+        return;
+
+    // ---- prefetch cursor: the item the next load takes, and what depends on its tile ----
+    const int px = 4 * (tid & 15), kp = tid >> 4; // this thread's pixel run and k pair of a B chunk
+    int pk = 0, pc = cbeg, pmt = 0;
+    bool bvalid = false;
+    uint32_t bn = 0;
+    size_t bbase = 0;
+    auto set_ptile = [&](int k) __attribute__((always_inline)) {
+        const int t = wi + min(k, nT - 1) * Gx; // past the last tile: the last one again (never consumed)
+        const int qt = xcd + 8 * (t / a.MT);
+        pmt = t - (t / a.MT) * a.MT;
+        const uint32_t qb = (uint32_t)qt * BP + (uint32_t)px;
+        bvalid = qb < a.Q;
+        bn = bvalid ? fdiv(qb, a.divHW) : 0u;
+        bbase = (size_t)bn * a.K * a.HW + (bvalid ? qb - bn * (uint32_t)a.HW : 0u);
+    };
+    auto advance = [&]() __attribute__((always_inline)) {
+        if (++pc == cend) { // uniform over the workgroup; no memory access inside
+            pc = cbeg;
+            set_ptile(++pk);
+        }
+    };
+
+    // Staged items live in a ring of two register slots: item j is loaded during iteration j-2
+    // and written to LDS at the end of iteration j-1.  All loads are unconditional (indices
+    // clamped into the tensor) and validity is an AND mask applied on the way into LDS, so no
+    // branch and no use of loaded data sits between a load and the MFMAs it should overlap.
+    //
+    // A: the tile's three planes are copied as they are, 16 bytes per thread and plane.
+    u32x4 ra[2][3];
+    // B: thread -> (four pixels at 4*(tid%16), k pair tid/16); the pair of a pixel is one 32-bit
+    // LDS store per plane.
+    float rb0[2][2][4], rb1[2][2][PRO == PRO_BNBWD ? 4 : 1];
+    float bk0[2][2], bk1[2][2], bk2[2][2];
+    uint32_t rbok[2][2];
+    auto load = [&](int s) __attribute__((always_inline)) {
+        const uint16_t *tile = a.img + ((size_t)pmt * a.CH + pc) * 3 * kPlaneA;
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)
+            ra[s][pl] = *reinterpret_cast<const u32x4 *>(tile + pl * kPlaneA + 8 * tid);
+        const int k0 = pc * BK;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int k = k0 + 2 * kp + j, kc = min(k, a.K - 1);
+            rbok[s][j] = (bvalid && k < a.K) ? 0xffffffffu : 0u;
+            x3_ld4(a.B.p0, bbase + (size_t)kc * a.HW, rb0[s][j]);
+            if constexpr (PRO == PRO_BNBWD)
+                x3_ld4(a.B.p1, bbase + (size_t)kc * a.HW, rb1[s][j]);
+            if (PRO != PRO_NONE) {
+                bk0[s][j] = a.B.c0[kc];
+                bk1[s][j] = a.B.c1[kc];
+                bk2[s][j] = PRO == PRO_BNBWD ? a.B.c2[kc] : a.B.gate[(size_t)bn * a.K + kc];
+            }
+        }
+    };
+    auto store = [&](int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)
+            *reinterpret_cast<u32x4 *>(As(pl) + 8 * tid) = ra[s][pl];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float v[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                v[j] = and_mask(x3_apply<PRO>(rb0[s][j][r], rb1[s][j][PRO == PRO_BNBWD ? r : 0], bk0[s][j],
+                                              bk1[s][j], bk2[s][j]),
+                                rbok[s][j]);
+            uint32_t w[3];
+            x3_split2(v[0], v[1], w);
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                *reinterpret_cast<uint32_t *>(Bs(pl) + x3_at(px + r, 2 * kp)) = w[pl];
+        }
+    };
+
+    float16v acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        acc[r] = 0.f;
+
+    // ---- results of the current tile; register r of lane l is row 8*(r/4)+4*(l/32)+r%4, column l%32 ----
+    auto epilogue = [&](int ck) __attribute__((always_inline)) {
+        const int t = wi + ck * Gx;
+        const int qt = xcd + 8 * (t / a.MT), m0 = (t - (t / a.MT) * a.MT) * BM;
+        const uint32_t q0 = (uint32_t)qt * BP;
+        if constexpr (EPI != EPI_PARTIAL) {
+            // Through LDS, so that 16 lanes own 64 consecutive pixels of one output row: 16-byte
+            // accesses, one pixel-index division per thread, and a row's BN statistics summed
+            // inside those 16 lanes.  (The chunk's barrier has passed: the operand buffer is free.)
+            const int pg = tid & 15;
+            const uint32_t q = q0 + 4u * pg;
+            const bool valid = q < a.Q;
+            const uint32_t n = valid ? fdiv(q, a.divHW) : 0u;
+            const uint32_t pix = valid ? q - n * (uint32_t)a.HW : 0u;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                Ct[wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)][wp * 32 + (lane & 31)] = acc[r];
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = (tid >> 4) + 16 * i, m = m0 + row;
+                const bool ok = valid && m < a.M;
+                const float4 c = *reinterpret_cast<const float4 *>(&Ct[row][4 * pg]);
+                float v[4] = {c.x, c.y, c.z, c.w};
+                const size_t idx = ((size_t)n * a.M + min(m, a.M - 1)) * a.HW + pix;
+                if (EPI == EPI_RES) {
+                    const float4 rr = *reinterpret_cast<const float4 *>(a.res + idx);
+                    v[0] += rr.x;
+                    v[1] += rr.y;
+                    v[2] += rr.z;
+                    v[3] += rr.w;
+                }
+                if (EPI == EPI_AFFINE) { // psum / psq carry the row's scale and shift
+                    const float osc = a.psum[min(m, a.M - 1)], osh = a.psq[min(m, a.M - 1)];
+                    float4 rr = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (a.res)
+                        rr = *reinterpret_cast<const float4 *>(a.res + idx);
+                    v[0] = fmaf(v[0], osc, osh) + rr.x;
+                    v[1] = fmaf(v[1], osc, osh) + rr.y;
+                    v[2] = fmaf(v[2], osc, osh) + rr.z;
+                    v[3] = fmaf(v[3], osc, osh) + rr.w;
+                }
+                if (ok)
+                    *reinterpret_cast<float4 *>(a.out + idx) = make_float4(v[0], v[1], v[2], v[3]);
+                if (EPI == EPI_STATS) {
+                    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float sv = ok ? v[j] : 0.f;
+                        s1 += sv;
+                        s2 = fmaf(sv, sv, s2);
+                    }
+                    s1 = row16_sum(s1);
+                    s2 = row16_sum(s2);
+                    if (pg == 0 && m < a.M) {
+                        a.psum[(size_t)m * a.QT + qt] = s1;
+                        a.psq[(size_t)m * a.QT + qt] = s2;
+                    }
+                }
+            }
+        } else {
+            // a split contraction: the raw partial tile, lanes along the pixels
+            const uint32_t q = q0 + wp * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (q < a.Q && m < a.M)
+                    a.partial[((size_t)blockIdx.y * a.M + m) * a.Q + q] = acc[r];
+            }
+        }
+    };
+
+    set_ptile(0);
+    load(0);
+    advance();
+    load(1);
+    advance();
+    store(0);
+    __syncthreads();
+    int ck = 0, cj = 0; // current tile of this workgroup, chunk within it
+    auto body = [&](int u) __attribute__((always_inline)) {
+        load(u); // slot u is free: its item went to LDS last iteration
+        advance();
+        __builtin_amdgcn_sched_barrier(0); // loads first, then the MFMAs, then the staging arithmetic
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            bf16x8 av[3], bv[3];
+            const int ko = 16 * s + 8 * (lane >> 5);
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) {
+                av[pl] = x3_lds8(As(pl) + x3_img_at(wm * 32 + (lane & 31), ko));
+                bv[pl] = x3_lds8(Bs(pl) + x3_at(wp * 32 + (lane & 31), ko));
+            }
+            acc = x3_mfma6(av, bv, acc);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads(); // every wavefront has read the chunk
+        if (++cj == nch) { // uniform: the tile is complete
+            epilogue(ck);
+            __syncthreads(); // the output tile has left LDS
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[r] = 0.f;
+            cj = 0;
+            ++ck;
+        }
+        store(u ^ 1); // past the last item: a repeated item that is never consumed
+        __syncthreads();
+    };
+    int it = 0;
+    for (; it + 1 < total; it += 2) {
+        body(0);
+        body(1);
+    }
+    if (it < total)
+        body(0);
+}
+
+// Plan: 64 x 64 tiles; the contraction is split when the tiles alone cannot fill the chip
+// (`qtiles` is then the second stage's count of statistics partials per row).
+bool x3_conv_plan(int N, int M, int K, int HW, int *qtiles, int *splits)
+{
+    const long long Q = (long long)N * HW;
+    // (planes whose size is not a multiple of four, the 7x7 stages, stay with kernels_big.hip:
+    // their pixel runs straddle image boundaries and the scalar staging measured slower here)
+    if (K % 8 != 0 || M % 4 != 0 || HW % 4 != 0 || Q >= (1ll << 31) || K < 32 || M < 32)
+        return false;
+    *qtiles = (int)((Q + 63) / 64);
+    *splits = 1;
+    const long long tiles = (long long)*qtiles * ((M + 63) / 64);
+    const int chunks = (K + 31) / 32;
+    if (tiles < 384 && chunks >= 8) {
+        long long s = (768 + tiles - 1) / tiles;
+        if (s > chunks / 2)
+            s = chunks / 2;
+        if (s > 16)
+            s = 16;
+        const int per = (int)((chunks + s - 1) / s);
+        *splits = (chunks + per - 1) / per;
+        if (*splits > 1)
+            *qtiles = (int)((Q + 1023) / 1024);
+    }
+    return true;
+}
+
+size_t x3_conv_splitk_floats(int N, int M, int K, int HW)
+{
+    int qtiles, splits;
+    if (!x3_conv_plan(N, M, K, HW, &qtiles, &splits) || splits == 1)
+        return 0;
+    return (size_t)splits * M * N * HW;
+}
+
+// kernels_big.hip
+hipError_t launch_splitk_finish_f32(const float *partial, int S, int M, uint32_t Q, int HW, void *out,
+                                    const void *res, int epi, float *psum, float *psq, int NT,
+                                    hipStream_t st);
+
+hipError_t launch_x3_conv1x1(int N, int M, int K, int HW, const void *wimg, const Operand &B,
+                             void *out, int epi, const void *res, float *psum, float *psq,
+                             float *splitk_ws, hipStream_t st)
+{
+    int qtiles, splits;
+    if (!x3_conv_plan(N, M, K, HW, &qtiles, &splits) || !wimg)
+        return hipErrorInvalidValue;
+    if (splits > 1 && (!splitk_ws || epi == EPI_AFFINE))
+        return hipErrorInvalidValue;
+    X3ConvArgs a;
+    a.M = M;
+    a.K = K;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    a.divHW = make_div((uint32_t)HW);
+    a.img = (const uint16_t *)wimg;
+    a.CH = (K + 31) / 32;
+    a.B.p0 = (const float *)B.p0;
+    a.B.p1 = (const float *)B.p1;
+    a.B.c0 = B.c0;
+    a.B.c1 = B.c1;
+    a.B.c2 = B.c2;
+    a.B.gate = B.gate;
+    a.out = (float *)out;
+    a.res = (const float *)res;
+    a.psum = psum;
+    a.psq = psq;
+    a.QT = (int)((a.Q + 63u) / 64u);
+    a.MT = (M + 63) / 64;
+    a.partial = splitk_ws;
+    const int chunks = (K + 31) / 32;
+    a.chunksPerSplit = (chunks + splits - 1) / splits;
+    // workgroups per XCD: every workgroup gets the same number of tiles (or one fewer), at most
+    // about four workgroups per compute unit in all
+    const int tilesPerXcd = ((a.QT + 7) / 8) * a.MT;
+    const int cap = std::max(1, 128 / splits);
+    const int rounds = (tilesPerXcd + cap - 1) / cap;
+    const int gx = (tilesPerXcd + rounds - 1) / rounds;
+    dim3 grid((unsigned)(8 * gx), (unsigned)splits);
+    const int kepi = splits > 1 ? EPI_PARTIAL : epi;
+    hipError_t e = hipErrorInvalidValue;
+#define MBK_CASE(P, E)                                                                            \
+    if (B.pro == P && kepi == E) {                                                                \
+        hipLaunchKernelGGL((conv_x3_kernel<P, E>), grid, dim3(256), 0, st, a);                    \
+        e = hipGetLastError();                                                                    \
+    }
+    MBK_CASE(PRO_NONE, EPI_STATS)
+    MBK_CASE(PRO_BNSWISH_GATE, EPI_STATS)
+    MBK_CASE(PRO_BNBWD, EPI_NONE)
+    MBK_CASE(PRO_BNBWD, EPI_RES)
+    MBK_CASE(PRO_BNSWISH_GATE, EPI_AFFINE)
+    MBK_CASE(PRO_NONE, EPI_PARTIAL)
+    MBK_CASE(PRO_BNSWISH_GATE, EPI_PARTIAL)
+    MBK_CASE(PRO_BNBWD, EPI_PARTIAL)
+#undef MBK_CASE
+    if (e != hipSuccess || splits == 1)
+        return e;
+    return launch_splitk_finish_f32(splitk_ws, splits, M, a.Q, HW, out, res, epi, psum, psq, qtiles, st);
+}
+
+// ---- weight gradient -------------------------------------------------------------------------
+// dW[a,b] = sum_q op(U)[a,q] * op(V)[b,q].  Both operands are pixel-contiguous in memory, which
+// is the [row][k] layout the instruction wants, so a run of four pixels goes through its
+// prologue, is split and lands in LDS as one 8-byte store per plane.  A workgroup owns 128 rows
+// of U by 128 rows of V (each wavefront 64 x 64: four accumulator tiles, so every operand
+// fragment read from LDS feeds two MFMA groups) and a range of 32-pixel chunks (blockIdx.z);
+// with the narrow operand inside one tile the wide one is staged, and sent through its prologue,
+// once in the whole grid.  The splits' partial tiles are added by a fixed-order second stage.
+struct X3WgradArgs {
+    int Ma, Mb, HW;
+    uint32_t Q;
+    int chunksPerSplit; // chunks of 32 pixels
+    int tilesA, tilesB, splits;
+    FastDiv divHW;
+    X3Operand U, V;
+    float *partial;
+};
+
+// one operand's staging state: rows rr + 32*i (i < 4) of the 128-row tile, pixel run 4*qg
+template <int PRO>
+struct X3Rows {
+    float v0[4][4], v1[4][PRO == PRO_BNBWD ? 4 : 1];
+    float g[4];
+    float k0[4], k1[4], k2[4];
+    uint32_t rmask[4];
+
+    __device__ __forceinline__ void init(const X3Operand &o, int row0, int rr, int M)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = row0 + rr + 32 * i;
+            rmask[i] = r < M ? 0xffffffffu : 0u;
+            k0[i] = k1[i] = k2[i] = 0.f;
+            if (PRO != PRO_NONE && r < M) {
+                k0[i] = o.c0[r];
+                k1[i] = o.c1[r];
+                if (PRO == PRO_BNBWD)
+                    k2[i] = o.c2[r];
+            }
+        }
+    }
+    // n, pix: image and first pixel of the run (it lies inside one plane: HW % 4 == 0)
+    __device__ __forceinline__ void load(const X3Operand &o, int row0, int rr, int M, int HW, uint32_t n,
+                                         uint32_t pix)
+    {
+        // every pass loads, also past the last row (clamped, masked on the way into LDS): a branch
+        // around a load would make the loads of the following passes wait for it
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = min(row0 + rr + 32 * i, M - 1);
+            const size_t idx = ((size_t)n * M + r) * HW + pix;
+            x3_ld4(o.p0, idx, v0[i]);
+            if constexpr (PRO == PRO_BNBWD)
+                x3_ld4(o.p1, idx, v1[i]);
+            if constexpr (PRO == PRO_BNSWISH_GATE)
+                g[i] = o.gate[(size_t)n * M + r];
+        }
+    }
+    // prologue, split, three 8-byte LDS stores per pass
+    __device__ __forceinline__ void store(uint16_t *planes, int rr, int qg, uint32_t qmask) const
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float y[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                y[j] = and_mask(x3_apply<PRO>(v0[i][j], v1[i][PRO == PRO_BNBWD ? j : 0], k0[i], k1[i],
+                                              PRO == PRO_BNSWISH_GATE ? g[i] : k2[i]),
+                                qmask & rmask[i]);
+            uint32_t w0[3], w1[3];
+            x3_split2(y[0], y[1], w0);
+            x3_split2(y[2], y[3], w1);
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                *reinterpret_cast<uint2 *>(planes + pl * (128 * 32) + x3_img_at(rr + 32 * i, 4 * qg)) =
+                    make_uint2(w0[pl], w1[pl]);
+        }
+    }
+};
+
+template <int PROU, int PROV>
+__global__ __launch_bounds__(256, 2) void wgrad_x3_kernel(X3WgradArgs a)
+{
+    constexpr int BQ = 32, kPlane = 128 * 32; // planes in the layout of x3_img_at (128 rows)
+    __shared__ __attribute__((aligned(16))) uint16_t Us[3 * kPlane];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[3 * kPlane];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wa = wave >> 1, wb = wave & 1;
+    // workgroups that read the same pixels (all tiles of one split) run on the same XCD
+    // (blockIdx.x mod 8), so the operand that several tiles share comes out of that XCD's L2
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tiles = a.tilesA * a.tilesB;
+    const int split = (slot / tiles) * 8 + xcd, tile = slot % tiles;
+    if (split >= a.splits)
+        return;
+    const int a0 = (tile % a.tilesA) * 128, b0 = (tile / a.tilesA) * 128;
+    const int numChunks = (int)((a.Q + BQ - 1) / BQ);
+    const int cbeg = split * a.chunksPerSplit;
+    const int cend = min(cbeg + a.chunksPerSplit, numChunks);
+    const int qg = tid & 7, rr = tid >> 3;
+    X3Rows<PROU> ru;
+    X3Rows<PROV> rv;
+    ru.init(a.U, a0, rr, a.Ma);
+    rv.init(a.V, b0, rr, a.Mb);
+    uint32_t qmask = 0u;
+    // Prefetch of one chunk in registers: unconditional clamped loads, validity as an AND mask
+    // on the way into LDS.
+    auto load = [&](int chunk) __attribute__((always_inline)) {
+        const uint32_t q = (uint32_t)chunk * BQ + 4u * qg;
+        qmask = q < a.Q ? 0xffffffffu : 0u; // HW % 4 == 0: the run of four lies in one image
+        const uint32_t qc = qmask ? q : 0u;
+        const uint32_t n = fdiv(qc, a.divHW), pix = qc - n * (uint32_t)a.HW;
+        ru.load(a.U, a0, rr, a.Ma, a.HW, n, pix);
+        rv.load(a.V, b0, rr, a.Mb, a.HW, n, pix);
+    };
+    auto store = [&]() __attribute__((always_inline)) {
+        ru.store(Us, rr, qg, qmask);
+        rv.store(Vs, rr, qg, qmask);
+    };
+
+    float16v acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0.f;
+    if (cbeg < cend) { // uniform over the workgroup; an empty split writes zeros
+        load(cbeg);
+        store();
+        __syncthreads();
+        for (int cc = cbeg; cc < cend; ++cc) {
+            load(min(cc + 1, cend - 1));
+            // the loads are all issued before the MFMAs start and nothing that uses their data
+            // moves up among the MFMAs (the scheduler would otherwise wait for them there)
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < BQ / 16; ++s) {
+                const int ko = 16 * s + 8 * (lane >> 5);
+                bf16x8 av[2][3], bv[2][3];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int pl = 0; pl < 3; ++pl) {
+                        av[i][pl] = x3_lds8(Us + pl * kPlane + x3_img_at(wa * 64 + 32 * i + (lane & 31), ko));
+                        bv[i][pl] = x3_lds8(Vs + pl * kPlane + x3_img_at(wb * 64 + 32 * i + (lane & 31), ko));
+                    }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = x3_mfma6(av[i], bv[j], acc[i][j]); // rows past the end are zeros
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads(); // every wavefront has read the chunk
+            store();         // the repeated last chunk is stored but never consumed
+            __syncthreads();
+        }
+    }
+    float *dst = a.partial + (size_t)split * a.Ma * a.Mb;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ai = a0 + wa * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int bi = b0 + wb * 64 + 32 * j + (lane & 31);
+                if (ai < a.Ma && bi < a.Mb)
+                    dst[(size_t)ai * a.Mb + bi] = acc[i][j][r];
+            }
+}
+
+// Splits of the contraction: about 512 workgroups (two fit a compute unit), at least two chunks each.
+bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits)
+{
+    const long long Q = (long long)N * HW;
+    if (Q >= (1ll << 31) || HW % 4 != 0 || Ma < 64 || Mb < 64)
+        return false;
+    const long long tiles = (long long)((Ma + 127) / 128) * ((Mb + 127) / 128);
+    const long long chunks = (Q + 31) / 32;
+    long long s = (512 + tiles - 1) / tiles;
+    const long long smax = (chunks + 1) / 2;
+    if (s > smax)
+        s = smax;
+    if (s < 1)
+        s = 1;
+    const long long per = (chunks + s - 1) / s;
+    *splits = (int)((chunks + per - 1) / per);
+    return true;
+}
+
+hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
+                           float *partial, int *splits_out, hipStream_t st)
+{
+    int splits;
+    if (!x3_wgrad_plan(Ma, Mb, N, HW, &splits))
+        return hipErrorInvalidValue;
+    X3WgradArgs a;
+    a.Ma = Ma;
+    a.Mb = Mb;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    const int chunks = (int)((a.Q + 31u) / 32u);
+    a.chunksPerSplit = (chunks + splits - 1) / splits;
+    a.divHW = make_div((uint32_t)HW);
+    a.U.p0 = (const float *)U.p0;
+    a.U.p1 = (const float *)U.p1;
+    a.U.c0 = U.c0;
+    a.U.c1 = U.c1;
+    a.U.c2 = U.c2;
+    a.U.gate = U.gate;
+    a.V.p0 = (const float *)V.p0;
+    a.V.p1 = (const float *)V.p1;
+    a.V.c0 = V.c0;
+    a.V.c1 = V.c1;
+    a.V.c2 = V.c2;
+    a.V.gate = V.gate;
+    a.partial = partial;
+    *splits_out = splits;
+    a.tilesA = (Ma + 127) / 128;
+    a.tilesB = (Mb + 127) / 128;
+    a.splits = splits;
+    dim3 grid((unsigned)(((splits + 7) / 8) * 8 * a.tilesA * a.tilesB));
+#define MBK_CASE(PU, PV)                                                                          \
+    if (U.pro == PU && V.pro == PV) {                                                             \
+        hipLaunchKernelGGL((wgrad_x3_kernel<PU, PV>), grid, dim3(256), 0, st, a);                 \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(PRO_BNBWD, PRO_NONE)
+    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+} // namespace mbk

@@ -26,12 +26,17 @@ struct Plan {
     int HW, HWo;
     // saved workspace (byte offsets)
     size_t o_e, o_d, o_p, o_bn1, o_bn2, o_bn3, o_z, o_g, o_q, o_s3, o_s4, o_a1, o_sc, saved_bytes;
+    // weight images of the four 1x1 convolutions (kAbsent where the kernel family that serves
+    // the shape reads the weights themselves): expansion conv, projection conv, projection data
+    // gradient, expansion data gradient; written by forward, read again by backward
+    size_t o_wimg[4];
     // scratch workspace (byte offsets)
     size_t o_part;  // partial sums: 2 arrays of part_floats
     size_t o_wg2;   // projection weight gradient's partials while their reduction is deferred
     size_t o_part2; // partial sums of the depthwise output: 2 arrays of Cexp*NPdw
     size_t part_floats;
     size_t o_G, o_dy1, o_coef3, o_coef2, o_coef1, o_dg, o_A1, o_A2, o_dt, o_dq, o_dzs, o_pdw, o_wg;
+    size_t o_splitk; // partial tiles of a split 1x1 convolution
     size_t scratch_bytes;
     int NT1, NT5; // q-tiles of the expansion / projection conv
     int NPdw;     // partial results per channel of the depthwise kernels
@@ -127,6 +132,15 @@ Plan make_plan(const mbconv_desc *d)
     P.o_s4 = take((size_t)P.N * P.Cexp * f);
     P.o_a1 = (P.store && P.expand) ? take(P.nE * P.esz) : kAbsent;
     P.o_sc = P.store ? take(P.nD * P.esz) : kAbsent;
+    {
+        const bool use[4] = {P.expand && conv1x1_uses_weight_image(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false),
+                             conv1x1_uses_weight_image(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, P.store),
+                             conv1x1_uses_weight_image(P.bf16, P.N, P.Cexp, P.Cout, P.HWo, false),
+                             P.expand && conv1x1_uses_weight_image(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false)};
+        const int M[4] = {P.Cexp, P.Cout, P.Cexp, P.Cin}, K[4] = {P.Cin, P.Cexp, P.Cout, P.Cexp};
+        for (int i = 0; i < 4; ++i)
+            P.o_wimg[i] = use[i] ? take(x3_weight_image_bytes(M[i], K[i])) : kAbsent;
+    }
     P.saved_bytes = o;
 
     o = 0;
@@ -155,14 +169,14 @@ Plan make_plan(const mbconv_desc *d)
     size_t wg = (size_t)wgrad_splits(P.bf16, P.Cout, P.Cexp, P.N, P.HWo) * P.Cout * P.Cexp;
     if (P.expand)
         wg = std::max(wg, (size_t)wgrad_splits(P.bf16, P.Cexp, P.Cin, P.N, P.HW) * P.Cexp * P.Cin);
-    // the same region holds the partial tiles of a split 1x1 convolution
-    wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, P.store));
-    wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cexp, P.Cout, P.HWo, false));
-    if (P.expand) {
-        wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false));
-        wg = std::max(wg, conv1x1_splitk_floats(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false));
-    }
     P.o_wg = take(wg * f);
+    size_t sk = conv1x1_splitk_floats(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, P.store);
+    sk = std::max(sk, conv1x1_splitk_floats(P.bf16, P.N, P.Cexp, P.Cout, P.HWo, false));
+    if (P.expand) {
+        sk = std::max(sk, conv1x1_splitk_floats(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false));
+        sk = std::max(sk, conv1x1_splitk_floats(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false));
+    }
+    P.o_splitk = take(sk * f);
     P.o_wg2 = P.expand ? take((size_t)wgrad_splits(P.bf16, P.Cout, P.Cexp, P.N, P.HWo) * P.Cout * P.Cexp * f)
                        : kAbsent;
     P.scratch_bytes = o;
@@ -264,7 +278,7 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
     float *psq = psum + P.part_floats;
     float *psum2 = at<float>(scratch, P.o_part2);
     float *psq2 = psum2 + (size_t)P.Cexp * P.NPdw;
-    float *wg = at<float>(scratch, P.o_wg);
+    float *splitk = at<float>(scratch, P.o_splitk);
     float *bn2 = at<float>(saved, P.o_bn2), *bn3 = at<float>(saved, P.o_bn3);
     float *bn1 = P.expand ? at<float>(saved, P.o_bn1) : nullptr;
     void *d = at<char>(saved, P.o_d), *p = at<char>(saved, P.o_p);
@@ -278,6 +292,36 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
     };
     if (eval)
         MBK_STEP(P.expand ? MBCONV_STEP_BN1_FINALIZE : MBCONV_STEP_BN2_FINALIZE, eval_coefs());
+    // Weight images of the convolutions that want them (one launch; the two data-gradient images
+    // only in training mode).  The launch belongs to the step of the first convolution.
+    const auto wimg = [&](int i) -> const void * {
+        return P.o_wimg[i] == kAbsent ? nullptr : at<char>(saved, P.o_wimg[i]);
+    };
+    const auto prep_images = [&]() -> hipError_t {
+        const float *w[4];
+        int M[4], K[4], sm[4], sk[4], n = 0;
+        void *img[4];
+        const float *we = (const float *)prm->w_expand, *wp = (const float *)prm->w_proj;
+        const auto add = [&](int i, const float *src, int m, int k, int s_m, int s_k) {
+            if (P.o_wimg[i] == kAbsent)
+                return;
+            w[n] = src;
+            M[n] = m;
+            K[n] = k;
+            sm[n] = s_m;
+            sk[n] = s_k;
+            img[n] = at<char>(saved, P.o_wimg[i]);
+            ++n;
+        };
+        add(0, we, P.Cexp, P.Cin, P.Cin, 1);
+        add(1, wp, P.Cout, P.Cexp, P.Cexp, 1);
+        if (!eval) {
+            add(2, wp, P.Cexp, P.Cout, 1, P.Cexp);
+            add(3, we, P.Cin, P.Cexp, 1, P.Cin);
+        }
+        return n ? launch_x3_prep(n, w, M, K, sm, sk, img, st) : hipSuccess;
+    };
+    bool images_ready = false;
     // expansion conv + BN1 statistics
     const void *dw_in = x;
     if (P.expand) {
@@ -285,8 +329,15 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
         Operand B;
         B.p0 = x;
         B.pro = PRO_NONE;
-        MBK_STEP(MBCONV_STEP_EXPAND_CONV, launch_conv1x1(bf, P.N, P.Cexp, P.Cin, P.HW, prm->w_expand, P.Cin, 1, B, e,
-                               EPI_STATS, nullptr, psum, psq, nullptr, wg, st));
+        const auto conv = [&]() -> hipError_t {
+            const hipError_t pe = prep_images();
+            if (pe != hipSuccess)
+                return pe;
+            return launch_conv1x1(bf, P.N, P.Cexp, P.Cin, P.HW, prm->w_expand, P.Cin, 1, B, e, EPI_STATS,
+                                  nullptr, psum, psq, nullptr, splitk, st, wimg(0));
+        };
+        MBK_STEP(MBCONV_STEP_EXPAND_CONV, conv());
+        images_ready = true;
         dw_in = e;
     }
     // A normalisation's finalise step (partial sums -> scale, shift, mean, rstd, running
@@ -338,8 +389,14 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
             // go into the convolution's epilogue where the kernel family has one
             hipError_t fused = hipSuccess;
             const auto try_fused = [&]() {
+                if (!images_ready) { // a block without expansion conv
+                    const hipError_t pe = prep_images();
+                    if (pe != hipSuccess)
+                        return pe;
+                    images_ready = true;
+                }
                 fused = launch_conv1x1_affine(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B,
-                                              out, P.res ? x : nullptr, bn3, bn3 + P.Cout, st);
+                                              out, P.res ? x : nullptr, bn3, bn3 + P.Cout, st, wimg(1));
                 return fused == hipErrorNotSupported ? hipSuccess : fused;
             };
             MBK_STEP(MBCONV_STEP_PROJ_CONV, try_fused());
@@ -347,8 +404,17 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
                 return MBCONV_OK;
         }
         void *sc_store = (P.store && !eval) ? at<char>(saved, P.o_sc) : nullptr;
-        MBK_STEP(MBCONV_STEP_PROJ_CONV, launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p,
-                               EPI_STATS, nullptr, psum, psq, sc_store, wg, st));
+        const auto conv = [&]() -> hipError_t {
+            if (!images_ready) { // a block without expansion conv
+                const hipError_t pe = prep_images();
+                if (pe != hipSuccess)
+                    return pe;
+                images_ready = true;
+            }
+            return launch_conv1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, prm->w_proj, P.Cexp, 1, B, p, EPI_STATS,
+                                  nullptr, psum, psq, sc_store, splitk, st, wimg(1));
+        };
+        MBK_STEP(MBCONV_STEP_PROJ_CONV, conv());
         if (!eval && !fuse3)
             MBK_STEP(MBCONV_STEP_BN3_FINALIZE, launch_bn_finalize(P.Cout, P.NT5, m2, psum, psq, prm->bn3_gamma,
                                        prm->bn3_beta, eps, mom, fin3.run_mean, fin3.run_var, bn3, st));
@@ -397,7 +463,7 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
     const float *q = at<float>(saved, P.o_q);
     float *coef3 = at<float>(scratch, P.o_coef3), *coef2 = at<float>(scratch, P.o_coef2);
     void *G = at<char>(scratch, P.o_G);
-    float *wg = at<float>(scratch, P.o_wg);
+    float *wg = at<float>(scratch, P.o_wg), *splitk = at<float>(scratch, P.o_splitk);
     const double m2 = (double)P.N * P.HWo;
 
     // BN3 backward reductions
@@ -445,7 +511,8 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
                          launch_reduce_splits2(proj_reduce, {nullptr, 0, 0, nullptr}, st));
         } else {
             MBK_STEP(MBCONV_STEP_PROJ_DGRAD, launch_conv1x1(bf, P.N, P.Cexp, P.Cout, P.HWo, prm->w_proj, 1, P.Cexp, dp,
-                                                            G, EPI_NONE, nullptr, nullptr, nullptr, nullptr, wg, st));
+                                                            G, EPI_NONE, nullptr, nullptr, nullptr, nullptr, splitk, st,
+                                                            P.o_wimg[2] == kAbsent ? nullptr : at<char>(saved, P.o_wimg[2])));
             MBK_STEP(MBCONV_STEP_PROJ_WGRAD,
                      launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, pwg, gr->w_proj,
                                      P.expand ? &proj_reduce : nullptr, st));
@@ -544,7 +611,8 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
         }
         MBK_STEP(MBCONV_STEP_EXPAND_DGRAD, launch_conv1x1(bf, P.N, P.Cin, P.Cexp, P.HW, prm->w_expand, 1, P.Cin, de, dx,
                                P.res ? EPI_RES : EPI_NONE, P.res ? dout : nullptr, nullptr, nullptr,
-                               nullptr, wg, st));
+                               nullptr, splitk, st,
+                               P.o_wimg[3] == kAbsent ? nullptr : at<char>(saved, P.o_wimg[3])));
         Operand xo;
         xo.p0 = x;
         xo.pro = PRO_NONE;

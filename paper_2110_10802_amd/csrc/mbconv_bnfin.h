@@ -106,10 +106,13 @@ __device__ __forceinline__ void bn_fin_finish(const BnFin &f, int C, int c, int 
     double var = s2 * f.inv_m - mean * mean;
     if (var < 0.0)
         var = 0.0;
-    // 1/sqrt: the hardware estimate and one Newton step (the result is rounded to fp32)
+    // 1/sqrt: the hardware estimate and one Newton step (the result is rounded to fp32); for
+    // eps = 0 and a constant channel the estimate is already the answer (inf, as 1/sqrt(0) in
+    // the separate finalisation kernel) and the step would turn it into inf * 0
     const double xv = var + (double)f.eps;
     double rstd = __builtin_amdgcn_rsq(xv);
-    rstd = rstd * (1.5 - 0.5 * xv * rstd * rstd);
+    if (xv > 0.0)
+        rstd = rstd * (1.5 - 0.5 * xv * rstd * rstd);
     const double scale = (double)r.gm * rstd;
     sc = (float)scale;
     sh = (float)((double)r.bt - mean * scale);

@@ -39,9 +39,21 @@ inline int conv1x1_num_qtiles(int N, int HW) { return (int)(((long long)N * HW +
 // conv1x1_splitk_floats(...) floats (0 when the launch does not split).
 int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand);
 size_t conv1x1_splitk_floats(bool bf16, int N, int M, int K, int HW, bool stores_operand);
+//
+// fp32 convolutions of the wide blocks take their A operand from a weight image (bf16 planes in
+// the order the kernel keeps them in LDS, see kernels_x3.hip): where
+// conv1x1_uses_weight_image(...) says so, `wimg` must point to the image of this A (M rows, K
+// contraction indices), x3_weight_image_bytes(M, K) bytes, written by launch_x3_prep beforehand;
+// `w` is then not read.
+bool conv1x1_uses_weight_image(bool bf16, int N, int M, int K, int HW, bool stores_operand);
+size_t x3_weight_image_bytes(int M, int K);
+// Writes up to four images in one launch; image i is of A(m,k) = w[i][m*sm[i] + k*sk[i]], M[i] x K[i].
+hipError_t launch_x3_prep(int nsets, const float *const *w, const int *M, const int *K, const int *sm,
+                          const int *sk, void *const *img, hipStream_t st);
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
-                          float *psq, void *sc_store, float *splitk_ws, hipStream_t st);
+                          float *psq, void *sc_store, float *splitk_ws, hipStream_t st,
+                          const void *wimg = nullptr);
 
 // The same convolution with out = acc*scale[m] + shift[m] (+ res if non-null) as its epilogue.
 // Returns hipErrorNotSupported (nothing launched) when the kernel family that serves this
@@ -49,7 +61,8 @@ hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w,
 // steps.
 hipError_t launch_conv1x1_affine(bool bf16, int N, int M, int K, int HW, const void *w, int sAm,
                                  int sAk, const Operand &B, void *out, const void *res,
-                                 const float *scale, const float *shift, hipStream_t st);
+                                 const float *scale, const float *shift, hipStream_t st,
+                                 const void *wimg = nullptr);
 
 // Weight gradient of a 1x1 conv: dW[a,b] = sum_{n,q} op(U)[n,a,q] * op(V)[n,b,q].
 // `partial` needs wgrad_splits(...)*Ma*Mb floats.
