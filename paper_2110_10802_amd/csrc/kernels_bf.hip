@@ -46,6 +46,14 @@ __device__ __forceinline__ float bf_apply(float v0, float v1, float k0, float k1
         return actf(fmaf(v0, k0, k1)) * k2;
     return fmaf(k0, v0, fmaf(k1, v1, k2));
 }
+// Column of contraction index k in row `row` of the activation tile: the four 16-byte groups of
+// a row are permuted by bits 4-5 of the row, so that the transposing stores of a wavefront
+// (one 32-bit k pair to each of 16 rows that are four apart) fall on distinct banks; the
+// 16-byte fragment reads of 16 consecutive rows stay conflict-free.
+__device__ __forceinline__ int bf_bcol(int row, int k)
+{
+    return ((((k >> 3) ^ (row >> 4)) & 3) << 3) + (k & 7);
+}
 __device__ __forceinline__ bf16x8 bf_lds8(const uint16_t *p)
 {
     return *reinterpret_cast<const bf16x8 *>(p);
@@ -172,10 +180,10 @@ __global__ __launch_bounds__(256) void conv_bf_kernel(BfConvArgs a)
             // no arithmetic: re-pair the halves of the two channel rows
             const uint2 lo = make_uint2(rb0[slot_][0].x & rbok[slot_][0], rb0[slot_][0].y & rbok[slot_][0]);
             const uint2 hi = make_uint2(rb0[slot_][1].x & rbok[slot_][1], rb0[slot_][1].y & rbok[slot_][1]);
-            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + 0][2 * kp]) = (lo.x & 0xffffu) | (hi.x << 16);
-            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + 1][2 * kp]) = (lo.x >> 16) | (hi.x & 0xffff0000u);
-            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + 2][2 * kp]) = (lo.y & 0xffffu) | (hi.y << 16);
-            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + 3][2 * kp]) = (lo.y >> 16) | (hi.y & 0xffff0000u);
+            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + 0][bf_bcol(4 * pg, 2 * kp)]) = (lo.x & 0xffffu) | (hi.x << 16);
+            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + 1][bf_bcol(4 * pg, 2 * kp)]) = (lo.x >> 16) | (hi.x & 0xffff0000u);
+            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + 2][bf_bcol(4 * pg, 2 * kp)]) = (lo.y & 0xffffu) | (hi.y << 16);
+            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + 3][bf_bcol(4 * pg, 2 * kp)]) = (lo.y >> 16) | (hi.y & 0xffff0000u);
             return;
         }
         float v[2][4];
@@ -192,7 +200,7 @@ __global__ __launch_bounds__(256) void conv_bf_kernel(BfConvArgs a)
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + r][2 * kp]) = bf_pack2(v[0][r], v[1][r]);
+            *reinterpret_cast<uint32_t *>(&Bs[buf][4 * pg + r][bf_bcol(4 * pg, 2 * kp)]) = bf_pack2(v[0][r], v[1][r]);
     };
 
     float16v acc[WM];
@@ -223,7 +231,7 @@ __global__ __launch_bounds__(256) void conv_bf_kernel(BfConvArgs a)
         load_b(u, cl * BK);
 #pragma unroll
         for (int s = 0; s < BK / 16; ++s) {
-            const bf16x8 bv = bf_lds8(&Bs[buf][wp * 32 + (lane & 31)][16 * s + 8 * (lane >> 5)]);
+            const bf16x8 bv = bf_lds8(&Bs[buf][wp * 32 + (lane & 31)][bf_bcol(wp * 32 + (lane & 31), 16 * s + 8 * (lane >> 5))]);
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
                 const bf16x8 av = bf_lds8(&As[buf][wm * 32 * WM + 32 * i + (lane & 31)][16 * s + 8 * (lane >> 5)]);

@@ -529,11 +529,12 @@ hipError_t launch_x3_conv1x1(int N, int M, int K, int HW, const void *wimg, cons
 // ---- weight gradient -------------------------------------------------------------------------
 // dW[a,b] = sum_q op(U)[a,q] * op(V)[b,q].  Both operands are pixel-contiguous in memory, which
 // is the [row][k] layout the instruction wants, so a run of four pixels goes through its
-// prologue, is split and lands in LDS as one 8-byte store per plane.  A workgroup owns 128 rows
-// of U by 128 rows of V (each wavefront 64 x 64: four accumulator tiles, so every operand
-// fragment read from LDS feeds two MFMA groups) and a range of 32-pixel chunks (blockIdx.z);
-// with the narrow operand inside one tile the wide one is staged, and sent through its prologue,
-// once in the whole grid.  The splits' partial tiles are added by a fixed-order second stage.
+// prologue, is split and lands in LDS as one 8-byte store per plane.  A workgroup of eight
+// wavefronts owns 128 rows of U by 128 rows of V (each wavefront 64 x 32) and a range of
+// 32-pixel chunks; with the narrow operand inside one tile the wide one is staged, and sent
+// through its prologue, once in the whole grid.  Chunks are loaded two iterations ahead into a
+// ring of two register slots, so HBM stays busy while a chunk is split and multiplied.  The
+// splits' partial tiles are added by a fixed-order second stage.
 struct X3WgradArgs {
     int Ma, Mb, HW;
     uint32_t Q;
@@ -544,19 +545,16 @@ struct X3WgradArgs {
     float *partial;
 };
 
-// one operand's staging state: rows rr + 32*i (i < 4) of the 128-row tile, pixel run 4*qg
+// what a thread keeps per operand for the whole kernel: rows rr + 64*i (i < 2) of the 128-row tile
 template <int PRO>
-struct X3Rows {
-    float v0[4][4], v1[4][PRO == PRO_BNBWD ? 4 : 1];
-    float g[4];
-    float k0[4], k1[4], k2[4];
-    uint32_t rmask[4];
-
+struct X3RowConst {
+    float k0[2], k1[2], k2[2];
+    uint32_t rmask[2];
     __device__ __forceinline__ void init(const X3Operand &o, int row0, int rr, int M)
     {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = row0 + rr + 32 * i;
+        for (int i = 0; i < 2; ++i) {
+            const int r = row0 + rr + 64 * i;
             rmask[i] = r < M ? 0xffffffffu : 0u;
             k0[i] = k1[i] = k2[i] = 0.f;
             if (PRO != PRO_NONE && r < M) {
@@ -567,15 +565,21 @@ struct X3Rows {
             }
         }
     }
-    // n, pix: image and first pixel of the run (it lies inside one plane: HW % 4 == 0)
+};
+// one ring slot of an operand: the raw pixel runs (four pixels at 4*qg) of the thread's two rows
+template <int PRO>
+struct X3RowData {
+    float v0[2][4], v1[2][PRO == PRO_BNBWD ? 4 : 1];
+    float g[2];
+    // n, pix: image and first pixel of the run (it lies inside one plane: HW % 4 == 0).  Both rows
+    // load, also past the last row (clamped, masked on the way into LDS): a branch around a load
+    // would make the loads behind it wait.
     __device__ __forceinline__ void load(const X3Operand &o, int row0, int rr, int M, int HW, uint32_t n,
                                          uint32_t pix)
     {
-        // every pass loads, also past the last row (clamped, masked on the way into LDS): a branch
-        // around a load would make the loads of the following passes wait for it
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = min(row0 + rr + 32 * i, M - 1);
+        for (int i = 0; i < 2; ++i) {
+            const int r = min(row0 + rr + 64 * i, M - 1);
             const size_t idx = ((size_t)n * M + r) * HW + pix;
             x3_ld4(o.p0, idx, v0[i]);
             if constexpr (PRO == PRO_BNBWD)
@@ -584,37 +588,38 @@ struct X3Rows {
                 g[i] = o.gate[(size_t)n * M + r];
         }
     }
-    // prologue, split, three 8-byte LDS stores per pass
-    __device__ __forceinline__ void store(uint16_t *planes, int rr, int qg, uint32_t qmask) const
+    // prologue, split, three 8-byte LDS stores per row
+    __device__ __forceinline__ void store(const X3RowConst<PRO> &c, uint16_t *planes, int rr, int qg,
+                                          uint32_t qmask) const
     {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             float y[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                y[j] = and_mask(x3_apply<PRO>(v0[i][j], v1[i][PRO == PRO_BNBWD ? j : 0], k0[i], k1[i],
-                                              PRO == PRO_BNSWISH_GATE ? g[i] : k2[i]),
-                                qmask & rmask[i]);
+                y[j] = and_mask(x3_apply<PRO>(v0[i][j], v1[i][PRO == PRO_BNBWD ? j : 0], c.k0[i], c.k1[i],
+                                              PRO == PRO_BNSWISH_GATE ? g[i] : c.k2[i]),
+                                qmask & c.rmask[i]);
             uint32_t w0[3], w1[3];
             x3_split2(y[0], y[1], w0);
             x3_split2(y[2], y[3], w1);
 #pragma unroll
             for (int pl = 0; pl < 3; ++pl)
-                *reinterpret_cast<uint2 *>(planes + pl * (128 * 32) + x3_img_at(rr + 32 * i, 4 * qg)) =
+                *reinterpret_cast<uint2 *>(planes + pl * (128 * 32) + x3_img_at(rr + 64 * i, 4 * qg)) =
                     make_uint2(w0[pl], w1[pl]);
         }
     }
 };
 
 template <int PROU, int PROV>
-__global__ __launch_bounds__(256, 2) void wgrad_x3_kernel(X3WgradArgs a)
+__global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
 {
     constexpr int BQ = 32, kPlane = 128 * 32; // planes in the layout of x3_img_at (128 rows)
     __shared__ __attribute__((aligned(16))) uint16_t Us[3 * kPlane];
     __shared__ __attribute__((aligned(16))) uint16_t Vs[3 * kPlane];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wa = wave >> 1, wb = wave & 1;
+    const int wa = wave >> 2, wb = wave & 3; // rows 64*wa.. of U, 32*wb.. of V
     // workgroups that read the same pixels (all tiles of one split) run on the same XCD
     // (blockIdx.x mod 8), so the operand that several tiles share comes out of that XCD's L2
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -627,81 +632,83 @@ __global__ __launch_bounds__(256, 2) void wgrad_x3_kernel(X3WgradArgs a)
     const int cbeg = split * a.chunksPerSplit;
     const int cend = min(cbeg + a.chunksPerSplit, numChunks);
     const int qg = tid & 7, rr = tid >> 3;
-    X3Rows<PROU> ru;
-    X3Rows<PROV> rv;
-    ru.init(a.U, a0, rr, a.Ma);
-    rv.init(a.V, b0, rr, a.Mb);
-    uint32_t qmask = 0u;
-    // Prefetch of one chunk in registers: unconditional clamped loads, validity as an AND mask
-    // on the way into LDS.
-    auto load = [&](int chunk) __attribute__((always_inline)) {
+    X3RowConst<PROU> cu;
+    X3RowConst<PROV> cv;
+    cu.init(a.U, a0, rr, a.Ma);
+    cv.init(a.V, b0, rr, a.Mb);
+    X3RowData<PROU> du[2];
+    X3RowData<PROV> dv[2];
+    uint32_t qmask[2] = {0u, 0u};
+    // unconditional clamped loads, validity as an AND mask on the way into LDS
+    auto load = [&](int s, int chunk) __attribute__((always_inline)) {
         const uint32_t q = (uint32_t)chunk * BQ + 4u * qg;
-        qmask = q < a.Q ? 0xffffffffu : 0u; // HW % 4 == 0: the run of four lies in one image
-        const uint32_t qc = qmask ? q : 0u;
+        qmask[s] = q < a.Q ? 0xffffffffu : 0u; // HW % 4 == 0: the run of four lies in one image
+        const uint32_t qc = qmask[s] ? q : 0u;
         const uint32_t n = fdiv(qc, a.divHW), pix = qc - n * (uint32_t)a.HW;
-        ru.load(a.U, a0, rr, a.Ma, a.HW, n, pix);
-        rv.load(a.V, b0, rr, a.Mb, a.HW, n, pix);
+        du[s].load(a.U, a0, rr, a.Ma, a.HW, n, pix);
+        dv[s].load(a.V, b0, rr, a.Mb, a.HW, n, pix);
     };
-    auto store = [&]() __attribute__((always_inline)) {
-        ru.store(Us, rr, qg, qmask);
-        rv.store(Vs, rr, qg, qmask);
+    auto store = [&](int s) __attribute__((always_inline)) {
+        du[s].store(cu, Us, rr, qg, qmask[s]);
+        dv[s].store(cv, Vs, rr, qg, qmask[s]);
     };
 
-    float16v acc[2][2];
+    float16v acc[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[i][j][r] = 0.f;
+        for (int r = 0; r < 16; ++r)
+            acc[i][r] = 0.f;
     if (cbeg < cend) { // uniform over the workgroup; an empty split writes zeros
-        load(cbeg);
-        store();
+        load(0, cbeg);
+        load(1, min(cbeg + 1, cend - 1));
+        store(0);
         __syncthreads();
-        for (int cc = cbeg; cc < cend; ++cc) {
-            load(min(cc + 1, cend - 1));
+        auto step = [&](int u, int cc) __attribute__((always_inline)) {
+            load(u, min(cc + 2, cend - 1)); // slot u is free: its chunk went to LDS last iteration
             // the loads are all issued before the MFMAs start and nothing that uses their data
             // moves up among the MFMAs (the scheduler would otherwise wait for them there)
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int s = 0; s < BQ / 16; ++s) {
                 const int ko = 16 * s + 8 * (lane >> 5);
-                bf16x8 av[2][3], bv[2][3];
+                bf16x8 av[2][3], bv[3];
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int pl = 0; pl < 3; ++pl) {
-                        av[i][pl] = x3_lds8(Us + pl * kPlane + x3_img_at(wa * 64 + 32 * i + (lane & 31), ko));
-                        bv[i][pl] = x3_lds8(Vs + pl * kPlane + x3_img_at(wb * 64 + 32 * i + (lane & 31), ko));
-                    }
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[i][j] = x3_mfma6(av[i], bv[j], acc[i][j]); // rows past the end are zeros
+                for (int pl = 0; pl < 3; ++pl) {
+                    av[0][pl] = x3_lds8(Us + pl * kPlane + x3_img_at(wa * 64 + (lane & 31), ko));
+                    av[1][pl] = x3_lds8(Us + pl * kPlane + x3_img_at(wa * 64 + 32 + (lane & 31), ko));
+                    bv[pl] = x3_lds8(Vs + pl * kPlane + x3_img_at(wb * 32 + (lane & 31), ko));
+                }
+                acc[0] = x3_mfma6(av[0], bv, acc[0]); // rows past the end are zeros
+                acc[1] = x3_mfma6(av[1], bv, acc[1]);
             }
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads(); // every wavefront has read the chunk
-            store();         // the repeated last chunk is stored but never consumed
+            store(u ^ 1);    // the repeated last chunk is stored but never consumed
             __syncthreads();
+        };
+        int cc = cbeg;
+        for (; cc + 1 < cend; cc += 2) {
+            step(0, cc);
+            step(1, cc + 1);
         }
+        if (cc < cend) // uniform over the workgroup
+            step(0, cc);
     }
     float *dst = a.partial + (size_t)split * a.Ma * a.Mb;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int ai = a0 + wa * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const int bi = b0 + wb * 64 + 32 * j + (lane & 31);
-                if (ai < a.Ma && bi < a.Mb)
-                    dst[(size_t)ai * a.Mb + bi] = acc[i][j][r];
-            }
+        for (int r = 0; r < 16; ++r) {
+            const int ai = a0 + wa * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            const int bi = b0 + wb * 32 + (lane & 31);
+            if (ai < a.Ma && bi < a.Mb)
+                dst[(size_t)ai * a.Mb + bi] = acc[i][r];
+        }
 }
 
-// Splits of the contraction: about 512 workgroups (two fit a compute unit), at least two chunks each.
+// Splits of the contraction: about one workgroup (eight wavefronts) per compute unit, at least two
+// chunks each.
 bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits)
 {
     const long long Q = (long long)N * HW;
@@ -709,7 +716,7 @@ bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits)
         return false;
     const long long tiles = (long long)((Ma + 127) / 128) * ((Mb + 127) / 128);
     const long long chunks = (Q + 31) / 32;
-    long long s = (512 + tiles - 1) / tiles;
+    long long s = (256 + tiles - 1) / tiles; // 512 workgroups measured slower (twice the partial tiles)
     const long long smax = (chunks + 1) / 2;
     if (s > smax)
         s = smax;
@@ -754,7 +761,7 @@ hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, cons
     dim3 grid((unsigned)(((splits + 7) / 8) * 8 * a.tilesA * a.tilesB));
 #define MBK_CASE(PU, PV)                                                                          \
     if (U.pro == PU && V.pro == PV) {                                                             \
-        hipLaunchKernelGGL((wgrad_x3_kernel<PU, PV>), grid, dim3(256), 0, st, a);                 \
+        hipLaunchKernelGGL((wgrad_x3_kernel<PU, PV>), grid, dim3(512), 0, st, a);                 \
         return hipGetLastError();                                                                 \
     }
     MBK_CASE(PRO_BNBWD, PRO_NONE)
