@@ -64,6 +64,17 @@ __device__ __forceinline__ void x3_ld4(const float *p, size_t i, float (&v)[4])
     v[2] = t.z;
     v[3] = t.w;
 }
+// four consecutive floats at an address that is only 4-byte aligned (pixel runs of planes whose
+// size is not a multiple of four)
+typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));
+__device__ __forceinline__ void x3_ld4u(const float *p, size_t i, float (&v)[4])
+{
+    const float4u t = *reinterpret_cast<const float4u *>(p + i);
+    v[0] = t[0];
+    v[1] = t[1];
+    v[2] = t[2];
+    v[3] = t[3];
+}
 
 // Halfword offset of element (row, k) in a [rows][BK = 32] plane of pitch 40 halfwords (80 bytes).
 // The four 16-byte groups of a row are permuted by bits 4-5 of the row: the transposing stores
@@ -192,13 +203,19 @@ struct X3ConvArgs {
 // out[n,m,pix] = sum_k A(m,k) * op(B)[n,k,pix], A given as a weight image.  Requirements
 // (checked by the host): K % 8 == 0, M % 4 == 0, HW % 4 == 0.
 //
+// PT (plane tiles, for planes of at most 64 pixels whose size is not a multiple of four: the
+// 7x7 stages): a tile's 64 columns are the pixels of ONE image (QT = N), columns past the plane
+// are zeros.  Pixel runs then never straddle an image; the last, partial run of a plane is read
+// and written four pixels wide starting at HW-4, overlapping the run before it with identical
+// values, so every access stays 16 bytes wide (4-byte aligned) and inside its plane.
+//
 // Persistent workgroups.  Output tiles are dealt out per XCD (blockIdx.x mod 8): XCD x owns the
 // pixel tiles qt = x, x+8, ... with all their row tiles, so the workgroups that read the same
 // activation tile share an L2; workgroup i of the XCD's Gx takes that list's tiles i, i+Gx, ...
 // The (tile, chunk) items of a workgroup form one stream: the register ring prefetches two
 // items ahead across tile boundaries, so the first chunks of the next tile are in flight while
 // the current tile's results leave, and the start-up latency is paid once per workgroup.
-template <int PRO, int EPI>
+template <int PRO, int EPI, bool PT>
 __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
 {
     constexpr int BM = 64, BP = 64, BK = 32, PK = BK + 8, PC = BP + 4;
@@ -230,7 +247,10 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
         return;
 
     // ---- prefetch cursor: the item the next load takes, and what depends on its tile ----
-    const int px = 4 * (tid & 15), kp = tid >> 4; // this thread's pixel run and k pair of a B chunk
+    // this thread's pixel run (tile columns brow .. brow+3) and k pair of a B chunk
+    const int c0 = 4 * (tid & 15), kp = tid >> 4;
+    const bool runIn = !PT || c0 < a.HW;                            // the run holds pixels of the plane
+    const int brow = (PT && runIn && c0 + 4 > a.HW) ? a.HW - 4 : c0; // the partial run starts at HW-4
     int pk = 0, pc = cbeg, pmt = 0;
     bool bvalid = false;
     uint32_t bn = 0;
@@ -239,10 +259,16 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
         const int t = wi + min(k, nT - 1) * Gx; // past the last tile: the last one again (never consumed)
         const int qt = xcd + 8 * (t / a.MT);
         pmt = t - (t / a.MT) * a.MT;
-        const uint32_t qb = (uint32_t)qt * BP + (uint32_t)px;
-        bvalid = qb < a.Q;
-        bn = bvalid ? fdiv(qb, a.divHW) : 0u;
-        bbase = (size_t)bn * a.K * a.HW + (bvalid ? qb - bn * (uint32_t)a.HW : 0u);
+        if (PT) {
+            bvalid = runIn;
+            bn = (uint32_t)qt;
+            bbase = (size_t)bn * a.K * a.HW + (runIn ? brow : 0);
+        } else {
+            const uint32_t qb = (uint32_t)qt * BP + (uint32_t)c0;
+            bvalid = qb < a.Q;
+            bn = bvalid ? fdiv(qb, a.divHW) : 0u;
+            bbase = (size_t)bn * a.K * a.HW + (bvalid ? qb - bn * (uint32_t)a.HW : 0u);
+        }
     };
     auto advance = [&]() __attribute__((always_inline)) {
         if (++pc == cend) { // uniform over the workgroup; no memory access inside
@@ -273,9 +299,16 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
         for (int j = 0; j < 2; ++j) {
             const int k = k0 + 2 * kp + j, kc = min(k, a.K - 1);
             rbok[s][j] = (bvalid && k < a.K) ? 0xffffffffu : 0u;
-            x3_ld4(a.B.p0, bbase + (size_t)kc * a.HW, rb0[s][j]);
-            if constexpr (PRO == PRO_BNBWD)
-                x3_ld4(a.B.p1, bbase + (size_t)kc * a.HW, rb1[s][j]);
+            if (PT)
+                x3_ld4u(a.B.p0, bbase + (size_t)kc * a.HW, rb0[s][j]);
+            else
+                x3_ld4(a.B.p0, bbase + (size_t)kc * a.HW, rb0[s][j]);
+            if constexpr (PRO == PRO_BNBWD) {
+                if (PT)
+                    x3_ld4u(a.B.p1, bbase + (size_t)kc * a.HW, rb1[s][j]);
+                else
+                    x3_ld4(a.B.p1, bbase + (size_t)kc * a.HW, rb1[s][j]);
+            }
             if (PRO != PRO_NONE) {
                 bk0[s][j] = a.B.c0[kc];
                 bk1[s][j] = a.B.c1[kc];
@@ -299,7 +332,7 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
             x3_split2(v[0], v[1], w);
 #pragma unroll
             for (int pl = 0; pl < 3; ++pl)
-                *reinterpret_cast<uint32_t *>(Bs(pl) + x3_at(px + r, 2 * kp)) = w[pl];
+                *reinterpret_cast<uint32_t *>(Bs(pl) + x3_at(brow + r, 2 * kp)) = w[pl];
         }
     };
 
@@ -312,16 +345,26 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
     auto epilogue = [&](int ck) __attribute__((always_inline)) {
         const int t = wi + ck * Gx;
         const int qt = xcd + 8 * (t / a.MT), m0 = (t - (t / a.MT) * a.MT) * BM;
-        const uint32_t q0 = (uint32_t)qt * BP;
+        const uint32_t q0 = PT ? (uint32_t)qt * (uint32_t)a.HW : (uint32_t)qt * BP; // first pixel of the tile
         if constexpr (EPI != EPI_PARTIAL) {
-            // Through LDS, so that 16 lanes own 64 consecutive pixels of one output row: 16-byte
-            // accesses, one pixel-index division per thread, and a row's BN statistics summed
-            // inside those 16 lanes.  (The chunk's barrier has passed: the operand buffer is free.)
+            // Through LDS, so that 16 lanes own the pixels of one output row: 16-byte accesses, one
+            // pixel-index division per thread, and a row's BN statistics summed inside those 16
+            // lanes.  (The chunk's barrier has passed: the operand buffer is free.)
             const int pg = tid & 15;
-            const uint32_t q = q0 + 4u * pg;
-            const bool valid = q < a.Q;
-            const uint32_t n = valid ? fdiv(q, a.divHW) : 0u;
-            const uint32_t pix = valid ? q - n * (uint32_t)a.HW : 0u;
+            bool valid;
+            uint32_t n, pix;
+            int fresh = 0; // first element of the run that no other run covers
+            if (PT) {
+                valid = runIn;
+                n = (uint32_t)qt;
+                pix = runIn ? (uint32_t)brow : 0u;
+                fresh = runIn ? c0 - brow : 0;
+            } else {
+                const uint32_t q = q0 + 4u * pg;
+                valid = q < a.Q;
+                n = valid ? fdiv(q, a.divHW) : 0u;
+                pix = valid ? q - n * (uint32_t)a.HW : 0u;
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 Ct[wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)][wp * 32 + (lane & 31)] = acc[r];
@@ -330,33 +373,54 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
             for (int i = 0; i < 4; ++i) {
                 const int row = (tid >> 4) + 16 * i, m = m0 + row;
                 const bool ok = valid && m < a.M;
-                const float4 c = *reinterpret_cast<const float4 *>(&Ct[row][4 * pg]);
-                float v[4] = {c.x, c.y, c.z, c.w};
+                float v[4];
+                if (PT) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[j] = Ct[row][(runIn ? brow : 0) + j];
+                } else {
+                    const float4 c = *reinterpret_cast<const float4 *>(&Ct[row][4 * pg]);
+                    v[0] = c.x;
+                    v[1] = c.y;
+                    v[2] = c.z;
+                    v[3] = c.w;
+                }
                 const size_t idx = ((size_t)n * a.M + min(m, a.M - 1)) * a.HW + pix;
+                float rr[4] = {0.f, 0.f, 0.f, 0.f};
+                if (EPI == EPI_RES || (EPI == EPI_AFFINE && a.res)) {
+                    if (PT)
+                        x3_ld4u(a.res, idx, rr);
+                    else
+                        x3_ld4(a.res, idx, rr);
+                }
                 if (EPI == EPI_RES) {
-                    const float4 rr = *reinterpret_cast<const float4 *>(a.res + idx);
-                    v[0] += rr.x;
-                    v[1] += rr.y;
-                    v[2] += rr.z;
-                    v[3] += rr.w;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[j] += rr[j];
                 }
                 if (EPI == EPI_AFFINE) { // psum / psq carry the row's scale and shift
                     const float osc = a.psum[min(m, a.M - 1)], osh = a.psq[min(m, a.M - 1)];
-                    float4 rr = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (a.res)
-                        rr = *reinterpret_cast<const float4 *>(a.res + idx);
-                    v[0] = fmaf(v[0], osc, osh) + rr.x;
-                    v[1] = fmaf(v[1], osc, osh) + rr.y;
-                    v[2] = fmaf(v[2], osc, osh) + rr.z;
-                    v[3] = fmaf(v[3], osc, osh) + rr.w;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        v[j] = fmaf(v[j], osc, osh) + rr[j];
                 }
-                if (ok)
-                    *reinterpret_cast<float4 *>(a.out + idx) = make_float4(v[0], v[1], v[2], v[3]);
+                if (ok) {
+                    if (PT) {
+                        float4u o;
+                        o[0] = v[0];
+                        o[1] = v[1];
+                        o[2] = v[2];
+                        o[3] = v[3];
+                        *reinterpret_cast<float4u *>(a.out + idx) = o;
+                    } else {
+                        *reinterpret_cast<float4 *>(a.out + idx) = make_float4(v[0], v[1], v[2], v[3]);
+                    }
+                }
                 if (EPI == EPI_STATS) {
                     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float sv = ok ? v[j] : 0.f;
+                        const float sv = (ok && j >= fresh) ? v[j] : 0.f;
                         s1 += sv;
                         s2 = fmaf(sv, sv, s2);
                     }
@@ -370,16 +434,31 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
             }
         } else {
             // a split contraction: the raw partial tile, lanes along the pixels
-            const uint32_t q = q0 + wp * 32 + (lane & 31);
+            const int col = wp * 32 + (lane & 31);
+            const uint32_t q = q0 + (uint32_t)col;
+            const bool valid = PT ? col < a.HW : q < a.Q;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (q < a.Q && m < a.M)
+                if (valid && m < a.M)
                     a.partial[((size_t)blockIdx.y * a.M + m) * a.Q + q] = acc[r];
             }
         }
     };
 
+    // PT: tile columns past the plane must read as zeros, and the pixel runs do not cover all of
+    // them (the partial run starts early); they are cleared before the first item and again after
+    // every output tile, which passes through the same LDS.  (A store and a barrier follow.)
+    auto zero_pad = [&]() __attribute__((always_inline)) {
+        if (PT) {
+            for (int i = tid; i < 3 * BP * 4; i += 256) {
+                const int pl = i / (BP * 4), row = (i >> 2) & (BP - 1), g = i & 3;
+                if (row >= a.HW)
+                    *reinterpret_cast<uint4 *>(Bs(pl) + row * PK + 8 * g) = make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+    };
+    zero_pad();
     set_ptile(0);
     load(0);
     advance();
@@ -408,6 +487,7 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
         if (++cj == nch) { // uniform: the tile is complete
             epilogue(ck);
             __syncthreads(); // the output tile has left LDS
+            zero_pad();
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 acc[r] = 0.f;
@@ -431,11 +511,14 @@ __global__ __launch_bounds__(256) void conv_x3_kernel(X3ConvArgs a)
 bool x3_conv_plan(int N, int M, int K, int HW, int *qtiles, int *splits)
 {
     const long long Q = (long long)N * HW;
-    // (planes whose size is not a multiple of four, the 7x7 stages, stay with kernels_big.hip:
-    // their pixel runs straddle image boundaries and the scalar staging measured slower here)
-    if (K % 8 != 0 || M % 4 != 0 || HW % 4 != 0 || Q >= (1ll << 31) || K < 32 || M < 32)
+    if (K % 8 != 0 || M % 4 != 0 || Q >= (1ll << 31) || K < 32 || M < 32)
         return false;
-    *qtiles = (int)((Q + 63) / 64);
+    // planes whose size is not a multiple of four: one image per tile if a plane fits (the 7x7
+    // stages); larger ones stay with kernels_big.hip
+    const bool pt = HW % 4 != 0;
+    if (pt && (HW > 64 || HW < 4))
+        return false;
+    *qtiles = pt ? N : (int)((Q + 63) / 64);
     *splits = 1;
     const long long tiles = (long long)*qtiles * ((M + 63) / 64);
     const int chunks = (K + 31) / 32;
@@ -493,7 +576,8 @@ hipError_t launch_x3_conv1x1(int N, int M, int K, int HW, const void *wimg, cons
     a.res = (const float *)res;
     a.psum = psum;
     a.psq = psq;
-    a.QT = (int)((a.Q + 63u) / 64u);
+    const bool pt = HW % 4 != 0; // one image per tile
+    a.QT = pt ? N : (int)((a.Q + 63u) / 64u);
     a.MT = (M + 63) / 64;
     a.partial = splitk_ws;
     const int chunks = (K + 31) / 32;
@@ -509,7 +593,10 @@ hipError_t launch_x3_conv1x1(int N, int M, int K, int HW, const void *wimg, cons
     hipError_t e = hipErrorInvalidValue;
 #define MBK_CASE(P, E)                                                                            \
     if (B.pro == P && kepi == E) {                                                                \
-        hipLaunchKernelGGL((conv_x3_kernel<P, E>), grid, dim3(256), 0, st, a);                    \
+        if (pt)                                                                                   \
+            hipLaunchKernelGGL((conv_x3_kernel<P, E, true>), grid, dim3(256), 0, st, a);          \
+        else                                                                                      \
+            hipLaunchKernelGGL((conv_x3_kernel<P, E, false>), grid, dim3(256), 0, st, a);         \
         e = hipGetLastError();                                                                    \
     }
     MBK_CASE(PRO_NONE, EPI_STATS)
@@ -712,6 +799,8 @@ __global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
 bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits)
 {
     const long long Q = (long long)N * HW;
+    // (planes whose size is not a multiple of four stay with kernels_big.hip: one-image chunks with
+    // a shifted partial run measured slower there, 41 -> 52 us on 1152 x 192 channels at 7x7)
     if (Q >= (1ll << 31) || HW % 4 != 0 || Ma < 64 || Mb < 64)
         return false;
     const long long tiles = (long long)((Ma + 127) / 128) * ((Mb + 127) / 128);
