@@ -435,11 +435,11 @@ int wgrad_splits(bool bf16, int Ma, int Mb, int N, int HW)
 {
     bool swap;
     int splits;
+    if (MBK_X3W && !bf16 && x3_wgrad_plan(Ma, Mb, N, HW, &splits))
+        return splits;
     if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits))
         return splits;
     if (bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &splits))
-        return splits;
-    if (MBK_X3W && !bf16 && x3_wgrad_plan(Ma, Mb, N, HW, &splits))
         return splits;
     int wt;
     if (big_wgrad_plan(Ma, Mb, N, HW, &wt, &splits))
@@ -593,6 +593,12 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
     {
         bool swap;
         int splits;
+        if (MBK_X3W && !bf16 && x3_wgrad_plan(Ma, Mb, N, HW, &splits)) {
+            hipError_t e = launch_x3_wgrad(N, Ma, Mb, HW, U, V, partial, &splits, st);
+            if (e != hipSuccess)
+                return e;
+            return finish(splits);
+        }
         if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits)) {
             hipError_t e = launch_wgrad_cl(bf16, N, Ma, Mb, HW, U, V, partial, &splits, st);
             if (e != hipSuccess)
@@ -601,12 +607,6 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
         }
         if (bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &splits)) {
             hipError_t e = launch_bf_wgrad(N, Ma, Mb, HW, U, V, partial, &splits, st);
-            if (e != hipSuccess)
-                return e;
-            return finish(splits);
-        }
-        if (MBK_X3W && !bf16 && x3_wgrad_plan(Ma, Mb, N, HW, &splits)) {
-            hipError_t e = launch_x3_wgrad(N, Ma, Mb, HW, U, V, partial, &splits, st);
             if (e != hipSuccess)
                 return e;
             return finish(splits);

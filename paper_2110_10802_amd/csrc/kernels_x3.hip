@@ -632,15 +632,15 @@ struct X3WgradArgs {
     float *partial;
 };
 
-// what a thread keeps per operand for the whole kernel: rows rr + 64*i (i < 2) of the 128-row tile
-template <int PRO>
+// what a thread keeps per operand for the whole kernel: rows rr + 64*i (i < NP) of the tile
+template <int PRO, int NP>
 struct X3RowConst {
-    float k0[2], k1[2], k2[2];
-    uint32_t rmask[2];
+    float k0[NP], k1[NP], k2[NP];
+    uint32_t rmask[NP];
     __device__ __forceinline__ void init(const X3Operand &o, int row0, int rr, int M)
     {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NP; ++i) {
             const int r = row0 + rr + 64 * i;
             rmask[i] = r < M ? 0xffffffffu : 0u;
             k0[i] = k1[i] = k2[i] = 0.f;
@@ -653,11 +653,11 @@ struct X3RowConst {
         }
     }
 };
-// one ring slot of an operand: the raw pixel runs (four pixels at 4*qg) of the thread's two rows
-template <int PRO>
+// one ring slot of an operand: the raw pixel runs (four pixels at 4*qg) of the thread's rows
+template <int PRO, int NP>
 struct X3RowData {
-    float v0[2][4], v1[2][PRO == PRO_BNBWD ? 4 : 1];
-    float g[2];
+    float v0[NP][4], v1[NP][PRO == PRO_BNBWD ? 4 : 1];
+    float g[NP];
     // n, pix: image and first pixel of the run (it lies inside one plane: HW % 4 == 0).  Both rows
     // load, also past the last row (clamped, masked on the way into LDS): a branch around a load
     // would make the loads behind it wait.
@@ -665,7 +665,7 @@ struct X3RowData {
                                          uint32_t pix)
     {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NP; ++i) {
             const int r = min(row0 + rr + 64 * i, M - 1);
             const size_t idx = ((size_t)n * M + r) * HW + pix;
             x3_ld4(o.p0, idx, v0[i]);
@@ -676,11 +676,11 @@ struct X3RowData {
         }
     }
     // prologue, split, three 8-byte LDS stores per row
-    __device__ __forceinline__ void store(const X3RowConst<PRO> &c, uint16_t *planes, int rr, int qg,
+    __device__ __forceinline__ void store(const X3RowConst<PRO, NP> &c, uint16_t *planes, int rr, int qg,
                                           uint32_t qmask) const
     {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NP; ++i) {
             float y[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -692,21 +692,27 @@ struct X3RowData {
             x3_split2(y[2], y[3], w1);
 #pragma unroll
             for (int pl = 0; pl < 3; ++pl)
-                *reinterpret_cast<uint2 *>(planes + pl * (128 * 32) + x3_img_at(rr + 64 * i, 4 * qg)) =
+                *reinterpret_cast<uint2 *>(planes + pl * (NP * 64 * 32) + x3_img_at(rr + 64 * i, 4 * qg)) =
                     make_uint2(w0[pl], w1[pl]);
         }
     }
 };
 
-template <int PROU, int PROV>
+// VB: rows of the V tile, 128 or 64 (a narrow second operand: each wavefront then owns 32 x 32).
+// TR: the partial tile is written transposed (the host swaps the operands when the first one is
+// the narrow one).
+template <int PROU, int PROV, int VB, bool TR>
 __global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
 {
-    constexpr int BQ = 32, kPlane = 128 * 32; // planes in the layout of x3_img_at (128 rows)
+    constexpr int BQ = 32, kPlane = 128 * 32, kPlaneV = VB * 32; // planes in the layout of x3_img_at
+    constexpr int NA = VB == 128 ? 2 : 1;                        // 32-row blocks of U per wavefront
     __shared__ __attribute__((aligned(16))) uint16_t Us[3 * kPlane];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[3 * kPlane];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[3 * kPlaneV];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wa = wave >> 2, wb = wave & 3; // rows 64*wa.. of U, 32*wb.. of V
+    // first row of this wavefront's part of the U tile and of the V tile
+    const int ua = VB == 128 ? 64 * (wave >> 2) : 32 * (wave >> 1);
+    const int vb = VB == 128 ? 32 * (wave & 3) : 32 * (wave & 1);
     // workgroups that read the same pixels (all tiles of one split) run on the same XCD
     // (blockIdx.x mod 8), so the operand that several tiles share comes out of that XCD's L2
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -714,17 +720,17 @@ __global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
     const int split = (slot / tiles) * 8 + xcd, tile = slot % tiles;
     if (split >= a.splits)
         return;
-    const int a0 = (tile % a.tilesA) * 128, b0 = (tile / a.tilesA) * 128;
+    const int a0 = (tile % a.tilesA) * 128, b0 = (tile / a.tilesA) * VB;
     const int numChunks = (int)((a.Q + BQ - 1) / BQ);
     const int cbeg = split * a.chunksPerSplit;
     const int cend = min(cbeg + a.chunksPerSplit, numChunks);
     const int qg = tid & 7, rr = tid >> 3;
-    X3RowConst<PROU> cu;
-    X3RowConst<PROV> cv;
+    X3RowConst<PROU, 2> cu;
+    X3RowConst<PROV, VB / 64> cv;
     cu.init(a.U, a0, rr, a.Ma);
     cv.init(a.V, b0, rr, a.Mb);
-    X3RowData<PROU> du[2];
-    X3RowData<PROV> dv[2];
+    X3RowData<PROU, 2> du[2];
+    X3RowData<PROV, VB / 64> dv[2];
     uint32_t qmask[2] = {0u, 0u};
     // unconditional clamped loads, validity as an AND mask on the way into LDS
     auto load = [&](int s, int chunk) __attribute__((always_inline)) {
@@ -740,9 +746,9 @@ __global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
         dv[s].store(cv, Vs, rr, qg, qmask[s]);
     };
 
-    float16v acc[2];
+    float16v acc[NA];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NA; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             acc[i][r] = 0.f;
@@ -759,15 +765,17 @@ __global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
 #pragma unroll
             for (int s = 0; s < BQ / 16; ++s) {
                 const int ko = 16 * s + 8 * (lane >> 5);
-                bf16x8 av[2][3], bv[3];
+                bf16x8 av[NA][3], bv[3];
 #pragma unroll
                 for (int pl = 0; pl < 3; ++pl) {
-                    av[0][pl] = x3_lds8(Us + pl * kPlane + x3_img_at(wa * 64 + (lane & 31), ko));
-                    av[1][pl] = x3_lds8(Us + pl * kPlane + x3_img_at(wa * 64 + 32 + (lane & 31), ko));
-                    bv[pl] = x3_lds8(Vs + pl * kPlane + x3_img_at(wb * 32 + (lane & 31), ko));
+#pragma unroll
+                    for (int i = 0; i < NA; ++i)
+                        av[i][pl] = x3_lds8(Us + pl * kPlane + x3_img_at(ua + 32 * i + (lane & 31), ko));
+                    bv[pl] = x3_lds8(Vs + pl * kPlaneV + x3_img_at(vb + (lane & 31), ko));
                 }
-                acc[0] = x3_mfma6(av[0], bv, acc[0]); // rows past the end are zeros
-                acc[1] = x3_mfma6(av[1], bv, acc[1]);
+#pragma unroll
+                for (int i = 0; i < NA; ++i)
+                    acc[i] = x3_mfma6(av[i], bv, acc[i]); // rows past the end are zeros
             }
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads(); // every wavefront has read the chunk
@@ -784,26 +792,30 @@ __global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
     }
     float *dst = a.partial + (size_t)split * a.Ma * a.Mb;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NA; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int ai = a0 + wa * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            const int bi = b0 + wb * 32 + (lane & 31);
+            const int ai = a0 + ua + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            const int bi = b0 + vb + (lane & 31);
             if (ai < a.Ma && bi < a.Mb)
-                dst[(size_t)ai * a.Mb + bi] = acc[i][r];
+                dst[TR ? (size_t)bi * a.Ma + ai : (size_t)ai * a.Mb + bi] = acc[i][r];
         }
 }
 
-// Splits of the contraction: about one workgroup (eight wavefronts) per compute unit, at least two
-// chunks each.
+// Tile and splits.  The wider operand gets 128-row tiles; the other one 128-row tiles, or one
+// 64-row tile when it has at most 64 rows (and more than 32).  Splits of the contraction: about one workgroup (eight
+// wavefronts) per compute unit, at least two chunks each.
 bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits)
 {
     const long long Q = (long long)N * HW;
     // (planes whose size is not a multiple of four stay with kernels_big.hip: one-image chunks with
     // a shifted partial run measured slower there, 41 -> 52 us on 1152 x 192 channels at 7x7)
-    if (Q >= (1ll << 31) || HW % 4 != 0 || Ma < 64 || Mb < 64)
+    // (a side of at most 32 channels belongs to the fused backward kernels of kernels_wave.hip,
+    // which size their partial tiles by the plan of that file)
+    if (Q >= (1ll << 31) || HW % 4 != 0 || std::min(Ma, Mb) <= 32 || std::max(Ma, Mb) < 64)
         return false;
-    const long long tiles = (long long)((Ma + 127) / 128) * ((Mb + 127) / 128);
+    const int wide = std::max(Ma, Mb), narrow = std::min(Ma, Mb), vb = narrow <= 64 ? 64 : 128;
+    const long long tiles = (long long)((wide + 127) / 128) * ((narrow + vb - 1) / vb);
     const long long chunks = (Q + 31) / 32;
     long long s = (256 + tiles - 1) / tiles; // 512 workgroups measured slower (twice the partial tiles)
     const long long smax = (chunks + 1) / 2;
@@ -816,45 +828,55 @@ bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits)
     return true;
 }
 
+static X3Operand to_x3(const Operand &o)
+{
+    X3Operand d;
+    d.p0 = (const float *)o.p0;
+    d.p1 = (const float *)o.p1;
+    d.c0 = o.c0;
+    d.c1 = o.c1;
+    d.c2 = o.c2;
+    d.gate = o.gate;
+    return d;
+}
+
 hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
                            float *partial, int *splits_out, hipStream_t st)
 {
     int splits;
     if (!x3_wgrad_plan(Ma, Mb, N, HW, &splits))
         return hipErrorInvalidValue;
+    // a narrow first operand: the kernel computes the transposed product and writes it transposed
+    const bool swap = Ma < 64 && Mb >= 64;
+    const int vb = std::min(Ma, Mb) <= 64 ? 64 : 128;
     X3WgradArgs a;
-    a.Ma = Ma;
-    a.Mb = Mb;
+    a.Ma = swap ? Mb : Ma;
+    a.Mb = swap ? Ma : Mb;
     a.HW = HW;
     a.Q = (uint32_t)((long long)N * HW);
     const int chunks = (int)((a.Q + 31u) / 32u);
     a.chunksPerSplit = (chunks + splits - 1) / splits;
     a.divHW = make_div((uint32_t)HW);
-    a.U.p0 = (const float *)U.p0;
-    a.U.p1 = (const float *)U.p1;
-    a.U.c0 = U.c0;
-    a.U.c1 = U.c1;
-    a.U.c2 = U.c2;
-    a.U.gate = U.gate;
-    a.V.p0 = (const float *)V.p0;
-    a.V.p1 = (const float *)V.p1;
-    a.V.c0 = V.c0;
-    a.V.c1 = V.c1;
-    a.V.c2 = V.c2;
-    a.V.gate = V.gate;
+    a.U = to_x3(swap ? V : U);
+    a.V = to_x3(swap ? U : V);
     a.partial = partial;
     *splits_out = splits;
-    a.tilesA = (Ma + 127) / 128;
-    a.tilesB = (Mb + 127) / 128;
+    a.tilesA = (a.Ma + 127) / 128;
+    a.tilesB = (a.Mb + vb - 1) / vb;
     a.splits = splits;
     dim3 grid((unsigned)(((splits + 7) / 8) * 8 * a.tilesA * a.tilesB));
-#define MBK_CASE(PU, PV)                                                                          \
-    if (U.pro == PU && V.pro == PV) {                                                             \
-        hipLaunchKernelGGL((wgrad_x3_kernel<PU, PV>), grid, dim3(512), 0, st, a);                 \
+    const int pu = swap ? V.pro : U.pro, pv = swap ? U.pro : V.pro;
+#define MBK_CASE(PU, PV, VB_, TR_)                                                                \
+    if (pu == PU && pv == PV && vb == VB_ && swap == TR_) {                                       \
+        hipLaunchKernelGGL((wgrad_x3_kernel<PU, PV, VB_, TR_>), grid, dim3(512), 0, st, a);       \
         return hipGetLastError();                                                                 \
     }
-    MBK_CASE(PRO_BNBWD, PRO_NONE)
-    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE)
+    MBK_CASE(PRO_BNBWD, PRO_NONE, 128, false)
+    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE, 128, false)
+    MBK_CASE(PRO_BNBWD, PRO_NONE, 64, false)
+    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE, 64, false)
+    MBK_CASE(PRO_NONE, PRO_BNBWD, 64, true)
+    MBK_CASE(PRO_BNSWISH_GATE, PRO_BNBWD, 64, true)
 #undef MBK_CASE
     return hipErrorInvalidValue;
 }
