@@ -17,7 +17,9 @@ layer the paper measured.  Prints ONE JSON line:
   roofline_next the next slowest steps, from the untimed survey
   step_roofline algorithmic bytes of the whole step / ms_per_step against the HBM peak
   gemm          the 1x1 convolutions of the blocks whose GEMMs lie above the fp32 ridge
-                (chain blocks 7-16): flops, time and fraction of the fp32 MFMA peak
+                (chain blocks 7-16): flops and time, and per matrix-core instruction family
+                (fp32 MFMA; bf16 MFMA on three-plane splits of the fp32 operands, six issued
+                flops per flop of the contraction) the issued rate against that family's peak
   other_configs the single-block configs 1-3 (images/s, slowest kernel, roofline fraction)
   cpu_baseline  the fp64 CPU oracle timed on this host (a reported baseline, not a target)
 """
@@ -36,6 +38,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix rate, published
 F32_RIDGE = MFMA_F32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)  # flop per byte
 
 # HBM bytes per launch as rocprofv3 --pmc measured them (FETCH_SIZE, WRITE_SIZE, scaled by the
@@ -399,7 +402,10 @@ def run_chain(args) -> dict:
         nxt = sorted((c for c in cand if c != (bi, dominant)), key=lambda c: -survey[c[0]][c[1]])[:3]
         result["roofline_next"] = [_roofline_entry(f"block{i + 1}:{n}", algorithmic_bytes(shapes[i], n),
                                                    net(i, n)) for i, n in nxt]
-        # 1x1 convolutions above the fp32 ridge: the matrix-core roofline applies to these
+        # 1x1 convolutions above the fp32 ridge: the matrix-core roofline applies to these.  The
+        # library says which instruction family serves each launch: the fp32 MFMA, or the bf16
+        # MFMA on three-plane splits of the fp32 operands, which issues six times the flops of
+        # the contraction on the bf16 matrix cores; each family is priced against its own peak.
         rows = []
         for i, s in enumerate(shapes):
             if not gemm_is_mfma_bound(s) or not survey[i]:
@@ -407,20 +413,35 @@ def run_chain(args) -> dict:
             fl = step_flops(s)
             for n in GEMM_STEPS:
                 if n in fl and n in survey[i]:
-                    rows.append((i, n, fl[n], net(i, n)))
+                    eng = B.ENGINES[B.mbconv_step_engine(ctx[i]["desc"], B.STEPS[n])]
+                    rows.append((i, n, fl[n], net(i, n), eng))
         if rows:
+            issue = {"mfma_f32": (1, MFMA_F32_PEAK_TFLOPS), "mfma_bf16x3": (6, MFMA_BF16_PEAK_TFLOPS),
+                     "mfma_bf16": (1, MFMA_BF16_PEAK_TFLOPS)}
             tot_f, tot_ms = sum(r[2] for r in rows), sum(r[3] for r in rows)
+            tf = lambda f, ms: f / (ms * 1e-3) / 1e12
             slow = max(rows, key=lambda r: r[3])
             worst = min(rows, key=lambda r: r[2] / r[3])
             best = max(rows, key=lambda r: r[2] / r[3])
-            ent = lambda r: {"kernel": f"block{r[0] + 1}:{r[1]}", "flops": r[2], "kernel_ms": round(r[3], 5),
-                             "achieved": round(r[2] / (r[3] * 1e-3) / 1e12, 1),
-                             "frac": round(r[2] / (r[3] * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4)}
-            result["gemm"] = {"bound": "mfma", "dtype": "f32", "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            ent = lambda r: {"kernel": f"block{r[0] + 1}:{r[1]}", "engine": r[4], "flops": r[2],
+                             "kernel_ms": round(r[3], 5), "achieved": round(tf(r[2], r[3]), 1),
+                             "frac": round(tf(r[2], r[3]) * issue[r[4]][0] / issue[r[4]][1], 4)}
+            engines = {}
+            for e in sorted({r[4] for r in rows}):
+                sel = [r for r in rows if r[4] == e]
+                f, ms = sum(r[2] for r in sel), sum(r[3] for r in sel)
+                engines[e] = {"launches": len(sel), "flops": f, "issued_flops": f * issue[e][0],
+                              "ms": round(ms, 5), "achieved": round(tf(f, ms), 1),
+                              "issued": round(tf(f, ms) * issue[e][0], 1), "peak": issue[e][1],
+                              "frac": round(tf(f, ms) * issue[e][0] / issue[e][1], 4)}
+            result["gemm"] = {"bound": "mfma", "unit": "TFLOP/s",
                               "blocks": sorted({r[0] + 1 for r in rows}), "launches": len(rows),
                               "flops": tot_f, "ms": round(tot_ms, 5),
-                              "achieved": round(tot_f / (tot_ms * 1e-3) / 1e12, 1),
-                              "frac": round(tot_f / (tot_ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
+                              "achieved": round(tf(tot_f, tot_ms), 1),
+                              # context: the contraction's own flops against the fp32 MFMA peak,
+                              # the ceiling of a kernel that multiplies in fp32
+                              "vs_f32_mfma_peak": round(tf(tot_f, tot_ms) / MFMA_F32_PEAK_TFLOPS, 4),
+                              "engines": engines,
                               "slowest": ent(slow), "lowest_frac": ent(worst), "highest_frac": ent(best)}
         result["block_ms_survey"] = [round(sum(max(v - overhead_ms, 0.0) for v in r.values()), 5)
                                      for r in survey]

@@ -165,7 +165,9 @@ mbconv_status mbconv_forward_eval(const mbconv_desc *desc, const mbconv_params *
                                   const mbconv_bn_state *running, const void *x, void *out,
                                   void *workspace, void *hip_stream);
 
-/* Backward of the forward call that wrote saved_ws (same desc, params and x).
+/* Backward of the forward call that wrote saved_ws (same desc, params and x; the parameter VALUES
+ * must be those forward saw as well: for fp32 wide blocks saved_ws holds a re-encoded copy of the
+ * two 1x1 conv weights, which the data-gradient kernels read instead of params).
  *   dout [N,Cout,Ho,Wo] dtype, read-only.   dx [N,Cin,H,W] dtype, written.
  *   grads: every non-NULL member is overwritten with the gradient of sum(out*dout).
  * Every reduction runs in a fixed order without floating-point atomics, so results are
@@ -183,7 +185,9 @@ mbconv_status mbconv_backward(const mbconv_desc *desc, const mbconv_params *para
 typedef enum {
     MBCONV_STEP_NONE = 0,
     /* forward */
-    MBCONV_STEP_EXPAND_CONV = 1,   /* 1x1 expansion conv + BN1 partial statistics */
+    MBCONV_STEP_EXPAND_CONV = 1,   /* 1x1 expansion conv + BN1 partial statistics; for fp32 wide blocks also the
+                                      launch that re-encodes the 1x1 conv weights (in PROJ_CONV when
+                                      has_expand == 0) */
     MBCONV_STEP_BN1_FINALIZE = 2,  /* BN1_FINALIZE and BN3_FINALIZE do not occur where the kernel
                                       that consumes the statistics finalises them itself: DW_FWD
                                       and BN3_APPLY do for planes of 1024 elements or more (DW_FWD:
@@ -236,6 +240,21 @@ mbconv_status mbconv_forward_eval_probed(const mbconv_desc *desc, const mbconv_p
                                          const mbconv_bn_state *running, const void *x, void *out,
                                          void *workspace, void *hip_stream,
                                          const mbconv_probe *probe);
+
+/* Host-only: which arithmetic units serve one step of the launch sequence for this descriptor
+ * (for pricing a measured step against the right roofline).  Steps that are not 1x1 convolutions
+ * or their gradients run on the vector units.  A 1x1 step reports the matrix-core instruction
+ * family of its kernel: fp32 MFMA; bf16 MFMA on bf16-stored operands; or, for fp32 storage on the
+ * wide blocks, bf16 MFMA on operands split into three bf16 planes (six MFMAs per product block,
+ * fp32 accumulation: six times the arithmetic of one fp32 product at sixteen times the rate).
+ * `step` is an mbconv_step; returns MBCONV_EINVAL for a bad descriptor, step or pointer. */
+typedef enum mbconv_engine {
+    MBCONV_ENGINE_VECTOR = 0,
+    MBCONV_ENGINE_MFMA_F32 = 1,
+    MBCONV_ENGINE_MFMA_BF16 = 2,
+    MBCONV_ENGINE_MFMA_BF16X3 = 3
+} mbconv_engine;
+mbconv_status mbconv_step_engine(const mbconv_desc *desc, int32_t step, int32_t *engine);
 
 /* Static string for a status code. */
 const char *mbconv_status_string(mbconv_status status);

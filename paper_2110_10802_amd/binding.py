@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmbconv.so")
 MBCONV_F32, MBCONV_BF16 = 0, 1
 MBCONV_RECOMPUTE, MBCONV_STORE = 0, 1
 MBCONV_ACT_SWISH, MBCONV_ACT_RELU6 = 0, 1
-ABI_VERSION = 3
+ABI_VERSION = 4
 ABSENT = C.c_size_t(-1).value
 
 PARAM_NAMES = ["w_expand", "bn1_gamma", "bn1_beta", "w_dw", "bn2_gamma", "bn2_beta", "se_w1",
@@ -26,8 +26,10 @@ RUNNING_NAMES = ["bn1_mean", "bn1_var", "bn2_mean", "bn2_var", "bn3_mean", "bn3_
 SAVED_NAMES = ["e", "d", "p", "bn1", "bn2", "bn3", "z", "g", "q", "a1", "sc"]
 EXPORTS = ["mbconv_workspace_size", "mbconv_saved_offsets", "mbconv_forward", "mbconv_backward",
            "mbconv_forward_probed", "mbconv_backward_probed", "mbconv_eval_workspace_size",
-           "mbconv_forward_eval", "mbconv_forward_eval_probed", "mbconv_status_string",
-           "mbconv_abi_version"]
+           "mbconv_forward_eval", "mbconv_forward_eval_probed", "mbconv_step_engine",
+           "mbconv_status_string", "mbconv_abi_version"]
+# mbconv_engine values
+ENGINES = {0: "vector", 1: "mfma_f32", 2: "mfma_bf16", 3: "mfma_bf16x3"}
 # mbconv_step values (launch order of the two calls)
 STEPS = {"expand_conv": 1, "bn1_finalize": 2, "dw_fwd": 3, "bn2_finalize": 4, "se_pool": 5,
          "se_fc": 6, "proj_conv": 7, "bn3_finalize": 8, "bn3_apply": 9, "bn3_bwd_reduce": 10,
@@ -185,6 +187,15 @@ def mbconv_forward_probed(desc: Desc, params: Any, running: Any, x: Any, out: An
                                        C.byref(probe))
     if rc != 0:
         raise MBConvError(rc, "mbconv_forward")
+
+
+def mbconv_step_engine(desc: Desc, step: int) -> int:
+    """Arithmetic units that serve one step of the launch sequence (host only): key of ENGINES."""
+    eng = C.c_int32(0)
+    rc = load().mbconv_step_engine(C.byref(desc), int(step), C.byref(eng))
+    if rc != 0:
+        raise MBConvError(rc, "mbconv_step_engine")
+    return eng.value
 
 
 def mbconv_eval_workspace_size(desc: Desc) -> int:

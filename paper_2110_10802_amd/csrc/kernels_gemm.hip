@@ -247,6 +247,29 @@ bool conv1x1_uses_weight_image(bool bf16, int N, int M, int K, int HW, bool stor
            x3_conv_plan(N, M, K, HW, &qtiles, &splits);
 }
 
+// which matrix-core instruction family serves a launch (values of mbconv_engine in mbconv.h)
+int conv1x1_engine(bool bf16, int N, int M, int K, int HW, bool stores_operand)
+{
+    if (conv1x1_uses_weight_image(bf16, N, M, K, HW, stores_operand))
+        return 3;
+    int qtiles, splits;
+    if (bf16 && !stores_operand && !wave_conv_kind(M, K, HW) && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
+        return 2;
+    return 1;
+}
+int wgrad1x1_engine(bool bf16, int Ma, int Mb, int N, int HW)
+{
+    bool swap;
+    int splits;
+    if (MBK_X3W && !bf16 && x3_wgrad_plan(Ma, Mb, N, HW, &splits))
+        return 3;
+    if (wgrad_cl_plan(Ma, Mb, N, HW, &swap, &splits))
+        return 1;
+    if (bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &splits))
+        return 2;
+    return 1;
+}
+
 int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand)
 {
     const int kind = stores_operand ? 0 : wave_conv_kind(M, K, HW);

@@ -648,7 +648,52 @@ bool relu6(const mbconv_desc *d) { return d && d->activation == MBCONV_ACT_RELU6
 
 extern "C" {
 
-int32_t mbconv_abi_version(void) { return 3; }
+int32_t mbconv_abi_version(void) { return 4; }
+
+mbconv_status mbconv_step_engine(const mbconv_desc *desc, int32_t step, int32_t *engine)
+{
+    const mbconv_status s = check_desc(desc);
+    if (s != MBCONV_OK)
+        return s;
+    if (!engine || step <= MBCONV_STEP_NONE || step >= MBCONV_STEP_COUNT)
+        return MBCONV_EINVAL;
+    const Plan P = make_plan(desc);
+    int e = MBCONV_ENGINE_VECTOR;
+    switch (step) {
+    case MBCONV_STEP_EXPAND_CONV:
+        if (P.expand)
+            e = conv1x1_engine(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false);
+        break;
+    case MBCONV_STEP_PROJ_CONV:
+        e = conv1x1_engine(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, P.store);
+        break;
+    case MBCONV_STEP_PROJ_DGRAD:
+    case MBCONV_STEP_PROJ_WGRAD: {
+        int ps = 0;
+        const bool fused = projbwd_fused_plan(P.N, P.Cexp, P.Cout, P.HWo, &ps);
+        if (step == MBCONV_STEP_PROJ_DGRAD)
+            e = fused ? MBCONV_ENGINE_MFMA_F32 : conv1x1_engine(P.bf16, P.N, P.Cexp, P.Cout, P.HWo, false);
+        else
+            e = fused ? MBCONV_ENGINE_VECTOR : wgrad1x1_engine(P.bf16, P.Cout, P.Cexp, P.N, P.HWo);
+        break;
+    }
+    case MBCONV_STEP_EXPAND_DGRAD:
+    case MBCONV_STEP_EXPAND_WGRAD:
+        if (P.expand) {
+            int fs = 0;
+            const bool fused = bwd1x1_fused_plan(P.N, P.Cexp, P.Cin, P.HW, &fs);
+            if (step == MBCONV_STEP_EXPAND_DGRAD)
+                e = fused ? MBCONV_ENGINE_MFMA_F32 : conv1x1_engine(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false);
+            else
+                e = fused ? MBCONV_ENGINE_VECTOR : wgrad1x1_engine(P.bf16, P.Cexp, P.Cin, P.N, P.HW);
+        }
+        break;
+    default:
+        break;
+    }
+    *engine = e;
+    return MBCONV_OK;
+}
 
 const char *mbconv_status_string(mbconv_status s)
 {

@@ -38,6 +38,10 @@ inline int conv1x1_num_qtiles(int N, int HW) { return (int)(((long long)N * HW +
 // Long contractions with few output tiles are split over workgroups; `splitk_ws` then needs
 // conv1x1_splitk_floats(...) floats (0 when the launch does not split).
 int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand);
+// matrix-core instruction family of a launch: 1 fp32 MFMA, 2 bf16 MFMA on bf16 data, 3 bf16 MFMA
+// on three-plane splits of fp32 data
+int conv1x1_engine(bool bf16, int N, int M, int K, int HW, bool stores_operand);
+int wgrad1x1_engine(bool bf16, int Ma, int Mb, int N, int HW);
 size_t conv1x1_splitk_floats(bool bf16, int N, int M, int K, int HW, bool stores_operand);
 //
 // fp32 convolutions of the wide blocks take their A operand from a weight image (bf16 planes in

@@ -145,3 +145,33 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+
+
+def test_step_engine_query():
+    """Host-only query: which units serve a step (used by bench.py to price its GEMM figures)."""
+    chain = b0_chain()
+    E = B.ENGINES
+    # block 10 (112 -> 672 -> 112, 14x14, fp32): all six 1x1 steps on bf16 MFMAs over split operands
+    d = B.make_desc(chain[9])
+    for name in ("expand_conv", "proj_conv", "proj_dgrad", "proj_wgrad", "expand_dgrad", "expand_wgrad"):
+        assert E[B.mbconv_step_engine(d, B.STEPS[name])] == "mfma_bf16x3", name
+    assert E[B.mbconv_step_engine(d, B.STEPS["dw_fwd"])] == "vector"
+    # block 14 (7x7): the convolutions use plane tiles, the weight gradients the fp32 MFMA kernels
+    d = B.make_desc(chain[13])
+    assert E[B.mbconv_step_engine(d, B.STEPS["proj_conv"])] == "mfma_bf16x3"
+    assert E[B.mbconv_step_engine(d, B.STEPS["proj_wgrad"])] == "mfma_f32"
+    # config 1 (24 -> 144 -> 24): skinny kernels on the fp32 MFMA; the fused backward kernels make
+    # the weight-gradient steps plain sums
+    d = B.make_desc(CONFIG1)
+    assert E[B.mbconv_step_engine(d, B.STEPS["expand_conv"])] == "mfma_f32"
+    assert E[B.mbconv_step_engine(d, B.STEPS["expand_dgrad"])] == "mfma_f32"
+    assert E[B.mbconv_step_engine(d, B.STEPS["expand_wgrad"])] == "vector"
+    # config 3 (bf16 storage)
+    d = B.make_desc(CONFIG3)
+    assert E[B.mbconv_step_engine(d, B.STEPS["proj_conv"])] == "mfma_bf16"
+    assert E[B.mbconv_step_engine(d, B.STEPS["expand_wgrad"])] == "mfma_bf16"
+    with pytest.raises(B.MBConvError):
+        B.mbconv_step_engine(d, 0)
+    with pytest.raises(B.MBConvError):
+        B.mbconv_step_engine(d, 99)
+
