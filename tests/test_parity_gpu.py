@@ -56,6 +56,17 @@ SMALL = {
     "dw_two_images_noexpand": _shape(N=5, Cin=684, Cexp=684, Cse=6, Cout=24, H=36, W=36,
                                      has_expand=False, residual=False),
     "dw_two_images_bf16": _shape(dtype="bf16", N=5, Cin=24, Cexp=684, Cse=6, Cout=24, H=36, W=36),
+    # fp32 wide blocks on the bf16 matrix cores (three-plane operand splits): plane tiles whose size
+    # leaves a partial pixel run of two, three and one pixels (6x7, 3x5, 7x7), the last two with a
+    # split contraction (few tiles, long K) and a residual in the epilogue of the data gradient;
+    # ragged row and k tiles (40, 56, 72 channels; K = 40, 72: a last chunk of 8 of 32);
+    # weight gradients with a narrow operand on either side (64-row tile, swapped operands)
+    "x3_plane_6x7": _shape(N=3, Cin=40, Cexp=96, Cse=10, Cout=48, H=6, W=7, residual=False),
+    "x3_plane_3x5_split": _shape(N=5, Cin=64, Cexp=512, Cse=16, Cout=64, H=3, W=5, k=5),
+    "x3_plane_7x7_split": _shape(N=9, Cin=40, Cexp=320, Cse=10, Cout=40, H=7, W=7, k=5),
+    "x3_narrow_wgrad": _shape(N=2, Cin=48, Cexp=288, Cse=12, Cout=56, H=8, W=8, residual=False),
+    "x3_split_res": _shape(N=2, Cin=72, Cexp=432, Cse=18, Cout=72, H=4, W=4),
+    "x3_ragged_pixels": _shape(N=3, Cin=72, Cexp=136, Cse=18, Cout=72, H=6, W=10),
     "bf16_small": _shape(dtype="bf16", H=14, W=14, k=5, Cin=16, Cexp=64, Cout=16, N=4),
     "bf16_s2": _shape(dtype="bf16", H=16, W=16, k=3, stride=2, Cin=16, Cexp=32, Cout=24, N=4,
                       residual=False),
