@@ -508,6 +508,7 @@ struct BfWgradArgs {
     int Ma, Mb, HW;
     uint32_t Q;
     int chunksPerSplit; // chunks of 64 pixels
+    int tilesA, tilesB, splits;
     FastDiv divHW;
     BfOperand U, V;
     float *partial;
@@ -526,9 +527,16 @@ __global__ __launch_bounds__(256) void wgrad_bf_kernel(BfWgradArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wa = wave >> 1, wb = wave & 1;
-    const int a0 = blockIdx.x * BA, b0 = blockIdx.y * BB;
+    // workgroups that read the same pixels (all tiles of one split) run on the same XCD
+    // (blockIdx.x mod 8), so the operand that several tiles share comes out of that XCD's L2
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tiles = a.tilesA * a.tilesB;
+    const int split = (slot / tiles) * 8 + xcd, tile = slot % tiles;
+    if (split >= a.splits)
+        return;
+    const int a0 = (tile % a.tilesA) * BA, b0 = (tile / a.tilesA) * BB;
     const int numChunks = (int)((a.Q + BQ - 1) / BQ);
-    const int cbeg = blockIdx.z * a.chunksPerSplit;
+    const int cbeg = split * a.chunksPerSplit;
     const int cend = min(cbeg + a.chunksPerSplit, numChunks);
 
     const int qg = tid & 15, rrow = tid >> 4;
@@ -676,7 +684,7 @@ __global__ __launch_bounds__(256) void wgrad_bf_kernel(BfWgradArgs a)
         if ((cend - cbeg) & 1)
             step(0, cc);
     }
-    float *dst = a.partial + (size_t)blockIdx.z * a.Ma * a.Mb;
+    float *dst = a.partial + (size_t)split * a.Ma * a.Mb;
 #pragma unroll
     for (int i = 0; i < WA; ++i)
 #pragma unroll
@@ -751,8 +759,10 @@ hipError_t launch_bf_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, cons
     *splits_out = splits;
     int wa, wb;
     bf_wgrad_tile(Ma, Mb, &wa, &wb);
-    dim3 grid((unsigned)((Ma + 64 * wa - 1) / (64 * wa)), (unsigned)((Mb + 64 * wb - 1) / (64 * wb)),
-              (unsigned)splits);
+    a.tilesA = (Ma + 64 * wa - 1) / (64 * wa);
+    a.tilesB = (Mb + 64 * wb - 1) / (64 * wb);
+    a.splits = splits;
+    dim3 grid((unsigned)(((splits + 7) / 8) * 8 * a.tilesA * a.tilesB));
 #define MBK_CASE(PU, PV, A, B)                                                                    \
     if (U.pro == PU && V.pro == PV && wa == A && wb == B) {                                       \
         hipLaunchKernelGGL((wgrad_bf_kernel<PU, PV, A, B>), grid, dim3(256), 0, st, a);           \
