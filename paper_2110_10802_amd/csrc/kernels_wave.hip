@@ -1282,6 +1282,25 @@ hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const 
 #undef MBK_CASE
 }
 
+// kernels_x3.hip
+bool bwd1x1_x3_supported(int Cw, int Cn, int HW);
+hipError_t launch_bwd1x1_x3(int N, int Cw, int Cn, int HW, const Operand &de, const void *xin,
+                            const void *w, void *dx, const void *res, float *partial, int splits,
+                            hipStream_t st);
+
+#ifndef MBK_X3B
+#define MBK_X3B 1
+#endif
+// which matrix-core form serves the fused backward of this shape: 1 = fp32 MFMA (bwd1x1_lt),
+// 3 = three bf16 planes (bwd1x1_x3); 0: the shape is not fused
+int bwd1x1_fused_engine(bool bf16, int N, int Cw, int Cn, int HW)
+{
+    int splits;
+    if (!bwd1x1_fused_plan(N, Cw, Cn, HW, &splits))
+        return 0;
+    return (!bf16 && MBK_X3B && bwd1x1_x3_supported(Cw, Cn, HW)) ? 3 : 1; // (bf16 storage: fp32 MFMA)
+}
+
 bool bwd1x1_fused_plan(int N, int Cw, int Cn, int HW, int *splits)
 {
     bool swap;
@@ -1298,6 +1317,12 @@ hipError_t launch_bwd1x1_fused(bool bf16, int N, int Cw, int Cn, int HW, const O
     int splits;
     if (!bwd1x1_fused_plan(N, Cw, Cn, HW, &splits) || de.pro != PRO_BNBWD)
         return hipErrorInvalidValue;
+    // fp32, at most 16 -> 96 channels: the wave-per-chunk kernel on the bf16 matrix cores
+    // (same partial-tile layout and count)
+    if (bwd1x1_fused_engine(bf16, N, Cw, Cn, HW) == 3) {
+        *splits_out = splits;
+        return launch_bwd1x1_x3(N, Cw, Cn, HW, de, xin, w, dx, res, partial, splits, st);
+    }
     Bwd1x1Args b = {};
     WgradClArgs &a = b.g;
     a.N = N;

@@ -881,4 +881,349 @@ hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, cons
     return hipErrorInvalidValue;
 }
 
+// ---- both gradients of a narrow -> wide 1x1 convolution, a wavefront per pixel chunk ---------
+// The expansion conv's backward when its input has at most 16 channels and its output at most
+// 96: dx = W^T de (+ dout) and dW = de x^T from one pass over de = c0*dy1 + c1*e + c2 (BN1's
+// backward applied on the way in), the two widest tensors of the block.  Same fusion as
+// bwd1x1_lt in kernels_wave.hip (section "Guided Optimization Case Study: EfficientNet": the
+// consumers of a tensor fused), rebuilt around what bounds that kernel, two workgroup barriers and
+// a VALU-rate fp32 MFMA phase per 32-pixel chunk:
+//   - a wavefront owns whole chunks of 32 pixels (chunk = 4*workgroup + wavefront, stride
+//     4*grid); nothing crosses wavefronts inside the loop, so there is no barrier in it;
+//   - lane (r = lane%16, g = lane/16) loads pixels 2r and 2r+1 of the chunk for the channels
+//     32s + 8g .. +7 of every 32-channel step s, eight bytes at a time: sixteen consecutive lanes
+//     read a whole 128-byte line (lanes that hold different ROWS of a tile, the layout the weight
+//     gradient would take from registers, cost the address unit a cache line per lane: measured,
+//     161 us on 16 -> 96 channels and 803 k pixels), and eight channels of one pixel are
+//     exactly the B operand of v_mfma_f32_16x16x32_bf16 for the data gradient (column = pixel:
+//     one tile for the even pixels, one for the odd; contraction = channels), whose A operand,
+//     W^T, waits in registers: the data gradient needs no LDS;
+//   - the weight gradient contracts over pixels, so each 32-channel step goes through LDS once,
+//     transposed: [channel][pixel] bf16 planes, the lane's two pixels of a channel as one 32-bit
+//     store, read back 16 bytes per lane as the A operand (row = channel); x takes the same route
+//     once per chunk;
+//   - the next chunk's values of a step are requested as soon as this chunk's have been
+//     consumed, so they travel during the rest of the chunk's arithmetic.
+// fp32 operands are split into three bf16 planes as everywhere in this file.  The four
+// wavefronts' weight-gradient tiles are added in wavefront order at the end, the workgroups'
+// partial tiles by reduce_splits: fixed order, no atomics.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct X3Bwd1x1Args {
+    int Cn, Cw, HW;
+    uint32_t Q;
+    int numChunks;
+    FastDiv divHW;
+    const float *x, *dy, *e;   // [N][Cn][HW]; [N][Cw][HW] twice
+    const float *c0, *c1, *c2; // [Cw]: de = c0*dy + c1*e + c2
+    const float *w;            // [Cw][Cn]
+    float *dx;                 // [N][Cn][HW]
+    const float *res;          // optional, added to dx
+    float *partial;            // [grid][Cw][Cn]
+};
+
+__device__ __forceinline__ f32x4 x3_mfma6_16(const bf16x8 (&a)[3], const bf16x8 (&b)[3], f32x4 acc)
+{
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[2], b[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[0], b[2], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[1], b[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[1], b[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[0], b[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[0], b[0], acc, 0, 0, 0);
+    return acc;
+}
+
+// eight values -> the three planes of an MFMA operand (value t in halfword t); p keeps the
+// packed pairs (values 2t and 2t+1 of plane pl in p[t][pl])
+__device__ __forceinline__ void x3_split8(const float (&v)[8], uint32_t (&p)[4][3], bf16x8 (&o)[3])
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        x3_split2(v[2 * t], v[2 * t + 1], p[t]);
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl) {
+        const u32x4 q = {p[0][pl], p[1][pl], p[2][pl], p[3][pl]};
+        o[pl] = __builtin_bit_cast(bf16x8, q);
+    }
+}
+
+__device__ __forceinline__ void x3_wave_lds_fence()
+{
+    // a wavefront's LDS operations execute in order: only the compiler has to be held
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// NT: 16-channel tiles of the wide side (Cw <= 16*NT), even.
+template <int NT, bool RES>
+__global__ __launch_bounds__(256, 2) void bwd1x1_x3_kernel(X3Bwd1x1Args a)
+{
+    constexpr int KS = NT / 2;  // steps of 32 wide channels
+    constexpr int PH = 40;      // halfwords per LDS row: 32 pixel positions + 8 (the 16-byte reads
+                                // of 16 consecutive rows fall on distinct banks)
+    constexpr int LD = 32 * PH; // one plane of a 32-channel step
+    constexpr int LX = 16 * PH; // one plane of x
+    constexpr int WAVE_HW = 3 * LD + 3 * LX;
+    extern __shared__ uint16_t lds16[];
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 15, g = lane >> 4;
+    uint16_t *Ld = lds16 + wv * WAVE_HW, *Lx = Ld + 3 * LD;
+    const int Cn = a.Cn, Cw = a.Cw, HW = a.HW;
+
+    // the BN-backward coefficients of the wide rows wait in LDS, {c0, c1, c2, -} per channel
+    // (zero past the last row: de = 0); registers are what is scarce here
+    f32x4 *Cl = reinterpret_cast<f32x4 *>(lds16 + 4 * WAVE_HW); // [16*NT]
+    for (int c = threadIdx.x; c < 16 * NT; c += 256) {
+        const int cc = c < Cw ? c : Cw - 1;
+        const uint32_t m = c < Cw ? 0xffffffffu : 0u;
+        Cl[c] = (f32x4){and_mask(a.c0[cc], m), and_mask(a.c1[cc], m), and_mask(a.c2[cc], m), 0.f};
+    }
+    // Element offsets are 32 bits (the host checks the tensors' sizes), so that a load is a
+    // uniform base (tensor + t*HW, scalar registers) plus one vector register: the lane's eight
+    // channels of step s start at row 32s + 8g, clamped to the last group of eight (Cw % 8 == 0;
+    // groups past the end meet zero coefficients); rows 4g + v of x and dx, clamped likewise
+    // (read, never stored).
+    uint32_t vrow[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+        vrow[s] = (uint32_t)min(32 * s + 8 * g, Cw - 8) * (uint32_t)HW;
+    uint32_t joff[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        joff[v] = (uint32_t)(4 * g + v < Cn ? 4 * g + v : Cn - 1) * (uint32_t)HW;
+    // W^T as the data gradient's A operand: row j = r, contraction = channels 32s + 8g .. +7
+    bf16x8 wa[KS][3];
+    {
+        float wv8[KS][8];
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int c = 32 * s + 8 * g + t;
+                const bool ok = c < Cw && r < Cn;
+                wv8[s][t] = and_mask(a.w[ok ? (size_t)c * Cn + r : 0], ok ? 0xffffffffu : 0u);
+            }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            uint32_t p[4][3];
+            x3_split8(wv8[s], p, wa[s]);
+        }
+    }
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+        acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const uint32_t vimg = (uint32_t)Cw * (uint32_t)HW, uimg = (uint32_t)Cn * (uint32_t)HW;
+    const int cStep = 4 * (int)gridDim.x;
+    int ch = 4 * (int)blockIdx.x + wv;
+    // the lane's two pixels of chunk c (2r and 2r + 1: one image, HW being even): element
+    // offsets in the wide tensors and in x / dx
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const auto locate = [&](int c, uint32_t &vb, uint32_t &ub, uint32_t &okm) {
+        const uint32_t q = (uint32_t)c * 32u + 2u * (uint32_t)r;
+        okm = q < a.Q ? 0xffffffffu : 0u;
+        const uint32_t qs = q < a.Q ? q : 0u;
+        const uint32_t n = fdiv(qs, a.divHW), pix = qs - n * (uint32_t)HW;
+        vb = n * vimg + pix;
+        ub = n * uimg + pix;
+    };
+    float vy[KS][2][8], ve[KS][2][8], xv[2][4];
+    const auto fetch_step = [&](int s, uint32_t vb) {
+        const uint32_t o = vb + vrow[s];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const float *py = a.dy + (size_t)t * HW, *pe = a.e + (size_t)t * HW; // uniform
+            const f32x2 y2 = *reinterpret_cast<const f32x2 *>(py + o);
+            const f32x2 e2 = *reinterpret_cast<const f32x2 *>(pe + o);
+            vy[s][0][t] = y2[0];
+            vy[s][1][t] = y2[1];
+            ve[s][0][t] = e2[0];
+            ve[s][1][t] = e2[1];
+        }
+    };
+    const auto fetch_x = [&](uint32_t ub) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const f32x2 x2 = *reinterpret_cast<const f32x2 *>(a.x + ub + joff[v]);
+            xv[0][v] = x2[0];
+            xv[1][v] = x2[1];
+        }
+    };
+    uint32_t vb, ub, okm;
+    __syncthreads(); // Cl
+    // (a wavefront without a chunk loads chunk 0 and never uses it)
+    locate(ch < a.numChunks ? ch : 0, vb, ub, okm);
+    fetch_x(ub);
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+        fetch_step(s, vb);
+
+    for (; ch < a.numChunks; ch += cStep) {
+        // the next chunk (the last one re-reads itself: loads stay unconditional)
+        const int nx = ch + cStep < a.numChunks ? ch + cStep : ch;
+        uint32_t nvb, nub, nokm;
+        locate(nx, nvb, nub, nokm);
+        const uint32_t o0 = ub;
+        const bool ook = okm != 0u;
+
+        // x: the weight gradient's B operand (column j, contraction = pixels)
+        {
+            uint32_t w[4][3];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const uint32_t m = 4 * g + v < Cn ? okm : 0u;
+                x3_split2(and_mask(xv[0][v], m), and_mask(xv[1][v], m), w[v]);
+            }
+            fetch_x(nub);
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    *reinterpret_cast<uint32_t *>(Lx + pl * LX + (4 * g + v) * PH + 2 * r) = w[v][pl];
+        }
+        x3_wave_lds_fence();
+        bf16x8 bx[3];
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)
+            bx[pl] = x3_lds8(Lx + pl * LX + r * PH + 8 * g);
+
+        f32x4 accd[2] = {(f32x4){0.f, 0.f, 0.f, 0.f}, (f32x4){0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            float d0[8], d1[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const f32x4 k = Cl[32 * s + 8 * g + t];
+                d0[t] = and_mask(fmaf(k[0], vy[s][0][t], fmaf(k[1], ve[s][0][t], k[2])), okm);
+                d1[t] = and_mask(fmaf(k[0], vy[s][1][t], fmaf(k[1], ve[s][1][t], k[2])), okm);
+            }
+            fetch_step(s, nvb);
+            // data gradient: dx[j][pixel] += sum_c W[c][j] * de[c][pixel], straight from registers
+            // (tile 0: the even pixels of the chunk, tile 1: the odd ones)
+            uint32_t p0[4][3], p1[4][3];
+            bf16x8 b0[3], b1[3];
+            x3_split8(d0, p0, b0);
+            x3_split8(d1, p1, b1);
+            accd[0] = x3_mfma6_16(wa[s], b0, accd[0]);
+            accd[1] = x3_mfma6_16(wa[s], b1, accd[1]);
+            // transposed for the weight gradient: channel 8g + t, pixels 2r and 2r + 1
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+#pragma unroll
+                for (int t2 = 0; t2 < 4; ++t2) {
+                    const uint32_t lo = (p0[t2][pl] & 0xffffu) | (p1[t2][pl] << 16);
+                    const uint32_t hi = (p0[t2][pl] >> 16) | (p1[t2][pl] & 0xffff0000u);
+                    uint16_t *dst = Ld + pl * LD + (8 * g + 2 * t2) * PH + 2 * r;
+                    *reinterpret_cast<uint32_t *>(dst) = lo;
+                    *reinterpret_cast<uint32_t *>(dst + PH) = hi;
+                }
+            x3_wave_lds_fence();
+            // weight gradient of the step's two 16-channel tiles
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) {
+                bf16x8 av[3];
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl)
+                    av[pl] = x3_lds8(Ld + pl * LD + (16 * i2 + r) * PH + 8 * g);
+                acc[2 * s + i2] = x3_mfma6_16(av, bx, acc[2 * s + i2]);
+            }
+            x3_wave_lds_fence(); // these reads before the next step's stores
+        }
+        f32x2 rs[4];
+        if (RES) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                rs[v] = *reinterpret_cast<const f32x2 *>(a.res + o0 + joff[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            f32x2 o = {accd[0][v], accd[1][v]};
+            if (RES)
+                o += rs[v];
+            if (ook && 4 * g + v < Cn)
+                *reinterpret_cast<f32x2 *>(a.dx + o0 + joff[v]) = o;
+        }
+        vb = nvb;
+        ub = nub;
+        okm = nokm;
+    }
+    // the four wavefronts' weight-gradient tiles, added in wavefront order
+    __syncthreads();
+    float *Rd = reinterpret_cast<float *>(Ld); // [16*NT][16] of this wavefront
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            Rd[(16 * i + 4 * g + v) * 16 + r] = acc[i][v];
+    __syncthreads();
+    float *dst = a.partial + (size_t)blockIdx.x * Cw * Cn;
+    for (int el = threadIdx.x; el < 16 * NT * 16; el += 256) {
+        const int c = el >> 4, j = el & 15;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            sum += reinterpret_cast<const float *>(lds16 + w * WAVE_HW)[el];
+        if (c < Cw && j < Cn)
+            dst[(size_t)c * Cn + j] = sum;
+    }
+}
+
+bool bwd1x1_x3_supported(int Cw, int Cn, int HW)
+{
+    return Cn <= 16 && Cn < Cw && Cw <= 96 && Cw % 8 == 0 && HW % 2 == 0; // (pixel pairs)
+}
+
+// `splits` workgroups of four wavefronts; partial: [splits][Cw][Cn].
+hipError_t launch_bwd1x1_x3(int N, int Cw, int Cn, int HW, const Operand &de, const void *xin,
+                            const void *w, void *dx, const void *res, float *partial, int splits,
+                            hipStream_t st)
+{
+    if (!bwd1x1_x3_supported(Cw, Cn, HW) || de.pro != PRO_BNBWD || splits < 1)
+        return hipErrorInvalidValue;
+    if ((long long)N * Cw * HW >= (1ll << 30)) // 32-bit byte offsets in the kernel
+        return hipErrorInvalidValue;
+    X3Bwd1x1Args a;
+    a.Cn = Cn;
+    a.Cw = Cw;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    a.numChunks = (int)((a.Q + 31u) / 32u);
+    a.divHW = make_div((uint32_t)HW);
+    a.x = (const float *)xin;
+    a.dy = (const float *)de.p0;
+    a.e = (const float *)de.p1;
+    a.c0 = de.c0;
+    a.c1 = de.c1;
+    a.c2 = de.c2;
+    a.w = (const float *)w;
+    a.dx = (float *)dx;
+    a.res = (const float *)res;
+    a.partial = partial;
+    const int nt = Cw <= 32 ? 2 : Cw <= 64 ? 4 : 6;
+    // per wavefront three planes of a 32-channel step and of x (rows of 40 halfwords), and the
+    // coefficient table
+    const size_t lds = (size_t)4 * 3 * (32 + 16) * 40 * sizeof(uint16_t) + (size_t)16 * nt * 4 * sizeof(float);
+#define MBK_CASE(NT_, RES_)                                                                       \
+    if (nt == NT_ && (res != nullptr) == RES_) {                                                  \
+        auto kern = bwd1x1_x3_kernel<NT_, RES_>;                                                  \
+        const hipError_t e_ = hipFuncSetAttribute(                                                \
+            (const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
+        if (e_ != hipSuccess)                                                                     \
+            return e_;                                                                            \
+        hipLaunchKernelGGL(kern, dim3((unsigned)splits), dim3(256), lds, st, a);                  \
+        return hipGetLastError();                                                                 \
+    }
+    MBK_CASE(2, false)
+    MBK_CASE(2, true)
+    MBK_CASE(4, false)
+    MBK_CASE(4, true)
+    MBK_CASE(6, false)
+    MBK_CASE(6, true)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
 } // namespace mbk

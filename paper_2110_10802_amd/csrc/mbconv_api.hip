@@ -683,7 +683,8 @@ mbconv_status mbconv_step_engine(const mbconv_desc *desc, int32_t step, int32_t 
             int fs = 0;
             const bool fused = bwd1x1_fused_plan(P.N, P.Cexp, P.Cin, P.HW, &fs);
             if (step == MBCONV_STEP_EXPAND_DGRAD)
-                e = fused ? MBCONV_ENGINE_MFMA_F32 : conv1x1_engine(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false);
+                e = fused ? bwd1x1_fused_engine(P.bf16, P.N, P.Cexp, P.Cin, P.HW)
+                          : conv1x1_engine(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false);
             else
                 e = fused ? MBCONV_ENGINE_VECTOR : wgrad1x1_engine(P.bf16, P.Cexp, P.Cin, P.N, P.HW);
         }

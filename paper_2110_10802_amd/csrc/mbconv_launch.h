@@ -108,6 +108,8 @@ hipError_t launch_projbwd_fused(bool bf16, int N, int Cw, int Cn, int HW, const 
                                 const Operand &sc, const void *w, void *G, float *partial,
                                 int *splits_out, const BnBwdFin *fin, hipStream_t st);
 bool bwd1x1_fused_plan(int N, int Cw, int Cn, int HW, int *splits);
+// 0: not fused; else the mbconv_engine value of the kernel launch_bwd1x1_fused picks
+int bwd1x1_fused_engine(bool bf16, int N, int Cw, int Cn, int HW);
 hipError_t launch_bwd1x1_fused(bool bf16, int N, int Cw, int Cn, int HW, const Operand &de,
                                const void *xin, const void *w, void *dx, const void *res,
                                float *partial, int *splits_out, hipStream_t st);

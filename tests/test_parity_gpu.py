@@ -67,6 +67,14 @@ SMALL = {
     "x3_narrow_wgrad": _shape(N=2, Cin=48, Cexp=288, Cse=12, Cout=56, H=8, W=8, residual=False),
     "x3_split_res": _shape(N=2, Cin=72, Cexp=432, Cse=18, Cout=72, H=4, W=4),
     "x3_ragged_pixels": _shape(N=3, Cin=72, Cexp=136, Cse=18, Cout=72, H=6, W=10),
+    # expansion-conv backward of at most 16 -> 96 channels (a multiple of eight) on planes of an
+    # even number of pixels: a wavefront per 32-pixel chunk on the bf16 matrix cores, with six,
+    # four and two 16-channel tiles; full tiles with the residual; a ragged narrow side, 40 wide
+    # channels (the last 16-channel tile half empty) and a last chunk of 18 pixels that starts in
+    # one image and ends in the next; 24 channels on 8x8
+    "x3_bwd1x1_96": _shape(N=3, Cin=16, Cexp=96, Cse=4, Cout=16, H=8, W=12),
+    "x3_bwd1x1_ragged": _shape(N=3, Cin=5, Cexp=40, Cse=3, Cout=7, H=6, W=5, residual=False),
+    "x3_bwd1x1_two_tiles": _shape(N=2, Cin=8, Cexp=24, Cse=2, Cout=8, H=8, W=8),
     "bf16_small": _shape(dtype="bf16", H=14, W=14, k=5, Cin=16, Cexp=64, Cout=16, N=4),
     "bf16_s2": _shape(dtype="bf16", H=16, W=16, k=3, stride=2, Cin=16, Cexp=32, Cout=24, N=4,
                       residual=False),
