@@ -240,8 +240,12 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_fwd_kernel(Dw2Args 
                 const int x0 = 4 * (gidx - h * a.W4);
                 float v[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    v[r] = x0 + r < W ? (EXPAND ? actf(fmaf(ev[i][r], scale, shift)) : ev[i][r]) : 0.f;
+                for (int r = 0; r < 4; ++r) {
+                    // straight-line code for all four elements (a branch per element would run
+                    // the four exp/rcp chains one after the other); whole runs need no mask
+                    const float t = EXPAND ? actf(fmaf(ev[i][r], scale, shift)) : ev[i][r];
+                    v[r] = GVI == 4 ? t : and_mask(t, x0 + r < W ? 0xffffffffu : 0u);
+                }
                 *reinterpret_cast<float4v *>(tile + (h + P) * WP + 4 + x0) =
                     float4v{v[0], v[1], v[2], v[3]};
             }
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256) void dw2_fwd_kernel(Dw2Args 
         d2_out_store<T, GVO>((T *)a.d, plane * (size_t)a.Ho * a.Wo + (size_t)i * a.Wo + j0, j0, a.Wo, o);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            if (j0 + r < a.Wo) {
+            if (GVO == 4 || j0 + r < a.Wo) {
                 const float sv = as_stored<T>(o[r]);
                 acc2[0] += sv;
                 acc2[1] = fmaf(sv, sv, acc2[1]);
@@ -370,7 +374,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256, (TPP > 256 && K == 3) ? 8 : 
                 const float s2 = act_aux(y2);
                 const float grad2 = act_grad(y2, s2);
                 const float dy2 = fmaf(Gv[r], gate, dzs) * grad2;
-                ddv[r] = oj0 + r < Wo ? fmaf(c0, dy2, fmaf(c1, dv[r], c2)) : 0.f;
+                ddv[r] = (GVO == 4 || oj0 + r < Wo) ? fmaf(c0, dy2, fmaf(c1, dv[r], c2)) : 0.f;
             }
         }
     }
@@ -399,7 +403,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256, (TPP > 256 && K == 3) ? 8 : 
                 for (int r = 0; r < 4; ++r) {
                     y1[r] = fmaf(rawk[i][r], scale1, shift1);
                     const float v = EXPAND ? act_val(y1[r], sgk[i][r]) : rawk[i][r];
-                    a1c[r] = x0 + r < W ? v : 0.f;
+                    a1c[r] = (GVI == 4 || x0 + r < W) ? v : 0.f;
                 }
                 float da[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -441,7 +445,7 @@ __global__ __launch_bounds__(TPP > 256 ? TPP : 256, (TPP > 256 && K == 3) ? 8 : 
                     for (int r = 0; r < 4; ++r) {
                         const float raw = rawk[i][r], sg = sgk[i][r];
                         o[r] = da[r] * act_grad(y1[r], sg);
-                        if (x0 + r < W) {
+                        if (GVI == 4 || x0 + r < W) {
                             const float sv = as_stored<T>(o[r]);
                             acc[K * K] += sv;
                             acc[K * K + 1] = fmaf(sv, (raw - mean1) * rstd1, acc[K * K + 1]);
