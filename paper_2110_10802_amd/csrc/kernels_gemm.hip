@@ -232,25 +232,49 @@ hipError_t launch_x3_conv1x1(int N, int M, int K, int HW, const void *wimg, cons
 bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits);
 hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
                            float *partial, int *splits_out, hipStream_t st);
+bool xw_conv_plan(int N, int M, int K, int HW, int pro, int epi, int *nt);
+hipError_t launch_xw_conv1x1(int N, int M, int K, int HW, const void *wimg, const Operand &B,
+                             void *out, int epi, float *psum, float *psq, hipStream_t st);
 #ifndef MBK_X3
 #define MBK_X3 1
+#endif
+#ifndef MBK_XW
+#define MBK_XW 1
 #endif
 #ifndef MBK_X3W
 #define MBK_X3W 1
 #endif
 
+// short contraction, many rows, a role the kernel has: weights resident in LDS (conv_xw)
+static bool xw_applies(bool bf16, int N, int M, int K, int HW, bool stores_operand, int pro, int epi,
+                       int *nt)
+{
+    return MBK_XW && !bf16 && !stores_operand && pro >= 0 && epi >= 0 && !wave_conv_kind(M, K, HW) &&
+           xw_conv_plan(N, M, K, HW, pro, epi, nt);
+}
+
 // fp32 convolutions of the wide blocks run on the bf16 matrix cores from a weight image
-bool conv1x1_uses_weight_image(bool bf16, int N, int M, int K, int HW, bool stores_operand)
+bool conv1x1_uses_weight_image(bool bf16, int N, int M, int K, int HW, bool stores_operand, int pro,
+                               int epi)
 {
     int qtiles, splits;
+    if (xw_applies(bf16, N, M, K, HW, stores_operand, pro, epi, &qtiles))
+        return true;
     return MBK_X3 && !bf16 && !stores_operand && !wave_conv_kind(M, K, HW) &&
            x3_conv_plan(N, M, K, HW, &qtiles, &splits);
 }
 
-// which matrix-core instruction family serves a launch (values of mbconv_engine in mbconv.h)
-int conv1x1_engine(bool bf16, int N, int M, int K, int HW, bool stores_operand)
+int conv1x1_image_lane_order(bool bf16, int N, int M, int K, int HW, bool stores_operand, int pro,
+                             int epi)
 {
-    if (conv1x1_uses_weight_image(bf16, N, M, K, HW, stores_operand))
+    int nt;
+    return xw_applies(bf16, N, M, K, HW, stores_operand, pro, epi, &nt) ? 1 : 0;
+}
+
+// which matrix-core instruction family serves a launch (values of mbconv_engine in mbconv.h)
+int conv1x1_engine(bool bf16, int N, int M, int K, int HW, bool stores_operand, int pro, int epi)
+{
+    if (conv1x1_uses_weight_image(bf16, N, M, K, HW, stores_operand, pro, epi))
         return 3;
     int qtiles, splits;
     if (bf16 && !stores_operand && !wave_conv_kind(M, K, HW) && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
@@ -270,12 +294,15 @@ int wgrad1x1_engine(bool bf16, int Ma, int Mb, int N, int HW)
     return 1;
 }
 
-int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand)
+int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand, int pro,
+                         int epi)
 {
     const int kind = stores_operand ? 0 : wave_conv_kind(M, K, HW);
     if (kind)
         return wave_conv_num_partials(kind, N, M, HW);
     int wt, qtiles, splits;
+    if (xw_applies(bf16, N, M, K, HW, stores_operand, pro, epi, &qtiles))
+        return qtiles;
     if (bf16 && !stores_operand && bf_conv_plan(N, M, K, HW, &qtiles, &splits))
         return qtiles;
     if (conv1x1_uses_weight_image(bf16, N, M, K, HW, stores_operand)) {
@@ -304,6 +331,14 @@ hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w,
                           float *psq, void *sc_store, float *splitk_ws, hipStream_t st,
                           const void *wimg)
 {
+    {
+        int nt;
+        if (xw_applies(bf16, N, M, K, HW, sc_store != nullptr, B.pro, epi, &nt)) {
+            if (!wimg)
+                return hipErrorInvalidValue;
+            return launch_xw_conv1x1(N, M, K, HW, wimg, B, out, epi, psum, psq, st);
+        }
+    }
     if (conv1x1_uses_weight_image(bf16, N, M, K, HW, sc_store != nullptr)) {
         if (!wimg)
             return hipErrorInvalidValue;

@@ -120,6 +120,7 @@ struct X3PrepSet {
     int M, K, sm, sk;
     uint16_t *img;
     int CH, firstTile;
+    int lane_order; // the tile's arrangement: 0 as described above (conv_x3), 1 for conv_xw
 };
 struct X3PrepArgs {
     X3PrepSet s[4];
@@ -149,9 +150,12 @@ __global__ __launch_bounds__(256) void x3_prep_kernel(X3PrepArgs a)
     for (int j = 0; j < 4; ++j)
         x3_split2(v[2 * j], v[2 * j + 1], w[j]);
     uint16_t *tile = S.img + ((size_t)mt * S.CH + ch) * 3 * 2048;
+    // lane order: the tile as four 16-row MFMA operands, [row tile][plane][lane] with lane =
+    // row % 16 + 16 * (k / 8): a wavefront reads an operand as 64 consecutive 16-byte pieces
+    const int at1 = (((r >> 4) * 3) * 64 + (r & 15) + 16 * g) * 8;
 #pragma unroll
     for (int pl = 0; pl < 3; ++pl)
-        *reinterpret_cast<uint4 *>(tile + pl * 2048 + x3_img_at(r, 8 * g)) =
+        *reinterpret_cast<uint4 *>(tile + (S.lane_order ? at1 + pl * 512 : pl * 2048 + x3_img_at(r, 8 * g))) =
             make_uint4(w[0][pl], w[1][pl], w[2][pl], w[3][pl]);
 }
 
@@ -162,7 +166,7 @@ size_t x3_weight_image_bytes(int M, int K)
 
 // Writes up to four images in one launch; set i: A(m,k) = w[i][m*sm[i] + k*sk[i]], M[i] x K[i].
 hipError_t launch_x3_prep(int nsets, const float *const *w, const int *M, const int *K, const int *sm,
-                          const int *sk, void *const *img, hipStream_t st)
+                          const int *sk, void *const *img, const int *lane_order, hipStream_t st)
 {
     if (nsets < 1 || nsets > 4)
         return hipErrorInvalidValue;
@@ -175,6 +179,7 @@ hipError_t launch_x3_prep(int nsets, const float *const *w, const int *M, const 
         a.s[i].sm = sm[i];
         a.s[i].sk = sk[i];
         a.s[i].img = (uint16_t *)img[i];
+        a.s[i].lane_order = lane_order[i];
         a.s[i].CH = (K[i] + 31) / 32;
         a.s[i].firstTile = tiles;
         tiles += ((M[i] + 63) / 64) * a.s[i].CH;
@@ -908,6 +913,7 @@ hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, cons
 // wavefronts' weight-gradient tiles are added in wavefront order at the end, the workgroups'
 // partial tiles by reduce_splits: fixed order, no atomics.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct X3Bwd1x1Args {
     int Cn, Cw, HW;
@@ -1021,7 +1027,6 @@ __global__ __launch_bounds__(256, 2) void bwd1x1_x3_kernel(X3Bwd1x1Args a)
     int ch = 4 * (int)blockIdx.x + wv;
     // the lane's two pixels of chunk c (2r and 2r + 1: one image, HW being even): element
     // offsets in the wide tensors and in x / dx
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
     const auto locate = [&](int c, uint32_t &vb, uint32_t &ub, uint32_t &okm) {
         const uint32_t q = (uint32_t)c * 32u + 2u * (uint32_t)r;
         okm = q < a.Q ? 0xffffffffu : 0u;
@@ -1222,6 +1227,324 @@ hipError_t launch_bwd1x1_x3(int N, int Cw, int Cn, int HW, const Operand &de, co
     MBK_CASE(4, true)
     MBK_CASE(6, false)
     MBK_CASE(6, true)
+#undef MBK_CASE
+    return hipErrorInvalidValue;
+}
+
+// ---- 1x1 convolution with a short contraction: weights resident in LDS, a wavefront per chunk ----
+// out[n][m][q] = sum_k W[m][k] * op(B)[n][k][q] for K <= 192 and many rows (the expansion conv,
+// K = Cin, and the projection conv's data gradient, K = Cout, of the wide blocks).  In conv_x3
+// every 64 x 64 output tile stages its own copy of the B operand (load, split into planes, LDS
+// stores, two barriers per 32 values of k) and lasts 2-3 us per 32 values of k for 0.2 us of
+// matrix-core time; with a short contraction the tile's prologue and epilogue are most of it.
+// Here the roles are turned round:
+//   - a workgroup owns a slab of 64 output rows; the slab's weights, all of K, are copied once
+//     from the weight image into LDS (at most 72 KB) in the lane order of the MFMA's A operand,
+//     so an operand is one 16-byte LDS read per lane and plane, conflict-free;
+//   - a wavefront owns whole chunks of 32 pixels: lane (r, g) loads, for every 32 values of k,
+//     the values k = 8g .. 8g+7 of its two pixels (2r and 2r+1 of the chunk when the plane size
+//     is even: eight-byte loads, sixteen lanes cover a 128-byte line; r and 16+r otherwise),
+//     which after the prologue and the split into planes ARE the B operands of
+//     v_mfma_f32_16x16x32_bf16 (column = pixel, contraction = k): no LDS stores, no barrier in
+//     the loop, and the operand is split once per pixel chunk and slab instead of once per tile;
+//   - the next chunk's values of a k step are requested as soon as this chunk's have been
+//     consumed; the accumulators (4 row tiles x 2 pixel tiles) are stored straight from
+//     registers, eight bytes per lane, sixteen lanes to a 128-byte line;
+//   - BN statistics of the output (EPI_STATS) are kept per lane over the wavefront's chunks and
+//     reduced once at the end: lanes of a row, then the four wavefronts in order through LDS.
+// Workgroup b: die = b % 8, then slab and chunk set, so that the workgroups of all slabs that
+// read the same pixel chunks run on the same die and share its L2.
+struct X3WArgs {
+    int M, K, HW;
+    uint32_t Q;
+    int numChunks;
+    FastDiv divHW;
+    const uint16_t *img; // weight image in lane order
+    X3Operand B;
+    float *out;
+    float *psum, *psq; // EPI_STATS: [M][NT]
+    int NT;            // chunk sets (= statistics partials per row)
+    int slabs;
+};
+
+template <int KS, bool PAIR, int PRO, int EPI>
+__global__ __launch_bounds__(256, 2) void conv_xw_kernel(X3WArgs a)
+{
+    static_assert(PRO == PRO_NONE || PRO == PRO_BNBWD, "prologues of the short-contraction roles");
+    static_assert(EPI == EPI_NONE || EPI == EPI_STATS, "epilogues of the short-contraction roles");
+    constexpr int NP = PRO == PRO_BNBWD ? 2 : 1;
+    constexpr int STEP_HW = 4 * 3 * 64 * 8; // halfwords of the slab per k step: 4 row tiles, 3 planes
+    extern __shared__ uint16_t lds16[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, g = lane >> 4;
+    const int M = a.M, K = a.K, HW = a.HW;
+    const int die = blockIdx.x & 7, bi = blockIdx.x >> 3;
+    const int slab = bi % a.slabs, cs = (bi / a.slabs) * 8 + die;
+
+    // the slab's weights: KS * 12 KB, copied as they lie in the image (requested here, parked in
+    // LDS below, after the first chunk's values have been requested as well)
+    u32x4 slabv[KS * 3];
+    {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(a.img + (size_t)slab * KS * STEP_HW);
+#pragma unroll
+        for (int i = 0; i < KS * 3; ++i)
+            slabv[i] = src[tid + 256 * i];
+    }
+    // BN-backward coefficients per contraction index, {c0, c1, c2, -} (zero past K)
+    f32x4 *Cl = reinterpret_cast<f32x4 *>(lds16 + KS * STEP_HW); // [32*KS] (PRO_BNBWD)
+    float *Rd = reinterpret_cast<float *>(lds16 + KS * STEP_HW); // [4][128]  (EPI_STATS, at the end)
+    if (PRO == PRO_BNBWD) {
+        for (int k = tid; k < 32 * KS; k += 256) {
+            const int kk = k < K ? k : K - 1;
+            const uint32_t m = k < K ? 0xffffffffu : 0u;
+            Cl[k] = (f32x4){and_mask(a.B.c0[kk], m), and_mask(a.B.c1[kk], m), and_mask(a.B.c2[kk], m), 0.f};
+        }
+    }
+    // the lane's eight contraction rows of step s start at row 32s + 8g, clamped to the last
+    // group of eight (K % 8 == 0; the weight image is zero past K, the values read are finite)
+    uint32_t vrow[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+        vrow[s] = (uint32_t)min(32 * s + 8 * g, K - 8) * (uint32_t)HW;
+    const uint32_t mrow = (uint32_t)(64 * slab + 4 * g) * (uint32_t)HW; // output row 16i + v above it
+    const uint32_t bimg = (uint32_t)K * (uint32_t)HW, oimg = (uint32_t)M * (uint32_t)HW;
+
+    // pixel tile pt of chunk c: pixel 2r + pt (pairs) or r + 16 pt
+    const auto locate = [&](int c, uint32_t (&bo)[2], uint32_t (&oo)[2], uint32_t (&okm)[2]) {
+#pragma unroll
+        for (int pt = 0; pt < (PAIR ? 1 : 2); ++pt) {
+            const uint32_t q = (uint32_t)c * 32u + (PAIR ? 2u * (uint32_t)r : 16u * pt + (uint32_t)r);
+            okm[pt] = q < a.Q ? 0xffffffffu : 0u;
+            const uint32_t qs = q < a.Q ? q : 0u;
+            const uint32_t n = fdiv(qs, a.divHW), pix = qs - n * (uint32_t)HW;
+            bo[pt] = n * bimg + pix;
+            oo[pt] = n * oimg + pix;
+        }
+        if (PAIR) {
+            bo[1] = bo[0];
+            oo[1] = oo[0];
+            okm[1] = okm[0];
+        }
+    };
+    float xv[NP][KS][2][8];
+    const auto fetch_step = [&](int s, const uint32_t (&bo)[2]) {
+        const uint32_t o0 = bo[0] + vrow[s], o1 = bo[1] + vrow[s];
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const float *pb = (p == 0 ? a.B.p0 : a.B.p1) + (size_t)t * HW; // uniform
+                if (PAIR) {
+                    const f32x2 v2 = *reinterpret_cast<const f32x2 *>(pb + o0);
+                    xv[p][s][0][t] = v2[0];
+                    xv[p][s][1][t] = v2[1];
+                } else {
+                    xv[p][s][0][t] = pb[o0];
+                    xv[p][s][1][t] = pb[o1];
+                }
+            }
+    };
+
+    f32x4 acc[4][2];
+    float s1[4][4], s2[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            s1[i][v] = s2[i][v] = 0.f;
+
+    const int cStep = 4 * a.NT;
+    int ch = 4 * cs + wv;
+    uint32_t bo[2], oo[2], okm[2];
+    locate(ch < a.numChunks ? ch : 0, bo, oo, okm);
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+        fetch_step(s, bo);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < KS * 3; ++i)
+        reinterpret_cast<u32x4 *>(lds16)[tid + 256 * i] = slabv[i];
+    __syncthreads(); // the slab, Cl
+
+    for (; ch < a.numChunks; ch += cStep) {
+        const int nx = ch + cStep < a.numChunks ? ch + cStep : ch;
+        uint32_t nbo[2], noo[2], nokm[2];
+        locate(nx, nbo, noo, nokm);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            acc[i][0] = acc[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            float d0[8], d1[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                if (PRO == PRO_BNBWD) {
+                    const f32x4 k = Cl[32 * s + 8 * g + t];
+                    d0[t] = fmaf(k[0], xv[0][s][0][t], fmaf(k[1], xv[NP - 1][s][0][t], k[2]));
+                    d1[t] = fmaf(k[0], xv[0][s][1][t], fmaf(k[1], xv[NP - 1][s][1][t], k[2]));
+                } else {
+                    d0[t] = xv[0][s][0][t];
+                    d1[t] = xv[0][s][1][t];
+                }
+                d0[t] = and_mask(d0[t], okm[0]);
+                d1[t] = and_mask(d1[t], okm[1]);
+            }
+            fetch_step(s, nbo);
+            uint32_t p0[4][3], p1[4][3];
+            bf16x8 b0[3], b1[3];
+            x3_split8(d0, p0, b0);
+            x3_split8(d1, p1, b1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                bf16x8 av[3];
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl)
+                    av[pl] = x3_lds8(lds16 + s * STEP_HW + ((i * 3 + pl) * 64 + lane) * 8);
+                acc[i][0] = x3_mfma6_16(av, b0, acc[i][0]);
+                acc[i][1] = x3_mfma6_16(av, b1, acc[i][1]);
+            }
+            // (one step at a time: the scheduler would otherwise split every step's operands
+            // ahead of the first MFMA and run out of registers)
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // rows 64 slab + 16i + 4g + v, the lane's two pixels
+        const bool ok0 = okm[0] != 0u, ok1 = okm[1] != 0u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float *po = a.out + (size_t)(16 * i + v) * HW; // uniform
+                const float x0 = acc[i][0][v], x1 = acc[i][1][v];
+                const bool mok = 64 * slab + 16 * i + 4 * g + v < M;
+                if (PAIR) {
+                    if (ok0 && mok)
+                        *reinterpret_cast<f32x2 *>(po + oo[0] + mrow) = (f32x2){x0, x1};
+                } else {
+                    if (ok0 && mok)
+                        po[oo[0] + mrow] = x0;
+                    if (ok1 && mok)
+                        po[oo[1] + mrow] = x1;
+                }
+                if (EPI == EPI_STATS) { // (pixels past the end were masked to zero on the way in)
+                    s1[i][v] += x0 + x1;
+                    s2[i][v] = fmaf(x0, x0, fmaf(x1, x1, s2[i][v]));
+                }
+            }
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt) {
+            bo[pt] = nbo[pt];
+            oo[pt] = noo[pt];
+            okm[pt] = nokm[pt];
+        }
+    }
+    if (EPI == EPI_STATS) {
+        // lanes of a row hold the same 16 channels: add them, then the wavefronts in order
+        __syncthreads(); // (Rd lies over Cl)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float t1 = row16_sum(s1[i][v]), t2 = row16_sum(s2[i][v]);
+                if (r == 0) {
+                    Rd[wv * 128 + 16 * i + 4 * g + v] = t1;
+                    Rd[wv * 128 + 64 + 16 * i + 4 * g + v] = t2;
+                }
+            }
+        __syncthreads();
+        if (tid < 128) {
+            const int mm = 64 * slab + (tid & 63);
+            const float t = (Rd[tid] + Rd[128 + tid]) + (Rd[256 + tid] + Rd[384 + tid]);
+            if (mm < M)
+                (tid < 64 ? a.psum : a.psq)[(size_t)mm * a.NT + cs] = t;
+        }
+    }
+}
+
+// Shapes and roles served: contraction of at most 192 (96 with the two-tensor prologue), a
+// multiple of 8; at least one 64-row slab of output; fp32.  `nt`: chunk sets = statistics
+// partials per row (a multiple of 8: one per die and round).
+bool xw_conv_plan(int N, int M, int K, int HW, int pro, int epi, int *nt)
+{
+    const long long Q = (long long)N * HW;
+    if (K % 8 != 0 || K < 32 || K > (pro == PRO_BNBWD ? 96 : 192) || M < 64 || M < K)
+        return false;
+    if ((pro != PRO_NONE && pro != PRO_BNBWD) || (epi != EPI_NONE && epi != EPI_STATS))
+        return false;
+    if (Q * M >= (1ll << 30) || Q * K >= (1ll << 30)) // 32-bit byte offsets in the kernel
+        return false;
+    const int slabs = (M + 63) / 64;
+    const long long chunks = (Q + 31) / 32;
+    // about two workgroups per CU in all, a multiple of 8 (one per die); of the counts that
+    // need the same number of rounds over the chunk groups (four chunks, one per wavefront),
+    // the smallest
+    long long sets = (512 + slabs - 1) / slabs;
+    sets = (sets + 7) / 8 * 8;
+    const long long groups = (chunks + 3) / 4;
+    if (sets > groups)
+        sets = (groups + 7) / 8 * 8;
+    const long long rounds = (groups + sets - 1) / sets;
+    sets = ((groups + rounds - 1) / rounds + 7) / 8 * 8;
+    *nt = (int)sets;
+    return true;
+}
+
+hipError_t launch_xw_conv1x1(int N, int M, int K, int HW, const void *wimg, const Operand &B,
+                             void *out, int epi, float *psum, float *psq, hipStream_t st)
+{
+    int nt;
+    if (!xw_conv_plan(N, M, K, HW, B.pro, epi, &nt) || !wimg)
+        return hipErrorInvalidValue;
+    X3WArgs a;
+    a.M = M;
+    a.K = K;
+    a.HW = HW;
+    a.Q = (uint32_t)((long long)N * HW);
+    a.numChunks = (int)((a.Q + 31u) / 32u);
+    a.divHW = make_div((uint32_t)HW);
+    a.img = (const uint16_t *)wimg;
+    a.B = to_x3(B);
+    a.out = (float *)out;
+    a.psum = psum;
+    a.psq = psq;
+    a.NT = nt;
+    a.slabs = (M + 63) / 64;
+    const int ks = (K + 31) / 32;
+    const bool pair = HW % 2 == 0;
+    const dim3 grid((unsigned)(a.slabs * nt));
+    const size_t lds = (size_t)ks * 12288 + (B.pro == PRO_BNBWD ? std::max((size_t)ks * 512, (size_t)2048) : 2048);
+#define MBK_CASE(KS_, PAIR_, PRO_, EPI_)                                                          \
+    if (ks == KS_ && pair == PAIR_ && B.pro == PRO_ && epi == EPI_) {                             \
+        auto kern = conv_xw_kernel<KS_, PAIR_, PRO_, EPI_>;                                       \
+        const hipError_t e_ = hipFuncSetAttribute(                                                \
+            (const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
+        if (e_ != hipSuccess)                                                                     \
+            return e_;                                                                            \
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);                                    \
+        return hipGetLastError();                                                                 \
+    }
+#define MBK_KS(KS_)                                                                               \
+    MBK_CASE(KS_, true, PRO_NONE, EPI_STATS)                                                      \
+    MBK_CASE(KS_, false, PRO_NONE, EPI_STATS)                                                     \
+    MBK_CASE(KS_, true, PRO_NONE, EPI_NONE)                                                       \
+    MBK_CASE(KS_, false, PRO_NONE, EPI_NONE)
+    MBK_KS(1)
+    MBK_KS(2)
+    MBK_KS(3)
+    MBK_KS(4)
+    MBK_KS(5)
+    MBK_KS(6)
+#undef MBK_KS
+#define MBK_KS(KS_)                                                                               \
+    MBK_CASE(KS_, true, PRO_BNBWD, EPI_NONE)                                                      \
+    MBK_CASE(KS_, false, PRO_BNBWD, EPI_NONE)                                                     \
+    MBK_CASE(KS_, true, PRO_BNBWD, EPI_STATS)                                                     \
+    MBK_CASE(KS_, false, PRO_BNBWD, EPI_STATS)
+    MBK_KS(1)
+    MBK_KS(2)
+    MBK_KS(3)
+    MBK_KS(4)
+#undef MBK_KS
 #undef MBK_CASE
     return hipErrorInvalidValue;
 }

@@ -30,6 +30,7 @@ struct Plan {
     // the shape reads the weights themselves): expansion conv, projection conv, projection data
     // gradient, expansion data gradient; written by forward, read again by backward
     size_t o_wimg[4];
+    int wimg_lane_order[4]; // how the kernel that reads image i wants its tiles arranged
     // scratch workspace (byte offsets)
     size_t o_part;  // partial sums: 2 arrays of part_floats
     size_t o_wg2;   // projection weight gradient's partials while their reduction is deferred
@@ -78,6 +79,27 @@ mbconv_status check_desc(const mbconv_desc *d)
     return MBCONV_OK;
 }
 
+// The four 1x1 convolutions of a block as launch_conv1x1 sees them: expansion conv, projection
+// conv, projection data gradient, expansion data gradient (training mode; the evaluation-mode
+// projection conv with BN3 folded into its epilogue reads the same image).
+struct ConvRole {
+    bool present, stores;
+    int M, K, HW, pro, epi;
+};
+ConvRole conv_role(const Plan &P, int i)
+{
+    switch (i) {
+    case 0:
+        return {P.expand, false, P.Cexp, P.Cin, P.HW, PRO_NONE, EPI_STATS};
+    case 1:
+        return {true, P.store, P.Cout, P.Cexp, P.HWo, PRO_BNSWISH_GATE, EPI_STATS};
+    case 2:
+        return {true, false, P.Cexp, P.Cout, P.HWo, PRO_BNBWD, EPI_NONE};
+    default:
+        return {P.expand, false, P.Cin, P.Cexp, P.HW, PRO_BNBWD, P.res ? EPI_RES : EPI_NONE};
+    }
+}
+
 Plan make_plan(const mbconv_desc *d)
 {
     Plan P = {};
@@ -109,8 +131,9 @@ Plan make_plan(const mbconv_desc *d)
         const DwShape ds = {P.N, P.Cexp, P.H, P.W, P.Ho, P.Wo, P.k, P.s, P.p};
         P.NPdw = dw_num_partials(ds, P.store && P.expand);
     }
-    P.NT1 = conv1x1_num_partials(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false);
-    P.NT5 = conv1x1_num_partials(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, d->policy == MBCONV_STORE);
+    P.NT1 = conv1x1_num_partials(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false, PRO_NONE, EPI_STATS);
+    P.NT5 = conv1x1_num_partials(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, d->policy == MBCONV_STORE,
+                                 PRO_BNSWISH_GATE, EPI_STATS);
 
     size_t o = 0;
     auto take = [&o](size_t bytes) {
@@ -133,13 +156,15 @@ Plan make_plan(const mbconv_desc *d)
     P.o_a1 = (P.store && P.expand) ? take(P.nE * P.esz) : kAbsent;
     P.o_sc = P.store ? take(P.nD * P.esz) : kAbsent;
     {
-        const bool use[4] = {P.expand && conv1x1_uses_weight_image(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false),
-                             conv1x1_uses_weight_image(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, P.store),
-                             conv1x1_uses_weight_image(P.bf16, P.N, P.Cexp, P.Cout, P.HWo, false),
-                             P.expand && conv1x1_uses_weight_image(P.bf16, P.N, P.Cin, P.Cexp, P.HW, false)};
-        const int M[4] = {P.Cexp, P.Cout, P.Cexp, P.Cin}, K[4] = {P.Cin, P.Cexp, P.Cout, P.Cexp};
-        for (int i = 0; i < 4; ++i)
-            P.o_wimg[i] = use[i] ? take(x3_weight_image_bytes(M[i], K[i])) : kAbsent;
+        const ConvRole ro[4] = {conv_role(P, 0), conv_role(P, 1), conv_role(P, 2), conv_role(P, 3)};
+        for (int i = 0; i < 4; ++i) {
+            const bool use = ro[i].present && conv1x1_uses_weight_image(P.bf16, P.N, ro[i].M, ro[i].K, ro[i].HW,
+                                                                          ro[i].stores, ro[i].pro, ro[i].epi);
+            P.o_wimg[i] = use ? take(x3_weight_image_bytes(ro[i].M, ro[i].K)) : kAbsent;
+            P.wimg_lane_order[i] = use ? conv1x1_image_lane_order(P.bf16, P.N, ro[i].M, ro[i].K, ro[i].HW,
+                                                                  ro[i].stores, ro[i].pro, ro[i].epi)
+                                       : 0;
+        }
     }
     P.saved_bytes = o;
 
@@ -299,7 +324,7 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
     };
     const auto prep_images = [&]() -> hipError_t {
         const float *w[4];
-        int M[4], K[4], sm[4], sk[4], n = 0;
+        int M[4], K[4], sm[4], sk[4], lo[4], n = 0;
         void *img[4];
         const float *we = (const float *)prm->w_expand, *wp = (const float *)prm->w_proj;
         const auto add = [&](int i, const float *src, int m, int k, int s_m, int s_k) {
@@ -311,6 +336,7 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
             sm[n] = s_m;
             sk[n] = s_k;
             img[n] = at<char>(saved, P.o_wimg[i]);
+            lo[n] = P.wimg_lane_order[i];
             ++n;
         };
         add(0, we, P.Cexp, P.Cin, P.Cin, 1);
@@ -319,7 +345,7 @@ mbconv_status forward_impl(const mbconv_desc *desc, const mbconv_params *prm, mb
             add(2, wp, P.Cexp, P.Cout, 1, P.Cexp);
             add(3, we, P.Cin, P.Cexp, 1, P.Cin);
         }
-        return n ? launch_x3_prep(n, w, M, K, sm, sk, img, st) : hipSuccess;
+        return n ? launch_x3_prep(n, w, M, K, sm, sk, img, lo, st) : hipSuccess;
     };
     bool images_ready = false;
     // expansion conv + BN1 statistics
@@ -662,7 +688,7 @@ mbconv_status mbconv_step_engine(const mbconv_desc *desc, int32_t step, int32_t 
     switch (step) {
     case MBCONV_STEP_EXPAND_CONV:
         if (P.expand)
-            e = conv1x1_engine(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false);
+            e = conv1x1_engine(P.bf16, P.N, P.Cexp, P.Cin, P.HW, false, PRO_NONE, EPI_STATS);
         break;
     case MBCONV_STEP_PROJ_CONV:
         e = conv1x1_engine(P.bf16, P.N, P.Cout, P.Cexp, P.HWo, P.store);
@@ -672,7 +698,7 @@ mbconv_status mbconv_step_engine(const mbconv_desc *desc, int32_t step, int32_t 
         int ps = 0;
         const bool fused = projbwd_fused_plan(P.N, P.Cexp, P.Cout, P.HWo, &ps);
         if (step == MBCONV_STEP_PROJ_DGRAD)
-            e = fused ? MBCONV_ENGINE_MFMA_F32 : conv1x1_engine(P.bf16, P.N, P.Cexp, P.Cout, P.HWo, false);
+            e = fused ? MBCONV_ENGINE_MFMA_F32 : conv1x1_engine(P.bf16, P.N, P.Cexp, P.Cout, P.HWo, false, PRO_BNBWD, EPI_NONE);
         else
             e = fused ? MBCONV_ENGINE_VECTOR : wgrad1x1_engine(P.bf16, P.Cout, P.Cexp, P.N, P.HWo);
         break;

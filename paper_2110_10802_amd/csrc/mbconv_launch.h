@@ -37,10 +37,14 @@ inline int conv1x1_num_qtiles(int N, int HW) { return (int)(((long long)N * HW +
 // sc_store (optional) receives the operand after its prologue (STORE policy).
 // Long contractions with few output tiles are split over workgroups; `splitk_ws` then needs
 // conv1x1_splitk_floats(...) floats (0 when the launch does not split).
-int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand);
+// (`pro`, `epi`: the prologue and epilogue the launch will run with, where the caller knows
+// them: some kernel families serve a shape only in certain roles; -1: not stated)
+int conv1x1_num_partials(bool bf16, int N, int M, int K, int HW, bool stores_operand, int pro = -1,
+                         int epi = -1);
 // matrix-core instruction family of a launch: 1 fp32 MFMA, 2 bf16 MFMA on bf16 data, 3 bf16 MFMA
 // on three-plane splits of fp32 data
-int conv1x1_engine(bool bf16, int N, int M, int K, int HW, bool stores_operand);
+int conv1x1_engine(bool bf16, int N, int M, int K, int HW, bool stores_operand, int pro = -1,
+                   int epi = -1);
 int wgrad1x1_engine(bool bf16, int Ma, int Mb, int N, int HW);
 size_t conv1x1_splitk_floats(bool bf16, int N, int M, int K, int HW, bool stores_operand);
 //
@@ -49,11 +53,16 @@ size_t conv1x1_splitk_floats(bool bf16, int N, int M, int K, int HW, bool stores
 // conv1x1_uses_weight_image(...) says so, `wimg` must point to the image of this A (M rows, K
 // contraction indices), x3_weight_image_bytes(M, K) bytes, written by launch_x3_prep beforehand;
 // `w` is then not read.
-bool conv1x1_uses_weight_image(bool bf16, int N, int M, int K, int HW, bool stores_operand);
+bool conv1x1_uses_weight_image(bool bf16, int N, int M, int K, int HW, bool stores_operand,
+                               int pro = -1, int epi = -1);
+// 1: the kernel that serves this launch wants the image's tiles in lane order (launch_x3_prep)
+int conv1x1_image_lane_order(bool bf16, int N, int M, int K, int HW, bool stores_operand, int pro,
+                             int epi);
 size_t x3_weight_image_bytes(int M, int K);
-// Writes up to four images in one launch; image i is of A(m,k) = w[i][m*sm[i] + k*sk[i]], M[i] x K[i].
+// Writes up to four images in one launch; image i is of A(m,k) = w[i][m*sm[i] + k*sk[i]], M[i] x K[i],
+// its 64 x 32 tiles arranged as conv1x1_image_lane_order says (lane_order[i]).
 hipError_t launch_x3_prep(int nsets, const float *const *w, const int *M, const int *K, const int *sm,
-                          const int *sk, void *const *img, hipStream_t st);
+                          const int *sk, void *const *img, const int *lane_order, hipStream_t st);
 hipError_t launch_conv1x1(bool bf16, int N, int M, int K, int HW, const void *w, int sAm, int sAk,
                           const Operand &B, void *out, int epi, const void *res, float *psum,
                           float *psq, void *sc_store, float *splitk_ws, hipStream_t st,

@@ -75,6 +75,13 @@ SMALL = {
     "x3_bwd1x1_96": _shape(N=3, Cin=16, Cexp=96, Cse=4, Cout=16, H=8, W=12),
     "x3_bwd1x1_ragged": _shape(N=3, Cin=5, Cexp=40, Cse=3, Cout=7, H=6, W=5, residual=False),
     "x3_bwd1x1_two_tiles": _shape(N=2, Cin=8, Cexp=24, Cse=2, Cout=8, H=8, W=8),
+    # 1x1 convolutions with a short contraction and many rows (expansion conv, projection data
+    # gradient): weights resident in LDS, a wavefront per 32-pixel chunk.  An odd plane (single
+    # pixels per lane instead of pairs, a last chunk of 19 pixels, 40 = one full and one quarter
+    # step of the contraction, 168 rows = two slabs and 40 rows); the longest contraction (192)
+    # with the statistics epilogue; other shapes above take the same kernels (mid_14x14, wide, ...)
+    "xw_odd_plane": _shape(N=3, Cin=40, Cexp=168, Cse=10, Cout=40, H=7, W=7, k=5),
+    "xw_k192": _shape(N=2, Cin=192, Cexp=320, Cse=8, Cout=96, H=4, W=6, residual=False),
     "bf16_small": _shape(dtype="bf16", H=14, W=14, k=5, Cin=16, Cexp=64, Cout=16, N=4),
     "bf16_s2": _shape(dtype="bf16", H=16, W=16, k=3, stride=2, Cin=16, Cexp=32, Cout=24, N=4,
                       residual=False),
