@@ -344,8 +344,15 @@ def run_chain(args) -> dict:
               " ".join(f"{n}={v * 1e3:.0f}" for n, v in row.items()), file=sys.stderr)
     ev.destroy(e0)
     ev.destroy(e1)
-    cand = [(i, n) for i, row in enumerate(survey) for n in row
-            if algorithmic_bytes(shapes[i], n) is not None]
+    def chain_bytes(i, n):
+        # (where a block's two weight gradients share one launch, the survey has no proj_wgrad
+        # step and the expand_wgrad step moves the bytes of both)
+        b = algorithmic_bytes(shapes[i], n)
+        if b is not None and n == "expand_wgrad" and survey and survey[i] and "proj_wgrad" not in survey[i]:
+            b += step_bytes(shapes[i]).get("proj_wgrad", 0)
+        return b
+
+    cand = [(i, n) for i, row in enumerate(survey) for n in row if chain_bytes(i, n) is not None]
     if args.probe_step or args.no_survey:
         default_probe = f"{only + 1}:dw_bwd" if only is not None else "2:dw_bwd"
         bi, dominant = (args.probe_step or default_probe).split(":")
@@ -371,7 +378,7 @@ def run_chain(args) -> dict:
         ev.destroy(a)
         ev.destroy(b)
     kern_ms = max(kern_ms_raw - overhead_ms, 1e-6)
-    nbytes = algorithmic_bytes(shapes[bi], dominant)
+    nbytes = chain_bytes(bi, dominant)
     achieved = nbytes / (kern_ms * 1e-3) / 1e9
     N = shapes[0].N
     active = [s for i, s in enumerate(shapes) if only is None or i == only]
@@ -400,7 +407,7 @@ def run_chain(args) -> dict:
     if survey:
         net = lambda i, n: max(survey[i][n] - overhead_ms, 1e-6)
         nxt = sorted((c for c in cand if c != (bi, dominant)), key=lambda c: -survey[c[0]][c[1]])[:3]
-        result["roofline_next"] = [_roofline_entry(f"block{i + 1}:{n}", algorithmic_bytes(shapes[i], n),
+        result["roofline_next"] = [_roofline_entry(f"block{i + 1}:{n}", chain_bytes(i, n),
                                                    net(i, n)) for i, n in nxt]
         # 1x1 convolutions above the fp32 ridge: the matrix-core roofline applies to these.  The
         # library says which instruction family serves each launch: the fp32 MFMA, or the bf16
@@ -414,7 +421,10 @@ def run_chain(args) -> dict:
             for n in GEMM_STEPS:
                 if n in fl and n in survey[i]:
                     eng = B.ENGINES[B.mbconv_step_engine(ctx[i]["desc"], B.STEPS[n])]
-                    rows.append((i, n, fl[n], net(i, n), eng))
+                    f = fl[n]
+                    if n == "expand_wgrad" and "proj_wgrad" in fl and "proj_wgrad" not in survey[i]:
+                        f += fl["proj_wgrad"]  # the two weight gradients share this launch
+                    rows.append((i, n, f, net(i, n), eng))
         if rows:
             issue = {"mfma_f32": (1, MFMA_F32_PEAK_TFLOPS), "mfma_bf16x3": (6, MFMA_BF16_PEAK_TFLOPS),
                      "mfma_bf16": (1, MFMA_BF16_PEAK_TFLOPS)}

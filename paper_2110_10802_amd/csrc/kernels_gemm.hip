@@ -232,6 +232,13 @@ hipError_t launch_x3_conv1x1(int N, int M, int K, int HW, const void *wimg, cons
 bool x3_wgrad_plan(int Ma, int Mb, int N, int HW, int *splits);
 hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
                            float *partial, int *splits_out, hipStream_t st);
+hipError_t launch_x3_wgrad_pair(int N, int MaA, int MbA, int HWA, const Operand &UA, const Operand &VA,
+                                float *partialA, int *splitsA, int MaB, int MbB, int HWB,
+                                const Operand &UB, const Operand &VB, float *partialB, int *splitsB,
+                                hipStream_t st);
+#ifndef MBK_X3PAIR
+#define MBK_X3PAIR 1
+#endif
 bool xw_conv_plan(int N, int M, int K, int HW, int pro, int epi, int *nt);
 hipError_t launch_xw_conv1x1(int N, int M, int K, int HW, const void *wimg, const Operand &B,
                              void *out, int epi, float *psum, float *psq, hipStream_t st);
@@ -633,6 +640,40 @@ static hipError_t wgrad_dispatch(const WgradArgs &a, int pu, int pv, dim3 grid, 
     MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE)
 #undef MBK_CASE
     return hipErrorInvalidValue;
+}
+
+// Two weight gradients of one block (A and B, each as launch_wgrad1x1 takes it) in one launch
+// where both are shapes of the split-operand kernel; the sums over their splits are described in
+// *ra and *rb for the caller to launch.  hipErrorNotSupported (nothing was launched) unless
+// wgrad1x1_pair_supported holds.
+bool wgrad1x1_pair_supported(bool bf16, int N, int MaA, int MbA, int HWA, int MaB, int MbB, int HWB)
+{
+    int s;
+    return MBK_X3PAIR && MBK_X3W && !bf16 && x3_wgrad_plan(MaA, MbA, N, HWA, &s) &&
+           x3_wgrad_plan(MaB, MbB, N, HWB, &s);
+}
+hipError_t launch_wgrad1x1_pair(bool bf16, int N, int MaA, int MbA, int HWA, const Operand &UA,
+                                const Operand &VA, float *partialA, float *dWA, SplitReduce *ra,
+                                int MaB, int MbB, int HWB, const Operand &UB, const Operand &VB,
+                                float *partialB, float *dWB, SplitReduce *rb, hipStream_t st)
+{
+    if (!wgrad1x1_pair_supported(bf16, N, MaA, MbA, HWA, MaB, MbB, HWB))
+        return hipErrorNotSupported;
+    int sa = 0, sb = 0;
+    hipError_t e = launch_x3_wgrad_pair(N, MaA, MbA, HWA, UA, VA, partialA, &sa, MaB, MbB, HWB, UB, VB,
+                                        partialB, &sb, st);
+    if (e == hipErrorNotSupported) {
+        // a pair of kernel forms the launch does not have (e.g. a stored activation on the
+        // projection side): one after the other
+        e = launch_x3_wgrad(N, MaA, MbA, HWA, UA, VA, partialA, &sa, st);
+        if (e == hipSuccess)
+            e = launch_x3_wgrad(N, MaB, MbB, HWB, UB, VB, partialB, &sb, st);
+    }
+    if (e != hipSuccess)
+        return e;
+    *ra = {partialA, sa, (size_t)MaA * MbA, dWA};
+    *rb = {partialB, sb, (size_t)MaB * MbB, dWB};
+    return hipSuccess;
 }
 
 hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Operand &U,

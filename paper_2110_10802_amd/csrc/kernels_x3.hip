@@ -706,13 +706,13 @@ struct X3RowData {
 // VB: rows of the V tile, 128 or 64 (a narrow second operand: each wavefront then owns 32 x 32).
 // TR: the partial tile is written transposed (the host swaps the operands when the first one is
 // the narrow one).
+// (`bid`: the workgroup's index within this weight gradient's grid; Us, Vs: LDS for three planes
+// of 128 and of VB rows)
 template <int PROU, int PROV, int VB, bool TR>
-__global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
+__device__ __forceinline__ void wgrad_x3_body(const X3WgradArgs &a, int bid, uint16_t *Us, uint16_t *Vs)
 {
     constexpr int BQ = 32, kPlane = 128 * 32, kPlaneV = VB * 32; // planes in the layout of x3_img_at
     constexpr int NA = VB == 128 ? 2 : 1;                        // 32-row blocks of U per wavefront
-    __shared__ __attribute__((aligned(16))) uint16_t Us[3 * kPlane];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[3 * kPlaneV];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // first row of this wavefront's part of the U tile and of the V tile
@@ -720,7 +720,7 @@ __global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
     const int vb = VB == 128 ? 32 * (wave & 3) : 32 * (wave & 1);
     // workgroups that read the same pixels (all tiles of one split) run on the same XCD
     // (blockIdx.x mod 8), so the operand that several tiles share comes out of that XCD's L2
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int xcd = bid & 7, slot = bid >> 3;
     const int tiles = a.tilesA * a.tilesB;
     const int split = (slot / tiles) * 8 + xcd, tile = slot % tiles;
     if (split >= a.splits)
@@ -807,6 +807,47 @@ __global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
         }
 }
 
+template <int PROU, int PROV, int VB, bool TR>
+__global__ __launch_bounds__(512) void wgrad_x3_kernel(X3WgradArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t Us[3 * 128 * 32];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[3 * VB * 32];
+    wgrad_x3_body<PROU, PROV, VB, TR>(a, (int)blockIdx.x, Us, Vs);
+}
+
+// The six forms of the kernel above, by number (x3_wgrad_variant).
+template <int VAR>
+__device__ __forceinline__ void wgrad_x3_variant(const X3WgradArgs &a, int bid, uint16_t *Us, uint16_t *Vs)
+{
+    if (VAR == 0)
+        wgrad_x3_body<PRO_BNBWD, PRO_NONE, 128, false>(a, bid, Us, Vs);
+    else if (VAR == 1)
+        wgrad_x3_body<PRO_BNBWD, PRO_BNSWISH_GATE, 128, false>(a, bid, Us, Vs);
+    else if (VAR == 2)
+        wgrad_x3_body<PRO_BNBWD, PRO_NONE, 64, false>(a, bid, Us, Vs);
+    else if (VAR == 3)
+        wgrad_x3_body<PRO_BNBWD, PRO_BNSWISH_GATE, 64, false>(a, bid, Us, Vs);
+    else if (VAR == 4)
+        wgrad_x3_body<PRO_NONE, PRO_BNBWD, 64, true>(a, bid, Us, Vs);
+    else
+        wgrad_x3_body<PRO_BNSWISH_GATE, PRO_BNBWD, 64, true>(a, bid, Us, Vs);
+}
+
+// Two weight gradients in one launch (a block's projection and expansion conv: independent of
+// each other, each about one workgroup per compute unit and bound by the latency of its own
+// load-stage-multiply chain): the first gridA workgroups work on `a`, the others on `b`, and
+// with at most 128 registers two workgroups, one of each, share a compute unit.
+template <int VARA, int VARB>
+__global__ __launch_bounds__(512, 4) void wgrad_x3_pair_kernel(X3WgradArgs a, X3WgradArgs b, int gridA)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t Us[3 * 128 * 32];
+    __shared__ __attribute__((aligned(16))) uint16_t Vs[3 * 128 * 32];
+    if ((int)blockIdx.x < gridA) // uniform over the workgroup
+        wgrad_x3_variant<VARA>(a, (int)blockIdx.x, Us, Vs);
+    else
+        wgrad_x3_variant<VARB>(b, (int)blockIdx.x - gridA, Us, Vs);
+}
+
 // Tile and splits.  The wider operand gets 128-row tiles; the other one 128-row tiles, or one
 // 64-row tile when it has at most 64 rows (and more than 32).  Splits of the contraction: about one workgroup (eight
 // wavefronts) per compute unit, at least two chunks each.
@@ -845,12 +886,13 @@ static X3Operand to_x3(const Operand &o)
     return d;
 }
 
-hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
-                           float *partial, int *splits_out, hipStream_t st)
+// Arguments, grid and kernel form (0..5, see wgrad_x3_variant) of one weight gradient.
+static bool x3_wgrad_setup(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
+                           float *partial, X3WgradArgs *out, unsigned *grid, int *variant, int *splits_out)
 {
     int splits;
     if (!x3_wgrad_plan(Ma, Mb, N, HW, &splits))
-        return hipErrorInvalidValue;
+        return false;
     // a narrow first operand: the kernel computes the transposed product and writes it transposed
     const bool swap = Ma < 64 && Mb >= 64;
     const int vb = std::min(Ma, Mb) <= 64 ? 64 : 128;
@@ -869,21 +911,80 @@ hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, cons
     a.tilesA = (a.Ma + 127) / 128;
     a.tilesB = (a.Mb + vb - 1) / vb;
     a.splits = splits;
-    dim3 grid((unsigned)(((splits + 7) / 8) * 8 * a.tilesA * a.tilesB));
+    *grid = (unsigned)(((splits + 7) / 8) * 8 * a.tilesA * a.tilesB);
     const int pu = swap ? V.pro : U.pro, pv = swap ? U.pro : V.pro;
-#define MBK_CASE(PU, PV, VB_, TR_)                                                                \
-    if (pu == PU && pv == PV && vb == VB_ && swap == TR_) {                                       \
-        hipLaunchKernelGGL((wgrad_x3_kernel<PU, PV, VB_, TR_>), grid, dim3(512), 0, st, a);       \
+    int var = -1;
+    if (!swap && pu == PRO_BNBWD && pv == PRO_NONE)
+        var = vb == 128 ? 0 : 2;
+    else if (!swap && pu == PRO_BNBWD && pv == PRO_BNSWISH_GATE)
+        var = vb == 128 ? 1 : 3;
+    else if (swap && vb == 64 && pu == PRO_NONE && pv == PRO_BNBWD)
+        var = 4;
+    else if (swap && vb == 64 && pu == PRO_BNSWISH_GATE && pv == PRO_BNBWD)
+        var = 5;
+    if (var < 0)
+        return false;
+    *out = a;
+    *variant = var;
+    return true;
+}
+
+hipError_t launch_x3_wgrad(int N, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
+                           float *partial, int *splits_out, hipStream_t st)
+{
+    X3WgradArgs a;
+    unsigned grid;
+    int var;
+    if (!x3_wgrad_setup(N, Ma, Mb, HW, U, V, partial, &a, &grid, &var, splits_out))
+        return hipErrorInvalidValue;
+#define MBK_CASE(VAR, PU, PV, VB_, TR_)                                                           \
+    if (var == VAR) {                                                                             \
+        hipLaunchKernelGGL((wgrad_x3_kernel<PU, PV, VB_, TR_>), dim3(grid), dim3(512), 0, st, a); \
         return hipGetLastError();                                                                 \
     }
-    MBK_CASE(PRO_BNBWD, PRO_NONE, 128, false)
-    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE, 128, false)
-    MBK_CASE(PRO_BNBWD, PRO_NONE, 64, false)
-    MBK_CASE(PRO_BNBWD, PRO_BNSWISH_GATE, 64, false)
-    MBK_CASE(PRO_NONE, PRO_BNBWD, 64, true)
-    MBK_CASE(PRO_BNSWISH_GATE, PRO_BNBWD, 64, true)
+    MBK_CASE(0, PRO_BNBWD, PRO_NONE, 128, false)
+    MBK_CASE(1, PRO_BNBWD, PRO_BNSWISH_GATE, 128, false)
+    MBK_CASE(2, PRO_BNBWD, PRO_NONE, 64, false)
+    MBK_CASE(3, PRO_BNBWD, PRO_BNSWISH_GATE, 64, false)
+    MBK_CASE(4, PRO_NONE, PRO_BNBWD, 64, true)
+    MBK_CASE(5, PRO_BNSWISH_GATE, PRO_BNBWD, 64, true)
 #undef MBK_CASE
     return hipErrorInvalidValue;
+}
+
+// The projection conv's weight gradient (A: dp x sc) and the expansion conv's (B: de x x) in one
+// launch.  Returns hipErrorNotSupported, nothing launched, when one of them is not a shape of
+// this file or their forms are not a pair the launch has.
+hipError_t launch_x3_wgrad_pair(int N, int MaA, int MbA, int HWA, const Operand &UA, const Operand &VA,
+                                float *partialA, int *splitsA, int MaB, int MbB, int HWB,
+                                const Operand &UB, const Operand &VB, float *partialB, int *splitsB,
+                                hipStream_t st)
+{
+    X3WgradArgs a, b;
+    unsigned ga, gb;
+    int va, vb;
+    if (!x3_wgrad_setup(N, MaA, MbA, HWA, UA, VA, partialA, &a, &ga, &va, splitsA) ||
+        !x3_wgrad_setup(N, MaB, MbB, HWB, UB, VB, partialB, &b, &gb, &vb, splitsB))
+        return hipErrorNotSupported;
+#define MBK_CASE(VA_, VB_)                                                                        \
+    if (va == VA_ && vb == VB_) {                                                                 \
+        hipLaunchKernelGGL((wgrad_x3_pair_kernel<VA_, VB_>), dim3(ga + gb), dim3(512), 0, st, a, b, \
+                           (int)ga);                                                              \
+        return hipGetLastError();                                                                 \
+    }
+    // projection side: dp (BN backward) with the gated activation, 128- or 64-row tile, or
+    // swapped; expansion side: de (BN backward) with the block's input, likewise
+    MBK_CASE(1, 0)
+    MBK_CASE(1, 2)
+    MBK_CASE(3, 2)
+    MBK_CASE(3, 0)
+    MBK_CASE(5, 2)
+    MBK_CASE(5, 0)
+    MBK_CASE(1, 4)
+    MBK_CASE(3, 4)
+    MBK_CASE(5, 4)
+#undef MBK_CASE
+    return hipErrorNotSupported;
 }
 
 // ---- both gradients of a narrow -> wide 1x1 convolution, a wavefront per pixel chunk ---------

@@ -505,6 +505,9 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
     // projection conv: data gradient G = W_p^T dp and weight gradient dW_p = dp * sc^T,
     // dp rebuilt in the prologue from dout and p
     SplitReduce proj_reduce = {nullptr, 0, 0, nullptr};
+    bool pair_wgrads = false; // the projection conv's weight gradient shares the expansion conv's launch
+    Operand pair_dp, pair_sc;
+    float *pair_pwg = nullptr;
     Operand dp;
     dp.p0 = dout;
     dp.p1 = p;
@@ -539,9 +542,21 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
             MBK_STEP(MBCONV_STEP_PROJ_DGRAD, launch_conv1x1(bf, P.N, P.Cexp, P.Cout, P.HWo, prm->w_proj, 1, P.Cexp, dp,
                                                             G, EPI_NONE, nullptr, nullptr, nullptr, nullptr, splitk, st,
                                                             P.o_wimg[2] == kAbsent ? nullptr : at<char>(saved, P.o_wimg[2])));
-            MBK_STEP(MBCONV_STEP_PROJ_WGRAD,
-                     launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, pwg, gr->w_proj,
-                                     P.expand ? &proj_reduce : nullptr, st));
+            // where both weight gradients of the block are shapes of the split-operand kernel and
+            // the expansion conv's backward is not a fused kernel, this one waits and shares the
+            // other's launch (its operands stay as they are until the end of the pass)
+            int fs = 0;
+            pair_wgrads = P.expand && !bwd1x1_fused_plan(P.N, P.Cexp, P.Cin, P.HW, &fs) &&
+                          wgrad1x1_pair_supported(bf, P.N, P.Cout, P.Cexp, P.HWo, P.Cexp, P.Cin, P.HW);
+            if (pair_wgrads) {
+                pair_dp = dp;
+                pair_sc = sc;
+                pair_pwg = pwg;
+            } else {
+                MBK_STEP(MBCONV_STEP_PROJ_WGRAD,
+                         launch_wgrad1x1(bf, P.N, P.Cout, P.Cexp, P.HWo, dp, sc, pwg, gr->w_proj,
+                                         P.expand ? &proj_reduce : nullptr, st));
+            }
         }
     }
     // SE backward and BN2 backward reductions
@@ -644,8 +659,13 @@ mbconv_status backward_impl(const mbconv_desc *desc, const mbconv_params *prm, c
         xo.pro = PRO_NONE;
         const auto both = [&]() {
             SplitReduce exp_reduce;
-            const hipError_t e = launch_wgrad1x1(bf, P.N, P.Cexp, P.Cin, P.HW, de, xo, wg, gr->w_expand,
-                                                 &exp_reduce, st);
+            hipError_t e;
+            if (pair_wgrads)
+                e = launch_wgrad1x1_pair(bf, P.N, P.Cout, P.Cexp, P.HWo, pair_dp, pair_sc, pair_pwg, gr->w_proj,
+                                         &proj_reduce, P.Cexp, P.Cin, P.HW, de, xo, wg, gr->w_expand,
+                                         &exp_reduce, st);
+            else
+                e = launch_wgrad1x1(bf, P.N, P.Cexp, P.Cin, P.HW, de, xo, wg, gr->w_expand, &exp_reduce, st);
             return e != hipSuccess ? e : launch_reduce_splits2(exp_reduce, proj_reduce, st);
         };
         MBK_STEP(MBCONV_STEP_EXPAND_WGRAD, both());

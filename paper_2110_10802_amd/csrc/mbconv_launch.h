@@ -93,6 +93,13 @@ hipError_t launch_wgrad1x1(bool bf16, int N, int Ma, int Mb, int HW, const Opera
                            const Operand &V, float *partial, float *dW, SplitReduce *defer,
                            hipStream_t st);
 hipError_t launch_reduce_splits2(const SplitReduce &a, const SplitReduce &b, hipStream_t st);
+// Two independent weight gradients (A, B) in one launch, for the shapes wgrad1x1_pair_supported
+// names; their second stages come back in *ra and *rb.  hipErrorNotSupported: nothing launched.
+bool wgrad1x1_pair_supported(bool bf16, int N, int MaA, int MbA, int HWA, int MaB, int MbB, int HWB);
+hipError_t launch_wgrad1x1_pair(bool bf16, int N, int MaA, int MbA, int HWA, const Operand &UA,
+                                const Operand &VA, float *partialA, float *dWA, SplitReduce *ra,
+                                int MaB, int MbB, int HWB, const Operand &UB, const Operand &VB,
+                                float *partialB, float *dWB, SplitReduce *rb, hipStream_t st);
 
 // Both gradients of a 1x1 convolution from Cn (narrow) to Cw (wide) channels in one pass over
 // de, the gradient at its output (PRO_BNBWD operand, [N,Cw,HW]):

@@ -16,7 +16,7 @@ if len(sys.argv) != 2:
     sys.exit(__doc__)
 base = sys.argv[1]
 
-FWD = [("expand_conv", r"x3_prep|conv_x3|conv_pe|conv_pr|conv_big|conv_bf|conv1x1_kernel|splitk_finish"),
+FWD = [("expand_conv", r"x3_prep|conv_x3|conv_xw|conv_pe|conv_pr|conv_big|conv_bf|conv1x1_kernel|splitk_finish"),
        ("bn1_finalize", r"bn_finalize"),
        ("dw_fwd", r"dw4_fwd|dwr_fwd|dw2_fwd|dw_fwd_k"),
        ("bn2_finalize", r"bn_finalize"),
@@ -27,13 +27,13 @@ FWD = [("expand_conv", r"x3_prep|conv_x3|conv_pe|conv_pr|conv_big|conv_bf|conv1x
        ("bn3_apply", r"bn_apply")]
 BWD = [("bn3_bwd_reduce", r"OpDot"),
        ("bn3_bwd_finalize", r"bn_bwd_finalize"),
-       ("proj_dgrad", r"wgrad_lt_kernel<.*true>|projbwd_wave|conv_x3|conv_pe|conv_pr|conv_big|conv_bf|conv1x1_kernel|splitk_finish"),
+       ("proj_dgrad", r"wgrad_lt_kernel<.*true>|projbwd_wave|conv_x3|conv_xw|conv_pe|conv_pr|conv_big|conv_bf|conv1x1_kernel|splitk_finish"),
        ("proj_wgrad", r"wgrad_lt_kernel<.*false>|wgrad_x3|wgrad_big|wgrad_bf|wgrad1x1|wgrad_cl|reduce_splits"),
        ("gate_sums", r"OpGate"),
        ("se_bwd", r"se_bwd|bn2_bwd_nose"),
        ("dw_bwd", r"dw4_bwd|dwr_bwd|dw2_bwd|dw_bwd_kernel"),
        ("dw_wgrad_reduce", r"dw_bwd_finalize|reduce_planes"),
-       ("expand_dgrad", r"bwd1x1_lt|conv_x3|conv_pe|conv_pr|conv_big|conv_bf|conv1x1_kernel|splitk_finish"),
+       ("expand_dgrad", r"bwd1x1_lt|bwd1x1_x3|conv_x3|conv_pe|conv_pr|conv_big|conv_bf|conv1x1_kernel|splitk_finish"),
        ("expand_wgrad", r"wgrad_lt|wgrad_x3|wgrad_big|wgrad_bf|wgrad1x1|wgrad_cl|reduce_splits")]
 NOEXP = {"expand_conv", "bn1_finalize", "expand_dgrad", "expand_wgrad"}
 
