@@ -680,25 +680,24 @@ struct BigWgradArgs {
     float *partial;
 };
 
+// (bx, by, bz: tile of U rows, tile of V rows, split; Us, Vs: the LDS buffers)
 template <typename T, int PROU, int PROV, int WA, int WB, int VEC>
-__global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
+__device__ __forceinline__ void wgrad_big_body(const BigWgradArgs &a, int bx, int by, int bz,
+                                               float (*Us)[32][64 * WA + 2], float (*Vs)[32][64 * WB + 2])
 {
     constexpr int BA = 64 * WA, BB = 64 * WB, BQ = 32;
-    constexpr int PU = BA + 2, PV = BB + 2;
     constexpr int QCOLS = BQ / VEC;     // runs per operand row
     constexpr int RROWS = 256 / QCOLS;  // rows staged per pass
     constexpr int NRU = BA / RROWS, NRV = BB / RROWS; // runs per thread of U and of V
     // two LDS buffers, except for the 128x128 tile, where two would exceed 64 KiB
     constexpr int NBUF = (WA == 2 && WB == 2) ? 1 : 2;
-    __shared__ __attribute__((aligned(16))) float Us[NBUF][BQ][PU];
-    __shared__ __attribute__((aligned(16))) float Vs[NBUF][BQ][PV];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wa = wave >> 1, wb = wave & 1;
-    const int a0 = blockIdx.x * BA, b0 = blockIdx.y * BB;
+    const int a0 = bx * BA, b0 = by * BB;
     const int numChunks = (int)((a.Q + BQ - 1) / BQ);
-    const int cbeg = blockIdx.z * a.chunksPerSplit;
+    const int cbeg = bz * a.chunksPerSplit;
     const int cend = min(cbeg + a.chunksPerSplit, numChunks);
 
     const int qcol = tid % QCOLS, rrow = tid / QCOLS;
@@ -812,7 +811,7 @@ __global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
             __syncthreads();
         }
     }
-    float *dst = a.partial + (size_t)blockIdx.z * a.Ma * a.Mb;
+    float *dst = a.partial + (size_t)bz * a.Ma * a.Mb;
 #pragma unroll
     for (int i = 0; i < WA; ++i)
 #pragma unroll
@@ -824,6 +823,34 @@ __global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
                 if (ai < a.Ma && bi < a.Mb)
                     dst[(size_t)ai * a.Mb + bi] = acc[i][j][r];
             }
+}
+
+template <typename T, int PROU, int PROV, int WA, int WB, int VEC>
+__global__ __launch_bounds__(256) void wgrad_big_kernel(BigWgradArgs a)
+{
+    constexpr int NBUF = (WA == 2 && WB == 2) ? 1 : 2;
+    __shared__ __attribute__((aligned(16))) float Us[NBUF][32][64 * WA + 2];
+    __shared__ __attribute__((aligned(16))) float Vs[NBUF][32][64 * WB + 2];
+    wgrad_big_body<T, PROU, PROV, WA, WB, VEC>(a, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, Us, Vs);
+}
+
+// Two weight gradients of one block in one launch (64 x 64 tiles, no run vectorisation: the 7x7
+// stages): the launches are a few hundred workgroups each and bound by the latency of their own
+// load-stage-multiply chain, so together they fill the wavefront slots either leaves empty.
+// The first gridA workgroups work on `a` (projection conv: dp x gated activation), the others on
+// `b` (expansion conv: de x block input); tiles and splits are decoded from the linear index.
+template <typename T>
+__global__ __launch_bounds__(256) void wgrad_big_pair_kernel(BigWgradArgs a, BigWgradArgs b, int gridA)
+{
+    __shared__ __attribute__((aligned(16))) float Us[2][32][66];
+    __shared__ __attribute__((aligned(16))) float Vs[2][32][66];
+    if ((int)blockIdx.x < gridA) { // uniform over the workgroup
+        const int i = (int)blockIdx.x, ta = (a.Ma + 63) / 64, tb = (a.Mb + 63) / 64;
+        wgrad_big_body<T, PRO_BNBWD, PRO_BNSWISH_GATE, 1, 1, 1>(a, i % ta, (i / ta) % tb, i / (ta * tb), Us, Vs);
+    } else {
+        const int i = (int)blockIdx.x - gridA, ta = (b.Ma + 63) / 64, tb = (b.Mb + 63) / 64;
+        wgrad_big_body<T, PRO_BNBWD, PRO_NONE, 1, 1, 1>(b, i % ta, (i / ta) % tb, i / (ta * tb), Us, Vs);
+    }
 }
 
 // `wt` packs the tile factors as 4*WA + WB.
@@ -892,6 +919,46 @@ hipError_t launch_big_wgrad(bool bf16, int N, int Ma, int Mb, int HW, const Oper
         return hipErrorInvalidValue;
     return bf16 ? MBK_GO(bf16_t) : MBK_GO(float);
 #undef MBK_GO
+}
+
+// The pair of launch_big_wgrad calls (A: U = BN-backward operand, V = gated activation; B: U =
+// BN-backward operand, V = plain) in one launch; hipErrorNotSupported (nothing launched) for
+// other operand kinds, tile shapes or plane sizes that are a multiple of four.
+hipError_t launch_big_wgrad_pair(bool bf16, int N, int MaA, int MbA, int HWA, const Operand &UA,
+                                 const Operand &VA, float *partialA, int *splitsA, int MaB, int MbB,
+                                 int HWB, const Operand &UB, const Operand &VB, float *partialB,
+                                 int *splitsB, hipStream_t st)
+{
+    int wta, wtb, sa, sb;
+    if (!big_wgrad_plan(MaA, MbA, N, HWA, &wta, &sa) || !big_wgrad_plan(MaB, MbB, N, HWB, &wtb, &sb))
+        return hipErrorNotSupported;
+    if (wta != 5 || wtb != 5 || HWA % 4 == 0 || HWB % 4 == 0 || UA.pro != PRO_BNBWD ||
+        VA.pro != PRO_BNSWISH_GATE || UB.pro != PRO_BNBWD || VB.pro != PRO_NONE)
+        return hipErrorNotSupported;
+    const auto fill = [N](BigWgradArgs &a, int Ma, int Mb, int HW, const Operand &U, const Operand &V,
+                          float *partial, int splits) {
+        a.Ma = Ma;
+        a.Mb = Mb;
+        a.HW = HW;
+        a.Q = (uint32_t)((long long)N * HW);
+        const int chunks = (int)((a.Q + 31u) / 32u);
+        a.chunksPerSplit = (chunks + splits - 1) / splits;
+        a.divHW = make_div((uint32_t)HW);
+        a.U = to_big(U);
+        a.V = to_big(V);
+        a.partial = partial;
+        return ((Ma + 63) / 64) * ((Mb + 63) / 64) * splits;
+    };
+    BigWgradArgs a, b;
+    const int ga = fill(a, MaA, MbA, HWA, UA, VA, partialA, sa);
+    const int gb = fill(b, MaB, MbB, HWB, UB, VB, partialB, sb);
+    *splitsA = sa;
+    *splitsB = sb;
+    if (bf16)
+        hipLaunchKernelGGL(wgrad_big_pair_kernel<bf16_t>, dim3((unsigned)(ga + gb)), dim3(256), 0, st, a, b, ga);
+    else
+        hipLaunchKernelGGL(wgrad_big_pair_kernel<float>, dim3((unsigned)(ga + gb)), dim3(256), 0, st, a, b, ga);
+    return hipGetLastError();
 }
 
 } // namespace mbk

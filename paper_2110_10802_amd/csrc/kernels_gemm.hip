@@ -239,6 +239,11 @@ hipError_t launch_x3_wgrad_pair(int N, int MaA, int MbA, int HWA, const Operand 
 #ifndef MBK_X3PAIR
 #define MBK_X3PAIR 1
 #endif
+// kernels_big.hip
+hipError_t launch_big_wgrad_pair(bool bf16, int N, int MaA, int MbA, int HWA, const Operand &UA,
+                                 const Operand &VA, float *partialA, int *splitsA, int MaB, int MbB,
+                                 int HWB, const Operand &UB, const Operand &VB, float *partialB,
+                                 int *splitsB, hipStream_t st);
 bool xw_conv_plan(int N, int M, int K, int HW, int pro, int epi, int *nt);
 hipError_t launch_xw_conv1x1(int N, int M, int K, int HW, const void *wimg, const Operand &B,
                              void *out, int epi, float *psum, float *psq, hipStream_t st);
@@ -646,28 +651,56 @@ static hipError_t wgrad_dispatch(const WgradArgs &a, int pu, int pv, dim3 grid, 
 // where both are shapes of the split-operand kernel; the sums over their splits are described in
 // *ra and *rb for the caller to launch.  hipErrorNotSupported (nothing was launched) unless
 // wgrad1x1_pair_supported holds.
+// 1: both are shapes of the split-operand kernel; 2: both go to the 64 x 64-tile kernel of
+// kernels_big.hip with planes that are not a multiple of four pixels (the 7x7 stages); 0: no pair
+static int wgrad1x1_pair_kind(bool bf16, int N, int MaA, int MbA, int HWA, int MaB, int MbB, int HWB)
+{
+    if (!MBK_X3PAIR)
+        return 0;
+    int s, wt;
+    bool swap;
+    const bool xa = MBK_X3W && !bf16 && x3_wgrad_plan(MaA, MbA, N, HWA, &s);
+    const bool xb = MBK_X3W && !bf16 && x3_wgrad_plan(MaB, MbB, N, HWB, &s);
+    if (xa && xb)
+        return 1;
+    const auto big = [&](bool x3, int Ma, int Mb, int HW) {
+        return !x3 && HW % 4 != 0 && !wgrad_cl_plan(Ma, Mb, N, HW, &swap, &s) &&
+               !(bf16 && bf_wgrad_plan(Ma, Mb, N, HW, &s)) && big_wgrad_plan(Ma, Mb, N, HW, &wt, &s) && wt == 5;
+    };
+    return big(xa, MaA, MbA, HWA) && big(xb, MaB, MbB, HWB) ? 2 : 0;
+}
 bool wgrad1x1_pair_supported(bool bf16, int N, int MaA, int MbA, int HWA, int MaB, int MbB, int HWB)
 {
-    int s;
-    return MBK_X3PAIR && MBK_X3W && !bf16 && x3_wgrad_plan(MaA, MbA, N, HWA, &s) &&
-           x3_wgrad_plan(MaB, MbB, N, HWB, &s);
+    return wgrad1x1_pair_kind(bf16, N, MaA, MbA, HWA, MaB, MbB, HWB) != 0;
 }
 hipError_t launch_wgrad1x1_pair(bool bf16, int N, int MaA, int MbA, int HWA, const Operand &UA,
                                 const Operand &VA, float *partialA, float *dWA, SplitReduce *ra,
                                 int MaB, int MbB, int HWB, const Operand &UB, const Operand &VB,
                                 float *partialB, float *dWB, SplitReduce *rb, hipStream_t st)
 {
-    if (!wgrad1x1_pair_supported(bf16, N, MaA, MbA, HWA, MaB, MbB, HWB))
+    const int kind = wgrad1x1_pair_kind(bf16, N, MaA, MbA, HWA, MaB, MbB, HWB);
+    if (!kind)
         return hipErrorNotSupported;
     int sa = 0, sb = 0;
-    hipError_t e = launch_x3_wgrad_pair(N, MaA, MbA, HWA, UA, VA, partialA, &sa, MaB, MbB, HWB, UB, VB,
-                                        partialB, &sb, st);
-    if (e == hipErrorNotSupported) {
-        // a pair of kernel forms the launch does not have (e.g. a stored activation on the
-        // projection side): one after the other
-        e = launch_x3_wgrad(N, MaA, MbA, HWA, UA, VA, partialA, &sa, st);
-        if (e == hipSuccess)
-            e = launch_x3_wgrad(N, MaB, MbB, HWB, UB, VB, partialB, &sb, st);
+    hipError_t e;
+    if (kind == 1) {
+        e = launch_x3_wgrad_pair(N, MaA, MbA, HWA, UA, VA, partialA, &sa, MaB, MbB, HWB, UB, VB, partialB, &sb,
+                                 st);
+        if (e == hipErrorNotSupported) {
+            // a pair of kernel forms the launch does not have (e.g. a stored activation on the
+            // projection side): one after the other
+            e = launch_x3_wgrad(N, MaA, MbA, HWA, UA, VA, partialA, &sa, st);
+            if (e == hipSuccess)
+                e = launch_x3_wgrad(N, MaB, MbB, HWB, UB, VB, partialB, &sb, st);
+        }
+    } else {
+        e = launch_big_wgrad_pair(bf16, N, MaA, MbA, HWA, UA, VA, partialA, &sa, MaB, MbB, HWB, UB, VB,
+                                  partialB, &sb, st);
+        if (e == hipErrorNotSupported) {
+            e = launch_big_wgrad(bf16, N, MaA, MbA, HWA, UA, VA, partialA, &sa, st);
+            if (e == hipSuccess)
+                e = launch_big_wgrad(bf16, N, MaB, MbB, HWB, UB, VB, partialB, &sb, st);
+        }
     }
     if (e != hipSuccess)
         return e;
