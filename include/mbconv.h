@@ -207,7 +207,10 @@ typedef enum {
     MBCONV_STEP_PROJ_DGRAD = 12,   /* for Cout <= 32 (and H*W a multiple of 4) one kernel computes the
                                       data gradient and the weight gradient's split partial sums */
     MBCONV_STEP_PROJ_WGRAD = 13,   /* with an expansion conv: the split partial sums only, their sum is
-                                      part of EXPAND_WGRAD's last launch */
+                                      part of EXPAND_WGRAD's last launch; does not occur where the two 1x1
+                                      weight gradients of the block share one launch (wide blocks whose
+                                      two gradients take the same kernel family): that launch is
+                                      EXPAND_WGRAD's first */
     MBCONV_STEP_GATE_SUMS = 14,
     MBCONV_STEP_SE_BWD = 15,       /* when no_se: BN2's parameter gradients and backward coefficients only */
     MBCONV_STEP_DW_BWD = 16,       /* BN2 backward + depthwise dgrad/wgrad + Swish' + BN1 partials */
@@ -215,7 +218,8 @@ typedef enum {
                                           launch also finalises BN1's backward */
     MBCONV_STEP_BN1_BWD_FINALIZE = 18, /* launches nothing (see step 17): a probe on it times an empty event pair */
     MBCONV_STEP_EXPAND_DGRAD = 19,
-    MBCONV_STEP_EXPAND_WGRAD = 20, /* and the sums over the splits of both 1x1 weight gradients */
+    MBCONV_STEP_EXPAND_WGRAD = 20, /* and the sums over the splits of both 1x1 weight gradients (and the
+                                      projection conv's weight gradient itself, see PROJ_WGRAD) */
     MBCONV_STEP_COUNT = 21
 } mbconv_step;
 
